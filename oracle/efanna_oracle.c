@@ -1,0 +1,452 @@
+/*
+ * CPU oracle for approximate kNN-graph construction (EFANNA, arXiv 1609.07228):
+ * randomized truncated KD-trees (Alg. 2), leaf-level conquer step of the
+ * divide-and-conquer initialisation (Alg. 3 with the conquer depth at the leaves)
+ * and NN-descent refinement (Alg. 4).
+ *
+ * THIS IS TEST INFRASTRUCTURE.  It is a plain, slow, step-by-step statement of
+ * what the method computes, used only to check the GPU library and to serve as
+ * the timed CPU baseline.  It shares no code with the GPU library and nothing
+ * in the product path may call it.
+ *
+ * The method is a randomized heuristic followed by an iteration, so there is no
+ * closed form to write down; the oracle follows the algorithms' steps.  Every
+ * random or order-dependent choice of the paper is replaced by a seeded,
+ * order-independent rule, which makes the whole pipeline a deterministic
+ * function of (X, parameters, seed):
+ *
+ *  - split dimension (Alg. 2, "randomly choose dimension"): uniform over the d
+ *    dimensions from a counter-based generator keyed by (seed, tree, heap id of
+ *    the node);
+ *  - split value (Alg. 2, "mean over the point set"): the mean, evaluated in
+ *    exact integer arithmetic on coordinates quantised to 2^-20, so that the
+ *    order of summation cannot matter: a point goes left iff cnt*q(x) < sum q;
+ *  - a node is a leaf when it holds at most S points (S = largest leaf
+ *    population); if a mean split leaves one side empty the node is cut into
+ *    positional halves;
+ *  - distances are squared L2 in float32, accumulated in 16 interleaved
+ *    partial sums that are then added pairwise in a fixed tree; every list is
+ *    ordered by (distance, id);
+ *  - NN-descent (Alg. 4) uses pool size P = K, takes the L closest new-flagged
+ *    entries of each pool as the sampled "new" set, builds reverse lists as the
+ *    transpose of the sampled lists capped at L entries by a seeded hash, and
+ *    treats the pool update as a set operation: pool := the K smallest
+ *    (distance, id) of pool U proposals, an id already present keeping its
+ *    entry and flag.
+ *
+ * Parity pins: see tests/test_oracle_*.py (exact brute force on tiny inputs,
+ * structural invariants recomputed independently in Python integers, special
+ * cases that reduce to exact kNN).  The number of iterations NN-descent needs
+ * to reach a given accuracy is not fixed by anything the paper prints:
+ * convergence speed is "parity unpinned" beyond those properties.
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+/* ------------------------------------------------------------------------- */
+/* counter-based random numbers                                               */
+
+static uint64_t mix64(uint64_t z)
+{
+    z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ULL;
+    z = (z ^ (z >> 27)) * 0x94D049BB133111EBULL;
+    return z ^ (z >> 31);
+}
+
+/* Alg. 2 "randomly choose dimension": one draw per (tree, node). */
+uint64_t oracle_node_rand(uint64_t seed, int32_t tree, uint64_t heap_id)
+{
+    uint64_t s = mix64(seed + 0x9E3779B97F4A7C15ULL * (uint64_t)(tree + 1));
+    return mix64(s + heap_id);
+}
+
+/* priority of "u is a reverse neighbour of v" when a reverse list overflows */
+uint32_t oracle_reverse_hash(uint64_t seed, int32_t iter, int32_t v, int32_t u)
+{
+    uint64_t s = mix64(seed + 0x9E3779B97F4A7C15ULL * (uint64_t)(iter + 1));
+    return (uint32_t)(mix64(s + (((uint64_t)(uint32_t)v << 32) | (uint32_t)u)) >> 32);
+}
+
+/* ------------------------------------------------------------------------- */
+/* distance: squared L2, float32, 16 interleaved partial sums, fixed tree      */
+
+float oracle_dist(const float *a, const float *b, int32_t d)
+{
+    float acc[16];
+    for (int l = 0; l < 16; ++l) acc[l] = 0.0f;
+    for (int32_t j = 0; j < d; ++j) {
+        float diff = a[j] - b[j];
+        acc[j & 15] = fmaf(diff, diff, acc[j & 15]);
+    }
+    for (int s = 8; s >= 1; s >>= 1)
+        for (int l = 0; l < s; ++l) acc[l] = acc[l] + acc[l + s];
+    return acc[0];
+}
+
+/* ------------------------------------------------------------------------- */
+/* Alg. 2: randomized truncated KD-trees                                       */
+
+static int64_t quantise(float x) { return (int64_t)rint((double)x * 1048576.0); }
+
+typedef struct {
+    const float *X;
+    int64_t n;
+    int32_t d, S, tree;
+    uint64_t seed;
+    int32_t *perm;     /* this tree's id array, partitioned in place */
+    int32_t *tmp;      /* scratch of n ids */
+    int32_t *leaf_off; /* this tree's leaf offsets */
+    int32_t n_leaves;
+} tree_ctx;
+
+static void build_node(tree_ctx *c, uint64_t heap_id, int32_t depth, int64_t b, int64_t e)
+{
+    int64_t cnt = e - b;
+    if (cnt <= c->S) { /* leaf: record where it starts */
+        c->leaf_off[c->n_leaves++] = (int32_t)b;
+        return;
+    }
+    int64_t mid = b; /* first position of the right part */
+    if (depth < 60) {
+        int32_t dim = (int32_t)(oracle_node_rand(c->seed, c->tree, heap_id) % (uint64_t)c->d);
+        int64_t sum = 0;
+        for (int64_t p = b; p < e; ++p) sum += quantise(c->X[(int64_t)c->perm[p] * c->d + dim]);
+        int64_t nl = 0, nr = 0;
+        for (int64_t p = b; p < e; ++p) { /* stable: both parts keep their order */
+            int32_t id = c->perm[p];
+            if (cnt * quantise(c->X[(int64_t)id * c->d + dim]) < sum) c->perm[b + nl++] = id;
+            else c->tmp[nr++] = id;
+        }
+        memcpy(c->perm + b + nl, c->tmp, (size_t)nr * sizeof(int32_t));
+        mid = b + nl;
+    }
+    if (mid == b || mid == e) mid = b + cnt / 2; /* degenerate: positional halves */
+    /* heap ids past depth 60 are never used for a draw; keep them from wrapping */
+    uint64_t child = depth < 60 ? 2 * heap_id : heap_id;
+    build_node(c, child, depth + 1, b, mid);
+    build_node(c, child + 1, depth + 1, mid, e);
+}
+
+/* perm: [T][n] ids, leaves contiguous, left-to-right.  leaf_off: [T][n+1] start
+ * position of every leaf, terminated by n.  n_leaves: [T]. */
+int oracle_build_trees(const float *X, int64_t n, int32_t d, int32_t T, int32_t S, uint64_t seed,
+                       int32_t *perm, int32_t *leaf_off, int32_t *n_leaves)
+{
+    if (!X || n < 1 || d < 1 || T < 1 || S < 1) return -1;
+    int32_t *tmp = (int32_t *)malloc((size_t)n * sizeof(int32_t));
+    if (!tmp) return -4;
+    for (int32_t t = 0; t < T; ++t) {
+        tree_ctx c = {X, n, d, S, t, seed, perm + (int64_t)t * n, tmp,
+                      leaf_off + (int64_t)t * (n + 1), 0};
+        for (int64_t i = 0; i < n; ++i) c.perm[i] = (int32_t)i;
+        build_node(&c, 1, 0, 0, n);
+        c.leaf_off[c.n_leaves] = (int32_t)n;
+        n_leaves[t] = c.n_leaves;
+    }
+    free(tmp);
+    return 0;
+}
+
+/* ------------------------------------------------------------------------- */
+/* pools: per point up to K entries sorted by (dist, id); id -1 / +inf = empty  */
+
+typedef struct { float dist; int32_t id; uint8_t is_new; } entry;
+
+static int entry_less(float da, int32_t ia, float db, int32_t ib)
+{
+    return da < db || (da == db && ia < ib);
+}
+
+/* pool := K smallest of pool U {(dist,id,new)}; an id already present is kept
+ * as it is.  Returns 1 if the entry went in. */
+static int pool_insert(entry *pool, int32_t *cnt, int32_t K, float dist, int32_t id)
+{
+    for (int32_t s = 0; s < *cnt; ++s)
+        if (pool[s].id == id) return 0;
+    if (*cnt == K && !entry_less(dist, id, pool[K - 1].dist, pool[K - 1].id)) return 0;
+    int32_t s = (*cnt < K) ? (*cnt)++ : K - 1;
+    while (s > 0 && entry_less(dist, id, pool[s - 1].dist, pool[s - 1].id)) {
+        pool[s] = pool[s - 1];
+        --s;
+    }
+    pool[s].dist = dist;
+    pool[s].id = id;
+    pool[s].is_new = 1;
+    return 1;
+}
+
+static void pools_load(entry *pool, int32_t *cnt, int64_t n, int32_t K, const int32_t *ids,
+                       const float *dists, const uint8_t *flags)
+{
+    for (int64_t i = 0; i < n; ++i) {
+        int32_t c = 0;
+        for (int32_t s = 0; s < K; ++s)
+            if (ids[i * K + s] >= 0) {
+                entry *e = &pool[i * K + c++];
+                e->id = ids[i * K + s];
+                e->dist = dists[i * K + s];
+                e->is_new = flags[i * K + s];
+            }
+        cnt[i] = c;
+    }
+}
+
+static void pools_store(const entry *pool, const int32_t *cnt, int64_t n, int32_t K, int32_t *ids,
+                        float *dists, uint8_t *flags)
+{
+    for (int64_t i = 0; i < n; ++i)
+        for (int32_t s = 0; s < K; ++s) {
+            int live = s < cnt[i];
+            ids[i * K + s] = live ? pool[i * K + s].id : -1;
+            dists[i * K + s] = live ? pool[i * K + s].dist : INFINITY;
+            flags[i * K + s] = live ? pool[i * K + s].is_new : 0;
+        }
+}
+
+/* ------------------------------------------------------------------------- */
+/* Alg. 3, conquer step at the leaves: for each point, the candidates are the   */
+/* other members of its leaf in every tree; keep the K closest.                 */
+
+static int cmp_i32(const void *a, const void *b)
+{
+    int32_t x = *(const int32_t *)a, y = *(const int32_t *)b;
+    return (x > y) - (x < y);
+}
+
+/* rows == NULL: all points, output row r belongs to point r.  Otherwise output
+ * row r belongs to point rows[r].  Outputs are [n_rows][K]. */
+int oracle_init_graph(const float *X, int64_t n, int32_t d, const int32_t *perm,
+                      const int32_t *leaf_off, const int32_t *n_leaves, int32_t T, int32_t K,
+                      const int64_t *rows, int64_t n_rows, int32_t *ids, float *dists,
+                      uint8_t *flags)
+{
+    if (!X || !perm || !leaf_off || !n_leaves || n < 1 || K < 1 || T < 1) return -1;
+    if (!rows) n_rows = n;
+    /* leaf_of[t][i] = index of the leaf of tree t that holds point i */
+    int32_t *leaf_of = (int32_t *)malloc((size_t)T * n * sizeof(int32_t));
+    if (!leaf_of) return -4;
+    int32_t max_leaf = 0;
+    for (int32_t t = 0; t < T; ++t) {
+        const int32_t *off = leaf_off + (int64_t)t * (n + 1);
+        for (int32_t l = 0; l < n_leaves[t]; ++l) {
+            if (off[l + 1] - off[l] > max_leaf) max_leaf = off[l + 1] - off[l];
+            for (int32_t p = off[l]; p < off[l + 1]; ++p)
+                leaf_of[(int64_t)t * n + perm[(int64_t)t * n + p]] = l;
+        }
+    }
+    int64_t cap = (int64_t)T * max_leaf;
+#pragma omp parallel
+    {
+        int32_t *cand = (int32_t *)malloc((size_t)cap * sizeof(int32_t));
+        entry *pool = (entry *)malloc((size_t)K * sizeof(entry));
+#pragma omp for schedule(dynamic, 256)
+        for (int64_t r = 0; r < n_rows; ++r) {
+            int64_t i = rows ? rows[r] : r;
+            int64_t nc = 0;
+            for (int32_t t = 0; t < T; ++t) {
+                const int32_t *off = leaf_off + (int64_t)t * (n + 1);
+                int32_t l = leaf_of[(int64_t)t * n + i];
+                for (int32_t p = off[l]; p < off[l + 1]; ++p) {
+                    int32_t j = perm[(int64_t)t * n + p];
+                    if (j != i) cand[nc++] = j;
+                }
+            }
+            qsort(cand, (size_t)nc, sizeof(int32_t), cmp_i32);
+            int32_t cnt = 0;
+            for (int64_t c = 0; c < nc; ++c) {
+                if (c > 0 && cand[c] == cand[c - 1]) continue;
+                int32_t j = cand[c];
+                pool_insert(pool, &cnt, K, oracle_dist(X + i * d, X + (int64_t)j * d, d), j);
+            }
+            for (int32_t s = 0; s < K; ++s) {
+                ids[r * K + s] = s < cnt ? pool[s].id : -1;
+                dists[r * K + s] = s < cnt ? pool[s].dist : INFINITY;
+                flags[r * K + s] = s < cnt ? 1 : 0; /* Alg. 4: G_new = G_init */
+            }
+        }
+        free(cand);
+        free(pool);
+    }
+    free(leaf_of);
+    return 0;
+}
+
+/* ------------------------------------------------------------------------- */
+/* Alg. 4: NN-descent refinement                                               */
+
+typedef struct { uint32_t hash; int32_t id; } rcand;
+
+static int cmp_rcand(const void *a, const void *b)
+{
+    const rcand *x = (const rcand *)a, *y = (const rcand *)b;
+    if (x->hash != y->hash) return (x->hash > y->hash) - (x->hash < y->hash);
+    return (x->id > y->id) - (x->id < y->id);
+}
+
+/* rev[v] = the (at most L) sources u with v in fwd[u] that have the smallest
+ * (hash(seed, iter, v, u), u). */
+static void reverse_lists(const int32_t *fwd, const int32_t *fwd_cnt, int32_t fwd_stride, int64_t n,
+                          int32_t L, uint64_t seed, int32_t iter, int32_t *rev, int32_t *rev_cnt)
+{
+    int64_t *start = (int64_t *)calloc((size_t)n + 1, sizeof(int64_t));
+    for (int64_t u = 0; u < n; ++u)
+        for (int32_t s = 0; s < fwd_cnt[u]; ++s) start[fwd[u * fwd_stride + s] + 1]++;
+    for (int64_t v = 0; v < n; ++v) start[v + 1] += start[v];
+    rcand *all = (rcand *)malloc((size_t)(start[n] > 0 ? start[n] : 1) * sizeof(rcand));
+    int64_t *fill = (int64_t *)malloc((size_t)n * sizeof(int64_t));
+    memcpy(fill, start, (size_t)n * sizeof(int64_t));
+    for (int64_t u = 0; u < n; ++u)
+        for (int32_t s = 0; s < fwd_cnt[u]; ++s) {
+            int32_t v = fwd[u * fwd_stride + s];
+            rcand *c = &all[fill[v]++];
+            c->id = (int32_t)u;
+            c->hash = oracle_reverse_hash(seed, iter, v, (int32_t)u);
+        }
+    for (int64_t v = 0; v < n; ++v) {
+        int64_t m = start[v + 1] - start[v];
+        qsort(all + start[v], (size_t)m, sizeof(rcand), cmp_rcand);
+        int32_t keep = m < L ? (int32_t)m : L;
+        for (int32_t s = 0; s < keep; ++s) rev[v * L + s] = all[start[v] + s].id;
+        rev_cnt[v] = keep;
+    }
+    free(fill);
+    free(all);
+    free(start);
+}
+
+static int32_t sorted_union(const int32_t *a, int32_t na, const int32_t *b, int32_t nb, int32_t *out)
+{
+    int32_t m = 0;
+    for (int32_t s = 0; s < na; ++s) out[m++] = a[s];
+    for (int32_t s = 0; s < nb; ++s) out[m++] = b[s];
+    qsort(out, (size_t)m, sizeof(int32_t), cmp_i32);
+    int32_t u = 0;
+    for (int32_t s = 0; s < m; ++s)
+        if (s == 0 || out[s] != out[s - 1]) out[u++] = out[s];
+    return u;
+}
+
+/* ids/dists/flags: [n][K] pools, in and out (sorted by (dist,id), empties last).
+ * iter0: index of the first iteration (a resumed run passes the number already
+ * done).  stats: [iters][2] = {distance evaluations, accepted insertions}; the
+ * second figure counts insertions that may be evicted again within the same
+ * iteration, so unlike the pools it depends on the order of evaluation. */
+int oracle_nndescent(const float *X, int64_t n, int32_t d, int32_t K, int32_t *ids, float *dists,
+                     uint8_t *flags, int32_t iters, int32_t L, uint64_t seed, int32_t iter0,
+                     uint64_t *stats)
+{
+    if (!X || !ids || !dists || !flags || n < 2 || K < 1 || L < 1 || iters < 0) return -1;
+    entry *pool = (entry *)malloc((size_t)n * K * sizeof(entry));
+    int32_t *cnt = (int32_t *)malloc((size_t)n * sizeof(int32_t));
+    int32_t *nw = (int32_t *)malloc((size_t)n * L * sizeof(int32_t));
+    int32_t *od = (int32_t *)malloc((size_t)n * K * sizeof(int32_t));
+    int32_t *rnw = (int32_t *)malloc((size_t)n * L * sizeof(int32_t));
+    int32_t *rod = (int32_t *)malloc((size_t)n * L * sizeof(int32_t));
+    int32_t *nw_c = (int32_t *)malloc((size_t)n * sizeof(int32_t));
+    int32_t *od_c = (int32_t *)malloc((size_t)n * sizeof(int32_t));
+    int32_t *rnw_c = (int32_t *)malloc((size_t)n * sizeof(int32_t));
+    int32_t *rod_c = (int32_t *)malloc((size_t)n * sizeof(int32_t));
+#ifdef _OPENMP
+    omp_lock_t *lock = (omp_lock_t *)malloc((size_t)n * sizeof(omp_lock_t));
+    for (int64_t i = 0; i < n; ++i) omp_init_lock(&lock[i]);
+#endif
+    pools_load(pool, cnt, n, K, ids, dists, flags);
+
+    for (int32_t it = 0; it < iters; ++it) {
+        /* sample: walk each pool in ascending order; the first L new-flagged
+         * entries become the "new" set (and lose their flag), old-flagged
+         * entries met on the way become the "old" set. */
+        for (int64_t i = 0; i < n; ++i) {
+            int32_t a = 0, b = 0;
+            for (int32_t s = 0; s < cnt[i] && a < L; ++s) {
+                entry *e = &pool[i * K + s];
+                if (e->is_new) {
+                    nw[i * L + a++] = e->id;
+                    e->is_new = 0;
+                } else {
+                    od[i * K + b++] = e->id;
+                }
+            }
+            nw_c[i] = a;
+            od_c[i] = b;
+        }
+        reverse_lists(nw, nw_c, L, n, L, seed, 2 * (iter0 + it), rnw, rnw_c);
+        reverse_lists(od, od_c, K, n, L, seed, 2 * (iter0 + it) + 1, rod, rod_c);
+
+        /* local join: every unordered pair inside U_new and every pair of
+         * U_new x U_old is evaluated once and proposed to both end points. */
+        uint64_t evals = 0, updates = 0;
+#pragma omp parallel reduction(+ : evals, updates)
+        {
+            int32_t *un = (int32_t *)malloc((size_t)2 * L * sizeof(int32_t));
+            int32_t *uo = (int32_t *)malloc((size_t)(K + L) * sizeof(int32_t));
+#pragma omp for schedule(dynamic, 64)
+            for (int64_t i = 0; i < n; ++i) {
+                int32_t n_new = sorted_union(nw + i * L, nw_c[i], rnw + i * L, rnw_c[i], un);
+                int32_t n_all = sorted_union(od + i * K, od_c[i], rod + i * L, rod_c[i], uo);
+                int32_t n_old = 0;
+                for (int32_t s = 0; s < n_all; ++s) /* U_old \ U_new */
+                    if (!bsearch(&uo[s], un, (size_t)n_new, sizeof(int32_t), cmp_i32))
+                        uo[n_old++] = uo[s];
+                for (int32_t a = 0; a < n_new; ++a) {
+                    int32_t u = un[a];
+                    for (int32_t b = a + 1; b < n_new + n_old; ++b) {
+                        int32_t v = b < n_new ? un[b] : uo[b - n_new];
+                        float dist = oracle_dist(X + (int64_t)u * d, X + (int64_t)v * d, d);
+                        ++evals;
+#ifdef _OPENMP
+                        omp_set_lock(&lock[u]);
+#endif
+                        updates += pool_insert(pool + (int64_t)u * K, &cnt[u], K, dist, v);
+#ifdef _OPENMP
+                        omp_unset_lock(&lock[u]);
+                        omp_set_lock(&lock[v]);
+#endif
+                        updates += pool_insert(pool + (int64_t)v * K, &cnt[v], K, dist, u);
+#ifdef _OPENMP
+                        omp_unset_lock(&lock[v]);
+#endif
+                    }
+                }
+            }
+            free(un);
+            free(uo);
+        }
+        if (stats) {
+            stats[2 * it] = evals;
+            stats[2 * it + 1] = updates;
+        }
+    }
+    pools_store(pool, cnt, n, K, ids, dists, flags);
+#ifdef _OPENMP
+    for (int64_t i = 0; i < n; ++i) omp_destroy_lock(&lock[i]);
+    free(lock);
+#endif
+    free(rod_c); free(rnw_c); free(od_c); free(nw_c);
+    free(rod); free(rnw); free(od); free(nw);
+    free(cnt); free(pool);
+    return 0;
+}
+
+void oracle_set_num_threads(int t)
+{
+#ifdef _OPENMP
+    if (t > 0) omp_set_num_threads(t);
+#else
+    (void)t;
+#endif
+}
+
+int oracle_num_threads(void)
+{
+#ifdef _OPENMP
+    return omp_get_max_threads();
+#else
+    return 1;
+#endif
+}

@@ -1,0 +1,128 @@
+"""Pins for the oracle's randomized truncated KD-trees (Alg. 2): hand-computable
+cases, structural invariants, and an independent top-down re-derivation of every
+split in Python integers."""
+import numpy as np
+import pytest
+
+import oracle
+from paper_1609_07228_amd import synth
+
+
+def leaves_of(perm_t, off_t, nl):
+    return [perm_t[off_t[l]:off_t[l + 1]] for l in range(nl)]
+
+
+def test_hand_case_perfect_binary_tree():
+    # one dimension, values 0..7, leaf size 2: mean 3.5 -> {0..3},{4..7}; then 1.5
+    # and 5.5 -> four leaves of two, whatever the seed (d = 1 leaves no choice)
+    X = np.arange(8, dtype=np.float32).reshape(8, 1)
+    for seed in (0, 1, 99):
+        perm, off, nl = oracle.build_trees(X, T=3, S=2, seed=seed)
+        for t in range(3):
+            assert nl[t] == 4
+            assert off[t, :5].tolist() == [0, 2, 4, 6, 8]
+            assert perm[t].tolist() == list(range(8))
+
+
+def test_hand_case_shuffled_values_stable_partition():
+    # values chosen so that ids interleave: mean of [5,1,7,3,6,0,4,2] = 3.5
+    X = np.array([5, 1, 7, 3, 6, 0, 4, 2], dtype=np.float32).reshape(8, 1)
+    perm, off, nl = oracle.build_trees(X, T=1, S=4, seed=3)
+    # left = ids with value < 3.5 in id order, right likewise
+    assert perm[0].tolist() == [1, 3, 5, 7, 0, 2, 4, 6]
+    assert nl[0] == 2 and off[0, :3].tolist() == [0, 4, 8]
+
+
+def test_value_equal_to_mean_goes_right():
+    X = np.array([0, 2, 4, 2], dtype=np.float32).reshape(4, 1)  # mean 2
+    perm, off, nl = oracle.build_trees(X, T=1, S=3, seed=0)
+    assert perm[0].tolist() == [0, 1, 2, 3]
+    assert off[0, :3].tolist() == [0, 1, 4]
+
+
+def test_all_equal_points_split_into_positional_halves():
+    X = np.full((10, 4), 3.25, dtype=np.float32)
+    perm, off, nl = oracle.build_trees(X, T=2, S=3, seed=5)
+    for t in range(2):
+        assert perm[t].tolist() == list(range(10))          # nothing moves
+        assert off[t, :nl[t] + 1].tolist() == [0, 2, 5, 7, 10]  # 10 -> 5+5 -> (2,3)+(2,3)
+
+
+def test_single_leaf_when_n_le_S():
+    X = np.random.default_rng(0).standard_normal((7, 3)).astype(np.float32)
+    perm, off, nl = oracle.build_trees(X, T=1, S=7, seed=0)
+    assert nl[0] == 1 and off[0, :2].tolist() == [0, 7] and perm[0].tolist() == list(range(7))
+
+
+def q(x):
+    # round-half-even of x * 2^20, exact: Python floats are doubles and the
+    # product of a float32 value with 2^20 is exact in a double
+    return round(float(x) * 1048576.0)
+
+
+def rederive(X, T, S, seed):
+    """Top-down rebuild with Python integers: every segment of every tree must be
+    sorted(left ids) ++ sorted(right ids) of the mean split on the node's dimension."""
+    n, d = X.shape
+    perms, offs = [], []
+    for t in range(T):
+        out, off = [], []
+
+        def rec(ids, h, depth):
+            if len(ids) <= S:
+                off.append(len(out))
+                out.extend(ids)
+                return
+            dim = oracle.node_rand(seed, t, h) % d
+            qs = [q(X[i, dim]) for i in ids]
+            tot = sum(qs)
+            left = [i for i, v in zip(ids, qs) if len(ids) * v < tot]
+            right = [i for i, v in zip(ids, qs) if not len(ids) * v < tot]
+            if not left or not right:
+                left, right = ids[:len(ids) // 2], ids[len(ids) // 2:]
+            rec(left, 2 * h, depth + 1)
+            rec(right, 2 * h + 1, depth + 1)
+
+        rec(list(range(n)), 1, 0)
+        off.append(n)
+        perms.append(out)
+        offs.append(off)
+    return perms, offs
+
+
+@pytest.mark.parametrize("name,n,T,S", [("gmm10k_d32", 3000, 4, 8), ("sift100k_like", 2500, 3, 16),
+                                         ("mixed4m_d96", 2000, 2, 64)])
+def test_rederivation_in_python_integers(name, n, T, S):
+    X = synth.generate(name, n=n)
+    perm, off, nl = oracle.build_trees(X, T=T, S=S, seed=synth.ALGO_SEED)
+    perms, offs = rederive(X, T, S, synth.ALGO_SEED)
+    for t in range(T):
+        assert perm[t].tolist() == perms[t]
+        assert off[t, :nl[t] + 1].tolist() == offs[t]
+
+
+def test_structural_invariants_and_randomisation():
+    X = synth.generate("sift100k_like", n=20000)
+    T, S = 4, 16
+    perm, off, nl = oracle.build_trees(X, T=T, S=S, seed=1)
+    perm2, off2, nl2 = oracle.build_trees(X, T=T, S=S, seed=1)
+    assert np.array_equal(perm, perm2) and np.array_equal(off, off2)
+    for t in range(T):
+        assert np.array_equal(np.sort(perm[t]), np.arange(20000))
+        o = off[t, :nl[t] + 1]
+        sizes = np.diff(o)
+        assert o[0] == 0 and o[-1] == 20000 and sizes.min() >= 1 and sizes.max() <= S
+        for leaf in leaves_of(perm[t], o, nl[t]):
+            assert np.all(np.diff(leaf) > 0)       # ids ascending inside a leaf
+    assert not np.array_equal(perm[0], perm[1])    # trees differ
+    perm3, _, _ = oracle.build_trees(X, T=T, S=S, seed=2)
+    assert not np.array_equal(perm, perm3)         # seeds differ
+
+
+def test_quantisation_ties_and_large_values():
+    # values closer than 2^-21 quantise together; mean compare stays exact near 2^20
+    X = np.array([[1.0], [1.0 + 2.0 ** -23], [1000000.0], [-1000000.0], [3.0], [5.0]],
+                 dtype=np.float32)
+    perm, off, nl = oracle.build_trees(X, T=1, S=1, seed=0)
+    perms, offs = rederive(X, 1, 1, 0)
+    assert perm[0].tolist() == perms[0] and off[0, :nl[0] + 1].tolist() == offs[0]
