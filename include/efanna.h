@@ -1,0 +1,163 @@
+/*
+ * efanna.h - C ABI of the gfx950 (MI355X) kNN-graph construction library.
+ *
+ * The library builds an approximate K-nearest-neighbour graph over N float32 vectors
+ * of dimension d under squared L2 distance, following the offline index-building
+ * path of EFANNA (arXiv 1609.07228, Section 3.3): randomized truncated KD-trees
+ * (Alg. 2) divide the points, a brute-force pass inside every leaf gives each point
+ * its initial neighbours (Alg. 3 with the conquer depth at the leaves), and NN-descent
+ * local joins refine the graph (Alg. 4).
+ *
+ * Conventions shared by every entry point
+ *  - Pointers marked [device] are device (HBM) addresses owned by the caller; the
+ *    library neither allocates nor frees device memory.  Temporary storage comes from
+ *    a caller-provided workspace (`ws`, `ws_bytes`, 256-byte aligned); its required
+ *    size is returned by the matching *_workspace_bytes function.  Workspace contents
+ *    need not survive between calls.
+ *  - Pointers marked [host] are ordinary host addresses.
+ *  - `stream` is a hipStream_t (NULL = the default stream).  Work is enqueued on it;
+ *    entry points documented as synchronising wait for that stream before returning.
+ *  - Return value: EFANNA_OK or a negative efanna_status.  Argument errors are
+ *    detected on the host before anything is launched.
+ *  - Distances are SQUARED Euclidean distances evaluated in float32 with a fixed
+ *    order of operations: partial sum l (0..15) accumulates, by fused multiply-add
+ *    and in ascending j, the squares of the differences of coordinates j = l mod 16;
+ *    the sixteen partial sums are then added as l += l+8, l += l+4, l += l+2,
+ *    l += l+1.  The value is symmetric in its arguments and is the one stored,
+ *    compared and returned everywhere.  Lists are ordered by (distance, id).
+ *  - Results are a deterministic function of the inputs and the seed: concurrent
+ *    list updates are set operations (a list ends up holding the K smallest
+ *    (distance, id) keys ever proposed to it), so scheduling cannot change them.
+ *  - Calls that use the same graph, workspace or stream concurrently race; calls on
+ *    distinct buffers and streams are independent.  The library keeps no global state.
+ */
+#ifndef EFANNA_H
+#define EFANNA_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    EFANNA_OK = 0,
+    EFANNA_EINVAL = -1,     /* null pointer or parameter out of range                 */
+    EFANNA_EWORKSPACE = -2, /* workspace missing, misaligned or too small             */
+    EFANNA_EINPUT = -3,     /* X holds a non-finite value or |x| >= 2^20              */
+    EFANNA_EHIP = -4,       /* a HIP runtime call failed                              */
+    EFANNA_ECAPACITY = -5,  /* a tree has more leaves than `max_leaves`               */
+    EFANNA_EUNSUPPORTED = -6 /* shape outside what the kernels handle (see each call) */
+} efanna_status;
+
+/* Limits of this build (checked, EFANNA_EUNSUPPORTED / EFANNA_EINVAL beyond them). */
+#define EFANNA_MAX_K 128        /* graph degree                                        */
+#define EFANNA_MAX_SAMPLE 64    /* NN-descent sample size L                            */
+#define EFANNA_MAX_LEAF 64      /* leaf population S                                   */
+#define EFANNA_MAX_TREES 64
+
+/* A graph entry: bits 63..32 float32 bit pattern of the squared distance, bits 31..1
+ * neighbour id, bit 0 the "new" mark of Alg. 4.  An empty slot has distance +inf.
+ * Rows of `graph` are K such entries in no particular order. */
+typedef uint64_t efanna_entry;
+
+const char *efanna_status_string(int status);
+
+/* ---- Alg. 2: randomized truncated KD-trees ------------------------------------------
+ * For each of n_trees trees the n point ids are partitioned recursively: a node with
+ * more than leaf_size points draws a dimension uniformly (counter-based generator
+ * keyed by seed, tree index and the node's heap id: root 1, children 2h and 2h+1),
+ * and sends to the left the points whose coordinate is below the node's mean, keeping
+ * the relative order of ids on both sides.  The mean test is exact: coordinates are
+ * quantised to multiples of 2^-20 and compared as cnt*q(x) < sum(q).  If one side
+ * would be empty (or below depth 60) the node is cut into positional halves.
+ *
+ * X        [device] n*d float32, row-major, finite, |x| < 2^20.
+ * perm     [device] out, n_trees*n int32: ids of tree t at perm[t*n ..], every leaf a
+ *          contiguous run, leaves in left-to-right order, ids ascending inside a leaf.
+ * leaf_off [device] out, n_trees*(max_leaves+1) int32: start of each leaf of tree t
+ *          within perm[t*n ..], followed by n.
+ * n_leaves [host]   out, n_trees int32.
+ * max_leaves        capacity of leaf_off per tree (n always suffices).
+ * Synchronises the stream (the host drives one launch group per tree level).
+ * Limits: n*n_trees < 2^31, 1 <= leaf_size <= EFANNA_MAX_LEAF, n_trees <= EFANNA_MAX_TREES.
+ */
+size_t efanna_trees_workspace_bytes(int64_t n, int32_t n_trees, int32_t leaf_size);
+
+int efanna_build_trees(const float *X, int64_t n, int32_t d, int32_t n_trees, int32_t leaf_size,
+                       uint64_t seed, int32_t *perm, int32_t *leaf_off, int32_t max_leaves,
+                       int32_t *n_leaves, void *ws, size_t ws_bytes, void *stream);
+
+/* ---- Alg. 3, conquer step at the leaves ----------------------------------------------
+ * Every pair of points that share a leaf in some tree is evaluated once per tree and
+ * proposed to both end points; graph row i ends up holding the K closest distinct
+ * leaf-mates of i over all trees (fewer if there are fewer; the rest of the row is
+ * empty).  Every entry carries the "new" mark (Alg. 4 starts from G_new = G_init).
+ *
+ * perm, leaf_off, max_leaves, n_leaves: as produced by efanna_build_trees.
+ * graph    [device] out, n*k entries.
+ * Asynchronous on `stream`.  Limits: k <= EFANNA_MAX_K, k < n, n < 2^31 - 256, a leaf
+ * of leaf_size rows of d floats must fit the 160 KB LDS.
+ */
+size_t efanna_init_workspace_bytes(int64_t n, int32_t n_trees);
+
+int efanna_init_graph(const float *X, int64_t n, int32_t d, const int32_t *perm,
+                      const int32_t *leaf_off, int32_t max_leaves, const int32_t *n_leaves,
+                      int32_t n_trees, int32_t leaf_size, int32_t k, efanna_entry *graph,
+                      void *ws, size_t ws_bytes, void *stream);
+
+/* ---- Alg. 4: NN-descent refinement -----------------------------------------------------
+ * Runs `iters` iterations with pool size P = k.  One iteration: (1) in every row the
+ * sample_L closest entries carrying the new mark form the row's "new" set and lose the
+ * mark, unmarked entries closer than the last of them form its "old" set; (2) reverse
+ * lists are the transposes of those sets, each capped at sample_L members by keeping
+ * the smallest seeded hash of (iteration, target, source); (3) for every point the
+ * union of its new and reverse-new sets is joined with itself and with the union of
+ * its old and reverse-old sets: each unordered pair is evaluated once and proposed to
+ * both end points; (4) a row keeps the k smallest (distance, id) among its entries and
+ * the proposals, an id already present keeping its entry and mark, fresh entries marked
+ * new.  There is no early termination.
+ *
+ * graph    [device] in/out.  The call may be repeated to continue refining: pass the
+ *          number of iterations already done as first_iter so that the hash stream
+ *          continues (k calls of one iteration equal one call of k iterations).
+ * stats    [device] out or NULL: iters*2 uint64: {distance evaluations, accepted list
+ *          insertions} per iteration.  The first is deterministic; the second counts
+ *          insertions that may be displaced later in the same iteration.
+ * Asynchronous on `stream`.  Limits: k <= EFANNA_MAX_K, sample_L <= EFANNA_MAX_SAMPLE,
+ * (3*sample_L + k) rows of d floats must fit the 160 KB LDS.
+ */
+size_t efanna_nndescent_workspace_bytes(int64_t n, int32_t k, int32_t sample_L);
+
+int efanna_nndescent(const float *X, int64_t n, int32_t d, int32_t k, efanna_entry *graph,
+                     int32_t iters, int32_t sample_L, uint64_t seed, int32_t first_iter,
+                     uint64_t *stats, void *ws, size_t ws_bytes, void *stream);
+
+/* ---- result ("Ensure: approximate kNN graph G") -------------------------------------
+ * Sorts every row by (distance, id) and unpacks it.
+ * ids   [device] out, n*k int32, -1 in empty slots (always at the tail).
+ * dists [device] out, n*k float32 squared distances, +inf in empty slots.
+ * flags [device] out or NULL, n*k uint8: the new marks.
+ * Asynchronous on `stream`; does not modify graph.
+ */
+int efanna_get_graph(const efanna_entry *graph, int64_t n, int32_t k, int32_t *ids, float *dists,
+                     uint8_t *flags, void *stream);
+
+/* Inverse of efanna_get_graph: packs (ids, dists, flags) rows into graph entries, so
+ * that NN-descent can start from any initial graph (for example a random one).
+ * Empty slots are given by id < 0 (ids >= n are treated the same way).  flags NULL marks
+ * every entry new.  Asynchronous on `stream`. */
+int efanna_set_graph(efanna_entry *graph, int64_t n, int32_t k, const int32_t *ids,
+                     const float *dists, const uint8_t *flags, void *stream);
+
+/* Squared distances of m explicit pairs, in the library's fixed order of operations
+ * (the definition at the top of this file).  a_ids, b_ids [device] m int32; out
+ * [device] m float32.  Asynchronous on `stream`. */
+int efanna_pair_distances(const float *X, int64_t n, int32_t d, const int32_t *a_ids,
+                          const int32_t *b_ids, int64_t m, float *out, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* EFANNA_H */

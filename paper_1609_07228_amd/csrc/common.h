@@ -1,0 +1,164 @@
+// Device-side helpers shared by the gfx950 kernels: counter-based generator, packed
+// graph entries, the lock-free bounded list insertion and small wave utilities.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "../../include/efanna.h"
+
+typedef unsigned long long u64;
+typedef unsigned int u32;
+
+#define EF_WAVE 64
+#define EF_INF_BITS 0x7F800000u
+
+#define EF_HIP_CHECK(expr)                         \
+    do {                                           \
+        hipError_t e_ = (expr);                    \
+        if (e_ != hipSuccess) return EFANNA_EHIP;  \
+    } while (0)
+
+// ---- counter-based generator (SplitMix64 finaliser) ---------------------------------
+__host__ __device__ inline u64 ef_mix64(u64 z)
+{
+    z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ULL;
+    z = (z ^ (z >> 27)) * 0x94D049BB133111EBULL;
+    return z ^ (z >> 31);
+}
+// stream key for (seed, k): tree index for node draws, iteration stream for reverse hashes
+__host__ __device__ inline u64 ef_stream_key(u64 seed, int k)
+{
+    return ef_mix64(seed + 0x9E3779B97F4A7C15ULL * (u64)(k + 1));
+}
+
+// ---- packed graph entries -------------------------------------------------------------
+__device__ inline u64 ef_pack(float dist, int id, int is_new)
+{
+    return ((u64)__float_as_uint(dist) << 32) | ((u64)(u32)id << 1) | (u64)(is_new & 1);
+}
+// slot s of an empty row: +inf with a per-slot id so that all entries of a row differ
+__host__ __device__ inline u64 ef_empty_entry(int slot)
+{
+    return ((u64)EF_INF_BITS << 32) | ((u64)(0x7FFFFFFFu - (u32)slot) << 1);
+}
+__device__ inline u32 ef_dist_bits(u64 e) { return (u32)(e >> 32); }
+__device__ inline int ef_id(u64 e) { return (int)((u32)e >> 1); }
+__device__ inline bool ef_is_empty(u64 e) { return ef_dist_bits(e) >= EF_INF_BITS; }
+
+__device__ inline u64 ef_load_coherent(const u64 *p)
+{
+    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ inline u32 ef_load_coherent(const u32 *p)
+{
+    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+// ---- lock-free bounded insertion ---------------------------------------------------------
+// `list` holds `cap` distinct 64-bit keys.  The call makes the list hold the `cap`
+// smallest keys of (list U {key}), where two keys are the same element when they agree
+// after dropping the lowest `ignore` bits (the new mark of a graph entry).
+//
+// Why concurrent calls are safe without a lock: a slot is only ever overwritten by a
+// smaller key (compare-and-swap of the slot that held the maximum of a snapshot), so
+// slot values decrease monotonically.  A successful CAS proves that slot still held the
+// snapshot's maximum; every other slot can only have got smaller since it was read, so
+// the replaced key was the true maximum at that instant, and the inserted key cannot
+// have appeared elsewhere in the meantime (it would have had to replace a maximum no
+// smaller than the one just replaced).  The final content is therefore the set of the
+// `cap` smallest keys ever offered, whatever the interleaving.
+//
+// Returns true if the key went in; *new_max then holds an upper bound of the list's
+// maximum after the insertion.
+__device__ inline bool ef_bounded_insert(u64 *list, int cap, u64 key, int ignore, u64 *new_max)
+{
+    const u64 kcmp = key >> ignore;
+    for (;;) {
+        u64 mx = 0, mx2 = 0;
+        int ms = 0;
+        bool dup = false;
+        for (int s = 0; s < cap; ++s) {
+            u64 e = ef_load_coherent(list + s);
+            dup |= (e >> ignore) == kcmp;
+            if (e > mx) {
+                mx2 = mx;
+                mx = e;
+                ms = s;
+            } else if (e > mx2) {
+                mx2 = e;
+            }
+        }
+        if (dup || kcmp >= (mx >> ignore)) return false;
+        u64 seen = atomicCAS(list + ms, mx, key);
+        if (seen == mx) {
+            *new_max = key > mx2 ? key : mx2;
+            return true;
+        }
+    }
+}
+
+// ---- wave utilities ---------------------------------------------------------------------
+__device__ inline int ef_lane() { return (int)(threadIdx.x & (EF_WAVE - 1)); }
+
+__device__ inline long long ef_wave_sum_i64(long long v)
+{
+    for (int m = 32; m >= 1; m >>= 1) v += __shfl_xor(v, m, EF_WAVE);
+    return v;
+}
+__device__ inline int ef_wave_sum_i32(int v)
+{
+    for (int m = 32; m >= 1; m >>= 1) v += __shfl_xor(v, m, EF_WAVE);
+    return v;
+}
+// inclusive prefix sum over the wave
+__device__ inline int ef_wave_scan_i32(int v)
+{
+    const int lane = ef_lane();
+    for (int o = 1; o < EF_WAVE; o <<= 1) {
+        int t = __shfl_up(v, o, EF_WAVE);
+        if (lane >= o) v += t;
+    }
+    return v;
+}
+
+// Squared L2 distance in the library's fixed order, evaluated by a group of 16
+// consecutive lanes: lane l of the group owns partial sum l.  Every lane of the group
+// returns the full value.  All 16 lanes must be active.
+__device__ inline float ef_group_reduce16(float acc)
+{
+    acc += __shfl_xor(acc, 8, 16);
+    acc += __shfl_xor(acc, 4, 16);
+    acc += __shfl_xor(acc, 2, 16);
+    acc += __shfl_xor(acc, 1, 16);
+    return acc;
+}
+
+// 16 partial sums per lane (one per pair of a 4x4 tile) across a 16-lane group ->
+// lane l keeps the total of pair l.  Same adds, in the same tree, as ef_group_reduce16
+// applied to each pair, but with 15 exchanges instead of 64.
+__device__ inline float ef_group_transpose_reduce16(const float (&acc)[16], int gl)
+{
+    float a8[8], a4[4], a2[2];
+    const bool b3 = gl & 8, b2 = gl & 4, b1 = gl & 2, b0 = gl & 1;
+#pragma unroll
+    for (int k = 0; k < 8; ++k) {
+        float keep = b3 ? acc[k + 8] : acc[k];
+        float send = b3 ? acc[k] : acc[k + 8];
+        a8[k] = keep + __shfl_xor(send, 8, 16);
+    }
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+        float keep = b2 ? a8[k + 4] : a8[k];
+        float send = b2 ? a8[k] : a8[k + 4];
+        a4[k] = keep + __shfl_xor(send, 4, 16);
+    }
+#pragma unroll
+    for (int k = 0; k < 2; ++k) {
+        float keep = b1 ? a4[k + 2] : a4[k];
+        float send = b1 ? a4[k] : a4[k + 2];
+        a2[k] = keep + __shfl_xor(send, 2, 16);
+    }
+    float keep = b0 ? a2[1] : a2[0];
+    float send = b0 ? a2[0] : a2[1];
+    return keep + __shfl_xor(send, 1, 16);
+}

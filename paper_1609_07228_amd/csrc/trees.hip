@@ -1,0 +1,426 @@
+// Randomized truncated KD-trees (Alg. 2) for gfx950.
+//
+// All trees are built together, one level per launch group.  The ids of tree t live in
+// positions [t*n, (t+1)*n) of one array of T*n "positions"; a node is a segment of
+// positions.  Per level:
+//   1. sum      every position adds its quantised coordinate (on the node's dimension)
+//               to the node's 64-bit integer sum (wave-reduced when a wave lies inside
+//               one node, integer atomics otherwise: exact in any order);
+//   2. scan     device-wide exclusive prefix sum of the "goes left" predicate
+//               cnt*q(x) < sum, from which every position derives its rank inside
+//               its node, i.e. a stable partition without any per-node launch;
+//   3. children one thread per node fixes the split point, appends the children that
+//               still hold more than leaf_size points to the next level's node table
+//               and marks the first position of children that became leaves;
+//   4. scatter  every position moves its id to its place in the child segment.
+// The host reads one counter per level (the number of nodes of the next level).
+#include "common.h"
+
+namespace {
+
+constexpr int kBlock = 256;
+constexpr int kScanItems = 8;                       // per thread
+constexpr int kScanTile = kBlock * kScanItems;      // positions per scan block
+
+struct Node {
+    int b, e;        // segment of positions [b, e)
+    u64 heap;        // heap id: root 1, children 2h, 2h+1
+    long long sum;   // sum of quantised coordinates
+    int dim;         // split dimension, -1: positional split only (depth cap)
+    int depth;
+    int mid;         // first position of the right child
+    int moved;       // 1: mean split, 0: positional halves (ids stay where they are)
+    int child[2];    // index in the next level's table, -1 if that child is a leaf
+};
+
+struct Counters {
+    int next_nodes;
+    int bad_input;
+};
+
+__device__ inline long long quantise(float x) { return (long long)rint((double)x * 1048576.0); }
+
+__global__ void check_input_kernel(const float *__restrict__ X, size_t total, Counters *c)
+{
+    size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    size_t stride = (size_t)gridDim.x * blockDim.x;
+    bool bad = false;
+    for (; i < total; i += stride) {
+        float x = X[i];
+        bad |= !(fabsf(x) < 1048576.0f);   // false for NaN and inf as well
+    }
+    if (__any(bad) && ef_lane() == 0) atomicOr(&c->bad_input, 1);
+}
+
+__global__ void roots_kernel(Node *nodes, int *node_of, unsigned char *leaf_flag, int n, int T,
+                             int S, u64 seed, int d, Counters *c)
+{
+    size_t p = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    size_t total = (size_t)n * T;
+    const bool live = n > S;
+    if (p < total) {
+        node_of[p] = live ? (int)(p / (size_t)n) : -1;
+        leaf_flag[p] = (!live && p % (size_t)n == 0) ? 1 : 0;
+    }
+    if (p < (size_t)T && live) {
+        Node nd;
+        nd.b = (int)p * n;
+        nd.e = nd.b + n;
+        nd.heap = 1;
+        nd.sum = 0;
+        nd.dim = (int)(ef_mix64(ef_stream_key(seed, (int)p) + 1) % (u64)d);
+        nd.depth = 0;
+        nd.mid = nd.b;
+        nd.moved = 0;
+        nd.child[0] = nd.child[1] = -1;
+        nodes[p] = nd;
+    }
+    if (p == 0) c->next_nodes = 0;
+}
+
+__global__ void sum_kernel(const float *__restrict__ X, int d, const int *__restrict__ perm,
+                           const int *__restrict__ node_of, Node *nodes, float *__restrict__ val,
+                           size_t total)
+{
+    size_t p = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    int s = -1;
+    long long q = 0;
+    if (p < total) {
+        s = node_of[p];
+        if (s >= 0) {
+            int dim = nodes[s].dim;
+            if (dim >= 0) {
+                float x = X[(size_t)perm[p] * d + dim];
+                val[p] = x;
+                q = quantise(x);
+            } else {
+                s = -1;
+            }
+        }
+    }
+    int s0 = __shfl(s, 0, EF_WAVE);
+    if (__all(s == s0)) {
+        if (s0 < 0) return;
+        long long tot = ef_wave_sum_i64(q);
+        if (ef_lane() == 0) atomicAdd((u64 *)&nodes[s0].sum, (u64)tot);
+    } else if (s >= 0) {
+        atomicAdd((u64 *)&nodes[s].sum, (u64)q);
+    }
+}
+
+// predicate sources for the scan
+struct LeftPred {
+    const int *node_of;
+    const Node *nodes;
+    const float *val;
+    __device__ int operator()(size_t p) const
+    {
+        int s = node_of[p];
+        if (s < 0) return 0;
+        const Node &nd = nodes[s];
+        if (nd.dim < 0) return 0;
+        long long cnt = nd.e - nd.b;
+        return cnt * quantise(val[p]) < nd.sum ? 1 : 0;
+    }
+};
+struct FlagPred {
+    const unsigned char *flag;
+    __device__ int operator()(size_t p) const { return flag[p]; }
+};
+
+__device__ inline int block_sum(int v, int *sh)
+{
+    v = ef_wave_sum_i32(v);
+    if (ef_lane() == 0) sh[threadIdx.x / EF_WAVE] = v;
+    __syncthreads();
+    int tot = 0;
+    for (int w = 0; w < kBlock / EF_WAVE; ++w) tot += sh[w];
+    __syncthreads();
+    return tot;
+}
+
+template <class Pred>
+__global__ void scan_reduce_kernel(Pred pred, size_t total, int *block_sums)
+{
+    __shared__ int sh[kBlock / EF_WAVE];
+    size_t base = (size_t)blockIdx.x * kScanTile + (size_t)threadIdx.x * kScanItems;
+    int v = 0;
+    for (int k = 0; k < kScanItems; ++k)
+        if (base + k < total) v += pred(base + k);
+    int tot = block_sum(v, sh);
+    if (threadIdx.x == 0) block_sums[blockIdx.x] = tot;
+}
+
+// exclusive scan of block_sums in place, single block; block_sums[nb] = grand total
+__global__ void scan_blocksums_kernel(int *block_sums, int nb)
+{
+    __shared__ int sh[kBlock / EF_WAVE];
+    __shared__ int carry_sh;
+    if (threadIdx.x == 0) carry_sh = 0;
+    __syncthreads();
+    for (int base = 0; base < nb; base += kBlock) {
+        int i = base + threadIdx.x;
+        int v = i < nb ? block_sums[i] : 0;
+        int inc = ef_wave_scan_i32(v);
+        if (ef_lane() == EF_WAVE - 1) sh[threadIdx.x / EF_WAVE] = inc;
+        __syncthreads();
+        int woff = 0;
+        for (int w = 0; w < (int)(threadIdx.x / EF_WAVE); ++w) woff += sh[w];
+        int carry = carry_sh;
+        if (i < nb) block_sums[i] = carry + woff + inc - v;
+        __syncthreads();
+        if (threadIdx.x == kBlock - 1) carry_sh = carry + woff + inc;
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) block_sums[nb] = carry_sh;
+}
+
+// out[p] = number of set predicates before p; out[total] = grand total
+template <class Pred>
+__global__ void scan_apply_kernel(Pred pred, size_t total, const int *block_sums, int nb, int *out)
+{
+    __shared__ int sh[kBlock / EF_WAVE];
+    size_t base = (size_t)blockIdx.x * kScanTile + (size_t)threadIdx.x * kScanItems;
+    int f[kScanItems];
+    int v = 0;
+    for (int k = 0; k < kScanItems; ++k) {
+        f[k] = base + k < total ? pred(base + k) : 0;
+        v += f[k];
+    }
+    int inc = ef_wave_scan_i32(v);
+    if (ef_lane() == EF_WAVE - 1) sh[threadIdx.x / EF_WAVE] = inc;
+    __syncthreads();
+    int off = block_sums[blockIdx.x] + inc - v;
+    for (int w = 0; w < (int)(threadIdx.x / EF_WAVE); ++w) off += sh[w];
+    for (int k = 0; k < kScanItems; ++k) {
+        if (base + k < total) out[base + k] = off;
+        off += f[k];
+    }
+    if (blockIdx.x == 0 && threadIdx.x == 0) out[total] = block_sums[nb];
+}
+
+__global__ void children_kernel(Node *cur, int n_cur, Node *next, const int *__restrict__ lcount,
+                                unsigned char *leaf_flag, int S, u64 seed, int n, int d,
+                                Counters *c)
+{
+    int s = blockIdx.x * blockDim.x + threadIdx.x;
+    int live[2] = {0, 0};
+    Node nd;
+    if (s < n_cur) {
+        nd = cur[s];
+        int cnt = nd.e - nd.b;
+        int nl = nd.dim >= 0 ? lcount[nd.e] - lcount[nd.b] : 0;
+        if (nl == 0 || nl == cnt) {
+            nd.moved = 0;
+            nd.mid = nd.b + cnt / 2;
+        } else {
+            nd.moved = 1;
+            nd.mid = nd.b + nl;
+        }
+        live[0] = (nd.mid - nd.b) > S;
+        live[1] = (nd.e - nd.mid) > S;
+    }
+    // one counter bump per wave
+    int want = live[0] + live[1];
+    int inc = ef_wave_scan_i32(want);
+    int wave_total = __shfl(inc, EF_WAVE - 1, EF_WAVE);
+    int base = 0;
+    if (ef_lane() == EF_WAVE - 1 && wave_total > 0) base = atomicAdd(&c->next_nodes, wave_total);
+    base = __shfl(base, EF_WAVE - 1, EF_WAVE);
+    if (s >= n_cur) return;
+    int slot = base + inc - want;
+    const int tree = nd.b / n;
+    const u64 key = ef_stream_key(seed, tree);
+    for (int side = 0; side < 2; ++side) {
+        int cb = side ? nd.mid : nd.b, ce = side ? nd.e : nd.mid;
+        if (live[side]) {
+            Node ch;
+            ch.b = cb;
+            ch.e = ce;
+            ch.depth = nd.depth + 1;
+            // below depth 60 heap ids would overflow: such nodes only split positionally
+            ch.heap = nd.depth < 60 ? 2 * nd.heap + side : nd.heap;
+            ch.dim = ch.depth < 60 ? (int)(ef_mix64(key + ch.heap) % (u64)d) : -1;
+            ch.sum = 0;
+            ch.mid = cb;
+            ch.moved = 0;
+            ch.child[0] = ch.child[1] = -1;
+            next[slot] = ch;
+            nd.child[side] = slot++;
+        } else {
+            nd.child[side] = -1;
+            leaf_flag[cb] = 1;
+        }
+    }
+    cur[s] = nd;
+}
+
+__global__ void scatter_kernel(const int *__restrict__ perm_in, int *__restrict__ perm_out,
+                               const int *__restrict__ node_in, int *__restrict__ node_out,
+                               const Node *__restrict__ nodes, const float *__restrict__ val,
+                               const int *__restrict__ lcount, size_t total)
+{
+    size_t p = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (p >= total) return;
+    int s = node_in[p];
+    int id = perm_in[p];
+    if (s < 0) {
+        perm_out[p] = id;
+        node_out[p] = -1;
+        return;
+    }
+    const Node nd = nodes[s];
+    size_t dst = p;
+    if (nd.moved) {
+        long long cnt = nd.e - nd.b;
+        bool left = cnt * quantise(val[p]) < nd.sum;
+        int lc = lcount[p] - lcount[nd.b];
+        dst = left ? (size_t)nd.b + lc : (size_t)nd.mid + ((int)(p - nd.b) - lc);
+    }
+    perm_out[dst] = id;
+    node_out[dst] = nd.child[dst < (size_t)nd.mid ? 0 : 1];
+}
+
+__global__ void iota_kernel(int *perm, int n, size_t total)
+{
+    size_t p = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (p < total) perm[p] = (int)(p % (size_t)n);
+}
+
+__global__ void leaf_offsets_kernel(const unsigned char *__restrict__ leaf_flag,
+                                    const int *__restrict__ rank, int n, int T, int max_leaves,
+                                    int *__restrict__ leaf_off, int *__restrict__ n_leaves_dev)
+{
+    size_t p = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    size_t total = (size_t)n * T;
+    if (p < total && leaf_flag[p]) {
+        int t = (int)(p / (size_t)n);
+        int idx = rank[p] - rank[(size_t)t * n];
+        if (idx < max_leaves) leaf_off[(size_t)t * (max_leaves + 1) + idx] = (int)(p - (size_t)t * n);
+    }
+    if (p < (size_t)T) {
+        int t = (int)p;
+        int cnt = rank[(size_t)(t + 1) * n] - rank[(size_t)t * n];
+        n_leaves_dev[t] = cnt;
+        if (cnt <= max_leaves) leaf_off[(size_t)t * (max_leaves + 1) + cnt] = n;
+    }
+}
+
+inline size_t align_up(size_t x) { return (x + 255) & ~(size_t)255; }
+
+struct TreeWs {
+    int *perm_tmp, *node_a, *node_b, *lcount, *block_sums, *n_leaves_dev;
+    float *val;
+    unsigned char *leaf_flag;
+    Node *nodes_a, *nodes_b;
+    Counters *counters;
+    size_t bytes;
+};
+
+TreeWs carve(void *ws, int64_t n, int32_t T, int32_t S)
+{
+    size_t total = (size_t)n * T;
+    size_t max_nodes = total / (size_t)(S + 1) + (size_t)T + 1;
+    size_t nb = (total + kScanTile - 1) / kScanTile;
+    char *p = (char *)ws;
+    size_t off = 0;
+    TreeWs w;
+    auto take = [&](size_t bytes) {
+        char *r = p ? p + off : nullptr;
+        off += align_up(bytes);
+        return r;
+    };
+    w.perm_tmp = (int *)take(total * 4);
+    w.node_a = (int *)take(total * 4);
+    w.node_b = (int *)take(total * 4);
+    w.lcount = (int *)take((total + 1) * 4);
+    w.val = (float *)take(total * 4);
+    w.leaf_flag = (unsigned char *)take(total);
+    w.block_sums = (int *)take((nb + 1) * 4);
+    w.nodes_a = (Node *)take(max_nodes * sizeof(Node));
+    w.nodes_b = (Node *)take(max_nodes * sizeof(Node));
+    w.n_leaves_dev = (int *)take((size_t)T * 4);
+    w.counters = (Counters *)take(sizeof(Counters));
+    w.bytes = off;
+    return w;
+}
+
+template <class Pred>
+void device_scan(Pred pred, size_t total, int *block_sums, int *out, hipStream_t st)
+{
+    int nb = (int)((total + kScanTile - 1) / kScanTile);
+    scan_reduce_kernel<<<nb, kBlock, 0, st>>>(pred, total, block_sums);
+    scan_blocksums_kernel<<<1, kBlock, 0, st>>>(block_sums, nb);
+    scan_apply_kernel<<<nb, kBlock, 0, st>>>(pred, total, block_sums, nb, out);
+}
+
+}  // namespace
+
+extern "C" size_t efanna_trees_workspace_bytes(int64_t n, int32_t n_trees, int32_t leaf_size)
+{
+    if (n < 1 || n_trees < 1 || leaf_size < 1) return 0;
+    return carve(nullptr, n, n_trees, leaf_size).bytes;
+}
+
+extern "C" int efanna_build_trees(const float *X, int64_t n, int32_t d, int32_t n_trees,
+                                  int32_t leaf_size, uint64_t seed, int32_t *perm,
+                                  int32_t *leaf_off, int32_t max_leaves, int32_t *n_leaves,
+                                  void *ws, size_t ws_bytes, void *stream)
+{
+    if (!X || !perm || !leaf_off || !n_leaves) return EFANNA_EINVAL;
+    if (n < 1 || d < 1 || n_trees < 1 || n_trees > EFANNA_MAX_TREES || leaf_size < 1 ||
+        leaf_size > EFANNA_MAX_LEAF || max_leaves < 1)
+        return EFANNA_EINVAL;
+    if ((double)n * n_trees >= 2147483647.0 - 4096.0) return EFANNA_EINVAL;
+    if (!ws || ((uintptr_t)ws & 255) || ws_bytes < efanna_trees_workspace_bytes(n, n_trees, leaf_size))
+        return EFANNA_EWORKSPACE;
+    hipStream_t st = (hipStream_t)stream;
+    const int T = n_trees, S = leaf_size;
+    const size_t total = (size_t)n * T;
+    const int grid_pos = (int)((total + kBlock - 1) / kBlock);
+    TreeWs w = carve(ws, n, T, S);
+
+    EF_HIP_CHECK(hipMemsetAsync(w.counters, 0, sizeof(Counters), st));
+    check_input_kernel<<<1024, kBlock, 0, st>>>(X, (size_t)n * d, w.counters);
+    iota_kernel<<<grid_pos, kBlock, 0, st>>>(perm, (int)n, total);
+    roots_kernel<<<grid_pos, kBlock, 0, st>>>(w.nodes_a, w.node_a, w.leaf_flag, (int)n, T, S, seed,
+                                              d, w.counters);
+    Counters host_c;
+    EF_HIP_CHECK(hipMemcpyAsync(&host_c, w.counters, sizeof(Counters), hipMemcpyDeviceToHost, st));
+    EF_HIP_CHECK(hipStreamSynchronize(st));
+    if (host_c.bad_input) return EFANNA_EINPUT;
+
+    int *perm_cur = perm, *perm_nxt = w.perm_tmp;
+    int *node_cur = w.node_a, *node_nxt = w.node_b;
+    Node *nodes_cur = w.nodes_a, *nodes_nxt = w.nodes_b;
+    int n_cur = n > S ? T : 0;
+    while (n_cur > 0) {
+        sum_kernel<<<grid_pos, kBlock, 0, st>>>(X, d, perm_cur, node_cur, nodes_cur, w.val, total);
+        LeftPred pred{node_cur, nodes_cur, w.val};
+        device_scan(pred, total, w.block_sums, w.lcount, st);
+        children_kernel<<<(n_cur + kBlock - 1) / kBlock, kBlock, 0, st>>>(
+            nodes_cur, n_cur, nodes_nxt, w.lcount, w.leaf_flag, S, seed, (int)n, d, w.counters);
+        scatter_kernel<<<grid_pos, kBlock, 0, st>>>(perm_cur, perm_nxt, node_cur, node_nxt, nodes_cur,
+                                                    w.val, w.lcount, total);
+        EF_HIP_CHECK(hipMemcpyAsync(&host_c, w.counters, sizeof(Counters), hipMemcpyDeviceToHost, st));
+        EF_HIP_CHECK(hipMemsetAsync(&w.counters->next_nodes, 0, sizeof(int), st));
+        EF_HIP_CHECK(hipStreamSynchronize(st));
+        n_cur = host_c.next_nodes;
+        int *tp = perm_cur; perm_cur = perm_nxt; perm_nxt = tp;
+        int *tn = node_cur; node_cur = node_nxt; node_nxt = tn;
+        Node *tq = nodes_cur; nodes_cur = nodes_nxt; nodes_nxt = tq;
+    }
+    if (perm_cur != perm)
+        EF_HIP_CHECK(hipMemcpyAsync(perm, perm_cur, total * 4, hipMemcpyDeviceToDevice, st));
+
+    FlagPred fp{w.leaf_flag};
+    device_scan(fp, total, w.block_sums, w.lcount, st);
+    leaf_offsets_kernel<<<grid_pos, kBlock, 0, st>>>(w.leaf_flag, w.lcount, (int)n, T, max_leaves,
+                                                     leaf_off, w.n_leaves_dev);
+    EF_HIP_CHECK(hipMemcpyAsync(n_leaves, w.n_leaves_dev, (size_t)T * 4, hipMemcpyDeviceToHost, st));
+    EF_HIP_CHECK(hipStreamSynchronize(st));
+    EF_HIP_CHECK(hipGetLastError());
+    for (int t = 0; t < T; ++t)
+        if (n_leaves[t] > max_leaves) return EFANNA_ECAPACITY;
+    return EFANNA_OK;
+}

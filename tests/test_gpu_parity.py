@@ -1,0 +1,218 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU oracle on the
+same seeded inputs.  Integer / index results must agree bit for bit; the library's
+distances use the same fixed order of float32 operations as the oracle, so they agree
+bit for bit as well (which is stronger than the 1e-5 relative bound that is also
+checked against float64)."""
+import numpy as np
+import pytest
+
+import oracle
+from paper_1609_07228_amd import synth
+
+torch = pytest.importorskip("torch")
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def ef():
+    if not torch.cuda.is_available():
+        pytest.fail("GPU tests need a GPU: there is no CPU fallback")
+    from paper_1609_07228_amd import efanna
+    efanna.lib()
+    return efanna
+
+
+def dev(a):
+    return torch.from_numpy(np.ascontiguousarray(a)).to("cuda:0")
+
+
+def host(t):
+    return t.cpu().numpy()
+
+
+def trees_equal(ef, X, T, S, seed):
+    perm, off, nl = ef.efanna_build_trees(dev(X), T, S, seed)
+    operm, ooff, onl = oracle.build_trees(X, T, S, seed)
+    assert np.array_equal(nl, onl)
+    assert np.array_equal(host(perm), operm)
+    goff = host(off)
+    for t in range(T):
+        assert np.array_equal(goff[t, :nl[t] + 1], ooff[t, :onl[t] + 1])
+    return (perm, off, nl), (operm, ooff, onl)
+
+
+# ---------------------------------------------------------------------------------
+def test_pair_distances_bit_exact(ef):
+    rng = np.random.default_rng(0)
+    for d in (1, 5, 16, 31, 32, 96, 128, 960, 1000):
+        X = (rng.standard_normal((300, d)) * rng.choice([0.01, 1.0, 100.0], (300, 1))).astype(np.float32)
+        a = rng.integers(0, 300, 777).astype(np.int32)
+        b = rng.integers(0, 300, 777).astype(np.int32)
+        got = host(ef.efanna_pair_distances(dev(X), dev(a), dev(b)))
+        want = np.array([oracle.dist(X[i], X[j]) for i, j in zip(a, b)], dtype=np.float32)
+        assert got.tobytes() == want.tobytes(), f"d={d}"
+        ref = ((X[a].astype(np.float64) - X[b].astype(np.float64)) ** 2).sum(axis=1)
+        assert np.all(np.abs(got - ref) <= 1e-5 * ref)
+
+
+@pytest.mark.parametrize("name,n,T,S", [
+    ("gmm10k_d32", 10_000, 4, 8),          # the small configuration, full size
+    ("gmm10k_d32", 4_097, 3, 5),           # ragged sizes
+    ("sift100k_like", 30_000, 8, 16),
+    ("mixed4m_d96", 20_000, 16, 64),
+    ("gist1m_like", 3_000, 2, 16),
+])
+def test_trees_bit_exact(ef, name, n, T, S):
+    X = synth.generate(name, n=n)
+    trees_equal(ef, X, T, S, synth.ALGO_SEED)
+
+
+def test_trees_edge_cases(ef):
+    rng = np.random.default_rng(3)
+    # n <= S: one leaf per tree
+    X = rng.standard_normal((7, 3)).astype(np.float32)
+    trees_equal(ef, X, 2, 7, 0)
+    # all points equal: positional halves everywhere
+    trees_equal(ef, np.full((1000, 4), 2.5, dtype=np.float32), 2, 3, 5)
+    # heavy ties on an integer grid, leaf size 1, d = 1
+    trees_equal(ef, rng.integers(0, 4, (5000, 1)).astype(np.float32), 3, 1, 9)
+    # strongly skewed data: deep unbalanced trees
+    trees_equal(ef, np.exp(rng.standard_normal((20000, 2)) * 4).astype(np.float32).clip(0, 1e5), 2, 4, 1)
+
+
+def test_trees_reject_bad_input(ef):
+    X = np.zeros((100, 4), dtype=np.float32)
+    X[17, 2] = np.nan
+    with pytest.raises(ef.EfannaError) as e:
+        ef.efanna_build_trees(dev(X), 2, 4, 0)
+    assert e.value.status == -3
+    X[17, 2] = 2.0 ** 21
+    with pytest.raises(ef.EfannaError) as e:
+        ef.efanna_build_trees(dev(X), 2, 4, 0)
+    assert e.value.status == -3
+    X[17, 2] = 0
+    with pytest.raises(ef.EfannaError) as e:
+        ef.efanna_build_trees(dev(X), 2, 4, 0, workspace=torch.empty(256, dtype=torch.uint8, device="cuda:0"))
+    assert e.value.status == -2
+    with pytest.raises(ef.EfannaError) as e:
+        ef.efanna_build_trees(dev(X), 2, 4, 0, max_leaves=3)
+    assert e.value.status == -5
+
+
+def graph_equal(ef, graph, want):
+    ids, dists, flags = ef.efanna_get_graph(graph, with_flags=True)
+    ids, dists, flags = host(ids), host(dists), host(flags)
+    assert np.array_equal(ids, want[0])
+    assert dists.tobytes() == want[1].tobytes()
+    assert np.array_equal(flags, want[2])
+    return ids, dists
+
+
+@pytest.mark.parametrize("name,n,T,S,K", [
+    ("gmm10k_d32", 10_000, 4, 8, 10),
+    ("sift100k_like", 20_000, 8, 16, 20),
+    ("mixed4m_d96", 12_000, 4, 64, 100),
+    ("gist1m_like", 3_000, 3, 16, 10),
+    ("gmm10k_d32", 1_003, 2, 3, 16),       # mostly under-full rows
+])
+def test_init_graph_bit_exact(ef, name, n, T, S, K):
+    X = synth.generate(name, n=n)
+    (perm, off, nl), (operm, ooff, onl) = trees_equal(ef, X, T, S, synth.ALGO_SEED)
+    graph = ef.efanna_init_graph(dev(X), perm, off, nl, S, K)
+    want = oracle.init_graph(X, operm, ooff, onl, K)
+    ids, dists = graph_equal(ef, graph, want)
+    oracle.check_graph_invariants(X, ids, dists)
+
+
+def test_init_graph_odd_dimension_and_single_leaf(ef):
+    rng = np.random.default_rng(5)
+    X = rng.standard_normal((40, 21)).astype(np.float32)
+    (perm, off, nl), (operm, ooff, onl) = trees_equal(ef, X, 1, 64, 0)
+    assert nl[0] == 1
+    graph = ef.efanna_init_graph(dev(X), perm, off, nl, 64, 7)
+    want = oracle.init_graph(X, operm, ooff, onl, 7)
+    ids, _ = graph_equal(ef, graph, want)
+    tid, _ = oracle.exact_knn_definition(X, 7)
+    assert np.array_equal(ids, tid)          # one leaf holding everything: the exact graph
+
+
+@pytest.mark.parametrize("name,n,T,S,K,L,I", [
+    ("gmm10k_d32", 10_000, 4, 8, 10, 10, 4),      # the small configuration as quoted
+    ("sift100k_like", 20_000, 8, 16, 20, 20, 3),
+    ("mixed4m_d96", 6_000, 4, 64, 100, 50, 2),
+    ("gist1m_like", 2_000, 3, 16, 10, 10, 2),
+    ("gmm10k_d32", 3_001, 2, 8, 12, 5, 3),        # L < K: marks survive an iteration
+])
+def test_nndescent_bit_exact_every_iteration(ef, name, n, T, S, K, L, I):
+    X = synth.generate(name, n=n)
+    Xd = dev(X)
+    (perm, off, nl), (operm, ooff, onl) = trees_equal(ef, X, T, S, synth.ALGO_SEED)
+    graph = ef.efanna_init_graph(Xd, perm, off, nl, S, K)
+    want = oracle.init_graph(X, operm, ooff, onl, K)
+    for it in range(I):
+        stats = ef.efanna_nndescent(Xd, graph, 1, L, synth.ALGO_SEED, first_iter=it)
+        want = oracle.nndescent(X, *want[:3], 1, L, synth.ALGO_SEED, iter0=it)
+        ids, dists = graph_equal(ef, graph, want)
+        assert int(host(stats)[0, 0]) == int(want[3][0, 0])      # same pairs evaluated
+    oracle.check_graph_invariants(X, ids, dists)
+
+
+def test_nndescent_resume_and_recall(ef):
+    name = "gmm10k_d32"
+    p = synth.params(name)
+    X = synth.generate(name)
+    Xd = dev(X)
+    perm, off, nl = ef.efanna_build_trees(Xd, p["T"], p["S"], synth.ALGO_SEED)
+    g1 = ef.efanna_init_graph(Xd, perm, off, nl, p["S"], p["K"])
+    g2 = g1.clone()
+    ef.efanna_nndescent(Xd, g1, p["I"], p["L"], synth.ALGO_SEED)
+    for it in range(p["I"]):
+        ef.efanna_nndescent(Xd, g2, 1, p["L"], synth.ALGO_SEED, first_iter=it)
+    a, b = ef.efanna_get_graph(g1), ef.efanna_get_graph(g2)
+    assert torch.equal(a[0], b[0]) and torch.equal(a[1], b[1])
+    # recall against exact brute force equals the oracle's (the graphs are identical)
+    operm, ooff, onl = oracle.build_trees(X, p["T"], p["S"], synth.ALGO_SEED)
+    og = oracle.nndescent(X, *oracle.init_graph(X, operm, ooff, onl, p["K"]), p["I"], p["L"],
+                          synth.ALGO_SEED)
+    tid, _ = oracle.exact_knn(X, np.arange(X.shape[0]), p["K"])
+    r_gpu, r_cpu = oracle.recall(host(a[0]), tid), oracle.recall(og[0], tid)
+    assert abs(r_gpu - r_cpu) <= 0.005 and r_gpu > 0.8
+
+
+def test_set_get_roundtrip_and_random_start(ef):
+    rng = np.random.default_rng(8)
+    n, K = 3000, 10
+    X = rng.standard_normal((n, 6)).astype(np.float32)
+    ids = np.stack([rng.choice(np.delete(np.arange(n), i), K, replace=False) for i in range(n)]).astype(np.int32)
+    dists = np.array([[oracle.dist(X[i], X[j]) for j in row] for i, row in enumerate(ids)], dtype=np.float32)
+    order = np.lexsort((ids, dists), axis=1)
+    ids, dists = np.take_along_axis(ids, order, 1), np.take_along_axis(dists, order, 1)
+    ids[5, 7:] = -1
+    dists[5, 7:] = np.inf
+    flags = (ids >= 0).astype(np.uint8)
+    graph = ef.efanna_set_graph(dev(ids), dev(dists), dev(flags))
+    graph_equal(ef, graph, (ids, dists, flags))
+    # NN-descent from a random graph (the comparison method's starting point)
+    ef.efanna_nndescent(dev(X), graph, 6, K, 1)
+    want = oracle.nndescent(X, ids, dists, flags, 6, K, 1)
+    got_ids, _ = graph_equal(ef, graph, want)
+    tid, _ = oracle.exact_knn_definition(X, K)
+    assert oracle.recall(got_ids, tid) > 0.9
+
+
+def test_argument_errors(ef):
+    X = dev(np.zeros((100, 4), dtype=np.float32))
+    g = torch.zeros((100, 10), dtype=torch.int64, device="cuda:0")
+    for kwargs, status in [(dict(iters=1, sample_L=0, seed=0), -1),
+                           (dict(iters=1, sample_L=65, seed=0), -1),
+                           (dict(iters=-1, sample_L=4, seed=0), -1)]:
+        with pytest.raises(ef.EfannaError) as e:
+            ef.efanna_nndescent(X, g, **kwargs)
+        assert e.value.status == status
+    with pytest.raises(ef.EfannaError) as e:
+        ef.efanna_nndescent(X, g, 1, 4, 0, workspace=torch.empty(256, dtype=torch.uint8, device="cuda:0"))
+    assert e.value.status == -2
+    big = dev(np.zeros((200, 4000), dtype=np.float32))
+    with pytest.raises(ef.EfannaError) as e:      # (3L+K) rows of 4000 floats exceed the LDS
+        ef.efanna_nndescent(big, torch.zeros((200, 10), dtype=torch.int64, device="cuda:0"), 1, 10, 0)
+    assert e.value.status == -6
