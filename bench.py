@@ -1,0 +1,180 @@
+#!/usr/bin/env python3
+"""Benchmark of the whole kNN-graph construction path on one MI355X.
+
+One step = efanna_build_trees + efanna_init_graph + efanna_nndescent(I) +
+efanna_get_graph on a synthetic workload already resident in HBM.  Prints ONE JSON
+line: build seconds per step, distance evaluations per second, recall@K, the roofline
+of the dominant kernel (the NN-descent local join) and the CPU oracle timed on a
+bounded prefix of the same workload.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+sys.path.insert(0, os.path.dirname(os.path.abspath(__file__)))
+
+HBM_PEAK_GBS = 8000.0
+
+
+def exact_knn_torch(Xd, rows, K):
+    """Ground truth for recall on the sampled rows: float64 brute force with torch
+    (measurement infrastructure, outside the timed region and outside the library)."""
+    import torch
+    X64 = Xd.double()
+    norms = (X64 * X64).sum(1)
+    out = []
+    for r0 in range(0, rows.shape[0], 250):
+        rr = rows[r0:r0 + 250]
+        G = X64[rr] @ X64.T
+        G.mul_(-2.0).add_(norms[None, :]).add_(norms[rr][:, None])
+        G[torch.arange(rr.shape[0], device=G.device), rr] = float("inf")
+        out.append(torch.topk(G, K, dim=1, largest=False).indices)
+    return torch.cat(out).cpu().numpy()
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=3)
+    ap.add_argument("--warmup", type=int, default=1)
+    ap.add_argument("--workload", default="sift1m_like")
+    ap.add_argument("--n", type=int, default=None, help="use only the first n rows of the workload")
+    ap.add_argument("--cpu-rows", type=int, default=1_000_000,
+                    help="rows of the workload the CPU oracle is timed on (0 = skip)")
+    ap.add_argument("--recall-rows", type=int, default=10_000, help="0 = skip recall")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU; --gpus N with N > 1 is not supported "
+              "(no collectives, no sharding in this library)", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_1609_07228_amd import efanna, synth
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible; there is no CPU fallback", file=sys.stderr)
+        sys.exit(3)
+    efanna.lib()
+    name = args.workload
+    p = synth.params(name)
+    X = synth.generate(name, n=args.n)
+    n, d = X.shape
+    K, T, S, I, L = p["K"], p["T"], p["S"], p["I"], p["L"]
+    dev = torch.device("cuda:0")
+    Xd = torch.from_numpy(X).to(dev)
+    L_ = efanna.lib()
+    ws_tree = torch.empty(L_.efanna_trees_workspace_bytes(n, T, S), dtype=torch.uint8, device=dev)
+    ws_init = torch.empty(max(256, L_.efanna_init_workspace_bytes(n, T)), dtype=torch.uint8, device=dev)
+    ws_nnd = torch.empty(L_.efanna_nndescent_workspace_bytes(n, K, L), dtype=torch.uint8, device=dev)
+    graph = torch.empty((n, K), dtype=torch.int64, device=dev)
+    stats = torch.zeros((I, 4), dtype=torch.int64, device=dev)
+    phase_ms = np.zeros((I, 2), dtype=np.float32)
+    max_leaves = n // max(1, S // 4) + 16      # generous: mean splits leave leaves ~0.7*S full
+    state = {}
+    phases = np.zeros(4)
+    join_ms_sum, join_bytes_sum, join_launches = 0.0, 0.0, 0
+
+    def step(timed: bool):
+        nonlocal join_ms_sum, join_bytes_sum, join_launches
+        t0 = time.perf_counter()
+        perm, leaf_off, n_leaves = efanna.efanna_build_trees(Xd, T, S, synth.ALGO_SEED,
+                                                             max_leaves=max_leaves, workspace=ws_tree)
+        t1 = time.perf_counter()          # build_trees returns synchronised
+        efanna.efanna_init_graph(Xd, perm, leaf_off, n_leaves, S, K, graph=graph, workspace=ws_init)
+        torch.cuda.synchronize()
+        t2 = time.perf_counter()
+        efanna.efanna_nndescent(Xd, graph, I, L, synth.ALGO_SEED, stats=stats, workspace=ws_nnd,
+                                phase_ms=phase_ms)
+        t3 = time.perf_counter()          # synchronised by the phase timing
+        ids, dists = efanna.efanna_get_graph(graph)
+        torch.cuda.synchronize()
+        t4 = time.perf_counter()
+        if timed:
+            phases[:] += (t1 - t0, t2 - t1, t3 - t2, t4 - t3)
+            st = stats.cpu().numpy()
+            join_ms_sum += float(phase_ms[:, 1].sum())
+            join_bytes_sum += float((st[:, 2] * (d * 4 + 8) + st[:, 1] * 8).sum())
+            join_launches += I
+        state.update(perm=perm, leaf_off=leaf_off, n_leaves=n_leaves, ids=ids, dists=dists)
+
+    for _ in range(args.warmup):
+        step(False)
+    torch.cuda.synchronize()
+    t_begin = time.perf_counter()
+    for _ in range(args.steps):
+        step(True)
+    torch.cuda.synchronize()
+    seconds = (time.perf_counter() - t_begin) / max(1, args.steps)
+
+    # work done per step (identical in every step: the path is deterministic)
+    st = stats.cpu().numpy()
+    off = state["leaf_off"].cpu().numpy().astype(np.int64)
+    init_evals = 0
+    for t in range(T):
+        sizes = np.diff(off[t, :state["n_leaves"][t] + 1])
+        init_evals += int((sizes * (sizes - 1) // 2).sum())
+    evals = init_evals + int(st[:, 0].sum())
+
+    recall = None
+    if args.recall_rows > 0:
+        rows = synth.sample_rows(n, args.recall_rows)
+        truth = exact_knn_torch(Xd, torch.from_numpy(rows).to(dev), K)
+        got = state["ids"][torch.from_numpy(rows).to(dev)].cpu().numpy()
+        hits = sum(np.intersect1d(a[a >= 0], b).shape[0] for a, b in zip(got, truth))
+        recall = hits / float(truth.size)
+
+    cpu = None
+    if args.cpu_rows > 0:
+        import oracle
+        m = min(n, args.cpu_rows)
+        Xs = X[:m]
+        c0 = time.perf_counter()
+        operm, ooff, onl = oracle.build_trees(Xs, T, S, synth.ALGO_SEED)
+        g = oracle.init_graph(Xs, operm, ooff, onl, K)
+        g = oracle.nndescent(Xs, *g, I, L, synth.ALGO_SEED)
+        c_sec = time.perf_counter() - c0
+        c_evals = int(g[3][:, 0].sum())
+        for t in range(T):
+            sizes = np.diff(ooff[t, :onl[t] + 1]).astype(np.int64)
+            c_evals += int((sizes * (sizes - 1) // 2).sum())
+        cpu = {"value": c_evals / c_sec, "unit": "distance evals/s", "cores": oracle.num_threads(),
+               "kind": "oracle", "seconds": c_sec,
+               "sample": f"whole path (trees, leaf init, {I} NN-descent iterations) on the first "
+                         f"{m} rows of {name}"}
+
+    achieved = join_bytes_sum / 1e9 / (join_ms_sum / 1e3) if join_ms_sum > 0 else 0.0
+    out = {
+        "metric": "kNN-graph build seconds + distance evals/sec at recall@K, N=1M d=128 K=10",
+        "value": evals / seconds,
+        "unit": "distance evals/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": seconds * 1e3,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": name, "n": n, "d": d, "K": K, "trees": T, "leaf_size": S,
+                   "iterations": I, "sample_L": L},
+        "build_seconds": seconds,
+        "dist_evals_per_step": evals,
+        "recall_at_K": recall, "recall_rows": args.recall_rows if recall is not None else 0,
+        "phase_ms": {k: float(v) * 1e3 / max(1, args.steps)
+                     for k, v in zip(("trees", "init_graph", "nndescent", "get_graph"), phases)},
+        "nndescent_iter_ms": {"sample": [float(x) for x in phase_ms[:, 0]],
+                              "join": [float(x) for x in phase_ms[:, 1]]},
+        "roofline": {"kernel": "join_kernel", "bound": "hbm", "achieved": achieved,
+                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
+                     "traffic": None,
+                     "avg_launch_ms": join_ms_sum / max(1, join_launches),
+                     "algorithmic_bytes_per_launch": join_bytes_sum / max(1, join_launches)},
+        "cpu_baseline": cpu,
+    }
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -122,17 +122,21 @@ int efanna_init_graph(const float *X, int64_t n, int32_t d, const int32_t *perm,
  * graph    [device] in/out.  The call may be repeated to continue refining: pass the
  *          number of iterations already done as first_iter so that the hash stream
  *          continues (k calls of one iteration equal one call of k iterations).
- * stats    [device] out or NULL: iters*2 uint64: {distance evaluations, accepted list
- *          insertions} per iteration.  The first is deterministic; the second counts
- *          insertions that may be displaced later in the same iteration.
- * Asynchronous on `stream`.  Limits: k <= EFANNA_MAX_K, sample_L <= EFANNA_MAX_SAMPLE,
+ * stats    [device] out or NULL: iters*4 uint64 per iteration: {distance evaluations,
+ *          accepted list insertions, vectors gathered by the joins, 0}.  The first and
+ *          third are deterministic; the second counts insertions that may be displaced
+ *          later in the same iteration.
+ * phase_ms [host] out or NULL: iters*2 float: milliseconds of {sampling + reverse
+ *          lists, local join} per iteration, from HIP events on `stream`.  When given,
+ *          the call synchronises the stream before returning.
+ * Asynchronous on `stream` otherwise.  Limits: k <= EFANNA_MAX_K, sample_L <= EFANNA_MAX_SAMPLE,
  * (3*sample_L + k) rows of d floats must fit the 160 KB LDS.
  */
 size_t efanna_nndescent_workspace_bytes(int64_t n, int32_t k, int32_t sample_L);
 
 int efanna_nndescent(const float *X, int64_t n, int32_t d, int32_t k, efanna_entry *graph,
                      int32_t iters, int32_t sample_L, uint64_t seed, int32_t first_iter,
-                     uint64_t *stats, void *ws, size_t ws_bytes, void *stream);
+                     uint64_t *stats, float *phase_ms, void *ws, size_t ws_bytes, void *stream);
 
 /* ---- result ("Ensure: approximate kNN graph G") -------------------------------------
  * Sorts every row by (distance, id) and unpacks it.

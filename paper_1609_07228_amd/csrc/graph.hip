@@ -233,7 +233,7 @@ __global__ void join_kernel(const float *__restrict__ X, int n, int d, int strid
                             const int *__restrict__ nw_c, const int *__restrict__ od_c,
                             const u64 *__restrict__ rnew, const u64 *__restrict__ rold,
                             u64 *graph, u32 *worst, int *__restrict__ cnt_evals,
-                            int *__restrict__ cnt_upd)
+                            int *__restrict__ cnt_upd, int *__restrict__ cnt_rows)
 {
     extern __shared__ float smem[];
     const int max_new = 2 * L, max_old = K + L, max_rows = max_new + max_old;
@@ -306,11 +306,13 @@ __global__ void join_kernel(const float *__restrict__ X, int n, int d, int strid
     }
     __syncthreads();
     const int m_new = meta[0], m_old = meta[1], m = m_new + m_old;
-    if (tid == 0) cnt_evals[i] = m_new * (m_new - 1) / 2 + m_new * m_old;
-    if (m_new == 0 || m < 2) {
-        if (tid == 0) cnt_upd[i] = 0;
-        return;
+    const bool idle = m_new == 0 || m < 2;
+    if (tid == 0) {
+        cnt_evals[i] = m_new * (m_new - 1) / 2 + m_new * m_old;
+        cnt_rows[i] = idle ? 0 : m;
+        if (idle) cnt_upd[i] = 0;
     }
+    if (idle) return;
     // gather rows and thresholds
     const int wave = tid / EF_WAVE, lane = ef_lane(), n_waves = nthr / EF_WAVE;
     for (int r = wave; r < m; r += n_waves) {
@@ -351,18 +353,21 @@ __global__ void join_kernel(const float *__restrict__ X, int n, int d, int strid
 }
 
 __global__ void stats_kernel(const int *__restrict__ cnt_evals, const int *__restrict__ cnt_upd,
-                             int n, u64 *stats)
+                             const int *__restrict__ cnt_rows, int n, u64 *stats)
 {
-    long long ev = 0, up = 0;
+    long long ev = 0, up = 0, rw = 0;
     for (int i = blockIdx.x * blockDim.x + threadIdx.x; i < n; i += gridDim.x * blockDim.x) {
         ev += cnt_evals[i];
         up += cnt_upd[i];
+        rw += cnt_rows[i];
     }
     ev = ef_wave_sum_i64(ev);
     up = ef_wave_sum_i64(up);
+    rw = ef_wave_sum_i64(rw);
     if (ef_lane() == 0) {
         atomicAdd(stats, (u64)ev);
         atomicAdd(stats + 1, (u64)up);
+        atomicAdd(stats + 2, (u64)rw);
     }
 }
 
@@ -438,7 +443,7 @@ __global__ void pair_distances_kernel(const float *__restrict__ X, int d,
 }
 
 struct NndWs {
-    int *nw, *od, *nw_c, *od_c, *cnt_evals, *cnt_upd;
+    int *nw, *od, *nw_c, *od_c, *cnt_evals, *cnt_upd, *cnt_rows;
     u64 *rnew, *rold;
     u32 *worst;
     size_t bytes;
@@ -460,6 +465,7 @@ NndWs carve_nnd(void *ws, int64_t n, int K, int L)
     w.od_c = (int *)take((size_t)n * 4);
     w.cnt_evals = (int *)take((size_t)n * 4);
     w.cnt_upd = (int *)take((size_t)n * 4);
+    w.cnt_rows = (int *)take((size_t)n * 4);
     w.rnew = (u64 *)take((size_t)n * L * 8);
     w.rold = (u64 *)take((size_t)n * L * 8);
     w.worst = (u32 *)take((size_t)n * 4);
@@ -549,8 +555,8 @@ extern "C" size_t efanna_nndescent_workspace_bytes(int64_t n, int32_t k, int32_t
 
 extern "C" int efanna_nndescent(const float *X, int64_t n, int32_t d, int32_t k,
                                 efanna_entry *graph_, int32_t iters, int32_t sample_L,
-                                uint64_t seed, int32_t first_iter, uint64_t *stats_, void *ws,
-                                size_t ws_bytes, void *stream)
+                                uint64_t seed, int32_t first_iter, uint64_t *stats_,
+                                float *phase_ms, void *ws, size_t ws_bytes, void *stream)
 {
     if (!X || !graph_) return EFANNA_EINVAL;
     u64 *const graph = (u64 *)graph_;
@@ -572,21 +578,41 @@ extern "C" int efanna_nndescent(const float *X, int64_t n, int32_t d, int32_t k,
     int join_threads = max_pairs <= 1024 ? 64 : (max_pairs <= 4096 ? 128 : (max_pairs <= 12288 ? 256 : 512));
     EF_HIP_CHECK(hipFuncSetAttribute((const void *)join_kernel,
                                      hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-    if (stats) zero_u64_kernel<<<grid_for((size_t)iters * 2 + 1, kBlock), kBlock, 0, st>>>(stats, iters * 2);
+    if (stats) zero_u64_kernel<<<grid_for((size_t)iters * 4 + 1, kBlock), kBlock, 0, st>>>(stats, iters * 4);
     const int rows_per_block = kBlock / EF_WAVE;
+    // optional phase timing: events around the sampling and the join of every iteration
+    hipEvent_t *ev = nullptr;
+    if (phase_ms && iters > 0) {
+        ev = new hipEvent_t[(size_t)iters * 3];
+        for (int e = 0; e < iters * 3; ++e) EF_HIP_CHECK(hipEventCreate(&ev[e]));
+    }
     for (int it = 0; it < iters; ++it) {
         const int g = first_iter + it;
+        if (ev) EF_HIP_CHECK(hipEventRecord(ev[3 * it], st));
         fill_reverse_kernel<<<grid_for((size_t)n * L, kBlock), kBlock, 0, st>>>(w.rnew, w.rold,
                                                                               (size_t)n * L, L);
         sample_kernel<<<grid_for((size_t)n, rows_per_block), kBlock, 0, st>>>(
             graph, (int)n, K, L, ef_stream_key(seed, 2 * g), ef_stream_key(seed, 2 * g + 1), w.nw,
             w.od, w.nw_c, w.od_c, w.rnew, w.rold, w.worst);
+        if (ev) EF_HIP_CHECK(hipEventRecord(ev[3 * it + 1], st));
         join_kernel<<<(int)n, join_threads, lds, st>>>(X, (int)n, d, stride, K, L, w.nw, w.od, w.nw_c,
                                                        w.od_c, w.rnew, w.rold, graph, w.worst,
-                                                       w.cnt_evals, w.cnt_upd);
-        if (stats) stats_kernel<<<256, kBlock, 0, st>>>(w.cnt_evals, w.cnt_upd, (int)n, stats + 2 * it);
+                                                       w.cnt_evals, w.cnt_upd, w.cnt_rows);
+        if (ev) EF_HIP_CHECK(hipEventRecord(ev[3 * it + 2], st));
+        if (stats)
+            stats_kernel<<<256, kBlock, 0, st>>>(w.cnt_evals, w.cnt_upd, w.cnt_rows, (int)n,
+                                                 stats + 4 * it);
     }
     EF_HIP_CHECK(hipGetLastError());
+    if (ev) {
+        EF_HIP_CHECK(hipStreamSynchronize(st));
+        for (int it = 0; it < iters; ++it) {
+            EF_HIP_CHECK(hipEventElapsedTime(&phase_ms[2 * it], ev[3 * it], ev[3 * it + 1]));
+            EF_HIP_CHECK(hipEventElapsedTime(&phase_ms[2 * it + 1], ev[3 * it + 1], ev[3 * it + 2]));
+        }
+        for (int e = 0; e < iters * 3; ++e) hipEventDestroy(ev[e]);
+        delete[] ev;
+    }
     return EFANNA_OK;
 }
 
