@@ -166,6 +166,9 @@ def main():
                      for k, v in zip(("trees", "init_graph", "nndescent", "get_graph"), phases)},
         "nndescent_iter_ms": {"sample": [float(x) for x in phase_ms[:, 0]],
                               "join": [float(x) for x in phase_ms[:, 1]]},
+        "nndescent_iter_work": {"dist_evals": [int(x) for x in st[:, 0]],
+                                "insertions": [int(x) for x in st[:, 1]],
+                                "vectors_gathered": [int(x) for x in st[:, 2]]},
         "roofline": {"kernel": "join_kernel", "bound": "hbm", "achieved": achieved,
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
                      "traffic": None,

@@ -77,15 +77,23 @@ __device__ inline bool ef_bounded_insert(u64 *list, int cap, u64 key, int ignore
         u64 mx = 0, mx2 = 0;
         int ms = 0;
         bool dup = false;
-        for (int s = 0; s < cap; ++s) {
-            u64 e = ef_load_coherent(list + s);
-            dup |= (e >> ignore) == kcmp;
-            if (e > mx) {
-                mx2 = mx;
-                mx = e;
-                ms = s;
-            } else if (e > mx2) {
-                mx2 = e;
+        // eight slot reads in flight at a time: the row read costs one or two memory
+        // round trips instead of one per slot
+        for (int s0 = 0; s0 < cap; s0 += 8) {
+            u64 e[8];
+#pragma unroll
+            for (int k = 0; k < 8; ++k) e[k] = s0 + k < cap ? ef_load_coherent(list + s0 + k) : 0;
+#pragma unroll
+            for (int k = 0; k < 8; ++k) {
+                if (s0 + k >= cap) break;
+                dup |= (e[k] >> ignore) == kcmp;
+                if (e[k] > mx) {
+                    mx2 = mx;
+                    mx = e[k];
+                    ms = s0 + k;
+                } else if (e[k] > mx2) {
+                    mx2 = e[k];
+                }
             }
         }
         if (dup || kcmp >= (mx >> ignore)) return false;
