@@ -130,7 +130,8 @@ int efanna_init_graph(const float *X, int64_t n, int32_t d, const int32_t *perm,
  *          lists, local join} per iteration, from HIP events on `stream`.  When given,
  *          the call synchronises the stream before returning.
  * Asynchronous on `stream` otherwise.  Limits: k <= EFANNA_MAX_K, sample_L <= EFANNA_MAX_SAMPLE,
- * (3*sample_L + k) rows of d floats must fit the 160 KB LDS.
+ * if k + 2*sample_L > 32 (or rows are not 16-byte aligned), k + 2*sample_L rows of d floats
+ * must fit the 160 KB LDS.
  */
 size_t efanna_nndescent_workspace_bytes(int64_t n, int32_t k, int32_t sample_L);
 

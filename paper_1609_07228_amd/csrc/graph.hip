@@ -26,7 +26,7 @@ __host__ __device__ inline int align4(int x) { return (x + 3) & ~3; }
 __global__ void fill_reverse_kernel(u64 *a, u64 *b, size_t total, int L, int *work_count)
 {
     size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (i < 2) work_count[i] = 0;
+    if (i < 3) work_count[i] = 0;
     if (i < total) {
         u64 v = ~0ULL - (u64)(i % (size_t)L);
         a[i] = v;
@@ -116,64 +116,6 @@ __device__ inline int drain_queue(const Proposal *queue, int count, u64 *graph, 
         if (ef_bounded_insert(graph + (size_t)p.target * K, K, p.key, 1, &new_max)) {
             atomicMin(worst + p.target, ef_dist_bits(new_max));
             ++updates;
-        }
-    }
-    return updates;
-}
-
-// The local join of one set of rows held in LDS: rows [0, m_new) are joined with each
-// other and with rows [m_new, m).  uid: global ids, thr: threshold bits per row.
-// queue: LDS, capacity q_cap >= 4 * blockDim; q_count: LDS counter (zeroed by the caller
-// before the preceding barrier).  Returns this thread's number of accepted insertions.
-__device__ inline int join_rows(const float *rows, int stride, int d, const int *uid,
-                                const u32 *thr, int m_new, int m, Proposal *queue, int *q_count,
-                                int q_cap, u64 *graph, u32 *worst, int K)
-{
-    const int tid = threadIdx.x, nthr = blockDim.x;
-    const int ntr = (m_new + 3) >> 2, ntc = (m + 3) >> 2;
-    const int n_tiles = ntr * ntc - ntr * (ntr - 1) / 2;
-    const int grp = tid >> 4, gl = tid & 15, n_grp = nthr >> 4;
-    int updates = 0;
-    for (int q0 = 0; q0 < n_tiles; q0 += n_grp) {
-        const int q = q0 + grp;
-        if (q < n_tiles) {
-            int ti = 0, rem = q;
-            while (rem >= ntc - ti) {
-                rem -= ntc - ti;
-                ++ti;
-            }
-            const int tj = ti + rem;
-            int ra[4], rb[4];
-#pragma unroll
-            for (int r = 0; r < 4; ++r) {
-                ra[r] = min(4 * ti + r, m - 1);
-                rb[r] = min(4 * tj + r, m - 1);
-            }
-            const float dist = tile_distance(rows, stride, d, ra, rb, gl);
-            const int ia = 4 * ti + (gl >> 2), ib = 4 * tj + (gl & 3);
-            if (ia < ib && ia < m_new && ib < m) {
-                const u32 db = __float_as_uint(dist);
-                const int a = uid[ia], b = uid[ib];
-                if (db <= thr[ia]) {
-                    const int slot = atomicAdd(q_count, 1);
-                    queue[slot].key = ef_pack(dist, b, 1);
-                    queue[slot].target = a;
-                }
-                if (db <= thr[ib]) {
-                    const int slot = atomicAdd(q_count, 1);
-                    queue[slot].key = ef_pack(dist, a, 1);
-                    queue[slot].target = b;
-                }
-            }
-        }
-        __syncthreads();
-        const int count = *q_count;
-        const bool last = q0 + n_grp >= n_tiles;
-        if (last || count + 2 * nthr > q_cap) {     // next round could overflow: drain now
-            updates += drain_queue(queue, count, graph, worst, K, tid, nthr);
-            __syncthreads();
-            if (tid == 0) *q_count = 0;
-            __syncthreads();
         }
     }
     return updates;
@@ -337,16 +279,15 @@ sample_kernel(u64 *graph, int n, int K, int L, u64 key_new, u64 key_old, int *__
     }
 }
 
-// After sampling: sort the points that have something to join into two work lists by an
-// upper bound of the number of vectors their join gathers, so that the common small joins
-// run with a small LDS footprint (many waves per CU) and only the few large ones pay for
-// the worst case.  Points with an empty new set are dropped here.
+// After sampling: sort the points that have something to join into three work lists by
+// an upper bound of the number of vectors their join gathers (<= rows0, <= rows1, more),
+// so that each list runs with the kernel and footprint that fits it.  Points with an
+// empty new set are dropped here.  work: [3][n], work_count: [3].
 __global__ void classify_kernel(const int *__restrict__ nw_c, const int *__restrict__ od_c,
                                 const u64 *__restrict__ rnew, const u64 *__restrict__ rold, int n,
-                                int L, int small_rows, int *__restrict__ work_small,
-                                int *__restrict__ work_large, int *__restrict__ work_count,
-                                int *__restrict__ cnt_evals, int *__restrict__ cnt_upd,
-                                int *__restrict__ cnt_rows)
+                                int L, int rows0, int rows1, int *__restrict__ work,
+                                int *__restrict__ work_count, int *__restrict__ cnt_evals,
+                                int *__restrict__ cnt_upd, int *__restrict__ cnt_rows)
 {
     const int i = blockIdx.x * blockDim.x + threadIdx.x;
     int cls = -1;
@@ -357,107 +298,432 @@ __global__ void classify_kernel(const int *__restrict__ nw_c, const int *__restr
             ro += (u32)rold[(size_t)i * L + s] < 0x80000000u ? 1 : 0;
         }
         const int ub_new = nw_c[i] + rn, ub = ub_new + od_c[i] + ro;
-        if (ub_new >= 1 && ub >= 2) cls = ub <= small_rows ? 0 : 1;
+        if (ub_new >= 1 && ub >= 2) cls = ub <= rows0 ? 0 : (ub <= rows1 ? 1 : 2);
         else cnt_evals[i] = cnt_upd[i] = cnt_rows[i] = 0;
     }
     const int lane = ef_lane();
 #pragma unroll
-    for (int c = 0; c < 2; ++c) {
+    for (int c = 0; c < 3; ++c) {
         const u64 mask = __ballot(cls == c);
         if (mask == 0) continue;
         int base = 0;
         const int leader = __ffsll((long long)mask) - 1;
         if (lane == leader) base = atomicAdd(&work_count[c], __popcll(mask));
         base = __shfl(base, leader, EF_WAVE);
-        if (cls == c) (c == 0 ? work_small : work_large)[base + __popcll(mask & ((1ULL << lane) - 1))] = i;
+        if (cls == c) work[(size_t)c * n + base + __popcll(mask & ((1ULL << lane) - 1))] = i;
     }
 }
 
 // ---------------------------------------------------------------------------------------
-// Alg. 4 step 3+4: local joins.  Each block walks a work list (grid-strided), one point
-// at a time.  cap_rows: how many vectors the LDS row buffer of this launch holds.
+// Alg. 4 step 3+4: local joins.
+//
+// Each block walks a work list (grid-strided), one point at a time:
+//   0. candidates: the four id lists are merged and de-duplicated through a small LDS
+//      hash table into U_new ++ U_old;
+//   1. gather: their rows, thresholds and squared norms go to LDS;
+//   2. filter: 16x16 blocks of the Gram matrix U_new x U are formed with fp32 MFMA
+//      (v_mfma_f32_16x16x4f32); a pair survives if |a|^2 + |b|^2 - 2ab, lowered by a
+//      bound on the rounding error of that expression, is not above the larger of
+//      the two rows' thresholds.  The bound is conservative, so no pair that the exact
+//      test would accept is dropped; most pairs are, at a quarter of the VALU cost;
+//   3. survivors get the library's fixed-order distance (one 16-lane group per pair),
+//      the exact threshold test, and go to the proposal queue;
+//   4. the queue is drained into the graph rows with the lock-free insertion.
+// cap_rows: how many vectors the LDS row buffer of this launch holds.
 
-__global__ void join_kernel(const float *__restrict__ X, int n, int d, int stride, u32 q4_magic,
-                            int K, int L,
+typedef float floatx4 __attribute__((ext_vector_type(4)));
+
+struct JoinLds {
+    float *rows;      // [cap_rows][stride], columns d..dpad-1 zero
+    int *uid;         // [cap_rows] U_new ++ U_old
+    u32 *thr;         // [cap_rows] threshold bits
+    float *nrm;       // [cap_rows] squared norms (float32, any order: filter only)
+    int *tab;         // [tab_size] hash table for de-duplication
+    int *meta;        // [0] m (fill count) [1] m_new [2] updates [3] queue count [4] survivor count
+    u32 *surv;        // [s_cap] a | b << 16
+    Proposal *queue;  // [q_cap]
+};
+
+__host__ __device__ inline size_t join_lds_floats(int cap_rows, int stride, int tab_size, int s_cap)
+{
+    return (size_t)align4(cap_rows * stride) + align4(3 * cap_rows) + tab_size + 8 + align4(s_cap);
+}
+
+__device__ inline JoinLds join_lds_carve(float *smem, int cap_rows, int stride, int tab_size, int s_cap)
+{
+    JoinLds l;
+    l.rows = smem;
+    l.uid = (int *)(smem + align4(cap_rows * stride));
+    l.thr = (u32 *)(l.uid + cap_rows);
+    l.nrm = (float *)(l.thr + cap_rows);
+    l.tab = l.uid + align4(3 * cap_rows);
+    l.meta = l.tab + tab_size;
+    l.surv = (u32 *)(l.meta + 8);
+    l.queue = (Proposal *)(l.surv + align4(s_cap));
+    return l;
+}
+
+// insert id into the open-addressing table; true if it was not there yet
+__device__ inline bool hash_insert(int *tab, int tab_mask, int tab_shift, int id)
+{
+    u32 slot = ((u32)id * 2654435761u) >> tab_shift;
+    for (;;) {
+        const int old = atomicCAS(&tab[slot], -1, id);
+        if (old == -1) return true;
+        if (old == id) return false;
+        slot = (slot + 1) & tab_mask;
+    }
+}
+
+__global__ void join_kernel(const float *__restrict__ X, const float *__restrict__ norms, int d,
+                            int dpad, int stride, u32 q4_magic, int K, int L,
                             const int *__restrict__ work, const int *__restrict__ work_count,
-                            int cap_rows, const int *__restrict__ nw, const int *__restrict__ od,
-                            const u64 *__restrict__ rnew, const u64 *__restrict__ rold,
-                            u64 *graph, u32 *worst, int *__restrict__ cnt_evals,
-                            int *__restrict__ cnt_upd, int *__restrict__ cnt_rows, int q_cap)
+                            int cap_rows, int tab_size, int tab_shift, int s_cap, int q_cap,
+                            float margin_rel, float thr_scale, const int *__restrict__ nw,
+                            const int *__restrict__ od, const u64 *__restrict__ rnew,
+                            const u64 *__restrict__ rold, u64 *graph, u32 *worst,
+                            int *__restrict__ cnt_evals, int *__restrict__ cnt_upd,
+                            int *__restrict__ cnt_rows)
 {
     extern __shared__ float smem[];
-    const int n_cand = 3 * L + K;
-    float *rows = smem;
-    int *cand = (int *)(smem + align4(cap_rows * stride));   // [3L+K] raw candidates
-    int *uid = cand + n_cand;                                 // [cap_rows] U_new ++ U_old
-    u32 *thr = (u32 *)(uid + cap_rows);                       // [cap_rows]
-    int *meta = (int *)(smem + align4(cap_rows * stride) + align4(n_cand + 2 * cap_rows));
-    Proposal *queue = (Proposal *)(meta + 4);   // meta: [0] m_new [1] m_old [2] updates [3] queue count
+    const JoinLds lds = join_lds_carve(smem, cap_rows, stride, tab_size, s_cap);
     const int tid = threadIdx.x, nthr = blockDim.x;
+    const int lane = tid & (EF_WAVE - 1), wave = tid / EF_WAVE, n_waves = nthr / EF_WAVE;
+    const int grp = tid >> 4, gl = tid & 15, n_grp = nthr >> 4;
     const int count = *work_count;
     for (int w = blockIdx.x; w < count; w += gridDim.x) {
         const int i = work[w];
-        // raw candidates: [0,L) sampled new, [L,2L) reverse new, [2L,2L+K) sampled old,
-        // [2L+K,3L+K) reverse old; -1 = nothing
-        for (int a = tid; a < n_cand; a += nthr) {
+        // ---- 0. candidates -------------------------------------------------------------
+        for (int t = tid; t < tab_size; t += nthr) lds.tab[t] = -1;
+        if (tid < 8) lds.meta[tid] = 0;
+        __syncthreads();
+        for (int a = tid; a < 2 * L; a += nthr) {     // new: sampled, then reverse
             int id;
             if (a < L) id = nw[(size_t)i * L + a];
-            else if (a < 2 * L) {
+            else {
                 const u64 k = rnew[(size_t)i * L + (a - L)];
                 id = (u32)k >= 0x80000000u ? -1 : (int)(u32)k;
-            } else if (a < 2 * L + K) id = od[(size_t)i * K + (a - 2 * L)];
+            }
+            if (id >= 0 && hash_insert(lds.tab, tab_size - 1, tab_shift, id))
+                lds.uid[atomicAdd(&lds.meta[0], 1)] = id;
+        }
+        __syncthreads();
+        const int m_new = lds.meta[0];      // everything so far is new
+        __syncthreads();                    // ... and nobody adds before everybody has read it
+        for (int a = tid; a < K + L; a += nthr) {     // old: sampled, then reverse; not if already new
+            int id;
+            if (a < K) id = od[(size_t)i * K + a];
             else {
-                const u64 k = rold[(size_t)i * L + (a - 2 * L - K)];
+                const u64 k = rold[(size_t)i * L + (a - K)];
                 id = (u32)k >= 0x80000000u ? -1 : (int)(u32)k;
             }
-            cand[a] = id;
-        }
-        if (tid == 0) {
-            meta[2] = 0;
-            meta[3] = 0;
+            if (id >= 0 && hash_insert(lds.tab, tab_size - 1, tab_shift, id))
+                lds.uid[atomicAdd(&lds.meta[0], 1)] = id;
         }
         __syncthreads();
-        // de-duplicate (first occurrence wins) and compact with wave 0
-        if (tid < EF_WAVE) {
-            int m = 0, m_new = 0;
-            for (int base = 0; base < n_cand; base += EF_WAVE) {
-                const int a = base + tid;
-                bool keep = false;
-                int id = -1;
-                if (a < n_cand) {
-                    id = cand[a];
-                    keep = id >= 0;
-                    for (int b = 0; b < a && keep; ++b) keep = cand[b] != id;
-                }
-                const u64 mask = __ballot(keep);
-                if (keep) uid[m + __popcll(mask & ((1ULL << tid) - 1))] = id;
-                // candidates below 2L are the new ones; 2L need not be a multiple of 64
-                const int lim = 2 * L - base;
-                const u64 new_mask = lim >= EF_WAVE ? ~0ULL : (lim <= 0 ? 0ULL : ((1ULL << lim) - 1));
-                m_new += __popcll(mask & new_mask);
-                m += __popcll(mask);
-            }
-            if (tid == 0) {
-                meta[0] = m_new;
-                meta[1] = m - m_new;
-            }
-        }
-        __syncthreads();
-        const int m_new = meta[0], m_old = meta[1], m = m_new + m_old;
+        const int m = lds.meta[0], m_old = m - m_new;
         if (tid == 0) {
             cnt_evals[i] = m_new * (m_new - 1) / 2 + m_new * m_old;
             cnt_rows[i] = m;
         }
-        for (int r = tid; r < m; r += nthr) thr[r] = ef_load_coherent(worst + uid[r]);
-        gather_rows(X, d, stride, q4_magic, uid, m, rows, tid, nthr);
+        // ---- 1. gather -------------------------------------------------------------------
+        for (int r = tid; r < m; r += nthr) {
+            const int id = lds.uid[r];
+            lds.thr[r] = ef_load_coherent(worst + id);
+            lds.nrm[r] = norms[id];
+        }
+        gather_rows(X, d, stride, q4_magic, lds.uid, m, lds.rows, tid, nthr);
+        if (dpad > d)
+            for (int f = tid; f < m * (dpad - d); f += nthr) {
+                const int r = f / (dpad - d), c = f - r * (dpad - d);
+                lds.rows[r * stride + d + c] = 0.0f;
+            }
         __syncthreads();
-        const int updates = join_rows(rows, stride, d, uid, thr, m_new, m, queue, &meta[3], q_cap,
-                                      graph, worst, K);
-        if (updates) atomicAdd(&meta[2], updates);
+        // ---- 2..4: blocks of 16x16 pairs, in rounds of one block per wave -----------------
+        const int nbr = (m_new + 15) >> 4, nbc = (m + 15) >> 4;
+        const int n_blocks = nbr * nbc - nbr * (nbr - 1) / 2;     // block row <= block column
+        int updates = 0;
+        for (int q0 = 0; q0 < n_blocks; q0 += n_waves) {
+            const int q = q0 + wave;
+            if (q < n_blocks) {
+                int bi = 0, rem = q;
+                while (rem >= nbc - bi) {
+                    rem -= nbc - bi;
+                    ++bi;
+                }
+                const int bj = bi + rem;
+                const int r16 = lane & 15, g = lane >> 4;
+                const float *pa = lds.rows + min(16 * bi + r16, m - 1) * stride + 4 * g;
+                const float *pb = lds.rows + min(16 * bj + r16, m - 1) * stride + 4 * g;
+                floatx4 acc0 = {0.f, 0.f, 0.f, 0.f}, acc1 = {0.f, 0.f, 0.f, 0.f};
+                for (int c = 0; c < dpad; c += 16) {
+                    const float4 va = *reinterpret_cast<const float4 *>(pa + c);
+                    const float4 vb = *reinterpret_cast<const float4 *>(pb + c);
+                    acc0 = __builtin_amdgcn_mfma_f32_16x16x4f32(va.x, vb.x, acc0, 0, 0, 0);
+                    acc1 = __builtin_amdgcn_mfma_f32_16x16x4f32(va.y, vb.y, acc1, 0, 0, 0);
+                    acc0 = __builtin_amdgcn_mfma_f32_16x16x4f32(va.z, vb.z, acc0, 0, 0, 0);
+                    acc1 = __builtin_amdgcn_mfma_f32_16x16x4f32(va.w, vb.w, acc1, 0, 0, 0);
+                }
+                // lane holds G[a = 16 bi + 4 g + k][b = 16 bj + r16], k = 0..3
+                const int b = 16 * bj + r16;
+                const float nb = lds.nrm[min(b, m - 1)];
+                const float tb = __uint_as_float(lds.thr[min(b, m - 1)]);
+#pragma unroll
+                for (int k = 0; k < 4; ++k) {
+                    const int a = 16 * bi + 4 * g + k;
+                    if (a < b && a < m_new && b < m) {
+                        const float na = lds.nrm[a];
+                        const float ta = __uint_as_float(lds.thr[a]);
+                        const float sum = na + nb;
+                        const float approx = sum - 2.0f * (acc0[k] + acc1[k]);
+                        if (approx - margin_rel * sum <= fmaxf(ta, tb) * thr_scale)
+                            lds.surv[atomicAdd(&lds.meta[4], 1)] = (u32)a | ((u32)b << 16);
+                    }
+                }
+            }
+            __syncthreads();
+            const int n_surv = lds.meta[4];
+            const bool last = q0 + n_waves >= n_blocks;
+            if (last || n_surv + 256 * n_waves > s_cap) {
+                // ---- 3. exact distances of the survivors, one 16-lane group per pair,
+                //         in chunks whose proposals (two per pair at most) fit the queue -------
+                for (int c0 = 0; c0 < n_surv; c0 += q_cap / 2) {
+                    const int c1 = min(n_surv, c0 + q_cap / 2);
+                    for (int p0 = c0; p0 < c1; p0 += n_grp) {
+                        const int p = min(p0 + grp, c1 - 1);      // keep whole groups busy
+                        const u32 ab = lds.surv[p];
+                        const int a = ab & 0xFFFF, b = ab >> 16;
+                        const float *ra = lds.rows + a * stride, *rb = lds.rows + b * stride;
+                        float acc = 0.0f;
+                        for (int j = gl; j < dpad; j += 16) {      // padding columns are 0 in both rows
+                            const float diff = ra[j] - rb[j];
+                            acc = __builtin_fmaf(diff, diff, acc);
+                        }
+                        const float dist = ef_group_reduce16(acc);
+                        if (gl == 0 && p0 + grp < c1) {
+                            const u32 db = __float_as_uint(dist);
+                            if (db <= lds.thr[a]) {
+                                const int slot = atomicAdd(&lds.meta[3], 1);
+                                lds.queue[slot].key = ef_pack(dist, lds.uid[b], 1);
+                                lds.queue[slot].target = lds.uid[a];
+                            }
+                            if (db <= lds.thr[b]) {
+                                const int slot = atomicAdd(&lds.meta[3], 1);
+                                lds.queue[slot].key = ef_pack(dist, lds.uid[a], 1);
+                                lds.queue[slot].target = lds.uid[b];
+                            }
+                        }
+                    }
+                    __syncthreads();
+                    // ---- 4. drain -----------------------------------------------------------
+                    updates += drain_queue(lds.queue, lds.meta[3], graph, worst, K, tid, nthr);
+                    __syncthreads();
+                    if (tid == 0) lds.meta[3] = 0;
+                    __syncthreads();
+                }
+                if (tid == 0) lds.meta[4] = 0;
+                __syncthreads();
+            }
+        }
+        if (updates) atomicAdd(&lds.meta[2], updates);
         __syncthreads();
-        if (tid == 0) cnt_upd[i] = meta[2];
+        if (tid == 0) cnt_upd[i] = lds.meta[2];
         __syncthreads();
     }
+}
+
+// ---------------------------------------------------------------------------------------
+// The same local join for points whose join gathers at most 16 * NB vectors (NB = 1, 2),
+// which is nearly all of them.  One wave per point and no row buffer in LDS: lane
+// (r, g) = (lane % 16, lane / 16) loads 16-byte pieces of vector r (and 16 + r) straight
+// from memory into the registers the MFMA reads, 128 coordinates at a time, so a block
+// needs a few KB of LDS and many more waves fit a CU to hide the memory round trips.
+// Survivors of the filter (few) re-read their two rows, which are still in L2.
+// Requires d % 4 == 0 and a 16-byte aligned X.
+
+template <int NB>
+__global__ void __launch_bounds__(EF_WAVE)
+join_reg_kernel(const float *__restrict__ X, const float *__restrict__ norms, int d, int K, int L,
+                const int *__restrict__ work, const int *__restrict__ work_count, int tab_size,
+                int tab_shift, int q_cap, float margin_rel, float thr_scale,
+                const int *__restrict__ nw, const int *__restrict__ od,
+                const u64 *__restrict__ rnew, const u64 *__restrict__ rold, u64 *graph, u32 *worst,
+                int *__restrict__ cnt_evals, int *__restrict__ cnt_upd, int *__restrict__ cnt_rows)
+{
+    constexpr int R = 16 * NB;                    // rows
+    constexpr int S_CAP = R * (R - 1) / 2 + 8;    // every pair may survive
+    extern __shared__ float smem[];
+    int *uid = (int *)smem;                       // [R]
+    u32 *thr = (u32 *)(uid + R);                  // [R]
+    float *nrm = (float *)(thr + R);              // [R]
+    int *meta = (int *)(nrm + R);                 // [8]: [0] m [2] updates [3] queue count [4] survivors
+    int *tab = meta + 8;                          // [tab_size]
+    u32 *surv = (u32 *)(tab + tab_size);          // [S_CAP]
+    Proposal *queue = (Proposal *)(surv + align4(S_CAP));   // [q_cap]
+    const int lane = threadIdx.x, r16 = lane & 15, g = lane >> 4, gl = r16, grp = g;
+    const int count = *work_count;
+    const int n_cand_new = 2 * L, n_cand_old = K + L;
+    for (int w = blockIdx.x; w < count; w += gridDim.x) {
+        const int i = work[w];
+        // ---- 0. candidates ---------------------------------------------------------------
+        for (int t = lane; t < tab_size; t += EF_WAVE) tab[t] = -1;
+        if (lane < 8) meta[lane] = 0;
+        __syncthreads();
+        for (int a = lane; a < n_cand_new; a += EF_WAVE) {
+            int id;
+            if (a < L) id = nw[(size_t)i * L + a];
+            else {
+                const u64 k = rnew[(size_t)i * L + (a - L)];
+                id = (u32)k >= 0x80000000u ? -1 : (int)(u32)k;
+            }
+            if (id >= 0 && hash_insert(tab, tab_size - 1, tab_shift, id)) uid[atomicAdd(&meta[0], 1)] = id;
+        }
+        __syncthreads();
+        const int m_new = meta[0];
+        __syncthreads();
+        for (int a = lane; a < n_cand_old; a += EF_WAVE) {
+            int id;
+            if (a < K) id = od[(size_t)i * K + a];
+            else {
+                const u64 k = rold[(size_t)i * L + (a - K)];
+                id = (u32)k >= 0x80000000u ? -1 : (int)(u32)k;
+            }
+            if (id >= 0 && hash_insert(tab, tab_size - 1, tab_shift, id)) uid[atomicAdd(&meta[0], 1)] = id;
+        }
+        __syncthreads();
+        const int m = meta[0], m_old = m - m_new;
+        if (lane == 0) {
+            cnt_evals[i] = m_new * (m_new - 1) / 2 + m_new * m_old;
+            cnt_rows[i] = m;
+        }
+        if (lane < m) {
+            const int id = uid[lane];
+            thr[lane] = ef_load_coherent(worst + id);
+            nrm[lane] = norms[id];
+        }
+        // ---- 1+2. Gram blocks from register operands ---------------------------------------
+        const float *pa = X + (size_t)uid[min(r16, m - 1)] * d + 4 * g;
+        const float *pb = NB > 1 ? X + (size_t)uid[min(16 + r16, m - 1)] * d + 4 * g : pa;
+        const bool need11 = NB > 1 && m_new > 16;      // block (1,1) only if new rows reach it
+        floatx4 acc[3][2];
+#pragma unroll
+        for (int q = 0; q < 3; ++q)
+#pragma unroll
+            for (int h = 0; h < 2; ++h) acc[q][h] = (floatx4){0.f, 0.f, 0.f, 0.f};
+        for (int c0 = 0; c0 < d; c0 += 128) {
+            float4 va[8], vb[8];
+#pragma unroll
+            for (int s = 0; s < 8; ++s) {
+                const int j = c0 + 16 * s + 4 * g;
+                const bool in = j + 3 < d;                 // d % 4 == 0: a piece is in or out
+                va[s] = in ? *reinterpret_cast<const float4 *>(pa + c0 + 16 * s) : make_float4(0.f, 0.f, 0.f, 0.f);
+                if (NB > 1)
+                    vb[s] = in ? *reinterpret_cast<const float4 *>(pb + c0 + 16 * s) : make_float4(0.f, 0.f, 0.f, 0.f);
+            }
+#pragma unroll
+            for (int s = 0; s < 8; ++s) {
+                if (c0 + 16 * s >= d) break;
+                acc[0][0] = __builtin_amdgcn_mfma_f32_16x16x4f32(va[s].x, va[s].x, acc[0][0], 0, 0, 0);
+                acc[0][1] = __builtin_amdgcn_mfma_f32_16x16x4f32(va[s].y, va[s].y, acc[0][1], 0, 0, 0);
+                acc[0][0] = __builtin_amdgcn_mfma_f32_16x16x4f32(va[s].z, va[s].z, acc[0][0], 0, 0, 0);
+                acc[0][1] = __builtin_amdgcn_mfma_f32_16x16x4f32(va[s].w, va[s].w, acc[0][1], 0, 0, 0);
+                if (NB > 1) {
+                    acc[1][0] = __builtin_amdgcn_mfma_f32_16x16x4f32(va[s].x, vb[s].x, acc[1][0], 0, 0, 0);
+                    acc[1][1] = __builtin_amdgcn_mfma_f32_16x16x4f32(va[s].y, vb[s].y, acc[1][1], 0, 0, 0);
+                    acc[1][0] = __builtin_amdgcn_mfma_f32_16x16x4f32(va[s].z, vb[s].z, acc[1][0], 0, 0, 0);
+                    acc[1][1] = __builtin_amdgcn_mfma_f32_16x16x4f32(va[s].w, vb[s].w, acc[1][1], 0, 0, 0);
+                    if (need11) {
+                        acc[2][0] = __builtin_amdgcn_mfma_f32_16x16x4f32(vb[s].x, vb[s].x, acc[2][0], 0, 0, 0);
+                        acc[2][1] = __builtin_amdgcn_mfma_f32_16x16x4f32(vb[s].y, vb[s].y, acc[2][1], 0, 0, 0);
+                        acc[2][0] = __builtin_amdgcn_mfma_f32_16x16x4f32(vb[s].z, vb[s].z, acc[2][0], 0, 0, 0);
+                        acc[2][1] = __builtin_amdgcn_mfma_f32_16x16x4f32(vb[s].w, vb[s].w, acc[2][1], 0, 0, 0);
+                    }
+                }
+            }
+        }
+        __syncthreads();      // thr, nrm visible
+        // ---- filter: lane holds G[a = 16 bi + 4 g + k][b = 16 bj + r16] of block q -----------
+#pragma unroll
+        for (int q = 0; q < (NB > 1 ? 3 : 1); ++q) {
+            const int bi = q == 2 ? 1 : 0, bj = q == 0 ? 0 : 1;
+            const int b = 16 * bj + r16;
+            const float nb = nrm[min(b, m - 1)];
+            const float tb = __uint_as_float(thr[min(b, m - 1)]);
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                const int a = 16 * bi + 4 * g + k;
+                if (a < b && a < m_new && b < m) {
+                    const float sum = nrm[a] + nb;
+                    const float approx = sum - 2.0f * (acc[q][0][k] + acc[q][1][k]);
+                    if (approx - margin_rel * sum <= fmaxf(__uint_as_float(thr[a]), tb) * thr_scale)
+                        surv[atomicAdd(&meta[4], 1)] = (u32)a | ((u32)b << 16);
+                }
+            }
+        }
+        __syncthreads();
+        // ---- 3. survivors: fixed-order distance, one 16-lane group per pair -------------------
+        const int n_surv = meta[4];
+        int updates = 0;
+        for (int c0 = 0; c0 < n_surv; c0 += q_cap / 2) {
+            const int c1 = min(n_surv, c0 + q_cap / 2);
+            for (int p0 = c0; p0 < c1; p0 += 4) {
+                const int p = min(p0 + grp, c1 - 1);
+                const u32 ab = surv[p];
+                const int a = ab & 0xFFFF, b = ab >> 16;
+                const float *ra = X + (size_t)uid[a] * d + gl, *rb = X + (size_t)uid[b] * d + gl;
+                float accd = 0.0f;
+                for (int j0 = 0; j0 < d; j0 += 128) {
+                    float xa[8], xb[8];
+#pragma unroll
+                    for (int s = 0; s < 8; ++s) {
+                        const bool in = j0 + 16 * s + gl < d;
+                        xa[s] = in ? ra[j0 + 16 * s] : 0.0f;
+                        xb[s] = in ? rb[j0 + 16 * s] : 0.0f;
+                    }
+#pragma unroll
+                    for (int s = 0; s < 8; ++s) {
+                        const float diff = xa[s] - xb[s];     // 0 beyond d: leaves the sum unchanged
+                        accd = __builtin_fmaf(diff, diff, accd);
+                    }
+                }
+                const float dist = ef_group_reduce16(accd);
+                if (gl == 0 && p0 + grp < c1) {
+                    const u32 db = __float_as_uint(dist);
+                    if (db <= thr[a]) {
+                        const int slot = atomicAdd(&meta[3], 1);
+                        queue[slot].key = ef_pack(dist, uid[b], 1);
+                        queue[slot].target = uid[a];
+                    }
+                    if (db <= thr[b]) {
+                        const int slot = atomicAdd(&meta[3], 1);
+                        queue[slot].key = ef_pack(dist, uid[a], 1);
+                        queue[slot].target = uid[b];
+                    }
+                }
+            }
+            __syncthreads();
+            updates += drain_queue(queue, meta[3], graph, worst, K, lane, EF_WAVE);
+            __syncthreads();
+            if (lane == 0) meta[3] = 0;
+            __syncthreads();
+        }
+        updates = ef_wave_sum_i32(updates);
+        if (lane == 0) cnt_upd[i] = updates;
+        __syncthreads();
+    }
+}
+
+// squared norms in float32 (only the join's filter uses them; any summation order will do)
+__global__ void norms_kernel(const float *__restrict__ X, int n, int d, float *__restrict__ norms)
+{
+    const size_t g = ((size_t)blockIdx.x * blockDim.x + threadIdx.x) >> 4;
+    const int gl = threadIdx.x & 15;
+    const size_t gc = g < (size_t)n ? g : (size_t)n - 1;
+    const float *a = X + gc * d;
+    float acc = 0.0f;
+    for (int j = gl; j < d; j += 16) acc = __builtin_fmaf(a[j], a[j], acc);
+    acc = ef_group_reduce16(acc);
+    if (g < (size_t)n && gl == 0) norms[g] = acc;
 }
 
 __global__ void stats_kernel(const int *__restrict__ cnt_evals, const int *__restrict__ cnt_upd,
@@ -551,9 +817,10 @@ __global__ void pair_distances_kernel(const float *__restrict__ X, int d,
 }
 
 struct NndWs {
-    int *nw, *od, *nw_c, *od_c, *cnt_evals, *cnt_upd, *cnt_rows, *work_small, *work_large, *work_count;
+    int *nw, *od, *nw_c, *od_c, *cnt_evals, *cnt_upd, *cnt_rows, *work, *work_count;
     u64 *rnew, *rold;
     u32 *worst;
+    float *norms;
     size_t bytes;
 };
 
@@ -574,12 +841,12 @@ NndWs carve_nnd(void *ws, int64_t n, int K, int L)
     w.cnt_evals = (int *)take((size_t)n * 4);
     w.cnt_upd = (int *)take((size_t)n * 4);
     w.cnt_rows = (int *)take((size_t)n * 4);
-    w.work_small = (int *)take((size_t)n * 4);
-    w.work_large = (int *)take((size_t)n * 4);
-    w.work_count = (int *)take(2 * 4);
+    w.work = (int *)take((size_t)n * 3 * 4);
+    w.work_count = (int *)take(4 * 4);
     w.rnew = (u64 *)take((size_t)n * L * 8);
     w.rold = (u64 *)take((size_t)n * L * 8);
     w.worst = (u32 *)take((size_t)n * 4);
+    w.norms = (float *)take((size_t)n * 4);
     w.bytes = off;
     return w;
 }
@@ -668,34 +935,72 @@ extern "C" int efanna_nndescent(const float *X, int64_t n, int32_t d, int32_t k,
     if (!ws || ((uintptr_t)ws & 255) || ws_bytes < efanna_nndescent_workspace_bytes(n, k, sample_L))
         return EFANNA_EWORKSPACE;
     const int K = k, L = sample_L;
-    const int stride = d + kRowPad;
-    const int max_rows = 3 * L + K;
-    // two launch shapes: joins that gather at most small_rows vectors, and the rest
-    const int small_rows = max_rows <= 16 ? max_rows : (max_rows * 2 / 5 < 16 ? 16 : align4(max_rows * 2 / 5));
-    auto threads_for = [](long pairs) {
-        return pairs <= 1024 ? 64 : (pairs <= 4096 ? 128 : (pairs <= 12288 ? 256 : 512));
+    const int dpad = (d + 15) & ~15;
+    const int stride = dpad + kRowPad;
+    // a join gathers at most K + 2L vectors: new and old sets together come from one row
+    // of K entries, each reverse list adds at most L
+    const int max_rows = K + 2 * L;
+    // three work lists: joins of at most 16 and at most 32 vectors run from register
+    // operands (needs 16-byte aligned rows), the rest through the LDS row buffer
+    const bool reg_ok = (d & 3) == 0 && ((uintptr_t)X & 15) == 0;
+    const int rows0 = reg_ok ? 16 : 0, rows1 = reg_ok ? 32 : 0;
+    int tab_size = 64, tab_shift = 26;
+    while (tab_size < 2 * max_rows) {
+        tab_size <<= 1;
+        --tab_shift;
+    }
+    struct Shape {
+        int cap_rows, threads, s_cap, q_cap, grid;
+        size_t lds;
     };
-    auto lds_for = [&](int cap_rows, int threads) {
-        return (size_t)(align4(cap_rows * stride) + align4(max_rows + 2 * cap_rows)) * 4 + 16 +
-               (size_t)(4 * threads) * sizeof(Proposal);
-    };
-    const int thr_large = threads_for((long)L * (2 * L - 1) + (long)2 * L * (K + L));
-    const int thr_small = threads_for((long)small_rows * small_rows / 2);
-    const size_t lds_large = lds_for(max_rows, thr_large), lds_small = lds_for(small_rows, thr_small);
-    if (lds_large > kLdsLimit) return EFANNA_EUNSUPPORTED;
-    hipStream_t st = (hipStream_t)stream;
-    NndWs w = carve_nnd(ws, n, K, L);
-    EF_HIP_CHECK(hipFuncSetAttribute((const void *)join_kernel,
-                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_large));
-    // persistent grids: as many blocks as fit the 256 CUs at once (LDS- or wave-limited), twice over
-    auto grid_for_lds = [](size_t lds, int threads) {
-        long per_cu = (long)(kLdsLimit / lds);
-        const long by_waves = 32 / (threads / EF_WAVE);
+    auto shape_for = [&](int cap_rows) {
+        Shape sh;
+        sh.cap_rows = cap_rows;
+        const long blocks = (long)((cap_rows + 15) / 16) * ((cap_rows + 15) / 16);
+        sh.threads = blocks <= 2 ? 64 : (blocks <= 9 ? 128 : (blocks <= 36 ? 256 : 512));
+        const long pairs = (long)cap_rows * (cap_rows - 1) / 2;
+        for (bool fits = false; !fits; sh.threads /= 2) {
+            const int n_waves = sh.threads / EF_WAVE;
+            // a round of blocks adds at most 256 survivors per wave, and the list is emptied
+            // whenever the next round might not fit; more room means fewer drains
+            sh.s_cap = 256 * n_waves;
+            if (pairs > sh.s_cap && pairs <= 1024) sh.s_cap = align4((int)pairs);
+            if (cap_rows <= 16) sh.s_cap = 128;     // a single block of at most 120 pairs
+            for (sh.q_cap = 4 * sh.threads; sh.q_cap >= 128 && !fits; sh.q_cap /= 2) {
+                sh.lds = join_lds_floats(cap_rows, stride, tab_size, sh.s_cap) * 4 +
+                         (size_t)sh.q_cap * sizeof(Proposal);
+                fits = sh.lds <= kLdsLimit;
+                if (fits) break;
+            }
+            if (fits || sh.threads == EF_WAVE) break;
+        }
+        const int n_waves = sh.threads / EF_WAVE;
+        // persistent grid: as many blocks as fit the 256 CUs at once, twice over
+        long per_cu = (long)(kLdsLimit / sh.lds);
+        const long by_waves = 32 / n_waves;
         if (per_cu > by_waves) per_cu = by_waves;
         if (per_cu < 1) per_cu = 1;
-        return (int)(256 * per_cu * 2);
+        sh.grid = (int)(256 * per_cu * 2);
+        return sh;
     };
-    const int grid_small = grid_for_lds(lds_small, thr_small), grid_large = grid_for_lds(lds_large, thr_large);
+    const Shape large = shape_for(max_rows);
+    if (max_rows > rows1 && large.lds > kLdsLimit) return EFANNA_EUNSUPPORTED;
+    const int reg_q_cap = 128;
+    auto reg_lds = [&](int R) {
+        return (size_t)(3 * R + 8 + tab_size + align4(R * (R - 1) / 2 + 8)) * 4 +
+               (size_t)reg_q_cap * sizeof(Proposal);
+    };
+    const int reg_grid = 256 * 32;
+    // filter margins: Gram-form rounding error <= (2*dpad + 4) u (|a|^2 + |b|^2), u = 2^-24,
+    // doubled; the fixed-order distance is within (d/16 + 8) u of the true one, doubled twice
+    const float margin_rel = (float)((4.0 * dpad + 16.0) * 5.9604644775390625e-08);
+    const float thr_scale = (float)(1.0 + 4.0 * (d / 16.0 + 8.0) * 5.9604644775390625e-08);
+    hipStream_t st = (hipStream_t)stream;
+    NndWs w = carve_nnd(ws, n, K, L);
+    if (max_rows > rows1)
+        EF_HIP_CHECK(hipFuncSetAttribute((const void *)join_kernel,
+                                         hipFuncAttributeMaxDynamicSharedMemorySize, (int)large.lds));
+    norms_kernel<<<grid_for((size_t)n * 16, kBlock), kBlock, 0, st>>>(X, (int)n, d, w.norms);
     if (stats) zero_u64_kernel<<<grid_for((size_t)iters * 4 + 1, kBlock), kBlock, 0, st>>>(stats, iters * 4);
     const int rows_per_block = kBlock / EF_WAVE;
     // optional phase timing: events around the sampling and the join of every iteration
@@ -713,16 +1018,26 @@ extern "C" int efanna_nndescent(const float *X, int64_t n, int32_t d, int32_t k,
             graph, (int)n, K, L, ef_stream_key(seed, 2 * g), ef_stream_key(seed, 2 * g + 1), w.nw,
             w.od, w.nw_c, w.od_c, w.rnew, w.rold, w.worst);
         classify_kernel<<<grid_for((size_t)n, kBlock), kBlock, 0, st>>>(
-            w.nw_c, w.od_c, w.rnew, w.rold, (int)n, L, small_rows, w.work_small, w.work_large,
-            w.work_count, w.cnt_evals, w.cnt_upd, w.cnt_rows);
+            w.nw_c, w.od_c, w.rnew, w.rold, (int)n, L, rows0, rows1, w.work, w.work_count,
+            w.cnt_evals, w.cnt_upd, w.cnt_rows);
         if (ev) EF_HIP_CHECK(hipEventRecord(ev[3 * it + 1], st));
-        join_kernel<<<grid_small, thr_small, lds_small, st>>>(
-            X, (int)n, d, stride, q4_magic_for(d), K, L, w.work_small, w.work_count, small_rows, w.nw, w.od, w.rnew,
-            w.rold, graph, w.worst, w.cnt_evals, w.cnt_upd, w.cnt_rows, 4 * thr_small);
-        if (small_rows < max_rows)
-            join_kernel<<<grid_large, thr_large, lds_large, st>>>(
-                X, (int)n, d, stride, q4_magic_for(d), K, L, w.work_large, w.work_count + 1, max_rows, w.nw, w.od,
-                w.rnew, w.rold, graph, w.worst, w.cnt_evals, w.cnt_upd, w.cnt_rows, 4 * thr_large);
+        if (reg_ok) {
+            join_reg_kernel<1><<<reg_grid, EF_WAVE, reg_lds(16), st>>>(
+                X, w.norms, d, K, L, w.work, w.work_count, tab_size, tab_shift, reg_q_cap, margin_rel,
+                thr_scale, w.nw, w.od, w.rnew, w.rold, graph, w.worst, w.cnt_evals, w.cnt_upd,
+                w.cnt_rows);
+            if (max_rows > 16)
+                join_reg_kernel<2><<<reg_grid, EF_WAVE, reg_lds(32), st>>>(
+                    X, w.norms, d, K, L, w.work + (size_t)n, w.work_count + 1, tab_size, tab_shift,
+                    reg_q_cap, margin_rel, thr_scale, w.nw, w.od, w.rnew, w.rold, graph, w.worst,
+                    w.cnt_evals, w.cnt_upd, w.cnt_rows);
+        }
+        if (max_rows > rows1)
+            join_kernel<<<large.grid, large.threads, large.lds, st>>>(
+                X, w.norms, d, dpad, stride, q4_magic_for(d), K, L, w.work + 2 * (size_t)n,
+                w.work_count + 2, large.cap_rows, tab_size, tab_shift, large.s_cap, large.q_cap,
+                margin_rel, thr_scale, w.nw, w.od, w.rnew, w.rold, graph, w.worst, w.cnt_evals,
+                w.cnt_upd, w.cnt_rows);
         if (ev) EF_HIP_CHECK(hipEventRecord(ev[3 * it + 2], st));
         if (stats)
             stats_kernel<<<256, kBlock, 0, st>>>(w.cnt_evals, w.cnt_upd, w.cnt_rows, (int)n,

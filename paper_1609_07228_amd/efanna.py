@@ -37,7 +37,7 @@ def lib():
     machine without hipcc, never falls back to anything else."""
     global _lib
     if _lib is None:
-        path = _build.LIB
+        path = os.environ.get("EFANNA_HIP_LIBRARY") or _build.LIB   # override: another build of the same sources
         if not os.path.exists(path):
             _build.build()
         L = C.CDLL(path)

@@ -212,7 +212,7 @@ def test_argument_errors(ef):
     with pytest.raises(ef.EfannaError) as e:
         ef.efanna_nndescent(X, g, 1, 4, 0, workspace=torch.empty(256, dtype=torch.uint8, device="cuda:0"))
     assert e.value.status == -2
-    big = dev(np.zeros((200, 4000), dtype=np.float32))
-    with pytest.raises(ef.EfannaError) as e:      # (3L+K) rows of 4000 floats exceed the LDS
-        ef.efanna_nndescent(big, torch.zeros((200, 10), dtype=torch.int64, device="cuda:0"), 1, 10, 0)
+    big = dev(np.zeros((300, 4000), dtype=np.float32))
+    with pytest.raises(ef.EfannaError) as e:      # joins of up to K+2L = 200 rows of 4000 floats exceed the LDS
+        ef.efanna_nndescent(big, torch.zeros((300, 100), dtype=torch.int64, device="cuda:0"), 1, 50, 0)
     assert e.value.status == -6
