@@ -78,10 +78,12 @@ __global__ void roots_kernel(Node *nodes, int *node_of, unsigned char *leaf_flag
     if (p == 0) c->next_nodes = 0;
 }
 
-__global__ void sum_kernel(const float *__restrict__ X, int d, const int *__restrict__ perm,
-                           const int *__restrict__ node_of, Node *nodes, float *__restrict__ val,
-                           size_t total)
+__global__ void __launch_bounds__(kBlock)
+sum_kernel(const float *__restrict__ X, int d, const int *__restrict__ perm,
+           const int *__restrict__ node_of, Node *nodes, float *__restrict__ val, size_t total)
 {
+    __shared__ long long wave_tot[kBlock / EF_WAVE];
+    __shared__ int wave_node[kBlock / EF_WAVE];
     size_t p = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
     int s = -1;
     long long q = 0;
@@ -98,12 +100,33 @@ __global__ void sum_kernel(const float *__restrict__ X, int d, const int *__rest
             }
         }
     }
-    int s0 = __shfl(s, 0, EF_WAVE);
-    if (__all(s == s0)) {
-        if (s0 < 0) return;
-        long long tot = ef_wave_sum_i64(q);
-        if (ef_lane() == 0) atomicAdd((u64 *)&nodes[s0].sum, (u64)tot);
-    } else if (s >= 0) {
+    // Positions of a node are contiguous, so inside a wave equal node indices form runs.
+    // Segmented inclusive scan over the runs; the last lane of a run then holds its sum.
+    const int lane = ef_lane(), wave = threadIdx.x / EF_WAVE;
+    for (int o = 1; o < EF_WAVE; o <<= 1) {
+        const long long q_up = __shfl_up(q, o, EF_WAVE);
+        const int s_up = __shfl_up(s, o, EF_WAVE);
+        if (lane >= o && s_up == s) q += q_up;
+    }
+    const int s_next = __shfl_down(s, 1, EF_WAVE);
+    const bool tail = lane == EF_WAVE - 1 || s_next != s;
+    const int s_first = __shfl(s, 0, EF_WAVE);
+    const bool uniform = __all(s == s_first);      // the whole wave lies in one node
+    if (lane == EF_WAVE - 1) {
+        wave_tot[wave] = q;
+        wave_node[wave] = uniform ? s : -2;
+    }
+    __syncthreads();
+    // near the root a whole block lies in one node: one atomic for the block
+    bool block_uniform = true;
+    for (int w = 0; w < kBlock / EF_WAVE; ++w) block_uniform &= wave_node[w] == wave_node[0] && wave_node[0] != -2;
+    if (block_uniform) {
+        if (threadIdx.x == 0 && wave_node[0] >= 0) {
+            long long tot = 0;
+            for (int w = 0; w < kBlock / EF_WAVE; ++w) tot += wave_tot[w];
+            atomicAdd((u64 *)&nodes[wave_node[0]].sum, (u64)tot);
+        }
+    } else if (tail && s >= 0) {
         atomicAdd((u64 *)&nodes[s].sum, (u64)q);
     }
 }
