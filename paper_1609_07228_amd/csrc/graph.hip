@@ -23,10 +23,15 @@ __host__ __device__ inline int align4(int x) { return (x + 3) & ~3; }
 // fills
 
 // reverse lists: slot s of an empty list holds ~0 - s (above every real key)
-__global__ void fill_reverse_kernel(u64 *a, u64 *b, size_t total, int L, int *work_count)
+__global__ void fill_reverse_kernel(u64 *a, u64 *b, size_t total, int L, int *a_count, int *b_count,
+                                    size_t n, int *work_count)
 {
     size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (i < 3) work_count[i] = 0;
+    if (i < 4) work_count[i] = 0;     // three work lists and the overflow queue
+    if (i < n) {
+        a_count[i] = 0;
+        b_count[i] = 0;
+    }
     if (i < total) {
         u64 v = ~0ULL - (u64)(i % (size_t)L);
         a[i] = v;
@@ -193,90 +198,149 @@ init_tree_kernel(const float *__restrict__ X, int d, int stride, u32 q4_magic, i
 
 // ---------------------------------------------------------------------------------------
 // Alg. 4 step 1+2: sample the new / old sets of every row, clear the sampled marks,
-// refresh the row's threshold and push the row's id into the reverse lists of the
-// sampled neighbours.  One wave per row, up to 128 entries (two per lane).
+// refresh the row's threshold and enter the row's id into the reverse lists of the
+// sampled neighbours.
+//
+// A row is handled by a group of G lanes holding E entries each (G*E >= K); ranks among
+// the marked and the unmarked entries come from broadcasting every entry to the group.
+//
+// Reverse lists keep the L members with the smallest (hash, source) key.  Most lists
+// never overflow, so the first L arrivals of a list just take the next free slot (one
+// counter bump); later arrivals are parked in an overflow queue and settled by
+// reverse_overflow_kernel, after this kernel has finished, with the bounded insertion.
+// Whatever the arrival order, a list ends up with the L smallest keys offered to it.
 
+struct Overflow {
+    u64 key;      // hash << 32 | source
+    int target;   // list owner
+    int which;    // 0: reverse-new, 1: reverse-old
+};
+
+// Offer `key` to reverse list v.  Returns true if the list had no free slot: the caller
+// parks the key for reverse_overflow_kernel.
+__device__ inline bool reverse_offer(u64 *lists, int *counts, int L, int v, u64 key)
+{
+    // a list that is already full is not bumped again: popular points would otherwise
+    // serialise thousands of atomics on one counter
+    if (ef_load_coherent((const u32 *)&counts[v]) >= (u32)L) return true;
+    const int pos = atomicAdd(&counts[v], 1);
+    if (pos >= L) return true;
+    lists[(size_t)v * L + pos] = key;
+    return false;
+}
+
+template <int G, int E>
 __global__ void __launch_bounds__(kBlock)
 sample_kernel(u64 *graph, int n, int K, int L, u64 key_new, u64 key_old, int *__restrict__ nw,
               int *__restrict__ od, int *__restrict__ nw_c, int *__restrict__ od_c, u64 *rnew,
-              u64 *rold, u32 *worst)
+              u64 *rold, int *rnew_c, int *rold_c, Overflow *overflow, int *overflow_rows,
+              u32 *worst)
 {
-    __shared__ u64 keys_sh[kBlock / EF_WAVE][2 * EF_WAVE];
-    __shared__ u64 stop_sh[kBlock / EF_WAVE];
-    const int wave = threadIdx.x / EF_WAVE, lane = ef_lane();
-    const int i = blockIdx.x * (kBlock / EF_WAVE) + wave;
-    u64 *keys = keys_sh[wave];
-    u64 e[2] = {~0ULL, ~0ULL};
-    if (i < n) {
-        if (lane < K) e[0] = graph[(size_t)i * K + lane];
-        if (lane + EF_WAVE < K) e[1] = graph[(size_t)i * K + lane + EF_WAVE];
-    }
-    keys[lane] = e[0];
-    keys[lane + EF_WAVE] = e[1];
-    if (lane == 0) stop_sh[wave] = ~0ULL;
-    __syncthreads();
-    if (i >= n) return;     // whole wave leaves together; no block barrier follows
-    // ranks among new-marked and among old entries
-    int rn[2] = {0, 0}, ro[2] = {0, 0};
-    for (int k = 0; k < K; ++k) {
-        const u64 o = keys[k];
-        const bool o_new = o & 1, o_old = !o_new && !ef_is_empty(o);
+    const int gl = threadIdx.x & (G - 1);
+    const int i = (int)(((size_t)blockIdx.x * kBlock + threadIdx.x) / G);
+    const bool row_ok = i < n;
+    u64 e[E];
 #pragma unroll
-        for (int h = 0; h < 2; ++h) {
-            const bool less = o < e[h];
-            rn[h] += (less && o_new) ? 1 : 0;
-            ro[h] += (less && o_old) ? 1 : 0;
+    for (int h = 0; h < E; ++h) {
+        const int slot = gl + h * G;
+        e[h] = row_ok && slot < K ? graph[(size_t)i * K + slot] : ~0ULL;
+    }
+    // ranks among new-marked and among old entries (all lanes of the group take part)
+    int rn[E], ro[E];
+#pragma unroll
+    for (int h = 0; h < E; ++h) rn[h] = ro[h] = 0;
+#pragma unroll
+    for (int part = 0; part < E; ++part) {
+        const int k_end = min(K - part * G, G);
+        for (int k = 0; k < k_end; ++k) {
+            const u64 o = __shfl(e[part], k, G);
+            const bool o_new = o & 1, o_old = !o_new && !ef_is_empty(o);
+#pragma unroll
+            for (int h = 0; h < E; ++h) {
+                const bool less = o < e[h];
+                rn[h] += (less && o_new) ? 1 : 0;
+                ro[h] += (less && o_old) ? 1 : 0;
+            }
         }
     }
-    bool valid[2], is_new[2], is_old[2], take_new[2];
+    bool is_new[E], is_old[E], take_new[E];
     int total_new = 0;
     u32 wbits = 0;
+    u64 stop = ~0ULL;      // key of the L-th new entry, if there is one
 #pragma unroll
-    for (int h = 0; h < 2; ++h) {
-        valid[h] = lane + h * EF_WAVE < K;
-        is_new[h] = valid[h] && (e[h] & 1);
-        is_old[h] = valid[h] && !(e[h] & 1) && !ef_is_empty(e[h]);
+    for (int h = 0; h < E; ++h) {
+        const bool valid = gl + h * G < K;
+        is_new[h] = valid && (e[h] & 1);
+        is_old[h] = valid && !(e[h] & 1) && !ef_is_empty(e[h]);
         take_new[h] = is_new[h] && rn[h] < L;
         total_new += is_new[h] ? 1 : 0;
-        if (valid[h]) wbits = max(wbits, ef_dist_bits(e[h]));
-        if (take_new[h] && rn[h] == L - 1) stop_sh[wave] = e[h];   // the L-th new entry
+        if (valid) wbits = max(wbits, ef_dist_bits(e[h]));
+        if (take_new[h] && rn[h] == L - 1) stop = e[h];
     }
-    total_new = ef_wave_sum_i32(total_new);
-    for (int m = 32; m >= 1; m >>= 1) wbits = max(wbits, (u32)__shfl_xor((int)wbits, m, EF_WAVE));
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
-    __builtin_amdgcn_wave_barrier();
-    const u64 stop = stop_sh[wave];     // ~0 when fewer than L new entries exist
-    int n_old = 0;
+    for (int m = G / 2; m >= 1; m >>= 1) {
+        total_new += __shfl_xor(total_new, m, G);
+        wbits = max(wbits, (u32)__shfl_xor((int)wbits, m, G));
+        const u64 other = __shfl_xor(stop, m, G);
+        stop = other < stop ? other : stop;
+    }
+    int n_old = 0, n_parked = 0;     // parked keys of row i go to overflow[i*K ...], in group order
+    const int group_shift = (int)(threadIdx.x & (EF_WAVE - 1) & ~(G - 1));
+    const u64 group_bits = G == 64 ? ~0ULL : ((1ULL << G) - 1);
 #pragma unroll
-    for (int h = 0; h < 2; ++h) {
-        const int slot = lane + h * EF_WAVE;
+    for (int h = 0; h < E; ++h) {
+        const int slot = gl + h * G;
         const int id = ef_id(e[h]);
-        if (take_new[h]) {
-            nw[(size_t)i * L + rn[h]] = id;
-            graph[(size_t)i * K + slot] = e[h] & ~1ULL;
-            u64 nm;
-            u64 hk = (ef_mix64(key_new + (((u64)(u32)id << 32) | (u32)i)) >> 32 << 32) | (u32)i;
-            ef_bounded_insert(rnew + (size_t)id * L, L, hk, 0, &nm);
+#pragma unroll
+        for (int which = 0; which < 2; ++which) {
+            const bool take = row_ok && (which == 0 ? take_new[h] : (is_old[h] && e[h] < stop));
+            bool parked = false;
+            u64 hk = 0;
+            if (take) {
+                if (which == 0) {
+                    nw[(size_t)i * L + rn[h]] = id;
+                    graph[(size_t)i * K + slot] = e[h] & ~1ULL;
+                } else {
+                    od[(size_t)i * K + ro[h]] = id;
+                    ++n_old;
+                }
+                hk = (ef_mix64((which == 0 ? key_new : key_old) + (((u64)(u32)id << 32) | (u32)i)) >> 32 << 32) | (u32)i;
+                parked = reverse_offer(which == 0 ? rnew : rold, which == 0 ? rnew_c : rold_c, L, id, hk);
+            }
+            const u64 mask = (__ballot(parked) >> group_shift) & group_bits;
+            if (parked) {
+                Overflow &o = overflow[(size_t)i * K + n_parked + __popcll(mask & ((1ULL << gl) - 1))];
+                o.key = hk;
+                o.target = id;
+                o.which = which;
+            }
+            n_parked += __popcll(mask);
         }
-        const bool take_old = is_old[h] && e[h] < stop;
-        if (take_old) {
-            od[(size_t)i * K + ro[h]] = id;
-            u64 nm;
-            u64 hk = (ef_mix64(key_old + (((u64)(u32)id << 32) | (u32)i)) >> 32 << 32) | (u32)i;
-            ef_bounded_insert(rold + (size_t)id * L, L, hk, 0, &nm);
-        }
-        n_old += take_old ? 1 : 0;
     }
-    n_old = ef_wave_sum_i32(n_old);
+    for (int m = G / 2; m >= 1; m >>= 1) n_old += __shfl_xor(n_old, m, G);
+    if (!row_ok) return;
     // unused tails of both lists read as -1, so the join needs no counts to parse them
     const int n_new = min(total_new, L);
-    for (int s = n_new + lane; s < L; s += EF_WAVE) nw[(size_t)i * L + s] = -1;
-    for (int s = n_old + lane; s < K; s += EF_WAVE) od[(size_t)i * K + s] = -1;
-    if (lane == 0) {
+    for (int s = n_new + gl; s < L; s += G) nw[(size_t)i * L + s] = -1;
+    for (int s = n_old + gl; s < K; s += G) od[(size_t)i * K + s] = -1;
+    if (gl == 0) {
         nw_c[i] = n_new;
         od_c[i] = n_old;
         worst[i] = wbits;
+        overflow_rows[i] = n_parked;
     }
+}
+
+// one thread per (row, parked key)
+__global__ void reverse_overflow_kernel(const Overflow *__restrict__ overflow,
+                                        const int *__restrict__ overflow_rows, int n, int K,
+                                        u64 *rnew, u64 *rold, int L)
+{
+    const size_t t = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const int i = (int)(t / (size_t)K), j = (int)(t - (size_t)i * K);
+    if (i >= n || j >= overflow_rows[i]) return;
+    const Overflow ov = overflow[(size_t)i * K + j];
+    u64 nm;
+    ef_bounded_insert((ov.which ? rold : rnew) + (size_t)ov.target * L, L, ov.key, 0, &nm);
 }
 
 // After sampling: sort the points that have something to join into three work lists by
@@ -284,7 +348,7 @@ sample_kernel(u64 *graph, int n, int K, int L, u64 key_new, u64 key_old, int *__
 // so that each list runs with the kernel and footprint that fits it.  Points with an
 // empty new set are dropped here.  work: [3][n], work_count: [3].
 __global__ void classify_kernel(const int *__restrict__ nw_c, const int *__restrict__ od_c,
-                                const u64 *__restrict__ rnew, const u64 *__restrict__ rold, int n,
+                                const int *__restrict__ rnew_c, const int *__restrict__ rold_c, int n,
                                 int L, int rows0, int rows1, int *__restrict__ work,
                                 int *__restrict__ work_count, int *__restrict__ cnt_evals,
                                 int *__restrict__ cnt_upd, int *__restrict__ cnt_rows)
@@ -292,11 +356,7 @@ __global__ void classify_kernel(const int *__restrict__ nw_c, const int *__restr
     const int i = blockIdx.x * blockDim.x + threadIdx.x;
     int cls = -1;
     if (i < n) {
-        int rn = 0, ro = 0;
-        for (int s = 0; s < L; ++s) {
-            rn += (u32)rnew[(size_t)i * L + s] < 0x80000000u ? 1 : 0;
-            ro += (u32)rold[(size_t)i * L + s] < 0x80000000u ? 1 : 0;
-        }
+        const int rn = min(rnew_c[i], L), ro = min(rold_c[i], L);
         const int ub_new = nw_c[i] + rn, ub = ub_new + od_c[i] + ro;
         if (ub_new >= 1 && ub >= 2) cls = ub <= rows0 ? 0 : (ub <= rows1 ? 1 : 2);
         else cnt_evals[i] = cnt_upd[i] = cnt_rows[i] = 0;
@@ -817,7 +877,8 @@ __global__ void pair_distances_kernel(const float *__restrict__ X, int d,
 }
 
 struct NndWs {
-    int *nw, *od, *nw_c, *od_c, *cnt_evals, *cnt_upd, *cnt_rows, *work, *work_count;
+    int *nw, *od, *nw_c, *od_c, *cnt_evals, *cnt_upd, *cnt_rows, *work, *work_count, *rnew_c, *rold_c, *overflow_rows;
+    void *overflow;
     u64 *rnew, *rold;
     u32 *worst;
     float *norms;
@@ -843,6 +904,10 @@ NndWs carve_nnd(void *ws, int64_t n, int K, int L)
     w.cnt_rows = (int *)take((size_t)n * 4);
     w.work = (int *)take((size_t)n * 3 * 4);
     w.work_count = (int *)take(4 * 4);
+    w.rnew_c = (int *)take((size_t)n * 4);
+    w.rold_c = (int *)take((size_t)n * 4);
+    w.overflow = take((size_t)n * K * 16);
+    w.overflow_rows = (int *)take((size_t)n * 4);
     w.rnew = (u64 *)take((size_t)n * L * 8);
     w.rold = (u64 *)take((size_t)n * L * 8);
     w.worst = (u32 *)take((size_t)n * 4);
@@ -1002,7 +1067,6 @@ extern "C" int efanna_nndescent(const float *X, int64_t n, int32_t d, int32_t k,
                                          hipFuncAttributeMaxDynamicSharedMemorySize, (int)large.lds));
     norms_kernel<<<grid_for((size_t)n * 16, kBlock), kBlock, 0, st>>>(X, (int)n, d, w.norms);
     if (stats) zero_u64_kernel<<<grid_for((size_t)iters * 4 + 1, kBlock), kBlock, 0, st>>>(stats, iters * 4);
-    const int rows_per_block = kBlock / EF_WAVE;
     // optional phase timing: events around the sampling and the join of every iteration
     hipEvent_t *ev = nullptr;
     if (phase_ms && iters > 0) {
@@ -1013,12 +1077,24 @@ extern "C" int efanna_nndescent(const float *X, int64_t n, int32_t d, int32_t k,
         const int g = first_iter + it;
         if (ev) EF_HIP_CHECK(hipEventRecord(ev[3 * it], st));
         fill_reverse_kernel<<<grid_for((size_t)n * L, kBlock), kBlock, 0, st>>>(
-            w.rnew, w.rold, (size_t)n * L, L, w.work_count);
-        sample_kernel<<<grid_for((size_t)n, rows_per_block), kBlock, 0, st>>>(
-            graph, (int)n, K, L, ef_stream_key(seed, 2 * g), ef_stream_key(seed, 2 * g + 1), w.nw,
-            w.od, w.nw_c, w.od_c, w.rnew, w.rold, w.worst);
+            w.rnew, w.rold, (size_t)n * L, L, w.rnew_c, w.rold_c, (size_t)n, w.work_count);
+        {
+            const u64 kn = ef_stream_key(seed, 2 * g), ko = ef_stream_key(seed, 2 * g + 1);
+            Overflow *ovf = (Overflow *)w.overflow;
+#define EF_SAMPLE(G, E)                                                                          \
+    sample_kernel<G, E><<<grid_for((size_t)n * G, kBlock), kBlock, 0, st>>>(                     \
+        graph, (int)n, K, L, kn, ko, w.nw, w.od, w.nw_c, w.od_c, w.rnew, w.rold, w.rnew_c,       \
+        w.rold_c, ovf, w.overflow_rows, w.worst)
+            if (K <= 16) EF_SAMPLE(16, 1);
+            else if (K <= 32) EF_SAMPLE(32, 1);
+            else if (K <= 64) EF_SAMPLE(64, 1);
+            else EF_SAMPLE(64, 2);
+#undef EF_SAMPLE
+            reverse_overflow_kernel<<<grid_for((size_t)n * K, kBlock), kBlock, 0, st>>>(
+                ovf, w.overflow_rows, (int)n, K, w.rnew, w.rold, L);
+        }
         classify_kernel<<<grid_for((size_t)n, kBlock), kBlock, 0, st>>>(
-            w.nw_c, w.od_c, w.rnew, w.rold, (int)n, L, rows0, rows1, w.work, w.work_count,
+            w.nw_c, w.od_c, w.rnew_c, w.rold_c, (int)n, L, rows0, rows1, w.work, w.work_count,
             w.cnt_evals, w.cnt_upd, w.cnt_rows);
         if (ev) EF_HIP_CHECK(hipEventRecord(ev[3 * it + 1], st));
         if (reg_ok) {
