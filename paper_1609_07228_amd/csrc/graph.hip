@@ -598,11 +598,16 @@ __global__ void join_kernel(const float *__restrict__ X, const float *__restrict
 // (r, g) = (lane % 16, lane / 16) loads 16-byte pieces of vector r (and 16 + r) straight
 // from memory into the registers the MFMA reads, 128 coordinates at a time, so a block
 // needs a few KB of LDS and many more waves fit a CU to hide the memory round trips.
-// Survivors of the filter (few) re-read their two rows, which are still in L2.
+// Survivors of the filter (few) get their exact distance from the same registers when
+// the vectors fit them in one piece (ONE: d <= 128): lane (a, g) fetches the matching
+// pieces of row b from lane (b, g) with cross-lane reads, accumulates the four partial
+// sums it owns (coordinates = 4g..4g+3 mod 16, ascending) and the 16 partial sums are
+// added in the fixed tree across the four lanes of row a.  Longer vectors are re-read
+// from memory (they are still in L2) by one 16-lane group per pair.
 // Requires d % 4 == 0 and a 16-byte aligned X.
 
-template <int NB>
-__global__ void __launch_bounds__(EF_WAVE)
+template <int NB, bool ONE>
+__global__ void __launch_bounds__(EF_WAVE) __attribute__((amdgpu_waves_per_eu(NB > 1 ? 3 : 4)))
 join_reg_kernel(const float *__restrict__ X, const float *__restrict__ norms, int d, int K, int L,
                 const int *__restrict__ work, const int *__restrict__ work_count, int tab_size,
                 int tab_shift, int q_cap, float margin_rel, float thr_scale,
@@ -618,43 +623,60 @@ join_reg_kernel(const float *__restrict__ X, const float *__restrict__ norms, in
     float *nrm = (float *)(thr + R);              // [R]
     int *meta = (int *)(nrm + R);                 // [8]: [0] m [2] updates [3] queue count [4] survivors
     int *tab = meta + 8;                          // [tab_size]
-    u32 *surv = (u32 *)(tab + tab_size);          // [S_CAP]
+    u32 *surv = (u32 *)(tab + tab_size);          // [S_CAP] pair list, or [R] per-row masks (ONE)
     Proposal *queue = (Proposal *)(surv + align4(S_CAP));   // [q_cap]
     const int lane = threadIdx.x, r16 = lane & 15, g = lane >> 4, gl = r16, grp = g;
     const int count = *work_count;
     const int n_cand_new = 2 * L, n_cand_old = K + L;
-    for (int w = blockIdx.x; w < count; w += gridDim.x) {
-        const int i = work[w];
+    // Raw candidate ids of one point, spread over the lanes.  The first 64 new and the first
+    // 64 old candidate slots (all of them unless 2L or K + L exceed 64) are fetched one
+    // point ahead, so that the list reads of the next point overlap the arithmetic and the
+    // list updates of this one.
+    auto cand_new = [&](int i, int a) {
+        if (a < L) return nw[(size_t)i * L + a];
+        const u64 key = rnew[(size_t)i * L + (a - L)];
+        return (u32)key >= 0x80000000u ? -1 : (int)(u32)key;
+    };
+    auto cand_old = [&](int i, int a) {
+        if (a < K) return od[(size_t)i * K + a];
+        const u64 key = rold[(size_t)i * L + (a - K)];
+        return (u32)key >= 0x80000000u ? -1 : (int)(u32)key;
+    };
+    int w = blockIdx.x;
+    int i = w < count ? work[w] : -1;
+    int cn = i >= 0 && lane < n_cand_new ? cand_new(i, lane) : -1;
+    int co = i >= 0 && lane < n_cand_old ? cand_old(i, lane) : -1;
+    int i_next = w + (int)gridDim.x < count ? work[w + gridDim.x] : -1;
+    for (; i >= 0; w += gridDim.x) {
         // ---- 0. candidates ---------------------------------------------------------------
         for (int t = lane; t < tab_size; t += EF_WAVE) tab[t] = -1;
         if (lane < 8) meta[lane] = 0;
+        if (ONE && lane < R) surv[lane] = 0;
         __syncthreads();
-        for (int a = lane; a < n_cand_new; a += EF_WAVE) {
-            int id;
-            if (a < L) id = nw[(size_t)i * L + a];
-            else {
-                const u64 k = rnew[(size_t)i * L + (a - L)];
-                id = (u32)k >= 0x80000000u ? -1 : (int)(u32)k;
-            }
+        if (cn >= 0 && hash_insert(tab, tab_size - 1, tab_shift, cn)) uid[atomicAdd(&meta[0], 1)] = cn;
+        for (int a = lane + EF_WAVE; a < n_cand_new; a += EF_WAVE) {
+            const int id = cand_new(i, a);
             if (id >= 0 && hash_insert(tab, tab_size - 1, tab_shift, id)) uid[atomicAdd(&meta[0], 1)] = id;
         }
         __syncthreads();
         const int m_new = meta[0];
         __syncthreads();
-        for (int a = lane; a < n_cand_old; a += EF_WAVE) {
-            int id;
-            if (a < K) id = od[(size_t)i * K + a];
-            else {
-                const u64 k = rold[(size_t)i * L + (a - K)];
-                id = (u32)k >= 0x80000000u ? -1 : (int)(u32)k;
-            }
+        if (co >= 0 && hash_insert(tab, tab_size - 1, tab_shift, co)) uid[atomicAdd(&meta[0], 1)] = co;
+        for (int a = lane + EF_WAVE; a < n_cand_old; a += EF_WAVE) {
+            const int id = cand_old(i, a);
             if (id >= 0 && hash_insert(tab, tab_size - 1, tab_shift, id)) uid[atomicAdd(&meta[0], 1)] = id;
         }
         __syncthreads();
+        // the next point's lists start travelling now; its index was asked for a point ago
+        const int i_cur = i;
+        i = i_next;
+        cn = i >= 0 && lane < n_cand_new ? cand_new(i, lane) : -1;
+        co = i >= 0 && lane < n_cand_old ? cand_old(i, lane) : -1;
+        i_next = w + 2 * (int)gridDim.x < count ? work[w + 2 * gridDim.x] : -1;
         const int m = meta[0], m_old = m - m_new;
         if (lane == 0) {
-            cnt_evals[i] = m_new * (m_new - 1) / 2 + m_new * m_old;
-            cnt_rows[i] = m;
+            cnt_evals[i_cur] = m_new * (m_new - 1) / 2 + m_new * m_old;
+            cnt_rows[i_cur] = m;
         }
         if (lane < m) {
             const int id = uid[lane];
@@ -665,20 +687,21 @@ join_reg_kernel(const float *__restrict__ X, const float *__restrict__ norms, in
         const float *pa = X + (size_t)uid[min(r16, m - 1)] * d + 4 * g;
         const float *pb = NB > 1 ? X + (size_t)uid[min(16 + r16, m - 1)] * d + 4 * g : pa;
         const bool need11 = NB > 1 && m_new > 16;      // block (1,1) only if new rows reach it
-        floatx4 acc[3][2];
+        constexpr int NQ = NB > 1 ? 3 : 1;      // Gram blocks (0,0), (0,1), (1,1)
+        floatx4 acc[NQ][2];
 #pragma unroll
-        for (int q = 0; q < 3; ++q)
+        for (int q = 0; q < NQ; ++q)
 #pragma unroll
             for (int h = 0; h < 2; ++h) acc[q][h] = (floatx4){0.f, 0.f, 0.f, 0.f};
+        float4 va[8], vb[NB > 1 ? 8 : 1];
         for (int c0 = 0; c0 < d; c0 += 128) {
-            float4 va[8], vb[8];
 #pragma unroll
             for (int s = 0; s < 8; ++s) {
                 const int j = c0 + 16 * s + 4 * g;
                 const bool in = j + 3 < d;                 // d % 4 == 0: a piece is in or out
                 va[s] = in ? *reinterpret_cast<const float4 *>(pa + c0 + 16 * s) : make_float4(0.f, 0.f, 0.f, 0.f);
                 if (NB > 1)
-                    vb[s] = in ? *reinterpret_cast<const float4 *>(pb + c0 + 16 * s) : make_float4(0.f, 0.f, 0.f, 0.f);
+                    vb[NB > 1 ? s : 0] = in ? *reinterpret_cast<const float4 *>(pb + c0 + 16 * s) : make_float4(0.f, 0.f, 0.f, 0.f);
             }
 #pragma unroll
             for (int s = 0; s < 8; ++s) {
@@ -688,15 +711,17 @@ join_reg_kernel(const float *__restrict__ X, const float *__restrict__ norms, in
                 acc[0][0] = __builtin_amdgcn_mfma_f32_16x16x4f32(va[s].z, va[s].z, acc[0][0], 0, 0, 0);
                 acc[0][1] = __builtin_amdgcn_mfma_f32_16x16x4f32(va[s].w, va[s].w, acc[0][1], 0, 0, 0);
                 if (NB > 1) {
-                    acc[1][0] = __builtin_amdgcn_mfma_f32_16x16x4f32(va[s].x, vb[s].x, acc[1][0], 0, 0, 0);
-                    acc[1][1] = __builtin_amdgcn_mfma_f32_16x16x4f32(va[s].y, vb[s].y, acc[1][1], 0, 0, 0);
-                    acc[1][0] = __builtin_amdgcn_mfma_f32_16x16x4f32(va[s].z, vb[s].z, acc[1][0], 0, 0, 0);
-                    acc[1][1] = __builtin_amdgcn_mfma_f32_16x16x4f32(va[s].w, vb[s].w, acc[1][1], 0, 0, 0);
+                    constexpr int Q1 = NB > 1 ? 1 : 0, Q2 = NB > 1 ? 2 : 0;
+                    const float4 wb = vb[NB > 1 ? s : 0];
+                    acc[Q1][0] = __builtin_amdgcn_mfma_f32_16x16x4f32(va[s].x, wb.x, acc[Q1][0], 0, 0, 0);
+                    acc[Q1][1] = __builtin_amdgcn_mfma_f32_16x16x4f32(va[s].y, wb.y, acc[Q1][1], 0, 0, 0);
+                    acc[Q1][0] = __builtin_amdgcn_mfma_f32_16x16x4f32(va[s].z, wb.z, acc[Q1][0], 0, 0, 0);
+                    acc[Q1][1] = __builtin_amdgcn_mfma_f32_16x16x4f32(va[s].w, wb.w, acc[Q1][1], 0, 0, 0);
                     if (need11) {
-                        acc[2][0] = __builtin_amdgcn_mfma_f32_16x16x4f32(vb[s].x, vb[s].x, acc[2][0], 0, 0, 0);
-                        acc[2][1] = __builtin_amdgcn_mfma_f32_16x16x4f32(vb[s].y, vb[s].y, acc[2][1], 0, 0, 0);
-                        acc[2][0] = __builtin_amdgcn_mfma_f32_16x16x4f32(vb[s].z, vb[s].z, acc[2][0], 0, 0, 0);
-                        acc[2][1] = __builtin_amdgcn_mfma_f32_16x16x4f32(vb[s].w, vb[s].w, acc[2][1], 0, 0, 0);
+                        acc[Q2][0] = __builtin_amdgcn_mfma_f32_16x16x4f32(wb.x, wb.x, acc[Q2][0], 0, 0, 0);
+                        acc[Q2][1] = __builtin_amdgcn_mfma_f32_16x16x4f32(wb.y, wb.y, acc[Q2][1], 0, 0, 0);
+                        acc[Q2][0] = __builtin_amdgcn_mfma_f32_16x16x4f32(wb.z, wb.z, acc[Q2][0], 0, 0, 0);
+                        acc[Q2][1] = __builtin_amdgcn_mfma_f32_16x16x4f32(wb.w, wb.w, acc[Q2][1], 0, 0, 0);
                     }
                 }
             }
@@ -715,15 +740,81 @@ join_reg_kernel(const float *__restrict__ X, const float *__restrict__ norms, in
                 if (a < b && a < m_new && b < m) {
                     const float sum = nrm[a] + nb;
                     const float approx = sum - 2.0f * (acc[q][0][k] + acc[q][1][k]);
-                    if (approx - margin_rel * sum <= fmaxf(__uint_as_float(thr[a]), tb) * thr_scale)
-                        surv[atomicAdd(&meta[4], 1)] = (u32)a | ((u32)b << 16);
+                    if (approx - margin_rel * sum <= fmaxf(__uint_as_float(thr[a]), tb) * thr_scale) {
+                        if (ONE) atomicOr(&surv[a], 1u << b);
+                        else surv[atomicAdd(&meta[4], 1)] = (u32)a | ((u32)b << 16);
+                    }
                 }
             }
         }
         __syncthreads();
-        // ---- 3. survivors: fixed-order distance, one 16-lane group per pair -------------------
-        const int n_surv = meta[4];
         int updates = 0;
+        // ---- 3a. survivors from registers: each row works through its own partners ------------
+        if (ONE) {
+#pragma unroll
+            for (int q = 0; q < (NB > 1 ? 3 : 1); ++q) {
+                const int bi = q == 2 ? 1 : 0, bj = q == 0 ? 0 : 1;
+                const int a = 16 * bi + r16;
+                u32 bits = (surv[a] >> (16 * bj)) & 0xFFFFu;
+                while (__any(bits != 0)) {
+                    const bool has = bits != 0;
+                    const int bl = has ? __ffs((int)bits) - 1 : r16;     // idle rows pair with themselves
+                    bits &= bits - 1;
+                    const int src = bl + 16 * g;
+                    float p0 = 0.f, p1 = 0.f, p2 = 0.f, p3 = 0.f;
+#pragma unroll
+                    for (int s = 0; s < 8; ++s) {
+                        if (16 * s >= d) break;
+                        const float4 own = bi == 0 ? va[s] : vb[NB > 1 ? s : 0];
+                        const float4 oth = bj == 0 ? va[s] : vb[NB > 1 ? s : 0];
+                        const float d0 = own.x - __shfl(oth.x, src, EF_WAVE);
+                        const float d1 = own.y - __shfl(oth.y, src, EF_WAVE);
+                        const float d2 = own.z - __shfl(oth.z, src, EF_WAVE);
+                        const float d3 = own.w - __shfl(oth.w, src, EF_WAVE);
+                        p0 = __builtin_fmaf(d0, d0, p0);
+                        p1 = __builtin_fmaf(d1, d1, p1);
+                        p2 = __builtin_fmaf(d2, d2, p2);
+                        p3 = __builtin_fmaf(d3, d3, p3);
+                    }
+                    // partial sum l lives in lane g = l / 4, slot l % 4: l += l+8, l += l+4 across
+                    // lanes, l += l+2, l += l+1 inside lane g = 0
+                    p0 += __shfl_xor(p0, 32, EF_WAVE);
+                    p1 += __shfl_xor(p1, 32, EF_WAVE);
+                    p2 += __shfl_xor(p2, 32, EF_WAVE);
+                    p3 += __shfl_xor(p3, 32, EF_WAVE);
+                    p0 += __shfl_xor(p0, 16, EF_WAVE);
+                    p1 += __shfl_xor(p1, 16, EF_WAVE);
+                    p2 += __shfl_xor(p2, 16, EF_WAVE);
+                    p3 += __shfl_xor(p3, 16, EF_WAVE);
+                    const float dist = (p0 + p2) + (p1 + p3);
+                    if (has && g == 0) {
+                        const int b = 16 * bj + bl;
+                        const u32 db = __float_as_uint(dist);
+                        if (db <= thr[a]) {
+                            const int slot = atomicAdd(&meta[3], 1);
+                            queue[slot].key = ef_pack(dist, uid[b], 1);
+                            queue[slot].target = uid[a];
+                        }
+                        if (db <= thr[b]) {
+                            const int slot = atomicAdd(&meta[3], 1);
+                            queue[slot].key = ef_pack(dist, uid[a], 1);
+                            queue[slot].target = uid[b];
+                        }
+                    }
+                    __syncthreads();
+                    if (meta[3] + 32 > q_cap) {      // a round adds at most two proposals per row
+                        updates += drain_queue(queue, meta[3], graph, worst, K, lane, EF_WAVE);
+                        __syncthreads();
+                        if (lane == 0) meta[3] = 0;
+                        __syncthreads();
+                    }
+                }
+            }
+            updates += drain_queue(queue, meta[3], graph, worst, K, lane, EF_WAVE);
+            __syncthreads();
+        }
+        // ---- 3b. survivors re-read from memory, one 16-lane group per pair ----------------------
+        const int n_surv = ONE ? 0 : meta[4];
         for (int c0 = 0; c0 < n_surv; c0 += q_cap / 2) {
             const int c1 = min(n_surv, c0 + q_cap / 2);
             for (int p0 = c0; p0 < c1; p0 += 4) {
@@ -768,7 +859,7 @@ join_reg_kernel(const float *__restrict__ X, const float *__restrict__ norms, in
             __syncthreads();
         }
         updates = ef_wave_sum_i32(updates);
-        if (lane == 0) cnt_upd[i] = updates;
+        if (lane == 0) cnt_upd[i_cur] = updates;
         __syncthreads();
     }
 }
@@ -1098,15 +1189,18 @@ extern "C" int efanna_nndescent(const float *X, int64_t n, int32_t d, int32_t k,
             w.cnt_evals, w.cnt_upd, w.cnt_rows);
         if (ev) EF_HIP_CHECK(hipEventRecord(ev[3 * it + 1], st));
         if (reg_ok) {
-            join_reg_kernel<1><<<reg_grid, EF_WAVE, reg_lds(16), st>>>(
-                X, w.norms, d, K, L, w.work, w.work_count, tab_size, tab_shift, reg_q_cap, margin_rel,
-                thr_scale, w.nw, w.od, w.rnew, w.rold, graph, w.worst, w.cnt_evals, w.cnt_upd,
-                w.cnt_rows);
-            if (max_rows > 16)
-                join_reg_kernel<2><<<reg_grid, EF_WAVE, reg_lds(32), st>>>(
-                    X, w.norms, d, K, L, w.work + (size_t)n, w.work_count + 1, tab_size, tab_shift,
-                    reg_q_cap, margin_rel, thr_scale, w.nw, w.od, w.rnew, w.rold, graph, w.worst,
-                    w.cnt_evals, w.cnt_upd, w.cnt_rows);
+#define EF_JOIN_REG(NB, ONE, LIST)                                                                 \
+    join_reg_kernel<NB, ONE><<<reg_grid, EF_WAVE, reg_lds(16 * NB), st>>>(                         \
+        X, w.norms, d, K, L, w.work + (size_t)(LIST) * n, w.work_count + (LIST), tab_size,         \
+        tab_shift, reg_q_cap, margin_rel, thr_scale, w.nw, w.od, w.rnew, w.rold, graph, w.worst,   \
+        w.cnt_evals, w.cnt_upd, w.cnt_rows)
+            if (d <= 128) EF_JOIN_REG(1, true, 0);
+            else EF_JOIN_REG(1, false, 0);
+            if (max_rows > 16) {
+                if (d <= 128) EF_JOIN_REG(2, true, 1);
+                else EF_JOIN_REG(2, false, 1);
+            }
+#undef EF_JOIN_REG
         }
         if (max_rows > rows1)
             join_kernel<<<large.grid, large.threads, large.lds, st>>>(
