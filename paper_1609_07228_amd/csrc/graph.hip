@@ -606,6 +606,9 @@ __global__ void join_kernel(const float *__restrict__ X, const float *__restrict
 // from memory (they are still in L2) by one 16-lane group per pair.
 // Requires d % 4 == 0 and a 16-byte aligned X.
 
+// where the survivors of Gram blocks (0,0), (0,1), (1,1) start in the LDS survivor buffer
+__device__ constexpr int kSurvBase[3] = {0, 120, 376};
+
 template <int NB, bool ONE>
 __global__ void __launch_bounds__(EF_WAVE) __attribute__((amdgpu_waves_per_eu(NB > 1 ? 3 : 4)))
 join_reg_kernel(const float *__restrict__ X, const float *__restrict__ norms, int d, int K, int L,
@@ -621,9 +624,9 @@ join_reg_kernel(const float *__restrict__ X, const float *__restrict__ norms, in
     int *uid = (int *)smem;                       // [R]
     u32 *thr = (u32 *)(uid + R);                  // [R]
     float *nrm = (float *)(thr + R);              // [R]
-    int *meta = (int *)(nrm + R);                 // [8]: [0] m [2] updates [3] queue count [4] survivors
+    int *meta = (int *)(nrm + R);                 // [8]: [0] m [3] queue count [4..6] survivors per block
     int *tab = meta + 8;                          // [tab_size]
-    u32 *surv = (u32 *)(tab + tab_size);          // [S_CAP] pair list, or [R] per-row masks (ONE)
+    u32 *surv = (u32 *)(tab + tab_size);          // [S_CAP] surviving pairs
     Proposal *queue = (Proposal *)(surv + align4(S_CAP));   // [q_cap]
     const int lane = threadIdx.x, r16 = lane & 15, g = lane >> 4, gl = r16, grp = g;
     const int count = *work_count;
@@ -651,7 +654,6 @@ join_reg_kernel(const float *__restrict__ X, const float *__restrict__ norms, in
         // ---- 0. candidates ---------------------------------------------------------------
         for (int t = lane; t < tab_size; t += EF_WAVE) tab[t] = -1;
         if (lane < 8) meta[lane] = 0;
-        if (ONE && lane < R) surv[lane] = 0;
         __syncthreads();
         if (cn >= 0 && hash_insert(tab, tab_size - 1, tab_shift, cn)) uid[atomicAdd(&meta[0], 1)] = cn;
         for (int a = lane + EF_WAVE; a < n_cand_new; a += EF_WAVE) {
@@ -741,7 +743,8 @@ join_reg_kernel(const float *__restrict__ X, const float *__restrict__ norms, in
                     const float sum = nrm[a] + nb;
                     const float approx = sum - 2.0f * (acc[q][0][k] + acc[q][1][k]);
                     if (approx - margin_rel * sum <= fmaxf(__uint_as_float(thr[a]), tb) * thr_scale) {
-                        if (ONE) atomicOr(&surv[a], 1u << b);
+                        // ONE: one list per Gram block, entries are rows local to the block
+                        if (ONE) surv[kSurvBase[q] + atomicAdd(&meta[4 + q], 1)] = (u32)(a & 15) | ((u32)(b & 15) << 8);
                         else surv[atomicAdd(&meta[4], 1)] = (u32)a | ((u32)b << 16);
                     }
                 }
@@ -749,46 +752,48 @@ join_reg_kernel(const float *__restrict__ X, const float *__restrict__ norms, in
         }
         __syncthreads();
         int updates = 0;
-        // ---- 3a. survivors from registers: each row works through its own partners ------------
+        // ---- 3a. survivors from registers, sixteen pairs per round --------------------------
+        // The four lanes r16 + 16 g (g = 0..3) of column r16 take pair p0 + r16: lane g
+        // fetches the pieces it needs of rows a and b from lanes a + 16 g and b + 16 g,
+        // which hold the coordinates = 4g..4g+3 (mod 16) of those rows.
         if (ONE) {
 #pragma unroll
             for (int q = 0; q < (NB > 1 ? 3 : 1); ++q) {
                 const int bi = q == 2 ? 1 : 0, bj = q == 0 ? 0 : 1;
-                const int a = 16 * bi + r16;
-                u32 bits = (surv[a] >> (16 * bj)) & 0xFFFFu;
-                while (__any(bits != 0)) {
-                    const bool has = bits != 0;
-                    const int bl = has ? __ffs((int)bits) - 1 : r16;     // idle rows pair with themselves
-                    bits &= bits - 1;
-                    const int src = bl + 16 * g;
-                    float p0 = 0.f, p1 = 0.f, p2 = 0.f, p3 = 0.f;
+                const int n_q = meta[4 + q];
+                for (int p0 = 0; p0 < n_q; p0 += 16) {
+                    const bool has = p0 + r16 < n_q;
+                    const u32 ent = surv[kSurvBase[q] + min(p0 + r16, n_q - 1)];
+                    const int al = ent & 15, bl = (ent >> 8) & 15;
+                    const int src_a = al + 16 * g, src_b = bl + 16 * g;
+                    float p0s = 0.f, p1s = 0.f, p2s = 0.f, p3s = 0.f;
 #pragma unroll
                     for (int s = 0; s < 8; ++s) {
                         if (16 * s >= d) break;
                         const float4 own = bi == 0 ? va[s] : vb[NB > 1 ? s : 0];
                         const float4 oth = bj == 0 ? va[s] : vb[NB > 1 ? s : 0];
-                        const float d0 = own.x - __shfl(oth.x, src, EF_WAVE);
-                        const float d1 = own.y - __shfl(oth.y, src, EF_WAVE);
-                        const float d2 = own.z - __shfl(oth.z, src, EF_WAVE);
-                        const float d3 = own.w - __shfl(oth.w, src, EF_WAVE);
-                        p0 = __builtin_fmaf(d0, d0, p0);
-                        p1 = __builtin_fmaf(d1, d1, p1);
-                        p2 = __builtin_fmaf(d2, d2, p2);
-                        p3 = __builtin_fmaf(d3, d3, p3);
+                        const float d0 = __shfl(own.x, src_a, EF_WAVE) - __shfl(oth.x, src_b, EF_WAVE);
+                        const float d1 = __shfl(own.y, src_a, EF_WAVE) - __shfl(oth.y, src_b, EF_WAVE);
+                        const float d2 = __shfl(own.z, src_a, EF_WAVE) - __shfl(oth.z, src_b, EF_WAVE);
+                        const float d3 = __shfl(own.w, src_a, EF_WAVE) - __shfl(oth.w, src_b, EF_WAVE);
+                        p0s = __builtin_fmaf(d0, d0, p0s);
+                        p1s = __builtin_fmaf(d1, d1, p1s);
+                        p2s = __builtin_fmaf(d2, d2, p2s);
+                        p3s = __builtin_fmaf(d3, d3, p3s);
                     }
                     // partial sum l lives in lane g = l / 4, slot l % 4: l += l+8, l += l+4 across
                     // lanes, l += l+2, l += l+1 inside lane g = 0
-                    p0 += __shfl_xor(p0, 32, EF_WAVE);
-                    p1 += __shfl_xor(p1, 32, EF_WAVE);
-                    p2 += __shfl_xor(p2, 32, EF_WAVE);
-                    p3 += __shfl_xor(p3, 32, EF_WAVE);
-                    p0 += __shfl_xor(p0, 16, EF_WAVE);
-                    p1 += __shfl_xor(p1, 16, EF_WAVE);
-                    p2 += __shfl_xor(p2, 16, EF_WAVE);
-                    p3 += __shfl_xor(p3, 16, EF_WAVE);
-                    const float dist = (p0 + p2) + (p1 + p3);
+                    p0s += __shfl_xor(p0s, 32, EF_WAVE);
+                    p1s += __shfl_xor(p1s, 32, EF_WAVE);
+                    p2s += __shfl_xor(p2s, 32, EF_WAVE);
+                    p3s += __shfl_xor(p3s, 32, EF_WAVE);
+                    p0s += __shfl_xor(p0s, 16, EF_WAVE);
+                    p1s += __shfl_xor(p1s, 16, EF_WAVE);
+                    p2s += __shfl_xor(p2s, 16, EF_WAVE);
+                    p3s += __shfl_xor(p3s, 16, EF_WAVE);
+                    const float dist = (p0s + p2s) + (p1s + p3s);
                     if (has && g == 0) {
-                        const int b = 16 * bj + bl;
+                        const int a = 16 * bi + al, b = 16 * bj + bl;
                         const u32 db = __float_as_uint(dist);
                         if (db <= thr[a]) {
                             const int slot = atomicAdd(&meta[3], 1);
@@ -802,7 +807,7 @@ join_reg_kernel(const float *__restrict__ X, const float *__restrict__ norms, in
                         }
                     }
                     __syncthreads();
-                    if (meta[3] + 32 > q_cap) {      // a round adds at most two proposals per row
+                    if (meta[3] + 32 > q_cap) {      // a round adds at most two proposals per pair
                         updates += drain_queue(queue, meta[3], graph, worst, K, lane, EF_WAVE);
                         __syncthreads();
                         if (lane == 0) meta[3] = 0;
