@@ -27,7 +27,7 @@ __global__ void fill_reverse_kernel(u64 *a, u64 *b, size_t total, int L, int *a_
                                     size_t n, int *work_count)
 {
     size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (i < 4) work_count[i] = 0;     // three work lists and the overflow queue
+    if (i < 8) work_count[i] = 0;     // three work lists, insertion counter
     if (i < n) {
         a_count[i] = 0;
         b_count[i] = 0;
@@ -358,8 +358,9 @@ __global__ void classify_kernel(const int *__restrict__ nw_c, const int *__restr
     if (i < n) {
         const int rn = min(rnew_c[i], L), ro = min(rold_c[i], L);
         const int ub_new = nw_c[i] + rn, ub = ub_new + od_c[i] + ro;
+        cnt_upd[i] = 0;      // only the joins through the LDS row buffer count per point
         if (ub_new >= 1 && ub >= 2) cls = ub <= rows0 ? 0 : (ub <= rows1 ? 1 : 2);
-        else cnt_evals[i] = cnt_upd[i] = cnt_rows[i] = 0;
+        else cnt_evals[i] = cnt_rows[i] = 0;
     }
     const int lane = ef_lane();
 #pragma unroll
@@ -616,7 +617,7 @@ join_reg_kernel(const float *__restrict__ X, const float *__restrict__ norms, in
                 int tab_shift, int q_cap, float margin_rel, float thr_scale,
                 const int *__restrict__ nw, const int *__restrict__ od,
                 const u64 *__restrict__ rnew, const u64 *__restrict__ rold, u64 *graph, u32 *worst,
-                int *__restrict__ cnt_evals, int *__restrict__ cnt_upd, int *__restrict__ cnt_rows)
+                int *__restrict__ cnt_evals, u64 *__restrict__ upd_total, int *__restrict__ cnt_rows)
 {
     constexpr int R = 16 * NB;                    // rows
     constexpr int S_CAP = R * (R - 1) / 2 + 8;    // every pair may survive
@@ -650,10 +651,15 @@ join_reg_kernel(const float *__restrict__ X, const float *__restrict__ norms, in
     int cn = i >= 0 && lane < n_cand_new ? cand_new(i, lane) : -1;
     int co = i >= 0 && lane < n_cand_old ? cand_old(i, lane) : -1;
     int i_next = w + (int)gridDim.x < count ? work[w + gridDim.x] : -1;
+    // Proposals wait in the queue across points and are applied when about half of it is
+    // full (and at the end): late iterations accept well under one proposal per point, and
+    // a drain costs two memory round trips whatever its size.
+    int updates = 0;
+    if (lane == 0) meta[3] = 0;
     for (; i >= 0; w += gridDim.x) {
         // ---- 0. candidates ---------------------------------------------------------------
         for (int t = lane; t < tab_size; t += EF_WAVE) tab[t] = -1;
-        if (lane < 8) meta[lane] = 0;
+        if (lane < 8 && lane != 3) meta[lane] = 0;
         __syncthreads();
         if (cn >= 0 && hash_insert(tab, tab_size - 1, tab_shift, cn)) uid[atomicAdd(&meta[0], 1)] = cn;
         for (int a = lane + EF_WAVE; a < n_cand_new; a += EF_WAVE) {
@@ -751,7 +757,6 @@ join_reg_kernel(const float *__restrict__ X, const float *__restrict__ norms, in
             }
         }
         __syncthreads();
-        int updates = 0;
         // ---- 3a. survivors from registers, sixteen pairs per round --------------------------
         // The four lanes r16 + 16 g (g = 0..3) of column r16 take pair p0 + r16: lane g
         // fetches the pieces it needs of rows a and b from lanes a + 16 g and b + 16 g,
@@ -815,11 +820,15 @@ join_reg_kernel(const float *__restrict__ X, const float *__restrict__ norms, in
                     }
                 }
             }
-            updates += drain_queue(queue, meta[3], graph, worst, K, lane, EF_WAVE);
-            __syncthreads();
         }
         // ---- 3b. survivors re-read from memory, one 16-lane group per pair ----------------------
         const int n_surv = ONE ? 0 : meta[4];
+        if (!ONE && n_surv > 0 && meta[3] > 0) {      // the chunks below want an empty queue
+            updates += drain_queue(queue, meta[3], graph, worst, K, lane, EF_WAVE);
+            __syncthreads();
+            if (lane == 0) meta[3] = 0;
+            __syncthreads();
+        }
         for (int c0 = 0; c0 < n_surv; c0 += q_cap / 2) {
             const int c1 = min(n_surv, c0 + q_cap / 2);
             for (int p0 = c0; p0 < c1; p0 += 4) {
@@ -863,10 +872,17 @@ join_reg_kernel(const float *__restrict__ X, const float *__restrict__ norms, in
             if (lane == 0) meta[3] = 0;
             __syncthreads();
         }
-        updates = ef_wave_sum_i32(updates);
-        if (lane == 0) cnt_upd[i_cur] = updates;
+        if (meta[3] >= q_cap / 2) {
+            updates += drain_queue(queue, meta[3], graph, worst, K, lane, EF_WAVE);
+            __syncthreads();
+            if (lane == 0) meta[3] = 0;
+        }
         __syncthreads();
     }
+    __syncthreads();
+    updates += drain_queue(queue, meta[3], graph, worst, K, lane, EF_WAVE);
+    updates = ef_wave_sum_i32(updates);
+    if (lane == 0 && updates) atomicAdd(upd_total, (u64)updates);
 }
 
 // squared norms in float32 (only the join's filter uses them; any summation order will do)
@@ -883,8 +899,9 @@ __global__ void norms_kernel(const float *__restrict__ X, int n, int d, float *_
 }
 
 __global__ void stats_kernel(const int *__restrict__ cnt_evals, const int *__restrict__ cnt_upd,
-                             const int *__restrict__ cnt_rows, int n, u64 *stats)
+                             const int *__restrict__ cnt_rows, int n, const u64 *upd_total, u64 *stats)
 {
+    if (blockIdx.x == 0 && threadIdx.x == 0) atomicAdd(stats + 1, *upd_total);
     long long ev = 0, up = 0, rw = 0;
     for (int i = blockIdx.x * blockDim.x + threadIdx.x; i < n; i += gridDim.x * blockDim.x) {
         ev += cnt_evals[i];
@@ -999,7 +1016,7 @@ NndWs carve_nnd(void *ws, int64_t n, int K, int L)
     w.cnt_upd = (int *)take((size_t)n * 4);
     w.cnt_rows = (int *)take((size_t)n * 4);
     w.work = (int *)take((size_t)n * 3 * 4);
-    w.work_count = (int *)take(4 * 4);
+    w.work_count = (int *)take(8 * 4);     // [0..2] list sizes, [4..5] accepted insertions (u64)
     w.rnew_c = (int *)take((size_t)n * 4);
     w.rold_c = (int *)take((size_t)n * 4);
     w.overflow = take((size_t)n * K * 16);
@@ -1198,7 +1215,7 @@ extern "C" int efanna_nndescent(const float *X, int64_t n, int32_t d, int32_t k,
     join_reg_kernel<NB, ONE><<<reg_grid, EF_WAVE, reg_lds(16 * NB), st>>>(                         \
         X, w.norms, d, K, L, w.work + (size_t)(LIST) * n, w.work_count + (LIST), tab_size,         \
         tab_shift, reg_q_cap, margin_rel, thr_scale, w.nw, w.od, w.rnew, w.rold, graph, w.worst,   \
-        w.cnt_evals, w.cnt_upd, w.cnt_rows)
+        w.cnt_evals, (u64 *)(w.work_count + 4), w.cnt_rows)
             if (d <= 128) EF_JOIN_REG(1, true, 0);
             else EF_JOIN_REG(1, false, 0);
             if (max_rows > 16) {
@@ -1216,7 +1233,7 @@ extern "C" int efanna_nndescent(const float *X, int64_t n, int32_t d, int32_t k,
         if (ev) EF_HIP_CHECK(hipEventRecord(ev[3 * it + 2], st));
         if (stats)
             stats_kernel<<<256, kBlock, 0, st>>>(w.cnt_evals, w.cnt_upd, w.cnt_rows, (int)n,
-                                                 stats + 4 * it);
+                                                 (const u64 *)(w.work_count + 4), stats + 4 * it);
     }
     EF_HIP_CHECK(hipGetLastError());
     if (ev) {
