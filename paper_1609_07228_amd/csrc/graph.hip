@@ -343,24 +343,70 @@ __global__ void reverse_overflow_kernel(const Overflow *__restrict__ overflow,
     ef_bounded_insert((ov.which ? rold : rnew) + (size_t)ov.target * L, L, ov.key, 0, &nm);
 }
 
-// After sampling: sort the points that have something to join into three work lists by
-// an upper bound of the number of vectors their join gathers (<= rows0, <= rows1, more),
-// so that each list runs with the kernel and footprint that fits it.  Points with an
-// empty new set are dropped here.  work: [3][n], work_count: [3].
-__global__ void classify_kernel(const int *__restrict__ nw_c, const int *__restrict__ od_c,
-                                const int *__restrict__ rnew_c, const int *__restrict__ rold_c, int n,
-                                int L, int rows0, int rows1, int *__restrict__ work,
-                                int *__restrict__ work_count, int *__restrict__ cnt_evals,
-                                int *__restrict__ cnt_upd, int *__restrict__ cnt_rows)
+// After sampling and the reverse lists: one thread per point merges its four id lists
+// into U_new ++ U_old (Alg. 4: G_new U G_rnew, G_old U G_rold), without duplicates and
+// with everything already in U_new left out of U_old, and files the point under one of
+// three work lists by the number of vectors its join gathers (<= rows0, <= rows1, more).
+// Points with an empty U_new are dropped.  A thread compares only what can collide:
+// ids inside one sampled list are distinct, and so are the sources inside one reverse
+// list.  ulist: [n][cap] (written through LDS so that the stores coalesce), ucount: [n]
+// (m_new, m); work: [3][n], work_count: [3].
+__global__ void prepare_kernel(const int *__restrict__ nw, const int *__restrict__ od,
+                               const int *__restrict__ nw_c, const int *__restrict__ od_c,
+                               const u64 *__restrict__ rnew, const u64 *__restrict__ rold,
+                               const int *__restrict__ rnew_c, const int *__restrict__ rold_c,
+                               int n, int K, int L, int cap, int rows0, int rows1,
+                               int *__restrict__ ulist, int2 *__restrict__ ucount,
+                               int *__restrict__ work, int *__restrict__ work_count,
+                               int *__restrict__ cnt_evals, int *__restrict__ cnt_upd,
+                               int *__restrict__ cnt_rows)
 {
+    extern __shared__ int ids_sh[];
+    const int pitch = cap | 1;                      // odd: threads hit different banks
+    int *mine = ids_sh + threadIdx.x * pitch;
     const int i = blockIdx.x * blockDim.x + threadIdx.x;
-    int cls = -1;
+    int cls = -1, m = 0;
     if (i < n) {
+        const int c_new = nw_c[i], c_old = od_c[i];
         const int rn = min(rnew_c[i], L), ro = min(rold_c[i], L);
-        const int ub_new = nw_c[i] + rn, ub = ub_new + od_c[i] + ro;
+        for (int a = 0; a < c_new; ++a) mine[m++] = nw[(size_t)i * L + a];
+        for (int a = 0; a < rn; ++a) {
+            const int id = (int)(u32)rnew[(size_t)i * L + a];
+            bool dup = false;
+            for (int k = 0; k < c_new; ++k) dup |= mine[k] == id;
+            if (!dup) mine[m++] = id;
+        }
+        const int m_new = m;
+        for (int a = 0; a < c_old; ++a) {
+            const int id = od[(size_t)i * K + a];
+            bool dup = false;
+            for (int k = c_new; k < m_new; ++k) dup |= mine[k] == id;      // only reverse-new can collide
+            if (!dup) mine[m++] = id;
+        }
+        const int m_mid = m;
+        for (int a = 0; a < ro; ++a) {
+            const int id = (int)(u32)rold[(size_t)i * L + a];
+            bool dup = false;
+            for (int k = 0; k < m_mid; ++k) dup |= mine[k] == id;
+            if (!dup) mine[m++] = id;
+        }
+        ucount[i] = make_int2(m_new, m);
         cnt_upd[i] = 0;      // only the joins through the LDS row buffer count per point
-        if (ub_new >= 1 && ub >= 2) cls = ub <= rows0 ? 0 : (ub <= rows1 ? 1 : 2);
-        else cnt_evals[i] = cnt_rows[i] = 0;
+        if (m_new >= 1 && m >= 2) {
+            cls = m <= rows0 ? 0 : (m <= rows1 ? 1 : 2);
+            cnt_evals[i] = m_new * (m_new - 1) / 2 + m_new * (m - m_new);
+            cnt_rows[i] = m;
+        } else {
+            cnt_evals[i] = cnt_rows[i] = 0;
+        }
+    }
+    for (int k = m; k < cap; ++k) mine[k] = -1;
+    __syncthreads();
+    // coalesced write-out of the block's lists
+    const int first = blockIdx.x * blockDim.x, rows_here = min((int)blockDim.x, n - first);
+    for (int f = threadIdx.x; f < rows_here * cap; f += blockDim.x) {
+        const int r = f / cap, c = f - r * cap;
+        ulist[(size_t)first * cap + f] = ids_sh[r * pitch + c];
     }
     const int lane = ef_lane();
 #pragma unroll
@@ -399,94 +445,50 @@ struct JoinLds {
     int *uid;         // [cap_rows] U_new ++ U_old
     u32 *thr;         // [cap_rows] threshold bits
     float *nrm;       // [cap_rows] squared norms (float32, any order: filter only)
-    int *tab;         // [tab_size] hash table for de-duplication
-    int *meta;        // [0] m (fill count) [1] m_new [2] updates [3] queue count [4] survivor count
+    int *meta;        // [2] updates [3] queue count [4] survivor count
     u32 *surv;        // [s_cap] a | b << 16
     Proposal *queue;  // [q_cap]
 };
 
-__host__ __device__ inline size_t join_lds_floats(int cap_rows, int stride, int tab_size, int s_cap)
+__host__ __device__ inline size_t join_lds_floats(int cap_rows, int stride, int s_cap)
 {
-    return (size_t)align4(cap_rows * stride) + align4(3 * cap_rows) + tab_size + 8 + align4(s_cap);
+    return (size_t)align4(cap_rows * stride) + align4(3 * cap_rows) + 8 + align4(s_cap);
 }
 
-__device__ inline JoinLds join_lds_carve(float *smem, int cap_rows, int stride, int tab_size, int s_cap)
+__device__ inline JoinLds join_lds_carve(float *smem, int cap_rows, int stride, int s_cap)
 {
     JoinLds l;
     l.rows = smem;
     l.uid = (int *)(smem + align4(cap_rows * stride));
     l.thr = (u32 *)(l.uid + cap_rows);
     l.nrm = (float *)(l.thr + cap_rows);
-    l.tab = l.uid + align4(3 * cap_rows);
-    l.meta = l.tab + tab_size;
+    l.meta = l.uid + align4(3 * cap_rows);
     l.surv = (u32 *)(l.meta + 8);
     l.queue = (Proposal *)(l.surv + align4(s_cap));
     return l;
 }
 
-// insert id into the open-addressing table; true if it was not there yet
-__device__ inline bool hash_insert(int *tab, int tab_mask, int tab_shift, int id)
-{
-    u32 slot = ((u32)id * 2654435761u) >> tab_shift;
-    for (;;) {
-        const int old = atomicCAS(&tab[slot], -1, id);
-        if (old == -1) return true;
-        if (old == id) return false;
-        slot = (slot + 1) & tab_mask;
-    }
-}
-
 __global__ void join_kernel(const float *__restrict__ X, const float *__restrict__ norms, int d,
-                            int dpad, int stride, u32 q4_magic, int K, int L,
+                            int dpad, int stride, u32 q4_magic, int K,
                             const int *__restrict__ work, const int *__restrict__ work_count,
-                            int cap_rows, int tab_size, int tab_shift, int s_cap, int q_cap,
-                            float margin_rel, float thr_scale, const int *__restrict__ nw,
-                            const int *__restrict__ od, const u64 *__restrict__ rnew,
-                            const u64 *__restrict__ rold, u64 *graph, u32 *worst,
-                            int *__restrict__ cnt_evals, int *__restrict__ cnt_upd,
-                            int *__restrict__ cnt_rows)
+                            int cap_rows, int s_cap, int q_cap, float margin_rel, float thr_scale,
+                            const int *__restrict__ ulist, const int2 *__restrict__ ucount,
+                            int ucap, u64 *graph, u32 *worst, int *__restrict__ cnt_upd)
 {
     extern __shared__ float smem[];
-    const JoinLds lds = join_lds_carve(smem, cap_rows, stride, tab_size, s_cap);
+    const JoinLds lds = join_lds_carve(smem, cap_rows, stride, s_cap);
     const int tid = threadIdx.x, nthr = blockDim.x;
     const int lane = tid & (EF_WAVE - 1), wave = tid / EF_WAVE, n_waves = nthr / EF_WAVE;
     const int grp = tid >> 4, gl = tid & 15, n_grp = nthr >> 4;
     const int count = *work_count;
     for (int w = blockIdx.x; w < count; w += gridDim.x) {
         const int i = work[w];
-        // ---- 0. candidates -------------------------------------------------------------
-        for (int t = tid; t < tab_size; t += nthr) lds.tab[t] = -1;
+        // ---- 0. the point's U_new ++ U_old ------------------------------------------------
+        const int2 mc = ucount[i];
+        const int m_new = mc.x, m = mc.y;
+        for (int r = tid; r < m; r += nthr) lds.uid[r] = ulist[(size_t)i * ucap + r];
         if (tid < 8) lds.meta[tid] = 0;
         __syncthreads();
-        for (int a = tid; a < 2 * L; a += nthr) {     // new: sampled, then reverse
-            int id;
-            if (a < L) id = nw[(size_t)i * L + a];
-            else {
-                const u64 k = rnew[(size_t)i * L + (a - L)];
-                id = (u32)k >= 0x80000000u ? -1 : (int)(u32)k;
-            }
-            if (id >= 0 && hash_insert(lds.tab, tab_size - 1, tab_shift, id))
-                lds.uid[atomicAdd(&lds.meta[0], 1)] = id;
-        }
-        __syncthreads();
-        const int m_new = lds.meta[0];      // everything so far is new
-        __syncthreads();                    // ... and nobody adds before everybody has read it
-        for (int a = tid; a < K + L; a += nthr) {     // old: sampled, then reverse; not if already new
-            int id;
-            if (a < K) id = od[(size_t)i * K + a];
-            else {
-                const u64 k = rold[(size_t)i * L + (a - K)];
-                id = (u32)k >= 0x80000000u ? -1 : (int)(u32)k;
-            }
-            if (id >= 0 && hash_insert(lds.tab, tab_size - 1, tab_shift, id))
-                lds.uid[atomicAdd(&lds.meta[0], 1)] = id;
-        }
-        __syncthreads();
-        const int m = lds.meta[0], m_old = m - m_new;
-        if (tid == 0) {
-            cnt_evals[i] = m_new * (m_new - 1) / 2 + m_new * m_old;
-            cnt_rows[i] = m;
-        }
         // ---- 1. gather -------------------------------------------------------------------
         for (int r = tid; r < m; r += nthr) {
             const int id = lds.uid[r];
@@ -612,12 +614,11 @@ __device__ constexpr int kSurvBase[3] = {0, 120, 376};
 
 template <int NB, bool ONE>
 __global__ void __launch_bounds__(EF_WAVE) __attribute__((amdgpu_waves_per_eu(NB > 1 ? 3 : 4)))
-join_reg_kernel(const float *__restrict__ X, const float *__restrict__ norms, int d, int K, int L,
-                const int *__restrict__ work, const int *__restrict__ work_count, int tab_size,
-                int tab_shift, int q_cap, float margin_rel, float thr_scale,
-                const int *__restrict__ nw, const int *__restrict__ od,
-                const u64 *__restrict__ rnew, const u64 *__restrict__ rold, u64 *graph, u32 *worst,
-                int *__restrict__ cnt_evals, u64 *__restrict__ upd_total, int *__restrict__ cnt_rows)
+join_reg_kernel(const float *__restrict__ X, const float *__restrict__ norms, int d, int K,
+                const int *__restrict__ work, const int *__restrict__ work_count, int q_cap,
+                float margin_rel, float thr_scale, const int *__restrict__ ulist,
+                const int2 *__restrict__ ucount, int ucap, u64 *graph, u32 *worst,
+                u64 *__restrict__ upd_total)
 {
     constexpr int R = 16 * NB;                    // rows
     constexpr int S_CAP = R * (R - 1) / 2 + 8;    // every pair may survive
@@ -625,31 +626,17 @@ join_reg_kernel(const float *__restrict__ X, const float *__restrict__ norms, in
     int *uid = (int *)smem;                       // [R]
     u32 *thr = (u32 *)(uid + R);                  // [R]
     float *nrm = (float *)(thr + R);              // [R]
-    int *meta = (int *)(nrm + R);                 // [8]: [0] m [3] queue count [4..6] survivors per block
-    int *tab = meta + 8;                          // [tab_size]
-    u32 *surv = (u32 *)(tab + tab_size);          // [S_CAP] surviving pairs
+    int *meta = (int *)(nrm + R);                 // [8]: [3] queue count [4..6] survivors per block
+    u32 *surv = (u32 *)(meta + 8);                // [S_CAP] surviving pairs
     Proposal *queue = (Proposal *)(surv + align4(S_CAP));   // [q_cap]
     const int lane = threadIdx.x, r16 = lane & 15, g = lane >> 4, gl = r16, grp = g;
     const int count = *work_count;
-    const int n_cand_new = 2 * L, n_cand_old = K + L;
-    // Raw candidate ids of one point, spread over the lanes.  The first 64 new and the first
-    // 64 old candidate slots (all of them unless 2L or K + L exceed 64) are fetched one
-    // point ahead, so that the list reads of the next point overlap the arithmetic and the
-    // list updates of this one.
-    auto cand_new = [&](int i, int a) {
-        if (a < L) return nw[(size_t)i * L + a];
-        const u64 key = rnew[(size_t)i * L + (a - L)];
-        return (u32)key >= 0x80000000u ? -1 : (int)(u32)key;
-    };
-    auto cand_old = [&](int i, int a) {
-        if (a < K) return od[(size_t)i * K + a];
-        const u64 key = rold[(size_t)i * L + (a - K)];
-        return (u32)key >= 0x80000000u ? -1 : (int)(u32)key;
-    };
+    // The id list and the sizes of the next point are fetched one point ahead, so that
+    // they travel while this point is being worked on.
     int w = blockIdx.x;
     int i = w < count ? work[w] : -1;
-    int cn = i >= 0 && lane < n_cand_new ? cand_new(i, lane) : -1;
-    int co = i >= 0 && lane < n_cand_old ? cand_old(i, lane) : -1;
+    int u_pre = i >= 0 && lane < R ? ulist[(size_t)i * ucap + min(lane, ucap - 1)] : -1;
+    int2 c_pre = i >= 0 ? ucount[i] : make_int2(0, 0);
     int i_next = w + (int)gridDim.x < count ? work[w + gridDim.x] : -1;
     // Proposals wait in the queue across points and are applied when about half of it is
     // full (and at the end): late iterations accept well under one proposal per point, and
@@ -657,35 +644,15 @@ join_reg_kernel(const float *__restrict__ X, const float *__restrict__ norms, in
     int updates = 0;
     if (lane == 0) meta[3] = 0;
     for (; i >= 0; w += gridDim.x) {
-        // ---- 0. candidates ---------------------------------------------------------------
-        for (int t = lane; t < tab_size; t += EF_WAVE) tab[t] = -1;
+        // ---- 0. the point's U_new ++ U_old ------------------------------------------------
+        const int m_new = c_pre.x, m = c_pre.y;
+        if (lane < R) uid[lane] = u_pre;
         if (lane < 8 && lane != 3) meta[lane] = 0;
         __syncthreads();
-        if (cn >= 0 && hash_insert(tab, tab_size - 1, tab_shift, cn)) uid[atomicAdd(&meta[0], 1)] = cn;
-        for (int a = lane + EF_WAVE; a < n_cand_new; a += EF_WAVE) {
-            const int id = cand_new(i, a);
-            if (id >= 0 && hash_insert(tab, tab_size - 1, tab_shift, id)) uid[atomicAdd(&meta[0], 1)] = id;
-        }
-        __syncthreads();
-        const int m_new = meta[0];
-        __syncthreads();
-        if (co >= 0 && hash_insert(tab, tab_size - 1, tab_shift, co)) uid[atomicAdd(&meta[0], 1)] = co;
-        for (int a = lane + EF_WAVE; a < n_cand_old; a += EF_WAVE) {
-            const int id = cand_old(i, a);
-            if (id >= 0 && hash_insert(tab, tab_size - 1, tab_shift, id)) uid[atomicAdd(&meta[0], 1)] = id;
-        }
-        __syncthreads();
-        // the next point's lists start travelling now; its index was asked for a point ago
-        const int i_cur = i;
         i = i_next;
-        cn = i >= 0 && lane < n_cand_new ? cand_new(i, lane) : -1;
-        co = i >= 0 && lane < n_cand_old ? cand_old(i, lane) : -1;
+        u_pre = i >= 0 && lane < R ? ulist[(size_t)i * ucap + min(lane, ucap - 1)] : -1;
+        c_pre = i >= 0 ? ucount[i] : make_int2(0, 0);
         i_next = w + 2 * (int)gridDim.x < count ? work[w + 2 * gridDim.x] : -1;
-        const int m = meta[0], m_old = m - m_new;
-        if (lane == 0) {
-            cnt_evals[i_cur] = m_new * (m_new - 1) / 2 + m_new * m_old;
-            cnt_rows[i_cur] = m;
-        }
         if (lane < m) {
             const int id = uid[lane];
             thr[lane] = ef_load_coherent(worst + id);
@@ -990,7 +957,8 @@ __global__ void pair_distances_kernel(const float *__restrict__ X, int d,
 }
 
 struct NndWs {
-    int *nw, *od, *nw_c, *od_c, *cnt_evals, *cnt_upd, *cnt_rows, *work, *work_count, *rnew_c, *rold_c, *overflow_rows;
+    int *nw, *od, *nw_c, *od_c, *cnt_evals, *cnt_upd, *cnt_rows, *work, *work_count, *rnew_c, *rold_c, *overflow_rows, *ulist;
+    int2 *ucount;
     void *overflow;
     u64 *rnew, *rold;
     u32 *worst;
@@ -1021,6 +989,8 @@ NndWs carve_nnd(void *ws, int64_t n, int K, int L)
     w.rold_c = (int *)take((size_t)n * 4);
     w.overflow = take((size_t)n * K * 16);
     w.overflow_rows = (int *)take((size_t)n * 4);
+    w.ulist = (int *)take((size_t)n * (K + 2 * L) * 4);
+    w.ucount = (int2 *)take((size_t)n * 8);
     w.rnew = (u64 *)take((size_t)n * L * 8);
     w.rold = (u64 *)take((size_t)n * L * 8);
     w.worst = (u32 *)take((size_t)n * 4);
@@ -1122,11 +1092,6 @@ extern "C" int efanna_nndescent(const float *X, int64_t n, int32_t d, int32_t k,
     // operands (needs 16-byte aligned rows), the rest through the LDS row buffer
     const bool reg_ok = (d & 3) == 0 && ((uintptr_t)X & 15) == 0;
     const int rows0 = reg_ok ? 16 : 0, rows1 = reg_ok ? 32 : 0;
-    int tab_size = 64, tab_shift = 26;
-    while (tab_size < 2 * max_rows) {
-        tab_size <<= 1;
-        --tab_shift;
-    }
     struct Shape {
         int cap_rows, threads, s_cap, q_cap, grid;
         size_t lds;
@@ -1145,7 +1110,7 @@ extern "C" int efanna_nndescent(const float *X, int64_t n, int32_t d, int32_t k,
             if (pairs > sh.s_cap && pairs <= 1024) sh.s_cap = align4((int)pairs);
             if (cap_rows <= 16) sh.s_cap = 128;     // a single block of at most 120 pairs
             for (sh.q_cap = 4 * sh.threads; sh.q_cap >= 128 && !fits; sh.q_cap /= 2) {
-                sh.lds = join_lds_floats(cap_rows, stride, tab_size, sh.s_cap) * 4 +
+                sh.lds = join_lds_floats(cap_rows, stride, sh.s_cap) * 4 +
                          (size_t)sh.q_cap * sizeof(Proposal);
                 fits = sh.lds <= kLdsLimit;
                 if (fits) break;
@@ -1165,10 +1130,14 @@ extern "C" int efanna_nndescent(const float *X, int64_t n, int32_t d, int32_t k,
     if (max_rows > rows1 && large.lds > kLdsLimit) return EFANNA_EUNSUPPORTED;
     const int reg_q_cap = 128;
     auto reg_lds = [&](int R) {
-        return (size_t)(3 * R + 8 + tab_size + align4(R * (R - 1) / 2 + 8)) * 4 +
+        return (size_t)(3 * R + 8 + align4(R * (R - 1) / 2 + 8)) * 4 +
                (size_t)reg_q_cap * sizeof(Proposal);
     };
     const int reg_grid = 256 * 32;
+    // prepare: one thread per point with max_rows ids of LDS each
+    int prep_threads = (int)(65536 / ((size_t)(max_rows | 1) * 4)) / EF_WAVE * EF_WAVE;
+    prep_threads = prep_threads > kBlock ? kBlock : (prep_threads < EF_WAVE ? EF_WAVE : prep_threads);
+    const size_t prep_lds = (size_t)prep_threads * (max_rows | 1) * 4;
     // filter margins: Gram-form rounding error <= (2*dpad + 4) u (|a|^2 + |b|^2), u = 2^-24,
     // doubled; the fixed-order distance is within (d/16 + 8) u of the true one, doubled twice
     const float margin_rel = (float)((4.0 * dpad + 16.0) * 5.9604644775390625e-08);
@@ -1206,16 +1175,16 @@ extern "C" int efanna_nndescent(const float *X, int64_t n, int32_t d, int32_t k,
             reverse_overflow_kernel<<<grid_for((size_t)n * K, kBlock), kBlock, 0, st>>>(
                 ovf, w.overflow_rows, (int)n, K, w.rnew, w.rold, L);
         }
-        classify_kernel<<<grid_for((size_t)n, kBlock), kBlock, 0, st>>>(
-            w.nw_c, w.od_c, w.rnew_c, w.rold_c, (int)n, L, rows0, rows1, w.work, w.work_count,
-            w.cnt_evals, w.cnt_upd, w.cnt_rows);
+        prepare_kernel<<<grid_for((size_t)n, prep_threads), prep_threads, prep_lds, st>>>(
+            w.nw, w.od, w.nw_c, w.od_c, w.rnew, w.rold, w.rnew_c, w.rold_c, (int)n, K, L, max_rows, rows0,
+            rows1, w.ulist, w.ucount, w.work, w.work_count, w.cnt_evals, w.cnt_upd, w.cnt_rows);
         if (ev) EF_HIP_CHECK(hipEventRecord(ev[3 * it + 1], st));
         if (reg_ok) {
 #define EF_JOIN_REG(NB, ONE, LIST)                                                                 \
     join_reg_kernel<NB, ONE><<<reg_grid, EF_WAVE, reg_lds(16 * NB), st>>>(                         \
-        X, w.norms, d, K, L, w.work + (size_t)(LIST) * n, w.work_count + (LIST), tab_size,         \
-        tab_shift, reg_q_cap, margin_rel, thr_scale, w.nw, w.od, w.rnew, w.rold, graph, w.worst,   \
-        w.cnt_evals, (u64 *)(w.work_count + 4), w.cnt_rows)
+        X, w.norms, d, K, w.work + (size_t)(LIST) * n, w.work_count + (LIST), reg_q_cap,           \
+        margin_rel, thr_scale, w.ulist, w.ucount, max_rows, graph, w.worst,                        \
+        (u64 *)(w.work_count + 4))
             if (d <= 128) EF_JOIN_REG(1, true, 0);
             else EF_JOIN_REG(1, false, 0);
             if (max_rows > 16) {
@@ -1226,10 +1195,9 @@ extern "C" int efanna_nndescent(const float *X, int64_t n, int32_t d, int32_t k,
         }
         if (max_rows > rows1)
             join_kernel<<<large.grid, large.threads, large.lds, st>>>(
-                X, w.norms, d, dpad, stride, q4_magic_for(d), K, L, w.work + 2 * (size_t)n,
-                w.work_count + 2, large.cap_rows, tab_size, tab_shift, large.s_cap, large.q_cap,
-                margin_rel, thr_scale, w.nw, w.od, w.rnew, w.rold, graph, w.worst, w.cnt_evals,
-                w.cnt_upd, w.cnt_rows);
+                X, w.norms, d, dpad, stride, q4_magic_for(d), K, w.work + 2 * (size_t)n,
+                w.work_count + 2, large.cap_rows, large.s_cap, large.q_cap, margin_rel, thr_scale,
+                w.ulist, w.ucount, max_rows, graph, w.worst, w.cnt_upd);
         if (ev) EF_HIP_CHECK(hipEventRecord(ev[3 * it + 2], st));
         if (stats)
             stats_kernel<<<256, kBlock, 0, st>>>(w.cnt_evals, w.cnt_upd, w.cnt_rows, (int)n,
