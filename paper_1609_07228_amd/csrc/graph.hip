@@ -330,15 +330,16 @@ sample_kernel(u64 *graph, int n, int K, int L, u64 key_new, u64 key_old, int *__
     }
 }
 
-// one thread per (row, parked key)
+// one thread per (row, parked key): thread t serves key t % 2^kp_log of row t >> kp_log
 __global__ void reverse_overflow_kernel(const Overflow *__restrict__ overflow,
                                         const int *__restrict__ overflow_rows, int n, int K,
-                                        u64 *rnew, u64 *rold, int L)
+                                        int kp_log, u64 *rnew, u64 *rold, int L)
 {
     const size_t t = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
-    const int i = (int)(t / (size_t)K), j = (int)(t - (size_t)i * K);
-    if (i >= n || j >= overflow_rows[i]) return;
-    const Overflow ov = overflow[(size_t)i * K + j];
+    const size_t i = t >> kp_log;
+    const int j = (int)(t & ((1u << kp_log) - 1));
+    if (i >= (size_t)n || j >= overflow_rows[i]) return;
+    const Overflow ov = overflow[i * K + j];
     u64 nm;
     ef_bounded_insert((ov.which ? rold : rnew) + (size_t)ov.target * L, L, ov.key, 0, &nm);
 }
@@ -670,13 +671,21 @@ join_reg_kernel(const float *__restrict__ X, const float *__restrict__ norms, in
             for (int h = 0; h < 2; ++h) acc[q][h] = (floatx4){0.f, 0.f, 0.f, 0.f};
         float4 va[8], vb[NB > 1 ? 8 : 1];
         for (int c0 = 0; c0 < d; c0 += 128) {
+            if (c0 + 128 <= d) {     // a whole 128-coordinate piece: no per-load bounds test
 #pragma unroll
-            for (int s = 0; s < 8; ++s) {
-                const int j = c0 + 16 * s + 4 * g;
-                const bool in = j + 3 < d;                 // d % 4 == 0: a piece is in or out
-                va[s] = in ? *reinterpret_cast<const float4 *>(pa + c0 + 16 * s) : make_float4(0.f, 0.f, 0.f, 0.f);
-                if (NB > 1)
-                    vb[NB > 1 ? s : 0] = in ? *reinterpret_cast<const float4 *>(pb + c0 + 16 * s) : make_float4(0.f, 0.f, 0.f, 0.f);
+                for (int s = 0; s < 8; ++s) {
+                    va[s] = *reinterpret_cast<const float4 *>(pa + c0 + 16 * s);
+                    if (NB > 1) vb[NB > 1 ? s : 0] = *reinterpret_cast<const float4 *>(pb + c0 + 16 * s);
+                }
+            } else {
+#pragma unroll
+                for (int s = 0; s < 8; ++s) {
+                    const int j = c0 + 16 * s + 4 * g;
+                    const bool in = j + 3 < d;                 // d % 4 == 0: a piece is in or out
+                    va[s] = in ? *reinterpret_cast<const float4 *>(pa + c0 + 16 * s) : make_float4(0.f, 0.f, 0.f, 0.f);
+                    if (NB > 1)
+                        vb[NB > 1 ? s : 0] = in ? *reinterpret_cast<const float4 *>(pb + c0 + 16 * s) : make_float4(0.f, 0.f, 0.f, 0.f);
+                }
             }
 #pragma unroll
             for (int s = 0; s < 8; ++s) {
@@ -1172,8 +1181,10 @@ extern "C" int efanna_nndescent(const float *X, int64_t n, int32_t d, int32_t k,
             else if (K <= 64) EF_SAMPLE(64, 1);
             else EF_SAMPLE(64, 2);
 #undef EF_SAMPLE
-            reverse_overflow_kernel<<<grid_for((size_t)n * K, kBlock), kBlock, 0, st>>>(
-                ovf, w.overflow_rows, (int)n, K, w.rnew, w.rold, L);
+            int kp_log = 0;
+            while ((1 << kp_log) < K) ++kp_log;
+            reverse_overflow_kernel<<<grid_for((size_t)n << kp_log, kBlock), kBlock, 0, st>>>(
+                ovf, w.overflow_rows, (int)n, K, kp_log, w.rnew, w.rold, L);
         }
         prepare_kernel<<<grid_for((size_t)n, prep_threads), prep_threads, prep_lds, st>>>(
             w.nw, w.od, w.nw_c, w.od_c, w.rnew, w.rold, w.rnew_c, w.rold_c, (int)n, K, L, max_rows, rows0,
