@@ -123,12 +123,13 @@ int efanna_init_graph(const float *X, int64_t n, int32_t d, const int32_t *perm,
  *          number of iterations already done as first_iter so that the hash stream
  *          continues (k calls of one iteration equal one call of k iterations).
  * stats    [device] out or NULL: iters*4 uint64 per iteration: {distance evaluations,
- *          accepted list insertions, vectors gathered by the joins, 0}.  The first and
- *          third are deterministic; the second counts insertions that may be displaced
- *          later in the same iteration.
- * phase_ms [host] out or NULL: iters*2 float: milliseconds of {sampling + reverse
- *          lists, local join} per iteration, from HIP events on `stream`.  When given,
- *          the call synchronises the stream before returning.
+ *          accepted list insertions, vectors gathered by all joins, vectors gathered by
+ *          the joins of at most 16 vectors}.  All but the second are deterministic; the
+ *          second counts insertions that may be displaced later in the same iteration.
+ * phase_ms [host] out or NULL: iters*4 float: milliseconds of {sampling + reverse lists
+ *          + join lists, joins of at most 16 vectors, joins of 17..32 vectors, larger
+ *          joins} per iteration, from HIP events on `stream`.  When given, the call
+ *          synchronises the stream before returning.
  * Asynchronous on `stream` otherwise.  Limits: k <= EFANNA_MAX_K, sample_L <= EFANNA_MAX_SAMPLE,
  * if k + 2*sample_L > 32 (or rows are not 16-byte aligned), k + 2*sample_L rows of d floats
  * must fit the 160 KB LDS.

@@ -420,6 +420,9 @@ __global__ void prepare_kernel(const int *__restrict__ nw, const int *__restrict
         base = __shfl(base, leader, EF_WAVE);
         if (cls == c) work[(size_t)c * n + base + __popcll(mask & ((1ULL << lane) - 1))] = i;
     }
+    // vectors gathered by the joins of the first list (for the bandwidth accounting)
+    const int rows0_here = ef_wave_sum_i32(cls == 0 ? m : 0);
+    if (lane == 0 && rows0_here) atomicAdd((u64 *)(work_count + 6), (u64)rows0_here);
 }
 
 // ---------------------------------------------------------------------------------------
@@ -877,7 +880,10 @@ __global__ void norms_kernel(const float *__restrict__ X, int n, int d, float *_
 __global__ void stats_kernel(const int *__restrict__ cnt_evals, const int *__restrict__ cnt_upd,
                              const int *__restrict__ cnt_rows, int n, const u64 *upd_total, u64 *stats)
 {
-    if (blockIdx.x == 0 && threadIdx.x == 0) atomicAdd(stats + 1, *upd_total);
+    if (blockIdx.x == 0 && threadIdx.x == 0) {
+        atomicAdd(stats + 1, upd_total[0]);
+        atomicAdd(stats + 3, upd_total[1]);     // vectors gathered by the first work list
+    }
     long long ev = 0, up = 0, rw = 0;
     for (int i = blockIdx.x * blockDim.x + threadIdx.x; i < n; i += gridDim.x * blockDim.x) {
         ev += cnt_evals[i];
@@ -993,7 +999,7 @@ NndWs carve_nnd(void *ws, int64_t n, int K, int L)
     w.cnt_upd = (int *)take((size_t)n * 4);
     w.cnt_rows = (int *)take((size_t)n * 4);
     w.work = (int *)take((size_t)n * 3 * 4);
-    w.work_count = (int *)take(8 * 4);     // [0..2] list sizes, [4..5] accepted insertions (u64)
+    w.work_count = (int *)take(8 * 4);     // [0..2] list sizes, [4..5] accepted insertions, [6..7] rows of list 0 (u64)
     w.rnew_c = (int *)take((size_t)n * 4);
     w.rold_c = (int *)take((size_t)n * 4);
     w.overflow = take((size_t)n * K * 16);
@@ -1161,12 +1167,12 @@ extern "C" int efanna_nndescent(const float *X, int64_t n, int32_t d, int32_t k,
     // optional phase timing: events around the sampling and the join of every iteration
     hipEvent_t *ev = nullptr;
     if (phase_ms && iters > 0) {
-        ev = new hipEvent_t[(size_t)iters * 3];
-        for (int e = 0; e < iters * 3; ++e) EF_HIP_CHECK(hipEventCreate(&ev[e]));
+        ev = new hipEvent_t[(size_t)iters * 5];
+        for (int e = 0; e < iters * 5; ++e) EF_HIP_CHECK(hipEventCreate(&ev[e]));
     }
     for (int it = 0; it < iters; ++it) {
         const int g = first_iter + it;
-        if (ev) EF_HIP_CHECK(hipEventRecord(ev[3 * it], st));
+        if (ev) EF_HIP_CHECK(hipEventRecord(ev[5 * it], st));
         fill_reverse_kernel<<<grid_for((size_t)n * L, kBlock), kBlock, 0, st>>>(
             w.rnew, w.rold, (size_t)n * L, L, w.rnew_c, w.rold_c, (size_t)n, w.work_count);
         {
@@ -1189,7 +1195,7 @@ extern "C" int efanna_nndescent(const float *X, int64_t n, int32_t d, int32_t k,
         prepare_kernel<<<grid_for((size_t)n, prep_threads), prep_threads, prep_lds, st>>>(
             w.nw, w.od, w.nw_c, w.od_c, w.rnew, w.rold, w.rnew_c, w.rold_c, (int)n, K, L, max_rows, rows0,
             rows1, w.ulist, w.ucount, w.work, w.work_count, w.cnt_evals, w.cnt_upd, w.cnt_rows);
-        if (ev) EF_HIP_CHECK(hipEventRecord(ev[3 * it + 1], st));
+        if (ev) EF_HIP_CHECK(hipEventRecord(ev[5 * it + 1], st));
         if (reg_ok) {
 #define EF_JOIN_REG(NB, ONE, LIST)                                                                 \
     join_reg_kernel<NB, ONE><<<reg_grid, EF_WAVE, reg_lds(16 * NB), st>>>(                         \
@@ -1198,18 +1204,22 @@ extern "C" int efanna_nndescent(const float *X, int64_t n, int32_t d, int32_t k,
         (u64 *)(w.work_count + 4))
             if (d <= 128) EF_JOIN_REG(1, true, 0);
             else EF_JOIN_REG(1, false, 0);
+            if (ev) EF_HIP_CHECK(hipEventRecord(ev[5 * it + 2], st));
             if (max_rows > 16) {
                 if (d <= 128) EF_JOIN_REG(2, true, 1);
                 else EF_JOIN_REG(2, false, 1);
             }
 #undef EF_JOIN_REG
+        } else if (ev) {
+            EF_HIP_CHECK(hipEventRecord(ev[5 * it + 2], st));
         }
+        if (ev) EF_HIP_CHECK(hipEventRecord(ev[5 * it + 3], st));
         if (max_rows > rows1)
             join_kernel<<<large.grid, large.threads, large.lds, st>>>(
                 X, w.norms, d, dpad, stride, q4_magic_for(d), K, w.work + 2 * (size_t)n,
                 w.work_count + 2, large.cap_rows, large.s_cap, large.q_cap, margin_rel, thr_scale,
                 w.ulist, w.ucount, max_rows, graph, w.worst, w.cnt_upd);
-        if (ev) EF_HIP_CHECK(hipEventRecord(ev[3 * it + 2], st));
+        if (ev) EF_HIP_CHECK(hipEventRecord(ev[5 * it + 4], st));
         if (stats)
             stats_kernel<<<256, kBlock, 0, st>>>(w.cnt_evals, w.cnt_upd, w.cnt_rows, (int)n,
                                                  (const u64 *)(w.work_count + 4), stats + 4 * it);
@@ -1218,10 +1228,10 @@ extern "C" int efanna_nndescent(const float *X, int64_t n, int32_t d, int32_t k,
     if (ev) {
         EF_HIP_CHECK(hipStreamSynchronize(st));
         for (int it = 0; it < iters; ++it) {
-            EF_HIP_CHECK(hipEventElapsedTime(&phase_ms[2 * it], ev[3 * it], ev[3 * it + 1]));
-            EF_HIP_CHECK(hipEventElapsedTime(&phase_ms[2 * it + 1], ev[3 * it + 1], ev[3 * it + 2]));
+            for (int ph = 0; ph < 4; ++ph)
+                EF_HIP_CHECK(hipEventElapsedTime(&phase_ms[4 * it + ph], ev[5 * it + ph], ev[5 * it + ph + 1]));
         }
-        for (int e = 0; e < iters * 3; ++e) (void)hipEventDestroy(ev[e]);
+        for (int e = 0; e < iters * 5; ++e) (void)hipEventDestroy(ev[e]);
         delete[] ev;
     }
     return EFANNA_OK;

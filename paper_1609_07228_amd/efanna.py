@@ -133,9 +133,10 @@ def efanna_nndescent(X: torch.Tensor, graph: torch.Tensor, iters: int, sample_L:
                      first_iter: int = 0, stats: torch.Tensor | None = None,
                      workspace: torch.Tensor | None = None, phase_ms: np.ndarray | None = None):
     """Alg. 4, in place on `graph`.  Returns stats [iters,4] (int64 device tensor:
-    distance evaluations, accepted insertions, vectors gathered, 0).  `phase_ms`, if
-    given, is a float32 numpy array [iters,2] that receives (sampling, join) times and
-    makes the call synchronise."""
+    distance evaluations, accepted insertions, vectors gathered, vectors gathered by the
+    joins of at most 16 vectors).  `phase_ms`, if given, is a float32 numpy array
+    [iters,4] that receives (sampling, small / medium / large joins) times and makes the
+    call synchronise."""
     X = _dev(X, torch.float32)
     n, d = X.shape
     graph = _dev(graph, torch.int64)
@@ -143,7 +144,7 @@ def efanna_nndescent(X: torch.Tensor, graph: torch.Tensor, iters: int, sample_L:
     if stats is None:
         stats = torch.zeros((max(iters, 1), 4), dtype=torch.int64, device=X.device)
     if phase_ms is not None:
-        assert phase_ms.dtype == np.float32 and phase_ms.size >= 2 * iters and phase_ms.flags.c_contiguous
+        assert phase_ms.dtype == np.float32 and phase_ms.size >= 4 * iters and phase_ms.flags.c_contiguous
     need = lib().efanna_nndescent_workspace_bytes(n, k, sample_L)
     ws = _workspace(need, X.device) if workspace is None else workspace
     _check(lib().efanna_nndescent(X.data_ptr(), n, d, k, graph.data_ptr(), iters, sample_L, seed,
