@@ -12,6 +12,7 @@
 namespace {
 
 constexpr int kBlock = 256;
+constexpr int kRegGrid = 256 * 32;     // blocks of the register-operand join kernels
 constexpr int kRowPad = 4;   // floats appended to each LDS row
 
 inline size_t align_up(size_t x) { return (x + 255) & ~(size_t)255; }
@@ -27,7 +28,7 @@ __global__ void fill_reverse_kernel(u64 *a, u64 *b, size_t total, int L, int *a_
                                     size_t n, int *work_count)
 {
     size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (i < 8) work_count[i] = 0;     // three work lists, insertion counter
+    if (i < 8) work_count[i] = 0;     // three work lists
     if (i < n) {
         a_count[i] = 0;
         b_count[i] = 0;
@@ -285,7 +286,7 @@ sample_kernel(u64 *graph, int n, int K, int L, u64 key_new, u64 key_old, int *__
     }
     int n_old = 0, n_parked = 0;     // parked keys of row i go to overflow[i*K ...], in group order
     const int group_shift = (int)(threadIdx.x & (EF_WAVE - 1) & ~(G - 1));
-    const u64 group_bits = G == 64 ? ~0ULL : ((1ULL << G) - 1);
+    const u64 group_bits = ~0ULL >> (64 - G);
 #pragma unroll
     for (int h = 0; h < E; ++h) {
         const int slot = gl + h * G;
@@ -356,7 +357,7 @@ __global__ void prepare_kernel(const int *__restrict__ nw, const int *__restrict
                                const int *__restrict__ nw_c, const int *__restrict__ od_c,
                                const u64 *__restrict__ rnew, const u64 *__restrict__ rold,
                                const int *__restrict__ rnew_c, const int *__restrict__ rold_c,
-                               int n, int K, int L, int cap, int rows0, int rows1,
+                               int n, int K, int L, int cap, u32 cap_magic, int rows0, int rows1,
                                int *__restrict__ ulist, int2 *__restrict__ ucount,
                                int *__restrict__ work, int *__restrict__ work_count,
                                int *__restrict__ cnt_evals, int *__restrict__ cnt_upd,
@@ -406,23 +407,32 @@ __global__ void prepare_kernel(const int *__restrict__ nw, const int *__restrict
     // coalesced write-out of the block's lists
     const int first = blockIdx.x * blockDim.x, rows_here = min((int)blockDim.x, n - first);
     for (int f = threadIdx.x; f < rows_here * cap; f += blockDim.x) {
-        const int r = f / cap, c = f - r * cap;
+        const int r = (int)(((u64)(u32)f * cap_magic) >> 32), c = f - r * cap;
         ulist[(size_t)first * cap + f] = ids_sh[r * pitch + c];
     }
-    const int lane = ef_lane();
+    // append to the work lists: ranks inside the block first, then one counter bump per
+    // list and block (bumps of one address serialise at about 11 ns each)
+    __shared__ int wave_cnt[3][kBlock / EF_WAVE], block_base[3];
+    const int lane = ef_lane(), wave = threadIdx.x / EF_WAVE, n_waves = blockDim.x / EF_WAVE;
+    int rank = 0;
 #pragma unroll
     for (int c = 0; c < 3; ++c) {
         const u64 mask = __ballot(cls == c);
-        if (mask == 0) continue;
-        int base = 0;
-        const int leader = __ffsll((long long)mask) - 1;
-        if (lane == leader) base = atomicAdd(&work_count[c], __popcll(mask));
-        base = __shfl(base, leader, EF_WAVE);
-        if (cls == c) work[(size_t)c * n + base + __popcll(mask & ((1ULL << lane) - 1))] = i;
+        if (cls == c) rank = __popcll(mask & ((1ULL << lane) - 1));
+        if (lane == 0) wave_cnt[c][wave] = __popcll(mask);
     }
-    // vectors gathered by the joins of the first list (for the bandwidth accounting)
-    const int rows0_here = ef_wave_sum_i32(cls == 0 ? m : 0);
-    if (lane == 0 && rows0_here) atomicAdd((u64 *)(work_count + 6), (u64)rows0_here);
+    __syncthreads();
+    if (threadIdx.x < 3) {
+        int tot = 0;
+        for (int v = 0; v < n_waves; ++v) tot += wave_cnt[threadIdx.x][v];
+        block_base[threadIdx.x] = tot ? atomicAdd(&work_count[threadIdx.x], tot) : 0;
+    }
+    __syncthreads();
+    if (cls >= 0) {
+        int off = block_base[cls] + rank;
+        for (int v = 0; v < wave; ++v) off += wave_cnt[cls][v];
+        work[(size_t)cls * n + off] = i;
+    }
 }
 
 // ---------------------------------------------------------------------------------------
@@ -622,7 +632,7 @@ join_reg_kernel(const float *__restrict__ X, const float *__restrict__ norms, in
                 const int *__restrict__ work, const int *__restrict__ work_count, int q_cap,
                 float margin_rel, float thr_scale, const int *__restrict__ ulist,
                 const int2 *__restrict__ ucount, int ucap, u64 *graph, u32 *worst,
-                u64 *__restrict__ upd_total)
+                int *__restrict__ upd_block)
 {
     constexpr int R = 16 * NB;                    // rows
     constexpr int S_CAP = R * (R - 1) / 2 + 8;    // every pair may survive
@@ -861,7 +871,7 @@ join_reg_kernel(const float *__restrict__ X, const float *__restrict__ norms, in
     __syncthreads();
     updates += drain_queue(queue, meta[3], graph, worst, K, lane, EF_WAVE);
     updates = ef_wave_sum_i32(updates);
-    if (lane == 0 && updates) atomicAdd(upd_total, (u64)updates);
+    if (lane == 0) upd_block[blockIdx.x] = updates;
 }
 
 // squared norms in float32 (only the join's filter uses them; any summation order will do)
@@ -878,25 +888,28 @@ __global__ void norms_kernel(const float *__restrict__ X, int n, int d, float *_
 }
 
 __global__ void stats_kernel(const int *__restrict__ cnt_evals, const int *__restrict__ cnt_upd,
-                             const int *__restrict__ cnt_rows, int n, const u64 *upd_total, u64 *stats)
+                             const int *__restrict__ cnt_rows, int n, int rows0,
+                             const int *__restrict__ upd_block, int n_upd_block, u64 *stats)
 {
-    if (blockIdx.x == 0 && threadIdx.x == 0) {
-        atomicAdd(stats + 1, upd_total[0]);
-        atomicAdd(stats + 3, upd_total[1]);     // vectors gathered by the first work list
-    }
-    long long ev = 0, up = 0, rw = 0;
-    for (int i = blockIdx.x * blockDim.x + threadIdx.x; i < n; i += gridDim.x * blockDim.x) {
+    long long ev = 0, up = 0, rw = 0, r0 = 0;
+    const int t = blockIdx.x * blockDim.x + threadIdx.x, nt = gridDim.x * blockDim.x;
+    for (int i = t; i < n; i += nt) {
         ev += cnt_evals[i];
         up += cnt_upd[i];
-        rw += cnt_rows[i];
+        const int rows = cnt_rows[i];
+        rw += rows;
+        r0 += rows <= rows0 ? rows : 0;
     }
+    for (int b = t; b < n_upd_block; b += nt) up += upd_block[b];   // joins that count per block
     ev = ef_wave_sum_i64(ev);
     up = ef_wave_sum_i64(up);
     rw = ef_wave_sum_i64(rw);
+    r0 = ef_wave_sum_i64(r0);
     if (ef_lane() == 0) {
         atomicAdd(stats, (u64)ev);
         atomicAdd(stats + 1, (u64)up);
         atomicAdd(stats + 2, (u64)rw);
+        atomicAdd(stats + 3, (u64)r0);
     }
 }
 
@@ -972,7 +985,7 @@ __global__ void pair_distances_kernel(const float *__restrict__ X, int d,
 }
 
 struct NndWs {
-    int *nw, *od, *nw_c, *od_c, *cnt_evals, *cnt_upd, *cnt_rows, *work, *work_count, *rnew_c, *rold_c, *overflow_rows, *ulist;
+    int *nw, *od, *nw_c, *od_c, *cnt_evals, *cnt_upd, *cnt_rows, *work, *work_count, *rnew_c, *rold_c, *overflow_rows, *ulist, *upd_block;
     int2 *ucount;
     void *overflow;
     u64 *rnew, *rold;
@@ -999,13 +1012,14 @@ NndWs carve_nnd(void *ws, int64_t n, int K, int L)
     w.cnt_upd = (int *)take((size_t)n * 4);
     w.cnt_rows = (int *)take((size_t)n * 4);
     w.work = (int *)take((size_t)n * 3 * 4);
-    w.work_count = (int *)take(8 * 4);     // [0..2] list sizes, [4..5] accepted insertions, [6..7] rows of list 0 (u64)
+    w.work_count = (int *)take(8 * 4);     // [0..2] list sizes
     w.rnew_c = (int *)take((size_t)n * 4);
     w.rold_c = (int *)take((size_t)n * 4);
     w.overflow = take((size_t)n * K * 16);
     w.overflow_rows = (int *)take((size_t)n * 4);
     w.ulist = (int *)take((size_t)n * (K + 2 * L) * 4);
     w.ucount = (int2 *)take((size_t)n * 8);
+    w.upd_block = (int *)take((size_t)2 * kRegGrid * 4);
     w.rnew = (u64 *)take((size_t)n * L * 8);
     w.rold = (u64 *)take((size_t)n * L * 8);
     w.worst = (u32 *)take((size_t)n * 4);
@@ -1148,7 +1162,7 @@ extern "C" int efanna_nndescent(const float *X, int64_t n, int32_t d, int32_t k,
         return (size_t)(3 * R + 8 + align4(R * (R - 1) / 2 + 8)) * 4 +
                (size_t)reg_q_cap * sizeof(Proposal);
     };
-    const int reg_grid = 256 * 32;
+    const int reg_grid = kRegGrid;
     // prepare: one thread per point with max_rows ids of LDS each
     int prep_threads = (int)(65536 / ((size_t)(max_rows | 1) * 4)) / EF_WAVE * EF_WAVE;
     prep_threads = prep_threads > kBlock ? kBlock : (prep_threads < EF_WAVE ? EF_WAVE : prep_threads);
@@ -1193,15 +1207,15 @@ extern "C" int efanna_nndescent(const float *X, int64_t n, int32_t d, int32_t k,
                 ovf, w.overflow_rows, (int)n, K, kp_log, w.rnew, w.rold, L);
         }
         prepare_kernel<<<grid_for((size_t)n, prep_threads), prep_threads, prep_lds, st>>>(
-            w.nw, w.od, w.nw_c, w.od_c, w.rnew, w.rold, w.rnew_c, w.rold_c, (int)n, K, L, max_rows, rows0,
-            rows1, w.ulist, w.ucount, w.work, w.work_count, w.cnt_evals, w.cnt_upd, w.cnt_rows);
+            w.nw, w.od, w.nw_c, w.od_c, w.rnew, w.rold, w.rnew_c, w.rold_c, (int)n, K, L, max_rows,
+            (u32)(((1ULL << 32) + max_rows - 1) / max_rows), rows0, rows1, w.ulist, w.ucount, w.work, w.work_count, w.cnt_evals, w.cnt_upd, w.cnt_rows);
         if (ev) EF_HIP_CHECK(hipEventRecord(ev[5 * it + 1], st));
         if (reg_ok) {
 #define EF_JOIN_REG(NB, ONE, LIST)                                                                 \
     join_reg_kernel<NB, ONE><<<reg_grid, EF_WAVE, reg_lds(16 * NB), st>>>(                         \
         X, w.norms, d, K, w.work + (size_t)(LIST) * n, w.work_count + (LIST), reg_q_cap,           \
         margin_rel, thr_scale, w.ulist, w.ucount, max_rows, graph, w.worst,                        \
-        (u64 *)(w.work_count + 4))
+        w.upd_block + (LIST) * reg_grid)
             if (d <= 128) EF_JOIN_REG(1, true, 0);
             else EF_JOIN_REG(1, false, 0);
             if (ev) EF_HIP_CHECK(hipEventRecord(ev[5 * it + 2], st));
@@ -1221,8 +1235,9 @@ extern "C" int efanna_nndescent(const float *X, int64_t n, int32_t d, int32_t k,
                 w.ulist, w.ucount, max_rows, graph, w.worst, w.cnt_upd);
         if (ev) EF_HIP_CHECK(hipEventRecord(ev[5 * it + 4], st));
         if (stats)
-            stats_kernel<<<256, kBlock, 0, st>>>(w.cnt_evals, w.cnt_upd, w.cnt_rows, (int)n,
-                                                 (const u64 *)(w.work_count + 4), stats + 4 * it);
+            stats_kernel<<<256, kBlock, 0, st>>>(w.cnt_evals, w.cnt_upd, w.cnt_rows, (int)n, rows0,
+                                                 w.upd_block, reg_ok ? (max_rows > 16 ? 2 : 1) * reg_grid : 0,
+                                                 stats + 4 * it);
     }
     EF_HIP_CHECK(hipGetLastError());
     if (ev) {
