@@ -3,6 +3,8 @@
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
+#include <stdio.h>
+#include <stdlib.h>
 
 #include "../../include/efanna.h"
 
@@ -12,10 +14,17 @@ typedef unsigned int u32;
 #define EF_WAVE 64
 #define EF_INF_BITS 0x7F800000u
 
-#define EF_HIP_CHECK(expr)                         \
-    do {                                           \
-        hipError_t e_ = (expr);                    \
-        if (e_ != hipSuccess) return EFANNA_EHIP;  \
+// a failed HIP call ends the entry point with EFANNA_EHIP; with EFANNA_DEBUG set in the
+// environment the call and the runtime's message are printed to stderr first
+#define EF_HIP_CHECK(expr)                                                                     \
+    do {                                                                                       \
+        hipError_t e_ = (expr);                                                                \
+        if (e_ != hipSuccess) {                                                                \
+            if (getenv("EFANNA_DEBUG"))                                                        \
+                fprintf(stderr, "efanna: %s:%d: %s -> %s\n", __FILE__, __LINE__, #expr,        \
+                        hipGetErrorString(e_));                                                \
+            return EFANNA_EHIP;                                                                \
+        }                                                                                      \
     } while (0)
 
 // ---- counter-based generator (SplitMix64 finaliser) ---------------------------------

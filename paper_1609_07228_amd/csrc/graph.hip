@@ -138,7 +138,7 @@ init_tree_kernel(const float *__restrict__ X, int d, int stride, u32 q4_magic, i
                  const int *__restrict__ perm_t, const int *__restrict__ leaf_off_t, int K,
                  u64 *graph, int first_tree)
 {
-    extern __shared__ float smem[];
+    extern __shared__ __align__(16) float smem[];
     float *rows = smem;                                   // [S][stride]
     float *dmat = smem + align4(S * stride);              // [S][S] pairwise distances
     u64 *pools = (u64 *)(dmat + align4(S * S));           // [S][K] rows being merged, ascending
@@ -489,7 +489,7 @@ __global__ void join_kernel(const float *__restrict__ X, const float *__restrict
                             const int *__restrict__ ulist, const int2 *__restrict__ ucount,
                             int ucap, u64 *graph, u32 *worst, int *__restrict__ cnt_upd)
 {
-    extern __shared__ float smem[];
+    extern __shared__ __align__(16) float smem[];
     const JoinLds lds = join_lds_carve(smem, cap_rows, stride, s_cap);
     const int tid = threadIdx.x, nthr = blockDim.x;
     const int lane = tid & (EF_WAVE - 1), wave = tid / EF_WAVE, n_waves = nthr / EF_WAVE;
@@ -636,7 +636,7 @@ join_reg_kernel(const float *__restrict__ X, const float *__restrict__ norms, in
 {
     constexpr int R = 16 * NB;                    // rows
     constexpr int S_CAP = R * (R - 1) / 2 + 8;    // every pair may survive
-    extern __shared__ float smem[];
+    extern __shared__ __align__(16) float smem[];
     int *uid = (int *)smem;                       // [R]
     u32 *thr = (u32 *)(uid + R);                  // [R]
     float *nrm = (float *)(thr + R);              // [R]

@@ -36,7 +36,23 @@ struct Node {
 struct Counters {
     int next_nodes;
     int bad_input;
+    int small_nodes;
 };
+
+// A node small enough to be finished inside one workgroup (finish_kernel).
+struct SmallNode {
+    int b, e;
+    u64 heap;
+    int depth, pad;
+};
+
+constexpr int kFinMax = 2048;      // largest segment finish_kernel takes
+constexpr int kFinNodes = 256;     // nodes of one level inside such a segment
+inline int finish_limit(int S)
+{
+    long f = (long)kFinNodes * (S + 1);     // so that a level never has more than kFinNodes live nodes
+    return f < kFinMax ? (int)f : kFinMax;
+}
 
 __device__ inline long long quantise(float x) { return (long long)rint((double)x * 1048576.0); }
 
@@ -53,14 +69,24 @@ __global__ void check_input_kernel(const float *__restrict__ X, size_t total, Co
 }
 
 __global__ void roots_kernel(Node *nodes, int *node_of, unsigned char *leaf_flag, int n, int T,
-                             int S, u64 seed, int d, Counters *c)
+                             int S, int fin, SmallNode *small, u64 seed, int d, Counters *c)
 {
     size_t p = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
     size_t total = (size_t)n * T;
-    const bool live = n > S;
+    const bool live = n > fin;       // otherwise the whole tree is finished in one workgroup
+    if (p < (size_t)T && !live && n > S) {
+        SmallNode sn;
+        sn.b = (int)p * n;
+        sn.e = sn.b + n;
+        sn.heap = 1;
+        sn.depth = 0;
+        sn.pad = 0;
+        small[p] = sn;
+        if (p == 0) c->small_nodes = T;
+    }
     if (p < total) {
         node_of[p] = live ? (int)(p / (size_t)n) : -1;
-        leaf_flag[p] = (!live && p % (size_t)n == 0) ? 1 : 0;
+        leaf_flag[p] = (n <= S && p % (size_t)n == 0) ? 1 : 0;
     }
     if (p < (size_t)T && live) {
         Node nd;
@@ -223,11 +249,11 @@ __global__ void scan_apply_kernel(Pred pred, size_t total, const int *block_sums
 }
 
 __global__ void children_kernel(Node *cur, int n_cur, Node *next, const int *__restrict__ lcount,
-                                unsigned char *leaf_flag, int S, u64 seed, int n, int d,
-                                Counters *c)
+                                unsigned char *leaf_flag, int S, int fin, SmallNode *small, u64 seed,
+                                int n, int d, Counters *c)
 {
     int s = blockIdx.x * blockDim.x + threadIdx.x;
-    int live[2] = {0, 0};
+    int kind[2] = {0, 0};      // 0 leaf, 1 finished later inside one workgroup, 2 next level
     Node nd;
     if (s < n_cur) {
         nd = cur[s];
@@ -240,29 +266,35 @@ __global__ void children_kernel(Node *cur, int n_cur, Node *next, const int *__r
             nd.moved = 1;
             nd.mid = nd.b + nl;
         }
-        live[0] = (nd.mid - nd.b) > S;
-        live[1] = (nd.e - nd.mid) > S;
+        const int sz[2] = {nd.mid - nd.b, nd.e - nd.mid};
+        for (int side = 0; side < 2; ++side) kind[side] = sz[side] <= S ? 0 : (sz[side] <= fin ? 1 : 2);
     }
-    // one counter bump per wave
-    int want = live[0] + live[1];
-    int inc = ef_wave_scan_i32(want);
-    int wave_total = __shfl(inc, EF_WAVE - 1, EF_WAVE);
-    int base = 0;
-    if (ef_lane() == EF_WAVE - 1 && wave_total > 0) base = atomicAdd(&c->next_nodes, wave_total);
+    // one counter bump per wave and list
+    const int want = (kind[0] == 2) + (kind[1] == 2), want_s = (kind[0] == 1) + (kind[1] == 1);
+    const int inc = ef_wave_scan_i32(want), inc_s = ef_wave_scan_i32(want_s);
+    const int wave_total = __shfl(inc, EF_WAVE - 1, EF_WAVE), wave_total_s = __shfl(inc_s, EF_WAVE - 1, EF_WAVE);
+    int base = 0, base_s = 0;
+    if (ef_lane() == EF_WAVE - 1) {
+        if (wave_total > 0) base = atomicAdd(&c->next_nodes, wave_total);
+        if (wave_total_s > 0) base_s = atomicAdd(&c->small_nodes, wave_total_s);
+    }
     base = __shfl(base, EF_WAVE - 1, EF_WAVE);
+    base_s = __shfl(base_s, EF_WAVE - 1, EF_WAVE);
     if (s >= n_cur) return;
-    int slot = base + inc - want;
+    int slot = base + inc - want, slot_s = base_s + inc_s - want_s;
     const int tree = nd.b / n;
     const u64 key = ef_stream_key(seed, tree);
     for (int side = 0; side < 2; ++side) {
         int cb = side ? nd.mid : nd.b, ce = side ? nd.e : nd.mid;
-        if (live[side]) {
+        // below depth 60 heap ids would overflow: such nodes only split positionally
+        const u64 ch_heap = nd.depth < 60 ? 2 * nd.heap + side : nd.heap;
+        nd.child[side] = -1;
+        if (kind[side] == 2) {
             Node ch;
             ch.b = cb;
             ch.e = ce;
             ch.depth = nd.depth + 1;
-            // below depth 60 heap ids would overflow: such nodes only split positionally
-            ch.heap = nd.depth < 60 ? 2 * nd.heap + side : nd.heap;
+            ch.heap = ch_heap;
             ch.dim = ch.depth < 60 ? (int)(ef_mix64(key + ch.heap) % (u64)d) : -1;
             ch.sum = 0;
             ch.mid = cb;
@@ -270,8 +302,15 @@ __global__ void children_kernel(Node *cur, int n_cur, Node *next, const int *__r
             ch.child[0] = ch.child[1] = -1;
             next[slot] = ch;
             nd.child[side] = slot++;
+        } else if (kind[side] == 1) {
+            SmallNode sn;
+            sn.b = cb;
+            sn.e = ce;
+            sn.heap = ch_heap;
+            sn.depth = nd.depth + 1;
+            sn.pad = 0;
+            small[slot_s++] = sn;
         } else {
-            nd.child[side] = -1;
             leaf_flag[cb] = 1;
         }
     }
@@ -302,6 +341,160 @@ __global__ void scatter_kernel(const int *__restrict__ perm_in, int *__restrict_
     }
     perm_out[dst] = id;
     node_out[dst] = nd.child[dst < (size_t)nd.mid ? 0 : 1];
+}
+
+// Finishes the subtree of one small node (at most kFinMax positions) inside a workgroup:
+// the same four steps per level as the device-wide kernels (integer sums, prefix sum of
+// the "goes left" predicate, children, stable scatter), but with the ids, the node table
+// and the prefix sums in LDS, so the lower half of a tree costs one launch instead of
+// half a dozen per level.
+struct LNode {
+    int b, e, mid, moved;      // local positions
+    u64 heap;
+    long long sum;
+    int dim, depth;
+    int child[2];
+};
+
+__global__ void __launch_bounds__(kBlock)
+finish_kernel(const float *__restrict__ X, int d, int *perm, const SmallNode *__restrict__ small,
+              unsigned char *leaf_flag, int S, u64 seed, int n)
+{
+    // One 16-byte aligned LDS block carved by hand (no separate static LDS variables, whose
+    // size would shift the 8-byte node records off their alignment).
+    extern __shared__ __align__(16) int fsm[];
+    int *const ids_base = fsm, *const nidx_base = fsm + 2 * kFinMax;      // [2][kFinMax] each
+    float *val = (float *)(fsm + 4 * kFinMax);
+    int *lcnt = fsm + 5 * kFinMax;                                 // [kFinMax + 1]
+    int *wave_tot = fsm + 6 * kFinMax + 4;                         // [kBlock / EF_WAVE]
+    int &n_next_sh = fsm[6 * kFinMax + 2];
+    LNode *const tabs_base = (LNode *)(fsm + 6 * kFinMax + 8);     // [2][kFinNodes], 8-byte aligned
+    const SmallNode seg = small[blockIdx.x];
+    const int cnt = seg.e - seg.b, tid = threadIdx.x;
+    const u64 key = ef_stream_key(seed, seg.b / n);
+    for (int p = tid; p < cnt; p += kBlock) {
+        ids_base[p] = perm[seg.b + p];
+        nidx_base[p] = 0;
+    }
+    if (tid == 0) {
+        LNode r;
+        r.b = 0;
+        r.e = cnt;
+        r.mid = 0;
+        r.moved = 0;
+        r.heap = seg.heap;
+        r.sum = 0;
+        r.depth = seg.depth;
+        r.dim = seg.depth < 60 ? (int)(ef_mix64(key + seg.heap) % (u64)d) : -1;
+        r.child[0] = r.child[1] = -1;
+        tabs_base[0] = r;
+        n_next_sh = 0;
+    }
+    __syncthreads();
+    int cur = 0, n_cur = 1;
+    const int chunk = (cnt + kBlock - 1) / kBlock;      // consecutive positions per thread in the scan
+    while (n_cur > 0) {
+        int *idc = ids_base + cur * kFinMax, *idn = ids_base + (cur ^ 1) * kFinMax;
+        int *nc = nidx_base + cur * kFinMax, *nn = nidx_base + (cur ^ 1) * kFinMax;
+        LNode *tc = tabs_base + cur * kFinNodes, *tn = tabs_base + (cur ^ 1) * kFinNodes;
+        // 1. sums
+        for (int p = tid; p < cnt; p += kBlock) {
+            const int k = nc[p];
+            if (k >= 0 && tc[k].dim >= 0) {
+                const float x = X[(size_t)idc[p] * d + tc[k].dim];
+                val[p] = x;
+                atomicAdd((u64 *)&tc[k].sum, (u64)quantise(x));
+            }
+        }
+        __syncthreads();
+        // 2. exclusive prefix sum of the "goes left" predicate over the segment
+        {
+            const int p0 = tid * chunk, p1 = min(cnt, p0 + chunk);
+            int mine = 0;
+            for (int p = p0; p < p1; ++p) {
+                const int k = nc[p];
+                int f = 0;
+                if (k >= 0 && tc[k].dim >= 0)
+                    f = (long long)(tc[k].e - tc[k].b) * quantise(val[p]) < tc[k].sum ? 1 : 0;
+                lcnt[p] = f;
+                mine += f;
+            }
+            const int incl = ef_wave_scan_i32(mine);
+            if (ef_lane() == EF_WAVE - 1) wave_tot[tid / EF_WAVE] = incl;
+            __syncthreads();
+            int off = incl - mine;
+            for (int v = 0; v < tid / EF_WAVE; ++v) off += wave_tot[v];
+            for (int p = p0; p < p1; ++p) {
+                const int f = lcnt[p];
+                lcnt[p] = off;
+                off += f;
+            }
+            if (tid == kBlock - 1) lcnt[cnt] = off;      // the last thread's running sum is the total
+        }
+        __syncthreads();
+        // 3. children
+        for (int k = tid; k < n_cur; k += kBlock) {
+            LNode nd = tc[k];
+            const int c = nd.e - nd.b;
+            const int nl = nd.dim >= 0 ? lcnt[nd.e] - lcnt[nd.b] : 0;
+            if (nl == 0 || nl == c) {
+                nd.moved = 0;
+                nd.mid = nd.b + c / 2;
+            } else {
+                nd.moved = 1;
+                nd.mid = nd.b + nl;
+            }
+            for (int side = 0; side < 2; ++side) {
+                const int cb = side ? nd.mid : nd.b, ce = side ? nd.e : nd.mid;
+                nd.child[side] = -1;
+                if (ce - cb > S) {
+                    LNode ch;
+                    ch.b = cb;
+                    ch.e = ce;
+                    ch.mid = cb;
+                    ch.moved = 0;
+                    ch.depth = nd.depth + 1;
+                    ch.heap = nd.depth < 60 ? 2 * nd.heap + side : nd.heap;
+                    ch.dim = ch.depth < 60 ? (int)(ef_mix64(key + ch.heap) % (u64)d) : -1;
+                    ch.sum = 0;
+                    ch.child[0] = ch.child[1] = -1;
+                    const int slot = atomicAdd(&n_next_sh, 1);
+                    tn[slot] = ch;
+                    nd.child[side] = slot;
+                } else {
+                    leaf_flag[seg.b + cb] = 1;
+                }
+            }
+            tc[k] = nd;
+        }
+        __syncthreads();
+        // 4. stable scatter
+        for (int p = tid; p < cnt; p += kBlock) {
+            const int k = nc[p];
+            const int id = idc[p];
+            if (k < 0) {
+                idn[p] = id;
+                nn[p] = -1;
+                continue;
+            }
+            const LNode &nd = tc[k];
+            int dst = p;
+            if (nd.moved) {
+                const bool left = (long long)(nd.e - nd.b) * quantise(val[p]) < nd.sum;
+                const int lc = lcnt[p] - lcnt[nd.b];
+                dst = left ? nd.b + lc : nd.mid + (p - nd.b - lc);
+            }
+            idn[dst] = id;
+            nn[dst] = nd.child[dst < nd.mid ? 0 : 1];
+        }
+        __syncthreads();
+        n_cur = n_next_sh;
+        cur ^= 1;
+        __syncthreads();
+        if (tid == 0) n_next_sh = 0;
+        __syncthreads();
+    }
+    for (int p = tid; p < cnt; p += kBlock) perm[seg.b + p] = ids_base[cur * kFinMax + p];
 }
 
 __global__ void iota_kernel(int *perm, int n, size_t total)
@@ -336,6 +529,7 @@ struct TreeWs {
     float *val;
     unsigned char *leaf_flag;
     Node *nodes_a, *nodes_b;
+    SmallNode *small;
     Counters *counters;
     size_t bytes;
 };
@@ -362,6 +556,7 @@ TreeWs carve(void *ws, int64_t n, int32_t T, int32_t S)
     w.block_sums = (int *)take((nb + 1) * 4);
     w.nodes_a = (Node *)take(max_nodes * sizeof(Node));
     w.nodes_b = (Node *)take(max_nodes * sizeof(Node));
+    w.small = (SmallNode *)take(max_nodes * sizeof(SmallNode));
     w.n_leaves_dev = (int *)take((size_t)T * 4);
     w.counters = (Counters *)take(sizeof(Counters));
     w.bytes = off;
@@ -406,8 +601,9 @@ extern "C" int efanna_build_trees(const float *X, int64_t n, int32_t d, int32_t 
     EF_HIP_CHECK(hipMemsetAsync(w.counters, 0, sizeof(Counters), st));
     check_input_kernel<<<1024, kBlock, 0, st>>>(X, (size_t)n * d, w.counters);
     iota_kernel<<<grid_pos, kBlock, 0, st>>>(perm, (int)n, total);
-    roots_kernel<<<grid_pos, kBlock, 0, st>>>(w.nodes_a, w.node_a, w.leaf_flag, (int)n, T, S, seed,
-                                              d, w.counters);
+    const int fin = finish_limit(S);
+    roots_kernel<<<grid_pos, kBlock, 0, st>>>(w.nodes_a, w.node_a, w.leaf_flag, (int)n, T, S, fin,
+                                              w.small, seed, d, w.counters);
     Counters host_c;
     EF_HIP_CHECK(hipMemcpyAsync(&host_c, w.counters, sizeof(Counters), hipMemcpyDeviceToHost, st));
     EF_HIP_CHECK(hipStreamSynchronize(st));
@@ -416,13 +612,14 @@ extern "C" int efanna_build_trees(const float *X, int64_t n, int32_t d, int32_t 
     int *perm_cur = perm, *perm_nxt = w.perm_tmp;
     int *node_cur = w.node_a, *node_nxt = w.node_b;
     Node *nodes_cur = w.nodes_a, *nodes_nxt = w.nodes_b;
-    int n_cur = n > S ? T : 0;
+    int n_cur = n > fin ? T : 0;
     while (n_cur > 0) {
         sum_kernel<<<grid_pos, kBlock, 0, st>>>(X, d, perm_cur, node_cur, nodes_cur, w.val, total);
         LeftPred pred{node_cur, nodes_cur, w.val};
         device_scan(pred, total, w.block_sums, w.lcount, st);
         children_kernel<<<(n_cur + kBlock - 1) / kBlock, kBlock, 0, st>>>(
-            nodes_cur, n_cur, nodes_nxt, w.lcount, w.leaf_flag, S, seed, (int)n, d, w.counters);
+            nodes_cur, n_cur, nodes_nxt, w.lcount, w.leaf_flag, S, fin, w.small, seed, (int)n, d,
+            w.counters);
         scatter_kernel<<<grid_pos, kBlock, 0, st>>>(perm_cur, perm_nxt, node_cur, node_nxt, nodes_cur,
                                                     w.val, w.lcount, total);
         EF_HIP_CHECK(hipMemcpyAsync(&host_c, w.counters, sizeof(Counters), hipMemcpyDeviceToHost, st));
@@ -432,6 +629,14 @@ extern "C" int efanna_build_trees(const float *X, int64_t n, int32_t d, int32_t 
         int *tp = perm_cur; perm_cur = perm_nxt; perm_nxt = tp;
         int *tn = node_cur; node_cur = node_nxt; node_nxt = tn;
         Node *tq = nodes_cur; nodes_cur = nodes_nxt; nodes_nxt = tq;
+    }
+    // host_c.small_nodes is current: it was read after the last level (or after the roots)
+    if (host_c.small_nodes > 0) {
+        const size_t fin_lds = (size_t)(6 * kFinMax + 8) * 4 + 2 * (size_t)kFinNodes * sizeof(LNode);
+        EF_HIP_CHECK(hipFuncSetAttribute((const void *)finish_kernel,
+                                         hipFuncAttributeMaxDynamicSharedMemorySize, (int)fin_lds));
+        finish_kernel<<<host_c.small_nodes, kBlock, fin_lds, st>>>(X, d, perm_cur, w.small, w.leaf_flag,
+                                                                  S, seed, (int)n);
     }
     if (perm_cur != perm)
         EF_HIP_CHECK(hipMemcpyAsync(perm, perm_cur, total * 4, hipMemcpyDeviceToDevice, st));
