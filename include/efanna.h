@@ -83,7 +83,7 @@ const char *efanna_status_string(int status);
  * Synchronises the stream (the host drives one launch group per tree level).
  * Limits: n*n_trees < 2^31, 1 <= leaf_size <= EFANNA_MAX_LEAF, n_trees <= EFANNA_MAX_TREES.
  */
-size_t efanna_trees_workspace_bytes(int64_t n, int32_t n_trees, int32_t leaf_size);
+size_t efanna_trees_workspace_bytes(int64_t n, int32_t d, int32_t n_trees, int32_t leaf_size);
 
 int efanna_build_trees(const float *X, int64_t n, int32_t d, int32_t n_trees, int32_t leaf_size,
                        uint64_t seed, int32_t *perm, int32_t *leaf_off, int32_t max_leaves,

@@ -56,14 +56,32 @@ inline int finish_limit(int S)
 
 __device__ inline long long quantise(float x) { return (long long)rint((double)x * 1048576.0); }
 
-__global__ void check_input_kernel(const float *__restrict__ X, size_t total, Counters *c)
+// Transposed copy XT[d][n] of the data, with the input check folded in.  The splits read
+// one coordinate of many points: in the row-major layout the upper levels (ids still
+// nearly consecutive) would touch one 4-byte word out of every row, a stride that keeps
+// hitting the same memory channels; in the transposed copy those reads are contiguous.
+__global__ void __launch_bounds__(kBlock)
+transpose_check_kernel(const float *__restrict__ X, int n, int d, float *__restrict__ XT, Counters *c)
 {
-    size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
-    size_t stride = (size_t)gridDim.x * blockDim.x;
+    __shared__ float tile[32][33];
+    const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;      // 32 x 8
+    const int r0 = blockIdx.x * 32, c0 = blockIdx.y * 32;
     bool bad = false;
-    for (; i < total; i += stride) {
-        float x = X[i];
-        bad |= !(fabsf(x) < 1048576.0f);   // false for NaN and inf as well
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+        const int row = r0 + ty + 8 * k, col = c0 + tx;
+        float v = 0.0f;
+        if (row < n && col < d) {
+            v = X[(size_t)row * d + col];
+            bad |= !(fabsf(v) < 1048576.0f);   // false for NaN and inf as well
+        }
+        tile[ty + 8 * k][tx] = v;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+        const int col = c0 + ty + 8 * k, row = r0 + tx;
+        if (row < n && col < d) XT[(size_t)col * n + row] = tile[tx][ty + 8 * k];
     }
     if (__any(bad) && ef_lane() == 0) atomicOr(&c->bad_input, 1);
 }
@@ -105,7 +123,7 @@ __global__ void roots_kernel(Node *nodes, int *node_of, unsigned char *leaf_flag
 }
 
 __global__ void __launch_bounds__(kBlock)
-sum_kernel(const float *__restrict__ X, int d, const int *__restrict__ perm,
+sum_kernel(const float *__restrict__ XT, int n, const int *__restrict__ perm,
            const int *__restrict__ node_of, Node *nodes, float *__restrict__ val, size_t total)
 {
     __shared__ long long wave_tot[kBlock / EF_WAVE];
@@ -118,7 +136,7 @@ sum_kernel(const float *__restrict__ X, int d, const int *__restrict__ perm,
         if (s >= 0) {
             int dim = nodes[s].dim;
             if (dim >= 0) {
-                float x = X[(size_t)perm[p] * d + dim];
+                float x = XT[(size_t)dim * n + perm[p]];
                 val[p] = x;
                 q = quantise(x);
             } else {
@@ -357,7 +375,7 @@ struct LNode {
 };
 
 __global__ void __launch_bounds__(kBlock)
-finish_kernel(const float *__restrict__ X, int d, int *perm, const SmallNode *__restrict__ small,
+finish_kernel(const float *__restrict__ XT, int d, int *perm, const SmallNode *__restrict__ small,
               unsigned char *leaf_flag, int S, u64 seed, int n)
 {
     // One 16-byte aligned LDS block carved by hand (no separate static LDS variables, whose
@@ -401,7 +419,7 @@ finish_kernel(const float *__restrict__ X, int d, int *perm, const SmallNode *__
         for (int p = tid; p < cnt; p += kBlock) {
             const int k = nc[p];
             if (k >= 0 && tc[k].dim >= 0) {
-                const float x = X[(size_t)idc[p] * d + tc[k].dim];
+                const float x = XT[(size_t)tc[k].dim * n + idc[p]];
                 val[p] = x;
                 atomicAdd((u64 *)&tc[k].sum, (u64)quantise(x));
             }
@@ -526,7 +544,7 @@ inline size_t align_up(size_t x) { return (x + 255) & ~(size_t)255; }
 
 struct TreeWs {
     int *perm_tmp, *node_a, *node_b, *lcount, *block_sums, *n_leaves_dev;
-    float *val;
+    float *val, *xt;
     unsigned char *leaf_flag;
     Node *nodes_a, *nodes_b;
     SmallNode *small;
@@ -534,7 +552,7 @@ struct TreeWs {
     size_t bytes;
 };
 
-TreeWs carve(void *ws, int64_t n, int32_t T, int32_t S)
+TreeWs carve(void *ws, int64_t n, int32_t d, int32_t T, int32_t S)
 {
     size_t total = (size_t)n * T;
     size_t max_nodes = total / (size_t)(S + 1) + (size_t)T + 1;
@@ -559,6 +577,7 @@ TreeWs carve(void *ws, int64_t n, int32_t T, int32_t S)
     w.small = (SmallNode *)take(max_nodes * sizeof(SmallNode));
     w.n_leaves_dev = (int *)take((size_t)T * 4);
     w.counters = (Counters *)take(sizeof(Counters));
+    w.xt = (float *)take((size_t)n * d * 4);
     w.bytes = off;
     return w;
 }
@@ -574,10 +593,11 @@ void device_scan(Pred pred, size_t total, int *block_sums, int *out, hipStream_t
 
 }  // namespace
 
-extern "C" size_t efanna_trees_workspace_bytes(int64_t n, int32_t n_trees, int32_t leaf_size)
+extern "C" size_t efanna_trees_workspace_bytes(int64_t n, int32_t d, int32_t n_trees,
+                                               int32_t leaf_size)
 {
-    if (n < 1 || n_trees < 1 || leaf_size < 1) return 0;
-    return carve(nullptr, n, n_trees, leaf_size).bytes;
+    if (n < 1 || d < 1 || n_trees < 1 || leaf_size < 1) return 0;
+    return carve(nullptr, n, d, n_trees, leaf_size).bytes;
 }
 
 extern "C" int efanna_build_trees(const float *X, int64_t n, int32_t d, int32_t n_trees,
@@ -590,16 +610,17 @@ extern "C" int efanna_build_trees(const float *X, int64_t n, int32_t d, int32_t 
         leaf_size > EFANNA_MAX_LEAF || max_leaves < 1)
         return EFANNA_EINVAL;
     if ((double)n * n_trees >= 2147483647.0 - 4096.0) return EFANNA_EINVAL;
-    if (!ws || ((uintptr_t)ws & 255) || ws_bytes < efanna_trees_workspace_bytes(n, n_trees, leaf_size))
+    if (!ws || ((uintptr_t)ws & 255) || ws_bytes < efanna_trees_workspace_bytes(n, d, n_trees, leaf_size))
         return EFANNA_EWORKSPACE;
     hipStream_t st = (hipStream_t)stream;
     const int T = n_trees, S = leaf_size;
     const size_t total = (size_t)n * T;
     const int grid_pos = (int)((total + kBlock - 1) / kBlock);
-    TreeWs w = carve(ws, n, T, S);
+    TreeWs w = carve(ws, n, d, T, S);
 
     EF_HIP_CHECK(hipMemsetAsync(w.counters, 0, sizeof(Counters), st));
-    check_input_kernel<<<1024, kBlock, 0, st>>>(X, (size_t)n * d, w.counters);
+    transpose_check_kernel<<<dim3((unsigned)((n + 31) / 32), (unsigned)((d + 31) / 32)), kBlock, 0, st>>>(
+        X, (int)n, d, w.xt, w.counters);
     iota_kernel<<<grid_pos, kBlock, 0, st>>>(perm, (int)n, total);
     const int fin = finish_limit(S);
     roots_kernel<<<grid_pos, kBlock, 0, st>>>(w.nodes_a, w.node_a, w.leaf_flag, (int)n, T, S, fin,
@@ -614,7 +635,7 @@ extern "C" int efanna_build_trees(const float *X, int64_t n, int32_t d, int32_t 
     Node *nodes_cur = w.nodes_a, *nodes_nxt = w.nodes_b;
     int n_cur = n > fin ? T : 0;
     while (n_cur > 0) {
-        sum_kernel<<<grid_pos, kBlock, 0, st>>>(X, d, perm_cur, node_cur, nodes_cur, w.val, total);
+        sum_kernel<<<grid_pos, kBlock, 0, st>>>(w.xt, (int)n, perm_cur, node_cur, nodes_cur, w.val, total);
         LeftPred pred{node_cur, nodes_cur, w.val};
         device_scan(pred, total, w.block_sums, w.lcount, st);
         children_kernel<<<(n_cur + kBlock - 1) / kBlock, kBlock, 0, st>>>(
@@ -635,7 +656,7 @@ extern "C" int efanna_build_trees(const float *X, int64_t n, int32_t d, int32_t 
         const size_t fin_lds = (size_t)(6 * kFinMax + 8) * 4 + 2 * (size_t)kFinNodes * sizeof(LNode);
         EF_HIP_CHECK(hipFuncSetAttribute((const void *)finish_kernel,
                                          hipFuncAttributeMaxDynamicSharedMemorySize, (int)fin_lds));
-        finish_kernel<<<host_c.small_nodes, kBlock, fin_lds, st>>>(X, d, perm_cur, w.small, w.leaf_flag,
+        finish_kernel<<<host_c.small_nodes, kBlock, fin_lds, st>>>(w.xt, d, perm_cur, w.small, w.leaf_flag,
                                                                   S, seed, (int)n);
     }
     if (perm_cur != perm)

@@ -45,7 +45,7 @@ def lib():
         L.efanna_status_string.restype = C.c_char_p
         L.efanna_status_string.argtypes = [C.c_int]
         L.efanna_trees_workspace_bytes.restype = sz
-        L.efanna_trees_workspace_bytes.argtypes = [i64, i32, i32]
+        L.efanna_trees_workspace_bytes.argtypes = [i64, i32, i32, i32]
         L.efanna_build_trees.restype = C.c_int
         L.efanna_build_trees.argtypes = [vp, i64, i32, i32, i32, u64, vp, vp, i32, vp, vp, sz, vp]
         L.efanna_init_workspace_bytes.restype = sz
@@ -98,7 +98,7 @@ def efanna_build_trees(X: torch.Tensor, n_trees: int, leaf_size: int, seed: int,
     perm = torch.empty((n_trees, n), dtype=torch.int32, device=X.device)
     leaf_off = torch.empty((n_trees, max_leaves + 1), dtype=torch.int32, device=X.device)
     n_leaves = np.zeros(n_trees, dtype=np.int32)
-    need = lib().efanna_trees_workspace_bytes(n, n_trees, leaf_size)
+    need = lib().efanna_trees_workspace_bytes(n, d, n_trees, leaf_size)
     ws = _workspace(need, X.device) if workspace is None else workspace
     _check(lib().efanna_build_trees(X.data_ptr(), n, d, n_trees, leaf_size, seed, perm.data_ptr(),
                                     leaf_off.data_ptr(), max_leaves,

@@ -47,9 +47,9 @@ def test_status_strings(lib):
 
 
 def test_workspace_sizes(lib):
-    assert lib.efanna_trees_workspace_bytes(0, 1, 1) == 0
-    a = lib.efanna_trees_workspace_bytes(1000, 4, 8)
-    b = lib.efanna_trees_workspace_bytes(2000, 4, 8)
+    assert lib.efanna_trees_workspace_bytes(0, 4, 1, 1) == 0
+    a = lib.efanna_trees_workspace_bytes(1000, 16, 4, 8)
+    b = lib.efanna_trees_workspace_bytes(2000, 16, 4, 8)
     assert 0 < a < b and a % 256 == 0
     assert lib.efanna_nndescent_workspace_bytes(1_000_000, 10, 10) < 600 * 2 ** 20
     assert lib.efanna_init_workspace_bytes(1000, 4) >= 256
