@@ -86,8 +86,8 @@ transpose_check_kernel(const float *__restrict__ X, int n, int d, float *__restr
     if (__any(bad) && ef_lane() == 0) atomicOr(&c->bad_input, 1);
 }
 
-__global__ void roots_kernel(Node *nodes, int *node_of, unsigned char *leaf_flag, int n, int T,
-                             int S, int fin, SmallNode *small, u64 seed, int d, Counters *c)
+__global__ void roots_kernel(Node *nodes, int *dims, int *node_of, unsigned char *leaf_flag, int n,
+                             int T, int S, int fin, SmallNode *small, u64 seed, int d, Counters *c)
 {
     size_t p = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
     size_t total = (size_t)n * T;
@@ -118,13 +118,15 @@ __global__ void roots_kernel(Node *nodes, int *node_of, unsigned char *leaf_flag
         nd.moved = 0;
         nd.child[0] = nd.child[1] = -1;
         nodes[p] = nd;
+        dims[p] = nd.dim;
     }
     if (p == 0) c->next_nodes = 0;
 }
 
 __global__ void __launch_bounds__(kBlock)
 sum_kernel(const float *__restrict__ XT, int n, const int *__restrict__ perm,
-           const int *__restrict__ node_of, Node *nodes, float *__restrict__ val, size_t total)
+           const int *__restrict__ node_of, Node *nodes, const int *__restrict__ dims,
+           float *__restrict__ val, size_t total)
 {
     __shared__ long long wave_tot[kBlock / EF_WAVE];
     __shared__ int wave_node[kBlock / EF_WAVE];
@@ -134,7 +136,9 @@ sum_kernel(const float *__restrict__ XT, int n, const int *__restrict__ perm,
     if (p < total) {
         s = node_of[p];
         if (s >= 0) {
-            int dim = nodes[s].dim;
+            // the split dimension comes from its own array: the node records are being hit
+            // by the sum atomics of this very kernel, and reads of such a line crawl
+            int dim = dims[s];
             if (dim >= 0) {
                 float x = XT[(size_t)dim * n + perm[p]];
                 val[p] = x;
@@ -266,7 +270,8 @@ __global__ void scan_apply_kernel(Pred pred, size_t total, const int *block_sums
     if (blockIdx.x == 0 && threadIdx.x == 0) out[total] = block_sums[nb];
 }
 
-__global__ void children_kernel(Node *cur, int n_cur, Node *next, const int *__restrict__ lcount,
+__global__ void children_kernel(Node *cur, int n_cur, Node *next, int *next_dims,
+                                const int *__restrict__ lcount,
                                 unsigned char *leaf_flag, int S, int fin, SmallNode *small, u64 seed,
                                 int n, int d, Counters *c)
 {
@@ -319,6 +324,7 @@ __global__ void children_kernel(Node *cur, int n_cur, Node *next, const int *__r
             ch.moved = 0;
             ch.child[0] = ch.child[1] = -1;
             next[slot] = ch;
+            next_dims[slot] = ch.dim;
             nd.child[side] = slot++;
         } else if (kind[side] == 1) {
             SmallNode sn;
@@ -547,6 +553,7 @@ struct TreeWs {
     float *val, *xt;
     unsigned char *leaf_flag;
     Node *nodes_a, *nodes_b;
+    int *dims_a, *dims_b;
     SmallNode *small;
     Counters *counters;
     size_t bytes;
@@ -575,6 +582,8 @@ TreeWs carve(void *ws, int64_t n, int32_t d, int32_t T, int32_t S)
     w.nodes_a = (Node *)take(max_nodes * sizeof(Node));
     w.nodes_b = (Node *)take(max_nodes * sizeof(Node));
     w.small = (SmallNode *)take(max_nodes * sizeof(SmallNode));
+    w.dims_a = (int *)take(max_nodes * 4);
+    w.dims_b = (int *)take(max_nodes * 4);
     w.n_leaves_dev = (int *)take((size_t)T * 4);
     w.counters = (Counters *)take(sizeof(Counters));
     w.xt = (float *)take((size_t)n * d * 4);
@@ -623,7 +632,7 @@ extern "C" int efanna_build_trees(const float *X, int64_t n, int32_t d, int32_t 
         X, (int)n, d, w.xt, w.counters);
     iota_kernel<<<grid_pos, kBlock, 0, st>>>(perm, (int)n, total);
     const int fin = finish_limit(S);
-    roots_kernel<<<grid_pos, kBlock, 0, st>>>(w.nodes_a, w.node_a, w.leaf_flag, (int)n, T, S, fin,
+    roots_kernel<<<grid_pos, kBlock, 0, st>>>(w.nodes_a, w.dims_a, w.node_a, w.leaf_flag, (int)n, T, S, fin,
                                               w.small, seed, d, w.counters);
     Counters host_c;
     EF_HIP_CHECK(hipMemcpyAsync(&host_c, w.counters, sizeof(Counters), hipMemcpyDeviceToHost, st));
@@ -633,13 +642,15 @@ extern "C" int efanna_build_trees(const float *X, int64_t n, int32_t d, int32_t 
     int *perm_cur = perm, *perm_nxt = w.perm_tmp;
     int *node_cur = w.node_a, *node_nxt = w.node_b;
     Node *nodes_cur = w.nodes_a, *nodes_nxt = w.nodes_b;
+    int *dims_cur = w.dims_a, *dims_nxt = w.dims_b;
     int n_cur = n > fin ? T : 0;
     while (n_cur > 0) {
-        sum_kernel<<<grid_pos, kBlock, 0, st>>>(w.xt, (int)n, perm_cur, node_cur, nodes_cur, w.val, total);
+        sum_kernel<<<grid_pos, kBlock, 0, st>>>(w.xt, (int)n, perm_cur, node_cur, nodes_cur, dims_cur, w.val,
+                                                total);
         LeftPred pred{node_cur, nodes_cur, w.val};
         device_scan(pred, total, w.block_sums, w.lcount, st);
         children_kernel<<<(n_cur + kBlock - 1) / kBlock, kBlock, 0, st>>>(
-            nodes_cur, n_cur, nodes_nxt, w.lcount, w.leaf_flag, S, fin, w.small, seed, (int)n, d,
+            nodes_cur, n_cur, nodes_nxt, dims_nxt, w.lcount, w.leaf_flag, S, fin, w.small, seed, (int)n, d,
             w.counters);
         scatter_kernel<<<grid_pos, kBlock, 0, st>>>(perm_cur, perm_nxt, node_cur, node_nxt, nodes_cur,
                                                     w.val, w.lcount, total);
@@ -650,6 +661,7 @@ extern "C" int efanna_build_trees(const float *X, int64_t n, int32_t d, int32_t 
         int *tp = perm_cur; perm_cur = perm_nxt; perm_nxt = tp;
         int *tn = node_cur; node_cur = node_nxt; node_nxt = tn;
         Node *tq = nodes_cur; nodes_cur = nodes_nxt; nodes_nxt = tq;
+        int *td = dims_cur; dims_cur = dims_nxt; dims_nxt = td;
     }
     // host_c.small_nodes is current: it was read after the last level (or after the roots)
     if (host_c.small_nodes > 0) {
