@@ -25,13 +25,15 @@ __host__ __device__ inline int align4(int x) { return (x + 3) & ~3; }
 
 // reverse lists: slot s of an empty list holds ~0 - s (above every real key)
 __global__ void fill_reverse_kernel(u64 *a, u64 *b, size_t total, int L, int *a_count, int *b_count,
-                                    size_t n, int *work_count)
+                                    u64 *list_max, size_t n, int *work_count)
 {
     size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (i < 8) work_count[i] = 0;     // three work lists
     if (i < n) {
         a_count[i] = 0;
         b_count[i] = 0;
+        list_max[i] = ~0ULL;
+        list_max[n + i] = ~0ULL;
     }
     if (i < total) {
         u64 v = ~0ULL - (u64)(i % (size_t)L);
@@ -331,18 +333,24 @@ sample_kernel(u64 *graph, int n, int K, int L, u64 key_new, u64 key_old, int *__
     }
 }
 
-// one thread per (row, parked key): thread t serves key t % 2^kp_log of row t >> kp_log
+// one thread per (row, parked key): thread t serves key t % 2^kp_log of row t >> kp_log.
+// list_max[which][v] is an upper bound of the largest key of (full) list v, lowered after
+// every successful insertion: the many keys offered to a popular point are turned away
+// after one read instead of a scan of the list.
 __global__ void reverse_overflow_kernel(const Overflow *__restrict__ overflow,
                                         const int *__restrict__ overflow_rows, int n, int K,
-                                        int kp_log, u64 *rnew, u64 *rold, int L)
+                                        int kp_log, u64 *rnew, u64 *rold, u64 *list_max, int L)
 {
     const size_t t = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
     const size_t i = t >> kp_log;
     const int j = (int)(t & ((1u << kp_log) - 1));
     if (i >= (size_t)n || j >= overflow_rows[i]) return;
     const Overflow ov = overflow[i * K + j];
+    u64 *bound = list_max + (size_t)ov.which * n + ov.target;
+    if (ov.key >= ef_load_coherent(bound)) return;
     u64 nm;
-    ef_bounded_insert((ov.which ? rold : rnew) + (size_t)ov.target * L, L, ov.key, 0, &nm);
+    if (ef_bounded_insert((ov.which ? rold : rnew) + (size_t)ov.target * L, L, ov.key, 0, &nm))
+        atomicMin(bound, nm);
 }
 
 // After sampling and the reverse lists: one thread per point merges its four id lists
@@ -988,7 +996,7 @@ struct NndWs {
     int *nw, *od, *nw_c, *od_c, *cnt_evals, *cnt_upd, *cnt_rows, *work, *work_count, *rnew_c, *rold_c, *overflow_rows, *ulist, *upd_block;
     int2 *ucount;
     void *overflow;
-    u64 *rnew, *rold;
+    u64 *rnew, *rold, *list_max;
     u32 *worst;
     float *norms;
     size_t bytes;
@@ -1022,6 +1030,7 @@ NndWs carve_nnd(void *ws, int64_t n, int K, int L)
     w.upd_block = (int *)take((size_t)2 * kRegGrid * 4);
     w.rnew = (u64 *)take((size_t)n * L * 8);
     w.rold = (u64 *)take((size_t)n * L * 8);
+    w.list_max = (u64 *)take((size_t)n * 2 * 8);
     w.worst = (u32 *)take((size_t)n * 4);
     w.norms = (float *)take((size_t)n * 4);
     w.bytes = off;
@@ -1188,7 +1197,7 @@ extern "C" int efanna_nndescent(const float *X, int64_t n, int32_t d, int32_t k,
         const int g = first_iter + it;
         if (ev) EF_HIP_CHECK(hipEventRecord(ev[5 * it], st));
         fill_reverse_kernel<<<grid_for((size_t)n * L, kBlock), kBlock, 0, st>>>(
-            w.rnew, w.rold, (size_t)n * L, L, w.rnew_c, w.rold_c, (size_t)n, w.work_count);
+            w.rnew, w.rold, (size_t)n * L, L, w.rnew_c, w.rold_c, w.list_max, (size_t)n, w.work_count);
         {
             const u64 kn = ef_stream_key(seed, 2 * g), ko = ef_stream_key(seed, 2 * g + 1);
             Overflow *ovf = (Overflow *)w.overflow;
@@ -1204,7 +1213,7 @@ extern "C" int efanna_nndescent(const float *X, int64_t n, int32_t d, int32_t k,
             int kp_log = 0;
             while ((1 << kp_log) < K) ++kp_log;
             reverse_overflow_kernel<<<grid_for((size_t)n << kp_log, kBlock), kBlock, 0, st>>>(
-                ovf, w.overflow_rows, (int)n, K, kp_log, w.rnew, w.rold, L);
+                ovf, w.overflow_rows, (int)n, K, kp_log, w.rnew, w.rold, w.list_max, L);
         }
         prepare_kernel<<<grid_for((size_t)n, prep_threads), prep_threads, prep_lds, st>>>(
             w.nw, w.od, w.nw_c, w.od_c, w.rnew, w.rold, w.rnew_c, w.rold_c, (int)n, K, L, max_rows,
