@@ -646,9 +646,10 @@ join_reg_kernel(const float *__restrict__ X, const float *__restrict__ norms, in
     constexpr int S_CAP = R * (R - 1) / 2 + 8;    // every pair may survive
     extern __shared__ __align__(16) float smem[];
     int *uid = (int *)smem;                       // [R]
-    u32 *thr = (u32 *)(uid + R);                  // [R]
-    float *nrm = (float *)(thr + R);              // [R]
-    int *meta = (int *)(nrm + R);                 // [8]: [3] queue count [4..6] survivors per block
+    u32 *thr = (u32 *)(uid + R);                  // [R] threshold bits (exact test)
+    float *nf = (float *)(thr + R);               // [R] |x|^2 (1 - margin)   } the filter's
+    float *tf = nf + R;                           // [R] threshold * scale    } operands
+    int *meta = (int *)(tf + R);                  // [8]: [3] queue count [4..6] survivors per block
     u32 *surv = (u32 *)(meta + 8);                // [S_CAP] surviving pairs
     Proposal *queue = (Proposal *)(surv + align4(S_CAP));   // [q_cap]
     const int lane = threadIdx.x, r16 = lane & 15, g = lane >> 4, gl = r16, grp = g;
@@ -677,8 +678,10 @@ join_reg_kernel(const float *__restrict__ X, const float *__restrict__ norms, in
         i_next = w + 2 * (int)gridDim.x < count ? work[w + 2 * gridDim.x] : -1;
         if (lane < m) {
             const int id = uid[lane];
-            thr[lane] = ef_load_coherent(worst + id);
-            nrm[lane] = norms[id];
+            const u32 t = ef_load_coherent(worst + id);
+            thr[lane] = t;
+            tf[lane] = __uint_as_float(t) * thr_scale;
+            nf[lane] = norms[id] * (1.0f - margin_rel);
         }
         // ---- 1+2. Gram blocks from register operands ---------------------------------------
         const float *pa = X + (size_t)uid[min(r16, m - 1)] * d + 4 * g;
@@ -733,23 +736,23 @@ join_reg_kernel(const float *__restrict__ X, const float *__restrict__ norms, in
         }
         __syncthreads();      // thr, nrm visible
         // ---- filter: lane holds G[a = 16 bi + 4 g + k][b = 16 bj + r16] of block q -----------
+        // pair (a, b) survives if (|a|^2 + |b|^2)(1 - margin) - 2 a.b <= max threshold * scale
 #pragma unroll
         for (int q = 0; q < (NB > 1 ? 3 : 1); ++q) {
             const int bi = q == 2 ? 1 : 0, bj = q == 0 ? 0 : 1;
-            const int b = 16 * bj + r16;
-            const float nb = nrm[min(b, m - 1)];
-            const float tb = __uint_as_float(thr[min(b, m - 1)]);
+            const int b = 16 * bj + r16, a0 = 16 * bi + 4 * g;
+            const int lim = b < m ? min(m_new, b) : 0;           // valid pairs: a < lim
+            const float nfb = nf[b], tfb = tf[b];                  // junk beyond m, masked by lim
+            const float4 nfa = *reinterpret_cast<const float4 *>(nf + a0);
+            const float4 tfa = *reinterpret_cast<const float4 *>(tf + a0);
+            const float nfa_k[4] = {nfa.x, nfa.y, nfa.z, nfa.w}, tfa_k[4] = {tfa.x, tfa.y, tfa.z, tfa.w};
 #pragma unroll
             for (int k = 0; k < 4; ++k) {
-                const int a = 16 * bi + 4 * g + k;
-                if (a < b && a < m_new && b < m) {
-                    const float sum = nrm[a] + nb;
-                    const float approx = sum - 2.0f * (acc[q][0][k] + acc[q][1][k]);
-                    if (approx - margin_rel * sum <= fmaxf(__uint_as_float(thr[a]), tb) * thr_scale) {
-                        // ONE: one list per Gram block, entries are rows local to the block
-                        if (ONE) surv[kSurvBase[q] + atomicAdd(&meta[4 + q], 1)] = (u32)(a & 15) | ((u32)(b & 15) << 8);
-                        else surv[atomicAdd(&meta[4], 1)] = (u32)a | ((u32)b << 16);
-                    }
+                const float lhs = __builtin_fmaf(-2.0f, acc[q][0][k] + acc[q][1][k], nfa_k[k] + nfb);
+                if (a0 + k < lim && lhs <= fmaxf(tfa_k[k], tfb)) {
+                    // ONE: one list per Gram block, entries are rows local to the block
+                    if (ONE) surv[kSurvBase[q] + atomicAdd(&meta[4 + q], 1)] = (u32)((a0 + k) & 15) | ((u32)(b & 15) << 8);
+                    else surv[atomicAdd(&meta[4], 1)] = (u32)(a0 + k) | ((u32)b << 16);
                 }
             }
         }
@@ -1168,7 +1171,7 @@ extern "C" int efanna_nndescent(const float *X, int64_t n, int32_t d, int32_t k,
     if (max_rows > rows1 && large.lds > kLdsLimit) return EFANNA_EUNSUPPORTED;
     const int reg_q_cap = 128;
     auto reg_lds = [&](int R) {
-        return (size_t)(3 * R + 8 + align4(R * (R - 1) / 2 + 8)) * 4 +
+        return (size_t)(4 * R + 8 + align4(R * (R - 1) / 2 + 8)) * 4 +
                (size_t)reg_q_cap * sizeof(Proposal);
     };
     const int reg_grid = kRegGrid;
