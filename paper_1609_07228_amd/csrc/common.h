@@ -86,14 +86,14 @@ __device__ inline bool ef_bounded_insert(u64 *list, int cap, u64 key, int ignore
         u64 mx = 0, mx2 = 0;
         int ms = 0;
         bool dup = false;
-        // eight slot reads in flight at a time: the row read costs one or two memory
-        // round trips instead of one per slot
-        for (int s0 = 0; s0 < cap; s0 += 8) {
-            u64 e[8];
+        // sixteen slot reads in flight at a time: a row of up to 16 entries costs one memory
+        // round trip instead of one per slot
+        for (int s0 = 0; s0 < cap; s0 += 16) {
+            u64 e[16];
 #pragma unroll
-            for (int k = 0; k < 8; ++k) e[k] = s0 + k < cap ? ef_load_coherent(list + s0 + k) : 0;
+            for (int k = 0; k < 16; ++k) e[k] = s0 + k < cap ? ef_load_coherent(list + s0 + k) : 0;
 #pragma unroll
-            for (int k = 0; k < 8; ++k) {
+            for (int k = 0; k < 16; ++k) {
                 if (s0 + k >= cap) break;
                 dup |= (e[k] >> ignore) == kcmp;
                 if (e[k] > mx) {
