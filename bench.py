@@ -21,6 +21,11 @@ sys.path.insert(0, os.path.dirname(os.path.abspath(__file__)))
 
 HBM_PEAK_GBS = 8000.0
 
+# HBM bytes per launch of the dominant kernel, from two rocprofv3 --pmc runs (FETCH_SIZE, WRITE_SIZE)
+# scaled by what the same counters read for a plain 256 MiB copy (factors 2.0 and 1.0); summary and
+# commands in profiles/join_kernels_sift1m_like_hbm_traffic.txt.  Only measured for the headline workload.
+MEASURED_TRAFFIC_BYTES = {"sift1m_like": {"calibrated": 5.67e9, "raw_counters": 2.94e9}}
+
 
 def exact_knn_torch(Xd, rows, K):
     """Ground truth for recall on the sampled rows: float64 brute force with torch
@@ -179,7 +184,10 @@ def main():
                                 "vectors_gathered_join_le16": [int(x) for x in st[:, 3]]},
         "roofline": {"kernel": "join_reg_kernel<1> (joins of at most 16 vectors)", "bound": "hbm",
                      "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                     "frac": achieved / HBM_PEAK_GBS,
+                     "traffic": (MEASURED_TRAFFIC_BYTES.get(name, {}).get("calibrated") if args.n is None else None),
+                     "traffic_raw_counters": (MEASURED_TRAFFIC_BYTES.get(name, {}).get("raw_counters")
+                                              if args.n is None else None),
                      "avg_launch_ms": k_ms_sum / max(1, k_launches),
                      "algorithmic_bytes_per_launch": k_bytes_sum / max(1, k_launches),
                      "all_join_kernels": {"achieved": achieved_all, "frac": achieved_all / HBM_PEAK_GBS,
