@@ -234,10 +234,9 @@ __device__ inline bool reverse_offer(u64 *lists, int *counts, int L, int v, u64 
 
 template <int G, int E>
 __global__ void __launch_bounds__(kBlock)
-sample_kernel(u64 *graph, int n, int K, int L, u64 key_new, u64 key_old, int *__restrict__ nw,
+sample_kernel(u64 *graph, int n, int K, int L, u64 key_new, int *__restrict__ nw,
               int *__restrict__ od, int *__restrict__ nw_c, int *__restrict__ od_c, u64 *rnew,
-              u64 *rold, int *rnew_c, int *rold_c, Overflow *overflow, int *overflow_rows,
-              u32 *worst)
+              int *rnew_c, Overflow *overflow, int *overflow_rows, u32 *worst)
 {
     const int gl = threadIdx.x & (G - 1);
     const int i = (int)(((size_t)blockIdx.x * kBlock + threadIdx.x) / G);
@@ -286,6 +285,9 @@ sample_kernel(u64 *graph, int n, int K, int L, u64 key_new, u64 key_old, int *__
         const u64 other = __shfl_xor(stop, m, G);
         stop = other < stop ? other : stop;
     }
+    // sampled new entries lose their mark, go to the new list and are offered to the reverse-new
+    // list of the neighbour; old entries only go to the old list here (reverse_old_kernel offers
+    // them once it is known which points take part in a join at all)
     int n_old = 0, n_parked = 0;     // parked keys of row i go to overflow[i*K ...], in group order
     const int group_shift = (int)(threadIdx.x & (EF_WAVE - 1) & ~(G - 1));
     const u64 group_bits = ~0ULL >> (64 - G);
@@ -293,31 +295,27 @@ sample_kernel(u64 *graph, int n, int K, int L, u64 key_new, u64 key_old, int *__
     for (int h = 0; h < E; ++h) {
         const int slot = gl + h * G;
         const int id = ef_id(e[h]);
-#pragma unroll
-        for (int which = 0; which < 2; ++which) {
-            const bool take = row_ok && (which == 0 ? take_new[h] : (is_old[h] && e[h] < stop));
-            bool parked = false;
-            u64 hk = 0;
-            if (take) {
-                if (which == 0) {
-                    nw[(size_t)i * L + rn[h]] = id;
-                    graph[(size_t)i * K + slot] = e[h] & ~1ULL;
-                } else {
-                    od[(size_t)i * K + ro[h]] = id;
-                    ++n_old;
-                }
-                hk = (ef_mix64((which == 0 ? key_new : key_old) + (((u64)(u32)id << 32) | (u32)i)) >> 32 << 32) | (u32)i;
-                parked = reverse_offer(which == 0 ? rnew : rold, which == 0 ? rnew_c : rold_c, L, id, hk);
-            }
-            const u64 mask = (__ballot(parked) >> group_shift) & group_bits;
-            if (parked) {
-                Overflow &o = overflow[(size_t)i * K + n_parked + __popcll(mask & ((1ULL << gl) - 1))];
-                o.key = hk;
-                o.target = id;
-                o.which = which;
-            }
-            n_parked += __popcll(mask);
+        if (row_ok && is_old[h] && e[h] < stop) {
+            od[(size_t)i * K + ro[h]] = id;
+            ++n_old;
         }
+        const bool take = row_ok && take_new[h];
+        bool parked = false;
+        u64 hk = 0;
+        if (take) {
+            nw[(size_t)i * L + rn[h]] = id;
+            graph[(size_t)i * K + slot] = e[h] & ~1ULL;
+            hk = (ef_mix64(key_new + (((u64)(u32)id << 32) | (u32)i)) >> 32 << 32) | (u32)i;
+            parked = reverse_offer(rnew, rnew_c, L, id, hk);
+        }
+        const u64 mask = (__ballot(parked) >> group_shift) & group_bits;
+        if (parked) {
+            Overflow &o = overflow[(size_t)i * K + n_parked + __popcll(mask & ((1ULL << gl) - 1))];
+            o.key = hk;
+            o.target = id;
+            o.which = 0;
+        }
+        n_parked += __popcll(mask);
     }
     for (int m = G / 2; m >= 1; m >>= 1) n_old += __shfl_xor(n_old, m, G);
     if (!row_ok) return;
@@ -331,6 +329,56 @@ sample_kernel(u64 *graph, int n, int K, int L, u64 key_new, u64 key_old, int *__
         worst[i] = wbits;
         overflow_rows[i] = n_parked;
     }
+}
+
+// Bit i of `active` says whether point i has a non-empty U_new (a sampled new neighbour or a
+// reverse-new member), i.e. whether it joins anything in this iteration.  One bit per point:
+// the map of a million points is 128 KB and stays in L2 for the random look-ups that follow.
+__global__ void __launch_bounds__(kBlock)
+active_kernel(const int *__restrict__ nw_c, const int *__restrict__ rnew_c, int n, u64 *__restrict__ active)
+{
+    const int i = blockIdx.x * kBlock + threadIdx.x;
+    const u64 mask = __ballot(i < n && (nw_c[i] > 0 || rnew_c[i] > 0));
+    if (ef_lane() == 0 && (i & ~(EF_WAVE - 1)) < n) active[i / EF_WAVE] = mask;
+}
+
+// Reverse-old lists, after sampling: row i offers itself to the reverse-old list of each of its
+// sampled old neighbours -- but only to those that join something; the list of a point whose
+// U_new is empty is never read (Alg. 4 pairs U_old only with U_new), so it stays empty.
+// One lane per slot of the old list, a group of G lanes per row as in sample_kernel; parked keys
+// go behind the ones sample_kernel parked for the row.
+template <int G>
+__global__ void __launch_bounds__(kBlock)
+reverse_old_kernel(const int *__restrict__ od, int n, int K, int L, u64 key_old,
+                   const u64 *__restrict__ active, u64 *rold, int *rold_c, Overflow *overflow,
+                   int *overflow_rows)
+{
+    const int gl = threadIdx.x & (G - 1);
+    const int i = (int)(((size_t)blockIdx.x * kBlock + threadIdx.x) / G);
+    const bool row_ok = i < n;
+    const int group_shift = (int)(threadIdx.x & (EF_WAVE - 1) & ~(G - 1));
+    const u64 group_bits = ~0ULL >> (64 - G);
+    int n_parked = row_ok ? overflow_rows[i] : 0;
+    const int first = n_parked;
+    for (int s0 = 0; s0 < K; s0 += G) {
+        const int slot = s0 + gl;
+        const int id = row_ok && slot < K ? od[(size_t)i * K + slot] : -1;
+        bool parked = false;
+        u64 hk = 0;
+        if (id >= 0 && ((active[id / EF_WAVE] >> (id % EF_WAVE)) & 1)) {
+            hk = (ef_mix64(key_old + (((u64)(u32)id << 32) | (u32)i)) >> 32 << 32) | (u32)i;
+            parked = reverse_offer(rold, rold_c, L, id, hk);
+        }
+        const u64 mask = (__ballot(parked) >> group_shift) & group_bits;
+        if (parked) {
+            Overflow &o = overflow[(size_t)i * K + n_parked + __popcll(mask & ((1ULL << gl) - 1))];
+            o.key = hk;
+            o.target = id;
+            o.which = 1;
+        }
+        n_parked += __popcll(mask);
+    }
+    if (row_ok && gl == 0 && n_parked != first) overflow_rows[i] = n_parked;
 }
 
 // one thread per (row, parked key): thread t serves key t % 2^kp_log of row t >> kp_log.
@@ -377,8 +425,10 @@ __global__ void prepare_kernel(const int *__restrict__ nw, const int *__restrict
     const int i = blockIdx.x * blockDim.x + threadIdx.x;
     int cls = -1, m = 0;
     if (i < n) {
-        const int c_new = nw_c[i], c_old = od_c[i];
+        const int c_new = nw_c[i];
+        int c_old = od_c[i];
         const int rn = min(rnew_c[i], L), ro = min(rold_c[i], L);
+        if (c_new + rn == 0) c_old = 0;      // empty U_new: no join, nothing to list
         for (int a = 0; a < c_new; ++a) mine[m++] = nw[(size_t)i * L + a];
         for (int a = 0; a < rn; ++a) {
             const int id = (int)(u32)rnew[(size_t)i * L + a];
@@ -999,7 +1049,7 @@ struct NndWs {
     int *nw, *od, *nw_c, *od_c, *cnt_evals, *cnt_upd, *cnt_rows, *work, *work_count, *rnew_c, *rold_c, *overflow_rows, *ulist, *upd_block;
     int2 *ucount;
     void *overflow;
-    u64 *rnew, *rold, *list_max;
+    u64 *rnew, *rold, *list_max, *active;
     u32 *worst;
     float *norms;
     size_t bytes;
@@ -1034,6 +1084,7 @@ NndWs carve_nnd(void *ws, int64_t n, int K, int L)
     w.rnew = (u64 *)take((size_t)n * L * 8);
     w.rold = (u64 *)take((size_t)n * L * 8);
     w.list_max = (u64 *)take((size_t)n * 2 * 8);
+    w.active = (u64 *)take((size_t)(n + 63) / 64 * 8);
     w.worst = (u32 *)take((size_t)n * 4);
     w.norms = (float *)take((size_t)n * 4);
     w.bytes = off;
@@ -1206,13 +1257,21 @@ extern "C" int efanna_nndescent(const float *X, int64_t n, int32_t d, int32_t k,
             Overflow *ovf = (Overflow *)w.overflow;
 #define EF_SAMPLE(G, E)                                                                          \
     sample_kernel<G, E><<<grid_for((size_t)n * G, kBlock), kBlock, 0, st>>>(                     \
-        graph, (int)n, K, L, kn, ko, w.nw, w.od, w.nw_c, w.od_c, w.rnew, w.rold, w.rnew_c,       \
-        w.rold_c, ovf, w.overflow_rows, w.worst)
+        graph, (int)n, K, L, kn, w.nw, w.od, w.nw_c, w.od_c, w.rnew, w.rnew_c, ovf,              \
+        w.overflow_rows, w.worst)
+#define EF_REVERSE_OLD(G)                                                                        \
+    reverse_old_kernel<G><<<grid_for((size_t)n * G, kBlock), kBlock, 0, st>>>(                   \
+        w.od, (int)n, K, L, ko, w.active, w.rold, w.rold_c, ovf, w.overflow_rows)
             if (K <= 16) EF_SAMPLE(16, 1);
             else if (K <= 32) EF_SAMPLE(32, 1);
             else if (K <= 64) EF_SAMPLE(64, 1);
             else EF_SAMPLE(64, 2);
+            active_kernel<<<grid_for((size_t)n, kBlock), kBlock, 0, st>>>(w.nw_c, w.rnew_c, (int)n, w.active);
+            if (K <= 16) EF_REVERSE_OLD(16);
+            else if (K <= 32) EF_REVERSE_OLD(32);
+            else EF_REVERSE_OLD(64);
 #undef EF_SAMPLE
+#undef EF_REVERSE_OLD
             int kp_log = 0;
             while ((1 << kp_log) < K) ++kp_log;
             reverse_overflow_kernel<<<grid_for((size_t)n << kp_log, kBlock), kBlock, 0, st>>>(
