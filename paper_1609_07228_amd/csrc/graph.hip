@@ -200,6 +200,168 @@ init_tree_kernel(const float *__restrict__ X, int d, int stride, u32 q4_magic, i
 }
 
 // ---------------------------------------------------------------------------------------
+// The same step for leaves of at most 16 points and d <= 128 (d % 4 == 0, X 16-byte aligned),
+// without a row buffer: persistent waves, one leaf at a time.
+//
+// Lane (r, g) = lane r + 16 g keeps, of member r of the leaf, the coordinates 16 s + 4 g + k
+// (s = 0..7, k = 0..3), i.e. the terms of partial sums 4g..4g+3 of the library's fixed
+// order.  Rotating the 16 lanes of a row by t (a DPP modifier, no memory traffic) puts
+// member r opposite member r +- t, so eight rotations meet all pairs of the leaf; the four
+// lanes of a column then add their partial sums in the fixed tree (8 apart, 4 apart, 2
+// apart, 1 apart), transposed so that lane (r, g) ends up with the distances of rotations
+// 2g+1 and 2g+2, and fetches the two that its mirror lanes computed towards r.
+//
+// Merge: the leaf owns its members' graph rows during the launch.  The old row (ascending,
+// in LDS) and the row's up to 15 candidates are merged by rank: a candidate's rank is the
+// number of old entries below it (binary search, which also finds it if it is already in
+// the row) plus the number of candidates below it; an old entry's rank is its index plus
+// the number of candidates below it.  Ranks below K are stored straight to the row.
+#define EF_ROW_ROR(x, t) __builtin_amdgcn_update_dpp(0, (x), 0x120 | (t), 0xF, 0xF, false)
+
+template <int T>
+__device__ inline void init_round(const float4 (&va)[8], int n_pieces, float (&p)[4])
+{
+    p[0] = p[1] = p[2] = p[3] = 0.0f;
+#pragma unroll
+    for (int s = 0; s < 8; ++s) {
+        if (s >= n_pieces) break;
+        const float d0 = va[s].x - __int_as_float(EF_ROW_ROR(__float_as_int(va[s].x), T));
+        const float d1 = va[s].y - __int_as_float(EF_ROW_ROR(__float_as_int(va[s].y), T));
+        const float d2 = va[s].z - __int_as_float(EF_ROW_ROR(__float_as_int(va[s].z), T));
+        const float d3 = va[s].w - __int_as_float(EF_ROW_ROR(__float_as_int(va[s].w), T));
+        p[0] = __builtin_fmaf(d0, d0, p[0]);
+        p[1] = __builtin_fmaf(d1, d1, p[1]);
+        p[2] = __builtin_fmaf(d2, d2, p[2]);
+        p[3] = __builtin_fmaf(d3, d3, p[3]);
+    }
+}
+
+constexpr int kCandPitch = 17;      // u64 per row of the candidate table (odd: rows on different banks)
+
+__global__ void __launch_bounds__(EF_WAVE) __attribute__((amdgpu_waves_per_eu(4)))
+init_reg_kernel(const float *__restrict__ X, int d, const int *__restrict__ perm_t,
+                const int *__restrict__ leaf_off_t, int n_leaves, int K, u64 *graph, int first_tree)
+{
+    extern __shared__ __align__(16) float smem[];
+    u64 *pools = (u64 *)smem;                         // [16][K] old rows, ascending
+    u64 *cand = pools + 16 * (size_t)K;               // [16][kCandPitch] candidates of each row
+    int *uid = (int *)(cand + 16 * kCandPitch);       // [16]
+    const int lane = threadIdx.x, r16 = lane & 15, g = lane >> 4;
+    const int n_pieces = (d + 15) >> 4;
+    // which way the rotation moves data: lane r receives from lane r + dirn (mod 16)
+    const int dirn = (EF_ROW_ROR(r16, 1) - r16) & 15;
+    // leaf boundaries are fetched two leaves ahead and member ids one leaf ahead
+    int leaf = blockIdx.x;
+    int b0 = leaf < n_leaves ? leaf_off_t[leaf] : 0;
+    int s0 = leaf < n_leaves ? min(leaf_off_t[leaf + 1] - b0, 16) : 0;
+    int id_pre = r16 < s0 ? perm_t[b0 + r16] : -1;
+    int leaf1 = leaf + (int)gridDim.x;
+    int b1 = leaf1 < n_leaves ? leaf_off_t[leaf1] : 0;
+    int s1 = leaf1 < n_leaves ? min(leaf_off_t[leaf1 + 1] - b1, 16) : 0;
+    for (; leaf < n_leaves; leaf += gridDim.x) {
+        const int s = s0, my_id = id_pre;
+        __syncthreads();                  // the previous leaf's LDS reads are done
+        if (g == 0) uid[r16] = my_id;
+        // operands and old rows of this leaf
+        float4 va[8];
+        const float *pa = X + (size_t)max(my_id, 0) * d + 4 * g;
+#pragma unroll
+        for (int q = 0; q < 8; ++q) {
+            const bool in = r16 < s && 16 * q + 4 * g + 3 < d;      // d % 4 == 0: a piece is in or out
+            va[q] = in ? *reinterpret_cast<const float4 *>(pa + 16 * q) : make_float4(0.f, 0.f, 0.f, 0.f);
+        }
+        for (int c = g; c < K; c += 4)
+            pools[r16 * K + c] = first_tree || r16 >= s ? ef_empty_entry(K - 1 - c)
+                                                        : graph[(size_t)my_id * K + c];
+        // prefetch for the leaves to come
+        s0 = s1;
+        b0 = b1;
+        id_pre = r16 < s0 ? perm_t[b0 + r16] : -1;
+        leaf1 += gridDim.x;
+        b1 = leaf1 < n_leaves ? leaf_off_t[leaf1] : 0;
+        s1 = leaf1 < n_leaves ? min(leaf_off_t[leaf1 + 1] - b1, 16) : 0;
+        // ---- distances: rotations 1..8 ----------------------------------------------------
+        float P[8][4];
+        init_round<1>(va, n_pieces, P[0]);
+        init_round<2>(va, n_pieces, P[1]);
+        init_round<3>(va, n_pieces, P[2]);
+        init_round<4>(va, n_pieces, P[3]);
+        init_round<5>(va, n_pieces, P[4]);
+        init_round<6>(va, n_pieces, P[5]);
+        init_round<7>(va, n_pieces, P[6]);
+        init_round<8>(va, n_pieces, P[7]);
+        // partial sums l and l+8 live 2 lanes-of-g apart (xor 32), l and l+4 one apart (xor 16)
+        const bool hi = g & 2, odd = g & 1;
+        float Q[4][4], R[2][4];
+#pragma unroll
+        for (int t = 0; t < 4; ++t)
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                const float keep = hi ? P[t + 4][k] : P[t][k], send = hi ? P[t][k] : P[t + 4][k];
+                Q[t][k] = keep + __shfl_xor(send, 32, EF_WAVE);
+            }
+#pragma unroll
+        for (int t = 0; t < 2; ++t)
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                const float keep = odd ? Q[t + 2][k] : Q[t][k], send = odd ? Q[t][k] : Q[t + 2][k];
+                R[t][k] = keep + __shfl_xor(send, 16, EF_WAVE);
+            }
+        __syncthreads();                  // uid, pools visible
+        // ---- candidates of row r16: rotations 2g+1, 2g+2, forwards and from the mirror lane ---
+        u64 key[4];
+        int lt[4];
+#pragma unroll
+        for (int t = 0; t < 2; ++t) {
+            const float dist = (R[t][0] + R[t][2]) + (R[t][1] + R[t][3]);
+            const int rot = 2 * g + 1 + t;
+            const int bf = (r16 + dirn * rot) & 15, br = (r16 - dirn * rot) & 15;
+            const float dist_r = __shfl(dist, br + 16 * g, EF_WAVE);     // lane br met r16 in this round
+            key[t] = r16 < s && bf < s ? ef_pack(dist, uid[bf], 1) : ~0ULL;
+            key[2 + t] = r16 < s && br < s && rot != 8 ? ef_pack(dist_r, uid[br], 1) : ~0ULL;
+        }
+        const u64 *row = pools + r16 * K;
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            int lo = 0, hi_ = K;
+            if (key[c] != ~0ULL && !first_tree) {
+                while (lo < hi_) {
+                    const int mid = (lo + hi_) >> 1;
+                    if (row[mid] < key[c]) lo = mid + 1;
+                    else hi_ = mid;
+                }
+                if (lo < K && row[lo] == key[c]) key[c] = ~0ULL;      // already there from an earlier tree
+            }
+            lt[c] = lo;
+            cand[r16 * kCandPitch + 4 * g + c] = key[c];
+        }
+        __syncthreads();
+        // ---- ranks ----------------------------------------------------------------------------
+        u64 cs[16];
+#pragma unroll
+        for (int o = 0; o < 16; ++o) cs[o] = cand[r16 * kCandPitch + o];
+        if (r16 < s) {
+            u64 *out = graph + (size_t)my_id * K;
+#pragma unroll
+            for (int c = 0; c < 4; ++c) {
+                if (key[c] == ~0ULL) continue;
+                int rank = lt[c];
+#pragma unroll
+                for (int o = 0; o < 16; ++o) rank += cs[o] < key[c] ? 1 : 0;
+                if (rank < K) out[rank] = key[c];
+            }
+            for (int j = g; j < K; j += 4) {
+                const u64 e = row[j];
+                int rank = j;
+#pragma unroll
+                for (int o = 0; o < 16; ++o) rank += cs[o] < e ? 1 : 0;
+                if (rank < K) out[rank] = e;
+            }
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------------------
 // Alg. 4 step 1+2: sample the new / old sets of every row, clear the sampled marks,
 // refresh the row's threshold and enter the row's id into the reverse lists of the
 // sampled neighbours.
@@ -1144,6 +1306,15 @@ extern "C" int efanna_init_graph(const float *X, int64_t n, int32_t d, const int
     const int stride = d + kRowPad;
     const size_t lds = (size_t)(align4(leaf_size * stride) + align4(leaf_size * leaf_size)) * 4 +
                        (size_t)leaf_size * k * 8 + (size_t)leaf_size * 4;
+    if (leaf_size <= 16 && d <= 128 && d % 4 == 0 && ((uintptr_t)X & 15) == 0) {
+        const size_t reg_lds = (size_t)16 * k * 8 + (size_t)16 * kCandPitch * 8 + 16 * 4;
+        for (int t = 0; t < n_trees; ++t)
+            init_reg_kernel<<<min(n_leaves[t], kRegGrid), EF_WAVE, reg_lds, st>>>(
+                X, d, perm + (size_t)t * n, leaf_off + (size_t)t * (max_leaves + 1), n_leaves[t], k,
+                graph, t == 0);
+        EF_HIP_CHECK(hipGetLastError());
+        return EFANNA_OK;
+    }
     if (lds > kLdsLimit) return EFANNA_EUNSUPPORTED;
     EF_HIP_CHECK(hipFuncSetAttribute((const void *)init_tree_kernel,
                                      hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));

@@ -136,6 +136,25 @@ def test_init_graph_odd_dimension_and_single_leaf(ef):
     assert np.array_equal(ids, tid)          # one leaf holding everything: the exact graph
 
 
+@pytest.mark.parametrize("d,S,K,T", [
+    (4, 16, 3, 3),          # one 16-byte piece per row
+    (20, 16, 10, 4),        # d a multiple of 4 but not of 16: ragged last piece
+    (100, 13, 10, 3),
+    (128, 16, 40, 5),       # K above the number of leaf mates of one tree: rows fill up over trees
+    (64, 2, 5, 6),          # leaves of one or two points
+])
+def test_init_graph_small_leaf_shapes(ef, d, S, K, T):
+    """Leaves of at most 16 points with d <= 128 take the kernel that keeps rows in registers."""
+    rng = np.random.default_rng(d * 131 + S)
+    X = rng.standard_normal((5_003, d)).astype(np.float32)
+    X[100:140] = X[100]                      # equal points: zero distances, ties broken by id
+    (perm, off, nl), (operm, ooff, onl) = trees_equal(ef, X, T, S, 11)
+    graph = ef.efanna_init_graph(dev(X), perm, off, nl, S, K)
+    want = oracle.init_graph(X, operm, ooff, onl, K)
+    ids, dists = graph_equal(ef, graph, want)
+    oracle.check_graph_invariants(X, ids, dists)
+
+
 @pytest.mark.parametrize("name,n,T,S,K,L,I", [
     ("gmm10k_d32", 10_000, 4, 8, 10, 10, 4),      # the small configuration as quoted
     ("sift100k_like", 20_000, 8, 16, 20, 20, 3),
