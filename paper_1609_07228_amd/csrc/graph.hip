@@ -200,12 +200,12 @@ init_tree_kernel(const float *__restrict__ X, int d, int stride, u32 q4_magic, i
 }
 
 // ---------------------------------------------------------------------------------------
-// The same step for leaves of at most 16 points and d <= 128 (d % 4 == 0, X 16-byte aligned),
-// without a row buffer: persistent waves, one leaf at a time.
+// The same step for leaves of at most 16 points (d % 4 == 0, X 16-byte aligned), without a
+// row buffer: persistent waves, one leaf at a time.
 //
 // Lane (r, g) = lane r + 16 g keeps, of member r of the leaf, the coordinates 16 s + 4 g + k
-// (s = 0..7, k = 0..3), i.e. the terms of partial sums 4g..4g+3 of the library's fixed
-// order.  Rotating the 16 lanes of a row by t (a DPP modifier, no memory traffic) puts
+// (s = 0..7, k = 0..3) of the current 128-coordinate piece, i.e. terms of partial sums
+// 4g..4g+3 of the library's fixed order.  Rotating the 16 lanes of a row by t (a DPP modifier, no memory traffic) puts
 // member r opposite member r +- t, so eight rotations meet all pairs of the leaf; the four
 // lanes of a column then add their partial sums in the fixed tree (8 apart, 4 apart, 2
 // apart, 1 apart), transposed so that lane (r, g) ends up with the distances of rotations
@@ -221,7 +221,6 @@ init_tree_kernel(const float *__restrict__ X, int d, int stride, u32 q4_magic, i
 template <int T>
 __device__ inline void init_round(const float4 (&va)[8], int n_pieces, float (&p)[4])
 {
-    p[0] = p[1] = p[2] = p[3] = 0.0f;
 #pragma unroll
     for (int s = 0; s < 8; ++s) {
         if (s >= n_pieces) break;
@@ -247,7 +246,6 @@ init_reg_kernel(const float *__restrict__ X, int d, const int *__restrict__ perm
     u64 *cand = pools + 16 * (size_t)K;               // [16][kCandPitch] candidates of each row
     int *uid = (int *)(cand + 16 * kCandPitch);       // [16]
     const int lane = threadIdx.x, r16 = lane & 15, g = lane >> 4;
-    const int n_pieces = (d + 15) >> 4;
     // which way the rotation moves data: lane r receives from lane r + dirn (mod 16)
     const int dirn = (EF_ROW_ROR(r16, 1) - r16) & 15;
     // leaf boundaries are fetched two leaves ahead and member ids one leaf ahead
@@ -262,14 +260,7 @@ init_reg_kernel(const float *__restrict__ X, int d, const int *__restrict__ perm
         const int s = s0, my_id = id_pre;
         __syncthreads();                  // the previous leaf's LDS reads are done
         if (g == 0) uid[r16] = my_id;
-        // operands and old rows of this leaf
-        float4 va[8];
-        const float *pa = X + (size_t)max(my_id, 0) * d + 4 * g;
-#pragma unroll
-        for (int q = 0; q < 8; ++q) {
-            const bool in = r16 < s && 16 * q + 4 * g + 3 < d;      // d % 4 == 0: a piece is in or out
-            va[q] = in ? *reinterpret_cast<const float4 *>(pa + 16 * q) : make_float4(0.f, 0.f, 0.f, 0.f);
-        }
+        // old rows of this leaf
         for (int c = g; c < K; c += 4)
             pools[r16 * K + c] = first_tree || r16 >= s ? ef_empty_entry(K - 1 - c)
                                                         : graph[(size_t)my_id * K + c];
@@ -280,16 +271,28 @@ init_reg_kernel(const float *__restrict__ X, int d, const int *__restrict__ perm
         leaf1 += gridDim.x;
         b1 = leaf1 < n_leaves ? leaf_off_t[leaf1] : 0;
         s1 = leaf1 < n_leaves ? min(leaf_off_t[leaf1 + 1] - b1, 16) : 0;
-        // ---- distances: rotations 1..8 ----------------------------------------------------
+        // ---- distances: rotations 1..8, 128 coordinates at a time ---------------------------
         float P[8][4];
-        init_round<1>(va, n_pieces, P[0]);
-        init_round<2>(va, n_pieces, P[1]);
-        init_round<3>(va, n_pieces, P[2]);
-        init_round<4>(va, n_pieces, P[3]);
-        init_round<5>(va, n_pieces, P[4]);
-        init_round<6>(va, n_pieces, P[5]);
-        init_round<7>(va, n_pieces, P[6]);
-        init_round<8>(va, n_pieces, P[7]);
+#pragma unroll
+        for (int t = 0; t < 8; ++t) P[t][0] = P[t][1] = P[t][2] = P[t][3] = 0.0f;
+        const float *pa = X + (size_t)max(my_id, 0) * d + 4 * g;
+        for (int c0 = 0; c0 < d; c0 += 128) {
+            float4 va[8];
+#pragma unroll
+            for (int q = 0; q < 8; ++q) {
+                const bool in = r16 < s && c0 + 16 * q + 4 * g + 3 < d;   // d % 4 == 0: a piece is in or out
+                va[q] = in ? *reinterpret_cast<const float4 *>(pa + c0 + 16 * q) : make_float4(0.f, 0.f, 0.f, 0.f);
+            }
+            const int n_pieces = min(8, (d - c0 + 15) >> 4);
+            init_round<1>(va, n_pieces, P[0]);
+            init_round<2>(va, n_pieces, P[1]);
+            init_round<3>(va, n_pieces, P[2]);
+            init_round<4>(va, n_pieces, P[3]);
+            init_round<5>(va, n_pieces, P[4]);
+            init_round<6>(va, n_pieces, P[5]);
+            init_round<7>(va, n_pieces, P[6]);
+            init_round<8>(va, n_pieces, P[7]);
+        }
         // partial sums l and l+8 live 2 lanes-of-g apart (xor 32), l and l+4 one apart (xor 16)
         const bool hi = g & 2, odd = g & 1;
         float Q[4][4], R[2][4];
@@ -1306,7 +1309,7 @@ extern "C" int efanna_init_graph(const float *X, int64_t n, int32_t d, const int
     const int stride = d + kRowPad;
     const size_t lds = (size_t)(align4(leaf_size * stride) + align4(leaf_size * leaf_size)) * 4 +
                        (size_t)leaf_size * k * 8 + (size_t)leaf_size * 4;
-    if (leaf_size <= 16 && d <= 128 && d % 4 == 0 && ((uintptr_t)X & 15) == 0) {
+    if (leaf_size <= 16 && d % 4 == 0 && ((uintptr_t)X & 15) == 0) {
         const size_t reg_lds = (size_t)16 * k * 8 + (size_t)16 * kCandPitch * 8 + 16 * 4;
         for (int t = 0; t < n_trees; ++t)
             init_reg_kernel<<<min(n_leaves[t], kRegGrid), EF_WAVE, reg_lds, st>>>(

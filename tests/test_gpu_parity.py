@@ -142,6 +142,7 @@ def test_init_graph_odd_dimension_and_single_leaf(ef):
     (100, 13, 10, 3),
     (128, 16, 40, 5),       # K above the number of leaf mates of one tree: rows fill up over trees
     (64, 2, 5, 6),          # leaves of one or two points
+    (200, 16, 10, 3),       # more than one 128-coordinate piece, the last one ragged
 ])
 def test_init_graph_small_leaf_shapes(ef, d, S, K, T):
     """Leaves of at most 16 points with d <= 128 take the kernel that keeps rows in registers."""
