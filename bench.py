@@ -53,6 +53,7 @@ def main():
     ap.add_argument("--cpu-rows", type=int, default=1_000_000,
                     help="rows of the workload the CPU oracle is timed on (0 = skip)")
     ap.add_argument("--recall-rows", type=int, default=10_000, help="0 = skip recall")
+    ap.add_argument("--progress", action="store_true", help="report each phase on stderr as it ends")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU; --gpus N with N > 1 is not supported "
@@ -70,6 +71,8 @@ def main():
     p = synth.params(name)
     X = synth.generate(name, n=args.n)
     n, d = X.shape
+    if args.progress:
+        print(f"generated {name}: {n} x {d}", file=sys.stderr, flush=True)
     K, T, S, I, L = p["K"], p["T"], p["S"], p["I"], p["L"]
     dev = torch.device("cuda:0")
     Xd = torch.from_numpy(X).to(dev)
@@ -102,6 +105,9 @@ def main():
         ids, dists = efanna.efanna_get_graph(graph)
         torch.cuda.synchronize()
         t4 = time.perf_counter()
+        if args.progress:
+            print(f"step: trees {t1 - t0:.3f} s, init {t2 - t1:.3f} s, nndescent {t3 - t2:.3f} s, "
+                  f"get {t4 - t3:.3f} s", file=sys.stderr, flush=True)
         if timed:
             phases[:] += (t1 - t0, t2 - t1, t3 - t2, t4 - t3)
             st = stats.cpu().numpy()

@@ -63,6 +63,140 @@ __device__ inline u32 ef_load_coherent(const u32 *p)
     return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
+// ---- coherent 16-byte row loads -----------------------------------------------------------
+// Graph rows and reverse lists are read while other waves update them, so the loads must come
+// from the point of coherence (as an agent-scope atomic load does), but the widest atomic
+// load is 8 bytes and every load is one transaction at the memory side.  Reading a row in
+// 16-byte pieces halves that count.  The compiler has no coherent 16-byte load, hence the
+// inline assembly: `NP` loads from p, p + 16, ... and the wait for them, in one statement
+// so that nothing can touch the destination registers before the data has arrived.
+typedef u32 ef_u32x4 __attribute__((ext_vector_type(4)));
+
+__device__ inline void ef_load_row_pieces_1(const void *p, ef_u32x4 (&q)[8])
+{
+    asm volatile(
+                     "global_load_dwordx4 %0, %1, off offset:0 sc1\n\t"
+                     "s_waitcnt vmcnt(0)"
+                 : "=&v"(q[0])
+                 : "v"(p)
+                 : "memory");
+}
+
+__device__ inline void ef_load_row_pieces_2(const void *p, ef_u32x4 (&q)[8])
+{
+    asm volatile(
+                     "global_load_dwordx4 %0, %2, off offset:0 sc1\n\t"
+                     "global_load_dwordx4 %1, %2, off offset:16 sc1\n\t"
+                     "s_waitcnt vmcnt(0)"
+                 : "=&v"(q[0]), "=&v"(q[1])
+                 : "v"(p)
+                 : "memory");
+}
+
+__device__ inline void ef_load_row_pieces_3(const void *p, ef_u32x4 (&q)[8])
+{
+    asm volatile(
+                     "global_load_dwordx4 %0, %3, off offset:0 sc1\n\t"
+                     "global_load_dwordx4 %1, %3, off offset:16 sc1\n\t"
+                     "global_load_dwordx4 %2, %3, off offset:32 sc1\n\t"
+                     "s_waitcnt vmcnt(0)"
+                 : "=&v"(q[0]), "=&v"(q[1]), "=&v"(q[2])
+                 : "v"(p)
+                 : "memory");
+}
+
+__device__ inline void ef_load_row_pieces_4(const void *p, ef_u32x4 (&q)[8])
+{
+    asm volatile(
+                     "global_load_dwordx4 %0, %4, off offset:0 sc1\n\t"
+                     "global_load_dwordx4 %1, %4, off offset:16 sc1\n\t"
+                     "global_load_dwordx4 %2, %4, off offset:32 sc1\n\t"
+                     "global_load_dwordx4 %3, %4, off offset:48 sc1\n\t"
+                     "s_waitcnt vmcnt(0)"
+                 : "=&v"(q[0]), "=&v"(q[1]), "=&v"(q[2]), "=&v"(q[3])
+                 : "v"(p)
+                 : "memory");
+}
+
+__device__ inline void ef_load_row_pieces_5(const void *p, ef_u32x4 (&q)[8])
+{
+    asm volatile(
+                     "global_load_dwordx4 %0, %5, off offset:0 sc1\n\t"
+                     "global_load_dwordx4 %1, %5, off offset:16 sc1\n\t"
+                     "global_load_dwordx4 %2, %5, off offset:32 sc1\n\t"
+                     "global_load_dwordx4 %3, %5, off offset:48 sc1\n\t"
+                     "global_load_dwordx4 %4, %5, off offset:64 sc1\n\t"
+                     "s_waitcnt vmcnt(0)"
+                 : "=&v"(q[0]), "=&v"(q[1]), "=&v"(q[2]), "=&v"(q[3]), "=&v"(q[4])
+                 : "v"(p)
+                 : "memory");
+}
+
+__device__ inline void ef_load_row_pieces_6(const void *p, ef_u32x4 (&q)[8])
+{
+    asm volatile(
+                     "global_load_dwordx4 %0, %6, off offset:0 sc1\n\t"
+                     "global_load_dwordx4 %1, %6, off offset:16 sc1\n\t"
+                     "global_load_dwordx4 %2, %6, off offset:32 sc1\n\t"
+                     "global_load_dwordx4 %3, %6, off offset:48 sc1\n\t"
+                     "global_load_dwordx4 %4, %6, off offset:64 sc1\n\t"
+                     "global_load_dwordx4 %5, %6, off offset:80 sc1\n\t"
+                     "s_waitcnt vmcnt(0)"
+                 : "=&v"(q[0]), "=&v"(q[1]), "=&v"(q[2]), "=&v"(q[3]), "=&v"(q[4]), "=&v"(q[5])
+                 : "v"(p)
+                 : "memory");
+}
+
+__device__ inline void ef_load_row_pieces_7(const void *p, ef_u32x4 (&q)[8])
+{
+    asm volatile(
+                     "global_load_dwordx4 %0, %7, off offset:0 sc1\n\t"
+                     "global_load_dwordx4 %1, %7, off offset:16 sc1\n\t"
+                     "global_load_dwordx4 %2, %7, off offset:32 sc1\n\t"
+                     "global_load_dwordx4 %3, %7, off offset:48 sc1\n\t"
+                     "global_load_dwordx4 %4, %7, off offset:64 sc1\n\t"
+                     "global_load_dwordx4 %5, %7, off offset:80 sc1\n\t"
+                     "global_load_dwordx4 %6, %7, off offset:96 sc1\n\t"
+                     "s_waitcnt vmcnt(0)"
+                 : "=&v"(q[0]), "=&v"(q[1]), "=&v"(q[2]), "=&v"(q[3]), "=&v"(q[4]), "=&v"(q[5]), "=&v"(q[6])
+                 : "v"(p)
+                 : "memory");
+}
+
+__device__ inline void ef_load_row_pieces_8(const void *p, ef_u32x4 (&q)[8])
+{
+    asm volatile(
+                     "global_load_dwordx4 %0, %8, off offset:0 sc1\n\t"
+                     "global_load_dwordx4 %1, %8, off offset:16 sc1\n\t"
+                     "global_load_dwordx4 %2, %8, off offset:32 sc1\n\t"
+                     "global_load_dwordx4 %3, %8, off offset:48 sc1\n\t"
+                     "global_load_dwordx4 %4, %8, off offset:64 sc1\n\t"
+                     "global_load_dwordx4 %5, %8, off offset:80 sc1\n\t"
+                     "global_load_dwordx4 %6, %8, off offset:96 sc1\n\t"
+                     "global_load_dwordx4 %7, %8, off offset:112 sc1\n\t"
+                     "s_waitcnt vmcnt(0)"
+                 : "=&v"(q[0]), "=&v"(q[1]), "=&v"(q[2]), "=&v"(q[3]), "=&v"(q[4]), "=&v"(q[5]), "=&v"(q[6]), "=&v"(q[7])
+                 : "v"(p)
+                 : "memory");
+}
+
+// pieces 0..np-1 of the row at p (16-byte aligned) into q; the rest of q is zero
+__device__ inline void ef_load_row_pieces(const void *p, int np, ef_u32x4 (&q)[8])
+{
+#pragma unroll
+    for (int k = 0; k < 8; ++k) q[k] = (ef_u32x4){0u, 0u, 0u, 0u};
+    switch (np) {
+    case 1: ef_load_row_pieces_1(p, q); break;
+    case 2: ef_load_row_pieces_2(p, q); break;
+    case 3: ef_load_row_pieces_3(p, q); break;
+    case 4: ef_load_row_pieces_4(p, q); break;
+    case 5: ef_load_row_pieces_5(p, q); break;
+    case 6: ef_load_row_pieces_6(p, q); break;
+    case 7: ef_load_row_pieces_7(p, q); break;
+    default: ef_load_row_pieces_8(p, q); break;
+    }
+}
+
 // ---- lock-free bounded insertion ---------------------------------------------------------
 // `list` holds `cap` distinct 64-bit keys.  The call makes the list hold the `cap`
 // smallest keys of (list U {key}), where two keys are the same element when they agree
@@ -86,12 +220,23 @@ __device__ inline bool ef_bounded_insert(u64 *list, int cap, u64 key, int ignore
         u64 mx = 0, mx2 = 0;
         int ms = 0;
         bool dup = false;
-        // sixteen slot reads in flight at a time: a row of up to 16 entries costs one memory
-        // round trip instead of one per slot
+        // sixteen slots in flight at a time: a row of up to 16 entries costs one memory round
+        // trip instead of one per slot
+        const bool wide = (cap & 1) == 0 && ((uintptr_t)list & 15) == 0;
         for (int s0 = 0; s0 < cap; s0 += 16) {
             u64 e[16];
+            if (wide) {      // even length, 16-byte aligned: eight 16-byte pieces
+                ef_u32x4 q[8];
+                ef_load_row_pieces(list + s0, min(8, (cap - s0) >> 1), q);
 #pragma unroll
-            for (int k = 0; k < 16; ++k) e[k] = s0 + k < cap ? ef_load_coherent(list + s0 + k) : 0;
+                for (int k = 0; k < 8; ++k) {
+                    e[2 * k] = ((u64)q[k].y << 32) | q[k].x;
+                    e[2 * k + 1] = ((u64)q[k].w << 32) | q[k].z;
+                }
+            } else {
+#pragma unroll
+                for (int k = 0; k < 16; ++k) e[k] = s0 + k < cap ? ef_load_coherent(list + s0 + k) : 0;
+            }
 #pragma unroll
             for (int k = 0; k < 16; ++k) {
                 if (s0 + k >= cap) break;
