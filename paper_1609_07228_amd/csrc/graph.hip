@@ -13,6 +13,7 @@ namespace {
 
 constexpr int kBlock = 256;
 constexpr int kRegGrid = 256 * 32;     // blocks of the register-operand join kernels
+constexpr int kMaxLargeGrid = 256 * 32 * 2;     // most blocks the LDS-row join kernel is launched with
 constexpr int kRowPad = 4;   // floats appended to each LDS row
 
 inline size_t align_up(size_t x) { return (x + 255) & ~(size_t)255; }
@@ -25,10 +26,13 @@ __host__ __device__ inline int align4(int x) { return (x + 3) & ~3; }
 
 // reverse lists: slot s of an empty list holds ~0 - s (above every real key)
 __global__ void fill_reverse_kernel(u64 *a, u64 *b, size_t total, int L, int *a_count, int *b_count,
-                                    u64 *list_max, size_t n, int *work_count)
+                                    u64 *list_max, size_t n, int *work_count, int *upd_block,
+                                    int n_upd_block)
 {
     size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (i < 8) work_count[i] = 0;     // three work lists
+    // insertion counts of join blocks: kernels that are not launched leave theirs at zero
+    for (size_t j = i; j < (size_t)n_upd_block; j += (size_t)gridDim.x * blockDim.x) upd_block[j] = 0;
     if (i < n) {
         a_count[i] = 0;
         b_count[i] = 0;
@@ -581,14 +585,14 @@ __global__ void prepare_kernel(const int *__restrict__ nw, const int *__restrict
                                int n, int K, int L, int cap, u32 cap_magic, int rows0, int rows1,
                                int *__restrict__ ulist, int2 *__restrict__ ucount,
                                int *__restrict__ work, int *__restrict__ work_count,
-                               int *__restrict__ cnt_evals, int *__restrict__ cnt_upd,
-                               int *__restrict__ cnt_rows)
+                               long long *__restrict__ part)
 {
     extern __shared__ int ids_sh[];
     const int pitch = cap | 1;                      // odd: threads hit different banks
     int *mine = ids_sh + threadIdx.x * pitch;
     const int i = blockIdx.x * blockDim.x + threadIdx.x;
     int cls = -1, m = 0;
+    int evals = 0, rows = 0;      // this point's share of the iteration's work counters
     if (i < n) {
         const int c_new = nw_c[i];
         int c_old = od_c[i];
@@ -616,13 +620,10 @@ __global__ void prepare_kernel(const int *__restrict__ nw, const int *__restrict
             if (!dup) mine[m++] = id;
         }
         ucount[i] = make_int2(m_new, m);
-        cnt_upd[i] = 0;      // only the joins through the LDS row buffer count per point
         if (m_new >= 1 && m >= 2) {
             cls = m <= rows0 ? 0 : (m <= rows1 ? 1 : 2);
-            cnt_evals[i] = m_new * (m_new - 1) / 2 + m_new * (m - m_new);
-            cnt_rows[i] = m;
-        } else {
-            cnt_evals[i] = cnt_rows[i] = 0;
+            evals = m_new * (m_new - 1) / 2 + m_new * (m - m_new);
+            rows = m;
         }
     }
     for (int k = m; k < cap; ++k) mine[k] = -1;
@@ -636,6 +637,7 @@ __global__ void prepare_kernel(const int *__restrict__ nw, const int *__restrict
     // append to the work lists: ranks inside the block first, then one counter bump per
     // list and block (bumps of one address serialise at about 11 ns each)
     __shared__ int wave_cnt[3][kBlock / EF_WAVE], block_base[3];
+    __shared__ int wave_sum[3][kBlock / EF_WAVE];
     const int lane = ef_lane(), wave = threadIdx.x / EF_WAVE, n_waves = blockDim.x / EF_WAVE;
     int rank = 0;
 #pragma unroll
@@ -644,11 +646,25 @@ __global__ void prepare_kernel(const int *__restrict__ nw, const int *__restrict
         if (cls == c) rank = __popcll(mask & ((1ULL << lane) - 1));
         if (lane == 0) wave_cnt[c][wave] = __popcll(mask);
     }
+    // the block's share of the counters: pairs evaluated, vectors gathered, vectors gathered by
+    // joins of at most rows0 vectors (a block's totals fit 32 bits)
+    const int s_ev = ef_wave_sum_i32(evals), s_rw = ef_wave_sum_i32(rows),
+              s_r0 = ef_wave_sum_i32(cls == 0 ? rows : 0);
+    if (lane == 0) {
+        wave_sum[0][wave] = s_ev;
+        wave_sum[1][wave] = s_rw;
+        wave_sum[2][wave] = s_r0;
+    }
     __syncthreads();
     if (threadIdx.x < 3) {
         int tot = 0;
-        for (int v = 0; v < n_waves; ++v) tot += wave_cnt[threadIdx.x][v];
+        long long sum = 0;
+        for (int v = 0; v < n_waves; ++v) {
+            tot += wave_cnt[threadIdx.x][v];
+            sum += wave_sum[threadIdx.x][v];
+        }
         block_base[threadIdx.x] = tot ? atomicAdd(&work_count[threadIdx.x], tot) : 0;
+        part[(size_t)blockIdx.x * 3 + threadIdx.x] = sum;
     }
     __syncthreads();
     if (cls >= 0) {
@@ -710,7 +726,7 @@ __global__ void join_kernel(const float *__restrict__ X, const float *__restrict
                             const int *__restrict__ work, const int *__restrict__ work_count,
                             int cap_rows, int s_cap, int q_cap, float margin_rel, float thr_scale,
                             const int *__restrict__ ulist, const int2 *__restrict__ ucount,
-                            int ucap, u64 *graph, u32 *worst, int *__restrict__ cnt_upd)
+                            int ucap, u64 *graph, u32 *worst, int *__restrict__ upd_block)
 {
     extern __shared__ __align__(16) float smem[];
     const JoinLds lds = join_lds_carve(smem, cap_rows, stride, s_cap);
@@ -718,6 +734,7 @@ __global__ void join_kernel(const float *__restrict__ X, const float *__restrict
     const int lane = tid & (EF_WAVE - 1), wave = tid / EF_WAVE, n_waves = nthr / EF_WAVE;
     const int grp = tid >> 4, gl = tid & 15, n_grp = nthr >> 4;
     const int count = *work_count;
+    int block_updates = 0;      // thread 0: insertions made by this block
     for (int w = blockIdx.x; w < count; w += gridDim.x) {
         const int i = work[w];
         // ---- 0. the point's U_new ++ U_old ------------------------------------------------
@@ -827,9 +844,10 @@ __global__ void join_kernel(const float *__restrict__ X, const float *__restrict
         }
         if (updates) atomicAdd(&lds.meta[2], updates);
         __syncthreads();
-        if (tid == 0) cnt_upd[i] = lds.meta[2];
+        if (tid == 0) block_updates += lds.meta[2];
         __syncthreads();
     }
+    if (tid == 0) upd_block[blockIdx.x] = block_updates;
 }
 
 // ---------------------------------------------------------------------------------------
@@ -893,7 +911,7 @@ join_reg_kernel(const float *__restrict__ X, const float *__restrict__ norms, in
         i_next = w + 2 * (int)gridDim.x < count ? work[w + 2 * gridDim.x] : -1;
         if (lane < m) {
             const int id = uid[lane];
-            const u32 t = ef_load_coherent(worst + id);
+            const u32 t = worst[id];
             thr[lane] = t;
             tf[lane] = __uint_as_float(t) * thr_scale;
             nf[lane] = norms[id] * (1.0f - margin_rel);
@@ -1113,20 +1131,20 @@ __global__ void norms_kernel(const float *__restrict__ X, int n, int d, float *_
     if (g < (size_t)n && gl == 0) norms[g] = acc;
 }
 
-__global__ void stats_kernel(const int *__restrict__ cnt_evals, const int *__restrict__ cnt_upd,
-                             const int *__restrict__ cnt_rows, int n, int rows0,
+// per-iteration counters from the per-block partial sums: part[b] = (pairs evaluated, vectors
+// gathered, vectors gathered by the smallest join class) of prepare block b; upd_block: insertions
+// per join block
+__global__ void stats_kernel(const long long *__restrict__ part, int n_part,
                              const int *__restrict__ upd_block, int n_upd_block, u64 *stats)
 {
     long long ev = 0, up = 0, rw = 0, r0 = 0;
     const int t = blockIdx.x * blockDim.x + threadIdx.x, nt = gridDim.x * blockDim.x;
-    for (int i = t; i < n; i += nt) {
-        ev += cnt_evals[i];
-        up += cnt_upd[i];
-        const int rows = cnt_rows[i];
-        rw += rows;
-        r0 += rows <= rows0 ? rows : 0;
+    for (int b = t; b < n_part; b += nt) {
+        ev += part[(size_t)b * 3];
+        rw += part[(size_t)b * 3 + 1];
+        r0 += part[(size_t)b * 3 + 2];
     }
-    for (int b = t; b < n_upd_block; b += nt) up += upd_block[b];   // joins that count per block
+    for (int b = t; b < n_upd_block; b += nt) up += upd_block[b];
     ev = ef_wave_sum_i64(ev);
     up = ef_wave_sum_i64(up);
     rw = ef_wave_sum_i64(rw);
@@ -1211,10 +1229,11 @@ __global__ void pair_distances_kernel(const float *__restrict__ X, int d,
 }
 
 struct NndWs {
-    int *nw, *od, *nw_c, *od_c, *cnt_evals, *cnt_upd, *cnt_rows, *work, *work_count, *rnew_c, *rold_c, *overflow_rows, *ulist, *upd_block;
+    int *nw, *od, *nw_c, *od_c, *work, *work_count, *rnew_c, *rold_c, *overflow_rows, *ulist, *upd_block;
     int2 *ucount;
     void *overflow;
     u64 *rnew, *rold, *list_max, *active;
+    long long *part;
     u32 *worst;
     float *norms;
     size_t bytes;
@@ -1234,9 +1253,7 @@ NndWs carve_nnd(void *ws, int64_t n, int K, int L)
     w.od = (int *)take((size_t)n * K * 4);
     w.nw_c = (int *)take((size_t)n * 4);
     w.od_c = (int *)take((size_t)n * 4);
-    w.cnt_evals = (int *)take((size_t)n * 4);
-    w.cnt_upd = (int *)take((size_t)n * 4);
-    w.cnt_rows = (int *)take((size_t)n * 4);
+    w.part = (long long *)take(((size_t)n / EF_WAVE + 1) * 3 * 8);      // prepare blocks hold >= 64 points
     w.work = (int *)take((size_t)n * 3 * 4);
     w.work_count = (int *)take(8 * 4);     // [0..2] list sizes
     w.rnew_c = (int *)take((size_t)n * 4);
@@ -1245,7 +1262,7 @@ NndWs carve_nnd(void *ws, int64_t n, int K, int L)
     w.overflow_rows = (int *)take((size_t)n * 4);
     w.ulist = (int *)take((size_t)n * (K + 2 * L) * 4);
     w.ucount = (int2 *)take((size_t)n * 8);
-    w.upd_block = (int *)take((size_t)2 * kRegGrid * 4);
+    w.upd_block = (int *)take((size_t)(2 * kRegGrid + kMaxLargeGrid) * 4);
     w.rnew = (u64 *)take((size_t)n * L * 8);
     w.rold = (u64 *)take((size_t)n * L * 8);
     w.list_max = (u64 *)take((size_t)n * 2 * 8);
@@ -1425,7 +1442,8 @@ extern "C" int efanna_nndescent(const float *X, int64_t n, int32_t d, int32_t k,
         const int g = first_iter + it;
         if (ev) EF_HIP_CHECK(hipEventRecord(ev[5 * it], st));
         fill_reverse_kernel<<<grid_for((size_t)n * L, kBlock), kBlock, 0, st>>>(
-            w.rnew, w.rold, (size_t)n * L, L, w.rnew_c, w.rold_c, w.list_max, (size_t)n, w.work_count);
+            w.rnew, w.rold, (size_t)n * L, L, w.rnew_c, w.rold_c, w.list_max, (size_t)n, w.work_count,
+            w.upd_block, 2 * kRegGrid + kMaxLargeGrid);
         {
             const u64 kn = ef_stream_key(seed, 2 * g), ko = ef_stream_key(seed, 2 * g + 1);
             Overflow *ovf = (Overflow *)w.overflow;
@@ -1453,7 +1471,7 @@ extern "C" int efanna_nndescent(const float *X, int64_t n, int32_t d, int32_t k,
         }
         prepare_kernel<<<grid_for((size_t)n, prep_threads), prep_threads, prep_lds, st>>>(
             w.nw, w.od, w.nw_c, w.od_c, w.rnew, w.rold, w.rnew_c, w.rold_c, (int)n, K, L, max_rows,
-            (u32)(((1ULL << 32) + max_rows - 1) / max_rows), rows0, rows1, w.ulist, w.ucount, w.work, w.work_count, w.cnt_evals, w.cnt_upd, w.cnt_rows);
+            (u32)(((1ULL << 32) + max_rows - 1) / max_rows), rows0, rows1, w.ulist, w.ucount, w.work, w.work_count, w.part);
         if (ev) EF_HIP_CHECK(hipEventRecord(ev[5 * it + 1], st));
         if (reg_ok) {
 #define EF_JOIN_REG(NB, ONE, LIST)                                                                 \
@@ -1477,12 +1495,11 @@ extern "C" int efanna_nndescent(const float *X, int64_t n, int32_t d, int32_t k,
             join_kernel<<<large.grid, large.threads, large.lds, st>>>(
                 X, w.norms, d, dpad, stride, q4_magic_for(d), K, w.work + 2 * (size_t)n,
                 w.work_count + 2, large.cap_rows, large.s_cap, large.q_cap, margin_rel, thr_scale,
-                w.ulist, w.ucount, max_rows, graph, w.worst, w.cnt_upd);
+                w.ulist, w.ucount, max_rows, graph, w.worst, w.upd_block + 2 * reg_grid);
         if (ev) EF_HIP_CHECK(hipEventRecord(ev[5 * it + 4], st));
         if (stats)
-            stats_kernel<<<256, kBlock, 0, st>>>(w.cnt_evals, w.cnt_upd, w.cnt_rows, (int)n, rows0,
-                                                 w.upd_block, reg_ok ? (max_rows > 16 ? 2 : 1) * reg_grid : 0,
-                                                 stats + 4 * it);
+            stats_kernel<<<16, kBlock, 0, st>>>(w.part, grid_for((size_t)n, prep_threads), w.upd_block,
+                                                2 * reg_grid + kMaxLargeGrid, stats + 4 * it);
     }
     EF_HIP_CHECK(hipGetLastError());
     if (ev) {
