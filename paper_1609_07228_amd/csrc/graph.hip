@@ -550,24 +550,26 @@ reverse_old_kernel(const int *__restrict__ od, int n, int K, int L, u64 key_old,
     if (row_ok && gl == 0 && n_parked != first) overflow_rows[i] = n_parked;
 }
 
-// one thread per (row, parked key): thread t serves key t % 2^kp_log of row t >> kp_log.
-// list_max[which][v] is an upper bound of the largest key of (full) list v, lowered after
-// every successful insertion: the many keys offered to a popular point are turned away
-// after one read instead of a scan of the list.
+// Four threads per row: thread t serves parked keys t % 4, t % 4 + 4, ... of row t / 4 (most
+// rows park fewer than four keys).  list_max[which][v] is an upper bound of the largest key of
+// (full) list v, lowered after every successful insertion: the many keys offered to a popular
+// point are turned away after one read instead of a scan of the list.
 __global__ void reverse_overflow_kernel(const Overflow *__restrict__ overflow,
                                         const int *__restrict__ overflow_rows, int n, int K,
-                                        int kp_log, u64 *rnew, u64 *rold, u64 *list_max, int L)
+                                        u64 *rnew, u64 *rold, u64 *list_max, int L)
 {
     const size_t t = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
-    const size_t i = t >> kp_log;
-    const int j = (int)(t & ((1u << kp_log) - 1));
-    if (i >= (size_t)n || j >= overflow_rows[i]) return;
-    const Overflow ov = overflow[i * K + j];
-    u64 *bound = list_max + (size_t)ov.which * n + ov.target;
-    if (ov.key >= ef_load_coherent(bound)) return;
-    u64 nm;
-    if (ef_bounded_insert((ov.which ? rold : rnew) + (size_t)ov.target * L, L, ov.key, 0, &nm))
-        atomicMin(bound, nm);
+    const size_t i = t >> 2;
+    if (i >= (size_t)n) return;
+    const int parked = overflow_rows[i];
+    for (int j = (int)(t & 3); j < parked; j += 4) {
+        const Overflow ov = overflow[i * K + j];
+        u64 *bound = list_max + (size_t)ov.which * n + ov.target;
+        if (ov.key >= ef_load_coherent(bound)) continue;
+        u64 nm;
+        if (ef_bounded_insert((ov.which ? rold : rnew) + (size_t)ov.target * L, L, ov.key, 0, &nm))
+            atomicMin(bound, nm);
+    }
 }
 
 // After sampling and the reverse lists: one thread per point merges its four id lists
@@ -1464,10 +1466,8 @@ extern "C" int efanna_nndescent(const float *X, int64_t n, int32_t d, int32_t k,
             else EF_REVERSE_OLD(64);
 #undef EF_SAMPLE
 #undef EF_REVERSE_OLD
-            int kp_log = 0;
-            while ((1 << kp_log) < K) ++kp_log;
-            reverse_overflow_kernel<<<grid_for((size_t)n << kp_log, kBlock), kBlock, 0, st>>>(
-                ovf, w.overflow_rows, (int)n, K, kp_log, w.rnew, w.rold, w.list_max, L);
+            reverse_overflow_kernel<<<grid_for((size_t)n * 4, kBlock), kBlock, 0, st>>>(
+                ovf, w.overflow_rows, (int)n, K, w.rnew, w.rold, w.list_max, L);
         }
         prepare_kernel<<<grid_for((size_t)n, prep_threads), prep_threads, prep_lds, st>>>(
             w.nw, w.od, w.nw_c, w.od_c, w.rnew, w.rold, w.rnew_c, w.rold_c, (int)n, K, L, max_rows,
