@@ -389,12 +389,12 @@ struct Overflow {
 };
 
 // Offer `key` to reverse list v.  Returns true if the list had no free slot: the caller
-// parks the key for reverse_overflow_kernel.
+// parks the key for reverse_overflow_kernel.  Every offer bumps the list's counter, full or
+// not: a read beforehand to spare full lists the bump costs more transactions than it saves
+// (bumps of one counter serialise at about 11 ns each, so a point that is the neighbour of
+// c others costs c * 11 ns at worst).
 __device__ inline bool reverse_offer(u64 *lists, int *counts, int L, int v, u64 key)
 {
-    // a list that is already full is not bumped again: popular points would otherwise
-    // serialise thousands of atomics on one counter
-    if (ef_load_coherent((const u32 *)&counts[v]) >= (u32)L) return true;
     const int pos = atomicAdd(&counts[v], 1);
     if (pos >= L) return true;
     lists[(size_t)v * L + pos] = key;
