@@ -37,6 +37,15 @@ def _load():
         lib.oracle_build_trees.restype = C.c_int
         lib.oracle_build_trees.argtypes = [C.c_void_p, C.c_int64, C.c_int32, C.c_int32, C.c_int32,
                                            C.c_uint64, C.c_void_p, C.c_void_p, C.c_void_p]
+        lib.oracle_build_trees_nodes.restype = C.c_int
+        lib.oracle_build_trees_nodes.argtypes = [C.c_void_p, C.c_int64, C.c_int32, C.c_int32, C.c_int32,
+                                                 C.c_uint64, C.c_void_p, C.c_void_p, C.c_void_p,
+                                                 C.c_void_p, C.c_void_p]
+        lib.oracle_conquer_graph.restype = C.c_int
+        lib.oracle_conquer_graph.argtypes = [C.c_void_p, C.c_int64, C.c_int32, C.c_void_p, C.c_void_p,
+                                             C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32,
+                                             C.c_int32, C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p,
+                                             C.c_void_p]
         lib.oracle_init_graph.restype = C.c_int
         lib.oracle_init_graph.argtypes = [C.c_void_p, C.c_int64, C.c_int32, C.c_void_p, C.c_void_p,
                                           C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_int64,
@@ -95,6 +104,54 @@ def build_trees(X, T: int, S: int, seed: int):
     if rc != 0:
         raise ValueError(f"oracle_build_trees failed: {rc}")
     return perm, leaf_off, n_leaves
+
+
+# one internal node of a tree, numbered by the leaf that starts its right part
+NODE_DTYPE = np.dtype([("sum", np.int64), ("dim", np.int32), ("cnt", np.int32), ("parent", np.int32),
+                       ("depth", np.int32), ("child", np.int32, (2,))], align=True)
+assert NODE_DTYPE.itemsize == 32
+
+
+def build_trees_nodes(X, T: int, S: int, seed: int):
+    """Alg. 2 with the internal nodes kept for the conquer step of Alg. 3.  Returns (perm,
+    leaf_off, n_leaves, nodes [T,n+1] NODE_DTYPE, leaf_up [T,n+1] int32)."""
+    X = _f32(X)
+    n, d = X.shape
+    perm = np.empty((T, n), dtype=np.int32)
+    leaf_off = np.full((T, n + 1), -1, dtype=np.int32)
+    n_leaves = np.zeros(T, dtype=np.int32)
+    nodes = np.zeros((T, n + 1), dtype=NODE_DTYPE)
+    leaf_up = np.full((T, n + 1), -1, dtype=np.int32)
+    rc = _load().oracle_build_trees_nodes(_p(X), n, d, T, S, seed, _p(perm), _p(leaf_off),
+                                          _p(n_leaves), _p(nodes), _p(leaf_up))
+    if rc != 0:
+        raise ValueError(f"oracle_build_trees_nodes failed: {rc}")
+    return perm, leaf_off, n_leaves, nodes, leaf_up
+
+
+def conquer_graph(X, perm, leaf_off, n_leaves, nodes, leaf_up, dep: int, K: int, rows=None):
+    """Alg. 3 with conquer-to depth `dep` (root = 0).  Returns (ids, dists, flags), each
+    [n_rows, K]."""
+    X = _f32(X)
+    n, d = X.shape
+    T = perm.shape[0]
+    assert perm.shape == (T, n) and leaf_off.shape == (T, n + 1)
+    assert nodes.shape == (T, n + 1) and nodes.dtype == NODE_DTYPE and leaf_up.shape == (T, n + 1)
+    rows_arr = None if rows is None else np.ascontiguousarray(rows, dtype=np.int64)
+    m = n if rows_arr is None else rows_arr.shape[0]
+    ids = np.empty((m, K), dtype=np.int32)
+    dists = np.empty((m, K), dtype=np.float32)
+    flags = np.empty((m, K), dtype=np.uint8)
+    rc = _load().oracle_conquer_graph(_p(X), n, d, _p(np.ascontiguousarray(perm)),
+                                      _p(np.ascontiguousarray(leaf_off)),
+                                      _p(np.ascontiguousarray(n_leaves)),
+                                      _p(np.ascontiguousarray(nodes)),
+                                      _p(np.ascontiguousarray(leaf_up)), dep, T, K,
+                                      None if rows_arr is None else _p(rows_arr), m,
+                                      _p(ids), _p(dists), _p(flags))
+    if rc != 0:
+        raise ValueError(f"oracle_conquer_graph failed: {rc}")
+    return ids, dists, flags
 
 
 def init_graph(X, perm, leaf_off, n_leaves, K: int, rows=None):

@@ -1,8 +1,9 @@
 /*
  * CPU oracle for approximate kNN-graph construction (EFANNA, arXiv 1609.07228):
- * randomized truncated KD-trees (Alg. 2), leaf-level conquer step of the
- * divide-and-conquer initialisation (Alg. 3 with the conquer depth at the leaves)
- * and NN-descent refinement (Alg. 4).
+ * randomized truncated KD-trees (Alg. 2), the conquer step of the
+ * divide-and-conquer initialisation (Alg. 3: the point's own leaf in every tree
+ * and, above the conquer-to depth, one leaf of every sibling subtree on the way
+ * up) and NN-descent refinement (Alg. 4).
  *
  * THIS IS TEST INFRASTRUCTURE.  It is a plain, slow, step-by-step statement of
  * what the method computes, used only to check the GPU library and to serve as
@@ -93,6 +94,19 @@ float oracle_dist(const float *a, const float *b, int32_t d)
 
 static int64_t quantise(float x) { return (int64_t)rint((double)x * 1048576.0); }
 
+/* An internal node as the conquer step of Alg. 3 needs it: the split test
+ * (dimension, sum of quantised coordinates, population: a point x goes left iff
+ * cnt*q(x[dim]) < sum), its depth (root 0), and links.  Internal nodes are
+ * numbered by the index of the leaf that starts their right part (1 ..
+ * n_leaves-1: every boundary between two leaves is the split point of exactly
+ * one internal node); child[s] >= 0 is such a number, child[s] < 0 is ~(leaf
+ * index); parent is -1 at the root. */
+typedef struct {
+    int64_t sum;
+    int32_t dim, cnt, parent, depth;
+    int32_t child[2];
+} oracle_node;
+
 typedef struct {
     const float *X;
     int64_t n;
@@ -102,19 +116,24 @@ typedef struct {
     int32_t *tmp;      /* scratch of n ids */
     int32_t *leaf_off; /* this tree's leaf offsets */
     int32_t n_leaves;
+    oracle_node *rec;  /* NULL, or n+1 records indexed by the position where the right part starts */
+    int32_t *leaf_rec; /* NULL, or for the leaf starting at position b: parent position * 2 + side */
 } tree_ctx;
 
-static void build_node(tree_ctx *c, uint64_t heap_id, int32_t depth, int64_t b, int64_t e)
+/* Returns the position where the node's right part starts (internal node) or
+ * ~(start position) for a leaf; the caller links it. */
+static int64_t build_node(tree_ctx *c, uint64_t heap_id, int32_t depth, int64_t b, int64_t e)
 {
     int64_t cnt = e - b;
     if (cnt <= c->S) { /* leaf: record where it starts */
         c->leaf_off[c->n_leaves++] = (int32_t)b;
-        return;
+        return ~b;
     }
     int64_t mid = b; /* first position of the right part */
+    int32_t dim = -1;
+    int64_t sum = 0;
     if (depth < 60) {
-        int32_t dim = (int32_t)(oracle_node_rand(c->seed, c->tree, heap_id) % (uint64_t)c->d);
-        int64_t sum = 0;
+        dim = (int32_t)(oracle_node_rand(c->seed, c->tree, heap_id) % (uint64_t)c->d);
         for (int64_t p = b; p < e; ++p) sum += quantise(c->X[(int64_t)c->perm[p] * c->d + dim]);
         int64_t nl = 0, nr = 0;
         for (int64_t p = b; p < e; ++p) { /* stable: both parts keep their order */
@@ -128,28 +147,76 @@ static void build_node(tree_ctx *c, uint64_t heap_id, int32_t depth, int64_t b, 
     if (mid == b || mid == e) mid = b + cnt / 2; /* degenerate: positional halves */
     /* heap ids past depth 60 are never used for a draw; keep them from wrapping */
     uint64_t child = depth < 60 ? 2 * heap_id : heap_id;
-    build_node(c, child, depth + 1, b, mid);
-    build_node(c, child + 1, depth + 1, mid, e);
+    int64_t kid[2];
+    kid[0] = build_node(c, child, depth + 1, b, mid);
+    kid[1] = build_node(c, child + 1, depth + 1, mid, e);
+    if (c->rec) {
+        oracle_node *r = &c->rec[mid];
+        r->sum = sum;
+        r->dim = dim;
+        r->cnt = (int32_t)cnt;
+        r->depth = depth;
+        r->parent = -1; /* the parent fills this in */
+        for (int s = 0; s < 2; ++s) {
+            r->child[s] = (int32_t)kid[s];
+            if (kid[s] >= 0) c->rec[kid[s]].parent = (int32_t)mid;
+            else c->leaf_rec[~kid[s]] = (int32_t)(mid * 2 + s);
+        }
+    }
+    return mid;
 }
 
 /* perm: [T][n] ids, leaves contiguous, left-to-right.  leaf_off: [T][n+1] start
- * position of every leaf, terminated by n.  n_leaves: [T]. */
-int oracle_build_trees(const float *X, int64_t n, int32_t d, int32_t T, int32_t S, uint64_t seed,
-                       int32_t *perm, int32_t *leaf_off, int32_t *n_leaves)
+ * position of every leaf, terminated by n.  n_leaves: [T].
+ * nodes (may be NULL): [T][n+1] internal nodes, numbered as described at
+ * oracle_node; leaf_up (NULL iff nodes is): [T][n+1], for leaf l the number of its
+ * parent node * 2 + (1 if l is the right child), -1 if the tree is one leaf. */
+int oracle_build_trees_nodes(const float *X, int64_t n, int32_t d, int32_t T, int32_t S,
+                             uint64_t seed, int32_t *perm, int32_t *leaf_off, int32_t *n_leaves,
+                             oracle_node *nodes, int32_t *leaf_up)
 {
-    if (!X || n < 1 || d < 1 || T < 1 || S < 1) return -1;
+    if (!X || n < 1 || d < 1 || T < 1 || S < 1 || (!nodes) != (!leaf_up)) return -1;
     int32_t *tmp = (int32_t *)malloc((size_t)n * sizeof(int32_t));
-    if (!tmp) return -4;
+    oracle_node *rec = nodes ? (oracle_node *)malloc((size_t)(n + 1) * sizeof(oracle_node)) : NULL;
+    int32_t *leaf_rec = nodes ? (int32_t *)malloc((size_t)(n + 1) * sizeof(int32_t)) : NULL;
+    int32_t *lidx = nodes ? (int32_t *)malloc((size_t)(n + 1) * sizeof(int32_t)) : NULL;
+    if (!tmp || (nodes && (!rec || !leaf_rec || !lidx))) return -4;
     for (int32_t t = 0; t < T; ++t) {
         tree_ctx c = {X, n, d, S, t, seed, perm + (int64_t)t * n, tmp,
-                      leaf_off + (int64_t)t * (n + 1), 0};
+                      leaf_off + (int64_t)t * (n + 1), 0, rec, leaf_rec};
         for (int64_t i = 0; i < n; ++i) c.perm[i] = (int32_t)i;
+        if (nodes)
+            for (int64_t i = 0; i <= n; ++i) leaf_rec[i] = -1;
         build_node(&c, 1, 0, 0, n);
         c.leaf_off[c.n_leaves] = (int32_t)n;
         n_leaves[t] = c.n_leaves;
+        if (!nodes) continue;
+        /* positions -> leaf numbers */
+        oracle_node *out = nodes + (int64_t)t * (n + 1);
+        int32_t *up = leaf_up + (int64_t)t * (n + 1);
+        for (int32_t l = 0; l < c.n_leaves; ++l) lidx[c.leaf_off[l]] = l;
+        for (int32_t l = 0; l < c.n_leaves; ++l) {
+            int32_t b = c.leaf_off[l];
+            up[l] = leaf_rec[b] < 0 ? -1 : lidx[leaf_rec[b] >> 1] * 2 + (leaf_rec[b] & 1);
+            if (l == 0) continue;
+            oracle_node r = rec[b]; /* the node whose right part starts with leaf l */
+            r.parent = r.parent < 0 ? -1 : lidx[r.parent];
+            for (int s = 0; s < 2; ++s)
+                r.child[s] = r.child[s] >= 0 ? lidx[r.child[s]] : ~lidx[~r.child[s]];
+            out[l] = r;
+        }
     }
     free(tmp);
+    free(rec);
+    free(leaf_rec);
+    free(lidx);
     return 0;
+}
+
+int oracle_build_trees(const float *X, int64_t n, int32_t d, int32_t T, int32_t S, uint64_t seed,
+                       int32_t *perm, int32_t *leaf_off, int32_t *n_leaves)
+{
+    return oracle_build_trees_nodes(X, n, d, T, S, seed, perm, leaf_off, n_leaves, NULL, NULL);
 }
 
 /* ------------------------------------------------------------------------- */
@@ -209,8 +276,9 @@ static void pools_store(const entry *pool, const int32_t *cnt, int64_t n, int32_
 }
 
 /* ------------------------------------------------------------------------- */
-/* Alg. 3, conquer step at the leaves: for each point, the candidates are the   */
-/* other members of its leaf in every tree; keep the K closest.                 */
+/* Alg. 3, conquer step: for each point, the candidates are the other members   */
+/* of its leaf in every tree and, above the conquer-to depth, the members of    */
+/* one leaf of every sibling subtree on the way up; keep the K closest.         */
 
 static int cmp_i32(const void *a, const void *b)
 {
@@ -218,14 +286,37 @@ static int cmp_i32(const void *a, const void *b)
     return (x > y) - (x < y);
 }
 
+/* Alg. 3, the walk up from the leaf: N is the ancestor of point i's leaf at
+ * depth d, Sib the child of N that is not on i's path; i is sent down the
+ * subtree of Sib by the split test of every node it meets (Section 3.3.2: the
+ * subtree is used as a classifier for i) and the members of the leaf it reaches
+ * join the candidates.  `up` is the link of the node below N on i's path.
+ * A node without a split dimension (below depth 60) sends every point left. */
+static int32_t sibling_leaf(const float *xi, const oracle_node *nodes, int32_t up)
+{
+    int32_t c = nodes[up >> 1].child[1 - (up & 1)];
+    while (c >= 0) {
+        const oracle_node *nd = &nodes[c];
+        int left = nd->dim < 0 || (int64_t)nd->cnt * quantise(xi[nd->dim]) < nd->sum;
+        c = nd->child[left ? 0 : 1];
+    }
+    return ~c;
+}
+
 /* rows == NULL: all points, output row r belongs to point r.  Otherwise output
- * row r belongs to point rows[r].  Outputs are [n_rows][K]. */
-int oracle_init_graph(const float *X, int64_t n, int32_t d, const int32_t *perm,
-                      const int32_t *leaf_off, const int32_t *n_leaves, int32_t T, int32_t K,
-                      const int64_t *rows, int64_t n_rows, int32_t *ids, float *dists,
-                      uint8_t *flags)
+ * row r belongs to point rows[r].  Outputs are [n_rows][K].
+ * nodes / leaf_up == NULL or dep above every leaf's depth: the conquer step
+ * stops at the leaves.  Otherwise, per tree, for d = depth(leaf) - 1 down to
+ * dep the leaf that i reaches in the sibling subtree of its ancestor at depth d
+ * is added (Alg. 3, the while loop). */
+int oracle_conquer_graph(const float *X, int64_t n, int32_t d, const int32_t *perm,
+                         const int32_t *leaf_off, const int32_t *n_leaves,
+                         const oracle_node *nodes, const int32_t *leaf_up, int32_t dep, int32_t T,
+                         int32_t K, const int64_t *rows, int64_t n_rows, int32_t *ids,
+                         float *dists, uint8_t *flags)
 {
     if (!X || !perm || !leaf_off || !n_leaves || n < 1 || K < 1 || T < 1) return -1;
+    if ((!nodes) != (!leaf_up)) return -1;
     if (!rows) n_rows = n;
     /* leaf_of[t][i] = index of the leaf of tree t that holds point i */
     int32_t *leaf_of = (int32_t *)malloc((size_t)T * n * sizeof(int32_t));
@@ -239,21 +330,33 @@ int oracle_init_graph(const float *X, int64_t n, int32_t d, const int32_t *perm,
                 leaf_of[(int64_t)t * n + perm[(int64_t)t * n + p]] = l;
         }
     }
-    int64_t cap = (int64_t)T * max_leaf;
 #pragma omp parallel
     {
+        int64_t cap = 1024, nc;
         int32_t *cand = (int32_t *)malloc((size_t)cap * sizeof(int32_t));
         entry *pool = (entry *)malloc((size_t)K * sizeof(entry));
 #pragma omp for schedule(dynamic, 256)
         for (int64_t r = 0; r < n_rows; ++r) {
             int64_t i = rows ? rows[r] : r;
-            int64_t nc = 0;
+            nc = 0;
             for (int32_t t = 0; t < T; ++t) {
                 const int32_t *off = leaf_off + (int64_t)t * (n + 1);
+                const oracle_node *nd = nodes ? nodes + (int64_t)t * (n + 1) : NULL;
                 int32_t l = leaf_of[(int64_t)t * n + i];
-                for (int32_t p = off[l]; p < off[l + 1]; ++p) {
-                    int32_t j = perm[(int64_t)t * n + p];
-                    if (j != i) cand[nc++] = j;
+                int32_t up = nodes ? leaf_up[(int64_t)t * (n + 1) + l] : -1;
+                for (;;) { /* the point's own leaf, then one leaf per ancestor */
+                    if (nc + max_leaf > cap) {
+                        cap = 2 * cap + max_leaf;
+                        cand = (int32_t *)realloc(cand, (size_t)cap * sizeof(int32_t));
+                    }
+                    for (int32_t p = off[l]; p < off[l + 1]; ++p) {
+                        int32_t j = perm[(int64_t)t * n + p];
+                        if (j != i) cand[nc++] = j;
+                    }
+                    if (up < 0 || nd[up >> 1].depth < dep) break;
+                    l = sibling_leaf(X + i * d, nd, up);
+                    int32_t j = up >> 1, pj = nd[j].parent;
+                    up = pj < 0 ? -1 : pj * 2 + (nd[pj].child[1] == j);
                 }
             }
             qsort(cand, (size_t)nc, sizeof(int32_t), cmp_i32);
@@ -274,6 +377,15 @@ int oracle_init_graph(const float *X, int64_t n, int32_t d, const int32_t *perm,
     }
     free(leaf_of);
     return 0;
+}
+
+int oracle_init_graph(const float *X, int64_t n, int32_t d, const int32_t *perm,
+                      const int32_t *leaf_off, const int32_t *n_leaves, int32_t T, int32_t K,
+                      const int64_t *rows, int64_t n_rows, int32_t *ids, float *dists,
+                      uint8_t *flags)
+{
+    return oracle_conquer_graph(X, n, d, perm, leaf_off, n_leaves, NULL, NULL, 0, T, K, rows,
+                                n_rows, ids, dists, flags);
 }
 
 /* ------------------------------------------------------------------------- */
