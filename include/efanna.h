@@ -4,9 +4,9 @@
  * The library builds an approximate K-nearest-neighbour graph over N float32 vectors
  * of dimension d under squared L2 distance, following the offline index-building
  * path of EFANNA (arXiv 1609.07228, Section 3.3): randomized truncated KD-trees
- * (Alg. 2) divide the points, a brute-force pass inside every leaf gives each point
- * its initial neighbours (Alg. 3 with the conquer depth at the leaves), and NN-descent
- * local joins refine the graph (Alg. 4).
+ * (Alg. 2) divide the points, a brute-force pass inside every leaf and, optionally,
+ * against one leaf of every sibling subtree up to a chosen depth gives each point its
+ * initial neighbours (Alg. 3), and NN-descent local joins refine the graph (Alg. 4).
  *
  * Conventions shared by every entry point
  *  - Pointers marked [device] are device (HBM) addresses owned by the caller; the
@@ -62,6 +62,19 @@ typedef enum {
  * Rows of `graph` are K such entries in no particular order. */
 typedef uint64_t efanna_entry;
 
+/* An internal tree node as the conquer step of Alg. 3 uses it.  A point x goes to the left
+ * child iff cnt * q(x[dim]) < sum, q(x) = x * 2^20 rounded to the nearest integer (ties to
+ * even), which is the test the node's own points were divided by; dim < 0 (nodes below depth
+ * 60, which are cut by position) sends every point left.  The internal nodes of a tree are
+ * numbered 1 .. n_leaves-1: node j is the one whose right part starts with leaf j.
+ * child[s] >= 0 names an internal node, child[s] < 0 is ~(leaf index); parent is -1 at the
+ * root; depth counts from 0 at the root. */
+typedef struct {
+    int64_t sum;
+    int32_t dim, cnt, parent, depth;
+    int32_t child[2];
+} efanna_node;
+
 const char *efanna_status_string(int status);
 
 /* ---- Alg. 2: randomized truncated KD-trees ------------------------------------------
@@ -80,30 +93,43 @@ const char *efanna_status_string(int status);
  *          within perm[t*n ..], followed by n.
  * n_leaves [host]   out, n_trees int32.
  * max_leaves        capacity of leaf_off per tree (n always suffices).
+ * nodes    [device] out or NULL, n_trees*(max_leaves+1) efanna_node: the internal nodes of
+ *          tree t at nodes[t*(max_leaves+1) + j], j = 1 .. n_leaves[t]-1 (entry 0 unused).
+ * leaf_up  [device] out or NULL (both or neither), n_trees*(max_leaves+1) int32: for leaf l of
+ *          tree t, 2 * (its parent node) + (1 if it is the right child); -1 if the tree is a
+ *          single leaf.  With nodes the workspace must be sized with with_nodes = 1.
  * Synchronises the stream (the host drives one launch group per tree level).
  * Limits: n*n_trees < 2^31, 1 <= leaf_size <= EFANNA_MAX_LEAF, n_trees <= EFANNA_MAX_TREES.
  */
-size_t efanna_trees_workspace_bytes(int64_t n, int32_t d, int32_t n_trees, int32_t leaf_size);
+size_t efanna_trees_workspace_bytes(int64_t n, int32_t d, int32_t n_trees, int32_t leaf_size,
+                                    int32_t with_nodes);
 
 int efanna_build_trees(const float *X, int64_t n, int32_t d, int32_t n_trees, int32_t leaf_size,
                        uint64_t seed, int32_t *perm, int32_t *leaf_off, int32_t max_leaves,
-                       int32_t *n_leaves, void *ws, size_t ws_bytes, void *stream);
+                       int32_t *n_leaves, efanna_node *nodes, int32_t *leaf_up, void *ws,
+                       size_t ws_bytes, void *stream);
 
-/* ---- Alg. 3, conquer step at the leaves ----------------------------------------------
- * Every pair of points that share a leaf in some tree is evaluated once per tree and
- * proposed to both end points; graph row i ends up holding the K closest distinct
- * leaf-mates of i over all trees (fewer if there are fewer; the rest of the row is
- * empty).  Every entry carries the "new" mark (Alg. 4 starts from G_new = G_init).
+/* ---- Alg. 3, conquer step ---------------------------------------------------------------
+ * Candidates of point i: in every tree, the other members of its leaf and - when nodes is
+ * given - for every ancestor N of that leaf with depth >= conquer_depth, the members of the
+ * leaf that i reaches when it is sent down the subtree of N's other child by the nodes' split
+ * tests (Section 3.3.2: the sibling subtree classifies i).  Graph row i ends up holding the K
+ * closest distinct candidates (fewer if there are fewer; the rest of the row is empty).
+ * Every entry carries the "new" mark (Alg. 4 starts from G_new = G_init).
  *
- * perm, leaf_off, max_leaves, n_leaves: as produced by efanna_build_trees.
+ * perm, leaf_off, max_leaves, n_leaves, nodes, leaf_up: as produced by efanna_build_trees.
+ * nodes, leaf_up NULL: the step stops at the leaves (conquer_depth is ignored).
+ * conquer_depth    >= 0; 0 walks up to the root.
  * graph    [device] out, n*k entries.
  * Asynchronous on `stream`.  Limits: k <= EFANNA_MAX_K, k < n, n < 2^31 - 256, a leaf
- * of leaf_size rows of d floats must fit the 160 KB LDS.
+ * of leaf_size rows of d floats must fit the 160 KB LDS; with nodes: leaf_size <= 16, d a
+ * multiple of 4 and X 16-byte aligned (EFANNA_EUNSUPPORTED otherwise).
  */
 size_t efanna_init_workspace_bytes(int64_t n, int32_t n_trees);
 
 int efanna_init_graph(const float *X, int64_t n, int32_t d, const int32_t *perm,
                       const int32_t *leaf_off, int32_t max_leaves, const int32_t *n_leaves,
+                      const efanna_node *nodes, const int32_t *leaf_up, int32_t conquer_depth,
                       int32_t n_trees, int32_t leaf_size, int32_t k, efanna_entry *graph,
                       void *ws, size_t ws_bytes, void *stream);
 

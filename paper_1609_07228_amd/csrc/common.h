@@ -40,6 +40,9 @@ __host__ __device__ inline u64 ef_stream_key(u64 seed, int k)
     return ef_mix64(seed + 0x9E3779B97F4A7C15ULL * (u64)(k + 1));
 }
 
+// coordinate of the exact mean test of Alg. 2: multiples of 2^-20 as integers
+__device__ inline long long ef_quantise(float x) { return (long long)rint((double)x * 1048576.0); }
+
 // ---- packed graph entries -------------------------------------------------------------
 __device__ inline u64 ef_pack(float dist, int id, int is_new)
 {

@@ -369,6 +369,227 @@ init_reg_kernel(const float *__restrict__ X, int d, const int *__restrict__ perm
 }
 
 // ---------------------------------------------------------------------------------------
+// Alg. 3 above the leaves: for every ancestor N of a point's leaf with depth >= dep, the point
+// is sent down the subtree of N's other child by the split test of each node it meets, and the
+// members of the leaf it reaches become candidates.  Runs after the leaf step of the same
+// tree; one wave per (home) leaf, which owns its members' graph rows during the launch.
+//
+// The members of a home leaf share their ancestors but may land in different leaves of a
+// sibling subtree; each distinct one is taken in turn: its rows are loaded as a second
+// register set, laid out like the home rows, and the sixteen rotations of it against the home
+// rows (two halves of eight, as in init_reg_kernel) meet every home member with every member
+// of that leaf.  Rows are merged by rank in LDS after every such leaf and stored at the end.
+// Requires leaves of at most 16 points, d % 4 == 0 and a 16-byte aligned X.
+
+template <int T>
+__device__ inline void cross_round(const float4 (&va)[8], const float4 (&vb)[8], int n_pieces, float (&p)[4])
+{
+#pragma unroll
+    for (int s = 0; s < 8; ++s) {
+        if (s >= n_pieces) break;
+        const float d0 = va[s].x - __int_as_float(EF_ROW_ROR(__float_as_int(vb[s].x), T));
+        const float d1 = va[s].y - __int_as_float(EF_ROW_ROR(__float_as_int(vb[s].y), T));
+        const float d2 = va[s].z - __int_as_float(EF_ROW_ROR(__float_as_int(vb[s].z), T));
+        const float d3 = va[s].w - __int_as_float(EF_ROW_ROR(__float_as_int(vb[s].w), T));
+        p[0] = __builtin_fmaf(d0, d0, p[0]);
+        p[1] = __builtin_fmaf(d1, d1, p[1]);
+        p[2] = __builtin_fmaf(d2, d2, p[2]);
+        p[3] = __builtin_fmaf(d3, d3, p[3]);
+    }
+}
+// rotation 0 pairs lane r with itself: the operand needs no move
+__device__ inline void cross_round0(const float4 (&va)[8], const float4 (&vb)[8], int n_pieces, float (&p)[4])
+{
+#pragma unroll
+    for (int s = 0; s < 8; ++s) {
+        if (s >= n_pieces) break;
+        const float d0 = va[s].x - vb[s].x, d1 = va[s].y - vb[s].y, d2 = va[s].z - vb[s].z,
+                    d3 = va[s].w - vb[s].w;
+        p[0] = __builtin_fmaf(d0, d0, p[0]);
+        p[1] = __builtin_fmaf(d1, d1, p[1]);
+        p[2] = __builtin_fmaf(d2, d2, p[2]);
+        p[3] = __builtin_fmaf(d3, d3, p[3]);
+    }
+}
+
+// eight partial-sum sets (one per rotation) -> lane g keeps the finished distances of
+// rotations 2g and 2g+1 of the eight; same adds, in the same tree, as the fixed order
+__device__ inline void reduce_rotations(const float (&P)[8][4], int g, float (&out)[2])
+{
+    const bool hi = g & 2, odd = g & 1;
+    float Q[4][4], R[2][4];
+#pragma unroll
+    for (int t = 0; t < 4; ++t)
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            const float keep = hi ? P[t + 4][k] : P[t][k], send = hi ? P[t][k] : P[t + 4][k];
+            Q[t][k] = keep + __shfl_xor(send, 32, EF_WAVE);
+        }
+#pragma unroll
+    for (int t = 0; t < 2; ++t)
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            const float keep = odd ? Q[t + 2][k] : Q[t][k], send = odd ? Q[t][k] : Q[t + 2][k];
+            R[t][k] = keep + __shfl_xor(send, 16, EF_WAVE);
+        }
+#pragma unroll
+    for (int t = 0; t < 2; ++t) out[t] = (R[t][0] + R[t][2]) + (R[t][1] + R[t][3]);
+}
+
+__global__ void __launch_bounds__(EF_WAVE)
+conquer_kernel(const float *__restrict__ X, int d, const int *__restrict__ perm_t,
+               const int *__restrict__ leaf_off_t, int n_leaves,
+               const efanna_node *__restrict__ nodes_t, const int *__restrict__ leaf_up_t, int dep,
+               int K, u64 *graph)
+{
+    extern __shared__ __align__(16) float smem[];
+    u64 *pools_a = (u64 *)smem;                       // [16][K] rows being merged, ascending
+    u64 *pools_b = pools_a + 16 * (size_t)K;          // [16][K] the other copy
+    u64 *cand = pools_b + 16 * (size_t)K;             // [16][kCandPitch]
+    int *uid_b = (int *)(cand + 16 * kCandPitch);     // [16] members of the sibling-side leaf
+    const int lane = threadIdx.x, r16 = lane & 15, g = lane >> 4;
+    const int dirn = (EF_ROW_ROR(r16, 1) - r16) & 15;      // lane r receives from lane r + dirn
+    for (int leaf = blockIdx.x; leaf < n_leaves; leaf += gridDim.x) {
+        // links read from the tables are clamped to the tables' range and the walks are bounded,
+        // so that tables which are not what the tree builder writes cannot lead out of them
+        const int last = n_leaves - 1;
+        int up = min(leaf_up_t[leaf], 2 * last + 1);
+        if (up < 0 || nodes_t[up >> 1].depth < dep) continue;      // nothing above this leaf to visit
+        const int b0 = leaf_off_t[leaf];
+        const int s = min(leaf_off_t[leaf + 1] - b0, 16);
+        const int my_id = r16 < s ? perm_t[b0 + r16] : -1;
+        const float *pa = X + (size_t)max(my_id, 0) * d + 4 * g;
+        __syncthreads();                  // the previous leaf's LDS reads are done
+        u64 *cur = pools_a, *nxt = pools_b;
+        for (int c = g; c < K; c += 4)
+            cur[r16 * K + c] = r16 < s ? graph[(size_t)my_id * K + c] : ef_empty_entry(K - 1 - c);
+        for (int climbed = 0; up >= 0 && climbed < 4096; ++climbed) {
+            const efanna_node anc = nodes_t[up >> 1];
+            if (anc.depth < dep) break;
+            // ---- every member goes down the sibling subtree ---------------------------------
+            int e = -1;      // leaf reached (members only)
+            if (r16 < s) {
+                int c = anc.child[1 - (up & 1)];
+                for (int steps = 0; c >= 0 && steps < 4096; ++steps) {
+                    const efanna_node nd = nodes_t[min(c, last)];
+                    const bool left = nd.dim < 0 ||
+                                      (long long)nd.cnt * ef_quantise(X[(size_t)my_id * d + min(nd.dim, d - 1)]) < nd.sum;
+                    c = nd.child[left ? 0 : 1];
+                }
+                e = c >= 0 ? 0 : min(~c, last);
+            }
+            // ---- one distinct leaf at a time --------------------------------------------------
+            for (;;) {
+                const u64 pending = __ballot(e >= 0);
+                if (pending == 0) break;
+                const int e_cur = __shfl(e, __ffsll((long long)pending) - 1, EF_WAVE);
+                const bool mine = e == e_cur;      // this member's candidates come from leaf e_cur
+                if (mine) e = -1;
+                const int bb = leaf_off_t[e_cur];
+                const int sb = min(leaf_off_t[e_cur + 1] - bb, 16);
+                const int id_b = r16 < sb ? perm_t[bb + r16] : -1;
+                if (g == 0) uid_b[r16] = id_b;
+                const float *pb = X + (size_t)max(id_b, 0) * d + 4 * g;
+                float dist[4];      // rotations 2g, 2g+1, 8+2g, 8+2g+1
+#pragma unroll
+                for (int half = 0; half < 2; ++half) {
+                    float P[8][4];
+#pragma unroll
+                    for (int t = 0; t < 8; ++t) P[t][0] = P[t][1] = P[t][2] = P[t][3] = 0.0f;
+                    for (int c0 = 0; c0 < d; c0 += 128) {
+                        float4 va[8], vb[8];
+#pragma unroll
+                        for (int q = 0; q < 8; ++q) {
+                            const bool in = c0 + 16 * q + 4 * g + 3 < d;      // d % 4 == 0: a piece is in or out
+                            va[q] = in && r16 < s ? *reinterpret_cast<const float4 *>(pa + c0 + 16 * q)
+                                                  : make_float4(0.f, 0.f, 0.f, 0.f);
+                            vb[q] = in && r16 < sb ? *reinterpret_cast<const float4 *>(pb + c0 + 16 * q)
+                                                   : make_float4(0.f, 0.f, 0.f, 0.f);
+                        }
+                        const int n_pieces = min(8, (d - c0 + 15) >> 4);
+                        if (half == 0) {
+                            cross_round0(va, vb, n_pieces, P[0]);
+                            cross_round<1>(va, vb, n_pieces, P[1]);
+                            cross_round<2>(va, vb, n_pieces, P[2]);
+                            cross_round<3>(va, vb, n_pieces, P[3]);
+                            cross_round<4>(va, vb, n_pieces, P[4]);
+                            cross_round<5>(va, vb, n_pieces, P[5]);
+                            cross_round<6>(va, vb, n_pieces, P[6]);
+                            cross_round<7>(va, vb, n_pieces, P[7]);
+                        } else {
+                            cross_round<8>(va, vb, n_pieces, P[0]);
+                            cross_round<9>(va, vb, n_pieces, P[1]);
+                            cross_round<10>(va, vb, n_pieces, P[2]);
+                            cross_round<11>(va, vb, n_pieces, P[3]);
+                            cross_round<12>(va, vb, n_pieces, P[4]);
+                            cross_round<13>(va, vb, n_pieces, P[5]);
+                            cross_round<14>(va, vb, n_pieces, P[6]);
+                            cross_round<15>(va, vb, n_pieces, P[7]);
+                        }
+                    }
+                    float two[2];
+                    reduce_rotations(P, g, two);
+                    dist[2 * half] = two[0];
+                    dist[2 * half + 1] = two[1];
+                }
+                __syncthreads();                  // uid_b and the current rows are visible
+                // ---- candidates of row r16 and their ranks ------------------------------------
+                const bool target = mine;      // the four lanes of a row hold the same verdict
+                u64 key[4];
+                int lt[4];
+                const u64 *row = cur + r16 * K;
+#pragma unroll
+                for (int c = 0; c < 4; ++c) {
+                    const int rot = 8 * (c >> 1) + 2 * g + (c & 1);
+                    const int bm = (r16 + dirn * rot) & 15;      // member of the other leaf met at this rotation
+                    key[c] = target && bm < sb ? ef_pack(dist[c], uid_b[bm], 1) : ~0ULL;
+                    int lo = 0, hi_ = K;
+                    if (key[c] != ~0ULL) {
+                        while (lo < hi_) {
+                            const int mid = (lo + hi_) >> 1;
+                            if (row[mid] < key[c]) lo = mid + 1;
+                            else hi_ = mid;
+                        }
+                        if (lo < K && row[lo] == key[c]) key[c] = ~0ULL;      // already in the row
+                    }
+                    lt[c] = lo;
+                    cand[r16 * kCandPitch + 4 * g + c] = key[c];
+                }
+                __syncthreads();
+                u64 cs[16];
+#pragma unroll
+                for (int o = 0; o < 16; ++o) cs[o] = cand[r16 * kCandPitch + o];
+                u64 *out = nxt + r16 * K;
+#pragma unroll
+                for (int c = 0; c < 4; ++c) {
+                    if (key[c] == ~0ULL) continue;
+                    int rank = lt[c];
+#pragma unroll
+                    for (int o = 0; o < 16; ++o) rank += cs[o] < key[c] ? 1 : 0;
+                    if (rank < K) out[rank] = key[c];
+                }
+                for (int j = g; j < K; j += 4) {
+                    const u64 en = row[j];
+                    int rank = j;
+#pragma unroll
+                    for (int o = 0; o < 16; ++o) rank += cs[o] < en ? 1 : 0;
+                    if (rank < K) out[rank] = en;
+                }
+                __syncthreads();                  // merged rows complete before they are read again
+                u64 *tmp = cur;
+                cur = nxt;
+                nxt = tmp;
+            }
+            // ---- next ancestor ---------------------------------------------------------------------
+            const int j = up >> 1, pj = min(anc.parent, last);
+            up = pj < 0 ? -1 : pj * 2 + (nodes_t[pj].child[1] == j ? 1 : 0);
+        }
+        if (r16 < s)
+            for (int c = g; c < K; c += 4) graph[(size_t)my_id * K + c] = cur[r16 * K + c];
+    }
+}
+
+// ---------------------------------------------------------------------------------------
 // Alg. 4 step 1+2: sample the new / old sets of every row, clear the sampled marks,
 // refresh the row's threshold and enter the row's id into the reverse lists of the
 // sampled neighbours.
@@ -1309,11 +1530,13 @@ extern "C" size_t efanna_init_workspace_bytes(int64_t n, int32_t n_trees)
 
 extern "C" int efanna_init_graph(const float *X, int64_t n, int32_t d, const int32_t *perm,
                                  const int32_t *leaf_off, int32_t max_leaves,
-                                 const int32_t *n_leaves, int32_t n_trees, int32_t leaf_size,
-                                 int32_t k, efanna_entry *graph_, void *ws, size_t ws_bytes,
-                                 void *stream)
+                                 const int32_t *n_leaves, const efanna_node *nodes,
+                                 const int32_t *leaf_up, int32_t conquer_depth, int32_t n_trees,
+                                 int32_t leaf_size, int32_t k, efanna_entry *graph_, void *ws,
+                                 size_t ws_bytes, void *stream)
 {
-    if (!X || !perm || !leaf_off || !n_leaves || !graph_) return EFANNA_EINVAL;
+    if (!X || !perm || !leaf_off || !n_leaves || !graph_ || (!nodes) != (!leaf_up)) return EFANNA_EINVAL;
+    if (nodes && conquer_depth < 0) return EFANNA_EINVAL;
     if (n < 2 || d < 1 || n_trees < 1 || n_trees > EFANNA_MAX_TREES || leaf_size < 1 ||
         leaf_size > EFANNA_MAX_LEAF || k < 1 || k > EFANNA_MAX_K || k >= n || max_leaves < 1 ||
         n >= 2147483647LL - 256)
@@ -1328,12 +1551,20 @@ extern "C" int efanna_init_graph(const float *X, int64_t n, int32_t d, const int
     const int stride = d + kRowPad;
     const size_t lds = (size_t)(align4(leaf_size * stride) + align4(leaf_size * leaf_size)) * 4 +
                        (size_t)leaf_size * k * 8 + (size_t)leaf_size * 4;
-    if (leaf_size <= 16 && d % 4 == 0 && ((uintptr_t)X & 15) == 0) {
+    const bool reg_ok = leaf_size <= 16 && d % 4 == 0 && ((uintptr_t)X & 15) == 0;
+    if (nodes && !reg_ok) return EFANNA_EUNSUPPORTED;      // the step above the leaves has one kernel only
+    if (reg_ok) {
         const size_t reg_lds = (size_t)16 * k * 8 + (size_t)16 * kCandPitch * 8 + 16 * 4;
-        for (int t = 0; t < n_trees; ++t)
+        const size_t conquer_lds = (size_t)2 * 16 * k * 8 + (size_t)16 * kCandPitch * 8 + 16 * 4;
+        for (int t = 0; t < n_trees; ++t) {
+            const int32_t *perm_t = perm + (size_t)t * n, *off_t = leaf_off + (size_t)t * (max_leaves + 1);
             init_reg_kernel<<<min(n_leaves[t], kRegGrid), EF_WAVE, reg_lds, st>>>(
-                X, d, perm + (size_t)t * n, leaf_off + (size_t)t * (max_leaves + 1), n_leaves[t], k,
-                graph, t == 0);
+                X, d, perm_t, off_t, n_leaves[t], k, graph, t == 0);
+            if (nodes)
+                conquer_kernel<<<min(n_leaves[t], kRegGrid), EF_WAVE, conquer_lds, st>>>(
+                    X, d, perm_t, off_t, n_leaves[t], nodes + (size_t)t * (max_leaves + 1),
+                    leaf_up + (size_t)t * (max_leaves + 1), conquer_depth, k, graph);
+        }
         EF_HIP_CHECK(hipGetLastError());
         return EFANNA_OK;
     }

@@ -31,6 +31,7 @@ struct Node {
     int mid;         // first position of the right child
     int moved;       // 1: mean split, 0: positional halves (ids stay where they are)
     int child[2];    // index in the next level's table, -1 if that child is a leaf
+    int parent;      // position where the parent's right part starts, -1 for a root
 };
 
 struct Counters {
@@ -43,8 +44,38 @@ struct Counters {
 struct SmallNode {
     int b, e;
     u64 heap;
-    int depth, pad;
+    int depth, parent;      // parent: as in Node
 };
+
+// Record of an internal node kept for the conquer step above the leaves (Alg. 3), stored at
+// the position where the node's right part starts (unique per node).  child[s] >= 0: the
+// position that identifies an internal child, < 0: ~(first position of a leaf child).  Every
+// field is written exactly once: sum .. depth by the node itself, child[s] by the node for a
+// leaf child and by the child for an internal one.
+struct NodeRec {
+    long long sum;
+    int dim, cnt, parent, depth;
+    int child[2];
+};
+static_assert(sizeof(NodeRec) == sizeof(efanna_node), "record and exported node share a layout");
+
+__device__ inline void record_node(NodeRec *rec, int *leaf_rec, int mid, long long sum, int dim,
+                                   int cnt, int parent, int depth)
+{
+    NodeRec &r = rec[mid];
+    r.sum = sum;
+    r.dim = dim;
+    r.cnt = cnt;
+    r.parent = parent;
+    r.depth = depth;
+    if (parent >= 0) rec[parent].child[mid > parent ? 1 : 0] = mid;
+    (void)leaf_rec;
+}
+__device__ inline void record_leaf(NodeRec *rec, int *leaf_rec, int b, int parent)
+{
+    leaf_rec[b] = parent;
+    if (parent >= 0) rec[parent].child[b >= parent ? 1 : 0] = ~b;
+}
 
 constexpr int kFinMax = 2048;      // largest segment finish_kernel takes
 constexpr int kFinNodes = 256;     // nodes of one level inside such a segment
@@ -54,7 +85,6 @@ inline int finish_limit(int S)
     return f < kFinMax ? (int)f : kFinMax;
 }
 
-__device__ inline long long quantise(float x) { return (long long)rint((double)x * 1048576.0); }
 
 // Transposed copy XT[d][n] of the data, with the input check folded in.  The splits read
 // one coordinate of many points: in the row-major layout the upper levels (ids still
@@ -98,7 +128,7 @@ __global__ void roots_kernel(Node *nodes, int *dims, int *node_of, unsigned char
         sn.e = sn.b + n;
         sn.heap = 1;
         sn.depth = 0;
-        sn.pad = 0;
+        sn.parent = -1;
         small[p] = sn;
         if (p == 0) c->small_nodes = T;
     }
@@ -117,6 +147,7 @@ __global__ void roots_kernel(Node *nodes, int *dims, int *node_of, unsigned char
         nd.mid = nd.b;
         nd.moved = 0;
         nd.child[0] = nd.child[1] = -1;
+        nd.parent = -1;
         nodes[p] = nd;
         dims[p] = nd.dim;
     }
@@ -142,7 +173,7 @@ sum_kernel(const float *__restrict__ XT, int n, const int *__restrict__ perm,
             if (dim >= 0) {
                 float x = XT[(size_t)dim * n + perm[p]];
                 val[p] = x;
-                q = quantise(x);
+                q = ef_quantise(x);
             } else {
                 s = -1;
             }
@@ -191,7 +222,7 @@ struct LeftPred {
         const Node &nd = nodes[s];
         if (nd.dim < 0) return 0;
         long long cnt = nd.e - nd.b;
-        return cnt * quantise(val[p]) < nd.sum ? 1 : 0;
+        return cnt * ef_quantise(val[p]) < nd.sum ? 1 : 0;
     }
 };
 struct FlagPred {
@@ -273,7 +304,7 @@ __global__ void scan_apply_kernel(Pred pred, size_t total, const int *block_sums
 __global__ void children_kernel(Node *cur, int n_cur, Node *next, int *next_dims,
                                 const int *__restrict__ lcount,
                                 unsigned char *leaf_flag, int S, int fin, SmallNode *small, u64 seed,
-                                int n, int d, Counters *c)
+                                int n, int d, Counters *c, NodeRec *rec, int *leaf_rec)
 {
     int s = blockIdx.x * blockDim.x + threadIdx.x;
     int kind[2] = {0, 0};      // 0 leaf, 1 finished later inside one workgroup, 2 next level
@@ -305,6 +336,7 @@ __global__ void children_kernel(Node *cur, int n_cur, Node *next, int *next_dims
     base_s = __shfl(base_s, EF_WAVE - 1, EF_WAVE);
     if (s >= n_cur) return;
     int slot = base + inc - want, slot_s = base_s + inc_s - want_s;
+    if (rec) record_node(rec, leaf_rec, nd.mid, nd.sum, nd.dim, nd.e - nd.b, nd.parent, nd.depth);
     const int tree = nd.b / n;
     const u64 key = ef_stream_key(seed, tree);
     for (int side = 0; side < 2; ++side) {
@@ -323,6 +355,7 @@ __global__ void children_kernel(Node *cur, int n_cur, Node *next, int *next_dims
             ch.mid = cb;
             ch.moved = 0;
             ch.child[0] = ch.child[1] = -1;
+            ch.parent = nd.mid;
             next[slot] = ch;
             next_dims[slot] = ch.dim;
             nd.child[side] = slot++;
@@ -332,10 +365,11 @@ __global__ void children_kernel(Node *cur, int n_cur, Node *next, int *next_dims
             sn.e = ce;
             sn.heap = ch_heap;
             sn.depth = nd.depth + 1;
-            sn.pad = 0;
+            sn.parent = nd.mid;
             small[slot_s++] = sn;
         } else {
             leaf_flag[cb] = 1;
+            if (rec) record_leaf(rec, leaf_rec, cb, nd.mid);
         }
     }
     cur[s] = nd;
@@ -359,7 +393,7 @@ __global__ void scatter_kernel(const int *__restrict__ perm_in, int *__restrict_
     size_t dst = p;
     if (nd.moved) {
         long long cnt = nd.e - nd.b;
-        bool left = cnt * quantise(val[p]) < nd.sum;
+        bool left = cnt * ef_quantise(val[p]) < nd.sum;
         int lc = lcount[p] - lcount[nd.b];
         dst = left ? (size_t)nd.b + lc : (size_t)nd.mid + ((int)(p - nd.b) - lc);
     }
@@ -378,11 +412,12 @@ struct LNode {
     long long sum;
     int dim, depth;
     int child[2];
+    int parent, pad;           // parent: global position, as in Node
 };
 
 __global__ void __launch_bounds__(kBlock)
 finish_kernel(const float *__restrict__ XT, int d, int *perm, const SmallNode *__restrict__ small,
-              unsigned char *leaf_flag, int S, u64 seed, int n)
+              unsigned char *leaf_flag, int S, u64 seed, int n, NodeRec *rec, int *leaf_rec)
 {
     // One 16-byte aligned LDS block carved by hand (no separate static LDS variables, whose
     // size would shift the 8-byte node records off their alignment).
@@ -411,6 +446,8 @@ finish_kernel(const float *__restrict__ XT, int d, int *perm, const SmallNode *_
         r.depth = seg.depth;
         r.dim = seg.depth < 60 ? (int)(ef_mix64(key + seg.heap) % (u64)d) : -1;
         r.child[0] = r.child[1] = -1;
+        r.parent = seg.parent;
+        r.pad = 0;
         tabs_base[0] = r;
         n_next_sh = 0;
     }
@@ -427,7 +464,7 @@ finish_kernel(const float *__restrict__ XT, int d, int *perm, const SmallNode *_
             if (k >= 0 && tc[k].dim >= 0) {
                 const float x = XT[(size_t)tc[k].dim * n + idc[p]];
                 val[p] = x;
-                atomicAdd((u64 *)&tc[k].sum, (u64)quantise(x));
+                atomicAdd((u64 *)&tc[k].sum, (u64)ef_quantise(x));
             }
         }
         __syncthreads();
@@ -439,7 +476,7 @@ finish_kernel(const float *__restrict__ XT, int d, int *perm, const SmallNode *_
                 const int k = nc[p];
                 int f = 0;
                 if (k >= 0 && tc[k].dim >= 0)
-                    f = (long long)(tc[k].e - tc[k].b) * quantise(val[p]) < tc[k].sum ? 1 : 0;
+                    f = (long long)(tc[k].e - tc[k].b) * ef_quantise(val[p]) < tc[k].sum ? 1 : 0;
                 lcnt[p] = f;
                 mine += f;
             }
@@ -468,6 +505,7 @@ finish_kernel(const float *__restrict__ XT, int d, int *perm, const SmallNode *_
                 nd.moved = 1;
                 nd.mid = nd.b + nl;
             }
+            if (rec) record_node(rec, leaf_rec, seg.b + nd.mid, nd.sum, nd.dim, c, nd.parent, nd.depth);
             for (int side = 0; side < 2; ++side) {
                 const int cb = side ? nd.mid : nd.b, ce = side ? nd.e : nd.mid;
                 nd.child[side] = -1;
@@ -482,11 +520,14 @@ finish_kernel(const float *__restrict__ XT, int d, int *perm, const SmallNode *_
                     ch.dim = ch.depth < 60 ? (int)(ef_mix64(key + ch.heap) % (u64)d) : -1;
                     ch.sum = 0;
                     ch.child[0] = ch.child[1] = -1;
+                    ch.parent = seg.b + nd.mid;
+                    ch.pad = 0;
                     const int slot = atomicAdd(&n_next_sh, 1);
                     tn[slot] = ch;
                     nd.child[side] = slot;
                 } else {
                     leaf_flag[seg.b + cb] = 1;
+                    if (rec) record_leaf(rec, leaf_rec, seg.b + cb, seg.b + nd.mid);
                 }
             }
             tc[k] = nd;
@@ -504,7 +545,7 @@ finish_kernel(const float *__restrict__ XT, int d, int *perm, const SmallNode *_
             const LNode &nd = tc[k];
             int dst = p;
             if (nd.moved) {
-                const bool left = (long long)(nd.e - nd.b) * quantise(val[p]) < nd.sum;
+                const bool left = (long long)(nd.e - nd.b) * ef_quantise(val[p]) < nd.sum;
                 const int lc = lcnt[p] - lcnt[nd.b];
                 dst = left ? nd.b + lc : nd.mid + (p - nd.b - lc);
             }
@@ -546,6 +587,39 @@ __global__ void leaf_offsets_kernel(const unsigned char *__restrict__ leaf_flag,
     }
 }
 
+// Internal nodes and leaf parents, renumbered by leaves: the node whose right part starts with
+// leaf l becomes node l of its tree (l >= 1), a leaf is named by its index.
+__global__ void export_nodes_kernel(const unsigned char *__restrict__ leaf_flag,
+                                    const int *__restrict__ rank, const NodeRec *__restrict__ rec,
+                                    const int *__restrict__ leaf_rec, int n, int T, int max_leaves,
+                                    efanna_node *__restrict__ nodes, int *__restrict__ leaf_up)
+{
+    size_t p = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    size_t total = (size_t)n * T;
+    if (p >= total || !leaf_flag[p]) return;
+    const int t = (int)(p / (size_t)n);
+    const int r0 = rank[(size_t)t * n];
+    const int l = rank[p] - r0;
+    if (l >= max_leaves) return;
+    const size_t base = (size_t)t * (max_leaves + 1);
+    // positions read back from the records are clamped into the tree: a slip in the
+    // bookkeeping then shows as a wrong table, never as a stray read
+    const int lo = t * n, hi = lo + n - 1;
+    auto at = [&](int pos) { return rank[min(max(pos, lo), hi)] - r0; };
+    const int par = leaf_rec[p];
+    leaf_up[base + l] = par < 0 ? -1 : at(par) * 2 + (p >= (size_t)par ? 1 : 0);
+    if (p == (size_t)t * n) return;      // the first leaf starts no node's right part
+    const NodeRec r = rec[p];
+    efanna_node o;
+    o.sum = r.sum;
+    o.dim = r.dim;
+    o.cnt = r.cnt;
+    o.parent = r.parent < 0 ? -1 : at(r.parent);
+    o.depth = r.depth;
+    for (int s = 0; s < 2; ++s) o.child[s] = r.child[s] >= 0 ? at(r.child[s]) : ~at(~r.child[s]);
+    nodes[base + l] = o;
+}
+
 inline size_t align_up(size_t x) { return (x + 255) & ~(size_t)255; }
 
 struct TreeWs {
@@ -556,10 +630,12 @@ struct TreeWs {
     int *dims_a, *dims_b;
     SmallNode *small;
     Counters *counters;
+    NodeRec *rec;        // only with node export
+    int *leaf_rec;
     size_t bytes;
 };
 
-TreeWs carve(void *ws, int64_t n, int32_t d, int32_t T, int32_t S)
+TreeWs carve(void *ws, int64_t n, int32_t d, int32_t T, int32_t S, bool with_nodes)
 {
     size_t total = (size_t)n * T;
     size_t max_nodes = total / (size_t)(S + 1) + (size_t)T + 1;
@@ -587,6 +663,8 @@ TreeWs carve(void *ws, int64_t n, int32_t d, int32_t T, int32_t S)
     w.n_leaves_dev = (int *)take((size_t)T * 4);
     w.counters = (Counters *)take(sizeof(Counters));
     w.xt = (float *)take((size_t)n * d * 4);
+    w.rec = with_nodes ? (NodeRec *)take(total * sizeof(NodeRec)) : nullptr;
+    w.leaf_rec = with_nodes ? (int *)take(total * 4) : nullptr;
     w.bytes = off;
     return w;
 }
@@ -603,31 +681,34 @@ void device_scan(Pred pred, size_t total, int *block_sums, int *out, hipStream_t
 }  // namespace
 
 extern "C" size_t efanna_trees_workspace_bytes(int64_t n, int32_t d, int32_t n_trees,
-                                               int32_t leaf_size)
+                                               int32_t leaf_size, int32_t with_nodes)
 {
     if (n < 1 || d < 1 || n_trees < 1 || leaf_size < 1) return 0;
-    return carve(nullptr, n, d, n_trees, leaf_size).bytes;
+    return carve(nullptr, n, d, n_trees, leaf_size, with_nodes != 0).bytes;
 }
 
 extern "C" int efanna_build_trees(const float *X, int64_t n, int32_t d, int32_t n_trees,
                                   int32_t leaf_size, uint64_t seed, int32_t *perm,
                                   int32_t *leaf_off, int32_t max_leaves, int32_t *n_leaves,
-                                  void *ws, size_t ws_bytes, void *stream)
+                                  efanna_node *nodes, int32_t *leaf_up, void *ws, size_t ws_bytes,
+                                  void *stream)
 {
-    if (!X || !perm || !leaf_off || !n_leaves) return EFANNA_EINVAL;
+    if (!X || !perm || !leaf_off || !n_leaves || (!nodes) != (!leaf_up)) return EFANNA_EINVAL;
     if (n < 1 || d < 1 || n_trees < 1 || n_trees > EFANNA_MAX_TREES || leaf_size < 1 ||
         leaf_size > EFANNA_MAX_LEAF || max_leaves < 1)
         return EFANNA_EINVAL;
     if ((double)n * n_trees >= 2147483647.0 - 4096.0) return EFANNA_EINVAL;
-    if (!ws || ((uintptr_t)ws & 255) || ws_bytes < efanna_trees_workspace_bytes(n, d, n_trees, leaf_size))
+    if (!ws || ((uintptr_t)ws & 255) ||
+        ws_bytes < efanna_trees_workspace_bytes(n, d, n_trees, leaf_size, nodes != nullptr))
         return EFANNA_EWORKSPACE;
     hipStream_t st = (hipStream_t)stream;
     const int T = n_trees, S = leaf_size;
     const size_t total = (size_t)n * T;
     const int grid_pos = (int)((total + kBlock - 1) / kBlock);
-    TreeWs w = carve(ws, n, d, T, S);
+    TreeWs w = carve(ws, n, d, T, S, nodes != nullptr);
 
     EF_HIP_CHECK(hipMemsetAsync(w.counters, 0, sizeof(Counters), st));
+    if (nodes) EF_HIP_CHECK(hipMemsetAsync(w.leaf_rec, 0xFF, total * 4, st));      // a lone root leaf has no parent
     transpose_check_kernel<<<dim3((unsigned)((n + 31) / 32), (unsigned)((d + 31) / 32)), kBlock, 0, st>>>(
         X, (int)n, d, w.xt, w.counters);
     iota_kernel<<<grid_pos, kBlock, 0, st>>>(perm, (int)n, total);
@@ -651,7 +732,7 @@ extern "C" int efanna_build_trees(const float *X, int64_t n, int32_t d, int32_t 
         device_scan(pred, total, w.block_sums, w.lcount, st);
         children_kernel<<<(n_cur + kBlock - 1) / kBlock, kBlock, 0, st>>>(
             nodes_cur, n_cur, nodes_nxt, dims_nxt, w.lcount, w.leaf_flag, S, fin, w.small, seed, (int)n, d,
-            w.counters);
+            w.counters, w.rec, w.leaf_rec);
         scatter_kernel<<<grid_pos, kBlock, 0, st>>>(perm_cur, perm_nxt, node_cur, node_nxt, nodes_cur,
                                                     w.val, w.lcount, total);
         EF_HIP_CHECK(hipMemcpyAsync(&host_c, w.counters, sizeof(Counters), hipMemcpyDeviceToHost, st));
@@ -669,7 +750,7 @@ extern "C" int efanna_build_trees(const float *X, int64_t n, int32_t d, int32_t 
         EF_HIP_CHECK(hipFuncSetAttribute((const void *)finish_kernel,
                                          hipFuncAttributeMaxDynamicSharedMemorySize, (int)fin_lds));
         finish_kernel<<<host_c.small_nodes, kBlock, fin_lds, st>>>(w.xt, d, perm_cur, w.small, w.leaf_flag,
-                                                                  S, seed, (int)n);
+                                                                  S, seed, (int)n, w.rec, w.leaf_rec);
     }
     if (perm_cur != perm)
         EF_HIP_CHECK(hipMemcpyAsync(perm, perm_cur, total * 4, hipMemcpyDeviceToDevice, st));
@@ -678,6 +759,9 @@ extern "C" int efanna_build_trees(const float *X, int64_t n, int32_t d, int32_t 
     device_scan(fp, total, w.block_sums, w.lcount, st);
     leaf_offsets_kernel<<<grid_pos, kBlock, 0, st>>>(w.leaf_flag, w.lcount, (int)n, T, max_leaves,
                                                      leaf_off, w.n_leaves_dev);
+    if (nodes)
+        export_nodes_kernel<<<grid_pos, kBlock, 0, st>>>(w.leaf_flag, w.lcount, w.rec, w.leaf_rec, (int)n, T,
+                                                         max_leaves, nodes, leaf_up);
     EF_HIP_CHECK(hipMemcpyAsync(n_leaves, w.n_leaves_dev, (size_t)T * 4, hipMemcpyDeviceToHost, st));
     EF_HIP_CHECK(hipStreamSynchronize(st));
     EF_HIP_CHECK(hipGetLastError());

@@ -45,13 +45,13 @@ def lib():
         L.efanna_status_string.restype = C.c_char_p
         L.efanna_status_string.argtypes = [C.c_int]
         L.efanna_trees_workspace_bytes.restype = sz
-        L.efanna_trees_workspace_bytes.argtypes = [i64, i32, i32, i32]
+        L.efanna_trees_workspace_bytes.argtypes = [i64, i32, i32, i32, i32]
         L.efanna_build_trees.restype = C.c_int
-        L.efanna_build_trees.argtypes = [vp, i64, i32, i32, i32, u64, vp, vp, i32, vp, vp, sz, vp]
+        L.efanna_build_trees.argtypes = [vp, i64, i32, i32, i32, u64, vp, vp, i32, vp, vp, vp, vp, sz, vp]
         L.efanna_init_workspace_bytes.restype = sz
         L.efanna_init_workspace_bytes.argtypes = [i64, i32]
         L.efanna_init_graph.restype = C.c_int
-        L.efanna_init_graph.argtypes = [vp, i64, i32, vp, vp, i32, vp, i32, i32, i32, vp, vp, sz, vp]
+        L.efanna_init_graph.argtypes = [vp, i64, i32, vp, vp, i32, vp, vp, vp, i32, i32, i32, i32, vp, vp, sz, vp]
         L.efanna_nndescent_workspace_bytes.restype = sz
         L.efanna_nndescent_workspace_bytes.argtypes = [i64, i32, i32]
         L.efanna_nndescent.restype = C.c_int
@@ -88,44 +88,70 @@ def _workspace(nbytes: int, device) -> torch.Tensor:
     return torch.empty(max(int(nbytes), 256), dtype=torch.uint8, device=device)
 
 
+NODE_BYTES = 32      # sizeof(efanna_node): int64 sum; int32 dim, cnt, parent, depth, child[2]
+
+
 def efanna_build_trees(X: torch.Tensor, n_trees: int, leaf_size: int, seed: int,
-                       max_leaves: int | None = None, workspace: torch.Tensor | None = None):
+                       max_leaves: int | None = None, workspace: torch.Tensor | None = None,
+                       with_nodes: bool = False):
     """Alg. 2.  Returns (perm [T,n] int32 device, leaf_off [T,max_leaves+1] int32 device,
-    n_leaves [T] int32 numpy).  Synchronises the current stream."""
+    n_leaves [T] int32 numpy) and, with_nodes, also (nodes [T,max_leaves+1,32] uint8 device
+    holding efanna_node records, leaf_up [T,max_leaves+1] int32 device).  Synchronises the
+    current stream."""
     X = _dev(X, torch.float32)
     n, d = X.shape
     max_leaves = n if max_leaves is None else int(max_leaves)
     perm = torch.empty((n_trees, n), dtype=torch.int32, device=X.device)
     leaf_off = torch.empty((n_trees, max_leaves + 1), dtype=torch.int32, device=X.device)
     n_leaves = np.zeros(n_trees, dtype=np.int32)
-    need = lib().efanna_trees_workspace_bytes(n, d, n_trees, leaf_size)
+    nodes = leaf_up = None
+    if with_nodes:
+        nodes = torch.zeros((n_trees, max_leaves + 1, NODE_BYTES), dtype=torch.uint8, device=X.device)
+        leaf_up = torch.full((n_trees, max_leaves + 1), -1, dtype=torch.int32, device=X.device)
+    need = lib().efanna_trees_workspace_bytes(n, d, n_trees, leaf_size, 1 if with_nodes else 0)
     ws = _workspace(need, X.device) if workspace is None else workspace
     _check(lib().efanna_build_trees(X.data_ptr(), n, d, n_trees, leaf_size, seed, perm.data_ptr(),
                                     leaf_off.data_ptr(), max_leaves,
-                                    n_leaves.ctypes.data_as(C.c_void_p), ws.data_ptr(), ws.numel(),
-                                    _stream()), "efanna_build_trees")
+                                    n_leaves.ctypes.data_as(C.c_void_p),
+                                    nodes.data_ptr() if with_nodes else None,
+                                    leaf_up.data_ptr() if with_nodes else None,
+                                    ws.data_ptr(), ws.numel(), _stream()), "efanna_build_trees")
+    if with_nodes:
+        return perm, leaf_off, n_leaves, nodes, leaf_up
     return perm, leaf_off, n_leaves
 
 
 def efanna_init_graph(X: torch.Tensor, perm: torch.Tensor, leaf_off: torch.Tensor,
                       n_leaves: np.ndarray, leaf_size: int, k: int,
-                      graph: torch.Tensor | None = None, workspace: torch.Tensor | None = None):
-    """Alg. 3 at the leaves.  Returns the packed graph [n,k] (int64 tensor holding the
-    64-bit entries)."""
+                      graph: torch.Tensor | None = None, workspace: torch.Tensor | None = None,
+                      nodes: torch.Tensor | None = None, leaf_up: torch.Tensor | None = None,
+                      conquer_depth: int = 0):
+    """Alg. 3.  Without nodes the conquer step stops at the leaves; with (nodes, leaf_up) from
+    efanna_build_trees it walks up to `conquer_depth` (0 = the root).  Returns the packed
+    graph [n,k] (int64 tensor holding the 64-bit entries)."""
     X = _dev(X, torch.float32)
     n, d = X.shape
     perm = _dev(perm, torch.int32)
     leaf_off = _dev(leaf_off, torch.int32)
     T = perm.shape[0]
     n_leaves = np.ascontiguousarray(n_leaves, dtype=np.int32)
+    if (nodes is None) != (leaf_up is None):
+        raise ValueError("nodes and leaf_up come together")
+    if nodes is not None:
+        nodes = _dev(nodes, torch.uint8)
+        leaf_up = _dev(leaf_up, torch.int32)
+        if nodes.shape != (T, leaf_off.shape[1], NODE_BYTES) or leaf_up.shape != leaf_off.shape:
+            raise ValueError("nodes / leaf_up do not match leaf_off")
     if graph is None:
         graph = torch.empty((n, k), dtype=torch.int64, device=X.device)
     need = lib().efanna_init_workspace_bytes(n, T)
     ws = _workspace(need, X.device) if workspace is None else workspace
     _check(lib().efanna_init_graph(X.data_ptr(), n, d, perm.data_ptr(), leaf_off.data_ptr(),
-                                   leaf_off.shape[1] - 1, n_leaves.ctypes.data_as(C.c_void_p), T,
-                                   leaf_size, k, graph.data_ptr(), ws.data_ptr(), ws.numel(),
-                                   _stream()), "efanna_init_graph")
+                                   leaf_off.shape[1] - 1, n_leaves.ctypes.data_as(C.c_void_p),
+                                   nodes.data_ptr() if nodes is not None else None,
+                                   leaf_up.data_ptr() if nodes is not None else None,
+                                   int(conquer_depth), T, leaf_size, k, graph.data_ptr(),
+                                   ws.data_ptr(), ws.numel(), _stream()), "efanna_init_graph")
     return graph
 
 
