@@ -78,7 +78,7 @@ def main():
     Xd = torch.from_numpy(X).to(dev)
     L_ = efanna.lib()
     ws_tree = torch.empty(L_.efanna_trees_workspace_bytes(n, d, T, S, 0), dtype=torch.uint8, device=dev)
-    ws_init = torch.empty(max(256, L_.efanna_init_workspace_bytes(n, T)), dtype=torch.uint8, device=dev)
+    ws_init = torch.empty(max(256, L_.efanna_init_workspace_bytes(n, 0)), dtype=torch.uint8, device=dev)
     ws_nnd = torch.empty(L_.efanna_nndescent_workspace_bytes(n, K, L), dtype=torch.uint8, device=dev)
     graph = torch.empty((n, K), dtype=torch.int64, device=dev)
     stats = torch.zeros((I, 4), dtype=torch.int64, device=dev)

@@ -98,6 +98,8 @@ const char *efanna_status_string(int status);
  * leaf_up  [device] out or NULL (both or neither), n_trees*(max_leaves+1) int32: for leaf l of
  *          tree t, 2 * (its parent node) + (1 if it is the right child); -1 if the tree is a
  *          single leaf.  With nodes the workspace must be sized with with_nodes = 1.
+ * tree_depth [host] out or NULL: depth of the deepest internal node over all trees (root 0),
+ *          -1 if every tree is a single leaf or nodes is NULL.
  * Synchronises the stream (the host drives one launch group per tree level).
  * Limits: n*n_trees < 2^31, 1 <= leaf_size <= EFANNA_MAX_LEAF, n_trees <= EFANNA_MAX_TREES.
  */
@@ -106,8 +108,8 @@ size_t efanna_trees_workspace_bytes(int64_t n, int32_t d, int32_t n_trees, int32
 
 int efanna_build_trees(const float *X, int64_t n, int32_t d, int32_t n_trees, int32_t leaf_size,
                        uint64_t seed, int32_t *perm, int32_t *leaf_off, int32_t max_leaves,
-                       int32_t *n_leaves, efanna_node *nodes, int32_t *leaf_up, void *ws,
-                       size_t ws_bytes, void *stream);
+                       int32_t *n_leaves, efanna_node *nodes, int32_t *leaf_up,
+                       int32_t *tree_depth, void *ws, size_t ws_bytes, void *stream);
 
 /* ---- Alg. 3, conquer step ---------------------------------------------------------------
  * Candidates of point i: in every tree, the other members of its leaf and - when nodes is
@@ -118,19 +120,23 @@ int efanna_build_trees(const float *X, int64_t n, int32_t d, int32_t n_trees, in
  * Every entry carries the "new" mark (Alg. 4 starts from G_new = G_init).
  *
  * perm, leaf_off, max_leaves, n_leaves, nodes, leaf_up: as produced by efanna_build_trees.
- * nodes, leaf_up NULL: the step stops at the leaves (conquer_depth is ignored).
- * conquer_depth    >= 0; 0 walks up to the root.
+ * nodes, leaf_up NULL: the step stops at the leaves (tree_depth, conquer_depth are ignored).
+ * tree_depth       as returned by efanna_build_trees (a larger value only costs workspace).
+ * conquer_depth    >= 0; 0 walks up to the root.  levels = tree_depth - conquer_depth + 1 is
+ *                  the number of ancestors a leaf can have in range; the workspace holds one
+ *                  int32 per point and level (efanna_init_workspace_bytes(n, levels); levels
+ *                  <= 0 or no nodes: 256 bytes).
  * graph    [device] out, n*k entries.
  * Asynchronous on `stream`.  Limits: k <= EFANNA_MAX_K, k < n, n < 2^31 - 256, a leaf
  * of leaf_size rows of d floats must fit the 160 KB LDS; with nodes: leaf_size <= 16, d a
- * multiple of 4 and X 16-byte aligned (EFANNA_EUNSUPPORTED otherwise).
+ * multiple of 4, X 16-byte aligned and levels <= 64 (EFANNA_EUNSUPPORTED otherwise).
  */
-size_t efanna_init_workspace_bytes(int64_t n, int32_t n_trees);
+size_t efanna_init_workspace_bytes(int64_t n, int32_t levels);
 
 int efanna_init_graph(const float *X, int64_t n, int32_t d, const int32_t *perm,
                       const int32_t *leaf_off, int32_t max_leaves, const int32_t *n_leaves,
-                      const efanna_node *nodes, const int32_t *leaf_up, int32_t conquer_depth,
-                      int32_t n_trees, int32_t leaf_size, int32_t k, efanna_entry *graph,
+                      const efanna_node *nodes, const int32_t *leaf_up, int32_t tree_depth,
+                      int32_t conquer_depth, int32_t n_trees, int32_t leaf_size, int32_t k, efanna_entry *graph,
                       void *ws, size_t ws_bytes, void *stream);
 
 /* ---- Alg. 4: NN-descent refinement -----------------------------------------------------

@@ -372,33 +372,21 @@ init_reg_kernel(const float *__restrict__ X, int d, const int *__restrict__ perm
 // Alg. 3 above the leaves: for every ancestor N of a point's leaf with depth >= dep, the point
 // is sent down the subtree of N's other child by the split test of each node it meets, and the
 // members of the leaf it reaches become candidates.  Runs after the leaf step of the same
-// tree; one wave per (home) leaf, which owns its members' graph rows during the launch.
+// tree, in two kernels: classify_kernel finds the leaf reached for every point and level,
+// conquer_kernel (one wave per home leaf, which owns its members' graph rows during the
+// launch) evaluates the distances and merges.
 //
-// The members of a home leaf share their ancestors but may land in different leaves of a
-// sibling subtree; each distinct one is taken in turn: its rows are loaded as a second
-// register set, laid out like the home rows, and the sixteen rotations of it against the home
-// rows (two halves of eight, as in init_reg_kernel) meet every home member with every member
-// of that leaf.  Rows are merged by rank in LDS after every such leaf and stored at the end.
+// The members of a home leaf share their ancestors but land in different leaves of a sibling
+// subtree more often than not, so every member is handled against its own leaf: lane (r, g)
+// keeps its share of home member r as in init_reg_kernel and loads the same share of the
+// members of the leaf that r reached, one after the other (members that reached the same leaf
+// find those rows in the cache).  Eight such members give eight sets of partial sums, which
+// the four lanes of a row add up in the fixed tree, transposed, as for rotations.  Rows are
+// merged by rank in LDS after every level and stored at the end.
 // Requires leaves of at most 16 points, d % 4 == 0 and a 16-byte aligned X.
 
-template <int T>
-__device__ inline void cross_round(const float4 (&va)[8], const float4 (&vb)[8], int n_pieces, float (&p)[4])
-{
-#pragma unroll
-    for (int s = 0; s < 8; ++s) {
-        if (s >= n_pieces) break;
-        const float d0 = va[s].x - __int_as_float(EF_ROW_ROR(__float_as_int(vb[s].x), T));
-        const float d1 = va[s].y - __int_as_float(EF_ROW_ROR(__float_as_int(vb[s].y), T));
-        const float d2 = va[s].z - __int_as_float(EF_ROW_ROR(__float_as_int(vb[s].z), T));
-        const float d3 = va[s].w - __int_as_float(EF_ROW_ROR(__float_as_int(vb[s].w), T));
-        p[0] = __builtin_fmaf(d0, d0, p[0]);
-        p[1] = __builtin_fmaf(d1, d1, p[1]);
-        p[2] = __builtin_fmaf(d2, d2, p[2]);
-        p[3] = __builtin_fmaf(d3, d3, p[3]);
-    }
-}
-// rotation 0 pairs lane r with itself: the operand needs no move
-__device__ inline void cross_round0(const float4 (&va)[8], const float4 (&vb)[8], int n_pieces, float (&p)[4])
+// partial sums of one pair: lane (r, g) adds the terms of its coordinates
+__device__ inline void accumulate_pair(const float4 (&va)[8], const float4 (&vb)[8], int n_pieces, float (&p)[4])
 {
 #pragma unroll
     for (int s = 0; s < 8; ++s) {
@@ -412,8 +400,8 @@ __device__ inline void cross_round0(const float4 (&va)[8], const float4 (&vb)[8]
     }
 }
 
-// eight partial-sum sets (one per rotation) -> lane g keeps the finished distances of
-// rotations 2g and 2g+1 of the eight; same adds, in the same tree, as the fixed order
+// eight partial-sum sets (one per pair) -> lane g keeps the finished distances of pairs 2g
+// and 2g+1 of the eight; same adds, in the same tree, as the fixed order
 __device__ inline void reduce_rotations(const float (&P)[8][4], int g, float (&out)[2])
 {
     const bool hi = g & 2, odd = g & 1;
@@ -436,95 +424,132 @@ __device__ inline void reduce_rotations(const float (&P)[8][4], int g, float (&o
     for (int t = 0; t < 2; ++t) out[t] = (R[t][0] + R[t][2]) + (R[t][1] + R[t][3]);
 }
 
+// Which leaf of each sibling subtree every point reaches: etab[p * levels + k] for the point at
+// position p of the tree's id array and the k-th ancestor of its leaf (k = 0: the leaf's
+// parent), -1 where there is no such ancestor or its depth is below dep.  A wave takes one
+// leaf at a time: all lanes climb the ancestors together (the links are the same for every
+// member), then lane (member r, slot g) sends member r down the sibling subtrees of ancestors
+// g, g+4, ...  Light on registers, so that many waves hide the chains of dependent loads.
+// Node j is the right child of its parent pj iff j > pj, leaf l iff l >= pj (nodes are
+// numbered by the leaf that starts their right part).  Links are clamped to the tables and
+// walks are bounded, so tables that are not the tree builder's cannot lead out of them.
+__global__ void __launch_bounds__(kBlock)
+classify_kernel(const float *__restrict__ X, int d, const int *__restrict__ perm_t,
+                const int *__restrict__ leaf_off_t, int n_leaves,
+                const efanna_node *__restrict__ nodes_t, const int *__restrict__ leaf_up_t, int dep,
+                int levels, int *__restrict__ etab)
+{
+    __shared__ int sib_sh[kBlock / EF_WAVE][64];      // sibling subtree of the k-th ancestor
+    const int lane = ef_lane(), wave = threadIdx.x / EF_WAVE, r16 = lane & 15, g = lane >> 4;
+    const int last = n_leaves - 1;
+    const int n_waves = gridDim.x * (kBlock / EF_WAVE);
+    for (int leaf = blockIdx.x * (kBlock / EF_WAVE) + wave; leaf < n_leaves; leaf += n_waves) {
+        const int b0 = leaf_off_t[leaf];
+        const int s = min(leaf_off_t[leaf + 1] - b0, 16);
+        const int my_id = r16 < s ? perm_t[b0 + r16] : -1;
+        int n_lev = 0;
+        int up = min(leaf_up_t[leaf], 2 * last + 1);
+        while (up >= 0 && n_lev < levels && n_lev < 64) {
+            const int j = up >> 1;
+            const efanna_node anc = nodes_t[j];
+            if (anc.depth < dep) break;
+            if (lane == 0) sib_sh[wave][n_lev] = anc.child[1 - (up & 1)];
+            ++n_lev;
+            const int pj = min(anc.parent, last);
+            up = pj < 0 ? -1 : pj * 2 + (j > pj ? 1 : 0);
+        }
+        // one wave: its LDS operations complete in program order; keep the compiler from moving
+        // the reads below above the writes
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        if (r16 < s) {
+            for (int k = g; k < levels; k += 4) {
+                int e = -1;
+                if (k < n_lev) {
+                    int c = sib_sh[wave][k];
+                    for (int steps = 0; c >= 0 && steps < 4096; ++steps) {
+                        const efanna_node nd = nodes_t[min(c, last)];
+                        const bool left = nd.dim < 0 ||
+                                          (long long)nd.cnt * ef_quantise(X[(size_t)my_id * d + min(nd.dim, d - 1)]) < nd.sum;
+                        c = nd.child[left ? 0 : 1];
+                    }
+                    e = c >= 0 ? 0 : min(~c, last);
+                }
+                etab[(size_t)(b0 + r16) * levels + k] = e;
+            }
+        }
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+    }
+}
+
 __global__ void __launch_bounds__(EF_WAVE)
 conquer_kernel(const float *__restrict__ X, int d, const int *__restrict__ perm_t,
-               const int *__restrict__ leaf_off_t, int n_leaves,
-               const efanna_node *__restrict__ nodes_t, const int *__restrict__ leaf_up_t, int dep,
-               int K, u64 *graph)
+               const int *__restrict__ leaf_off_t, int n_leaves, const int *__restrict__ etab,
+               int levels, int K, u64 *graph)
 {
     extern __shared__ __align__(16) float smem[];
     u64 *pools_a = (u64 *)smem;                       // [16][K] rows being merged, ascending
     u64 *pools_b = pools_a + 16 * (size_t)K;          // [16][K] the other copy
     u64 *cand = pools_b + 16 * (size_t)K;             // [16][kCandPitch]
-    int *uid_b = (int *)(cand + 16 * kCandPitch);     // [16] members of the sibling-side leaf
+    int *uid_b = (int *)(cand + 16 * kCandPitch);     // [16][16] members of the leaf each row reached
     const int lane = threadIdx.x, r16 = lane & 15, g = lane >> 4;
-    const int dirn = (EF_ROW_ROR(r16, 1) - r16) & 15;      // lane r receives from lane r + dirn
     for (int leaf = blockIdx.x; leaf < n_leaves; leaf += gridDim.x) {
-        // links read from the tables are clamped to the tables' range and the walks are bounded,
-        // so that tables which are not what the tree builder writes cannot lead out of them
-        const int last = n_leaves - 1;
-        int up = min(leaf_up_t[leaf], 2 * last + 1);
-        if (up < 0 || nodes_t[up >> 1].depth < dep) continue;      // nothing above this leaf to visit
         const int b0 = leaf_off_t[leaf];
         const int s = min(leaf_off_t[leaf + 1] - b0, 16);
+        // the ancestors are those of the leaf: a level exists for all members or for none
+        int e = r16 < s ? etab[(size_t)(b0 + r16) * levels] : -1;
+        if (__ballot(e >= 0) == 0) continue;      // nothing above this leaf to visit
         const int my_id = r16 < s ? perm_t[b0 + r16] : -1;
         const float *pa = X + (size_t)max(my_id, 0) * d + 4 * g;
         __syncthreads();                  // the previous leaf's LDS reads are done
         u64 *cur = pools_a, *nxt = pools_b;
         for (int c = g; c < K; c += 4)
             cur[r16 * K + c] = r16 < s ? graph[(size_t)my_id * K + c] : ef_empty_entry(K - 1 - c);
-        for (int climbed = 0; up >= 0 && climbed < 4096; ++climbed) {
-            const efanna_node anc = nodes_t[up >> 1];
-            if (anc.depth < dep) break;
-            // ---- every member goes down the sibling subtree ---------------------------------
-            int e = -1;      // leaf reached (members only)
-            if (r16 < s) {
-                int c = anc.child[1 - (up & 1)];
-                for (int steps = 0; c >= 0 && steps < 4096; ++steps) {
-                    const efanna_node nd = nodes_t[min(c, last)];
-                    const bool left = nd.dim < 0 ||
-                                      (long long)nd.cnt * ef_quantise(X[(size_t)my_id * d + min(nd.dim, d - 1)]) < nd.sum;
-                    c = nd.child[left ? 0 : 1];
-                }
-                e = c >= 0 ? 0 : min(~c, last);
+        for (int k = 0; k < levels; ++k) {
+            if (k > 0) {
+                e = r16 < s ? etab[(size_t)(b0 + r16) * levels + k] : -1;
+                if (__ballot(e >= 0) == 0) break;
             }
-            // ---- one distinct leaf at a time --------------------------------------------------
-            for (;;) {
-                const u64 pending = __ballot(e >= 0);
-                if (pending == 0) break;
-                const int e_cur = __shfl(e, __ffsll((long long)pending) - 1, EF_WAVE);
-                const bool mine = e == e_cur;      // this member's candidates come from leaf e_cur
-                if (mine) e = -1;
-                const int bb = leaf_off_t[e_cur];
-                const int sb = min(leaf_off_t[e_cur + 1] - bb, 16);
-                const int id_b = r16 < sb ? perm_t[bb + r16] : -1;
-                if (g == 0) uid_b[r16] = id_b;
-                const float *pb = X + (size_t)max(id_b, 0) * d + 4 * g;
-                float dist[4];      // rotations 2g, 2g+1, 8+2g, 8+2g+1
+            e = min(e, n_leaves - 1);
+            {
+                // ---- every member against the members of the leaf it reached ----------------------
+                const bool target = e >= 0;
+                const int bb = target ? leaf_off_t[e] : 0;
+                const int sb = target ? min(leaf_off_t[e + 1] - bb, 16) : 0;
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const int j = 4 * g + q;
+                    uid_b[r16 * 16 + j] = j < sb ? perm_t[bb + j] : -1;
+                }
+                __syncthreads();                  // uid_b and the current rows are visible
+                float dist[4];      // members 2g, 2g+1, 8+2g, 8+2g+1 of that leaf
 #pragma unroll
                 for (int half = 0; half < 2; ++half) {
                     float P[8][4];
 #pragma unroll
                     for (int t = 0; t < 8; ++t) P[t][0] = P[t][1] = P[t][2] = P[t][3] = 0.0f;
                     for (int c0 = 0; c0 < d; c0 += 128) {
-                        float4 va[8], vb[8];
+                        float4 va[8];
 #pragma unroll
                         for (int q = 0; q < 8; ++q) {
                             const bool in = c0 + 16 * q + 4 * g + 3 < d;      // d % 4 == 0: a piece is in or out
                             va[q] = in && r16 < s ? *reinterpret_cast<const float4 *>(pa + c0 + 16 * q)
                                                   : make_float4(0.f, 0.f, 0.f, 0.f);
-                            vb[q] = in && r16 < sb ? *reinterpret_cast<const float4 *>(pb + c0 + 16 * q)
-                                                   : make_float4(0.f, 0.f, 0.f, 0.f);
                         }
                         const int n_pieces = min(8, (d - c0 + 15) >> 4);
-                        if (half == 0) {
-                            cross_round0(va, vb, n_pieces, P[0]);
-                            cross_round<1>(va, vb, n_pieces, P[1]);
-                            cross_round<2>(va, vb, n_pieces, P[2]);
-                            cross_round<3>(va, vb, n_pieces, P[3]);
-                            cross_round<4>(va, vb, n_pieces, P[4]);
-                            cross_round<5>(va, vb, n_pieces, P[5]);
-                            cross_round<6>(va, vb, n_pieces, P[6]);
-                            cross_round<7>(va, vb, n_pieces, P[7]);
-                        } else {
-                            cross_round<8>(va, vb, n_pieces, P[0]);
-                            cross_round<9>(va, vb, n_pieces, P[1]);
-                            cross_round<10>(va, vb, n_pieces, P[2]);
-                            cross_round<11>(va, vb, n_pieces, P[3]);
-                            cross_round<12>(va, vb, n_pieces, P[4]);
-                            cross_round<13>(va, vb, n_pieces, P[5]);
-                            cross_round<14>(va, vb, n_pieces, P[6]);
-                            cross_round<15>(va, vb, n_pieces, P[7]);
+#pragma unroll
+                        for (int t = 0; t < 8; ++t) {
+                            const int id_b = uid_b[r16 * 16 + 8 * half + t];
+                            const float *pb = X + (size_t)max(id_b, 0) * d + 4 * g + c0;
+                            float4 vb[8];
+#pragma unroll
+                            for (int q = 0; q < 8; ++q) {
+                                const bool in = c0 + 16 * q + 4 * g + 3 < d;
+                                vb[q] = in && id_b >= 0 ? *reinterpret_cast<const float4 *>(pb + 16 * q)
+                                                        : make_float4(0.f, 0.f, 0.f, 0.f);
+                            }
+                            accumulate_pair(va, vb, n_pieces, P[t]);
                         }
                     }
                     float two[2];
@@ -532,17 +557,14 @@ conquer_kernel(const float *__restrict__ X, int d, const int *__restrict__ perm_
                     dist[2 * half] = two[0];
                     dist[2 * half + 1] = two[1];
                 }
-                __syncthreads();                  // uid_b and the current rows are visible
                 // ---- candidates of row r16 and their ranks ------------------------------------
-                const bool target = mine;      // the four lanes of a row hold the same verdict
                 u64 key[4];
                 int lt[4];
                 const u64 *row = cur + r16 * K;
 #pragma unroll
                 for (int c = 0; c < 4; ++c) {
-                    const int rot = 8 * (c >> 1) + 2 * g + (c & 1);
-                    const int bm = (r16 + dirn * rot) & 15;      // member of the other leaf met at this rotation
-                    key[c] = target && bm < sb ? ef_pack(dist[c], uid_b[bm], 1) : ~0ULL;
+                    const int bm = 8 * (c >> 1) + 2 * g + (c & 1);      // member of the leaf reached
+                    key[c] = bm < sb ? ef_pack(dist[c], uid_b[r16 * 16 + bm], 1) : ~0ULL;
                     int lo = 0, hi_ = K;
                     if (key[c] != ~0ULL) {
                         while (lo < hi_) {
@@ -580,9 +602,6 @@ conquer_kernel(const float *__restrict__ X, int d, const int *__restrict__ perm_
                 cur = nxt;
                 nxt = tmp;
             }
-            // ---- next ancestor ---------------------------------------------------------------------
-            const int j = up >> 1, pj = min(anc.parent, last);
-            up = pj < 0 ? -1 : pj * 2 + (nodes_t[pj].child[1] == j ? 1 : 0);
         }
         if (r16 < s)
             for (int c = g; c < K; c += 4) graph[(size_t)my_id * K + c] = cur[r16 * K + c];
@@ -1522,16 +1541,18 @@ extern "C" const char *efanna_status_string(int status)
     }
 }
 
-extern "C" size_t efanna_init_workspace_bytes(int64_t n, int32_t n_trees)
+extern "C" size_t efanna_init_workspace_bytes(int64_t n, int32_t levels)
 {
-    if (n < 1 || n_trees < 1) return 0;
-    return 256;   // nothing is needed at present; kept so that callers need not change
+    if (n < 1) return 0;
+    // one leaf index per point and visited level above the leaves
+    return levels > 0 ? align_up((size_t)n * (size_t)levels * 4) : 256;
 }
 
 extern "C" int efanna_init_graph(const float *X, int64_t n, int32_t d, const int32_t *perm,
                                  const int32_t *leaf_off, int32_t max_leaves,
                                  const int32_t *n_leaves, const efanna_node *nodes,
-                                 const int32_t *leaf_up, int32_t conquer_depth, int32_t n_trees,
+                                 const int32_t *leaf_up, int32_t tree_depth,
+                                 int32_t conquer_depth, int32_t n_trees,
                                  int32_t leaf_size, int32_t k, efanna_entry *graph_, void *ws,
                                  size_t ws_bytes, void *stream)
 {
@@ -1541,7 +1562,10 @@ extern "C" int efanna_init_graph(const float *X, int64_t n, int32_t d, const int
         leaf_size > EFANNA_MAX_LEAF || k < 1 || k > EFANNA_MAX_K || k >= n || max_leaves < 1 ||
         n >= 2147483647LL - 256)
         return EFANNA_EINVAL;
-    if (!ws || ((uintptr_t)ws & 255) || ws_bytes < efanna_init_workspace_bytes(n, n_trees))
+    // levels above the leaves that the conquer step visits (none without nodes)
+    const int levels = nodes ? (tree_depth - conquer_depth + 1 > 64 ? 64 : tree_depth - conquer_depth + 1) : 0;
+    if (nodes && tree_depth - conquer_depth + 1 > 64) return EFANNA_EUNSUPPORTED;
+    if (!ws || ((uintptr_t)ws & 255) || ws_bytes < efanna_init_workspace_bytes(n, levels))
         return EFANNA_EWORKSPACE;
     if (n * (int64_t)k >= 2147483647LL) return EFANNA_EINVAL;   // LDS row indices are 32-bit
     for (int t = 0; t < n_trees; ++t)
@@ -1555,15 +1579,19 @@ extern "C" int efanna_init_graph(const float *X, int64_t n, int32_t d, const int
     if (nodes && !reg_ok) return EFANNA_EUNSUPPORTED;      // the step above the leaves has one kernel only
     if (reg_ok) {
         const size_t reg_lds = (size_t)16 * k * 8 + (size_t)16 * kCandPitch * 8 + 16 * 4;
-        const size_t conquer_lds = (size_t)2 * 16 * k * 8 + (size_t)16 * kCandPitch * 8 + 16 * 4;
+        const size_t conquer_lds = (size_t)2 * 16 * k * 8 + (size_t)16 * kCandPitch * 8 + 16 * 16 * 4;
         for (int t = 0; t < n_trees; ++t) {
             const int32_t *perm_t = perm + (size_t)t * n, *off_t = leaf_off + (size_t)t * (max_leaves + 1);
             init_reg_kernel<<<min(n_leaves[t], kRegGrid), EF_WAVE, reg_lds, st>>>(
                 X, d, perm_t, off_t, n_leaves[t], k, graph, t == 0);
-            if (nodes)
-                conquer_kernel<<<min(n_leaves[t], kRegGrid), EF_WAVE, conquer_lds, st>>>(
+            if (levels > 0) {
+                int *etab = (int *)ws;
+                classify_kernel<<<min(grid_for((size_t)n_leaves[t], kBlock / EF_WAVE), 256 * 8), kBlock, 0, st>>>(
                     X, d, perm_t, off_t, n_leaves[t], nodes + (size_t)t * (max_leaves + 1),
-                    leaf_up + (size_t)t * (max_leaves + 1), conquer_depth, k, graph);
+                    leaf_up + (size_t)t * (max_leaves + 1), conquer_depth, levels, etab);
+                conquer_kernel<<<min(n_leaves[t], kRegGrid), EF_WAVE, conquer_lds, st>>>(
+                    X, d, perm_t, off_t, n_leaves[t], etab, levels, k, graph);
+            }
         }
         EF_HIP_CHECK(hipGetLastError());
         return EFANNA_OK;

@@ -38,6 +38,7 @@ struct Counters {
     int next_nodes;
     int bad_input;
     int small_nodes;
+    int max_depth;      // deepest internal node (only tracked with node export)
 };
 
 // A node small enough to be finished inside one workgroup (finish_kernel).
@@ -336,7 +337,10 @@ __global__ void children_kernel(Node *cur, int n_cur, Node *next, int *next_dims
     base_s = __shfl(base_s, EF_WAVE - 1, EF_WAVE);
     if (s >= n_cur) return;
     int slot = base + inc - want, slot_s = base_s + inc_s - want_s;
-    if (rec) record_node(rec, leaf_rec, nd.mid, nd.sum, nd.dim, nd.e - nd.b, nd.parent, nd.depth);
+    if (rec) {
+        record_node(rec, leaf_rec, nd.mid, nd.sum, nd.dim, nd.e - nd.b, nd.parent, nd.depth);
+        if (s == 0) atomicMax(&c->max_depth, nd.depth);      // all nodes of a level share their depth
+    }
     const int tree = nd.b / n;
     const u64 key = ef_stream_key(seed, tree);
     for (int side = 0; side < 2; ++side) {
@@ -417,7 +421,8 @@ struct LNode {
 
 __global__ void __launch_bounds__(kBlock)
 finish_kernel(const float *__restrict__ XT, int d, int *perm, const SmallNode *__restrict__ small,
-              unsigned char *leaf_flag, int S, u64 seed, int n, NodeRec *rec, int *leaf_rec)
+              unsigned char *leaf_flag, int S, u64 seed, int n, NodeRec *rec, int *leaf_rec,
+              int *max_depth)
 {
     // One 16-byte aligned LDS block carved by hand (no separate static LDS variables, whose
     // size would shift the 8-byte node records off their alignment).
@@ -427,6 +432,7 @@ finish_kernel(const float *__restrict__ XT, int d, int *perm, const SmallNode *_
     int *lcnt = fsm + 5 * kFinMax;                                 // [kFinMax + 1]
     int *wave_tot = fsm + 6 * kFinMax + 4;                         // [kBlock / EF_WAVE]
     int &n_next_sh = fsm[6 * kFinMax + 2];
+    int &depth_sh = fsm[6 * kFinMax + 3];                          // deepest node of this subtree
     LNode *const tabs_base = (LNode *)(fsm + 6 * kFinMax + 8);     // [2][kFinNodes], 8-byte aligned
     const SmallNode seg = small[blockIdx.x];
     const int cnt = seg.e - seg.b, tid = threadIdx.x;
@@ -450,6 +456,7 @@ finish_kernel(const float *__restrict__ XT, int d, int *perm, const SmallNode *_
         r.pad = 0;
         tabs_base[0] = r;
         n_next_sh = 0;
+        depth_sh = seg.depth;
     }
     __syncthreads();
     int cur = 0, n_cur = 1;
@@ -505,7 +512,10 @@ finish_kernel(const float *__restrict__ XT, int d, int *perm, const SmallNode *_
                 nd.moved = 1;
                 nd.mid = nd.b + nl;
             }
-            if (rec) record_node(rec, leaf_rec, seg.b + nd.mid, nd.sum, nd.dim, c, nd.parent, nd.depth);
+            if (rec) {
+                record_node(rec, leaf_rec, seg.b + nd.mid, nd.sum, nd.dim, c, nd.parent, nd.depth);
+                if (k == 0) depth_sh = nd.depth;      // levels are visited in order of depth
+            }
             for (int side = 0; side < 2; ++side) {
                 const int cb = side ? nd.mid : nd.b, ce = side ? nd.e : nd.mid;
                 nd.child[side] = -1;
@@ -560,6 +570,7 @@ finish_kernel(const float *__restrict__ XT, int d, int *perm, const SmallNode *_
         __syncthreads();
     }
     for (int p = tid; p < cnt; p += kBlock) perm[seg.b + p] = ids_base[cur * kFinMax + p];
+    if (rec && tid == 0) atomicMax(max_depth, depth_sh);
 }
 
 __global__ void iota_kernel(int *perm, int n, size_t total)
@@ -690,8 +701,8 @@ extern "C" size_t efanna_trees_workspace_bytes(int64_t n, int32_t d, int32_t n_t
 extern "C" int efanna_build_trees(const float *X, int64_t n, int32_t d, int32_t n_trees,
                                   int32_t leaf_size, uint64_t seed, int32_t *perm,
                                   int32_t *leaf_off, int32_t max_leaves, int32_t *n_leaves,
-                                  efanna_node *nodes, int32_t *leaf_up, void *ws, size_t ws_bytes,
-                                  void *stream)
+                                  efanna_node *nodes, int32_t *leaf_up, int32_t *tree_depth,
+                                  void *ws, size_t ws_bytes, void *stream)
 {
     if (!X || !perm || !leaf_off || !n_leaves || (!nodes) != (!leaf_up)) return EFANNA_EINVAL;
     if (n < 1 || d < 1 || n_trees < 1 || n_trees > EFANNA_MAX_TREES || leaf_size < 1 ||
@@ -750,7 +761,8 @@ extern "C" int efanna_build_trees(const float *X, int64_t n, int32_t d, int32_t 
         EF_HIP_CHECK(hipFuncSetAttribute((const void *)finish_kernel,
                                          hipFuncAttributeMaxDynamicSharedMemorySize, (int)fin_lds));
         finish_kernel<<<host_c.small_nodes, kBlock, fin_lds, st>>>(w.xt, d, perm_cur, w.small, w.leaf_flag,
-                                                                  S, seed, (int)n, w.rec, w.leaf_rec);
+                                                                  S, seed, (int)n, w.rec, w.leaf_rec,
+                                                                  &w.counters->max_depth);
     }
     if (perm_cur != perm)
         EF_HIP_CHECK(hipMemcpyAsync(perm, perm_cur, total * 4, hipMemcpyDeviceToDevice, st));
@@ -763,7 +775,13 @@ extern "C" int efanna_build_trees(const float *X, int64_t n, int32_t d, int32_t 
         export_nodes_kernel<<<grid_pos, kBlock, 0, st>>>(w.leaf_flag, w.lcount, w.rec, w.leaf_rec, (int)n, T,
                                                          max_leaves, nodes, leaf_up);
     EF_HIP_CHECK(hipMemcpyAsync(n_leaves, w.n_leaves_dev, (size_t)T * 4, hipMemcpyDeviceToHost, st));
+    if (nodes) EF_HIP_CHECK(hipMemcpyAsync(&host_c, w.counters, sizeof(Counters), hipMemcpyDeviceToHost, st));
     EF_HIP_CHECK(hipStreamSynchronize(st));
+    if (tree_depth) {
+        *tree_depth = -1;      // no internal node anywhere: every tree is a single leaf
+        for (int t = 0; t < T; ++t)
+            if (nodes && n_leaves[t] > 1) *tree_depth = host_c.max_depth;
+    }
     EF_HIP_CHECK(hipGetLastError());
     for (int t = 0; t < T; ++t)
         if (n_leaves[t] > max_leaves) return EFANNA_ECAPACITY;

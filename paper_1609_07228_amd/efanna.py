@@ -47,11 +47,11 @@ def lib():
         L.efanna_trees_workspace_bytes.restype = sz
         L.efanna_trees_workspace_bytes.argtypes = [i64, i32, i32, i32, i32]
         L.efanna_build_trees.restype = C.c_int
-        L.efanna_build_trees.argtypes = [vp, i64, i32, i32, i32, u64, vp, vp, i32, vp, vp, vp, vp, sz, vp]
+        L.efanna_build_trees.argtypes = [vp, i64, i32, i32, i32, u64, vp, vp, i32, vp, vp, vp, vp, vp, sz, vp]
         L.efanna_init_workspace_bytes.restype = sz
         L.efanna_init_workspace_bytes.argtypes = [i64, i32]
         L.efanna_init_graph.restype = C.c_int
-        L.efanna_init_graph.argtypes = [vp, i64, i32, vp, vp, i32, vp, vp, vp, i32, i32, i32, i32, vp, vp, sz, vp]
+        L.efanna_init_graph.argtypes = [vp, i64, i32, vp, vp, i32, vp, vp, vp, i32, i32, i32, i32, i32, vp, vp, sz, vp]
         L.efanna_nndescent_workspace_bytes.restype = sz
         L.efanna_nndescent_workspace_bytes.argtypes = [i64, i32, i32]
         L.efanna_nndescent.restype = C.c_int
@@ -96,8 +96,8 @@ def efanna_build_trees(X: torch.Tensor, n_trees: int, leaf_size: int, seed: int,
                        with_nodes: bool = False):
     """Alg. 2.  Returns (perm [T,n] int32 device, leaf_off [T,max_leaves+1] int32 device,
     n_leaves [T] int32 numpy) and, with_nodes, also (nodes [T,max_leaves+1,32] uint8 device
-    holding efanna_node records, leaf_up [T,max_leaves+1] int32 device).  Synchronises the
-    current stream."""
+    holding efanna_node records, leaf_up [T,max_leaves+1] int32 device, tree_depth int: depth of
+    the deepest internal node).  Synchronises the current stream."""
     X = _dev(X, torch.float32)
     n, d = X.shape
     max_leaves = n if max_leaves is None else int(max_leaves)
@@ -108,16 +108,17 @@ def efanna_build_trees(X: torch.Tensor, n_trees: int, leaf_size: int, seed: int,
     if with_nodes:
         nodes = torch.zeros((n_trees, max_leaves + 1, NODE_BYTES), dtype=torch.uint8, device=X.device)
         leaf_up = torch.full((n_trees, max_leaves + 1), -1, dtype=torch.int32, device=X.device)
+    depth = C.c_int32(-1)
     need = lib().efanna_trees_workspace_bytes(n, d, n_trees, leaf_size, 1 if with_nodes else 0)
     ws = _workspace(need, X.device) if workspace is None else workspace
     _check(lib().efanna_build_trees(X.data_ptr(), n, d, n_trees, leaf_size, seed, perm.data_ptr(),
                                     leaf_off.data_ptr(), max_leaves,
                                     n_leaves.ctypes.data_as(C.c_void_p),
                                     nodes.data_ptr() if with_nodes else None,
-                                    leaf_up.data_ptr() if with_nodes else None,
+                                    leaf_up.data_ptr() if with_nodes else None, C.byref(depth),
                                     ws.data_ptr(), ws.numel(), _stream()), "efanna_build_trees")
     if with_nodes:
-        return perm, leaf_off, n_leaves, nodes, leaf_up
+        return perm, leaf_off, n_leaves, nodes, leaf_up, int(depth.value)
     return perm, leaf_off, n_leaves
 
 
@@ -125,10 +126,10 @@ def efanna_init_graph(X: torch.Tensor, perm: torch.Tensor, leaf_off: torch.Tenso
                       n_leaves: np.ndarray, leaf_size: int, k: int,
                       graph: torch.Tensor | None = None, workspace: torch.Tensor | None = None,
                       nodes: torch.Tensor | None = None, leaf_up: torch.Tensor | None = None,
-                      conquer_depth: int = 0):
-    """Alg. 3.  Without nodes the conquer step stops at the leaves; with (nodes, leaf_up) from
-    efanna_build_trees it walks up to `conquer_depth` (0 = the root).  Returns the packed
-    graph [n,k] (int64 tensor holding the 64-bit entries)."""
+                      tree_depth: int = -1, conquer_depth: int = 0):
+    """Alg. 3.  Without nodes the conquer step stops at the leaves; with (nodes, leaf_up,
+    tree_depth) from efanna_build_trees it walks up to `conquer_depth` (0 = the root).
+    Returns the packed graph [n,k] (int64 tensor holding the 64-bit entries)."""
     X = _dev(X, torch.float32)
     n, d = X.shape
     perm = _dev(perm, torch.int32)
@@ -144,13 +145,14 @@ def efanna_init_graph(X: torch.Tensor, perm: torch.Tensor, leaf_off: torch.Tenso
             raise ValueError("nodes / leaf_up do not match leaf_off")
     if graph is None:
         graph = torch.empty((n, k), dtype=torch.int64, device=X.device)
-    need = lib().efanna_init_workspace_bytes(n, T)
+    levels = 0 if nodes is None else int(tree_depth) - int(conquer_depth) + 1
+    need = lib().efanna_init_workspace_bytes(n, levels)
     ws = _workspace(need, X.device) if workspace is None else workspace
     _check(lib().efanna_init_graph(X.data_ptr(), n, d, perm.data_ptr(), leaf_off.data_ptr(),
                                    leaf_off.shape[1] - 1, n_leaves.ctypes.data_as(C.c_void_p),
                                    nodes.data_ptr() if nodes is not None else None,
                                    leaf_up.data_ptr() if nodes is not None else None,
-                                   int(conquer_depth), T, leaf_size, k, graph.data_ptr(),
+                                   int(tree_depth), int(conquer_depth), T, leaf_size, k, graph.data_ptr(),
                                    ws.data_ptr(), ws.numel(), _stream()), "efanna_init_graph")
     return graph
 

@@ -53,22 +53,23 @@ def test_workspace_sizes(lib):
     assert 0 < a < b and a % 256 == 0
     assert lib.efanna_trees_workspace_bytes(1000, 16, 4, 8, 1) >= a + 1000 * 4 * 36      # node records
     assert lib.efanna_nndescent_workspace_bytes(1_000_000, 10, 10) < 600 * 2 ** 20
-    assert lib.efanna_init_workspace_bytes(1000, 4) >= 256
+    assert lib.efanna_init_workspace_bytes(1000, 0) == 256
+    assert lib.efanna_init_workspace_bytes(1000, 5) >= 1000 * 5 * 4
 
 
 def test_argument_errors_are_caught_on_the_host(lib):
     null = None
     one = C.c_void_p(256)      # never dereferenced: every call below must fail first
-    assert lib.efanna_build_trees(null, 10, 4, 1, 2, 0, one, one, 10, one, None, None, one, 1 << 20, None) == -1
-    assert lib.efanna_build_trees(one, 10, 0, 1, 2, 0, one, one, 10, one, None, None, one, 1 << 20, None) == -1
-    assert lib.efanna_build_trees(one, 10, 4, 65, 2, 0, one, one, 10, one, None, None, one, 1 << 20, None) == -1
-    assert lib.efanna_build_trees(one, 10, 4, 1, 65, 0, one, one, 10, one, None, None, one, 1 << 20, None) == -1
-    assert lib.efanna_build_trees(one, 10, 4, 1, 2, 0, one, one, 10, one, None, None, None, 0, None) == -2
-    assert lib.efanna_build_trees(one, 10, 4, 1, 2, 0, one, one, 10, one, None, None, C.c_void_p(257), 1 << 20, None) == -2
-    assert lib.efanna_build_trees(one, 10, 4, 1, 2, 0, one, one, 10, one, None, None, one, 16, None) == -2
+    assert lib.efanna_build_trees(null, 10, 4, 1, 2, 0, one, one, 10, one, None, None, None, one, 1 << 20, None) == -1
+    assert lib.efanna_build_trees(one, 10, 0, 1, 2, 0, one, one, 10, one, None, None, None, one, 1 << 20, None) == -1
+    assert lib.efanna_build_trees(one, 10, 4, 65, 2, 0, one, one, 10, one, None, None, None, one, 1 << 20, None) == -1
+    assert lib.efanna_build_trees(one, 10, 4, 1, 65, 0, one, one, 10, one, None, None, None, one, 1 << 20, None) == -1
+    assert lib.efanna_build_trees(one, 10, 4, 1, 2, 0, one, one, 10, one, None, None, None, None, 0, None) == -2
+    assert lib.efanna_build_trees(one, 10, 4, 1, 2, 0, one, one, 10, one, None, None, None, C.c_void_p(257), 1 << 20, None) == -2
+    assert lib.efanna_build_trees(one, 10, 4, 1, 2, 0, one, one, 10, one, None, None, None, one, 16, None) == -2
     # nodes without leaf_up (and the reverse) is an argument error
-    assert lib.efanna_build_trees(one, 10, 4, 1, 2, 0, one, one, 10, one, one, None, one, 1 << 20, None) == -1
-    assert lib.efanna_init_graph(one, 10, 4, one, one, 10, one, None, one, 0, 1, 2, 3, one, one, 256, None) == -1
+    assert lib.efanna_build_trees(one, 10, 4, 1, 2, 0, one, one, 10, one, one, None, None, one, 1 << 20, None) == -1
+    assert lib.efanna_init_graph(one, 10, 4, one, one, 10, one, None, one, 5, 0, 1, 2, 3, one, one, 256, None) == -1
     assert lib.efanna_nndescent(one, 10, 4, 10, one, 1, 4, 0, 0, None, None, one, 1 << 20, None) == -1  # k >= n
     assert lib.efanna_nndescent(one, 100, 4, 129, one, 1, 4, 0, 0, None, None, one, 1 << 30, None) == -1
     assert lib.efanna_get_graph(null, 10, 4, one, one, None, None) == -1

@@ -31,7 +31,7 @@ def test_headline_workload_bit_exact_against_oracle():
 
     # the benchmark's launch configuration
     ws_tree = torch.empty(L_.efanna_trees_workspace_bytes(n, d, T, S, 0), dtype=torch.uint8, device=dev)
-    ws_init = torch.empty(max(256, L_.efanna_init_workspace_bytes(n, T)), dtype=torch.uint8, device=dev)
+    ws_init = torch.empty(max(256, L_.efanna_init_workspace_bytes(n, 0)), dtype=torch.uint8, device=dev)
     ws_nnd = torch.empty(L_.efanna_nndescent_workspace_bytes(n, K, L), dtype=torch.uint8, device=dev)
     graph = torch.empty((n, K), dtype=torch.int64, device=dev)
     stats = torch.zeros((I, 4), dtype=torch.int64, device=dev)

@@ -157,8 +157,9 @@ def test_init_graph_small_leaf_shapes(ef, d, S, K, T):
 
 
 def tree_nodes_equal(ef, X, T, S, seed):
-    perm, off, nl, nodes, up = ef.efanna_build_trees(dev(X), T, S, seed, with_nodes=True)
+    perm, off, nl, nodes, up, depth = ef.efanna_build_trees(dev(X), T, S, seed, with_nodes=True)
     operm, ooff, onl, onodes, oup = oracle.build_trees_nodes(X, T, S, seed)
+    assert depth == max([int(onodes[t, 1:onl[t]]["depth"].max()) for t in range(T) if onl[t] > 1], default=-1)
     assert np.array_equal(nl, onl) and np.array_equal(host(perm), operm)
     gn = host(nodes).view(oracle.NODE_DTYPE)[..., 0]
     gu = host(up)
@@ -167,7 +168,7 @@ def tree_nodes_equal(ef, X, T, S, seed):
         assert np.array_equal(host(off)[t, :L + 1], ooff[t, :L + 1])
         assert gn[t, 1:L].tobytes() == onodes[t, 1:L].tobytes()
         assert np.array_equal(gu[t, :L], oup[t, :L])
-    return (perm, off, nl, nodes, up), (operm, ooff, onl, onodes, oup)
+    return (perm, off, nl, nodes, up, depth), (operm, ooff, onl, onodes, oup)
 
 
 @pytest.mark.parametrize("name,n,T,S", [
@@ -184,8 +185,8 @@ def test_tree_nodes_edge_cases(ef):
     X = np.zeros((300, 4), dtype=np.float32)                    # every split positional
     tree_nodes_equal(ef, X, 2, 4, 5)
     X = np.arange(40, dtype=np.float32).reshape(10, 4)
-    (_, _, nl, _, up), _ = tree_nodes_equal(ef, X, 3, 16, 1)    # a single leaf: no nodes at all
-    assert list(nl) == [1, 1, 1] and host(up)[0, 0] == -1
+    (_, _, nl, _, up, depth), _ = tree_nodes_equal(ef, X, 3, 16, 1)    # a single leaf: no nodes at all
+    assert list(nl) == [1, 1, 1] and host(up)[0, 0] == -1 and depth == -1
 
 
 @pytest.mark.parametrize("name,n,T,S,K,deps", [
@@ -198,13 +199,14 @@ def test_conquer_above_the_leaves_bit_exact(ef, name, n, T, S, K, deps):
     g, o = tree_nodes_equal(ef, X, T, S, synth.ALGO_SEED)
     for dep in deps:
         graph = ef.efanna_init_graph(dev(X), g[0], g[1], g[2], S, K, nodes=g[3], leaf_up=g[4],
-                                     conquer_depth=dep)
+                                     tree_depth=g[5], conquer_depth=dep)
         want = oracle.conquer_graph(X, *o, dep, K)
         ids, dists = graph_equal(ef, graph, want)
         oracle.check_graph_invariants(X, ids, dists)
     # a depth below every leaf is the leaf step
     plain = ef.efanna_init_graph(dev(X), g[0], g[1], g[2], S, K)
-    deep = ef.efanna_init_graph(dev(X), g[0], g[1], g[2], S, K, nodes=g[3], leaf_up=g[4], conquer_depth=10_000)
+    deep = ef.efanna_init_graph(dev(X), g[0], g[1], g[2], S, K, nodes=g[3], leaf_up=g[4], tree_depth=g[5],
+                                conquer_depth=10_000)
     assert torch.equal(ef.efanna_get_graph(plain)[0], ef.efanna_get_graph(deep)[0])
 
 
@@ -212,12 +214,13 @@ def test_conquer_shapes_and_limits(ef):
     rng = np.random.default_rng(21)
     X = rng.standard_normal((4_001, 200)).astype(np.float32)     # two 128-coordinate pieces, ragged
     g, o = tree_nodes_equal(ef, X, 2, 13, 3)
-    graph = ef.efanna_init_graph(dev(X), g[0], g[1], g[2], 13, 10, nodes=g[3], leaf_up=g[4], conquer_depth=4)
+    graph = ef.efanna_init_graph(dev(X), g[0], g[1], g[2], 13, 10, nodes=g[3], leaf_up=g[4], tree_depth=g[5],
+                                 conquer_depth=4)
     graph_equal(ef, graph, oracle.conquer_graph(X, *o, 4, 10))
     X = rng.standard_normal((2_000, 8)).astype(np.float32)
     g, _ = tree_nodes_equal(ef, X, 1, 64, 3)
     with pytest.raises(ef.EfannaError) as e:                     # only leaves of at most 16 points
-        ef.efanna_init_graph(dev(X), g[0], g[1], g[2], 64, 10, nodes=g[3], leaf_up=g[4], conquer_depth=0)
+        ef.efanna_init_graph(dev(X), g[0], g[1], g[2], 64, 10, nodes=g[3], leaf_up=g[4], tree_depth=g[5], conquer_depth=0)
     assert e.value.status == -6
 
 
