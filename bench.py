@@ -54,6 +54,10 @@ def main():
                     help="rows of the workload the CPU oracle is timed on (0 = skip)")
     ap.add_argument("--recall-rows", type=int, default=10_000, help="0 = skip recall")
     ap.add_argument("--progress", action="store_true", help="report each phase on stderr as it ends")
+    ap.add_argument("--conquer-depth", type=int, default=None,
+                    help="walk the conquer step of Alg. 3 up to this depth (default: stop at the leaves, "
+                         "the configuration the metric is quoted on); distance evaluations above the "
+                         "leaves are not counted in `value`")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU; --gpus N with N > 1 is not supported "
@@ -77,8 +81,11 @@ def main():
     dev = torch.device("cuda:0")
     Xd = torch.from_numpy(X).to(dev)
     L_ = efanna.lib()
-    ws_tree = torch.empty(L_.efanna_trees_workspace_bytes(n, d, T, S, 0), dtype=torch.uint8, device=dev)
-    ws_init = torch.empty(max(256, L_.efanna_init_workspace_bytes(n, 0)), dtype=torch.uint8, device=dev)
+    conquer = args.conquer_depth is not None
+    ws_tree = torch.empty(L_.efanna_trees_workspace_bytes(n, d, T, S, 1 if conquer else 0),
+                          dtype=torch.uint8, device=dev)
+    ws_init = torch.empty(max(256, L_.efanna_init_workspace_bytes(n, 64 if conquer else 0)),
+                          dtype=torch.uint8, device=dev)
     ws_nnd = torch.empty(L_.efanna_nndescent_workspace_bytes(n, K, L), dtype=torch.uint8, device=dev)
     graph = torch.empty((n, K), dtype=torch.int64, device=dev)
     stats = torch.zeros((I, 4), dtype=torch.int64, device=dev)
@@ -93,10 +100,16 @@ def main():
     def step(timed: bool):
         nonlocal k_ms_sum, k_bytes_sum, k_launches, all_ms_sum, all_bytes_sum
         t0 = time.perf_counter()
-        perm, leaf_off, n_leaves = efanna.efanna_build_trees(Xd, T, S, synth.ALGO_SEED,
-                                                             max_leaves=max_leaves, workspace=ws_tree)
+        trees = efanna.efanna_build_trees(Xd, T, S, synth.ALGO_SEED, max_leaves=max_leaves,
+                                          workspace=ws_tree, with_nodes=conquer)
+        perm, leaf_off, n_leaves = trees[:3]
         t1 = time.perf_counter()          # build_trees returns synchronised
-        efanna.efanna_init_graph(Xd, perm, leaf_off, n_leaves, S, K, graph=graph, workspace=ws_init)
+        if conquer:
+            efanna.efanna_init_graph(Xd, perm, leaf_off, n_leaves, S, K, graph=graph, workspace=ws_init,
+                                     nodes=trees[3], leaf_up=trees[4], tree_depth=trees[5],
+                                     conquer_depth=args.conquer_depth)
+        else:
+            efanna.efanna_init_graph(Xd, perm, leaf_off, n_leaves, S, K, graph=graph, workspace=ws_init)
         torch.cuda.synchronize()
         t2 = time.perf_counter()
         efanna.efanna_nndescent(Xd, graph, I, L, synth.ALGO_SEED, stats=stats, workspace=ws_nnd,
@@ -174,7 +187,8 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32", "data": "synthetic",
         "config": {"workload": name, "n": n, "d": d, "K": K, "trees": T, "leaf_size": S,
-                   "iterations": I, "sample_L": L},
+                   "iterations": I, "sample_L": L,
+                   "conquer_depth": args.conquer_depth if conquer else "leaves"},
         "build_seconds": seconds,
         "dist_evals_per_step": evals,
         "recall_at_K": recall, "recall_rows": args.recall_rows if recall is not None else 0,
