@@ -24,7 +24,7 @@ HBM_PEAK_GBS = 8000.0
 # HBM bytes per launch of the dominant kernel, from two rocprofv3 --pmc runs (FETCH_SIZE, WRITE_SIZE)
 # scaled by what the same counters read for a plain 256 MiB copy (factors 2.0 and 1.0); summary and
 # commands in profiles/join_kernels_sift1m_like_hbm_traffic.txt.  Only measured for the headline workload.
-MEASURED_TRAFFIC_BYTES = {"sift1m_like": {"calibrated": 5.67e9, "raw_counters": 2.94e9}}
+MEASURED_TRAFFIC_BYTES = {"sift1m_like": {"calibrated": 4.93e9, "raw_counters": 2.57e9}}
 
 
 def exact_knn_torch(Xd, rows, K):
@@ -54,6 +54,9 @@ def main():
                     help="rows of the workload the CPU oracle is timed on (0 = skip)")
     ap.add_argument("--recall-rows", type=int, default=10_000, help="0 = skip recall")
     ap.add_argument("--progress", action="store_true", help="report each phase on stderr as it ends")
+    ap.add_argument("--calibrate", action="store_true",
+                    help="after the timed steps, fill and copy 256 MiB with plain torch kernels: a known "
+                         "amount of HBM traffic to scale rocprofv3's FETCH_SIZE / WRITE_SIZE counters by")
     ap.add_argument("--conquer-depth", type=int, default=None,
                     help="walk the conquer step of Alg. 3 up to this depth (default: stop at the leaves, "
                          "the configuration the metric is quoted on); distance evaluations above the "
@@ -139,6 +142,15 @@ def main():
         step(True)
     torch.cuda.synchronize()
     seconds = (time.perf_counter() - t_begin) / max(1, args.steps)
+
+    if args.calibrate:
+        a = torch.empty(64 * 1024 * 1024, dtype=torch.float32, device=dev)
+        b = torch.empty_like(a)
+        a.fill_(1.0)
+        torch.cuda.synchronize()
+        b.copy_(a)
+        torch.cuda.synchronize()
+        del a, b
 
     # work done per step (identical in every step: the path is deterministic)
     st = stats.cpu().numpy()
