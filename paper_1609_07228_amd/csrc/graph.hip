@@ -1108,6 +1108,8 @@ __global__ void join_kernel(const float *__restrict__ X, const float *__restrict
 
 // where the survivors of Gram blocks (0,0), (0,1), (1,1) start in the LDS survivor buffer
 __device__ constexpr int kSurvBase[3] = {0, 120, 376};
+// d > 128: up to this many surviving pairs of a Gram block (per 16 rows) are read pair by pair
+constexpr int kFewPairs = 4;
 
 template <int NB, bool ONE>
 __global__ void __launch_bounds__(EF_WAVE) __attribute__((amdgpu_waves_per_eu(NB > 1 ? 3 : 4)))
@@ -1225,9 +1227,8 @@ join_reg_kernel(const float *__restrict__ X, const float *__restrict__ norms, in
             for (int k = 0; k < 4; ++k) {
                 const float lhs = __builtin_fmaf(-2.0f, acc[q][0][k] + acc[q][1][k], nfa_k[k] + nfb);
                 if (a0 + k < lim && lhs <= fmaxf(tfa_k[k], tfb)) {
-                    // ONE: one list per Gram block, entries are rows local to the block
-                    if (ONE) surv[kSurvBase[q] + atomicAdd(&meta[4 + q], 1)] = (u32)((a0 + k) & 15) | ((u32)(b & 15) << 8);
-                    else surv[atomicAdd(&meta[4], 1)] = (u32)(a0 + k) | ((u32)b << 16);
+                    // one list per Gram block, entries are rows local to the block
+                    surv[kSurvBase[q] + atomicAdd(&meta[4 + q], 1)] = (u32)((a0 + k) & 15) | ((u32)(b & 15) << 8);
                 }
             }
         }
@@ -1296,56 +1297,130 @@ join_reg_kernel(const float *__restrict__ X, const float *__restrict__ norms, in
                 }
             }
         }
-        // ---- 3b. survivors re-read from memory, one 16-lane group per pair ----------------------
-        const int n_surv = ONE ? 0 : meta[4];
-        if (!ONE && n_surv > 0 && meta[3] > 0) {      // the chunks below want an empty queue
-            updates += drain_queue(queue, meta[3], graph, worst, K, lane, EF_WAVE);
-            __syncthreads();
-            if (lane == 0) meta[3] = 0;
-            __syncthreads();
-        }
-        for (int c0 = 0; c0 < n_surv; c0 += q_cap / 2) {
-            const int c1 = min(n_surv, c0 + q_cap / 2);
-            for (int p0 = c0; p0 < c1; p0 += 4) {
-                const int p = min(p0 + grp, c1 - 1);
-                const u32 ab = surv[p];
-                const int a = ab & 0xFFFF, b = ab >> 16;
-                const float *ra = X + (size_t)uid[a] * d + gl, *rb = X + (size_t)uid[b] * d + gl;
-                float accd = 0.0f;
-                for (int j0 = 0; j0 < d; j0 += 128) {
-                    float xa[8], xb[8];
+        // ---- 3b. d > 128: the rows are streamed once more, 128 coordinates at a time, and up to
+        // eight rounds of sixteen surviving pairs collect their partial sums side by side -----------
+        if (!ONE) {
 #pragma unroll
-                    for (int s = 0; s < 8; ++s) {
-                        const bool in = j0 + 16 * s + gl < d;
-                        xa[s] = in ? ra[j0 + 16 * s] : 0.0f;
-                        xb[s] = in ? rb[j0 + 16 * s] : 0.0f;
+            for (int q = 0; q < (NB > 1 ? 3 : 1); ++q) {
+                const int bi = q == 2 ? 1 : 0, bj = q == 0 ? 0 : 1;
+                const int n_q = meta[4 + q];
+                // a few pairs: cheaper to read just their rows, one 16-lane group per pair
+                const int n_few = n_q <= kFewPairs * NB ? n_q : 0;
+                for (int p0 = 0; p0 < n_few; p0 += 4) {
+                    const u32 ent = surv[kSurvBase[q] + min(p0 + grp, n_few - 1)];
+                    const int a = 16 * bi + (int)(ent & 15), b = 16 * bj + (int)((ent >> 8) & 15);
+                    const float *ra = X + (size_t)uid[a] * d + gl, *rb = X + (size_t)uid[b] * d + gl;
+                    float accd = 0.0f;
+                    for (int j0 = 0; j0 < d; j0 += 128) {
+                        float xa[8], xb[8];
+#pragma unroll
+                        for (int s = 0; s < 8; ++s) {
+                            const bool in = j0 + 16 * s + gl < d;
+                            xa[s] = in ? ra[j0 + 16 * s] : 0.0f;
+                            xb[s] = in ? rb[j0 + 16 * s] : 0.0f;
+                        }
+#pragma unroll
+                        for (int s = 0; s < 8; ++s) {
+                            const float diff = xa[s] - xb[s];     // 0 beyond d: leaves the sum unchanged
+                            accd = __builtin_fmaf(diff, diff, accd);
+                        }
                     }
-#pragma unroll
-                    for (int s = 0; s < 8; ++s) {
-                        const float diff = xa[s] - xb[s];     // 0 beyond d: leaves the sum unchanged
-                        accd = __builtin_fmaf(diff, diff, accd);
+                    const float dist = ef_group_reduce16(accd);
+                    if (gl == 0 && p0 + grp < n_few) {
+                        const u32 db = __float_as_uint(dist);
+                        if (db <= thr[a]) {
+                            const int slot = atomicAdd(&meta[3], 1);
+                            queue[slot].key = ef_pack(dist, uid[b], 1);
+                            queue[slot].target = uid[a];
+                        }
+                        if (db <= thr[b]) {
+                            const int slot = atomicAdd(&meta[3], 1);
+                            queue[slot].key = ef_pack(dist, uid[a], 1);
+                            queue[slot].target = uid[b];
+                        }
+                    }
+                    __syncthreads();
+                    if (meta[3] + 32 > q_cap) {
+                        updates += drain_queue(queue, meta[3], graph, worst, K, lane, EF_WAVE);
+                        __syncthreads();
+                        if (lane == 0) meta[3] = 0;
+                        __syncthreads();
                     }
                 }
-                const float dist = ef_group_reduce16(accd);
-                if (gl == 0 && p0 + grp < c1) {
-                    const u32 db = __float_as_uint(dist);
-                    if (db <= thr[a]) {
-                        const int slot = atomicAdd(&meta[3], 1);
-                        queue[slot].key = ef_pack(dist, uid[b], 1);
-                        queue[slot].target = uid[a];
+                for (int g0 = n_few; g0 < n_q; g0 += 128) {
+                    const int n_rounds = min(8, (n_q - g0 + 15) >> 4);
+                    float ps[8][4];
+#pragma unroll
+                    for (int r = 0; r < 8; ++r) ps[r][0] = ps[r][1] = ps[r][2] = ps[r][3] = 0.f;
+                    for (int c0 = 0; c0 < d; c0 += 128) {
+#pragma unroll
+                        for (int s = 0; s < 8; ++s) {
+                            const bool in = c0 + 16 * s + 4 * g + 3 < d;      // d % 4 == 0: a piece is in or out
+                            if (bi == 0 || bj == 0)
+                                va[s] = in ? *reinterpret_cast<const float4 *>(pa + c0 + 16 * s) : make_float4(0.f, 0.f, 0.f, 0.f);
+                            if (NB > 1 && (bi == 1 || bj == 1))
+                                vb[NB > 1 ? s : 0] = in ? *reinterpret_cast<const float4 *>(pb + c0 + 16 * s) : make_float4(0.f, 0.f, 0.f, 0.f);
+                        }
+#pragma unroll
+                        for (int r = 0; r < 8; ++r) {
+                            if (r >= n_rounds) break;
+                            const u32 ent = surv[kSurvBase[q] + min(g0 + 16 * r + r16, n_q - 1)];
+                            const int src_a = (int)(ent & 15) + 16 * g, src_b = (int)((ent >> 8) & 15) + 16 * g;
+#pragma unroll
+                            for (int s = 0; s < 8; ++s) {
+                                if (c0 + 16 * s >= d) break;
+                                const float4 own = bi == 0 ? va[s] : vb[NB > 1 ? s : 0];
+                                const float4 oth = bj == 0 ? va[s] : vb[NB > 1 ? s : 0];
+                                const float d0 = __shfl(own.x, src_a, EF_WAVE) - __shfl(oth.x, src_b, EF_WAVE);
+                                const float d1 = __shfl(own.y, src_a, EF_WAVE) - __shfl(oth.y, src_b, EF_WAVE);
+                                const float d2 = __shfl(own.z, src_a, EF_WAVE) - __shfl(oth.z, src_b, EF_WAVE);
+                                const float d3 = __shfl(own.w, src_a, EF_WAVE) - __shfl(oth.w, src_b, EF_WAVE);
+                                ps[r][0] = __builtin_fmaf(d0, d0, ps[r][0]);
+                                ps[r][1] = __builtin_fmaf(d1, d1, ps[r][1]);
+                                ps[r][2] = __builtin_fmaf(d2, d2, ps[r][2]);
+                                ps[r][3] = __builtin_fmaf(d3, d3, ps[r][3]);
+                            }
+                        }
                     }
-                    if (db <= thr[b]) {
-                        const int slot = atomicAdd(&meta[3], 1);
-                        queue[slot].key = ef_pack(dist, uid[a], 1);
-                        queue[slot].target = uid[b];
+#pragma unroll
+                    for (int r = 0; r < 8; ++r) {
+                        if (r >= n_rounds) break;
+                        float p0s = ps[r][0], p1s = ps[r][1], p2s = ps[r][2], p3s = ps[r][3];
+                        p0s += __shfl_xor(p0s, 32, EF_WAVE);
+                        p1s += __shfl_xor(p1s, 32, EF_WAVE);
+                        p2s += __shfl_xor(p2s, 32, EF_WAVE);
+                        p3s += __shfl_xor(p3s, 32, EF_WAVE);
+                        p0s += __shfl_xor(p0s, 16, EF_WAVE);
+                        p1s += __shfl_xor(p1s, 16, EF_WAVE);
+                        p2s += __shfl_xor(p2s, 16, EF_WAVE);
+                        p3s += __shfl_xor(p3s, 16, EF_WAVE);
+                        const float dist = (p0s + p2s) + (p1s + p3s);
+                        const int pidx = g0 + 16 * r + r16;
+                        if (pidx < n_q && g == 0) {
+                            const u32 ent = surv[kSurvBase[q] + pidx];
+                            const int a = 16 * bi + (int)(ent & 15), b = 16 * bj + (int)((ent >> 8) & 15);
+                            const u32 db = __float_as_uint(dist);
+                            if (db <= thr[a]) {
+                                const int slot = atomicAdd(&meta[3], 1);
+                                queue[slot].key = ef_pack(dist, uid[b], 1);
+                                queue[slot].target = uid[a];
+                            }
+                            if (db <= thr[b]) {
+                                const int slot = atomicAdd(&meta[3], 1);
+                                queue[slot].key = ef_pack(dist, uid[a], 1);
+                                queue[slot].target = uid[b];
+                            }
+                        }
+                        __syncthreads();
+                        if (meta[3] + 32 > q_cap) {      // a round adds at most two proposals per pair
+                            updates += drain_queue(queue, meta[3], graph, worst, K, lane, EF_WAVE);
+                            __syncthreads();
+                            if (lane == 0) meta[3] = 0;
+                            __syncthreads();
+                        }
                     }
                 }
             }
-            __syncthreads();
-            updates += drain_queue(queue, meta[3], graph, worst, K, lane, EF_WAVE);
-            __syncthreads();
-            if (lane == 0) meta[3] = 0;
-            __syncthreads();
         }
         if (meta[3] >= q_cap / 2) {
             updates += drain_queue(queue, meta[3], graph, worst, K, lane, EF_WAVE);
