@@ -149,8 +149,13 @@ int efanna_init_graph(const float *X, int64_t n, int32_t d, const int32_t *perm,
  * its old and reverse-old sets: each unordered pair is evaluated once and proposed to
  * both end points; (4) a row keeps the k smallest (distance, id) among its entries and
  * the proposals, an id already present keeping its entry and mark, fresh entries marked
- * new.  There is no early termination.
+ * new.
  *
+ * delta    0: run all `iters` iterations.  > 0: early termination - stop after an iteration
+ *          that leaves fewer than delta*n*k entries carrying the new mark (fresh entries that
+ *          were still in their row when the iteration ended); the call then synchronises the
+ *          stream after every iteration.
+ * iters_done [host] out or NULL: iterations carried out.
  * graph    [device] in/out.  The call may be repeated to continue refining: pass the
  *          number of iterations already done as first_iter so that the hash stream
  *          continues (k calls of one iteration equal one call of k iterations).
@@ -170,6 +175,7 @@ size_t efanna_nndescent_workspace_bytes(int64_t n, int32_t k, int32_t sample_L);
 
 int efanna_nndescent(const float *X, int64_t n, int32_t d, int32_t k, efanna_entry *graph,
                      int32_t iters, int32_t sample_L, uint64_t seed, int32_t first_iter,
+                     float delta, int32_t *iters_done,
                      uint64_t *stats, float *phase_ms, void *ws, size_t ws_bytes, void *stream);
 
 /* ---- result ("Ensure: approximate kNN graph G") -------------------------------------

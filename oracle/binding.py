@@ -54,6 +54,10 @@ def _load():
         lib.oracle_nndescent.argtypes = [C.c_void_p, C.c_int64, C.c_int32, C.c_int32, C.c_void_p,
                                          C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_uint64,
                                          C.c_int32, C.c_void_p]
+        lib.oracle_nndescent_until.restype = C.c_int
+        lib.oracle_nndescent_until.argtypes = [C.c_void_p, C.c_int64, C.c_int32, C.c_int32, C.c_void_p,
+                                               C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_uint64,
+                                               C.c_int32, C.c_void_p, C.c_double, C.c_void_p]
         lib.oracle_num_threads.restype = C.c_int
         lib.oracle_set_num_threads.argtypes = [C.c_int]
         _lib = lib
@@ -175,9 +179,12 @@ def init_graph(X, perm, leaf_off, n_leaves, K: int, rows=None):
     return ids, dists, flags
 
 
-def nndescent(X, ids, dists, flags, iters: int, L: int, seed: int, iter0: int = 0):
+def nndescent(X, ids, dists, flags, iters: int, L: int, seed: int, iter0: int = 0,
+              delta: float = 0.0):
     """Alg. 4.  Returns new (ids, dists, flags) and stats [iters, 2] =
-    (distance evaluations, accepted insertions) per iteration."""
+    (distance evaluations, accepted insertions) per iteration.  With delta > 0 (early
+    termination) a fifth value follows: the number of iterations carried out, and stats
+    has that many rows."""
     X = _f32(X)
     n, d = X.shape
     K = ids.shape[1]
@@ -185,8 +192,11 @@ def nndescent(X, ids, dists, flags, iters: int, L: int, seed: int, iter0: int = 
     dists = np.array(dists, dtype=np.float32, order="C")
     flags = np.array(flags, dtype=np.uint8, order="C")
     stats = np.zeros((max(iters, 1), 2), dtype=np.uint64)
-    rc = _load().oracle_nndescent(_p(X), n, d, K, _p(ids), _p(dists), _p(flags), iters, L, seed,
-                                  iter0, _p(stats))
+    done = C.c_int32(0)
+    rc = _load().oracle_nndescent_until(_p(X), n, d, K, _p(ids), _p(dists), _p(flags), iters, L, seed,
+                                        iter0, _p(stats), float(delta), C.byref(done))
     if rc != 0:
         raise ValueError(f"oracle_nndescent failed: {rc}")
+    if delta > 0.0:
+        return ids, dists, flags, stats[:done.value], int(done.value)
     return ids, dists, flags, stats[:iters]

@@ -448,11 +448,17 @@ static int32_t sorted_union(const int32_t *a, int32_t na, const int32_t *b, int3
  * done).  stats: [iters][2] = {distance evaluations, accepted insertions}; the
  * second figure counts insertions that may be evicted again within the same
  * iteration, so unlike the pools it depends on the order of evaluation. */
-int oracle_nndescent(const float *X, int64_t n, int32_t d, int32_t K, int32_t *ids, float *dists,
-                     uint8_t *flags, int32_t iters, int32_t L, uint64_t seed, int32_t iter0,
-                     uint64_t *stats)
+/* delta > 0: early termination (Section 1 names it among the techniques taken over from
+ * NN-descent; Alg. 4 itself only has the iteration limit): stop after an iteration that
+ * leaves fewer than delta*n*K entries carrying the new mark, i.e. fresh entries that were
+ * still in their pool when the iteration ended.  iters_done (may be NULL) receives the
+ * number of iterations carried out. */
+int oracle_nndescent_until(const float *X, int64_t n, int32_t d, int32_t K, int32_t *ids,
+                           float *dists, uint8_t *flags, int32_t iters, int32_t L, uint64_t seed,
+                           int32_t iter0, uint64_t *stats, double delta, int32_t *iters_done)
 {
     if (!X || !ids || !dists || !flags || n < 2 || K < 1 || L < 1 || iters < 0) return -1;
+    if (iters_done) *iters_done = 0;
     entry *pool = (entry *)malloc((size_t)n * K * sizeof(entry));
     int32_t *cnt = (int32_t *)malloc((size_t)n * sizeof(int32_t));
     int32_t *nw = (int32_t *)malloc((size_t)n * L * sizeof(int32_t));
@@ -533,6 +539,13 @@ int oracle_nndescent(const float *X, int64_t n, int32_t d, int32_t K, int32_t *i
             stats[2 * it] = evals;
             stats[2 * it + 1] = updates;
         }
+        if (iters_done) *iters_done = it + 1;
+        if (delta > 0.0) {
+            int64_t fresh = 0;
+            for (int64_t i = 0; i < n; ++i)
+                for (int32_t c = 0; c < cnt[i]; ++c) fresh += pool[i * K + c].is_new;
+            if ((double)fresh < delta * (double)n * (double)K) break;
+        }
     }
     pools_store(pool, cnt, n, K, ids, dists, flags);
 #ifdef _OPENMP
@@ -543,6 +556,14 @@ int oracle_nndescent(const float *X, int64_t n, int32_t d, int32_t K, int32_t *i
     free(rod); free(rnw); free(od); free(nw);
     free(cnt); free(pool);
     return 0;
+}
+
+int oracle_nndescent(const float *X, int64_t n, int32_t d, int32_t K, int32_t *ids, float *dists,
+                     uint8_t *flags, int32_t iters, int32_t L, uint64_t seed, int32_t iter0,
+                     uint64_t *stats)
+{
+    return oracle_nndescent_until(X, n, d, K, ids, dists, flags, iters, L, seed, iter0, stats, 0.0,
+                                  NULL);
 }
 
 void oracle_set_num_threads(int t)

@@ -1474,6 +1474,25 @@ __global__ void stats_kernel(const long long *__restrict__ part, int n_part,
     }
 }
 
+// number of graph entries carrying the new mark (early termination)
+__global__ void __launch_bounds__(kBlock) count_new_kernel(const u64 *__restrict__ graph, size_t total, u64 *out)
+{
+    __shared__ int wave_cnt[kBlock / EF_WAVE];
+    int mine = 0;
+    for (size_t i = (size_t)blockIdx.x * kBlock + threadIdx.x; i < total; i += (size_t)gridDim.x * kBlock) {
+        const u64 e = graph[i];
+        mine += (e & 1) && !ef_is_empty(e) ? 1 : 0;
+    }
+    mine = ef_wave_sum_i32(mine);
+    if (ef_lane() == 0) wave_cnt[threadIdx.x / EF_WAVE] = mine;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        int tot = 0;
+        for (int w = 0; w < kBlock / EF_WAVE; ++w) tot += wave_cnt[w];
+        if (tot) atomicAdd(out, (u64)tot);
+    }
+}
+
 __global__ void zero_u64_kernel(u64 *p, int count)
 {
     int i = blockIdx.x * blockDim.x + threadIdx.x;
@@ -1549,7 +1568,7 @@ struct NndWs {
     int *nw, *od, *nw_c, *od_c, *work, *work_count, *rnew_c, *rold_c, *overflow_rows, *ulist, *upd_block;
     int2 *ucount;
     void *overflow;
-    u64 *rnew, *rold, *list_max, *active;
+    u64 *rnew, *rold, *list_max, *active, *fresh;
     long long *part;
     u32 *worst;
     float *norms;
@@ -1584,6 +1603,7 @@ NndWs carve_nnd(void *ws, int64_t n, int K, int L)
     w.rold = (u64 *)take((size_t)n * L * 8);
     w.list_max = (u64 *)take((size_t)n * 2 * 8);
     w.active = (u64 *)take((size_t)(n + 63) / 64 * 8);
+    w.fresh = (u64 *)take(8);
     w.worst = (u32 *)take((size_t)n * 4);
     w.norms = (float *)take((size_t)n * 4);
     w.bytes = off;
@@ -1690,10 +1710,12 @@ extern "C" size_t efanna_nndescent_workspace_bytes(int64_t n, int32_t k, int32_t
 
 extern "C" int efanna_nndescent(const float *X, int64_t n, int32_t d, int32_t k,
                                 efanna_entry *graph_, int32_t iters, int32_t sample_L,
-                                uint64_t seed, int32_t first_iter, uint64_t *stats_,
-                                float *phase_ms, void *ws, size_t ws_bytes, void *stream)
+                                uint64_t seed, int32_t first_iter, float delta,
+                                int32_t *iters_done, uint64_t *stats_, float *phase_ms, void *ws,
+                                size_t ws_bytes, void *stream)
 {
-    if (!X || !graph_) return EFANNA_EINVAL;
+    if (iters_done) *iters_done = 0;
+    if (!X || !graph_ || !(delta >= 0.0f)) return EFANNA_EINVAL;
     u64 *const graph = (u64 *)graph_;
     u64 *const stats = (u64 *)stats_;
     if (n < 2 || d < 1 || k < 1 || k > EFANNA_MAX_K || k >= n || iters < 0 || sample_L < 1 ||
@@ -1774,6 +1796,7 @@ extern "C" int efanna_nndescent(const float *X, int64_t n, int32_t d, int32_t k,
         ev = new hipEvent_t[(size_t)iters * 5];
         for (int e = 0; e < iters * 5; ++e) EF_HIP_CHECK(hipEventCreate(&ev[e]));
     }
+    int done = 0;
     for (int it = 0; it < iters; ++it) {
         const int g = first_iter + it;
         if (ev) EF_HIP_CHECK(hipEventRecord(ev[5 * it], st));
@@ -1834,13 +1857,27 @@ extern "C" int efanna_nndescent(const float *X, int64_t n, int32_t d, int32_t k,
         if (stats)
             stats_kernel<<<16, kBlock, 0, st>>>(w.part, grid_for((size_t)n, prep_threads), w.upd_block,
                                                 2 * reg_grid + kMaxLargeGrid, stats + 4 * it);
+        done = it + 1;
+        if (delta > 0.0f) {      // early termination: the host looks at the count after every iteration
+            u64 fresh = 0;
+            zero_u64_kernel<<<1, kBlock, 0, st>>>(w.fresh, 1);
+            count_new_kernel<<<1024, kBlock, 0, st>>>(graph, (size_t)n * K, w.fresh);
+            EF_HIP_CHECK(hipMemcpyAsync(&fresh, w.fresh, 8, hipMemcpyDeviceToHost, st));
+            EF_HIP_CHECK(hipStreamSynchronize(st));
+            if ((double)fresh < (double)delta * (double)n * (double)K) break;
+        }
     }
+    if (iters_done) *iters_done = done;
     EF_HIP_CHECK(hipGetLastError());
     if (ev) {
         EF_HIP_CHECK(hipStreamSynchronize(st));
         for (int it = 0; it < iters; ++it) {
-            for (int ph = 0; ph < 4; ++ph)
-                EF_HIP_CHECK(hipEventElapsedTime(&phase_ms[4 * it + ph], ev[5 * it + ph], ev[5 * it + ph + 1]));
+            for (int ph = 0; ph < 4; ++ph) {
+                if (it < done)
+                    EF_HIP_CHECK(hipEventElapsedTime(&phase_ms[4 * it + ph], ev[5 * it + ph], ev[5 * it + ph + 1]));
+                else
+                    phase_ms[4 * it + ph] = 0.0f;
+            }
         }
         for (int e = 0; e < iters * 5; ++e) (void)hipEventDestroy(ev[e]);
         delete[] ev;

@@ -267,6 +267,25 @@ def test_nndescent_resume_and_recall(ef):
     assert abs(r_gpu - r_cpu) <= 0.005 and r_gpu > 0.8
 
 
+def test_early_termination_and_larger_pools(ef):
+    """delta > 0 stops where the oracle stops; a pool larger than the graph degree (P > K) is a
+    run with k = P whose rows are cut to K at the end."""
+    X = synth.generate("gmm10k_d32", n=6000)
+    Xd = dev(X)
+    K, P, L = 10, 15, 10
+    (perm, off, nl), (operm, ooff, onl) = trees_equal(ef, X, 3, 8, synth.ALGO_SEED)
+    for delta in (0.05, 0.004):
+        graph = ef.efanna_init_graph(Xd, perm, off, nl, 8, P)
+        stats, done = ef.efanna_nndescent(Xd, graph, 12, L, synth.ALGO_SEED, delta=delta)
+        want = oracle.nndescent(X, *oracle.init_graph(X, operm, ooff, onl, P), 12, L, synth.ALGO_SEED,
+                                delta=delta)
+        assert done == want[4] and 1 <= done < 12 and stats.shape[0] == done
+        ids, dists = graph_equal(ef, graph, want)
+        assert np.array_equal(host(stats)[:, 0].astype(np.uint64), want[3][:, 0])
+    tid, _ = oracle.exact_knn(X, np.arange(X.shape[0]), K)
+    assert oracle.recall(ids[:, :K], tid) > 0.85          # the K closest of the P kept
+
+
 def test_set_get_roundtrip_and_random_start(ef):
     rng = np.random.default_rng(8)
     n, K = 3000, 10

@@ -275,3 +275,28 @@ def test_sampling_takes_the_L_closest_new_entries_only():
     assert int(st[0, 0]) == 1                       # the only joined pair is (1,2)
     assert ids2[1, 0] == 2 and ids2[2, 0] == 1 and dists2[1, 0] == 1.0 and flags2[1, 0] == 1
     assert np.all(ids2[3:] == -1)
+
+
+def test_early_termination_stops_where_the_fresh_entries_run_out():
+    """delta > 0: the run ends after the first iteration that leaves fewer than delta*n*K
+    entries carrying the new mark.  The expected stopping point is read off a run made
+    one iteration at a time, with the marks counted here."""
+    X = synth.generate("gmm10k_d32", n=2500)
+    K, L = 10, 10
+    perm, off, nl = oracle.build_trees(X, 3, 8, 42)
+    g0 = oracle.init_graph(X, perm, off, nl, K)
+    state, fresh = g0, []
+    for it in range(8):
+        state = oracle.nndescent(X, *state[:3], 1, L, 42, iter0=it)
+        fresh.append(int(state[2].sum()))
+    assert fresh[0] > fresh[-1]
+    for delta in (0.2, 0.02, 0.002):
+        limit = delta * X.shape[0] * K
+        want = next((i + 1 for i, f in enumerate(fresh) if f < limit), 8)
+        ids, dists, flags, stats, done = oracle.nndescent(X, *g0[:3], 8, L, 42, delta=delta)
+        assert done == want and stats.shape[0] == want
+        ref = oracle.nndescent(X, *g0[:3], want, L, 42)
+        assert np.array_equal(ids, ref[0]) and np.array_equal(flags, ref[2])
+    # a threshold nothing can meet stops after one iteration, zero never stops early
+    assert oracle.nndescent(X, *g0[:3], 5, L, 42, delta=2.0)[4] == 1
+    assert oracle.nndescent(X, *g0[:3], 3, L, 42)[3].shape[0] == 3
