@@ -80,3 +80,92 @@ def test_headline_workload_bit_exact_against_oracle():
     assert abs(r_gpu - r_cpu) <= 0.005
     assert r_gpu > 0.6
     assert (phase_ms[:, 1] > 0).all()
+
+
+def _progress(msg):
+    """Long tests leave a trace outside pytest's capture, so that a watcher can tell them
+    from a hang."""
+    import os
+    import time
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    os.makedirs(os.path.join(root, "gpurun_out"), exist_ok=True)
+    with open(os.path.join(root, "gpurun_out", "test_progress.log"), "a") as f:
+        f.write(f"{time.strftime('%H:%M:%S')} {msg}\n")
+
+
+@pytest.mark.timeout(600)
+def test_sift100k_like_full_size_bit_exact():
+    """The 100 000 x 128 configuration (K = 20, L = 20: joins of up to 60 vectors take the
+    kernel with rows in LDS) at full size, every element against the oracle."""
+    from paper_1609_07228_amd import efanna
+    name = "sift100k_like"
+    p = synth.params(name)
+    X = synth.generate(name)
+    Xd = torch.from_numpy(X).to("cuda:0")
+    perm, off, nl = efanna.efanna_build_trees(Xd, p["T"], p["S"], synth.ALGO_SEED)
+    graph = efanna.efanna_init_graph(Xd, perm, off, nl, p["S"], p["K"])
+    stats = efanna.efanna_nndescent(Xd, graph, p["I"], p["L"], synth.ALGO_SEED)
+    ids, dists, flags = [t.cpu().numpy() for t in efanna.efanna_get_graph(graph, with_flags=True)]
+    operm, ooff, onl = oracle.build_trees(X, p["T"], p["S"], synth.ALGO_SEED)
+    assert np.array_equal(perm.cpu().numpy(), operm)
+    want = oracle.nndescent(X, *oracle.init_graph(X, operm, ooff, onl, p["K"]), p["I"], p["L"],
+                            synth.ALGO_SEED)
+    assert np.array_equal(ids, want[0]) and dists.tobytes() == want[1].tobytes()
+    assert np.array_equal(flags, want[2])
+    assert np.array_equal(stats.cpu().numpy()[:, 0].astype(np.uint64), want[3][:, 0])
+
+
+def _full_size_properties(name, n_rows_init, n_rows_exact):
+    """Whole path at a size the oracle cannot refine in reasonable time: trees and sampled
+    rows of the initial graph bit-exact against the oracle, the refined graph checked
+    through properties that hold at any size."""
+    from paper_1609_07228_amd import efanna
+    p = synth.params(name)
+    K, T, S, I, L = p["K"], p["T"], p["S"], p["I"], p["L"]
+    X = synth.generate(name)
+    n, d = X.shape
+    _progress(f"{name}: generated {n} x {d}")
+    Xd = torch.from_numpy(X).to("cuda:0")
+    max_leaves = n // max(1, S // 4) + 16
+    perm, off, nl = efanna.efanna_build_trees(Xd, T, S, synth.ALGO_SEED, max_leaves=max_leaves)
+    graph = efanna.efanna_init_graph(Xd, perm, off, nl, S, K)
+    init_ids, init_dists = [t.cpu().numpy() for t in efanna.efanna_get_graph(graph)]
+    stats = efanna.efanna_nndescent(Xd, graph, I, L, synth.ALGO_SEED).cpu().numpy()
+    ids, dists = [t.cpu().numpy() for t in efanna.efanna_get_graph(graph)]
+    _progress(f"{name}: gpu path done")
+    # trees: every permutation and leaf boundary
+    operm, ooff, onl = oracle.build_trees(X, T, S, synth.ALGO_SEED)
+    assert np.array_equal(nl, onl) and np.array_equal(perm.cpu().numpy(), operm)
+    goff = off.cpu().numpy()
+    for t in range(T):
+        assert np.array_equal(goff[t, :onl[t] + 1], ooff[t, :onl[t] + 1])
+    _progress(f"{name}: trees equal")
+    # initial graph: sampled rows, one by one
+    rows = synth.sample_rows(n, n_rows_init)
+    want = oracle.init_graph(X, operm, ooff, onl, K, rows=rows)
+    assert np.array_equal(init_ids[rows], want[0])
+    assert init_dists[rows].tobytes() == want[1].tobytes()
+    _progress(f"{name}: initial graph rows equal")
+    # refined graph: structure, stored distances, monotone improvement, accuracy
+    oracle.check_graph_invariants(X, ids[rows], dists[rows], rows=rows)
+    for r in rows[:64]:
+        for c in (0, K // 2, K - 1):
+            assert dists[r, c] == oracle.dist(X[r], X[ids[r, c]])
+    assert np.all(dists[rows, K - 1] <= init_dists[rows, K - 1])      # the K-th distance never grows
+    sub = rows[:n_rows_exact]
+    tid, _ = oracle.exact_knn(X, sub, K)
+    r0, r1 = oracle.recall(init_ids[sub], tid), oracle.recall(ids[sub], tid)
+    _progress(f"{name}: accuracy {r0:.3f} -> {r1:.3f}")
+    assert r1 > r0 + 0.2 and r1 > 0.5
+    assert np.all(np.diff(stats[2:, 1].astype(np.int64)) < 0)          # insertions dry up
+    return r1
+
+
+@pytest.mark.timeout(900)
+def test_gist1m_like_full_size_properties():
+    _full_size_properties("gist1m_like", 2000, 200)
+
+
+@pytest.mark.timeout(900)
+def test_mixed4m_d96_full_size_properties():
+    _full_size_properties("mixed4m_d96", 1000, 100)
