@@ -134,35 +134,45 @@ __device__ inline int drain_queue(const Proposal *queue, int count, u64 *graph, 
 }
 
 // ---------------------------------------------------------------------------------------
-// Alg. 3 at the leaves, one tree per launch, one block (one wave) per leaf.  Within one
-// tree every point lies in exactly one leaf, so a block owns the graph rows of its
-// members for the duration of the launch: rows are merged in LDS without atomics and
-// written back sorted.  Launches of successive trees are ordered by the stream.
+// Alg. 3 at the leaves, one tree per launch, one block per leaf (64 threads per 16 leaf
+// slots).  Within one tree every point lies in exactly one leaf, so a block owns the graph
+// rows of its members for the duration of the launch and needs no atomics.  Launches of
+// successive trees are ordered by the stream.
+//
+// Rows and the members' old graph rows (ascending) go to LDS; distances come in 4x4 tiles by
+// 16-lane groups; then every (row a, mate o) pair becomes a candidate key and the rows are
+// merged by rank: a candidate's rank is the number of old entries below it (binary search,
+// which also finds it if an earlier tree put it there already) plus the number of candidates
+// of its row below it, an old entry's rank is its index plus the number of candidates below
+// it; ranks below K are stored straight to the row.  Every slot of a row is written exactly
+// once (K old entries plus the fresh candidates are at least K keys, all distinct).
 
-__global__ void __launch_bounds__(EF_WAVE)
+__global__ void __launch_bounds__(kBlock)
 init_tree_kernel(const float *__restrict__ X, int d, int stride, u32 q4_magic, int S,
                  const int *__restrict__ perm_t, const int *__restrict__ leaf_off_t, int K,
                  u64 *graph, int first_tree)
 {
     extern __shared__ __align__(16) float smem[];
     float *rows = smem;                                   // [S][stride]
-    float *dmat = smem + align4(S * stride);              // [S][S] pairwise distances
-    u64 *pools = (u64 *)(dmat + align4(S * S));           // [S][K] rows being merged, ascending
-    int *uid = (int *)(pools + (size_t)S * K);            // [S]
-    const int lane = threadIdx.x;
+    float *dmat = smem + align4(S * stride);              // [S][S] distances, then (as int) old entries below
+    u64 *pools = (u64 *)(dmat + align4(S * S));           // [S][K] old rows, ascending
+    u64 *cand = pools + (size_t)S * K;                    // [S][S + 1] candidate keys of each row
+    int *uid = (int *)(cand + (size_t)S * (S + 1));       // [S]
+    int *below = (int *)dmat;
+    const int tid = threadIdx.x, nthr = blockDim.x;
     const int b = leaf_off_t[blockIdx.x];
     const int s = min(leaf_off_t[blockIdx.x + 1] - b, S);   // never overrun the buffers
-    if (lane < s) uid[lane] = perm_t[b + lane];
+    if (tid < s) uid[tid] = perm_t[b + tid];
     __syncthreads();
-    gather_rows(X, d, stride, q4_magic, uid, s, rows, lane, EF_WAVE);
-    for (int e = lane; e < s * K; e += EF_WAVE) {
+    gather_rows(X, d, stride, q4_magic, uid, s, rows, tid, nthr);
+    for (int e = tid; e < s * K; e += nthr) {
         const int r = e / K, c = e - r * K;
         pools[e] = first_tree ? ef_empty_entry(K - 1 - c) : graph[(size_t)uid[r] * K + c];
     }
     __syncthreads();
     const int nt = (s + 3) >> 2, n_tiles = nt * (nt + 1) / 2;
-    const int grp = lane >> 4, gl = lane & 15;
-    for (int q = grp; q < n_tiles; q += 4) {
+    const int grp = tid >> 4, gl = tid & 15, n_grp = nthr >> 4;
+    for (int q = grp; q < n_tiles; q += n_grp) {
         int ti = 0, rem = q;
         while (rem >= nt - ti) {
             rem -= nt - ti;
@@ -183,23 +193,43 @@ init_tree_kernel(const float *__restrict__ X, int d, int stride, u32 q4_magic, i
         }
     }
     __syncthreads();
-    if (lane < s) {   // lane a merges the other members into row a (kept ascending)
-        u64 *row = pools + (size_t)lane * K;
-        for (int o = 0; o < s; ++o) {
-            if (o == lane) continue;
-            const u64 key = ef_pack(dmat[lane * S + o], uid[o], 1);
-            if (key >= row[K - 1]) continue;
-            int pos = K - 1;
-            while (pos > 0 && row[pos - 1] > key) --pos;
-            if (pos > 0 && row[pos - 1] == key) continue;   // already there from an earlier tree
-            for (int c = K - 1; c > pos; --c) row[c] = row[c - 1];
-            row[pos] = key;
+    // candidate keys; the distance's slot then holds the number of old entries below the key
+    const int pitch = S + 1;
+    for (int e = tid; e < s * s; e += nthr) {
+        const int a = e / s, o = e - a * s;
+        u64 key = ~0ULL;
+        int lo = 0;
+        if (o != a) {
+            key = ef_pack(dmat[a * S + o], uid[o], 1);
+            if (!first_tree) {
+                const u64 *row = pools + (size_t)a * K;
+                int hi = K;
+                while (lo < hi) {
+                    const int mid = (lo + hi) >> 1;
+                    if (row[mid] < key) lo = mid + 1;
+                    else hi = mid;
+                }
+                if (lo < K && row[lo] == key) key = ~0ULL;      // already there from an earlier tree
+            }
         }
+        cand[a * pitch + o] = key;
+        below[a * S + o] = lo;
     }
     __syncthreads();
-    for (int e = lane; e < s * K; e += EF_WAVE) {
-        const int r = e / K, c = e - r * K;
-        graph[(size_t)uid[r] * K + c] = pools[e];
+    for (int e = tid; e < s * s; e += nthr) {      // the candidates' places
+        const int a = e / s, o = e - a * s;
+        const u64 key = cand[a * pitch + o];
+        if (key == ~0ULL) continue;
+        int rank = below[a * S + o];
+        for (int k = 0; k < s; ++k) rank += cand[a * pitch + k] < key ? 1 : 0;
+        if (rank < K) graph[(size_t)uid[a] * K + rank] = key;
+    }
+    for (int e = tid; e < s * K; e += nthr) {      // the old entries' places
+        const int a = e / K, j = e - a * K;
+        const u64 en = pools[e];
+        int rank = j;
+        for (int k = 0; k < s; ++k) rank += cand[a * pitch + k] < en ? 1 : 0;
+        if (rank < K) graph[(size_t)uid[a] * K + rank] = en;
     }
 }
 
@@ -1669,7 +1699,9 @@ extern "C" int efanna_init_graph(const float *X, int64_t n, int32_t d, const int
     u64 *const graph = (u64 *)graph_;
     const int stride = d + kRowPad;
     const size_t lds = (size_t)(align4(leaf_size * stride) + align4(leaf_size * leaf_size)) * 4 +
-                       (size_t)leaf_size * k * 8 + (size_t)leaf_size * 4;
+                       (size_t)leaf_size * k * 8 + (size_t)leaf_size * (leaf_size + 1) * 8 +
+                       (size_t)leaf_size * 4;
+    const int block_threads = EF_WAVE * ((leaf_size + 15) / 16);
     const bool reg_ok = leaf_size <= 16 && d % 4 == 0 && ((uintptr_t)X & 15) == 0;
     if (nodes && !reg_ok) return EFANNA_EUNSUPPORTED;      // the step above the leaves has one kernel only
     if (reg_ok) {
@@ -1695,7 +1727,7 @@ extern "C" int efanna_init_graph(const float *X, int64_t n, int32_t d, const int
     EF_HIP_CHECK(hipFuncSetAttribute((const void *)init_tree_kernel,
                                      hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
     for (int t = 0; t < n_trees; ++t)
-        init_tree_kernel<<<n_leaves[t], EF_WAVE, lds, st>>>(
+        init_tree_kernel<<<n_leaves[t], block_threads, lds, st>>>(
             X, d, stride, q4_magic_for(d), leaf_size, perm + (size_t)t * n, leaf_off + (size_t)t * (max_leaves + 1), k,
             graph, t == 0);
     EF_HIP_CHECK(hipGetLastError());
