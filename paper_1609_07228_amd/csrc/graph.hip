@@ -12,7 +12,8 @@
 namespace {
 
 constexpr int kBlock = 256;
-constexpr int kRegGrid = 256 * 32;     // blocks of the register-operand join kernels
+constexpr int kRegGrid = 256 * 128;    // blocks of the register-operand join kernels (grid-strided over the work list)
+constexpr int kLeafGrid = 256 * 32;    // blocks of the register-operand leaf kernels
 constexpr int kMaxLargeGrid = 256 * 32 * 2;     // most blocks the LDS-row join kernel is launched with
 constexpr int kRowPad = 4;   // floats appended to each LDS row
 
@@ -1709,14 +1710,14 @@ extern "C" int efanna_init_graph(const float *X, int64_t n, int32_t d, const int
         const size_t conquer_lds = (size_t)2 * 16 * k * 8 + (size_t)16 * kCandPitch * 8 + 16 * 16 * 4;
         for (int t = 0; t < n_trees; ++t) {
             const int32_t *perm_t = perm + (size_t)t * n, *off_t = leaf_off + (size_t)t * (max_leaves + 1);
-            init_reg_kernel<<<min(n_leaves[t], kRegGrid), EF_WAVE, reg_lds, st>>>(
+            init_reg_kernel<<<min(n_leaves[t], kLeafGrid), EF_WAVE, reg_lds, st>>>(
                 X, d, perm_t, off_t, n_leaves[t], k, graph, t == 0);
             if (levels > 0) {
                 int *etab = (int *)ws;
                 classify_kernel<<<min(grid_for((size_t)n_leaves[t], kBlock / EF_WAVE), 256 * 8), kBlock, 0, st>>>(
                     X, d, perm_t, off_t, n_leaves[t], nodes + (size_t)t * (max_leaves + 1),
                     leaf_up + (size_t)t * (max_leaves + 1), conquer_depth, levels, etab);
-                conquer_kernel<<<min(n_leaves[t], kRegGrid), EF_WAVE, conquer_lds, st>>>(
+                conquer_kernel<<<min(n_leaves[t], kLeafGrid), EF_WAVE, conquer_lds, st>>>(
                     X, d, perm_t, off_t, n_leaves[t], etab, levels, k, graph);
             }
         }
