@@ -1162,38 +1162,41 @@ join_reg_kernel(const float *__restrict__ X, const float *__restrict__ norms, in
     Proposal *queue = (Proposal *)(surv + align4(S_CAP));   // [q_cap]
     const int lane = threadIdx.x, r16 = lane & 15, g = lane >> 4, gl = r16, grp = g;
     const int count = *work_count;
-    // The id list and the sizes of the next point are fetched one point ahead, so that
-    // they travel while this point is being worked on.
+    // The id list and the sizes of a point are fetched one point ahead, and the thresholds and
+    // norms of its vectors as soon as those ids are there, so that they travel while the
+    // point before is being worked on: the row loads are the only latency a point waits for.
+    // (Thresholds only ever fall: one that is a point old lets a few more pairs through the
+    // filter, nothing else.)
     int w = blockIdx.x;
     int i = w < count ? work[w] : -1;
     int u_pre = i >= 0 && lane < R ? ulist[(size_t)i * ucap + min(lane, ucap - 1)] : -1;
     int2 c_pre = i >= 0 ? ucount[i] : make_int2(0, 0);
     int i_next = w + (int)gridDim.x < count ? work[w + gridDim.x] : -1;
+    u32 t_pre = u_pre >= 0 ? worst[u_pre] : 0u;
+    float n_pre = u_pre >= 0 ? norms[u_pre] : 0.0f;
     // Proposals wait in the queue across points and are applied when about half of it is
     // full (and at the end): late iterations accept well under one proposal per point, and
     // a drain costs two memory round trips whatever its size.
     int updates = 0;
     if (lane == 0) meta[3] = 0;
     for (; i >= 0; w += gridDim.x) {
-        // ---- 0. the point's U_new ++ U_old ------------------------------------------------
+        // ---- 0. the point's U_new ++ U_old (the loop ends with a barrier: LDS is free) -------
         const int m_new = c_pre.x, m = c_pre.y;
-        if (lane < R) uid[lane] = u_pre;
+        const int u_cur = u_pre;
+        if (lane < R) {
+            uid[lane] = u_cur;
+            thr[lane] = t_pre;
+            tf[lane] = __uint_as_float(t_pre) * thr_scale;
+            nf[lane] = n_pre * (1.0f - margin_rel);
+        }
         if (lane < 8 && lane != 3) meta[lane] = 0;
-        __syncthreads();
         i = i_next;
         u_pre = i >= 0 && lane < R ? ulist[(size_t)i * ucap + min(lane, ucap - 1)] : -1;
         c_pre = i >= 0 ? ucount[i] : make_int2(0, 0);
         i_next = w + 2 * (int)gridDim.x < count ? work[w + 2 * gridDim.x] : -1;
-        if (lane < m) {
-            const int id = uid[lane];
-            const u32 t = worst[id];
-            thr[lane] = t;
-            tf[lane] = __uint_as_float(t) * thr_scale;
-            nf[lane] = norms[id] * (1.0f - margin_rel);
-        }
         // ---- 1+2. Gram blocks from register operands ---------------------------------------
-        const float *pa = X + (size_t)uid[min(r16, m - 1)] * d + 4 * g;
-        const float *pb = NB > 1 ? X + (size_t)uid[min(16 + r16, m - 1)] * d + 4 * g : pa;
+        const float *pa = X + (size_t)__shfl(u_cur, min(r16, m - 1), EF_WAVE) * d + 4 * g;
+        const float *pb = NB > 1 ? X + (size_t)__shfl(u_cur, min(16 + r16, m - 1), EF_WAVE) * d + 4 * g : pa;
         const bool need11 = NB > 1 && m_new > 16;      // block (1,1) only if new rows reach it
         constexpr int NQ = NB > 1 ? 3 : 1;      // Gram blocks (0,0), (0,1), (1,1)
         floatx4 acc[NQ][2];
@@ -1242,7 +1245,9 @@ join_reg_kernel(const float *__restrict__ X, const float *__restrict__ norms, in
                 }
             }
         }
-        __syncthreads();      // thr, nrm visible
+        __syncthreads();      // uid, thr, nf, tf visible
+        t_pre = u_pre >= 0 ? worst[u_pre] : 0u;      // the next point's; its ids have arrived by now
+        n_pre = u_pre >= 0 ? norms[u_pre] : 0.0f;
         // ---- filter: lane holds G[a = 16 bi + 4 g + k][b = 16 bj + r16] of block q -----------
         // pair (a, b) survives if (|a|^2 + |b|^2)(1 - margin) - 2 a.b <= max threshold * scale
 #pragma unroll
