@@ -231,27 +231,27 @@ struct FlagPred {
     __device__ int operator()(size_t p) const { return flag[p]; }
 };
 
-__device__ inline int block_sum(int v, int *sh)
-{
-    v = ef_wave_sum_i32(v);
-    if (ef_lane() == 0) sh[threadIdx.x / EF_WAVE] = v;
-    __syncthreads();
-    int tot = 0;
-    for (int w = 0; w < kBlock / EF_WAVE; ++w) tot += sh[w];
-    __syncthreads();
-    return tot;
-}
-
+// A scan block covers kScanTile consecutive positions; thread t looks at positions t,
+// t + kBlock, ... of the tile, so that a wave reads consecutive words.  The predicates are
+// single bits: a wave counts them with a ballot.
 template <class Pred>
 __global__ void scan_reduce_kernel(Pred pred, size_t total, int *block_sums)
 {
     __shared__ int sh[kBlock / EF_WAVE];
-    size_t base = (size_t)blockIdx.x * kScanTile + (size_t)threadIdx.x * kScanItems;
+    const size_t base = (size_t)blockIdx.x * kScanTile + threadIdx.x;
     int v = 0;
-    for (int k = 0; k < kScanItems; ++k)
-        if (base + k < total) v += pred(base + k);
-    int tot = block_sum(v, sh);
-    if (threadIdx.x == 0) block_sums[blockIdx.x] = tot;
+#pragma unroll
+    for (int k = 0; k < kScanItems; ++k) {
+        const size_t p = base + (size_t)k * kBlock;
+        v += __popcll(__ballot(p < total && pred(p)));
+    }
+    if (ef_lane() == 0) sh[threadIdx.x / EF_WAVE] = v;      // the whole wave holds the same count
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        int tot = 0;
+        for (int w = 0; w < kBlock / EF_WAVE; ++w) tot += sh[w];
+        block_sums[blockIdx.x] = tot;
+    }
 }
 
 // exclusive scan of block_sums in place, single block; block_sums[nb] = grand total
@@ -282,22 +282,29 @@ __global__ void scan_blocksums_kernel(int *block_sums, int nb)
 template <class Pred>
 __global__ void scan_apply_kernel(Pred pred, size_t total, const int *block_sums, int nb, int *out)
 {
-    __shared__ int sh[kBlock / EF_WAVE];
-    size_t base = (size_t)blockIdx.x * kScanTile + (size_t)threadIdx.x * kScanItems;
-    int f[kScanItems];
-    int v = 0;
+    __shared__ int sh[kScanItems][kBlock / EF_WAVE];      // set bits per row of kBlock positions and wave
+    const int lane = ef_lane(), wave = threadIdx.x / EF_WAVE;
+    const size_t base = (size_t)blockIdx.x * kScanTile + threadIdx.x;
+    int before[kScanItems];      // set bits before this position inside its wave's 64 positions
+#pragma unroll
     for (int k = 0; k < kScanItems; ++k) {
-        f[k] = base + k < total ? pred(base + k) : 0;
-        v += f[k];
+        const size_t p = base + (size_t)k * kBlock;
+        const u64 bal = __ballot(p < total && pred(p));
+        before[k] = __popcll(bal & ((1ULL << lane) - 1));
+        if (lane == 0) sh[k][wave] = __popcll(bal);
     }
-    int inc = ef_wave_scan_i32(v);
-    if (ef_lane() == EF_WAVE - 1) sh[threadIdx.x / EF_WAVE] = inc;
     __syncthreads();
-    int off = block_sums[blockIdx.x] + inc - v;
-    for (int w = 0; w < (int)(threadIdx.x / EF_WAVE); ++w) off += sh[w];
+    int off = block_sums[blockIdx.x];
+#pragma unroll
     for (int k = 0; k < kScanItems; ++k) {
-        if (base + k < total) out[base + k] = off;
-        off += f[k];
+        const size_t p = base + (size_t)k * kBlock;
+        int mine = off + before[k];
+        for (int w = 0; w < kBlock / EF_WAVE; ++w) {
+            const int c = sh[k][w];
+            mine += w < wave ? c : 0;
+            off += c;
+        }
+        if (p < total) out[p] = mine;
     }
     if (blockIdx.x == 0 && threadIdx.x == 0) out[total] = block_sums[nb];
 }
