@@ -35,7 +35,7 @@ struct Node {
 };
 
 struct Counters {
-    int next_nodes;
+    int n_nodes[2];     // live nodes of level l in n_nodes[l & 1]; children_kernel fills the other one
     int bad_input;
     int small_nodes;
     int max_depth;      // deepest internal node (only tracked with node export)
@@ -152,14 +152,18 @@ __global__ void roots_kernel(Node *nodes, int *dims, int *node_of, unsigned char
         nodes[p] = nd;
         dims[p] = nd.dim;
     }
-    if (p == 0) c->next_nodes = 0;
+    if (p == 0) {
+        c->n_nodes[0] = live ? T : 0;
+        c->n_nodes[1] = 0;
+    }
 }
 
 __global__ void __launch_bounds__(kBlock)
 sum_kernel(const float *__restrict__ XT, int n, const int *__restrict__ perm,
            const int *__restrict__ node_of, Node *nodes, const int *__restrict__ dims,
-           float *__restrict__ val, size_t total)
+           float *__restrict__ val, size_t total, Counters *c, int level)
 {
+    if (blockIdx.x == 0 && threadIdx.x == 0) c->n_nodes[(level + 1) & 1] = 0;      // filled by children_kernel
     __shared__ long long wave_tot[kBlock / EF_WAVE];
     __shared__ int wave_node[kBlock / EF_WAVE];
     size_t p = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
@@ -309,7 +313,7 @@ __global__ void scan_apply_kernel(Pred pred, size_t total, const int *block_sums
     if (blockIdx.x == 0 && threadIdx.x == 0) out[total] = block_sums[nb];
 }
 
-__global__ void children_kernel(Node *cur, int n_cur, Node *next, int *next_dims,
+__global__ void children_kernel(Node *cur, int level, Node *next, int *next_dims,
                                 const int *__restrict__ lcount,
                                 unsigned char *leaf_flag, int S, int fin, SmallNode *small, u64 seed,
                                 int n, int d, Counters *c, NodeRec *rec, int *leaf_rec)
@@ -317,6 +321,7 @@ __global__ void children_kernel(Node *cur, int n_cur, Node *next, int *next_dims
     int s = blockIdx.x * blockDim.x + threadIdx.x;
     int kind[2] = {0, 0};      // 0 leaf, 1 finished later inside one workgroup, 2 next level
     Node nd;
+    const int n_cur = c->n_nodes[level & 1];      // the launch covers the most nodes a level can have
     if (s < n_cur) {
         nd = cur[s];
         int cnt = nd.e - nd.b;
@@ -337,7 +342,7 @@ __global__ void children_kernel(Node *cur, int n_cur, Node *next, int *next_dims
     const int wave_total = __shfl(inc, EF_WAVE - 1, EF_WAVE), wave_total_s = __shfl(inc_s, EF_WAVE - 1, EF_WAVE);
     int base = 0, base_s = 0;
     if (ef_lane() == EF_WAVE - 1) {
-        if (wave_total > 0) base = atomicAdd(&c->next_nodes, wave_total);
+        if (wave_total > 0) base = atomicAdd(&c->n_nodes[(level + 1) & 1], wave_total);
         if (wave_total_s > 0) base_s = atomicAdd(&c->small_nodes, wave_total_s);
     }
     base = __shfl(base, EF_WAVE - 1, EF_WAVE);
@@ -742,21 +747,31 @@ extern "C" int efanna_build_trees(const float *X, int64_t n, int32_t d, int32_t 
     int *node_cur = w.node_a, *node_nxt = w.node_b;
     Node *nodes_cur = w.nodes_a, *nodes_nxt = w.nodes_b;
     int *dims_cur = w.dims_a, *dims_nxt = w.dims_b;
+    // Nodes of more than `fin` positions are split level by level, device-wide.  While
+    // 2^level * fin < n some node of the level is certainly that large, so those levels are
+    // enqueued without asking; after them the host looks at the count after every level.
+    // A level has at most total / (fin + 1) + T live nodes (they are disjoint).
+    int sure = 0;
+    if (n > fin)
+        for (long long cap = fin; cap < n; cap *= 2) ++sure;
+    const int max_live = (int)(total / (size_t)(fin + 1)) + T;
+    const int grid_nodes = (max_live + kBlock - 1) / kBlock;
     int n_cur = n > fin ? T : 0;
-    while (n_cur > 0) {
+    for (int level = 0; n_cur > 0; ++level) {
         sum_kernel<<<grid_pos, kBlock, 0, st>>>(w.xt, (int)n, perm_cur, node_cur, nodes_cur, dims_cur, w.val,
-                                                total);
+                                                total, w.counters, level);
         LeftPred pred{node_cur, nodes_cur, w.val};
         device_scan(pred, total, w.block_sums, w.lcount, st);
-        children_kernel<<<(n_cur + kBlock - 1) / kBlock, kBlock, 0, st>>>(
-            nodes_cur, n_cur, nodes_nxt, dims_nxt, w.lcount, w.leaf_flag, S, fin, w.small, seed, (int)n, d,
+        children_kernel<<<grid_nodes, kBlock, 0, st>>>(
+            nodes_cur, level, nodes_nxt, dims_nxt, w.lcount, w.leaf_flag, S, fin, w.small, seed, (int)n, d,
             w.counters, w.rec, w.leaf_rec);
         scatter_kernel<<<grid_pos, kBlock, 0, st>>>(perm_cur, perm_nxt, node_cur, node_nxt, nodes_cur,
                                                     w.val, w.lcount, total);
-        EF_HIP_CHECK(hipMemcpyAsync(&host_c, w.counters, sizeof(Counters), hipMemcpyDeviceToHost, st));
-        EF_HIP_CHECK(hipMemsetAsync(&w.counters->next_nodes, 0, sizeof(int), st));
-        EF_HIP_CHECK(hipStreamSynchronize(st));
-        n_cur = host_c.next_nodes;
+        if (level + 1 >= sure) {
+            EF_HIP_CHECK(hipMemcpyAsync(&host_c, w.counters, sizeof(Counters), hipMemcpyDeviceToHost, st));
+            EF_HIP_CHECK(hipStreamSynchronize(st));
+            n_cur = host_c.n_nodes[(level + 1) & 1];
+        }
         int *tp = perm_cur; perm_cur = perm_nxt; perm_nxt = tp;
         int *tn = node_cur; node_cur = node_nxt; node_nxt = tn;
         Node *tq = nodes_cur; nodes_cur = nodes_nxt; nodes_nxt = tq;
