@@ -80,6 +80,7 @@ __device__ inline void record_leaf(NodeRec *rec, int *leaf_rec, int b, int paren
 
 constexpr int kFinMax = 2048;      // largest segment finish_kernel takes
 constexpr int kFinNodes = 256;     // nodes of one level inside such a segment
+constexpr int kFinThreads = 512;    // threads of a finish_kernel block
 inline int finish_limit(int S)
 {
     long f = (long)kFinNodes * (S + 1);     // so that a level never has more than kFinNodes live nodes
@@ -431,7 +432,7 @@ struct LNode {
     int parent, pad;           // parent: global position, as in Node
 };
 
-__global__ void __launch_bounds__(kBlock)
+__global__ void __launch_bounds__(kFinThreads)
 finish_kernel(const float *__restrict__ XT, int d, int *perm, const SmallNode *__restrict__ small,
               unsigned char *leaf_flag, int S, u64 seed, int n, NodeRec *rec, int *leaf_rec,
               int *max_depth)
@@ -442,14 +443,14 @@ finish_kernel(const float *__restrict__ XT, int d, int *perm, const SmallNode *_
     int *const ids_base = fsm, *const nidx_base = fsm + 2 * kFinMax;      // [2][kFinMax] each
     float *val = (float *)(fsm + 4 * kFinMax);
     int *lcnt = fsm + 5 * kFinMax;                                 // [kFinMax + 1]
-    int *wave_tot = fsm + 6 * kFinMax + 4;                         // [kBlock / EF_WAVE]
+    int *wave_tot = fsm + 6 * kFinMax + 4;                         // [kFinThreads / EF_WAVE]
     int &n_next_sh = fsm[6 * kFinMax + 2];
     int &depth_sh = fsm[6 * kFinMax + 3];                          // deepest node of this subtree
-    LNode *const tabs_base = (LNode *)(fsm + 6 * kFinMax + 8);     // [2][kFinNodes], 8-byte aligned
+    LNode *const tabs_base = (LNode *)(fsm + 6 * kFinMax + 16);     // [2][kFinNodes], 8-byte aligned
     const SmallNode seg = small[blockIdx.x];
     const int cnt = seg.e - seg.b, tid = threadIdx.x;
     const u64 key = ef_stream_key(seed, seg.b / n);
-    for (int p = tid; p < cnt; p += kBlock) {
+    for (int p = tid; p < cnt; p += kFinThreads) {
         ids_base[p] = perm[seg.b + p];
         nidx_base[p] = 0;
     }
@@ -472,13 +473,13 @@ finish_kernel(const float *__restrict__ XT, int d, int *perm, const SmallNode *_
     }
     __syncthreads();
     int cur = 0, n_cur = 1;
-    const int chunk = (cnt + kBlock - 1) / kBlock;      // consecutive positions per thread in the scan
+    const int chunk = (cnt + kFinThreads - 1) / kFinThreads;      // consecutive positions per thread in the scan
     while (n_cur > 0) {
         int *idc = ids_base + cur * kFinMax, *idn = ids_base + (cur ^ 1) * kFinMax;
         int *nc = nidx_base + cur * kFinMax, *nn = nidx_base + (cur ^ 1) * kFinMax;
         LNode *tc = tabs_base + cur * kFinNodes, *tn = tabs_base + (cur ^ 1) * kFinNodes;
         // 1. sums
-        for (int p = tid; p < cnt; p += kBlock) {
+        for (int p = tid; p < cnt; p += kFinThreads) {
             const int k = nc[p];
             if (k >= 0 && tc[k].dim >= 0) {
                 const float x = XT[(size_t)tc[k].dim * n + idc[p]];
@@ -509,11 +510,11 @@ finish_kernel(const float *__restrict__ XT, int d, int *perm, const SmallNode *_
                 lcnt[p] = off;
                 off += f;
             }
-            if (tid == kBlock - 1) lcnt[cnt] = off;      // the last thread's running sum is the total
+            if (tid == kFinThreads - 1) lcnt[cnt] = off;      // the last thread's running sum is the total
         }
         __syncthreads();
         // 3. children
-        for (int k = tid; k < n_cur; k += kBlock) {
+        for (int k = tid; k < n_cur; k += kFinThreads) {
             LNode nd = tc[k];
             const int c = nd.e - nd.b;
             const int nl = nd.dim >= 0 ? lcnt[nd.e] - lcnt[nd.b] : 0;
@@ -556,7 +557,7 @@ finish_kernel(const float *__restrict__ XT, int d, int *perm, const SmallNode *_
         }
         __syncthreads();
         // 4. stable scatter
-        for (int p = tid; p < cnt; p += kBlock) {
+        for (int p = tid; p < cnt; p += kFinThreads) {
             const int k = nc[p];
             const int id = idc[p];
             if (k < 0) {
@@ -581,7 +582,7 @@ finish_kernel(const float *__restrict__ XT, int d, int *perm, const SmallNode *_
         if (tid == 0) n_next_sh = 0;
         __syncthreads();
     }
-    for (int p = tid; p < cnt; p += kBlock) perm[seg.b + p] = ids_base[cur * kFinMax + p];
+    for (int p = tid; p < cnt; p += kFinThreads) perm[seg.b + p] = ids_base[cur * kFinMax + p];
     if (rec && tid == 0) atomicMax(max_depth, depth_sh);
 }
 
@@ -779,10 +780,10 @@ extern "C" int efanna_build_trees(const float *X, int64_t n, int32_t d, int32_t 
     }
     // host_c.small_nodes is current: it was read after the last level (or after the roots)
     if (host_c.small_nodes > 0) {
-        const size_t fin_lds = (size_t)(6 * kFinMax + 8) * 4 + 2 * (size_t)kFinNodes * sizeof(LNode);
+        const size_t fin_lds = (size_t)(6 * kFinMax + 16) * 4 + 2 * (size_t)kFinNodes * sizeof(LNode);
         EF_HIP_CHECK(hipFuncSetAttribute((const void *)finish_kernel,
                                          hipFuncAttributeMaxDynamicSharedMemorySize, (int)fin_lds));
-        finish_kernel<<<host_c.small_nodes, kBlock, fin_lds, st>>>(w.xt, d, perm_cur, w.small, w.leaf_flag,
+        finish_kernel<<<host_c.small_nodes, kFinThreads, fin_lds, st>>>(w.xt, d, perm_cur, w.small, w.leaf_flag,
                                                                   S, seed, (int)n, w.rec, w.leaf_rec,
                                                                   &w.counters->max_depth);
     }
