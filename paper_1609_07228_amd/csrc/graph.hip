@@ -25,10 +25,12 @@ __host__ __device__ inline int align4(int x) { return (x + 3) & ~3; }
 // ---------------------------------------------------------------------------------------
 // fills
 
-// reverse lists: slot s of an empty list holds ~0 - s (above every real key)
-__global__ void fill_reverse_kernel(u64 *a, u64 *b, size_t total, int L, int *a_count, int *b_count,
-                                    u64 *list_max, size_t n, int *work_count, int *upd_block,
-                                    int n_upd_block)
+// per-iteration reset: reverse-list fill counts and bounds, work-list sizes, insertion
+// counts of the join blocks.  The lists themselves need no reset: the first L arrivals
+// overwrite slots 0..L-1 in some order, readers stop at min(count, L), and the bounded
+// insertion only ever touches lists that are full.
+__global__ void fill_reverse_kernel(int *a_count, int *b_count, u64 *list_max, size_t n,
+                                    int *work_count, int *upd_block, int n_upd_block)
 {
     size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (i < 8) work_count[i] = 0;     // three work lists
@@ -39,11 +41,6 @@ __global__ void fill_reverse_kernel(u64 *a, u64 *b, size_t total, int L, int *a_
         b_count[i] = 0;
         list_max[i] = ~0ULL;
         list_max[n + i] = ~0ULL;
-    }
-    if (i < total) {
-        u64 v = ~0ULL - (u64)(i % (size_t)L);
-        a[i] = v;
-        b[i] = v;
     }
 }
 
@@ -1838,9 +1835,9 @@ extern "C" int efanna_nndescent(const float *X, int64_t n, int32_t d, int32_t k,
     for (int it = 0; it < iters; ++it) {
         const int g = first_iter + it;
         if (ev) EF_HIP_CHECK(hipEventRecord(ev[5 * it], st));
-        fill_reverse_kernel<<<grid_for((size_t)n * L, kBlock), kBlock, 0, st>>>(
-            w.rnew, w.rold, (size_t)n * L, L, w.rnew_c, w.rold_c, w.list_max, (size_t)n, w.work_count,
-            w.upd_block, 2 * kRegGrid + kMaxLargeGrid);
+        fill_reverse_kernel<<<grid_for((size_t)n, kBlock), kBlock, 0, st>>>(
+            w.rnew_c, w.rold_c, w.list_max, (size_t)n, w.work_count, w.upd_block,
+            2 * kRegGrid + kMaxLargeGrid);
         {
             const u64 kn = ef_stream_key(seed, 2 * g), ko = ef_stream_key(seed, 2 * g + 1);
             Overflow *ovf = (Overflow *)w.overflow;
