@@ -351,7 +351,7 @@ init_reg_kernel(const float *__restrict__ X, int d, const int *__restrict__ perm
             const float dist = (R[t][0] + R[t][2]) + (R[t][1] + R[t][3]);
             const int rot = 2 * g + 1 + t;
             const int bf = (r16 + dirn * rot) & 15, br = (r16 - dirn * rot) & 15;
-            const float dist_r = __shfl(dist, br + 16 * g, EF_WAVE);     // lane br met r16 in this round
+            const float dist_r = __shfl(dist, br + 16 * g, EF_WAVE);     // lane br met r16 at this rotation
             key[t] = r16 < s && bf < s ? ef_pack(dist, uid[bf], 1) : ~0ULL;
             key[2 + t] = r16 < s && br < s && rot != 8 ? ef_pack(dist_r, uid[br], 1) : ~0ULL;
         }

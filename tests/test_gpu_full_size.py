@@ -83,14 +83,7 @@ def test_headline_workload_bit_exact_against_oracle():
 
 
 def _progress(msg):
-    """Long tests leave a trace outside pytest's capture, so that a watcher can tell them
-    from a hang."""
-    import os
-    import time
-    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
-    os.makedirs(os.path.join(root, "gpurun_out"), exist_ok=True)
-    with open(os.path.join(root, "gpurun_out", "test_progress.log"), "a") as f:
-        f.write(f"{time.strftime('%H:%M:%S')} {msg}\n")
+    print(msg, flush=True)      # shown with -s or on failure
 
 
 @pytest.mark.timeout(600)
