@@ -1321,7 +1321,9 @@ join_reg_kernel(const float *__restrict__ X, const float *__restrict__ norms, in
                         }
                     }
                     __syncthreads();
-                    if (meta[3] + 32 > q_cap) {      // a round adds at most two proposals per pair
+                    // NB = 1: the queue is sized so that a point's proposals always fit (at most 240
+                    // on top of fewer than q_cap / 2): no drain while the operands are live
+                    if (NB > 1 && meta[3] + 32 > q_cap) {      // a round adds at most two proposals per pair
                         updates += drain_queue(queue, meta[3], graph, worst, K, lane, EF_WAVE);
                         __syncthreads();
                         if (lane == 0) meta[3] = 0;
@@ -1804,8 +1806,11 @@ extern "C" int efanna_nndescent(const float *X, int64_t n, int32_t d, int32_t k,
     };
     const Shape large = shape_for(max_rows);
     if (max_rows > rows1 && large.lds > kLdsLimit) return EFANNA_EUNSUPPORTED;
-    const int reg_q_cap = 128;
+    // joins of at most 16 vectors from registers (d <= 128): room for a whole point's proposals
+    // (240) above the drain mark; the others drain between rounds as well
+    auto reg_q_cap_for = [&](int R) { return R == 16 && d <= 128 ? 512 : 128; };
     auto reg_lds = [&](int R) {
+        const int reg_q_cap = reg_q_cap_for(R);
         return (size_t)(4 * R + 8 + align4(R * (R - 1) / 2 + 8)) * 4 +
                (size_t)reg_q_cap * sizeof(Proposal);
     };
@@ -1868,7 +1873,7 @@ extern "C" int efanna_nndescent(const float *X, int64_t n, int32_t d, int32_t k,
         if (reg_ok) {
 #define EF_JOIN_REG(NB, ONE, LIST)                                                                 \
     join_reg_kernel<NB, ONE><<<reg_grid, EF_WAVE, reg_lds(16 * NB), st>>>(                         \
-        X, w.norms, d, K, w.work + (size_t)(LIST) * n, w.work_count + (LIST), reg_q_cap,           \
+        X, w.norms, d, K, w.work + (size_t)(LIST) * n, w.work_count + (LIST), reg_q_cap_for(16 * NB), \
         margin_rel, thr_scale, w.ulist, w.ucount, max_rows, graph, w.worst,                        \
         w.upd_block + (LIST) * reg_grid)
             if (d <= 128) EF_JOIN_REG(1, true, 0);
