@@ -58,6 +58,11 @@ def _load():
         lib.oracle_nndescent_until.argtypes = [C.c_void_p, C.c_int64, C.c_int32, C.c_int32, C.c_void_p,
                                                C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_uint64,
                                                C.c_int32, C.c_void_p, C.c_double, C.c_void_p]
+        lib.oracle_search.restype = C.c_int
+        lib.oracle_search.argtypes = [C.c_void_p, C.c_int64, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p,
+                                      C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_int32, C.c_void_p,
+                                      C.c_int64, C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_void_p,
+                                      C.c_void_p, C.c_void_p]
         lib.oracle_num_threads.restype = C.c_int
         lib.oracle_set_num_threads.argtypes = [C.c_int]
         _lib = lib
@@ -177,6 +182,30 @@ def init_graph(X, perm, leaf_off, n_leaves, K: int, rows=None):
     if rc != 0:
         raise ValueError(f"oracle_init_graph failed: {rc}")
     return ids, dists, flags
+
+
+def search(X, perm, leaf_off, n_leaves, nodes, S: int, graph_ids, queries, K: int, P: int, E: int,
+           iters: int):
+    """Alg. 1 for a batch of queries.  Returns (ids [nq,K] int32, dists [nq,K] float32,
+    checked [nq] int32 = distances evaluated per query)."""
+    X = _f32(X)
+    Q = _f32(queries)
+    n, d = X.shape
+    T = perm.shape[0]
+    assert Q.shape[1] == d and nodes.shape == (T, n + 1) and nodes.dtype == NODE_DTYPE
+    g = np.ascontiguousarray(graph_ids, dtype=np.int32)
+    assert g.shape[0] == n
+    nq = Q.shape[0]
+    ids = np.empty((nq, K), dtype=np.int32)
+    dists = np.empty((nq, K), dtype=np.float32)
+    checked = np.zeros(nq, dtype=np.int32)
+    rc = _load().oracle_search(_p(X), n, d, _p(np.ascontiguousarray(perm)),
+                               _p(np.ascontiguousarray(leaf_off)), _p(np.ascontiguousarray(n_leaves)),
+                               _p(np.ascontiguousarray(nodes)), T, S, _p(g), g.shape[1], _p(Q), nq, K, P, E,
+                               iters, _p(ids), _p(dists), _p(checked))
+    if rc != 0:
+        raise ValueError(f"oracle_search failed: {rc}")
+    return ids, dists, checked
 
 
 def nndescent(X, ids, dists, flags, iters: int, L: int, seed: int, iter0: int = 0,

@@ -3,7 +3,8 @@
  * randomized truncated KD-trees (Alg. 2), the conquer step of the
  * divide-and-conquer initialisation (Alg. 3: the point's own leaf in every tree
  * and, above the conquer-to depth, one leaf of every sibling subtree on the way
- * up) and NN-descent refinement (Alg. 4).
+ * up), NN-descent refinement (Alg. 4) and the search with the finished index
+ * (Alg. 1).
  *
  * THIS IS TEST INFRASTRUCTURE.  It is a plain, slow, step-by-step statement of
  * what the method computes, used only to check the GPU library and to serve as
@@ -564,6 +565,146 @@ int oracle_nndescent(const float *X, int64_t n, int32_t d, int32_t K, int32_t *i
 {
     return oracle_nndescent_until(X, n, d, K, ids, dists, flags, iters, L, seed, iter0, stats, 0.0,
                                   NULL);
+}
+
+/* ------------------------------------------------------------------------- */
+/* Alg. 1: search with the index (trees for the first candidates, the graph for  */
+/* NN-expansion).                                                               */
+
+typedef struct { double prio; int32_t link; } branch;
+
+/* Alg. 1, "search tree i for the top N_node closest leaf nodes according to the
+ * tree's search criteria": best-bin-first search as in randomized KD-trees.  Going
+ * down, the child on the query's side of the split is taken (the test that built
+ * the tree: left iff cnt*q(x) < sum) and the other child is put aside with the
+ * priority of the branch being followed plus the squared distance from the query's
+ * coordinate to the split value (the node's mean, sum / cnt, in coordinate units:
+ * 2^-20 of the quantised ones); after a leaf the branch with the smallest
+ * (priority, link) put aside so far is followed.  A node without a dimension sends
+ * the query left and puts the right child aside at the same priority.  Returns the
+ * number of leaves written to `leaves` (at most want). */
+static int32_t tree_search(const float *q, const oracle_node *nodes, int32_t n_leaves, int32_t want,
+                           int32_t *leaves, branch *heap, int32_t heap_cap)
+{
+    if (n_leaves == 1) {
+        leaves[0] = 0;
+        return want > 0 ? 1 : 0;
+    }
+    /* the root is the node without a parent */
+    int32_t root = -1;
+    for (int32_t j = 1; j < n_leaves; ++j)
+        if (nodes[j].parent < 0) root = j;
+    int32_t n_heap = 0, found = 0;
+    int32_t link = root;
+    double prio = 0.0;
+    while (found < want) {
+        while (link >= 0) { /* down to a leaf */
+            const oracle_node *nd = &nodes[link];
+            int left = 1;
+            double other = prio;
+            if (nd->dim >= 0) {
+                int64_t diff = (int64_t)nd->cnt * quantise(q[nd->dim]) - nd->sum;
+                left = diff < 0;
+                double gap = (double)diff / ((double)nd->cnt * 1048576.0);
+                other = fma(gap, gap, prio);
+            }
+            if (n_heap == heap_cap) return -1; /* cannot happen with the caller's capacity */
+            heap[n_heap].prio = other;
+            heap[n_heap].link = nd->child[left ? 1 : 0];
+            ++n_heap;
+            link = nd->child[left ? 0 : 1];
+        }
+        leaves[found++] = ~link;
+        if (n_heap == 0) break;
+        int32_t best = 0;
+        for (int32_t h = 1; h < n_heap; ++h)
+            if (heap[h].prio < heap[best].prio ||
+                (heap[h].prio == heap[best].prio && heap[h].link < heap[best].link))
+                best = h;
+        prio = heap[best].prio;
+        link = heap[best].link;
+        heap[best] = heap[--n_heap];
+    }
+    return found;
+}
+
+/* queries: [nq][d].  graph_ids: [n][Kg] neighbour ids (-1 = empty slot).  K <= P.
+ * Alg. 1 with N_node = P / S / T + 1 leaves per tree (integer divisions), the E
+ * closest points of those leaves as the first pool, then `iters` rounds in which
+ * every pool member that has not been expanded yet contributes its graph
+ * neighbours that have not been checked yet, and the pool keeps the P closest.
+ * Ties by id.  out_ids / out_dists: [nq][K], padded with -1 / +inf.
+ * n_checked (may be NULL): [nq] distances evaluated per query. */
+int oracle_search(const float *X, int64_t n, int32_t d, const int32_t *perm,
+                  const int32_t *leaf_off, const int32_t *n_leaves, const oracle_node *nodes,
+                  int32_t T, int32_t S, const int32_t *graph_ids, int32_t Kg, const float *queries,
+                  int64_t nq, int32_t K, int32_t P, int32_t E, int32_t iters, int32_t *out_ids,
+                  float *out_dists, int32_t *n_checked)
+{
+    if (!X || !perm || !leaf_off || !n_leaves || !nodes || !graph_ids || !queries) return -1;
+    if (n < 1 || T < 1 || S < 1 || K < 1 || P < K || E < 1 || E > P || iters < 0 || Kg < 1) return -1;
+    const int32_t want = P / S / T + 1;
+    int failed = 0;
+#pragma omp parallel
+    {
+        uint8_t *checked = (uint8_t *)calloc((size_t)n, 1);
+        entry *pool = (entry *)malloc((size_t)P * sizeof(entry));
+        int32_t *expand = (int32_t *)malloc((size_t)P * sizeof(int32_t));
+        int32_t *touched = (int32_t *)malloc((size_t)n * sizeof(int32_t));
+        int32_t *leaves = (int32_t *)malloc((size_t)want * sizeof(int32_t));
+        /* a descent puts aside one branch per level; trees are at most 60 + log2(n) deep */
+        const int32_t heap_cap = (want + 1) * 128;
+        branch *heap = (branch *)malloc((size_t)heap_cap * sizeof(branch));
+#pragma omp for schedule(dynamic, 16)
+        for (int64_t qi = 0; qi < nq; ++qi) {
+            const float *q = queries + qi * d;
+            int32_t cnt = 0, n_touched = 0, cap = E;
+            for (int32_t t = 0; t < T; ++t) {
+                const int32_t *off = leaf_off + (int64_t)t * (n + 1);
+                int32_t found = tree_search(q, nodes + (int64_t)t * (n + 1), n_leaves[t], want, leaves,
+                                            heap, heap_cap);
+                if (found < 0) {
+#pragma omp atomic write
+                    failed = 1;
+                    found = 0;
+                }
+                for (int32_t f = 0; f < found; ++f)
+                    for (int32_t p = off[leaves[f]]; p < off[leaves[f] + 1]; ++p) {
+                        int32_t j = perm[(int64_t)t * n + p];
+                        if (checked[j]) continue;
+                        checked[j] = 1;
+                        touched[n_touched++] = j;
+                        pool_insert(pool, &cnt, cap, oracle_dist(q, X + (int64_t)j * d, d), j);
+                    }
+            }
+            /* pool_insert marks what it takes as new: here "not expanded yet" */
+            cap = P;
+            for (int32_t it = 0; it < iters; ++it) {
+                int32_t n_exp = 0;
+                for (int32_t s = 0; s < cnt; ++s)
+                    if (pool[s].is_new) {
+                        pool[s].is_new = 0;
+                        expand[n_exp++] = pool[s].id;
+                    }
+                for (int32_t e = 0; e < n_exp; ++e)
+                    for (int32_t c = 0; c < Kg; ++c) {
+                        int32_t j = graph_ids[(int64_t)expand[e] * Kg + c];
+                        if (j < 0 || checked[j]) continue;
+                        checked[j] = 1;
+                        touched[n_touched++] = j;
+                        pool_insert(pool, &cnt, cap, oracle_dist(q, X + (int64_t)j * d, d), j);
+                    }
+            }
+            for (int32_t s = 0; s < K; ++s) {
+                out_ids[qi * K + s] = s < cnt ? pool[s].id : -1;
+                out_dists[qi * K + s] = s < cnt ? pool[s].dist : INFINITY;
+            }
+            if (n_checked) n_checked[qi] = n_touched;
+            for (int32_t s = 0; s < n_touched; ++s) checked[touched[s]] = 0;
+        }
+        free(checked); free(pool); free(expand); free(touched); free(leaves); free(heap);
+    }
+    return failed ? -6 : 0;
 }
 
 void oracle_set_num_threads(int t)
