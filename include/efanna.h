@@ -201,6 +201,35 @@ int efanna_set_graph(efanna_entry *graph, int64_t n, int32_t k, const int32_t *i
 int efanna_pair_distances(const float *X, int64_t n, int32_t d, const int32_t *a_ids,
                           const int32_t *b_ids, int64_t m, float *out, void *stream);
 
+/* ---- Alg. 1: search with the finished index ---------------------------------------------
+ * For each of nq queries: every tree is searched, best bin first, for its N_node = pool /
+ * leaf_size / n_trees + 1 closest leaves (going down, the child on the query's side of the
+ * split is taken and the other put aside with the priority of the branch followed plus the
+ * squared distance, in float64, from the query's coordinate to the node's mean sum / cnt;
+ * after a leaf the search continues from the smallest (priority, child link) put aside); the
+ * `expand` closest members of those leaves form the first pool; then, `iters` times, every
+ * pool member that has not been expanded yet hands in its graph neighbours, those never
+ * checked before are evaluated, and the pool keeps the `pool` closest.  Ties by id.
+ *
+ * perm .. nodes, tree_depth: as produced by efanna_build_trees with nodes.
+ * graph_ids [device] n*graph_k int32, neighbour ids as efanna_get_graph writes them (-1 = none).
+ * queries  [device] nq*d float32, row-major, 16-byte aligned.
+ * ids, dists [device] out, nq*k: the k closest pool members, ascending; -1 / +inf padding.
+ * checked  [device] out or NULL, nq int32: distances evaluated per query.
+ * Synchronises the stream.  Limits: k <= pool <= 1024, 1 <= expand <= pool, d a multiple of 4,
+ * X 16-byte aligned (EFANNA_EUNSUPPORTED otherwise).
+ */
+size_t efanna_search_workspace_bytes(int64_t nq, int32_t d, int32_t n_trees, int32_t leaf_size,
+                                     int32_t tree_depth, int32_t graph_k, int32_t pool,
+                                     int32_t iters);
+
+int efanna_search(const float *X, int64_t n, int32_t d, const int32_t *perm,
+                  const int32_t *leaf_off, int32_t max_leaves, const int32_t *n_leaves,
+                  const efanna_node *nodes, int32_t tree_depth, int32_t n_trees, int32_t leaf_size,
+                  const int32_t *graph_ids, int32_t graph_k, const float *queries, int64_t nq,
+                  int32_t k, int32_t pool, int32_t expand, int32_t iters, int32_t *ids,
+                  float *dists, int32_t *checked, void *ws, size_t ws_bytes, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

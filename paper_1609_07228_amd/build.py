@@ -5,7 +5,7 @@ import os
 import subprocess
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-SOURCES = [os.path.join(_HERE, "csrc", f) for f in ("trees.hip", "graph.hip")]
+SOURCES = [os.path.join(_HERE, "csrc", f) for f in ("trees.hip", "graph.hip", "search.hip")]
 HEADERS = [os.path.join(_HERE, "csrc", "common.h"),
            os.path.join(os.path.dirname(_HERE), "include", "efanna.h")]
 LIB = os.path.join(_HERE, "libefanna_hip.so")

@@ -22,7 +22,8 @@ STATUS = {0: "EFANNA_OK", -1: "EFANNA_EINVAL", -2: "EFANNA_EWORKSPACE", -3: "EFA
 # every symbol include/efanna.h declares
 SYMBOLS = ["efanna_status_string", "efanna_trees_workspace_bytes", "efanna_build_trees",
            "efanna_init_workspace_bytes", "efanna_init_graph", "efanna_nndescent_workspace_bytes",
-           "efanna_nndescent", "efanna_get_graph", "efanna_set_graph", "efanna_pair_distances"]
+           "efanna_nndescent", "efanna_get_graph", "efanna_set_graph", "efanna_pair_distances",
+           "efanna_search_workspace_bytes", "efanna_search"]
 
 
 class EfannaError(RuntimeError):
@@ -62,6 +63,11 @@ def lib():
         L.efanna_set_graph.argtypes = [vp, i64, i32, vp, vp, vp, vp]
         L.efanna_pair_distances.restype = C.c_int
         L.efanna_pair_distances.argtypes = [vp, i64, i32, vp, vp, i64, vp, vp]
+        L.efanna_search_workspace_bytes.restype = sz
+        L.efanna_search_workspace_bytes.argtypes = [i64, i32, i32, i32, i32, i32, i32, i32]
+        L.efanna_search.restype = C.c_int
+        L.efanna_search.argtypes = [vp, i64, i32, vp, vp, i32, vp, vp, i32, i32, i32, vp, i32, vp, i64,
+                                    i32, i32, i32, i32, vp, vp, vp, vp, sz, vp]
         _lib = L
     return _lib
 
@@ -223,3 +229,34 @@ def efanna_pair_distances(X: torch.Tensor, a_ids: torch.Tensor, b_ids: torch.Ten
                                        b_ids.data_ptr(), a_ids.shape[0], out.data_ptr(), _stream()),
            "efanna_pair_distances")
     return out
+
+
+def efanna_search(X: torch.Tensor, perm: torch.Tensor, leaf_off: torch.Tensor, n_leaves: np.ndarray,
+                  nodes: torch.Tensor, tree_depth: int, leaf_size: int, graph_ids: torch.Tensor,
+                  queries: torch.Tensor, k: int, pool: int, expand: int, iters: int,
+                  workspace: torch.Tensor | None = None):
+    """Alg. 1 for a batch of queries.  Returns (ids [nq,k] int32, dists [nq,k] float32,
+    checked [nq] int32: distances evaluated per query).  Synchronises the current stream."""
+    X = _dev(X, torch.float32)
+    Q = _dev(queries, torch.float32)
+    n, d = X.shape
+    nq = Q.shape[0]
+    perm = _dev(perm, torch.int32)
+    leaf_off = _dev(leaf_off, torch.int32)
+    nodes = _dev(nodes, torch.uint8)
+    g = _dev(graph_ids, torch.int32)
+    T = perm.shape[0]
+    n_leaves = np.ascontiguousarray(n_leaves, dtype=np.int32)
+    if Q.shape[1] != d or g.shape[0] != n or nodes.shape != (T, leaf_off.shape[1], NODE_BYTES):
+        raise ValueError("shapes of queries / graph / nodes do not match")
+    ids = torch.empty((nq, k), dtype=torch.int32, device=X.device)
+    dists = torch.empty((nq, k), dtype=torch.float32, device=X.device)
+    checked = torch.empty((nq,), dtype=torch.int32, device=X.device)
+    need = lib().efanna_search_workspace_bytes(nq, d, T, leaf_size, tree_depth, g.shape[1], pool, iters)
+    ws = _workspace(need, X.device) if workspace is None else workspace
+    _check(lib().efanna_search(X.data_ptr(), n, d, perm.data_ptr(), leaf_off.data_ptr(),
+                               leaf_off.shape[1] - 1, n_leaves.ctypes.data_as(C.c_void_p),
+                               nodes.data_ptr(), int(tree_depth), T, leaf_size, g.data_ptr(), g.shape[1],
+                               Q.data_ptr(), nq, k, pool, expand, iters, ids.data_ptr(), dists.data_ptr(),
+                               checked.data_ptr(), ws.data_ptr(), ws.numel(), _stream()), "efanna_search")
+    return ids, dists, checked

@@ -286,6 +286,63 @@ def test_early_termination_and_larger_pools(ef):
     assert oracle.recall(ids[:, :K], tid) > 0.85          # the K closest of the P kept
 
 
+def build_index(ef, X, T, S, K, iters, seed=synth.ALGO_SEED):
+    g, o = tree_nodes_equal(ef, X, T, S, seed)
+    Xd = dev(X)
+    graph = ef.efanna_init_graph(Xd, g[0], g[1], g[2], S, K)
+    if iters:
+        ef.efanna_nndescent(Xd, graph, iters, K, seed)
+    ids, _ = ef.efanna_get_graph(graph)
+    og = oracle.init_graph(X, o[0], o[1], o[2], K)
+    if iters:
+        og = oracle.nndescent(X, *og, iters, K, seed)
+    assert np.array_equal(host(ids), og[0])
+    return Xd, g, o, ids
+
+
+@pytest.mark.parametrize("name,n,T,S,K,P,E,I", [
+    ("gmm10k_d32", 6_000, 4, 8, 10, 60, 20, 4),
+    ("sift100k_like", 8_000, 4, 16, 20, 200, 50, 3),     # integer data: ties by id
+    ("gmm10k_d32", 3_000, 3, 8, 10, 40, 40, 0),          # the trees alone
+    ("gmm10k_d32", 2_000, 2, 4, 6, 7, 3, 6),             # one leaf per tree, a pool of 7 that keeps moving
+])
+def test_search_bit_exact(ef, name, n, T, S, K, P, E, I):
+    X = synth.generate(name, n=n)
+    Xd, g, o, ids = build_index(ef, X, T, S, K, 3)
+    rng = np.random.default_rng(n + P)
+    Q = (X[rng.choice(n, 300)] + rng.standard_normal((300, X.shape[1])) * np.float32(0.5)).astype(np.float32)
+    Q[:20] = X[rng.choice(n, 20)]                          # some queries are data points
+    kq = min(K, P)
+    got = ef.efanna_search(Xd, g[0], g[1], g[2], g[3], g[5], S, ids, dev(Q), kq, P, E, I)
+    want = oracle.search(X, o[0], o[1], o[2], o[3], S, host(ids), Q, kq, P, E, I)
+    assert np.array_equal(host(got[0]), want[0])
+    assert host(got[1]).tobytes() == want[1].tobytes()
+    assert np.array_equal(host(got[2]), want[2])
+
+
+def test_search_edge_cases(ef):
+    rng = np.random.default_rng(4)
+    X = rng.standard_normal((50, 8)).astype(np.float32)            # every tree a single leaf
+    Xd, g, o, ids = build_index(ef, X, 2, 64, 5, 0)
+    Q = rng.standard_normal((7, 8)).astype(np.float32)
+    got = ef.efanna_search(Xd, g[0], g[1], g[2], g[3], g[5], 64, ids, dev(Q), 5, 50, 50, 1)
+    want = oracle.search(X, o[0], o[1], o[2], o[3], 64, host(ids), Q, 5, 50, 50, 1)
+    assert np.array_equal(host(got[0]), want[0]) and host(got[1]).tobytes() == want[1].tobytes()
+    tid, _ = oracle.exact_knn_definition(np.vstack([X, Q[:1]]), 5)   # brute force for the first query
+    d2 = ((X.astype(np.float64) - Q[0].astype(np.float64)) ** 2).sum(1)
+    assert list(host(got[0])[0]) == list(np.lexsort((np.arange(50), d2))[:5])
+    # rows of the graph with empty slots, k larger than what can be found
+    X = synth.generate("gmm10k_d32", n=1_003)
+    Xd, g, o, ids = build_index(ef, X, 2, 3, 16, 0)
+    Q = X[:40] + np.float32(0.01)
+    got = ef.efanna_search(Xd, g[0], g[1], g[2], g[3], g[5], 3, ids, dev(Q), 16, 16, 4, 2)
+    want = oracle.search(X, o[0], o[1], o[2], o[3], 3, host(ids), Q, 16, 16, 4, 2)
+    assert np.array_equal(host(got[0]), want[0]) and np.array_equal(host(got[2]), want[2])
+    with pytest.raises(ef.EfannaError) as e:                        # pool below k
+        ef.efanna_search(Xd, g[0], g[1], g[2], g[3], g[5], 3, ids, dev(Q), 16, 8, 4, 2)
+    assert e.value.status == -1
+
+
 def test_set_get_roundtrip_and_random_start(ef):
     rng = np.random.default_rng(8)
     n, K = 3000, 10
