@@ -57,6 +57,12 @@ def main():
     ap.add_argument("--calibrate", action="store_true",
                     help="after the timed steps, fill and copy 256 MiB with plain torch kernels: a known "
                          "amount of HBM traffic to scale rocprofv3's FETCH_SIZE / WRITE_SIZE counters by")
+    ap.add_argument("--search", type=int, default=0, metavar="NQ",
+                    help="after the build, answer NQ synthetic queries with the index (Alg. 1) and add a "
+                         "`search` object to the line: queries per second, recall against brute force")
+    ap.add_argument("--search-pool", type=int, default=200, help="candidate pool size P of the search")
+    ap.add_argument("--search-expand", type=int, default=50, help="expansion factor E of the search")
+    ap.add_argument("--search-iters", type=int, default=4, help="NN-expansion rounds I of the search")
     ap.add_argument("--conquer-depth", type=int, default=None,
                     help="walk the conquer step of Alg. 3 up to this depth (default: stop at the leaves, "
                          "the configuration the metric is quoted on); distance evaluations above the "
@@ -188,6 +194,35 @@ def main():
                "sample": f"whole path (trees, leaf init, {I} NN-descent iterations) on the first "
                          f"{m} rows of {name}"}
 
+    search = None
+    if args.search > 0:
+        # the index of the last step, with the trees built once more to get their nodes
+        Q = torch.from_numpy(synth.generate_queries(name, args.search)).to(dev)
+        trees = efanna.efanna_build_trees(Xd, T, S, synth.ALGO_SEED, max_leaves=max_leaves, with_nodes=True)
+        gids = state["ids"]
+        for _ in range(2):      # the first call warms up
+            torch.cuda.synchronize()
+            s0 = time.perf_counter()
+            sid, sdist, schk = efanna.efanna_search(Xd, trees[0], trees[1], trees[2], trees[3], trees[5], S,
+                                                    gids, Q, K, args.search_pool, args.search_expand,
+                                                    args.search_iters)
+            torch.cuda.synchronize()
+            s_sec = time.perf_counter() - s0
+        truth_q = []
+        Q64, X64 = Q.double(), Xd.double()
+        xn = (X64 * X64).sum(1)
+        for r0 in range(0, args.search, 250):
+            G = Q64[r0:r0 + 250] @ X64.T
+            G.mul_(-2.0).add_(xn[None, :])
+            truth_q.append(torch.topk(G, K, dim=1, largest=False).indices)
+        truth_q = torch.cat(truth_q).cpu().numpy()
+        got_q = sid.cpu().numpy()
+        hits_q = sum(np.intersect1d(a[a >= 0], b).shape[0] for a, b in zip(got_q, truth_q))
+        search = {"queries": args.search, "queries_per_s": args.search / s_sec, "ms": s_sec * 1e3,
+                  "recall_at_K": hits_q / float(truth_q.size), "K": K, "pool": args.search_pool,
+                  "expand": args.search_expand, "iters": args.search_iters,
+                  "mean_points_checked": float(schk.float().mean().item())}
+
     achieved = k_bytes_sum / 1e9 / (k_ms_sum / 1e3) if k_ms_sum > 0 else 0.0
     achieved_all = all_bytes_sum / 1e9 / (all_ms_sum / 1e3) if all_ms_sum > 0 else 0.0
     out = {
@@ -226,6 +261,8 @@ def main():
                                           "ms_per_step": all_ms_sum / max(1, args.steps)}},
         "cpu_baseline": cpu,
     }
+    if search is not None:
+        out["search"] = search
     print(json.dumps(out))
 
 

@@ -86,6 +86,34 @@ def generate(name: str, n: int | None = None, out: np.ndarray | None = None) -> 
     return X
 
 
+def generate_queries(name: str, nq: int, query_seed: int = 0) -> np.ndarray:
+    """(nq, d) float32 query vectors for workload `name`: fresh draws from the same mixture
+    (the centres of `generate`, components and noise from a generator of their own seeded
+    with data_seed + 7919 * (query_seed + 1)), so they follow the data's distribution without
+    being data points."""
+    w = WORKLOADS[name]
+    d, n_comp = w["d"], w["n_comp"]
+    rng = np.random.Generator(np.random.PCG64(w["data_seed"]))
+    centres = (w["lo"] + (w["hi"] - w["lo"]) * rng.random((n_comp, d))).astype(np.float32)
+    rq = np.random.Generator(np.random.PCG64(w["data_seed"] + 7919 * (query_seed + 1)))
+    comp = rq.integers(0, n_comp, size=nq)
+    coin = rq.random(nq) < 0.5 if w["kind"] == "mixed" else None
+    x = rq.standard_normal((nq, d), dtype=np.float32)
+    x *= np.float32(w["sigma"])
+    x += centres[comp]
+    if w["kind"] == "u8grid":
+        np.clip(x, 0.0, 255.0, out=x)
+        np.rint(x, out=x)
+    elif w["kind"] == "unit":
+        np.clip(x, 0.0, 1.0, out=x)
+    elif w["kind"] == "mixed":
+        u = rq.random((nq, d), dtype=np.float32)
+        u *= np.float32(2.0)
+        u -= np.float32(1.0)
+        x[coin] = u[coin]
+    return x
+
+
 def sample_rows(n: int, m: int = 10_000, seed: int = SAMPLE_SEED) -> np.ndarray:
     """First m entries of a seeded permutation of range(n): the rows on which
     recall is measured when exact brute force over all rows is too slow."""
