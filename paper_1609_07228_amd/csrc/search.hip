@@ -240,6 +240,8 @@ search_kernel(const float *__restrict__ X, int d, int n, const int *__restrict__
                     key = ef_pack(lane_distance(q, X + (size_t)id * d, d), id, 1);
             }
             checked += __popcll(__ballot(key != ~0ULL));
+            if (count == E && key >= cur[E - 1]) key = ~0ULL;      // a full pool takes nothing beyond its last key
+            if (__ballot(key != ~0ULL) == 0) continue;
             count = pool_merge(cur, nxt, count, E, key, batch);
             u64 *tmp = cur;
             cur = nxt;
@@ -273,6 +275,8 @@ search_kernel(const float *__restrict__ X, int d, int n, const int *__restrict__
                         key = ef_pack(lane_distance(q, X + (size_t)id * d, d), id, 1);
                 }
                 checked += __popcll(__ballot(key != ~0ULL));
+                if (count == P && key >= cur[P - 1]) key = ~0ULL;      // a full pool takes nothing beyond its last key
+                if (__ballot(key != ~0ULL) == 0) continue;
                 count = pool_merge(cur, nxt, count, P, key, batch);
                 u64 *tmp = cur;
                 cur = nxt;
