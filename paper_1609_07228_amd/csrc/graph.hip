@@ -1139,6 +1139,36 @@ __device__ constexpr int kSurvBase[3] = {0, 120, 376};
 // d > 128: up to this many surviving pairs of a Gram block (per 16 rows) are read pair by pair
 constexpr int kFewPairs = 4;
 
+// Number of set bits of a ballot below the calling lane.
+__device__ inline int lanes_below(u64 ballot)
+{
+    return (int)__builtin_amdgcn_mbcnt_hi((u32)(ballot >> 32), __builtin_amdgcn_mbcnt_lo((u32)ballot, 0u));
+}
+
+// One surviving pair (rows a, b of the point's list) per lane with `mine` set: its distance is
+// offered to row a and to row b where it passes their thresholds.  All lanes of the wave call
+// this together; `fill` is the wave-uniform number of proposals queued, the new one is returned.
+__device__ inline int propose_pair(Proposal *queue, int fill, bool mine, float dist, int a, int b,
+                                   const u32 *thr, const int *uid)
+{
+    const u32 db = __float_as_uint(dist);
+    const int ua = uid[a], ub = uid[b];
+    const bool to_a = mine && db <= thr[a], to_b = mine && db <= thr[b];
+    const u64 mask_a = __ballot(to_a), mask_b = __ballot(to_b);
+    if (to_a) {
+        Proposal &p = queue[fill + lanes_below(mask_a)];
+        p.key = ef_pack(dist, ub, 1);
+        p.target = ua;
+    }
+    fill += __popcll(mask_a);
+    if (to_b) {
+        Proposal &p = queue[fill + lanes_below(mask_b)];
+        p.key = ef_pack(dist, ua, 1);
+        p.target = ub;
+    }
+    return fill + __popcll(mask_b);
+}
+
 template <int NB, bool ONE>
 __global__ void __launch_bounds__(EF_WAVE) __attribute__((amdgpu_waves_per_eu(NB > 1 ? 3 : 4)))
 join_reg_kernel(const float *__restrict__ X, const float *__restrict__ norms, int d, int K,
@@ -1154,8 +1184,7 @@ join_reg_kernel(const float *__restrict__ X, const float *__restrict__ norms, in
     u32 *thr = (u32 *)(uid + R);                  // [R] threshold bits (exact test)
     float *nf = (float *)(thr + R);               // [R] |x|^2 (1 - margin)   } the filter's
     float *tf = nf + R;                           // [R] threshold * scale    } operands
-    int *meta = (int *)(tf + R);                  // [8]: [3] queue count [4..6] survivors per block
-    u32 *surv = (u32 *)(meta + 8);                // [S_CAP] surviving pairs
+    u32 *surv = (u32 *)(tf + R);                  // [S_CAP] surviving pairs
     Proposal *queue = (Proposal *)(surv + align4(S_CAP));   // [q_cap]
     const int lane = threadIdx.x, r16 = lane & 15, g = lane >> 4, gl = r16, grp = g;
     const int count = *work_count;
@@ -1174,8 +1203,9 @@ join_reg_kernel(const float *__restrict__ X, const float *__restrict__ norms, in
     // Proposals wait in the queue across points and are applied when about half of it is
     // full (and at the end): late iterations accept well under one proposal per point, and
     // a drain costs two memory round trips whatever its size.
-    int updates = 0;
-    if (lane == 0) meta[3] = 0;
+    // The block is one wave: the fill of the queue and of the survivor lists are wave-uniform
+    // registers, and a lane finds its slot from a ballot (no LDS counters, no round trips).
+    int updates = 0, q_fill = 0;
     for (; i >= 0; w += gridDim.x) {
         // ---- 0. the point's U_new ++ U_old (the loop ends with a barrier: LDS is free) -------
         const int m_new = c_pre.x, m = c_pre.y;
@@ -1186,7 +1216,6 @@ join_reg_kernel(const float *__restrict__ X, const float *__restrict__ norms, in
             tf[lane] = __uint_as_float(t_pre) * thr_scale;
             nf[lane] = n_pre * (1.0f - margin_rel);
         }
-        if (lane < 8 && lane != 3) meta[lane] = 0;
         i = i_next;
         u_pre = i >= 0 && lane < R ? ulist[(size_t)i * ucap + min(lane, ucap - 1)] : -1;
         c_pre = i >= 0 ? ucount[i] : make_int2(0, 0);
@@ -1247,8 +1276,10 @@ join_reg_kernel(const float *__restrict__ X, const float *__restrict__ norms, in
         n_pre = u_pre >= 0 ? norms[u_pre] : 0.0f;
         // ---- filter: lane holds G[a = 16 bi + 4 g + k][b = 16 bj + r16] of block q -----------
         // pair (a, b) survives if (|a|^2 + |b|^2)(1 - margin) - 2 a.b <= max threshold * scale
+        int n_surv[NQ];
 #pragma unroll
         for (int q = 0; q < (NB > 1 ? 3 : 1); ++q) {
+            n_surv[q] = 0;
             const int bi = q == 2 ? 1 : 0, bj = q == 0 ? 0 : 1;
             const int b = 16 * bj + r16, a0 = 16 * bi + 4 * g;
             const int lim = b < m ? min(m_new, b) : 0;           // valid pairs: a < lim
@@ -1259,10 +1290,11 @@ join_reg_kernel(const float *__restrict__ X, const float *__restrict__ norms, in
 #pragma unroll
             for (int k = 0; k < 4; ++k) {
                 const float lhs = __builtin_fmaf(-2.0f, acc[q][0][k] + acc[q][1][k], nfa_k[k] + nfb);
-                if (a0 + k < lim && lhs <= fmaxf(tfa_k[k], tfb)) {
-                    // one list per Gram block, entries are rows local to the block
-                    surv[kSurvBase[q] + atomicAdd(&meta[4 + q], 1)] = (u32)((a0 + k) & 15) | ((u32)(b & 15) << 8);
-                }
+                // one list per Gram block, entries are rows local to the block
+                const bool keep = a0 + k < lim && lhs <= fmaxf(tfa_k[k], tfb);
+                const u64 kept = __ballot(keep);
+                if (keep) surv[kSurvBase[q] + n_surv[q] + lanes_below(kept)] = (u32)((a0 + k) & 15) | ((u32)(b & 15) << 8);
+                n_surv[q] += __popcll(kept);
             }
         }
         __syncthreads();
@@ -1274,7 +1306,7 @@ join_reg_kernel(const float *__restrict__ X, const float *__restrict__ norms, in
 #pragma unroll
             for (int q = 0; q < (NB > 1 ? 3 : 1); ++q) {
                 const int bi = q == 2 ? 1 : 0, bj = q == 0 ? 0 : 1;
-                const int n_q = meta[4 + q];
+                const int n_q = n_surv[q];
                 for (int p0 = 0; p0 < n_q; p0 += 16) {
                     const bool has = p0 + r16 < n_q;
                     const u32 ent = surv[kSurvBase[q] + min(p0 + r16, n_q - 1)];
@@ -1306,27 +1338,13 @@ join_reg_kernel(const float *__restrict__ X, const float *__restrict__ norms, in
                     p2s += __shfl_xor(p2s, 16, EF_WAVE);
                     p3s += __shfl_xor(p3s, 16, EF_WAVE);
                     const float dist = (p0s + p2s) + (p1s + p3s);
-                    if (has && g == 0) {
-                        const int a = 16 * bi + al, b = 16 * bj + bl;
-                        const u32 db = __float_as_uint(dist);
-                        if (db <= thr[a]) {
-                            const int slot = atomicAdd(&meta[3], 1);
-                            queue[slot].key = ef_pack(dist, uid[b], 1);
-                            queue[slot].target = uid[a];
-                        }
-                        if (db <= thr[b]) {
-                            const int slot = atomicAdd(&meta[3], 1);
-                            queue[slot].key = ef_pack(dist, uid[a], 1);
-                            queue[slot].target = uid[b];
-                        }
-                    }
+                    q_fill = propose_pair(queue, q_fill, has && g == 0, dist, 16 * bi + al, 16 * bj + bl, thr, uid);
                     __syncthreads();
                     // NB = 1: the queue is sized so that a point's proposals always fit (at most 240
                     // on top of fewer than q_cap / 2): no drain while the operands are live
-                    if (NB > 1 && meta[3] + 32 > q_cap) {      // a round adds at most two proposals per pair
-                        updates += drain_queue(queue, meta[3], graph, worst, K, lane, EF_WAVE);
-                        __syncthreads();
-                        if (lane == 0) meta[3] = 0;
+                    if (NB > 1 && q_fill + 32 > q_cap) {      // a round adds at most two proposals per pair
+                        updates += drain_queue(queue, q_fill, graph, worst, K, lane, EF_WAVE);
+                        q_fill = 0;
                         __syncthreads();
                     }
                 }
@@ -1338,7 +1356,7 @@ join_reg_kernel(const float *__restrict__ X, const float *__restrict__ norms, in
 #pragma unroll
             for (int q = 0; q < (NB > 1 ? 3 : 1); ++q) {
                 const int bi = q == 2 ? 1 : 0, bj = q == 0 ? 0 : 1;
-                const int n_q = meta[4 + q];
+                const int n_q = n_surv[q];
                 // a few pairs: cheaper to read just their rows, one 16-lane group per pair
                 const int n_few = n_q <= kFewPairs * NB ? n_q : 0;
                 for (int p0 = 0; p0 < n_few; p0 += 4) {
@@ -1361,24 +1379,11 @@ join_reg_kernel(const float *__restrict__ X, const float *__restrict__ norms, in
                         }
                     }
                     const float dist = ef_group_reduce16(accd);
-                    if (gl == 0 && p0 + grp < n_few) {
-                        const u32 db = __float_as_uint(dist);
-                        if (db <= thr[a]) {
-                            const int slot = atomicAdd(&meta[3], 1);
-                            queue[slot].key = ef_pack(dist, uid[b], 1);
-                            queue[slot].target = uid[a];
-                        }
-                        if (db <= thr[b]) {
-                            const int slot = atomicAdd(&meta[3], 1);
-                            queue[slot].key = ef_pack(dist, uid[a], 1);
-                            queue[slot].target = uid[b];
-                        }
-                    }
+                    q_fill = propose_pair(queue, q_fill, gl == 0 && p0 + grp < n_few, dist, a, b, thr, uid);
                     __syncthreads();
-                    if (meta[3] + 32 > q_cap) {
-                        updates += drain_queue(queue, meta[3], graph, worst, K, lane, EF_WAVE);
-                        __syncthreads();
-                        if (lane == 0) meta[3] = 0;
+                    if (q_fill + 32 > q_cap) {
+                        updates += drain_queue(queue, q_fill, graph, worst, K, lane, EF_WAVE);
+                        q_fill = 0;
                         __syncthreads();
                     }
                 }
@@ -1431,41 +1436,27 @@ join_reg_kernel(const float *__restrict__ X, const float *__restrict__ norms, in
                         p3s += __shfl_xor(p3s, 16, EF_WAVE);
                         const float dist = (p0s + p2s) + (p1s + p3s);
                         const int pidx = g0 + 16 * r + r16;
-                        if (pidx < n_q && g == 0) {
-                            const u32 ent = surv[kSurvBase[q] + pidx];
-                            const int a = 16 * bi + (int)(ent & 15), b = 16 * bj + (int)((ent >> 8) & 15);
-                            const u32 db = __float_as_uint(dist);
-                            if (db <= thr[a]) {
-                                const int slot = atomicAdd(&meta[3], 1);
-                                queue[slot].key = ef_pack(dist, uid[b], 1);
-                                queue[slot].target = uid[a];
-                            }
-                            if (db <= thr[b]) {
-                                const int slot = atomicAdd(&meta[3], 1);
-                                queue[slot].key = ef_pack(dist, uid[a], 1);
-                                queue[slot].target = uid[b];
-                            }
-                        }
+                        const u32 ent = surv[kSurvBase[q] + min(pidx, n_q - 1)];
+                        q_fill = propose_pair(queue, q_fill, pidx < n_q && g == 0, dist, 16 * bi + (int)(ent & 15),
+                                              16 * bj + (int)((ent >> 8) & 15), thr, uid);
                         __syncthreads();
-                        if (meta[3] + 32 > q_cap) {      // a round adds at most two proposals per pair
-                            updates += drain_queue(queue, meta[3], graph, worst, K, lane, EF_WAVE);
-                            __syncthreads();
-                            if (lane == 0) meta[3] = 0;
+                        if (q_fill + 32 > q_cap) {      // a round adds at most two proposals per pair
+                            updates += drain_queue(queue, q_fill, graph, worst, K, lane, EF_WAVE);
+                            q_fill = 0;
                             __syncthreads();
                         }
                     }
                 }
             }
         }
-        if (meta[3] >= q_cap / 2) {
-            updates += drain_queue(queue, meta[3], graph, worst, K, lane, EF_WAVE);
-            __syncthreads();
-            if (lane == 0) meta[3] = 0;
+        if (q_fill >= q_cap / 2) {
+            updates += drain_queue(queue, q_fill, graph, worst, K, lane, EF_WAVE);
+            q_fill = 0;
         }
         __syncthreads();
     }
     __syncthreads();
-    updates += drain_queue(queue, meta[3], graph, worst, K, lane, EF_WAVE);
+    updates += drain_queue(queue, q_fill, graph, worst, K, lane, EF_WAVE);
     updates = ef_wave_sum_i32(updates);
     if (lane == 0) upd_block[blockIdx.x] = updates;
 }
@@ -1811,7 +1802,7 @@ extern "C" int efanna_nndescent(const float *X, int64_t n, int32_t d, int32_t k,
     auto reg_q_cap_for = [&](int R) { return R == 16 && d <= 128 ? 512 : 128; };
     auto reg_lds = [&](int R) {
         const int reg_q_cap = reg_q_cap_for(R);
-        return (size_t)(4 * R + 8 + align4(R * (R - 1) / 2 + 8)) * 4 +
+        return (size_t)(4 * R + align4(R * (R - 1) / 2 + 8)) * 4 +
                (size_t)reg_q_cap * sizeof(Proposal);
     };
     const int reg_grid = kRegGrid;
