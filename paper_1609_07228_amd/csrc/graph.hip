@@ -25,15 +25,19 @@ __host__ __device__ inline int align4(int x) { return (x + 3) & ~3; }
 // ---------------------------------------------------------------------------------------
 // fills
 
+// number of overflow queues of the reverse lists, and ints between their counters
+constexpr int kOvfQueues = 256, kOvfCounterPitch = 16;
+
 // per-iteration reset: reverse-list fill counts and bounds, work-list sizes, insertion
 // counts of the join blocks.  The lists themselves need no reset: the first L arrivals
 // overwrite slots 0..L-1 in some order, readers stop at min(count, L), and the bounded
 // insertion only ever touches lists that are full.
 __global__ void fill_reverse_kernel(int *a_count, int *b_count, u64 *list_max, size_t n,
-                                    int *work_count, int *upd_block, int n_upd_block)
+                                    int *work_count, int *upd_block, int n_upd_block, int *ovf_count)
 {
     size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (i < 8) work_count[i] = 0;     // three work lists
+    for (size_t j = i; j < (size_t)kOvfQueues * kOvfCounterPitch; j += (size_t)gridDim.x * blockDim.x) ovf_count[j] = 0;
     // insertion counts of join blocks: kernels that are not launched leave theirs at zero
     for (size_t j = i; j < (size_t)n_upd_block; j += (size_t)gridDim.x * blockDim.x) upd_block[j] = 0;
     if (i < n) {
@@ -656,6 +660,40 @@ struct Overflow {
     int which;    // 0: reverse-new, 1: reverse-old
 };
 
+// Number of set bits of a ballot below the calling lane.
+__device__ inline int lanes_below(u64 ballot)
+{
+    return (int)__builtin_amdgcn_mbcnt_hi((u32)(ballot >> 32), __builtin_amdgcn_mbcnt_lo((u32)ballot, 0u));
+}
+
+// Parked keys go to kOvfQueues dense queues, block b of the sampling kernels to queue
+// b % kOvfQueues: a wave bumps its queue's counter once for all the keys it parks (bumps of one
+// address serialise, so the counters are many and a cache line apart), and
+// reverse_overflow_kernel gets one thread per parked key instead of a sweep over all rows.
+// A row parks at most K keys, so a queue holds at most (blocks per queue) x (rows per block) x K.
+
+__host__ __device__ inline int sample_group_for(int K) { return K <= 16 ? 16 : (K <= 32 ? 32 : 64); }
+
+__host__ __device__ inline size_t ovf_region_for(int64_t n, int K)
+{
+    const int G = sample_group_for(K);
+    const size_t blocks = ((size_t)n * G + kBlock - 1) / kBlock;
+    return (blocks + kOvfQueues - 1) / kOvfQueues * (size_t)(kBlock / G) * K;
+}
+
+// All lanes of the wave call this together; lanes with `parked` set file `o`.
+__device__ inline void park_keys(bool parked, const Overflow &o, Overflow *overflow, size_t region,
+                                 int *ovf_count)
+{
+    const u64 mask = __ballot(parked);
+    if (mask == 0) return;
+    const int q = blockIdx.x % kOvfQueues, leader = __ffsll((unsigned long long)mask) - 1;
+    int base = 0;
+    if (ef_lane() == leader) base = atomicAdd(ovf_count + q * kOvfCounterPitch, __popcll(mask));
+    base = __shfl(base, leader, EF_WAVE);
+    if (parked) overflow[(size_t)q * region + base + lanes_below(mask)] = o;
+}
+
 // Offer `key` to reverse list v.  Returns true if the list had no free slot: the caller
 // parks the key for reverse_overflow_kernel.  Every offer bumps the list's counter, full or
 // not: a read beforehand to spare full lists the bump costs more transactions than it saves
@@ -673,7 +711,7 @@ template <int G, int E>
 __global__ void __launch_bounds__(kBlock)
 sample_kernel(u64 *graph, int n, int K, int L, u64 key_new, int *__restrict__ nw,
               int *__restrict__ od, int *__restrict__ nw_c, int *__restrict__ od_c, u64 *rnew,
-              int *rnew_c, Overflow *overflow, int *overflow_rows, u32 *worst)
+              int *rnew_c, Overflow *overflow, size_t ovf_region, int *ovf_count, u32 *worst)
 {
     const int gl = threadIdx.x & (G - 1);
     const int i = (int)(((size_t)blockIdx.x * kBlock + threadIdx.x) / G);
@@ -725,9 +763,7 @@ sample_kernel(u64 *graph, int n, int K, int L, u64 key_new, int *__restrict__ nw
     // sampled new entries lose their mark, go to the new list and are offered to the reverse-new
     // list of the neighbour; old entries only go to the old list here (reverse_old_kernel offers
     // them once it is known which points take part in a join at all)
-    int n_old = 0, n_parked = 0;     // parked keys of row i go to overflow[i*K ...], in group order
-    const int group_shift = (int)(threadIdx.x & (EF_WAVE - 1) & ~(G - 1));
-    const u64 group_bits = ~0ULL >> (64 - G);
+    int n_old = 0;
 #pragma unroll
     for (int h = 0; h < E; ++h) {
         const int slot = gl + h * G;
@@ -745,14 +781,7 @@ sample_kernel(u64 *graph, int n, int K, int L, u64 key_new, int *__restrict__ nw
             hk = (ef_mix64(key_new + (((u64)(u32)id << 32) | (u32)i)) >> 32 << 32) | (u32)i;
             parked = reverse_offer(rnew, rnew_c, L, id, hk);
         }
-        const u64 mask = (__ballot(parked) >> group_shift) & group_bits;
-        if (parked) {
-            Overflow &o = overflow[(size_t)i * K + n_parked + __popcll(mask & ((1ULL << gl) - 1))];
-            o.key = hk;
-            o.target = id;
-            o.which = 0;
-        }
-        n_parked += __popcll(mask);
+        park_keys(parked, Overflow{hk, id, 0}, overflow, ovf_region, ovf_count);
     }
     for (int m = G / 2; m >= 1; m >>= 1) n_old += __shfl_xor(n_old, m, G);
     if (!row_ok) return;
@@ -764,7 +793,6 @@ sample_kernel(u64 *graph, int n, int K, int L, u64 key_new, int *__restrict__ nw
         nw_c[i] = n_new;
         od_c[i] = n_old;
         worst[i] = wbits;
-        overflow_rows[i] = n_parked;
     }
 }
 
@@ -788,15 +816,11 @@ template <int G>
 __global__ void __launch_bounds__(kBlock)
 reverse_old_kernel(const int *__restrict__ od, int n, int K, int L, u64 key_old,
                    const u64 *__restrict__ active, u64 *rold, int *rold_c, Overflow *overflow,
-                   int *overflow_rows)
+                   size_t ovf_region, int *ovf_count)
 {
     const int gl = threadIdx.x & (G - 1);
     const int i = (int)(((size_t)blockIdx.x * kBlock + threadIdx.x) / G);
     const bool row_ok = i < n;
-    const int group_shift = (int)(threadIdx.x & (EF_WAVE - 1) & ~(G - 1));
-    const u64 group_bits = ~0ULL >> (64 - G);
-    int n_parked = row_ok ? overflow_rows[i] : 0;
-    const int first = n_parked;
     for (int s0 = 0; s0 < K; s0 += G) {
         const int slot = s0 + gl;
         const int id = row_ok && slot < K ? od[(size_t)i * K + slot] : -1;
@@ -806,32 +830,24 @@ reverse_old_kernel(const int *__restrict__ od, int n, int K, int L, u64 key_old,
             hk = (ef_mix64(key_old + (((u64)(u32)id << 32) | (u32)i)) >> 32 << 32) | (u32)i;
             parked = reverse_offer(rold, rold_c, L, id, hk);
         }
-        const u64 mask = (__ballot(parked) >> group_shift) & group_bits;
-        if (parked) {
-            Overflow &o = overflow[(size_t)i * K + n_parked + __popcll(mask & ((1ULL << gl) - 1))];
-            o.key = hk;
-            o.target = id;
-            o.which = 1;
-        }
-        n_parked += __popcll(mask);
+        park_keys(parked, Overflow{hk, id, 1}, overflow, ovf_region, ovf_count);
     }
-    if (row_ok && gl == 0 && n_parked != first) overflow_rows[i] = n_parked;
 }
 
-// Four threads per row: thread t serves parked keys t % 4, t % 4 + 4, ... of row t / 4 (most
-// rows park fewer than four keys).  list_max[which][v] is an upper bound of the largest key of
-// (full) list v, lowered after every successful insertion: the many keys offered to a popular
-// point are turned away after one read instead of a scan of the list.
-__global__ void reverse_overflow_kernel(const Overflow *__restrict__ overflow,
-                                        const int *__restrict__ overflow_rows, int n, int K,
-                                        u64 *rnew, u64 *rold, u64 *list_max, int L)
+// One thread per parked key (queue blockIdx.y, blocks of a queue stride over its keys).
+// list_max[which][v] is an upper bound of the largest key of (full) list v, lowered after
+// every successful insertion: the many keys offered to a popular point are turned away after
+// one read instead of a scan of the list.
+constexpr int kOvfBlocksPerQueue = 16;
+
+__global__ void __launch_bounds__(kBlock)
+reverse_overflow_kernel(const Overflow *__restrict__ overflow, size_t ovf_region,
+                        const int *__restrict__ ovf_count, size_t n, u64 *rnew, u64 *rold,
+                        u64 *list_max, int L)
 {
-    const size_t t = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
-    const size_t i = t >> 2;
-    if (i >= (size_t)n) return;
-    const int parked = overflow_rows[i];
-    for (int j = (int)(t & 3); j < parked; j += 4) {
-        const Overflow ov = overflow[i * K + j];
+    const int q = blockIdx.y, parked = ovf_count[q * kOvfCounterPitch];
+    for (int e = blockIdx.x * kBlock + threadIdx.x; e < parked; e += kOvfBlocksPerQueue * kBlock) {
+        const Overflow ov = overflow[(size_t)q * ovf_region + e];
         u64 *bound = list_max + (size_t)ov.which * n + ov.target;
         if (ov.key >= ef_load_coherent(bound)) continue;
         u64 nm;
@@ -1138,12 +1154,6 @@ __global__ void join_kernel(const float *__restrict__ X, const float *__restrict
 __device__ constexpr int kSurvBase[3] = {0, 120, 376};
 // d > 128: up to this many surviving pairs of a Gram block (per 16 rows) are read pair by pair
 constexpr int kFewPairs = 4;
-
-// Number of set bits of a ballot below the calling lane.
-__device__ inline int lanes_below(u64 ballot)
-{
-    return (int)__builtin_amdgcn_mbcnt_hi((u32)(ballot >> 32), __builtin_amdgcn_mbcnt_lo((u32)ballot, 0u));
-}
 
 // One surviving pair (rows a, b of the point's list) per lane with `mine` set: its distance is
 // offered to row a and to row b where it passes their thresholds.  All lanes of the wave call
@@ -1591,7 +1601,7 @@ __global__ void pair_distances_kernel(const float *__restrict__ X, int d,
 }
 
 struct NndWs {
-    int *nw, *od, *nw_c, *od_c, *work, *work_count, *rnew_c, *rold_c, *overflow_rows, *ulist, *upd_block;
+    int *nw, *od, *nw_c, *od_c, *work, *work_count, *rnew_c, *rold_c, *ovf_count, *ulist, *upd_block;
     int2 *ucount;
     void *overflow;
     u64 *rnew, *rold, *list_max, *active, *fresh;
@@ -1620,8 +1630,8 @@ NndWs carve_nnd(void *ws, int64_t n, int K, int L)
     w.work_count = (int *)take(8 * 4);     // [0..2] list sizes
     w.rnew_c = (int *)take((size_t)n * 4);
     w.rold_c = (int *)take((size_t)n * 4);
-    w.overflow = take((size_t)n * K * 16);
-    w.overflow_rows = (int *)take((size_t)n * 4);
+    w.overflow = take(ovf_region_for(n, K) * kOvfQueues * sizeof(Overflow));
+    w.ovf_count = (int *)take((size_t)kOvfQueues * kOvfCounterPitch * 4);
     w.ulist = (int *)take((size_t)n * (K + 2 * L) * 4);
     w.ucount = (int2 *)take((size_t)n * 8);
     w.upd_block = (int *)take((size_t)(2 * kRegGrid + kMaxLargeGrid) * 4);
@@ -1833,17 +1843,18 @@ extern "C" int efanna_nndescent(const float *X, int64_t n, int32_t d, int32_t k,
         if (ev) EF_HIP_CHECK(hipEventRecord(ev[5 * it], st));
         fill_reverse_kernel<<<grid_for((size_t)n, kBlock), kBlock, 0, st>>>(
             w.rnew_c, w.rold_c, w.list_max, (size_t)n, w.work_count, w.upd_block,
-            2 * kRegGrid + kMaxLargeGrid);
+            2 * kRegGrid + kMaxLargeGrid, w.ovf_count);
         {
             const u64 kn = ef_stream_key(seed, 2 * g), ko = ef_stream_key(seed, 2 * g + 1);
             Overflow *ovf = (Overflow *)w.overflow;
+            const size_t ovf_region = ovf_region_for(n, K);
 #define EF_SAMPLE(G, E)                                                                          \
     sample_kernel<G, E><<<grid_for((size_t)n * G, kBlock), kBlock, 0, st>>>(                     \
         graph, (int)n, K, L, kn, w.nw, w.od, w.nw_c, w.od_c, w.rnew, w.rnew_c, ovf,              \
-        w.overflow_rows, w.worst)
+        ovf_region, w.ovf_count, w.worst)
 #define EF_REVERSE_OLD(G)                                                                        \
     reverse_old_kernel<G><<<grid_for((size_t)n * G, kBlock), kBlock, 0, st>>>(                   \
-        w.od, (int)n, K, L, ko, w.active, w.rold, w.rold_c, ovf, w.overflow_rows)
+        w.od, (int)n, K, L, ko, w.active, w.rold, w.rold_c, ovf, ovf_region, w.ovf_count)
             if (K <= 16) EF_SAMPLE(16, 1);
             else if (K <= 32) EF_SAMPLE(32, 1);
             else if (K <= 64) EF_SAMPLE(64, 1);
@@ -1854,8 +1865,8 @@ extern "C" int efanna_nndescent(const float *X, int64_t n, int32_t d, int32_t k,
             else EF_REVERSE_OLD(64);
 #undef EF_SAMPLE
 #undef EF_REVERSE_OLD
-            reverse_overflow_kernel<<<grid_for((size_t)n * 4, kBlock), kBlock, 0, st>>>(
-                ovf, w.overflow_rows, (int)n, K, w.rnew, w.rold, w.list_max, L);
+            reverse_overflow_kernel<<<dim3(kOvfBlocksPerQueue, kOvfQueues), kBlock, 0, st>>>(
+                ovf, ovf_region, w.ovf_count, (size_t)n, w.rnew, w.rold, w.list_max, L);
         }
         prepare_kernel<<<grid_for((size_t)n, prep_threads), prep_threads, prep_lds, st>>>(
             w.nw, w.od, w.nw_c, w.od_c, w.rnew, w.rold, w.rnew_c, w.rold_c, (int)n, K, L, max_rows,
