@@ -1572,6 +1572,26 @@ get_graph_kernel(const u64 *__restrict__ graph, int n, int K, int *__restrict__ 
     }
 }
 
+// Rows of at most G entries: a group of G lanes per row, ranks by broadcast inside the group.
+template <int G>
+__global__ void __launch_bounds__(kBlock)
+get_graph_group_kernel(const u64 *__restrict__ graph, int n, int K, int *__restrict__ ids,
+                       float *__restrict__ dists, unsigned char *__restrict__ flags)
+{
+    const int gl = threadIdx.x & (G - 1);
+    const size_t i = ((size_t)blockIdx.x * kBlock + threadIdx.x) / G;
+    const bool mine = i < (size_t)n && gl < K;
+    const u64 e = mine ? graph[i * K + gl] : ~0ULL;
+    int rank = 0;
+    for (int k = 0; k < K; ++k) rank += __shfl(e, k, G) < e ? 1 : 0;
+    if (!mine) return;
+    const size_t dst = i * K + rank;
+    const bool empty = ef_is_empty(e);
+    ids[dst] = empty ? -1 : ef_id(e);
+    dists[dst] = empty ? __uint_as_float(EF_INF_BITS) : __uint_as_float(ef_dist_bits(e));
+    if (flags) flags[dst] = empty ? 0 : (unsigned char)(e & 1);
+}
+
 __global__ void set_graph_kernel(u64 *graph, size_t total, int n, int K, const int *__restrict__ ids,
                                  const float *__restrict__ dists,
                                  const unsigned char *__restrict__ flags)
@@ -1932,8 +1952,15 @@ extern "C" int efanna_get_graph(const efanna_entry *graph_, int64_t n, int32_t k
 {
     const u64 *const graph = (const u64 *)graph_;
     if (!graph || !ids || !dists || n < 1 || k < 1 || k > EFANNA_MAX_K) return EFANNA_EINVAL;
-    get_graph_kernel<<<grid_for((size_t)n, kBlock / EF_WAVE), kBlock, 0, (hipStream_t)stream>>>(
-        graph, (int)n, k, ids, dists, flags);
+    if (k <= 16)
+        get_graph_group_kernel<16><<<grid_for((size_t)n * 16, kBlock), kBlock, 0, (hipStream_t)stream>>>(
+            graph, (int)n, k, ids, dists, flags);
+    else if (k <= 32)
+        get_graph_group_kernel<32><<<grid_for((size_t)n * 32, kBlock), kBlock, 0, (hipStream_t)stream>>>(
+            graph, (int)n, k, ids, dists, flags);
+    else
+        get_graph_kernel<<<grid_for((size_t)n, kBlock / EF_WAVE), kBlock, 0, (hipStream_t)stream>>>(
+            graph, (int)n, k, ids, dists, flags);
     EF_HIP_CHECK(hipGetLastError());
     return EFANNA_OK;
 }
