@@ -502,7 +502,7 @@ classify_kernel(const float *__restrict__ X, int d, const int *__restrict__ perm
                     for (int steps = 0; c >= 0 && steps < 4096; ++steps) {
                         const efanna_node nd = nodes_t[min(c, last)];
                         const bool left = nd.dim < 0 ||
-                                          (long long)nd.cnt * ef_quantise(X[(size_t)my_id * d + min(nd.dim, d - 1)]) < nd.sum;
+                                          (long long)nd.cnt * ef_quantise(X[(size_t)my_id * d + max(0, min(nd.dim, d - 1))]) < nd.sum;
                         c = nd.child[left ? 0 : 1];
                     }
                     e = c >= 0 ? 0 : min(~c, last);

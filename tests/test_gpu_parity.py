@@ -343,6 +343,91 @@ def test_search_edge_cases(ef):
     assert e.value.status == -1
 
 
+# ---------------------------------------------------------------------------------
+# The hand cases that pin the oracle's readings, put to the library directly: expected values
+# are worked out on paper (see the CPU tests of the same names), not taken from the oracle.
+
+def test_distance_hand_cases(ef):
+    def dist(where, d):
+        X = np.zeros((2, d), dtype=np.float32)
+        for j, v in where.items():
+            X[0, j] = v
+        one = np.zeros(1, dtype=np.int32)
+        ab = float(host(ef.efanna_pair_distances(dev(X), dev(one), dev(one + 1)))[0])
+        ba = float(host(ef.efanna_pair_distances(dev(X), dev(one + 1), dev(one)))[0])
+        assert ab == ba
+        return ab
+    # sixteen interleaved partial sums
+    assert dist({0: 4096.0, 16: 1.0, 17: 1.0}, 32) == 2.0 ** 24
+    assert dist({0: 4096.0, 1: 1.0, 17: 1.0}, 32) == 2.0 ** 24 + 2
+    assert dist({0: 4096.0, 8: 1.0, 24: 1.0}, 32) == 2.0 ** 24 + 2
+    # square and add round once
+    assert dist({0: 2.0 ** -12, 16: 1.0 + 2.0 ** -12}, 17) == 1.0 + 2.0 ** -11 + 2.0 ** -23
+    # the tree l += l+8, l += l+4, l += l+2, l += l+1
+    assert dist({0: 4096.0, 1: 1.0, 3: 1.0}, 16) == 2.0 ** 24 + 2
+    assert dist({0: 4096.0, 1: 1.0, 2: 1.0}, 16) == 2.0 ** 24
+    assert dist({0: 4096.0, 8: 1.0, 12: 1.0}, 16) == 2.0 ** 24
+    assert dist({0: 4096.0, 4: 1.0, 12: 1.0}, 16) == 2.0 ** 24 + 2
+
+
+def test_tree_hand_cases(ef):
+    step = 2.0 ** -20
+    for rows, want in (([1.0 * step, 0.0], [1, 0]), ([0.6 * step, 0.0], [1, 0]), ([0.5 * step, 0.0], [0, 1]),
+                       ([2.4 * step, 1.5 * step], [0, 1]), ([0.0, -0.6 * step], [1, 0])):
+        X = np.array(rows, dtype=np.float32)[:, None]
+        perm, off, nl = ef.efanna_build_trees(dev(X), 1, 1, 7)
+        assert nl[0] == 2 and list(host(perm)[0]) == want, rows
+    # 0..7 on a line, leaves of 2: splits at 3.5, then 1.5 and 5.5; a value equal to the mean goes right
+    X = np.arange(8, dtype=np.float32)[:, None]
+    perm, off, nl = ef.efanna_build_trees(dev(X), 1, 2, 3)
+    assert nl[0] == 4 and list(host(perm)[0]) == list(range(8)) and list(host(off)[0, :5]) == [0, 2, 4, 6, 8]
+    X = np.array([[1.0], [3.0], [2.0]], dtype=np.float32)           # mean 2: the 2 goes right, with the 3,
+    perm, off, nl = ef.efanna_build_trees(dev(X), 1, 1, 3)          # and left of it at the next split (mean 2.5)
+    assert list(host(perm)[0]) == [0, 2, 1] and list(host(off)[0, :4]) == [0, 1, 2, 3]
+
+
+def test_conquer_and_search_hand_cases(ef):
+    # the line 0..7 of the CPU hand cases, every coordinate of a point the same (the conquer step
+    # takes dimensions that are multiples of four): whichever dimension a node draws, it splits
+    # at the same place; squared distances are four times those on the line
+    X = np.repeat(np.arange(8, dtype=np.float32)[:, None], 4, axis=1)
+    Xd = dev(X)
+    perm, off, nl, nodes, up, depth = ef.efanna_build_trees(Xd, 1, 2, 3, with_nodes=True)
+    assert depth == 1
+
+    def neighbours(nodes_t, dep, row):
+        graph = ef.efanna_init_graph(Xd, perm, off, nl, 2, 6, nodes=nodes_t, leaf_up=up, tree_depth=depth,
+                                     conquer_depth=dep)
+        return sorted(int(v) for v in host(ef.efanna_get_graph(graph)[0])[row] if v >= 0)
+    assert neighbours(nodes, 2, 0) == [1]
+    assert neighbours(nodes, 1, 0) == [1, 2, 3]
+    assert neighbours(nodes, 0, 0) == [1, 2, 3, 4, 5]
+    assert neighbours(nodes, 0, 5) == [2, 3, 4, 6, 7]
+    # the root's left child turned into a node that split by position: every point goes left in it
+    edited = host(nodes).copy()
+    edited.view(oracle.NODE_DTYPE)[..., 0]["dim"][0, 1] = -1
+    assert neighbours(dev(edited), 0, 5) == [0, 1, 4, 6, 7]
+    # search, no graph edges: the trees alone
+    graph = np.full((8, 1), -1, dtype=np.int32)
+
+    def search(q, k, P, E, iters, g=graph):
+        got = ef.efanna_search(Xd, perm, off, nl, nodes, depth, 2, dev(g), dev(np.full((1, 4), q, dtype=np.float32)),
+                               k, P, E, iters)
+        return list(host(got[0])[0]), list(host(got[1])[0]), int(host(got[2])[0])
+    assert search(2.2, 1, 1, 1, 1)[::2] == ([2], 2)
+    assert search(2.2, 2, 2, 2, 1)[::2] == ([2, 3], 4)
+    assert search(2.2, 4, 4, 4, 1)[::2] == ([2, 3, 1, 4], 6)
+    assert search(2.2, 6, 6, 6, 1)[::2] == ([2, 3, 1, 4, 0, 5], 8)
+    # equal priorities are taken in link order: the third leaf for a query on the root's split is {6,7}
+    ids, dists, checked = search(3.5, 5, 5, 5, 1)
+    assert ids == [3, 4, 2, 5, 6] and dists == [1.0, 1.0, 9.0, 9.0, 25.0] and checked == 6
+    g2 = graph.copy()
+    g2[2, 0] = 7
+    assert search(2.2, 2, 2, 1, 1, g2)[::2] == ([2, 7], 5)
+    g2[2, 0] = 3                                       # already delivered by the leaves: not evaluated again
+    assert search(2.2, 2, 2, 1, 1, g2)[::2] == ([2, -1], 4)
+
+
 def test_set_get_roundtrip_and_random_start(ef):
     rng = np.random.default_rng(8)
     n, K = 3000, 10

@@ -47,6 +47,20 @@ def test_hand_case_on_a_line():
     assert sorted(int(v) for v in ids[5] if v >= 0) == [2, 3, 4, 6, 7]
 
 
+def test_node_without_a_split_test_sends_every_point_left():
+    # same tree, but the root's left child (leaves {0,1} and {2,3}) is made a node that split by
+    # position (dimension -1), as nodes below depth 60 are.  Point 5 would pass its test to the
+    # right (5 > 1.5); without a test it goes left, to {0,1}.
+    X = np.arange(8, dtype=np.float32)[:, None]
+    perm, off, nl, nodes, up = oracle.build_trees_nodes(X, 1, 2, 3)
+    ids, _, _ = oracle.conquer_graph(X, perm, off, nl, nodes, up, 0, 6)
+    assert sorted(int(v) for v in ids[5] if v >= 0) == [2, 3, 4, 6, 7]
+    nodes = nodes.copy()
+    nodes[0, 1]["dim"] = -1
+    ids, _, _ = oracle.conquer_graph(X, perm, off, nl, nodes, up, 0, 6)
+    assert sorted(int(v) for v in ids[5] if v >= 0) == [0, 1, 4, 6, 7]
+
+
 def test_depth_at_or_below_every_leaf_is_the_leaf_step():
     X = synth.generate("gmm10k_d32", n=3000)
     perm, off, nl, nodes, up = oracle.build_trees_nodes(X, 3, 8, 42)

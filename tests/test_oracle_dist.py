@@ -58,6 +58,24 @@ def test_interleave_width_is_16():
     assert float(oracle.dist(a, b)) == 2.0 ** 24 + 2
 
 
+def test_sixteen_partial_sums_not_eight():
+    # dimensions 8 and 24 share partial sum 8, away from the 2^24 in partial sum 0: their ones add
+    # to 2 there and survive the final adds.  With eight partial sums they would meet 2^24 one by
+    # one and be rounded away.
+    a, b = _unit(32, {0: 4096.0, 8: 1.0, 24: 1.0})
+    assert float(oracle.dist(a, b)) == 2.0 ** 24 + 2
+
+
+def test_square_and_add_round_once():
+    # (1 + 2^-12)^2 = 1 + 2^-11 + 2^-24 is not a float32.  Added to the 2^-24 already in the
+    # partial sum (dimension 0, same partial sum as dimension 16) the exact total 1 + 2^-11 + 2^-23
+    # is one, so a fused multiply-add returns it; rounding the square first loses the 2^-24 (tie
+    # to even), and adding 2^-24 afterwards loses it again.
+    a, b = _unit(17, {0: 2.0 ** -12, 16: 1.0 + 2.0 ** -12})
+    assert float(oracle.dist(a, b)) == 1.0 + 2.0 ** -11 + 2.0 ** -23
+    assert float(oracle.dist(b, a)) == 1.0 + 2.0 ** -11 + 2.0 ** -23
+
+
 def test_reduction_tree_shape():
     # partial sums are combined l += l+8, l += l+4, l += l+2, l += l+1.
     # ones in partials 1 and 3 meet each other (step 2) before meeting 2^24;

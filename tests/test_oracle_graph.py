@@ -297,6 +297,16 @@ def test_early_termination_stops_where_the_fresh_entries_run_out():
         assert done == want and stats.shape[0] == want
         ref = oracle.nndescent(X, *g0[:3], want, L, 42)
         assert np.array_equal(ids, ref[0]) and np.array_equal(flags, ref[2])
+    # exactly delta*n*K fresh entries is not "fewer": pick delta so that the limit, formed as the
+    # paper's delta*N*K in double precision, equals the count after the third iteration
+    n = X.shape[0]
+    delta = fresh[2] / (n * K)
+    for _ in range(64):
+        if delta * n * K == fresh[2]:
+            break
+        delta = float(np.nextafter(delta, 1.0 if delta * n * K < fresh[2] else 0.0))
+    assert delta * n * K == fresh[2] and fresh[3] < fresh[2] < fresh[1]
+    assert oracle.nndescent(X, *g0[:3], 8, L, 42, delta=delta)[4] == 4
     # a threshold nothing can meet stops after one iteration, zero never stops early
     assert oracle.nndescent(X, *g0[:3], 5, L, 42, delta=2.0)[4] == 1
     assert oracle.nndescent(X, *g0[:3], 3, L, 42)[3].shape[0] == 3

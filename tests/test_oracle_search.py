@@ -66,6 +66,26 @@ def test_hand_case_on_a_line():
     graph[2, 0] = 7
     ids, _, checked = oracle.search(X, t[0], t[1], t[2], t[3], 2, graph, Q, 2, 2, 1, 1)
     assert list(ids[0]) == [2, 7] and checked[0] == 5
+    # a graph neighbour that the leaves already delivered is not evaluated a second time
+    graph[2, 0] = 3
+    ids, _, checked = oracle.search(X, t[0], t[1], t[2], t[3], 2, graph, Q, 2, 2, 1, 1)
+    assert list(ids[0]) == [2] + [-1] and checked[0] == 4
+
+
+def test_equal_priorities_are_taken_in_link_order():
+    # same tree, query on the root's split value 3.5: the root sends it right (not below the
+    # mean) and puts its left child aside at priority 0.  Leaf {4,5} is found first and {6,7}
+    # put aside at (5.5-3.5)^2 = 4; the left child comes next, leads to {2,3} and puts {0,1}
+    # aside at (3.5-1.5)^2 = 4 as well.  Links of leaves are ~index: {6,7} is -4, {0,1} is -1,
+    # so the third leaf is {6,7}.
+    X = np.arange(8, dtype=np.float32)[:, None]
+    t = oracle.build_trees_nodes(X, 1, 2, 3)
+    graph = np.full((8, 1), -1, dtype=np.int32)
+    Q = np.array([[3.5]], dtype=np.float32)
+    ids, dists, checked = oracle.search(X, t[0], t[1], t[2], t[3], 2, graph, Q, 5, 5, 5, 1)
+    assert checked[0] == 6
+    assert list(ids[0]) == [3, 4, 2, 5, 6]
+    assert list(dists[0]) == [0.25, 0.25, 2.25, 2.25, 6.25]
 
 
 def python_leaves(q, nodes, n_leaves, want):

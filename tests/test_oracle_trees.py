@@ -119,6 +119,31 @@ def test_structural_invariants_and_randomisation():
     assert not np.array_equal(perm, perm3)         # seeds differ
 
 
+def test_split_test_resolves_steps_of_2_to_minus_20():
+    # two points 2^-20 apart, the larger one first: quantised to 1 and 0, sum 1, and 2*q < 1 only
+    # for the second point, which therefore goes left.  At any coarser resolution both quantise
+    # to 0, the split is degenerate and the positional halves keep the first point on the left.
+    X = np.array([[2.0 ** -20], [0.0]], dtype=np.float32)
+    perm, off, nl = oracle.build_trees(X, 1, 1, 7)
+    assert nl[0] == 2 and list(perm[0]) == [1, 0]
+
+
+def test_coordinates_are_rounded_to_nearest_even_not_truncated():
+    step = 2.0 ** -20
+    # 0.6 steps rounds to 1 (truncation would give 0 and a degenerate split): the second point goes left
+    X = np.array([[0.6 * step], [0.0]], dtype=np.float32)
+    assert list(oracle.build_trees(X, 1, 1, 7)[0][0]) == [1, 0]
+    # 0.5 steps is a tie and rounds to the even 0: both quantise alike, positional halves
+    X = np.array([[0.5 * step], [0.0]], dtype=np.float32)
+    assert list(oracle.build_trees(X, 1, 1, 7)[0][0]) == [0, 1]
+    # 1.5 steps is a tie and rounds to the even 2, 2.4 steps rounds to 2 as well: alike again
+    X = np.array([[2.4 * step], [1.5 * step]], dtype=np.float32)
+    assert list(oracle.build_trees(X, 1, 1, 7)[0][0]) == [0, 1]
+    # negative values: -0.6 steps rounds to -1, below 0
+    X = np.array([[0.0], [-0.6 * step]], dtype=np.float32)
+    assert list(oracle.build_trees(X, 1, 1, 7)[0][0]) == [1, 0]
+
+
 def test_quantisation_ties_and_large_values():
     # values closer than 2^-21 quantise together; mean compare stays exact near 2^20
     X = np.array([[1.0], [1.0 + 2.0 ** -23], [1000000.0], [-1000000.0], [3.0], [5.0]],
