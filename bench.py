@@ -63,6 +63,11 @@ def main():
     ap.add_argument("--search-pool", type=int, default=200, help="candidate pool size P of the search")
     ap.add_argument("--search-expand", type=int, default=50, help="expansion factor E of the search")
     ap.add_argument("--search-iters", type=int, default=4, help="NN-expansion rounds I of the search")
+    ap.add_argument("--ablation-init", type=int, default=0, metavar="ITERS",
+                    help="after the build, run NN-descent one iteration at a time for ITERS iterations from "
+                         "the tree-built initial graph and from a seeded random graph (the starting point of "
+                         "plain NN-descent) and add an `ablation_init` object: time and recall after every "
+                         "iteration of both")
     ap.add_argument("--conquer-depth", type=int, default=None,
                     help="walk the conquer step of Alg. 3 up to this depth (default: stop at the leaves, "
                          "the configuration the metric is quoted on); distance evaluations above the "
@@ -223,6 +228,55 @@ def main():
                   "expand": args.search_expand, "iters": args.search_iters,
                   "mean_points_checked": float(schk.float().mean().item())}
 
+    ablation = None
+    if args.ablation_init > 0:
+        rows = synth.sample_rows(n, max(1000, args.recall_rows))
+        rows_d = torch.from_numpy(rows).to(dev)
+        truth_a = exact_knn_torch(Xd, rows_d, K)
+
+        def recall_of(g):
+            got = efanna.efanna_get_graph(g)[0][rows_d].cpu().numpy()
+            return sum(np.intersect1d(a[a >= 0], b).shape[0] for a, b in zip(got, truth_a)) / float(truth_a.size)
+
+        def descend(g, start_ms):
+            curve, ms = [{"iterations": 0, "ms": start_ms, "recall_at_K": recall_of(g)}], start_ms
+            for it in range(args.ablation_init):
+                torch.cuda.synchronize()
+                a0 = time.perf_counter()
+                efanna.efanna_nndescent(Xd, g, 1, L, synth.ALGO_SEED, first_iter=it, workspace=ws_nnd)
+                torch.cuda.synchronize()
+                ms += (time.perf_counter() - a0) * 1e3
+                curve.append({"iterations": it + 1, "ms": ms, "recall_at_K": recall_of(g)})
+            return curve
+
+        def tree_start():
+            trees = efanna.efanna_build_trees(Xd, T, S, synth.ALGO_SEED, max_leaves=max_leaves, workspace=ws_tree)
+            g = efanna.efanna_init_graph(Xd, trees[0], trees[1], trees[2], S, K, workspace=ws_init)
+            return g
+
+        def random_start():
+            # K distinct random neighbours per point, never the point itself; a repeated draw leaves its slot empty
+            gen = torch.Generator(device=dev)
+            gen.manual_seed(synth.ALGO_SEED)
+            r = torch.randint(0, n - 1, (n, K), generator=gen, device=dev, dtype=torch.int64)
+            own = torch.arange(n, device=dev, dtype=torch.int64)[:, None]
+            ids = (r + (r >= own)).sort(dim=1).values
+            ids[:, 1:][ids[:, 1:] == ids[:, :-1]] = -1
+            dist = efanna.efanna_pair_distances(Xd, own.expand(n, K).reshape(-1).int(),
+                                                ids.clamp(min=0).reshape(-1).int()).view(n, K)
+            dist[ids < 0] = float("inf")
+            return efanna.efanna_set_graph(ids.int(), dist)
+
+        curves = {}
+        for label, start in (("tree_init", tree_start), ("random_init", random_start)):
+            start()                                   # warm-up
+            torch.cuda.synchronize()
+            a0 = time.perf_counter()
+            g = start()
+            torch.cuda.synchronize()
+            curves[label] = descend(g, (time.perf_counter() - a0) * 1e3)
+        ablation = {"recall_rows": int(rows.shape[0]), **curves}
+
     achieved = k_bytes_sum / 1e9 / (k_ms_sum / 1e3) if k_ms_sum > 0 else 0.0
     achieved_all = all_bytes_sum / 1e9 / (all_ms_sum / 1e3) if all_ms_sum > 0 else 0.0
     out = {
@@ -263,6 +317,8 @@ def main():
     }
     if search is not None:
         out["search"] = search
+    if ablation is not None:
+        out["ablation_init"] = ablation
     print(json.dumps(out))
 
 
