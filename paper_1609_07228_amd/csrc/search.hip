@@ -55,8 +55,8 @@ SearchShape search_shape(int64_t nq, int d, int T, int S, int tree_depth, int Kg
     sh.table_bytes = align_up((size_t)sh.waves * sh.table * 8);
     sh.roots_bytes = align_up((size_t)2 * T * 4);      // roots and a device copy of the leaf counts
     sh.bytes = sh.heap_bytes + sh.table_bytes + sh.roots_bytes;
-    // LDS: query, two pools, batch keys, expansion list, first candidates, leaves found
-    sh.lds = (size_t)((d + 3) & ~3) * 4 + 2 * (size_t)P * 8 + 64 * 8 + (size_t)P * 4 +
+    // LDS: query, pool, batch keys, expansion list, first candidates, leaves found
+    sh.lds = (size_t)((d + 3) & ~3) * 4 + (size_t)P * 8 + 64 * 8 + (size_t)P * 4 +
              (size_t)sh.max_first * 4 + (size_t)T * sh.want * 4 + (size_t)T * 4 + 64;
     return sh;
 }
@@ -116,31 +116,46 @@ __device__ inline float lane_distance(const float *q, const float *__restrict__ 
     return acc[0];
 }
 
-// Merge the wave's batch (one key per lane, ~0 = none) into the sorted pool `cur` (count keys,
-// room for cap); the result goes to `nxt`.  Returns the new count.  Keys are distinct.
-__device__ inline int pool_merge(const u64 *cur, u64 *nxt, int count, int cap, u64 key, u64 *batch)
+// Merge the wave's batch (one key per lane, ~0 = none) into the sorted pool (count keys, room for
+// cap), in place.  Returns the new count.  Keys are distinct.
+// The batch is packed to the front of `batch` first: usually only a few of its keys are there
+// at all (the others were checked before or lie beyond a full pool).  Pool members below the
+// smallest fresh key stay where they are; the others move up by the number of fresh keys below
+// them, 64 at a time from the top (a chunk is read before it is written, and it only writes at
+// or above its own places), and the fresh keys take the places left free.
+__device__ inline int pool_merge(u64 *pool, int count, int cap, u64 key, u64 *batch)
 {
     const int lane = ef_lane();
-    batch[lane] = key;
+    const u64 there = __ballot(key != ~0ULL);
+    const int fresh = __popcll(there);
+    if (key != ~0ULL) batch[__popcll(there & ((1ULL << lane) - 1))] = key;
     __syncthreads();
-    const int fresh = __popcll(__ballot(key != ~0ULL));
+    int lo = count, pos = 0;
     if (key != ~0ULL) {
-        int lo = 0, hi = count;
+        int hi = count;
+        lo = 0;
         while (lo < hi) {
             const int mid = (lo + hi) >> 1;
-            if (cur[mid] < key) lo = mid + 1;
+            if (pool[mid] < key) lo = mid + 1;
             else hi = mid;
         }
-        int pos = lo;
-        for (int o = 0; o < EF_WAVE; ++o) pos += batch[o] < key ? 1 : 0;
-        if (pos < cap) nxt[pos] = key;
+        pos = lo;
+        for (int o = 0; o < fresh; ++o) pos += batch[o] < key ? 1 : 0;
     }
-    for (int j = lane; j < count; j += EF_WAVE) {
-        const u64 e = cur[j];
-        int pos = j;
-        for (int o = 0; o < EF_WAVE; ++o) pos += batch[o] < e ? 1 : 0;
-        if (pos < cap) nxt[pos] = e;
+    int first = lo;                  // the lowest place any fresh key takes
+    for (int m = 32; m >= 1; m >>= 1) first = min(first, __shfl_xor(first, m, EF_WAVE));
+    for (int top = count; top > first; top -= EF_WAVE) {
+        const int j = top - EF_WAVE + lane;
+        u64 e = 0;
+        int up = 0;
+        if (j >= first) {
+            e = pool[j];
+            for (int o = 0; o < fresh; ++o) up += batch[o] < e ? 1 : 0;
+        }
+        __syncthreads();             // the chunk is in registers before any of it is overwritten
+        if (j >= first && j + up < cap) pool[j + up] = e;
     }
+    if (key != ~0ULL && pos < cap) pool[pos] = key;
     __syncthreads();
     return min(cap, count + fresh);
 }
@@ -156,9 +171,8 @@ search_kernel(const float *__restrict__ X, int d, int n, const int *__restrict__
     extern __shared__ __align__(16) float smem[];
     const int dq = (d + 3) & ~3;
     float *q = smem;                                   // [dq]
-    u64 *pool_a = (u64 *)(smem + dq);                  // [P]
-    u64 *pool_b = pool_a + P;                          // [P]
-    u64 *batch = pool_b + P;                           // [64]
+    u64 *cur = (u64 *)(smem + dq);                     // [P] the pool, ascending
+    u64 *batch = cur + P;                              // [64]
     int *expand = (int *)(batch + EF_WAVE);            // [P]
     int *first = expand + P;                           // [max_first] members of the leaves found
     int *leaves = first + max_first;                   // [T][want]
@@ -230,7 +244,6 @@ search_kernel(const float *__restrict__ X, int d, int n, const int *__restrict__
                 n_first += s;
             }
         __syncthreads();
-        u64 *cur = pool_a, *nxt = pool_b;
         int count = 0, checked = 0;
         for (int c0 = 0; c0 < n_first; c0 += EF_WAVE) {
             u64 key = ~0ULL;
@@ -242,10 +255,7 @@ search_kernel(const float *__restrict__ X, int d, int n, const int *__restrict__
             checked += __popcll(__ballot(key != ~0ULL));
             if (count == E && key >= cur[E - 1]) key = ~0ULL;      // a full pool takes nothing beyond its last key
             if (__ballot(key != ~0ULL) == 0) continue;
-            count = pool_merge(cur, nxt, count, E, key, batch);
-            u64 *tmp = cur;
-            cur = nxt;
-            nxt = tmp;
+            count = pool_merge(cur, count, E, key, batch);
         }
         // ---- 3. NN-expansion ---------------------------------------------------------------------
         for (int it = 0; it < iters; ++it) {
@@ -277,10 +287,7 @@ search_kernel(const float *__restrict__ X, int d, int n, const int *__restrict__
                 checked += __popcll(__ballot(key != ~0ULL));
                 if (count == P && key >= cur[P - 1]) key = ~0ULL;      // a full pool takes nothing beyond its last key
                 if (__ballot(key != ~0ULL) == 0) continue;
-                count = pool_merge(cur, nxt, count, P, key, batch);
-                u64 *tmp = cur;
-                cur = nxt;
-                nxt = tmp;
+                count = pool_merge(cur, count, P, key, batch);
             }
         }
         // ---- result: the K closest --------------------------------------------------------------
