@@ -58,7 +58,7 @@ SearchShape search_shape(int64_t nq, int d, int T, int S, int tree_depth, int Kg
     sh.roots_bytes = align_up((size_t)2 * T * 4);      // roots and a device copy of the leaf counts
     sh.bytes = sh.heap_bytes + sh.table_bytes + sh.roots_bytes;
     // LDS: query, pool, batch keys, expansion list, first candidates, leaves found
-    sh.lds = (size_t)((d + 3) & ~3) * 4 + (size_t)P * 8 + 64 * 8 + (size_t)P * 4 +
+    sh.lds = (size_t)((d + 15) & ~15) * 4 + (size_t)P * 8 + 64 * 8 + (size_t)P * 4 +
              (size_t)sh.max_first * 4 + (size_t)T * sh.want * 4 + (size_t)T * 4 + 64;
     return sh;
 }
@@ -92,35 +92,55 @@ __device__ inline bool checked_insert(u64 *table, int mask, u32 tag, int id)
     return false;      // a full table cannot happen: it holds twice what a query can check
 }
 
-// the library's distance between the query (LDS) and one row, by a single lane; the row comes in
-// pieces of 32 coordinates, eight 16-byte loads in flight at a time
-__device__ inline float lane_distance(const float *q, const float *__restrict__ row, int d)
+// The library's distance between the query (LDS) and the row of every lane's candidate (`id`, -1
+// = none), by the whole wave: sixteen candidates at a time, four lanes each.  Lane (r, g) = lane
+// r + 16 g loads the 16-byte pieces 16 s + 4 g of row r, so that four lanes fetch 64 contiguous
+// bytes and every byte fetched is used (a lane reading a whole row alone touches 64 rows per
+// load and finds their lines evicted before it comes back for the rest); it accumulates
+// partial sums 4g..4g+3 of the fixed order, and the four lanes of a row add up 8 apart, 4
+// apart, 2 apart, 1 apart.  The candidate of lane 16 g + r is handled in round g by column r,
+// so the lane that owns it is among the four that end up with its distance.
+// Requires d % 4 == 0 and a 16-byte aligned X; q holds the query padded with zeros to a multiple of 16.
+__device__ inline float wave_distances(const float *q, const float *__restrict__ X, int d, int id)
 {
-    float acc[16];
+    const int lane = ef_lane(), r16 = lane & 15, g = lane >> 4;
+    float mine = 0.0f;
+    for (int round = 0; round < 4; ++round) {
+        const int rid = __shfl(id, 16 * round + r16, EF_WAVE);
+        if (__ballot(rid >= 0) == 0) continue;
+        const float *row = X + (size_t)max(rid, 0) * d + 4 * g;
+        float p0 = 0.f, p1 = 0.f, p2 = 0.f, p3 = 0.f;
+        for (int c0 = 0; c0 < d; c0 += 128) {
+            float4 v[8];
 #pragma unroll
-    for (int l = 0; l < 16; ++l) acc[l] = 0.0f;
-    for (int j0 = 0; j0 < d; j0 += 32) {
-        float4 x[8];
+            for (int s = 0; s < 8; ++s)
+                v[s] = rid >= 0 && c0 + 16 * s + 4 * g + 3 < d ? *reinterpret_cast<const float4 *>(row + c0 + 16 * s)
+                                                               : make_float4(0.f, 0.f, 0.f, 0.f);
 #pragma unroll
-        for (int c = 0; c < 8; ++c)      // d % 4 == 0: a piece is in or out
-            x[c] = j0 + 4 * c < d ? *reinterpret_cast<const float4 *>(row + j0 + 4 * c) : make_float4(0.f, 0.f, 0.f, 0.f);
-#pragma unroll
-        for (int c = 0; c < 8; ++c) {
-            if (j0 + 4 * c >= d) break;
-            const float4 y = *reinterpret_cast<const float4 *>(q + j0 + 4 * c);
-            const float d0 = y.x - x[c].x, d1 = y.y - x[c].y, d2 = y.z - x[c].z, d3 = y.w - x[c].w;
-            const int l = 4 * (c & 3);
-            acc[l] = __builtin_fmaf(d0, d0, acc[l]);
-            acc[l + 1] = __builtin_fmaf(d1, d1, acc[l + 1]);
-            acc[l + 2] = __builtin_fmaf(d2, d2, acc[l + 2]);
-            acc[l + 3] = __builtin_fmaf(d3, d3, acc[l + 3]);
+            for (int s = 0; s < 8; ++s) {
+                if (c0 + 16 * s >= d) break;
+                const float4 y = *reinterpret_cast<const float4 *>(q + c0 + 16 * s + 4 * g);
+                const bool in = c0 + 16 * s + 4 * g + 3 < d;      // beyond d both sides count as zero
+                const float d0 = in ? y.x - v[s].x : 0.f, d1 = in ? y.y - v[s].y : 0.f,
+                            d2 = in ? y.z - v[s].z : 0.f, d3 = in ? y.w - v[s].w : 0.f;
+                p0 = __builtin_fmaf(d0, d0, p0);
+                p1 = __builtin_fmaf(d1, d1, p1);
+                p2 = __builtin_fmaf(d2, d2, p2);
+                p3 = __builtin_fmaf(d3, d3, p3);
+            }
         }
+        p0 += __shfl_xor(p0, 32, EF_WAVE);
+        p1 += __shfl_xor(p1, 32, EF_WAVE);
+        p2 += __shfl_xor(p2, 32, EF_WAVE);
+        p3 += __shfl_xor(p3, 32, EF_WAVE);
+        p0 += __shfl_xor(p0, 16, EF_WAVE);
+        p1 += __shfl_xor(p1, 16, EF_WAVE);
+        p2 += __shfl_xor(p2, 16, EF_WAVE);
+        p3 += __shfl_xor(p3, 16, EF_WAVE);
+        const float dist = (p0 + p2) + (p1 + p3);
+        if (g == round) mine = dist;
     }
-#pragma unroll
-    for (int s = 8; s >= 1; s >>= 1)
-#pragma unroll
-        for (int l = 0; l < s; ++l) acc[l] = acc[l] + acc[l + s];
-    return acc[0];
+    return mine;
 }
 
 // Merge the wave's batch (one key per lane, ~0 = none) into the sorted pool (count keys, room for
@@ -176,7 +196,7 @@ search_kernel(const float *__restrict__ X, int d, int n, const int *__restrict__
               Branch *heaps, u64 *tables, int *out_ids, float *out_dists, int *out_checked)
 {
     extern __shared__ __align__(16) float smem[];
-    const int dq = (d + 3) & ~3;
+    const int dq = (d + 15) & ~15;
     float *q = smem;                                   // [dq]
     u64 *cur = (u64 *)(smem + dq);                     // [P] the pool, ascending
     u64 *batch = cur + P;                              // [64]
@@ -254,11 +274,13 @@ search_kernel(const float *__restrict__ X, int d, int n, const int *__restrict__
         int count = 0, checked = 0;
         for (int c0 = 0; c0 < n_first; c0 += EF_WAVE) {
             u64 key = ~0ULL;
+            int cand = -1;
             if (c0 + lane < n_first) {
                 const int id = first[c0 + lane];
-                if (id >= 0 && id < n && checked_insert(table, mask, tag, id))
-                    key = ef_pack(lane_distance(q, X + (size_t)id * d, d), id, 1);
+                if (id >= 0 && id < n && checked_insert(table, mask, tag, id)) cand = id;
             }
+            const float dist = wave_distances(q, X, d, cand);
+            if (cand >= 0) key = ef_pack(dist, cand, 1);
             checked += __popcll(__ballot(key != ~0ULL));
             if (count == E && key >= cur[E - 1]) key = ~0ULL;      // a full pool takes nothing beyond its last key
             if (__ballot(key != ~0ULL) == 0) continue;
@@ -284,13 +306,15 @@ search_kernel(const float *__restrict__ X, int d, int n, const int *__restrict__
             const int total = n_exp * Kg;
             for (int f0 = 0; f0 < total; f0 += EF_WAVE) {
                 u64 key = ~0ULL;
+                int cand = -1;
                 const int f = f0 + lane;
                 if (f < total) {
                     const int src = expand[f / Kg];
                     const int id = graph_ids[(size_t)src * Kg + f % Kg];
-                    if (id >= 0 && id < n && checked_insert(table, mask, tag, id))
-                        key = ef_pack(lane_distance(q, X + (size_t)id * d, d), id, 1);
+                    if (id >= 0 && id < n && checked_insert(table, mask, tag, id)) cand = id;
                 }
+                const float dist = wave_distances(q, X, d, cand);
+                if (cand >= 0) key = ef_pack(dist, cand, 1);
                 checked += __popcll(__ballot(key != ~0ULL));
                 if (count == P && key >= cur[P - 1]) key = ~0ULL;      // a full pool takes nothing beyond its last key
                 if (__ballot(key != ~0ULL) == 0) continue;
