@@ -183,6 +183,42 @@ __device__ inline void ef_load_row_pieces_8(const void *p, ef_u32x4 (&q)[8])
                  : "memory");
 }
 
+// twenty-five pieces (fifty entries) at once: for long rows, in kernels with registers to spare
+constexpr int EF_WIDE_PIECES = 25;
+__device__ inline void ef_load_row_pieces_wide(const void *p, ef_u32x4 (&q)[EF_WIDE_PIECES])
+{
+    asm volatile(
+                     "global_load_dwordx4 %0, %25, off offset:0 sc1\n\t"
+                     "global_load_dwordx4 %1, %25, off offset:16 sc1\n\t"
+                     "global_load_dwordx4 %2, %25, off offset:32 sc1\n\t"
+                     "global_load_dwordx4 %3, %25, off offset:48 sc1\n\t"
+                     "global_load_dwordx4 %4, %25, off offset:64 sc1\n\t"
+                     "global_load_dwordx4 %5, %25, off offset:80 sc1\n\t"
+                     "global_load_dwordx4 %6, %25, off offset:96 sc1\n\t"
+                     "global_load_dwordx4 %7, %25, off offset:112 sc1\n\t"
+                     "global_load_dwordx4 %8, %25, off offset:128 sc1\n\t"
+                     "global_load_dwordx4 %9, %25, off offset:144 sc1\n\t"
+                     "global_load_dwordx4 %10, %25, off offset:160 sc1\n\t"
+                     "global_load_dwordx4 %11, %25, off offset:176 sc1\n\t"
+                     "global_load_dwordx4 %12, %25, off offset:192 sc1\n\t"
+                     "global_load_dwordx4 %13, %25, off offset:208 sc1\n\t"
+                     "global_load_dwordx4 %14, %25, off offset:224 sc1\n\t"
+                     "global_load_dwordx4 %15, %25, off offset:240 sc1\n\t"
+                     "global_load_dwordx4 %16, %25, off offset:256 sc1\n\t"
+                     "global_load_dwordx4 %17, %25, off offset:272 sc1\n\t"
+                     "global_load_dwordx4 %18, %25, off offset:288 sc1\n\t"
+                     "global_load_dwordx4 %19, %25, off offset:304 sc1\n\t"
+                     "global_load_dwordx4 %20, %25, off offset:320 sc1\n\t"
+                     "global_load_dwordx4 %21, %25, off offset:336 sc1\n\t"
+                     "global_load_dwordx4 %22, %25, off offset:352 sc1\n\t"
+                     "global_load_dwordx4 %23, %25, off offset:368 sc1\n\t"
+                     "global_load_dwordx4 %24, %25, off offset:384 sc1\n\t"
+                     "s_waitcnt vmcnt(0)"
+                 : "=&v"(q[0]), "=&v"(q[1]), "=&v"(q[2]), "=&v"(q[3]), "=&v"(q[4]), "=&v"(q[5]), "=&v"(q[6]), "=&v"(q[7]), "=&v"(q[8]), "=&v"(q[9]), "=&v"(q[10]), "=&v"(q[11]), "=&v"(q[12]), "=&v"(q[13]), "=&v"(q[14]), "=&v"(q[15]), "=&v"(q[16]), "=&v"(q[17]), "=&v"(q[18]), "=&v"(q[19]), "=&v"(q[20]), "=&v"(q[21]), "=&v"(q[22]), "=&v"(q[23]), "=&v"(q[24])
+                 : "v"(p)
+                 : "memory");
+}
+
 // pieces 0..np-1 of the row at p (16-byte aligned) into q; the rest of q is zero
 __device__ inline void ef_load_row_pieces(const void *p, int np, ef_u32x4 (&q)[8])
 {
@@ -216,17 +252,40 @@ __device__ inline void ef_load_row_pieces(const void *p, int np, ef_u32x4 (&q)[8
 //
 // Returns true if the key went in; *new_max then holds an upper bound of the list's
 // maximum after the insertion.
-__device__ inline bool ef_bounded_insert(u64 *list, int cap, u64 key, int ignore, u64 *new_max)
+template <bool WIDE>
+__device__ inline bool ef_bounded_insert_t(u64 *list, int cap, u64 key, int ignore, u64 *new_max)
 {
     const u64 kcmp = key >> ignore;
     for (;;) {
         u64 mx = 0, mx2 = 0;
         int ms = 0;
         bool dup = false;
-        // sixteen slots in flight at a time: a row of up to 16 entries costs one memory round
-        // trip instead of one per slot
+        auto see = [&](u64 e, int slot) {
+            dup |= (e >> ignore) == kcmp;
+            if (e > mx) {
+                mx2 = mx;
+                mx = e;
+                ms = slot;
+            } else if (e > mx2) {
+                mx2 = e;
+            }
+        };
+        // sixteen slots in flight at a time (fifty with WIDE, while the row has as many left): a
+        // row of up to 16 entries costs one memory round trip instead of one per slot
         const bool wide = (cap & 1) == 0 && ((uintptr_t)list & 15) == 0;
-        for (int s0 = 0; s0 < cap; s0 += 16) {
+        int s0 = 0;
+        if (WIDE && wide) {
+            for (; s0 + 2 * EF_WIDE_PIECES <= cap; s0 += 2 * EF_WIDE_PIECES) {
+                ef_u32x4 q[EF_WIDE_PIECES];
+                ef_load_row_pieces_wide(list + s0, q);
+#pragma unroll
+                for (int k = 0; k < EF_WIDE_PIECES; ++k) {
+                    see(((u64)q[k].y << 32) | q[k].x, s0 + 2 * k);
+                    see(((u64)q[k].w << 32) | q[k].z, s0 + 2 * k + 1);
+                }
+            }
+        }
+        for (; s0 < cap; s0 += 16) {
             u64 e[16];
             if (wide) {      // even length, 16-byte aligned: eight 16-byte pieces
                 ef_u32x4 q[8];
@@ -243,14 +302,7 @@ __device__ inline bool ef_bounded_insert(u64 *list, int cap, u64 key, int ignore
 #pragma unroll
             for (int k = 0; k < 16; ++k) {
                 if (s0 + k >= cap) break;
-                dup |= (e[k] >> ignore) == kcmp;
-                if (e[k] > mx) {
-                    mx2 = mx;
-                    mx = e[k];
-                    ms = s0 + k;
-                } else if (e[k] > mx2) {
-                    mx2 = e[k];
-                }
+                see(e[k], s0 + k);
             }
         }
         if (dup || kcmp >= (mx >> ignore)) return false;
@@ -260,6 +312,11 @@ __device__ inline bool ef_bounded_insert(u64 *list, int cap, u64 key, int ignore
             return true;
         }
     }
+}
+
+__device__ inline bool ef_bounded_insert(u64 *list, int cap, u64 key, int ignore, u64 *new_max)
+{
+    return ef_bounded_insert_t<false>(list, cap, key, ignore, new_max);
 }
 
 // ---- wave utilities ---------------------------------------------------------------------

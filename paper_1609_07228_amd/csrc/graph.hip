@@ -120,6 +120,7 @@ __device__ inline void gather_rows(const float *__restrict__ X, int d, int strid
 
 // Drain the proposal queue: every thread applies whole proposals on its own, so all the
 // row reads of up to blockDim proposals are in flight together.
+template <bool WIDE = false>
 __device__ inline int drain_queue(const Proposal *queue, int count, u64 *graph, u32 *worst, int K,
                                   int tid, int nthr)
 {
@@ -127,7 +128,7 @@ __device__ inline int drain_queue(const Proposal *queue, int count, u64 *graph, 
     for (int e = tid; e < count; e += nthr) {
         const Proposal p = queue[e];
         u64 new_max;
-        if (ef_bounded_insert(graph + (size_t)p.target * K, K, p.key, 1, &new_max)) {
+        if (ef_bounded_insert_t<WIDE>(graph + (size_t)p.target * K, K, p.key, 1, &new_max)) {
             atomicMin(worst + p.target, ef_dist_bits(new_max));
             ++updates;
         }
@@ -840,6 +841,8 @@ reverse_old_kernel(const int *__restrict__ od, int n, int K, int L, u64 key_old,
 // one read instead of a scan of the list.
 constexpr int kOvfBlocksPerQueue = 16;
 
+// WIDE: lists of fifty keys or more are read fifty keys at a time.
+template <bool WIDE>
 __global__ void __launch_bounds__(kBlock)
 reverse_overflow_kernel(const Overflow *__restrict__ overflow, size_t ovf_region,
                         const int *__restrict__ ovf_count, size_t n, u64 *rnew, u64 *rold,
@@ -851,7 +854,7 @@ reverse_overflow_kernel(const Overflow *__restrict__ overflow, size_t ovf_region
         u64 *bound = list_max + (size_t)ov.which * n + ov.target;
         if (ov.key >= ef_load_coherent(bound)) continue;
         u64 nm;
-        if (ef_bounded_insert((ov.which ? rold : rnew) + (size_t)ov.target * L, L, ov.key, 0, &nm))
+        if (ef_bounded_insert_t<WIDE>((ov.which ? rold : rnew) + (size_t)ov.target * L, L, ov.key, 0, &nm))
             atomicMin(bound, nm);
     }
 }
@@ -1007,7 +1010,8 @@ __device__ inline JoinLds join_lds_carve(float *smem, int cap_rows, int stride, 
     return l;
 }
 
-__global__ void join_kernel(const float *__restrict__ X, const float *__restrict__ norms, int d,
+template <bool WIDE>      // WIDE: graph rows of fifty entries or more are read fifty entries at a time
+__global__ void __launch_bounds__(512) join_kernel(const float *__restrict__ X, const float *__restrict__ norms, int d,
                             int dpad, int stride, u32 q4_magic, int K,
                             const int *__restrict__ work, const int *__restrict__ work_count,
                             int cap_rows, int s_cap, int q_cap, float margin_rel, float thr_scale,
@@ -1119,7 +1123,7 @@ __global__ void join_kernel(const float *__restrict__ X, const float *__restrict
                     }
                     __syncthreads();
                     // ---- 4. drain -----------------------------------------------------------
-                    updates += drain_queue(lds.queue, lds.meta[3], graph, worst, K, tid, nthr);
+                    updates += drain_queue<WIDE>(lds.queue, lds.meta[3], graph, worst, K, tid, nthr);
                     __syncthreads();
                     if (tid == 0) lds.meta[3] = 0;
                     __syncthreads();
@@ -1847,7 +1851,8 @@ extern "C" int efanna_nndescent(const float *X, int64_t n, int32_t d, int32_t k,
     hipStream_t st = (hipStream_t)stream;
     NndWs w = carve_nnd(ws, n, K, L);
     if (max_rows > rows1)
-        EF_HIP_CHECK(hipFuncSetAttribute((const void *)join_kernel,
+        EF_HIP_CHECK(hipFuncSetAttribute(K >= 2 * EF_WIDE_PIECES ? (const void *)join_kernel<true>
+                                                                 : (const void *)join_kernel<false>,
                                          hipFuncAttributeMaxDynamicSharedMemorySize, (int)large.lds));
     norms_kernel<<<grid_for((size_t)n * 16, kBlock), kBlock, 0, st>>>(X, (int)n, d, w.norms);
     if (stats) zero_u64_kernel<<<grid_for((size_t)iters * 4 + 1, kBlock), kBlock, 0, st>>>(stats, iters * 4);
@@ -1885,8 +1890,12 @@ extern "C" int efanna_nndescent(const float *X, int64_t n, int32_t d, int32_t k,
             else EF_REVERSE_OLD(64);
 #undef EF_SAMPLE
 #undef EF_REVERSE_OLD
-            reverse_overflow_kernel<<<dim3(kOvfBlocksPerQueue, kOvfQueues), kBlock, 0, st>>>(
-                ovf, ovf_region, w.ovf_count, (size_t)n, w.rnew, w.rold, w.list_max, L);
+            if (L >= 2 * EF_WIDE_PIECES)
+                reverse_overflow_kernel<true><<<dim3(kOvfBlocksPerQueue, kOvfQueues), kBlock, 0, st>>>(
+                    ovf, ovf_region, w.ovf_count, (size_t)n, w.rnew, w.rold, w.list_max, L);
+            else
+                reverse_overflow_kernel<false><<<dim3(kOvfBlocksPerQueue, kOvfQueues), kBlock, 0, st>>>(
+                    ovf, ovf_region, w.ovf_count, (size_t)n, w.rnew, w.rold, w.list_max, L);
         }
         prepare_kernel<<<grid_for((size_t)n, prep_threads), prep_threads, prep_lds, st>>>(
             w.nw, w.od, w.nw_c, w.od_c, w.rnew, w.rold, w.rnew_c, w.rold_c, (int)n, K, L, max_rows,
@@ -1910,11 +1919,16 @@ extern "C" int efanna_nndescent(const float *X, int64_t n, int32_t d, int32_t k,
             EF_HIP_CHECK(hipEventRecord(ev[5 * it + 2], st));
         }
         if (ev) EF_HIP_CHECK(hipEventRecord(ev[5 * it + 3], st));
-        if (max_rows > rows1)
-            join_kernel<<<large.grid, large.threads, large.lds, st>>>(
-                X, w.norms, d, dpad, stride, q4_magic_for(d), K, w.work + 2 * (size_t)n,
-                w.work_count + 2, large.cap_rows, large.s_cap, large.q_cap, margin_rel, thr_scale,
-                w.ulist, w.ucount, max_rows, graph, w.worst, w.upd_block + 2 * reg_grid);
+#define EF_JOIN_LARGE(WIDE)                                                                        \
+    join_kernel<WIDE><<<large.grid, large.threads, large.lds, st>>>(                               \
+        X, w.norms, d, dpad, stride, q4_magic_for(d), K, w.work + 2 * (size_t)n, w.work_count + 2, \
+        large.cap_rows, large.s_cap, large.q_cap, margin_rel, thr_scale, w.ulist, w.ucount,        \
+        max_rows, graph, w.worst, w.upd_block + 2 * reg_grid)
+        if (max_rows > rows1) {
+            if (K >= 2 * EF_WIDE_PIECES) EF_JOIN_LARGE(true);
+            else EF_JOIN_LARGE(false);
+        }
+#undef EF_JOIN_LARGE
         if (ev) EF_HIP_CHECK(hipEventRecord(ev[5 * it + 4], st));
         if (stats)
             stats_kernel<<<16, kBlock, 0, st>>>(w.part, grid_for((size_t)n, prep_threads), w.upd_block,
