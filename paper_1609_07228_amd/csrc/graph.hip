@@ -1201,6 +1201,7 @@ join_reg_kernel(const float *__restrict__ X, const float *__restrict__ norms, in
     u32 *surv = (u32 *)(tf + R);                  // [S_CAP] surviving pairs
     Proposal *queue = (Proposal *)(surv + align4(S_CAP));   // [q_cap]
     const int lane = threadIdx.x, r16 = lane & 15, g = lane >> 4, gl = r16, grp = g;
+    const int dirn = (EF_ROW_ROR(r16, 1) - r16) & 15;      // a rotation by t brings row r + t * dirn to row r
     const int count = *work_count;
     // The id list and the sizes of a point are fetched one point ahead, and the thresholds and
     // norms of its vectors as soon as those ids are there, so that they travel while the
@@ -1245,7 +1246,38 @@ join_reg_kernel(const float *__restrict__ X, const float *__restrict__ norms, in
 #pragma unroll
             for (int h = 0; h < 2; ++h) acc[q][h] = (floatx4){0.f, 0.f, 0.f, 0.f};
         float4 va[8], vb[NB > 1 ? 8 : 1];
-        for (int c0 = 0; c0 < d; c0 += 128) {
+        // Long vectors, at most 16 of them: with the filter the rows would have to be streamed a
+        // second time for the pairs that pass it.  Instead all pairs get their fixed-order
+        // distance in this one pass, as in init_reg_kernel: eight row rotations per
+        // 128-coordinate piece meet every pair (vector instructions that hide under the gather:
+        // 512 per 8 KB of rows), the four lanes of a column add their partial sums in the fixed
+        // tree, and lane (r, g) holds the distances from row r to the rows 2g+1 and 2g+2 places
+        // on.  No Gram block, no filter.
+        constexpr bool rotated = !ONE && NB == 1;
+        float two[2] = {0.f, 0.f};
+        if (rotated) {
+            float P[8][4];
+#pragma unroll
+            for (int t = 0; t < 8; ++t) P[t][0] = P[t][1] = P[t][2] = P[t][3] = 0.0f;
+            for (int c0 = 0; c0 < d; c0 += 128) {
+#pragma unroll
+                for (int s = 0; s < 8; ++s) {
+                    const bool in = c0 + 16 * s + 4 * g + 3 < d;      // d % 4 == 0: a piece is in or out
+                    va[s] = in ? *reinterpret_cast<const float4 *>(pa + c0 + 16 * s) : make_float4(0.f, 0.f, 0.f, 0.f);
+                }
+                const int n_pieces = min(8, (d - c0 + 15) >> 4);
+                init_round<1>(va, n_pieces, P[0]);
+                init_round<2>(va, n_pieces, P[1]);
+                init_round<3>(va, n_pieces, P[2]);
+                init_round<4>(va, n_pieces, P[3]);
+                init_round<5>(va, n_pieces, P[4]);
+                init_round<6>(va, n_pieces, P[5]);
+                init_round<7>(va, n_pieces, P[6]);
+                init_round<8>(va, n_pieces, P[7]);
+            }
+            reduce_rotations(P, g, two);
+        }
+        for (int c0 = 0; c0 < d && !rotated; c0 += 128) {
             if (c0 + 128 <= d) {     // a whole 128-coordinate piece: no per-load bounds test
 #pragma unroll
                 for (int s = 0; s < 8; ++s) {
@@ -1292,8 +1324,10 @@ join_reg_kernel(const float *__restrict__ X, const float *__restrict__ norms, in
         // pair (a, b) survives if (|a|^2 + |b|^2)(1 - margin) - 2 a.b <= max threshold * scale
         int n_surv[NQ];
 #pragma unroll
+        for (int q = 0; q < NQ; ++q) n_surv[q] = 0;
+#pragma unroll
         for (int q = 0; q < (NB > 1 ? 3 : 1); ++q) {
-            n_surv[q] = 0;
+            if (rotated) break;
             const int bi = q == 2 ? 1 : 0, bj = q == 0 ? 0 : 1;
             const int b = 16 * bj + r16, a0 = 16 * bi + 4 * g;
             const int lim = b < m ? min(m_new, b) : 0;           // valid pairs: a < lim
@@ -1312,6 +1346,21 @@ join_reg_kernel(const float *__restrict__ X, const float *__restrict__ norms, in
             }
         }
         __syncthreads();
+        if (rotated) {
+#pragma unroll
+            for (int t = 0; t < 2; ++t) {
+                if (q_fill + 2 * EF_WAVE > q_cap) {      // a step adds at most two proposals per lane
+                    updates += drain_queue(queue, q_fill, graph, worst, K, lane, EF_WAVE);
+                    q_fill = 0;
+                    __syncthreads();
+                }
+                const int rot = 2 * g + 1 + t, b = (r16 + dirn * rot) & 15;
+                // rotation 8 meets every pair from both ends: the lower row keeps it
+                const bool mine = r16 < m && b < m && min(r16, b) < m_new && (rot != 8 || r16 < b);
+                q_fill = propose_pair(queue, q_fill, mine, two[t], r16, b, thr, uid);
+                __syncthreads();
+            }
+        }
         // ---- 3a. survivors from registers, sixteen pairs per round --------------------------
         // The four lanes r16 + 16 g (g = 0..3) of column r16 take pair p0 + r16: lane g
         // fetches the pieces it needs of rows a and b from lanes a + 16 g and b + 16 g,
@@ -1833,7 +1882,7 @@ extern "C" int efanna_nndescent(const float *X, int64_t n, int32_t d, int32_t k,
     if (max_rows > rows1 && large.lds > kLdsLimit) return EFANNA_EUNSUPPORTED;
     // joins of at most 16 vectors from registers (d <= 128): room for a whole point's proposals
     // (240) above the drain mark; the others drain between rounds as well
-    auto reg_q_cap_for = [&](int R) { return R == 16 && d <= 128 ? 512 : 128; };
+    auto reg_q_cap_for = [&](int R) { return R == 16 ? (d <= 128 ? 512 : 256) : 128; };
     auto reg_lds = [&](int R) {
         const int reg_q_cap = reg_q_cap_for(R);
         return (size_t)(4 * R + align4(R * (R - 1) / 2 + 8)) * 4 +
