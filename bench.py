@@ -55,7 +55,7 @@ def main():
     ap.add_argument("--recall-rows", type=int, default=10_000, help="0 = skip recall")
     ap.add_argument("--progress", action="store_true", help="report each phase on stderr as it ends")
     ap.add_argument("--calibrate", action="store_true",
-                    help="after the timed steps, fill and copy 256 MiB with plain torch kernels: a known "
+                    help="after the timed steps, fill 256 MiB and add a constant to 256 MiB with plain torch kernels: a known "
                          "amount of HBM traffic to scale rocprofv3's FETCH_SIZE / WRITE_SIZE counters by")
     ap.add_argument("--search", type=int, default=0, metavar="NQ",
                     help="after the build, answer NQ synthetic queries with the index (Alg. 1) and add a "
@@ -159,7 +159,7 @@ def main():
         b = torch.empty_like(a)
         a.fill_(1.0)
         torch.cuda.synchronize()
-        b.copy_(a)
+        torch.add(a, 1.0, out=b)      # an elementwise kernel (a plain copy may go to a DMA engine instead)
         torch.cuda.synchronize()
         del a, b
 
