@@ -245,6 +245,28 @@ def test_nndescent_bit_exact_every_iteration(ef, name, n, T, S, K, L, I):
     oracle.check_graph_invariants(X, ids, dists)
 
 
+@pytest.mark.parametrize("n,d,T,S,K,L,I", [
+    (3_000, 200, 2, 12, 8, 8, 3),        # long vectors with a ragged last piece (128 + 72): joins by rotations
+    (2_500, 132, 2, 16, 10, 10, 2),      # just over one piece
+    (3_000, 16, 2, 16, 50, 50, 2),       # rows and lists of exactly fifty entries: one wide read
+    (3_000, 16, 2, 16, 52, 25, 2),       # fifty and a remainder of two
+    (2_000, 24, 2, 8, 7, 9, 3),          # odd row length (rows not 16-byte aligned), L > K
+])
+def test_nndescent_more_shapes(ef, n, d, T, S, K, L, I):
+    rng = np.random.default_rng(n + d + K)
+    X = rng.standard_normal((n, d)).astype(np.float32)
+    Xd = dev(X)
+    (perm, off, nl), (operm, ooff, onl) = trees_equal(ef, X, T, S, 11)
+    graph = ef.efanna_init_graph(Xd, perm, off, nl, S, K)
+    want = oracle.init_graph(X, operm, ooff, onl, K)
+    for it in range(I):
+        stats = ef.efanna_nndescent(Xd, graph, 1, L, 11, first_iter=it)
+        want = oracle.nndescent(X, *want[:3], 1, L, 11, iter0=it)
+        ids, dists = graph_equal(ef, graph, want)
+        assert int(host(stats)[0, 0]) == int(want[3][0, 0])
+    oracle.check_graph_invariants(X, ids, dists)
+
+
 def test_nndescent_resume_and_recall(ef):
     name = "gmm10k_d32"
     p = synth.params(name)
