@@ -108,10 +108,11 @@ def test_sift100k_like_full_size_bit_exact():
     assert np.array_equal(stats.cpu().numpy()[:, 0].astype(np.uint64), want[3][:, 0])
 
 
-def _full_size_properties(name, n_rows_init, n_rows_exact):
-    """Whole path at a size the oracle cannot refine in reasonable time: trees and sampled
-    rows of the initial graph bit-exact against the oracle, the refined graph checked
-    through properties that hold at any size."""
+def _full_size_properties(name, n_rows_init, n_rows_exact, refine_with_oracle=False):
+    """Whole path at full size: trees and sampled rows of the initial graph bit-exact against
+    the oracle, the refined graph checked through properties that hold at any size, and -
+    where the oracle refines the graph in about half a minute (refine_with_oracle) - every
+    element of the refined graph against it as well."""
     from paper_1609_07228_amd import efanna
     p = synth.params(name)
     K, T, S, I, L = p["K"], p["T"], p["S"], p["I"], p["L"]
@@ -151,12 +152,17 @@ def _full_size_properties(name, n_rows_init, n_rows_exact):
     _progress(f"{name}: accuracy {r0:.3f} -> {r1:.3f}")
     assert r1 > r0 + 0.2 and r1 > 0.5
     assert np.all(np.diff(stats[2:, 1].astype(np.int64)) < 0)          # insertions dry up
+    if refine_with_oracle:
+        full = oracle.nndescent(X, *oracle.init_graph(X, operm, ooff, onl, K), I, L, synth.ALGO_SEED)
+        _progress(f"{name}: oracle refined")
+        assert np.array_equal(ids, full[0]) and dists.tobytes() == full[1].tobytes()
+        assert np.array_equal(stats[:, 0].astype(np.uint64), full[3][:, 0])
     return r1
 
 
 @pytest.mark.timeout(900)
-def test_gist1m_like_full_size_properties():
-    _full_size_properties("gist1m_like", 2000, 200)
+def test_gist1m_like_full_size_bit_exact():
+    _full_size_properties("gist1m_like", 2000, 200, refine_with_oracle=True)
 
 
 @pytest.mark.timeout(900)
