@@ -272,6 +272,28 @@ __device__ inline void init_round(const float4 (&va)[8], int n_pieces, float (&p
     }
 }
 
+// the same for two sets of sixteen rows: row r of the first against row r + T (rotation) of the second
+template <int T>
+__device__ inline void cross_round(const float4 (&va)[8], const float4 (&vb)[8], int n_pieces, float (&p)[4])
+{
+#pragma unroll
+    for (int s = 0; s < 8; ++s) {
+        if (s >= n_pieces) break;
+        float4 w = vb[s];
+        if (T != 0) {
+            w.x = __int_as_float(EF_ROW_ROR(__float_as_int(vb[s].x), T ? T : 1));
+            w.y = __int_as_float(EF_ROW_ROR(__float_as_int(vb[s].y), T ? T : 1));
+            w.z = __int_as_float(EF_ROW_ROR(__float_as_int(vb[s].z), T ? T : 1));
+            w.w = __int_as_float(EF_ROW_ROR(__float_as_int(vb[s].w), T ? T : 1));
+        }
+        const float d0 = va[s].x - w.x, d1 = va[s].y - w.y, d2 = va[s].z - w.z, d3 = va[s].w - w.w;
+        p[0] = __builtin_fmaf(d0, d0, p[0]);
+        p[1] = __builtin_fmaf(d1, d1, p[1]);
+        p[2] = __builtin_fmaf(d2, d2, p[2]);
+        p[3] = __builtin_fmaf(d3, d3, p[3]);
+    }
+}
+
 constexpr int kCandPitch = 17;      // u64 per row of the candidate table (odd: rows on different banks)
 
 __global__ void __launch_bounds__(EF_WAVE) __attribute__((amdgpu_waves_per_eu(4)))
@@ -1246,26 +1268,32 @@ join_reg_kernel(const float *__restrict__ X, const float *__restrict__ norms, in
 #pragma unroll
             for (int h = 0; h < 2; ++h) acc[q][h] = (floatx4){0.f, 0.f, 0.f, 0.f};
         float4 va[8], vb[NB > 1 ? 8 : 1];
-        // Long vectors, at most 16 of them: with the filter the rows would have to be streamed a
-        // second time for the pairs that pass it.  Instead all pairs get their fixed-order
-        // distance in this one pass, as in init_reg_kernel: eight row rotations per
-        // 128-coordinate piece meet every pair (vector instructions that hide under the gather:
-        // 512 per 8 KB of rows), the four lanes of a column add their partial sums in the fixed
-        // tree, and lane (r, g) holds the distances from row r to the rows 2g+1 and 2g+2 places
-        // on.  No Gram block, no filter.
-        constexpr bool rotated = !ONE && NB == 1;
-        float two[2] = {0.f, 0.f};
+        // Long vectors (d > 128): with the filter the rows would have to be streamed again for the
+        // pairs that pass it, once per 128 of them.  Instead every pair gets its fixed-order
+        // distance straight away, as in init_reg_kernel: row rotations per 128-coordinate piece
+        // meet the pairs (vector instructions that hide under the gather: 512 per 8 KB of rows),
+        // the four lanes of a column add their partial sums in the fixed tree, and lane (r, g)
+        // holds the distances from row r to the rows 2g+1 and 2g+2 places on.  No Gram block, no
+        // filter.  At most 16 rows: one pass, eight rotations.  17..32 rows: a first pass for the
+        // pairs inside rows 0..15 and inside rows 16..31, a second one for rows 0..15 against
+        // rotations 0..15 of rows 16..31.
+        constexpr bool rotated = !ONE;
+        float two[2] = {0.f, 0.f}, two_b[2] = {0.f, 0.f};
         if (rotated) {
-            float P[8][4];
+            float P[8][4], PB[NB > 1 ? 8 : 1][4];
 #pragma unroll
             for (int t = 0; t < 8; ++t) P[t][0] = P[t][1] = P[t][2] = P[t][3] = 0.0f;
+            if (NB > 1) {
+#pragma unroll
+                for (int t = 0; t < 8; ++t) PB[NB > 1 ? t : 0][0] = PB[NB > 1 ? t : 0][1] = PB[NB > 1 ? t : 0][2] = PB[NB > 1 ? t : 0][3] = 0.0f;
+            }
             for (int c0 = 0; c0 < d; c0 += 128) {
+                const int n_pieces = min(8, (d - c0 + 15) >> 4);
 #pragma unroll
                 for (int s = 0; s < 8; ++s) {
                     const bool in = c0 + 16 * s + 4 * g + 3 < d;      // d % 4 == 0: a piece is in or out
                     va[s] = in ? *reinterpret_cast<const float4 *>(pa + c0 + 16 * s) : make_float4(0.f, 0.f, 0.f, 0.f);
                 }
-                const int n_pieces = min(8, (d - c0 + 15) >> 4);
                 init_round<1>(va, n_pieces, P[0]);
                 init_round<2>(va, n_pieces, P[1]);
                 init_round<3>(va, n_pieces, P[2]);
@@ -1274,8 +1302,25 @@ join_reg_kernel(const float *__restrict__ X, const float *__restrict__ norms, in
                 init_round<6>(va, n_pieces, P[5]);
                 init_round<7>(va, n_pieces, P[6]);
                 init_round<8>(va, n_pieces, P[7]);
+                if (NB > 1 && need11) {      // pairs inside rows 16..31 are wanted only if new rows reach them
+                    float4 (&wb)[8] = reinterpret_cast<float4 (&)[8]>(vb);
+#pragma unroll
+                    for (int s = 0; s < 8; ++s) {
+                        const bool in = c0 + 16 * s + 4 * g + 3 < d;
+                        wb[s] = in ? *reinterpret_cast<const float4 *>(pb + c0 + 16 * s) : make_float4(0.f, 0.f, 0.f, 0.f);
+                    }
+                    init_round<1>(wb, n_pieces, PB[0]);
+                    init_round<2>(wb, n_pieces, PB[NB > 1 ? 1 : 0]);
+                    init_round<3>(wb, n_pieces, PB[NB > 1 ? 2 : 0]);
+                    init_round<4>(wb, n_pieces, PB[NB > 1 ? 3 : 0]);
+                    init_round<5>(wb, n_pieces, PB[NB > 1 ? 4 : 0]);
+                    init_round<6>(wb, n_pieces, PB[NB > 1 ? 5 : 0]);
+                    init_round<7>(wb, n_pieces, PB[NB > 1 ? 6 : 0]);
+                    init_round<8>(wb, n_pieces, PB[NB > 1 ? 7 : 0]);
+                }
             }
             reduce_rotations(P, g, two);
+            if (NB > 1) reduce_rotations(reinterpret_cast<const float (&)[8][4]>(PB), g, two_b);
         }
         for (int c0 = 0; c0 < d && !rotated; c0 += 128) {
             if (c0 + 128 <= d) {     // a whole 128-coordinate piece: no per-load bounds test
@@ -1347,18 +1392,74 @@ join_reg_kernel(const float *__restrict__ X, const float *__restrict__ norms, in
         }
         __syncthreads();
         if (rotated) {
-#pragma unroll
-            for (int t = 0; t < 2; ++t) {
-                if (q_fill + 2 * EF_WAVE > q_cap) {      // a step adds at most two proposals per lane
+            auto room = [&]() {      // a step adds at most two proposals per lane
+                if (q_fill + 2 * EF_WAVE > q_cap) {
                     updates += drain_queue(queue, q_fill, graph, worst, K, lane, EF_WAVE);
                     q_fill = 0;
                     __syncthreads();
                 }
+            };
+#pragma unroll
+            for (int t = 0; t < 2; ++t) {
                 const int rot = 2 * g + 1 + t, b = (r16 + dirn * rot) & 15;
                 // rotation 8 meets every pair from both ends: the lower row keeps it
-                const bool mine = r16 < m && b < m && min(r16, b) < m_new && (rot != 8 || r16 < b);
-                q_fill = propose_pair(queue, q_fill, mine, two[t], r16, b, thr, uid);
+                const bool once = rot != 8 || r16 < b;
+                room();
+                q_fill = propose_pair(queue, q_fill, once && r16 < m && b < m && min(r16, b) < m_new, two[t], r16, b,
+                                      thr, uid);
                 __syncthreads();
+                if (NB > 1 && need11) {
+                    room();
+                    q_fill = propose_pair(queue, q_fill, once && 16 + r16 < m && 16 + b < m && 16 + min(r16, b) < m_new,
+                                          two_b[t], 16 + r16, 16 + b, thr, uid);
+                    __syncthreads();
+                }
+            }
+            if (NB > 1) {
+                // second pass: row r of rows 0..15 against rows 16 + (r + T) of rows 16..31, T = 0..15
+                float PX[2][8][4];
+#pragma unroll
+                for (int h = 0; h < 2; ++h)
+#pragma unroll
+                    for (int t = 0; t < 8; ++t) PX[h][t][0] = PX[h][t][1] = PX[h][t][2] = PX[h][t][3] = 0.0f;
+                float4 (&wb)[8] = reinterpret_cast<float4 (&)[8]>(vb);
+                for (int c0 = 0; c0 < d; c0 += 128) {
+                    const int n_pieces = min(8, (d - c0 + 15) >> 4);
+#pragma unroll
+                    for (int s = 0; s < 8; ++s) {
+                        const bool in = c0 + 16 * s + 4 * g + 3 < d;
+                        va[s] = in ? *reinterpret_cast<const float4 *>(pa + c0 + 16 * s) : make_float4(0.f, 0.f, 0.f, 0.f);
+                        wb[s] = in ? *reinterpret_cast<const float4 *>(pb + c0 + 16 * s) : make_float4(0.f, 0.f, 0.f, 0.f);
+                    }
+                    cross_round<0>(va, wb, n_pieces, PX[0][0]);
+                    cross_round<1>(va, wb, n_pieces, PX[0][1]);
+                    cross_round<2>(va, wb, n_pieces, PX[0][2]);
+                    cross_round<3>(va, wb, n_pieces, PX[0][3]);
+                    cross_round<4>(va, wb, n_pieces, PX[0][4]);
+                    cross_round<5>(va, wb, n_pieces, PX[0][5]);
+                    cross_round<6>(va, wb, n_pieces, PX[0][6]);
+                    cross_round<7>(va, wb, n_pieces, PX[0][7]);
+                    cross_round<8>(va, wb, n_pieces, PX[1][0]);
+                    cross_round<9>(va, wb, n_pieces, PX[1][1]);
+                    cross_round<10>(va, wb, n_pieces, PX[1][2]);
+                    cross_round<11>(va, wb, n_pieces, PX[1][3]);
+                    cross_round<12>(va, wb, n_pieces, PX[1][4]);
+                    cross_round<13>(va, wb, n_pieces, PX[1][5]);
+                    cross_round<14>(va, wb, n_pieces, PX[1][6]);
+                    cross_round<15>(va, wb, n_pieces, PX[1][7]);
+                }
+#pragma unroll
+                for (int h = 0; h < 2; ++h) {
+                    float cross[2];
+                    reduce_rotations(PX[h], g, cross);      // rotations 8h + 2g and 8h + 2g + 1
+#pragma unroll
+                    for (int t = 0; t < 2; ++t) {
+                        const int rot = 8 * h + 2 * g + t, b = 16 + ((r16 + dirn * rot) & 15);
+                        room();
+                        q_fill = propose_pair(queue, q_fill, b < m && r16 < m_new, cross[t], r16, b, thr, uid);
+                        __syncthreads();
+                    }
+                }
             }
         }
         // ---- 3a. survivors from registers, sixteen pairs per round --------------------------
@@ -1409,105 +1510,6 @@ join_reg_kernel(const float *__restrict__ X, const float *__restrict__ norms, in
                         updates += drain_queue(queue, q_fill, graph, worst, K, lane, EF_WAVE);
                         q_fill = 0;
                         __syncthreads();
-                    }
-                }
-            }
-        }
-        // ---- 3b. d > 128: the rows are streamed once more, 128 coordinates at a time, and up to
-        // eight rounds of sixteen surviving pairs collect their partial sums side by side -----------
-        if (!ONE) {
-#pragma unroll
-            for (int q = 0; q < (NB > 1 ? 3 : 1); ++q) {
-                const int bi = q == 2 ? 1 : 0, bj = q == 0 ? 0 : 1;
-                const int n_q = n_surv[q];
-                // a few pairs: cheaper to read just their rows, one 16-lane group per pair
-                const int n_few = n_q <= kFewPairs * NB ? n_q : 0;
-                for (int p0 = 0; p0 < n_few; p0 += 4) {
-                    const u32 ent = surv[kSurvBase[q] + min(p0 + grp, n_few - 1)];
-                    const int a = 16 * bi + (int)(ent & 15), b = 16 * bj + (int)((ent >> 8) & 15);
-                    const float *ra = X + (size_t)uid[a] * d + gl, *rb = X + (size_t)uid[b] * d + gl;
-                    float accd = 0.0f;
-                    for (int j0 = 0; j0 < d; j0 += 128) {
-                        float xa[8], xb[8];
-#pragma unroll
-                        for (int s = 0; s < 8; ++s) {
-                            const bool in = j0 + 16 * s + gl < d;
-                            xa[s] = in ? ra[j0 + 16 * s] : 0.0f;
-                            xb[s] = in ? rb[j0 + 16 * s] : 0.0f;
-                        }
-#pragma unroll
-                        for (int s = 0; s < 8; ++s) {
-                            const float diff = xa[s] - xb[s];     // 0 beyond d: leaves the sum unchanged
-                            accd = __builtin_fmaf(diff, diff, accd);
-                        }
-                    }
-                    const float dist = ef_group_reduce16(accd);
-                    q_fill = propose_pair(queue, q_fill, gl == 0 && p0 + grp < n_few, dist, a, b, thr, uid);
-                    __syncthreads();
-                    if (q_fill + 32 > q_cap) {
-                        updates += drain_queue(queue, q_fill, graph, worst, K, lane, EF_WAVE);
-                        q_fill = 0;
-                        __syncthreads();
-                    }
-                }
-                for (int g0 = n_few; g0 < n_q; g0 += 128) {
-                    const int n_rounds = min(8, (n_q - g0 + 15) >> 4);
-                    float ps[8][4];
-#pragma unroll
-                    for (int r = 0; r < 8; ++r) ps[r][0] = ps[r][1] = ps[r][2] = ps[r][3] = 0.f;
-                    for (int c0 = 0; c0 < d; c0 += 128) {
-#pragma unroll
-                        for (int s = 0; s < 8; ++s) {
-                            const bool in = c0 + 16 * s + 4 * g + 3 < d;      // d % 4 == 0: a piece is in or out
-                            if (bi == 0 || bj == 0)
-                                va[s] = in ? *reinterpret_cast<const float4 *>(pa + c0 + 16 * s) : make_float4(0.f, 0.f, 0.f, 0.f);
-                            if (NB > 1 && (bi == 1 || bj == 1))
-                                vb[NB > 1 ? s : 0] = in ? *reinterpret_cast<const float4 *>(pb + c0 + 16 * s) : make_float4(0.f, 0.f, 0.f, 0.f);
-                        }
-#pragma unroll
-                        for (int r = 0; r < 8; ++r) {
-                            if (r >= n_rounds) break;
-                            const u32 ent = surv[kSurvBase[q] + min(g0 + 16 * r + r16, n_q - 1)];
-                            const int src_a = (int)(ent & 15) + 16 * g, src_b = (int)((ent >> 8) & 15) + 16 * g;
-#pragma unroll
-                            for (int s = 0; s < 8; ++s) {
-                                if (c0 + 16 * s >= d) break;
-                                const float4 own = bi == 0 ? va[s] : vb[NB > 1 ? s : 0];
-                                const float4 oth = bj == 0 ? va[s] : vb[NB > 1 ? s : 0];
-                                const float d0 = __shfl(own.x, src_a, EF_WAVE) - __shfl(oth.x, src_b, EF_WAVE);
-                                const float d1 = __shfl(own.y, src_a, EF_WAVE) - __shfl(oth.y, src_b, EF_WAVE);
-                                const float d2 = __shfl(own.z, src_a, EF_WAVE) - __shfl(oth.z, src_b, EF_WAVE);
-                                const float d3 = __shfl(own.w, src_a, EF_WAVE) - __shfl(oth.w, src_b, EF_WAVE);
-                                ps[r][0] = __builtin_fmaf(d0, d0, ps[r][0]);
-                                ps[r][1] = __builtin_fmaf(d1, d1, ps[r][1]);
-                                ps[r][2] = __builtin_fmaf(d2, d2, ps[r][2]);
-                                ps[r][3] = __builtin_fmaf(d3, d3, ps[r][3]);
-                            }
-                        }
-                    }
-#pragma unroll
-                    for (int r = 0; r < 8; ++r) {
-                        if (r >= n_rounds) break;
-                        float p0s = ps[r][0], p1s = ps[r][1], p2s = ps[r][2], p3s = ps[r][3];
-                        p0s += __shfl_xor(p0s, 32, EF_WAVE);
-                        p1s += __shfl_xor(p1s, 32, EF_WAVE);
-                        p2s += __shfl_xor(p2s, 32, EF_WAVE);
-                        p3s += __shfl_xor(p3s, 32, EF_WAVE);
-                        p0s += __shfl_xor(p0s, 16, EF_WAVE);
-                        p1s += __shfl_xor(p1s, 16, EF_WAVE);
-                        p2s += __shfl_xor(p2s, 16, EF_WAVE);
-                        p3s += __shfl_xor(p3s, 16, EF_WAVE);
-                        const float dist = (p0s + p2s) + (p1s + p3s);
-                        const int pidx = g0 + 16 * r + r16;
-                        const u32 ent = surv[kSurvBase[q] + min(pidx, n_q - 1)];
-                        q_fill = propose_pair(queue, q_fill, pidx < n_q && g == 0, dist, 16 * bi + (int)(ent & 15),
-                                              16 * bj + (int)((ent >> 8) & 15), thr, uid);
-                        __syncthreads();
-                        if (q_fill + 32 > q_cap) {      // a round adds at most two proposals per pair
-                            updates += drain_queue(queue, q_fill, graph, worst, K, lane, EF_WAVE);
-                            q_fill = 0;
-                            __syncthreads();
-                        }
                     }
                 }
             }
@@ -1882,7 +1884,7 @@ extern "C" int efanna_nndescent(const float *X, int64_t n, int32_t d, int32_t k,
     if (max_rows > rows1 && large.lds > kLdsLimit) return EFANNA_EUNSUPPORTED;
     // joins of at most 16 vectors from registers (d <= 128): room for a whole point's proposals
     // (240) above the drain mark; the others drain between rounds as well
-    auto reg_q_cap_for = [&](int R) { return R == 16 ? (d <= 128 ? 512 : 256) : 128; };
+    auto reg_q_cap_for = [&](int R) { return R == 16 ? (d <= 128 ? 512 : 256) : (d <= 128 ? 128 : 384); };
     auto reg_lds = [&](int R) {
         const int reg_q_cap = reg_q_cap_for(R);
         return (size_t)(4 * R + align4(R * (R - 1) / 2 + 8)) * 4 +
