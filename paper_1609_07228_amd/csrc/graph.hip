@@ -280,7 +280,7 @@ __device__ inline void cross_round(const float4 (&va)[8], const float4 (&vb)[8],
     for (int s = 0; s < 8; ++s) {
         if (s >= n_pieces) break;
         float4 w = vb[s];
-        if (T != 0) {
+        if (T != 0) {      // (T ? T : 1: the rotation count is an immediate and 0 is not a valid one, used or not)
             w.x = __int_as_float(EF_ROW_ROR(__float_as_int(vb[s].x), T ? T : 1));
             w.y = __int_as_float(EF_ROW_ROR(__float_as_int(vb[s].y), T ? T : 1));
             w.z = __int_as_float(EF_ROW_ROR(__float_as_int(vb[s].z), T ? T : 1));
