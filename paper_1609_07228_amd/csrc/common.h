@@ -319,6 +319,114 @@ __device__ inline bool ef_bounded_insert(u64 *list, int cap, u64 key, int ignore
     return ef_bounded_insert_t<false>(list, cap, key, ignore, new_max);
 }
 
+// ---- the same insertion by a group of sixteen lanes (long rows) ----------------------------
+// n (1..4) pieces from n addresses, in flight together
+__device__ inline void ef_load_pieces_at(const void *p0, const void *p1, const void *p2, const void *p3,
+                                         int n, ef_u32x4 (&q)[4])
+{
+    switch (n) {
+    case 1:
+        asm volatile(
+                     "global_load_dwordx4 %0, %1, off sc1\n\t"
+                     "s_waitcnt vmcnt(0)"
+                     : "=&v"(q[0])
+                     : "v"(p0)
+                     : "memory");
+        break;
+    case 2:
+        asm volatile(
+                     "global_load_dwordx4 %0, %2, off sc1\n\t"
+                     "global_load_dwordx4 %1, %3, off sc1\n\t"
+                     "s_waitcnt vmcnt(0)"
+                     : "=&v"(q[0]), "=&v"(q[1])
+                     : "v"(p0), "v"(p1)
+                     : "memory");
+        break;
+    case 3:
+        asm volatile(
+                     "global_load_dwordx4 %0, %3, off sc1\n\t"
+                     "global_load_dwordx4 %1, %4, off sc1\n\t"
+                     "global_load_dwordx4 %2, %5, off sc1\n\t"
+                     "s_waitcnt vmcnt(0)"
+                     : "=&v"(q[0]), "=&v"(q[1]), "=&v"(q[2])
+                     : "v"(p0), "v"(p1), "v"(p2)
+                     : "memory");
+        break;
+    default:
+        asm volatile(
+                     "global_load_dwordx4 %0, %4, off sc1\n\t"
+                     "global_load_dwordx4 %1, %5, off sc1\n\t"
+                     "global_load_dwordx4 %2, %6, off sc1\n\t"
+                     "global_load_dwordx4 %3, %7, off sc1\n\t"
+                     "s_waitcnt vmcnt(0)"
+                     : "=&v"(q[0]), "=&v"(q[1]), "=&v"(q[2]), "=&v"(q[3])
+                     : "v"(p0), "v"(p1), "v"(p2), "v"(p3)
+                     : "memory");
+    }
+}
+
+// All sixteen lanes of a group (lane gl = 0..15 of it) call this with the same arguments and get
+// the same result.  Lane gl reads the 16-byte pieces gl, gl + 16, ... of the row, so that the
+// group fetches 256 contiguous bytes per load: a quarter of the memory transactions that a lane
+// reading the whole row alone needs, and one round trip for rows of up to 128 entries.  The
+// row must be 16-byte aligned and of even length; the group's lanes must all be active.
+__device__ inline bool ef_bounded_insert_g16(u64 *list, int cap, u64 key, int ignore, u64 *new_max, int gl)
+{
+    const u64 kcmp = key >> ignore;
+    const int np = cap >> 1;
+    for (;;) {
+        u64 mx = 0, mx2 = 0;
+        int ms = 0;
+        bool dup = false;
+        for (int p0 = 0; p0 < np; p0 += 64) {
+            const int n_ld = min(4, (np - p0 + 15) >> 4);
+            ef_u32x4 q[4];
+            const ef_u32x4 *row = reinterpret_cast<const ef_u32x4 *>(list);
+            // pieces beyond the row read its last piece again and are not looked at
+            ef_load_pieces_at(row + min(p0 + gl, np - 1), row + min(p0 + gl + 16, np - 1),
+                              row + min(p0 + gl + 32, np - 1), row + min(p0 + gl + 48, np - 1), n_ld, q);
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                const int piece = p0 + gl + 16 * k;
+                if (k >= n_ld || piece >= np) continue;
+                const u64 e2[2] = {((u64)q[k].y << 32) | q[k].x, ((u64)q[k].w << 32) | q[k].z};
+#pragma unroll
+                for (int h = 0; h < 2; ++h) {
+                    dup |= (e2[h] >> ignore) == kcmp;
+                    if (e2[h] > mx) {
+                        mx2 = mx;
+                        mx = e2[h];
+                        ms = 2 * piece + h;
+                    } else if (e2[h] > mx2) {
+                        mx2 = e2[h];
+                    }
+                }
+            }
+        }
+        // the group's largest and second largest entry (entries of a row are distinct)
+        for (int m = 8; m >= 1; m >>= 1) {
+            const u64 omx = __shfl_xor(mx, m, 16), omx2 = __shfl_xor(mx2, m, 16);
+            const int oms = __shfl_xor(ms, m, 16);
+            dup |= (bool)__shfl_xor((int)dup, m, 16);
+            if (omx > mx) {
+                mx2 = mx > omx2 ? mx : omx2;
+                mx = omx;
+                ms = oms;
+            } else if (omx > mx2) {
+                mx2 = omx;
+            }
+        }
+        if (dup || kcmp >= (mx >> ignore)) return false;
+        u64 seen = 0;
+        if (gl == 0) seen = atomicCAS(list + ms, mx, key);
+        seen = __shfl(seen, 0, 16);
+        if (seen == mx) {
+            *new_max = key > mx2 ? key : mx2;
+            return true;
+        }
+    }
+}
+
 // ---- wave utilities ---------------------------------------------------------------------
 __device__ inline int ef_lane() { return (int)(threadIdx.x & (EF_WAVE - 1)); }
 

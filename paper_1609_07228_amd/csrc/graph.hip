@@ -136,6 +136,24 @@ __device__ inline int drain_queue(const Proposal *queue, int count, u64 *graph, 
     return updates;
 }
 
+// The same for long rows (even length, 16-byte aligned): a group of sixteen threads per
+// proposal (nthr a multiple of 16; all threads of the block call this together).
+__device__ inline int drain_queue_g16(const Proposal *queue, int count, u64 *graph, u32 *worst, int K,
+                                      int tid, int nthr)
+{
+    int updates = 0;
+    const int gl = tid & 15;
+    for (int e = tid >> 4; e < count; e += nthr >> 4) {
+        const Proposal p = queue[e];
+        u64 new_max;
+        if (ef_bounded_insert_g16(graph + (size_t)p.target * K, K, p.key, 1, &new_max, gl) && gl == 0) {
+            atomicMin(worst + p.target, ef_dist_bits(new_max));
+            ++updates;
+        }
+    }
+    return updates;
+}
+
 // ---------------------------------------------------------------------------------------
 // Alg. 3 at the leaves, one tree per launch, one block per leaf (64 threads per 16 leaf
 // slots).  Within one tree every point lies in exactly one leaf, so a block owns the graph
@@ -1145,7 +1163,9 @@ __global__ void __launch_bounds__(512) join_kernel(const float *__restrict__ X, 
                     }
                     __syncthreads();
                     // ---- 4. drain -----------------------------------------------------------
-                    updates += drain_queue<WIDE>(lds.queue, lds.meta[3], graph, worst, K, tid, nthr);
+                    updates += WIDE && (K & 1) == 0 && ((uintptr_t)graph & 15) == 0
+                                   ? drain_queue_g16(lds.queue, lds.meta[3], graph, worst, K, tid, nthr)
+                                   : drain_queue<WIDE>(lds.queue, lds.meta[3], graph, worst, K, tid, nthr);
                     __syncthreads();
                     if (tid == 0) lds.meta[3] = 0;
                     __syncthreads();
