@@ -76,3 +76,29 @@ def test_argument_errors_are_caught_on_the_host(lib):
     assert lib.efanna_get_graph(null, 10, 4, one, one, None, None) == -1
     assert lib.efanna_set_graph(one, 10, 0, one, one, None, None) == -1
     assert lib.efanna_pair_distances(one, 10, 4, null, one, 5, one, None) == -1
+
+
+def test_bench_refuses_more_than_one_gpu_and_has_no_cpu_fallback():
+    import subprocess
+    import sys
+    bench = os.path.join(ROOT, "bench.py")
+    run = subprocess.run([sys.executable, bench, "--gpus", "2"], capture_output=True, text=True, timeout=120)
+    assert run.returncode == 2 and "one GPU" in run.stderr and run.stdout.strip() == ""
+    import torch
+    if not torch.cuda.is_available():      # on a box without a GPU the bench must stop, not fall back
+        run = subprocess.run([sys.executable, bench, "--steps", "1", "--warmup", "0"], capture_output=True,
+                             text=True, timeout=300)
+        assert run.returncode == 3 and "no CPU fallback" in run.stderr and run.stdout.strip() == ""
+
+
+def test_product_path_does_not_import_the_oracle():
+    """Only tests, the smoke check and the bench's cpu_baseline leg may touch oracle/."""
+    pkg = os.path.join(ROOT, "paper_1609_07228_amd")
+    for dirpath, _, files in os.walk(pkg):
+        for f in files:
+            if f.endswith((".py", ".hip", ".h", ".c", ".cpp")):
+                text = open(os.path.join(dirpath, f)).read()
+                assert not re.search(r"^\s*(import|from)\s+oracle\b|#include.*oracle|libefanna_oracle", text, flags=re.M), \
+                    os.path.join(dirpath, f)
+    bench = open(os.path.join(ROOT, "bench.py")).read()
+    assert bench.count("import oracle") == 1 and "if args.cpu_rows > 0:" in bench
