@@ -251,6 +251,9 @@ def test_nndescent_bit_exact_every_iteration(ef, name, n, T, S, K, L, I):
     (3_000, 16, 2, 16, 50, 50, 2),       # rows and lists of exactly fifty entries: one wide read
     (3_000, 16, 2, 16, 52, 25, 2),       # fifty and a remainder of two
     (2_000, 24, 2, 8, 7, 9, 3),          # odd row length (rows not 16-byte aligned), L > K
+    (12, 4, 2, 3, 10, 10, 3),            # hardly more points than K (the library wants k < n)
+    (33, 8, 1, 64, 5, 5, 2),             # one leaf holds everything
+    (65, 4, 3, 1, 4, 2, 4),              # leaves of one point: the initial graph is empty
 ])
 def test_nndescent_more_shapes(ef, n, d, T, S, K, L, I):
     rng = np.random.default_rng(n + d + K)
