@@ -7,6 +7,8 @@
 // values feed 16 fused multiply-adds per lane and step), and a transposed butterfly
 // leaves the finished distance of pair l in lane l.  Each lane then offers its pair to
 // the two rows concerned through the lock-free bounded insertion.
+#include <vector>
+
 #include "common.h"
 
 namespace {
@@ -1930,10 +1932,22 @@ extern "C" int efanna_nndescent(const float *X, int64_t n, int32_t d, int32_t k,
     norms_kernel<<<grid_for((size_t)n * 16, kBlock), kBlock, 0, st>>>(X, (int)n, d, w.norms);
     if (stats) zero_u64_kernel<<<grid_for((size_t)iters * 4 + 1, kBlock), kBlock, 0, st>>>(stats, iters * 4);
     // optional phase timing: events around the sampling and the join of every iteration
+    struct PhaseEvents {      // destroyed on every way out of the call
+        std::vector<hipEvent_t> list;
+        ~PhaseEvents()
+        {
+            for (hipEvent_t e : list) (void)hipEventDestroy(e);
+        }
+    } events;
     hipEvent_t *ev = nullptr;
     if (phase_ms && iters > 0) {
-        ev = new hipEvent_t[(size_t)iters * 5];
-        for (int e = 0; e < iters * 5; ++e) EF_HIP_CHECK(hipEventCreate(&ev[e]));
+        events.list.reserve((size_t)iters * 5);
+        for (int e = 0; e < iters * 5; ++e) {
+            hipEvent_t one;
+            EF_HIP_CHECK(hipEventCreate(&one));
+            events.list.push_back(one);
+        }
+        ev = events.list.data();
     }
     int done = 0;
     for (int it = 0; it < iters; ++it) {
@@ -2028,8 +2042,6 @@ extern "C" int efanna_nndescent(const float *X, int64_t n, int32_t d, int32_t k,
                     phase_ms[4 * it + ph] = 0.0f;
             }
         }
-        for (int e = 0; e < iters * 5; ++e) (void)hipEventDestroy(ev[e]);
-        delete[] ev;
     }
     return EFANNA_OK;
 }
