@@ -1538,8 +1538,11 @@ join_reg_kernel(const float *__restrict__ X, const float *__restrict__ norms, in
             }
         }
         if (q_fill >= q_cap / 2) {
-            updates += drain_queue(queue, q_fill, graph, worst, K, lane, EF_WAVE);
-            q_fill = 0;
+            // whole passes of 64 only, from the end of the queue: what is left waits for the next
+            // drain (a pass costs its two round trips however few lanes it fills)
+            const int rest = q_fill & (EF_WAVE - 1);
+            updates += drain_queue(queue + rest, q_fill - rest, graph, worst, K, lane, EF_WAVE);
+            q_fill = rest;
         }
         __syncthreads();
     }
