@@ -159,61 +159,77 @@ __global__ void roots_kernel(Node *nodes, int *dims, int *node_of, unsigned char
     }
 }
 
+// `tiles` consecutive tiles of kBlock positions per block.  Near the root every tile of a block
+// lies in the same node: their sums are carried in a register and go out as one atomic (the
+// few node records of the top levels would otherwise take one atomic per tile, all to the same
+// few addresses, which serialise).
 __global__ void __launch_bounds__(kBlock)
 sum_kernel(const float *__restrict__ XT, int n, const int *__restrict__ perm,
            const int *__restrict__ node_of, Node *nodes, const int *__restrict__ dims,
-           float *__restrict__ val, size_t total, Counters *c, int level)
+           float *__restrict__ val, size_t total, Counters *c, int level, int tiles)
 {
     if (blockIdx.x == 0 && threadIdx.x == 0) c->n_nodes[(level + 1) & 1] = 0;      // filled by children_kernel
     __shared__ long long wave_tot[kBlock / EF_WAVE];
     __shared__ int wave_node[kBlock / EF_WAVE];
-    size_t p = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
-    int s = -1;
-    long long q = 0;
-    if (p < total) {
-        s = node_of[p];
-        if (s >= 0) {
-            // the split dimension comes from its own array: the node records are being hit
-            // by the sum atomics of this very kernel, and reads of such a line crawl
-            int dim = dims[s];
-            if (dim >= 0) {
-                float x = XT[(size_t)dim * n + perm[p]];
-                val[p] = x;
-                q = ef_quantise(x);
-            } else {
-                s = -1;
+    int carry_node = -1;          // thread 0: node and sum of the uniform tiles seen so far
+    long long carry = 0;
+    for (int tile = 0; tile < tiles; ++tile) {
+        const size_t p = ((size_t)blockIdx.x * tiles + tile) * kBlock + threadIdx.x;
+        if (((size_t)blockIdx.x * tiles + tile) * kBlock >= total) break;
+        int s = -1;
+        long long q = 0;
+        if (p < total) {
+            s = node_of[p];
+            if (s >= 0) {
+                // the split dimension comes from its own array: the node records are being hit
+                // by the sum atomics of this very kernel, and reads of such a line crawl
+                int dim = dims[s];
+                if (dim >= 0) {
+                    float x = XT[(size_t)dim * n + perm[p]];
+                    val[p] = x;
+                    q = ef_quantise(x);
+                } else {
+                    s = -1;
+                }
             }
         }
-    }
-    // Positions of a node are contiguous, so inside a wave equal node indices form runs.
-    // Segmented inclusive scan over the runs; the last lane of a run then holds its sum.
-    const int lane = ef_lane(), wave = threadIdx.x / EF_WAVE;
-    for (int o = 1; o < EF_WAVE; o <<= 1) {
-        const long long q_up = __shfl_up(q, o, EF_WAVE);
-        const int s_up = __shfl_up(s, o, EF_WAVE);
-        if (lane >= o && s_up == s) q += q_up;
-    }
-    const int s_next = __shfl_down(s, 1, EF_WAVE);
-    const bool tail = lane == EF_WAVE - 1 || s_next != s;
-    const int s_first = __shfl(s, 0, EF_WAVE);
-    const bool uniform = __all(s == s_first);      // the whole wave lies in one node
-    if (lane == EF_WAVE - 1) {
-        wave_tot[wave] = q;
-        wave_node[wave] = uniform ? s : -2;
-    }
-    __syncthreads();
-    // near the root a whole block lies in one node: one atomic for the block
-    bool block_uniform = true;
-    for (int w = 0; w < kBlock / EF_WAVE; ++w) block_uniform &= wave_node[w] == wave_node[0] && wave_node[0] != -2;
-    if (block_uniform) {
-        if (threadIdx.x == 0 && wave_node[0] >= 0) {
-            long long tot = 0;
-            for (int w = 0; w < kBlock / EF_WAVE; ++w) tot += wave_tot[w];
-            atomicAdd((u64 *)&nodes[wave_node[0]].sum, (u64)tot);
+        // Positions of a node are contiguous, so inside a wave equal node indices form runs.
+        // Segmented inclusive scan over the runs; the last lane of a run then holds its sum.
+        const int lane = ef_lane(), wave = threadIdx.x / EF_WAVE;
+        for (int o = 1; o < EF_WAVE; o <<= 1) {
+            const long long q_up = __shfl_up(q, o, EF_WAVE);
+            const int s_up = __shfl_up(s, o, EF_WAVE);
+            if (lane >= o && s_up == s) q += q_up;
         }
-    } else if (tail && s >= 0) {
-        atomicAdd((u64 *)&nodes[s].sum, (u64)q);
+        const int s_next = __shfl_down(s, 1, EF_WAVE);
+        const bool tail = lane == EF_WAVE - 1 || s_next != s;
+        const int s_first = __shfl(s, 0, EF_WAVE);
+        const bool uniform = __all(s == s_first);      // the whole wave lies in one node
+        if (lane == EF_WAVE - 1) {
+            wave_tot[wave] = q;
+            wave_node[wave] = uniform ? s : -2;
+        }
+        __syncthreads();
+        // near the root a whole tile lies in one node: one sum for the tile
+        bool tile_uniform = true;
+        for (int w = 0; w < kBlock / EF_WAVE; ++w) tile_uniform &= wave_node[w] == wave_node[0] && wave_node[0] != -2;
+        if (tile_uniform) {
+            if (threadIdx.x == 0 && wave_node[0] >= 0) {
+                long long tot = 0;
+                for (int w = 0; w < kBlock / EF_WAVE; ++w) tot += wave_tot[w];
+                if (wave_node[0] != carry_node) {
+                    if (carry_node >= 0) atomicAdd((u64 *)&nodes[carry_node].sum, (u64)carry);
+                    carry_node = wave_node[0];
+                    carry = 0;
+                }
+                carry += tot;
+            }
+        } else if (tail && s >= 0) {
+            atomicAdd((u64 *)&nodes[s].sum, (u64)q);
+        }
+        __syncthreads();      // wave_tot / wave_node are free for the next tile
     }
+    if (threadIdx.x == 0 && carry_node >= 0) atomicAdd((u64 *)&nodes[carry_node].sum, (u64)carry);
 }
 
 // predicate sources for the scan
@@ -759,8 +775,10 @@ extern "C" int efanna_build_trees(const float *X, int64_t n, int32_t d, int32_t 
     const int grid_nodes = (max_live + kBlock - 1) / kBlock;
     int n_cur = n > fin ? T : 0;
     for (int level = 0; n_cur > 0; ++level) {
-        sum_kernel<<<grid_pos, kBlock, 0, st>>>(w.xt, (int)n, perm_cur, node_cur, nodes_cur, dims_cur, w.val,
-                                                total, w.counters, level);
+        // sixteen tiles per block while nodes are a million positions and more (levels 0..3 of the headline)
+        const int tiles = (total >> level) / (size_t)T >= (size_t)kBlock * 256 ? 16 : 1;
+        sum_kernel<<<(grid_pos + tiles - 1) / tiles, kBlock, 0, st>>>(w.xt, (int)n, perm_cur, node_cur, nodes_cur,
+                                                                      dims_cur, w.val, total, w.counters, level, tiles);
         LeftPred pred{node_cur, nodes_cur, w.val};
         device_scan(pred, total, w.block_sums, w.lcount, st);
         children_kernel<<<grid_nodes, kBlock, 0, st>>>(
