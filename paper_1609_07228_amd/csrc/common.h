@@ -252,10 +252,56 @@ __device__ inline void ef_load_row_pieces(const void *p, int np, ef_u32x4 (&q)[8
 //
 // Returns true if the key went in; *new_max then holds an upper bound of the list's
 // maximum after the insertion.
-template <bool WIDE>
+template <bool WIDE, bool REFINE = false>
 __device__ inline bool ef_bounded_insert_t(u64 *list, int cap, u64 key, int ignore, u64 *new_max)
 {
     const u64 kcmp = key >> ignore;
+    if (REFINE && cap <= 16) {
+        // Short lists: one snapshot.  A compare-and-swap that fails hands back what the slot
+        // holds now, which is all that is needed to go on: the snapshot is corrected in that
+        // one slot and the maximum taken again, without a second read of the list.  (The
+        // argument above only needs every slot to have been read at some time before the swap
+        // that succeeds, and the swapped slot to hold the snapshot's maximum.)
+        const bool wide = (cap & 1) == 0 && ((uintptr_t)list & 15) == 0;
+        u64 e[16];
+        if (wide) {
+            ef_u32x4 q[8];
+            ef_load_row_pieces(list, cap >> 1, q);
+#pragma unroll
+            for (int k = 0; k < 8; ++k) {
+                e[2 * k] = ((u64)q[k].y << 32) | q[k].x;
+                e[2 * k + 1] = ((u64)q[k].w << 32) | q[k].z;
+            }
+        } else {
+#pragma unroll
+            for (int k = 0; k < 16; ++k) e[k] = k < cap ? ef_load_coherent(list + k) : 0;
+        }
+        for (;;) {
+            u64 mx = 0, mx2 = 0;
+            int ms = 0;
+            bool dup = false;
+#pragma unroll
+            for (int k = 0; k < 16; ++k) {
+                if (k >= cap) break;
+                dup |= (e[k] >> ignore) == kcmp;
+                if (e[k] > mx) {
+                    mx2 = mx;
+                    mx = e[k];
+                    ms = k;
+                } else if (e[k] > mx2) {
+                    mx2 = e[k];
+                }
+            }
+            if (dup || kcmp >= (mx >> ignore)) return false;
+            const u64 seen = atomicCAS(list + ms, mx, key);
+            if (seen == mx) {
+                *new_max = key > mx2 ? key : mx2;
+                return true;
+            }
+#pragma unroll
+            for (int k = 0; k < 16; ++k) e[k] = k == ms ? seen : e[k];
+        }
+    }
     for (;;) {
         u64 mx = 0, mx2 = 0;
         int ms = 0;

@@ -123,7 +123,7 @@ __device__ inline void gather_rows(const float *__restrict__ X, int d, int strid
 
 // Drain the proposal queue: every thread applies whole proposals on its own, so all the
 // row reads of up to blockDim proposals are in flight together.
-template <bool WIDE = false>
+template <bool WIDE = false, bool REFINE = false>
 __device__ inline int drain_queue(const Proposal *queue, int count, u64 *graph, u32 *worst, int K,
                                   int tid, int nthr)
 {
@@ -131,7 +131,7 @@ __device__ inline int drain_queue(const Proposal *queue, int count, u64 *graph, 
     for (int e = tid; e < count; e += nthr) {
         const Proposal p = queue[e];
         u64 new_max;
-        if (ef_bounded_insert_t<WIDE>(graph + (size_t)p.target * K, K, p.key, 1, &new_max)) {
+        if (ef_bounded_insert_t<WIDE, REFINE>(graph + (size_t)p.target * K, K, p.key, 1, &new_max)) {
             atomicMin(worst + p.target, ef_dist_bits(new_max));
             ++updates;
         }
@@ -897,7 +897,7 @@ reverse_overflow_kernel(const Overflow *__restrict__ overflow, size_t ovf_region
         u64 *bound = list_max + (size_t)ov.which * n + ov.target;
         if (ov.key >= ef_load_coherent(bound)) continue;
         u64 nm;
-        if (ef_bounded_insert_t<WIDE>((ov.which ? rold : rnew) + (size_t)ov.target * L, L, ov.key, 0, &nm))
+        if (ef_bounded_insert_t<WIDE, true>((ov.which ? rold : rnew) + (size_t)ov.target * L, L, ov.key, 0, &nm))
             atomicMin(bound, nm);
     }
 }
@@ -1417,7 +1417,7 @@ join_reg_kernel(const float *__restrict__ X, const float *__restrict__ norms, in
         if (rotated) {
             auto room = [&]() {      // a step adds at most two proposals per lane
                 if (q_fill + 2 * EF_WAVE > q_cap) {
-                    updates += drain_queue(queue, q_fill, graph, worst, K, lane, EF_WAVE);
+                    updates += drain_queue<false, NB == 1>(queue, q_fill, graph, worst, K, lane, EF_WAVE);
                     q_fill = 0;
                     __syncthreads();
                 }
@@ -1530,7 +1530,7 @@ join_reg_kernel(const float *__restrict__ X, const float *__restrict__ norms, in
                     // NB = 1: the queue is sized so that a point's proposals always fit (at most 240
                     // on top of fewer than q_cap / 2): no drain while the operands are live
                     if (NB > 1 && q_fill + 32 > q_cap) {      // a round adds at most two proposals per pair
-                        updates += drain_queue(queue, q_fill, graph, worst, K, lane, EF_WAVE);
+                        updates += drain_queue<false, NB == 1>(queue, q_fill, graph, worst, K, lane, EF_WAVE);
                         q_fill = 0;
                         __syncthreads();
                     }
@@ -1541,13 +1541,13 @@ join_reg_kernel(const float *__restrict__ X, const float *__restrict__ norms, in
             // whole passes of 64 only, from the end of the queue: what is left waits for the next
             // drain (a pass costs its two round trips however few lanes it fills)
             const int rest = q_fill & (EF_WAVE - 1);
-            updates += drain_queue(queue + rest, q_fill - rest, graph, worst, K, lane, EF_WAVE);
+            updates += drain_queue<false, NB == 1>(queue + rest, q_fill - rest, graph, worst, K, lane, EF_WAVE);
             q_fill = rest;
         }
         __syncthreads();
     }
     __syncthreads();
-    updates += drain_queue(queue, q_fill, graph, worst, K, lane, EF_WAVE);
+    updates += drain_queue<false, NB == 1>(queue, q_fill, graph, worst, K, lane, EF_WAVE);
     updates = ef_wave_sum_i32(updates);
     if (lane == 0) upd_block[blockIdx.x] = updates;
 }
