@@ -24,7 +24,7 @@ HBM_PEAK_GBS = 8000.0
 # HBM bytes per launch of the dominant kernel, from two rocprofv3 --pmc runs (FETCH_SIZE, WRITE_SIZE)
 # scaled by what the same counters read for a plain 256 MiB copy (factors 2.0 and 1.0); summary and
 # commands in profiles/join_kernels_sift1m_like_hbm_traffic.txt.  Only measured for the headline workload.
-MEASURED_TRAFFIC_BYTES = {"sift1m_like": {"calibrated": 4.93e9, "raw_counters": 2.57e9}}
+MEASURED_TRAFFIC_BYTES = {"sift1m_like": {"calibrated": 4.85e9, "raw_counters": 2.53e9}}
 
 
 def exact_knn_torch(Xd, rows, K):
