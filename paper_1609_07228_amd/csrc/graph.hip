@@ -751,15 +751,15 @@ __device__ inline bool reverse_offer(u64 *lists, int *counts, int L, int v, u64 
     return false;
 }
 
-template <int G, int E>
-__global__ void __launch_bounds__(kBlock)
-sample_kernel(u64 *graph, int n, int K, int L, u64 key_new, int *__restrict__ nw,
-              int *__restrict__ od, int *__restrict__ nw_c, int *__restrict__ od_c, u64 *rnew,
-              int *rnew_c, Overflow *overflow, size_t ovf_region, int *ovf_count, u32 *worst)
+// The sampling of row i by its group of G lanes (all lanes of the wave call this together, rows
+// past the end with row_ok false).  offer(take, id): called by every lane once per entry it
+// holds; lanes with `take` set offer row i to the reverse-new list of point id.
+template <int G, int E, class Offer>
+__device__ inline void sample_row(u64 *graph, int i, bool row_ok, int K, int L, int *__restrict__ nw,
+                                  int *__restrict__ od, int *__restrict__ nw_c, int *__restrict__ od_c,
+                                  u32 *worst, Offer &&offer)
 {
     const int gl = threadIdx.x & (G - 1);
-    const int i = (int)(((size_t)blockIdx.x * kBlock + threadIdx.x) / G);
-    const bool row_ok = i < n;
     u64 e[E];
 #pragma unroll
     for (int h = 0; h < E; ++h) {
@@ -817,15 +817,11 @@ sample_kernel(u64 *graph, int n, int K, int L, u64 key_new, int *__restrict__ nw
             ++n_old;
         }
         const bool take = row_ok && take_new[h];
-        bool parked = false;
-        u64 hk = 0;
         if (take) {
             nw[(size_t)i * L + rn[h]] = id;
             graph[(size_t)i * K + slot] = e[h] & ~1ULL;
-            hk = (ef_mix64(key_new + (((u64)(u32)id << 32) | (u32)i)) >> 32 << 32) | (u32)i;
-            parked = reverse_offer(rnew, rnew_c, L, id, hk);
         }
-        park_keys(parked, Overflow{hk, id, 0}, overflow, ovf_region, ovf_count);
+        offer(take, id);
     }
     for (int m = G / 2; m >= 1; m >>= 1) n_old += __shfl_xor(n_old, m, G);
     if (!row_ok) return;
@@ -838,6 +834,30 @@ sample_kernel(u64 *graph, int n, int K, int L, u64 key_new, int *__restrict__ nw
         od_c[i] = n_old;
         worst[i] = wbits;
     }
+}
+
+// The key under which `source` competes for a place in a reverse list of `target`.
+__device__ inline u64 reverse_key(u64 stream_key, int target, int source)
+{
+    return (ef_mix64(stream_key + (((u64)(u32)target << 32) | (u32)source)) >> 32 << 32) | (u32)source;
+}
+
+template <int G, int E>
+__global__ void __launch_bounds__(kBlock)
+sample_kernel(u64 *graph, int n, int K, int L, u64 key_new, int *__restrict__ nw,
+              int *__restrict__ od, int *__restrict__ nw_c, int *__restrict__ od_c, u64 *rnew,
+              int *rnew_c, Overflow *overflow, size_t ovf_region, int *ovf_count, u32 *worst)
+{
+    const int i = (int)(((size_t)blockIdx.x * kBlock + threadIdx.x) / G);
+    sample_row<G, E>(graph, i, i < n, K, L, nw, od, nw_c, od_c, worst, [&](bool take, int id) {
+        bool parked = false;
+        u64 hk = 0;
+        if (take) {
+            hk = reverse_key(key_new, id, i);
+            parked = reverse_offer(rnew, rnew_c, L, id, hk);
+        }
+        park_keys(parked, Overflow{hk, id, 0}, overflow, ovf_region, ovf_count);
+    });
 }
 
 // Bit i of `active` says whether point i has a non-empty U_new (a sampled new neighbour or a
@@ -871,7 +891,7 @@ reverse_old_kernel(const int *__restrict__ od, int n, int K, int L, u64 key_old,
         bool parked = false;
         u64 hk = 0;
         if (id >= 0 && ((active[id / EF_WAVE] >> (id % EF_WAVE)) & 1)) {
-            hk = (ef_mix64(key_old + (((u64)(u32)id << 32) | (u32)i)) >> 32 << 32) | (u32)i;
+            hk = reverse_key(key_old, id, i);
             parked = reverse_offer(rold, rold_c, L, id, hk);
         }
         park_keys(parked, Overflow{hk, id, 1}, overflow, ovf_region, ovf_count);
@@ -899,6 +919,187 @@ reverse_overflow_kernel(const Overflow *__restrict__ overflow, size_t ovf_region
         u64 nm;
         if (ef_bounded_insert_t<WIDE, true>((ov.which ? rold : rnew) + (size_t)ov.target * L, L, ov.key, 0, &nm))
             atomicMin(bound, nm);
+    }
+}
+
+// ---------------------------------------------------------------------------------------
+// Reverse lists without device-wide atomics, for short rows and lists (K, L <= 16) of at most
+// 2^21 points.  A counter bump per offer is bound by the rate of atomics on random addresses;
+// here the offers are sorted by target range instead, and the lists of a range are built in LDS:
+//   1. an offer block (1024 threads) handles kBktRows consecutive source rows, keeps their
+//      offers (target << 32 | source) in LDS, counts them per bucket (bucket = target /
+//      kBktRows), and writes them to its own part of the offer array, bucket after bucket;
+//      table[bucket][block] = start << 16 | count of that run;
+//   2. a list block (one per bucket) walks the runs of its bucket, one thread per offer, and
+//      enters every key into the target's list in LDS with the bounded insertion (all slots start
+//      as the largest key, so a list fills from slot 0 up and then keeps its L smallest keys);
+//      lists and counts (filled slots) go out in one contiguous piece.
+// Whatever the order of the offers, a list ends up with the L smallest keys offered to it.
+
+constexpr int kBktRows = 1024;        // source rows per offer block = targets per bucket
+constexpr int kBktThreads = 1024;
+constexpr int64_t kBktMaxN = 1 << 21;    // table of (n / kBktRows)^2 runs: 16 MB at most
+
+__host__ __device__ inline bool bucketed_lists(int64_t n, int K, int L)
+{
+    return K <= 16 && L <= 16 && n <= kBktMaxN;
+}
+
+// All lanes of the wave call this together; lanes with `take` set append `offer`.
+__device__ inline void offer_append(bool take, u64 offer, u64 *offers, int *hist, int *fill)
+{
+    const u64 mask = __ballot(take);
+    if (mask == 0) return;
+    const int leader = __ffsll((unsigned long long)mask) - 1;
+    int base = 0;
+    if (ef_lane() == leader) base = atomicAdd(fill, __popcll(mask));
+    base = __shfl(base, leader, EF_WAVE);
+    if (take) {
+        offers[base + lanes_below(mask)] = offer;
+        atomicAdd(&hist[(int)(offer >> 32) / kBktRows], 1);
+    }
+}
+
+// End of an offer block: runs per bucket in `out` (this block's part of the offer array) and
+// the block's column of the table.  hist, cursor: [n_buckets] in LDS, n_buckets <= 2 * kBktThreads.
+__device__ inline void offers_flush(const u64 *offers, const int *hist, int *cursor, int n_buckets,
+                                    int total, u64 *__restrict__ out, u32 *__restrict__ table)
+{
+    __shared__ int wave_tot[kBktThreads / EF_WAVE];
+    const int t = threadIdx.x, b0 = 2 * t;
+    const int c0 = b0 < n_buckets ? hist[b0] : 0, c1 = b0 + 1 < n_buckets ? hist[b0 + 1] : 0;
+    const int incl = ef_wave_scan_i32(c0 + c1);
+    if (ef_lane() == EF_WAVE - 1) wave_tot[t / EF_WAVE] = incl;
+    __syncthreads();
+    int off = incl - (c0 + c1);
+    for (int v = 0; v < t / EF_WAVE; ++v) off += wave_tot[v];
+    if (b0 < n_buckets) {
+        cursor[b0] = off;
+        table[(size_t)b0 * gridDim.x + blockIdx.x] = (u32)off << 16 | (u32)c0;
+    }
+    if (b0 + 1 < n_buckets) {
+        cursor[b0 + 1] = off + c0;
+        table[(size_t)(b0 + 1) * gridDim.x + blockIdx.x] = (u32)(off + c0) << 16 | (u32)c1;
+    }
+    __syncthreads();
+    for (int e = t; e < total; e += kBktThreads) {
+        const u64 o = offers[e];
+        out[atomicAdd(&cursor[(int)(o >> 32) / kBktRows], 1)] = o;
+    }
+}
+
+// Alg. 4 step 1+2 for short rows: sample_row for kBktRows rows, the reverse-new offers to the
+// block's runs.  LDS: offers [kBktRows * L] u64, hist and cursor [n_buckets] int each.
+__global__ void __launch_bounds__(kBktThreads)
+sample_bucket_kernel(u64 *graph, int n, int K, int L, int *__restrict__ nw, int *__restrict__ od,
+                     int *__restrict__ nw_c, int *__restrict__ od_c, u32 *worst, int n_buckets,
+                     u64 *__restrict__ offer_runs, u32 *__restrict__ table)
+{
+    extern __shared__ __align__(16) u64 offer_sm[];
+    u64 *offers = offer_sm;
+    int *hist = (int *)(offers + (size_t)kBktRows * L), *cursor = hist + n_buckets;
+    __shared__ int fill;
+    for (int b = threadIdx.x; b < n_buckets; b += kBktThreads) hist[b] = 0;
+    if (threadIdx.x == 0) fill = 0;
+    __syncthreads();
+    constexpr int kRowsPerPass = kBktThreads / 16;
+    for (int pass = 0; pass < kBktRows / kRowsPerPass; ++pass) {
+        const int i = blockIdx.x * kBktRows + pass * kRowsPerPass + (int)(threadIdx.x >> 4);
+        sample_row<16, 1>(graph, i, i < n, K, L, nw, od, nw_c, od_c, worst, [&](bool take, int id) {
+            offer_append(take, ((u64)(u32)id << 32) | (u32)i, offers, hist, &fill);
+        });
+    }
+    __syncthreads();
+    offers_flush(offers, hist, cursor, n_buckets, fill, offer_runs + (size_t)blockIdx.x * kBktRows * L, table);
+}
+
+// Reverse-old offers of kBktRows rows (to points that join something, as in reverse_old_kernel).
+// LDS: offers [kBktRows * K] u64, hist and cursor [n_buckets] int each.
+__global__ void __launch_bounds__(kBktThreads)
+reverse_old_bucket_kernel(const int *__restrict__ od, int n, int K, const u64 *__restrict__ active,
+                          int n_buckets, u64 *__restrict__ offer_runs, u32 *__restrict__ table)
+{
+    extern __shared__ __align__(16) u64 offer_sm[];
+    u64 *offers = offer_sm;
+    int *hist = (int *)(offers + (size_t)kBktRows * K), *cursor = hist + n_buckets;
+    __shared__ int fill;
+    for (int b = threadIdx.x; b < n_buckets; b += kBktThreads) hist[b] = 0;
+    if (threadIdx.x == 0) fill = 0;
+    __syncthreads();
+    const int first = blockIdx.x * kBktRows, rows_here = min(kBktRows, n - first);
+    for (int f0 = 0; f0 < rows_here * K; f0 += kBktThreads) {      // all threads take every round
+        const int f = f0 + (int)threadIdx.x;
+        const int id = f < rows_here * K ? od[(size_t)first * K + f] : -1;
+        const bool take = id >= 0 && ((active[id / EF_WAVE] >> (id % EF_WAVE)) & 1);
+        offer_append(take, ((u64)(u32)id << 32) | (u32)(first + f / K), offers, hist, &fill);
+    }
+    __syncthreads();
+    offers_flush(offers, hist, cursor, n_buckets, fill, offer_runs + (size_t)blockIdx.x * kBktRows * K, table);
+}
+
+// The lists of one bucket.  run_cap: offers per part of an offer block (kBktRows * L or * K).
+// LDS: lists [kBktRows * L] u64, scan [n_blocks + 1] int; n_blocks <= 2 * kBktThreads.
+__global__ void __launch_bounds__(kBktThreads)
+bucket_lists_kernel(const u64 *__restrict__ offer_runs, const u32 *__restrict__ table, int n_blocks,
+                    int run_cap, u64 stream_key, int n, int L, u64 *__restrict__ lists,
+                    int *__restrict__ counts)
+{
+    extern __shared__ __align__(16) u64 offer_sm[];
+    u64 *ll = offer_sm;
+    int *scan = (int *)(ll + (size_t)kBktRows * L);
+    __shared__ int wave_tot[kBktThreads / EF_WAVE];
+    const int t = threadIdx.x, first = blockIdx.x * kBktRows, rows_here = min(kBktRows, n - first);
+    for (int f = t; f < kBktRows * L; f += kBktThreads) ll[f] = ~0ULL;
+    const u32 *runs = table + (size_t)blockIdx.x * n_blocks;
+    {
+        const int k0 = 2 * t;
+        const int c0 = k0 < n_blocks ? (int)(runs[k0] & 0xffffu) : 0;
+        const int c1 = k0 + 1 < n_blocks ? (int)(runs[k0 + 1] & 0xffffu) : 0;
+        const int incl = ef_wave_scan_i32(c0 + c1);
+        if (ef_lane() == EF_WAVE - 1) wave_tot[t / EF_WAVE] = incl;
+        __syncthreads();
+        int off = incl - (c0 + c1);
+        for (int v = 0; v < t / EF_WAVE; ++v) off += wave_tot[v];
+        if (k0 < n_blocks) scan[k0] = off;
+        if (k0 + 1 < n_blocks) scan[k0 + 1] = off + c0;
+        if (t == kBktThreads - 1) scan[n_blocks] = off + c0 + c1;      // everything before it, and its own
+    }
+    __syncthreads();
+    const int total = scan[n_blocks];
+    for (int j = t; j < total; j += kBktThreads) {
+        int lo = 0, hi = n_blocks;      // scan[lo] <= j < scan[hi]
+        while (hi - lo > 1) {
+            const int mid = (lo + hi) >> 1;
+            if (scan[mid] <= j) lo = mid;
+            else hi = mid;
+        }
+        const u64 o = offer_runs[(size_t)lo * run_cap + (runs[lo] >> 16) + (j - scan[lo])];
+        const int target = (int)(o >> 32), source = (int)(u32)o;
+        const int row = target - first;
+        if ((unsigned)row >= (unsigned)rows_here) continue;      // cannot happen: runs are filed by bucket
+        const u64 key = reverse_key(stream_key, target, source);
+        unsigned long long *list = (unsigned long long *)(ll + row * L);
+        for (;;) {
+            u64 mx = 0;
+            int ms = 0;
+            for (int a = 0; a < L; ++a) {
+                const u64 v = __hip_atomic_load(list + a, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+                if (v > mx) {      // the first of equal (empty) slots: lists fill from slot 0 up
+                    mx = v;
+                    ms = a;
+                }
+            }
+            if (key >= mx) break;
+            // slots only ever fall: if slot ms still holds mx, it still is the largest
+            if (atomicCAS(list + ms, (unsigned long long)mx, (unsigned long long)key) == mx) break;
+        }
+    }
+    __syncthreads();
+    for (int f = t; f < rows_here * L; f += kBktThreads) lists[(size_t)first * L + f] = ll[f];
+    if (t < rows_here) {
+        int c = 0;
+        for (int a = 0; a < L; ++a) c += ll[t * L + a] != ~0ULL ? 1 : 0;
+        counts[first + t] = c;
     }
 }
 
@@ -1705,7 +1906,8 @@ struct NndWs {
     int *nw, *od, *nw_c, *od_c, *work, *work_count, *rnew_c, *rold_c, *ovf_count, *ulist, *upd_block;
     int2 *ucount;
     void *overflow;
-    u64 *rnew, *rold, *list_max, *active, *fresh;
+    u64 *rnew, *rold, *list_max, *active, *fresh, *offer_runs;
+    u32 *run_table;
     long long *part;
     u32 *worst;
     float *norms;
@@ -1731,7 +1933,13 @@ NndWs carve_nnd(void *ws, int64_t n, int K, int L)
     w.work_count = (int *)take(8 * 4);     // [0..2] list sizes
     w.rnew_c = (int *)take((size_t)n * 4);
     w.rold_c = (int *)take((size_t)n * 4);
-    w.overflow = take(ovf_region_for(n, K) * kOvfQueues * sizeof(Overflow));
+    // reverse lists: either the overflow queues of the counter scheme or the offer runs and
+    // their table of the bucket scheme
+    const bool bkt = bucketed_lists(n, K, L);
+    const size_t n_bkt = (size_t)(n + kBktRows - 1) / kBktRows;
+    w.overflow = take(bkt ? 0 : ovf_region_for(n, K) * kOvfQueues * sizeof(Overflow));
+    w.offer_runs = (u64 *)take(bkt ? n_bkt * kBktRows * (size_t)(K > L ? K : L) * 8 : 0);
+    w.run_table = (u32 *)take(bkt ? n_bkt * n_bkt * 4 : 0);
     w.ovf_count = (int *)take((size_t)kOvfQueues * kOvfCounterPitch * 4);
     w.ulist = (int *)take((size_t)n * (K + 2 * L) * 4);
     w.ucount = (int2 *)take((size_t)n * 8);
@@ -1928,6 +2136,19 @@ extern "C" int efanna_nndescent(const float *X, int64_t n, int32_t d, int32_t k,
     const float thr_scale = (float)(1.0 + 4.0 * (d / 16.0 + 8.0) * 5.9604644775390625e-08);
     hipStream_t st = (hipStream_t)stream;
     NndWs w = carve_nnd(ws, n, K, L);
+    // reverse lists by buckets (short rows and lists): LDS of an offer or list block with `per_row`
+    // keys per row, and one int per bucket or offer block twice over
+    const bool bkt = bucketed_lists(n, K, L);
+    const int n_bkt = (int)((n + kBktRows - 1) / kBktRows);
+    auto bkt_lds = [&](int per_row) { return (size_t)kBktRows * per_row * 8 + ((size_t)2 * n_bkt + 4) * 4; };
+    if (bkt) {
+        EF_HIP_CHECK(hipFuncSetAttribute((const void *)sample_bucket_kernel,
+                                         hipFuncAttributeMaxDynamicSharedMemorySize, (int)bkt_lds(L)));
+        EF_HIP_CHECK(hipFuncSetAttribute((const void *)reverse_old_bucket_kernel,
+                                         hipFuncAttributeMaxDynamicSharedMemorySize, (int)bkt_lds(K)));
+        EF_HIP_CHECK(hipFuncSetAttribute((const void *)bucket_lists_kernel,
+                                         hipFuncAttributeMaxDynamicSharedMemorySize, (int)bkt_lds(L)));
+    }
     if (max_rows > rows1)
         EF_HIP_CHECK(hipFuncSetAttribute(K >= 2 * EF_WIDE_PIECES ? (const void *)join_kernel<true>
                                                                  : (const void *)join_kernel<false>,
@@ -1970,17 +2191,28 @@ extern "C" int efanna_nndescent(const float *X, int64_t n, int32_t d, int32_t k,
 #define EF_REVERSE_OLD(G)                                                                        \
     reverse_old_kernel<G><<<grid_for((size_t)n * G, kBlock), kBlock, 0, st>>>(                   \
         w.od, (int)n, K, L, ko, w.active, w.rold, w.rold_c, ovf, ovf_region, w.ovf_count)
-            if (K <= 16) EF_SAMPLE(16, 1);
+            if (bkt) {
+                sample_bucket_kernel<<<n_bkt, kBktThreads, bkt_lds(L), st>>>(
+                    graph, (int)n, K, L, w.nw, w.od, w.nw_c, w.od_c, w.worst, n_bkt, w.offer_runs, w.run_table);
+                bucket_lists_kernel<<<n_bkt, kBktThreads, bkt_lds(L), st>>>(
+                    w.offer_runs, w.run_table, n_bkt, kBktRows * L, kn, (int)n, L, w.rnew, w.rnew_c);
+            } else if (K <= 16) EF_SAMPLE(16, 1);
             else if (K <= 32) EF_SAMPLE(32, 1);
             else if (K <= 64) EF_SAMPLE(64, 1);
             else EF_SAMPLE(64, 2);
             active_kernel<<<grid_for((size_t)n, kBlock), kBlock, 0, st>>>(w.nw_c, w.rnew_c, (int)n, w.active);
-            if (K <= 16) EF_REVERSE_OLD(16);
+            if (bkt) {
+                reverse_old_bucket_kernel<<<n_bkt, kBktThreads, bkt_lds(K), st>>>(
+                    w.od, (int)n, K, w.active, n_bkt, w.offer_runs, w.run_table);
+                bucket_lists_kernel<<<n_bkt, kBktThreads, bkt_lds(L), st>>>(
+                    w.offer_runs, w.run_table, n_bkt, kBktRows * K, ko, (int)n, L, w.rold, w.rold_c);
+            } else if (K <= 16) EF_REVERSE_OLD(16);
             else if (K <= 32) EF_REVERSE_OLD(32);
             else EF_REVERSE_OLD(64);
 #undef EF_SAMPLE
 #undef EF_REVERSE_OLD
-            if (L >= 2 * EF_WIDE_PIECES)
+            if (bkt) {
+            } else if (L >= 2 * EF_WIDE_PIECES)
                 reverse_overflow_kernel<true><<<dim3(kOvfBlocksPerQueue, kOvfQueues), kBlock, 0, st>>>(
                     ovf, ovf_region, w.ovf_count, (size_t)n, w.rnew, w.rold, w.list_max, L);
             else
