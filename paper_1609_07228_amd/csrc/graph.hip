@@ -751,21 +751,28 @@ __device__ inline bool reverse_offer(u64 *lists, int *counts, int L, int v, u64 
     return false;
 }
 
-// The sampling of row i by its group of G lanes (all lanes of the wave call this together, rows
-// past the end with row_ok false).  offer(take, id): called by every lane once per entry it
-// holds; lanes with `take` set offer row i to the reverse-new list of point id.
-template <int G, int E, class Offer>
-__device__ inline void sample_row(u64 *graph, int i, bool row_ok, int K, int L, int *__restrict__ nw,
-                                  int *__restrict__ od, int *__restrict__ nw_c, int *__restrict__ od_c,
-                                  u32 *worst, Offer &&offer)
+// Entry gl + h * G of row i for lane gl of the row's group (the largest key where there is none).
+template <int G, int E>
+__device__ inline void sample_load(const u64 *graph, int i, bool row_ok, int K, u64 (&e)[E])
 {
     const int gl = threadIdx.x & (G - 1);
-    u64 e[E];
 #pragma unroll
     for (int h = 0; h < E; ++h) {
         const int slot = gl + h * G;
         e[h] = row_ok && slot < K ? graph[(size_t)i * K + slot] : ~0ULL;
     }
+}
+
+// The sampling of row i by its group of G lanes, which hold the row's entries e as sample_load
+// delivers them (all lanes of the wave call this together, rows past the end with row_ok false).
+// offer(take, id): called by every lane once per entry it holds; lanes with `take` set offer
+// row i to the reverse-new list of point id.
+template <int G, int E, class Offer>
+__device__ inline void sample_row(u64 *graph, const u64 (&e)[E], int i, bool row_ok, int K, int L,
+                                  int *__restrict__ nw, int *__restrict__ od, int *__restrict__ nw_c,
+                                  int *__restrict__ od_c, u32 *worst, Offer &&offer)
+{
+    const int gl = threadIdx.x & (G - 1);
     // ranks among new-marked and among old entries (all lanes of the group take part)
     int rn[E], ro[E];
 #pragma unroll
@@ -849,7 +856,9 @@ sample_kernel(u64 *graph, int n, int K, int L, u64 key_new, int *__restrict__ nw
               int *rnew_c, Overflow *overflow, size_t ovf_region, int *ovf_count, u32 *worst)
 {
     const int i = (int)(((size_t)blockIdx.x * kBlock + threadIdx.x) / G);
-    sample_row<G, E>(graph, i, i < n, K, L, nw, od, nw_c, od_c, worst, [&](bool take, int id) {
+    u64 e[E];
+    sample_load<G, E>(graph, i, i < n, K, e);
+    sample_row<G, E>(graph, e, i, i < n, K, L, nw, od, nw_c, od_c, worst, [&](bool take, int id) {
         bool parked = false;
         u64 hk = 0;
         if (take) {
@@ -927,26 +936,29 @@ reverse_overflow_kernel(const Overflow *__restrict__ overflow, size_t ovf_region
 // 2^21 points.  A counter bump per offer is bound by the rate of atomics on random addresses;
 // here the offers are sorted by target range instead, and the lists of a range are built in LDS:
 //   1. an offer block (1024 threads) handles kBktRows consecutive source rows, keeps their
-//      offers (target << 32 | source) in LDS, counts them per bucket (bucket = target /
-//      kBktRows), and writes them to its own part of the offer array, bucket after bucket;
-//      table[bucket][block] = start << 16 | count of that run;
+//      offers (one word: target << 10 | source row inside the block) in LDS, counts them per
+//      bucket (bucket = target / kBktRows), and writes them to its own part of the offer array,
+//      bucket after bucket; table[bucket][block] = start << 16 | count of that run;
 //   2. a list block (one per bucket) walks the runs of its bucket, one thread per offer, and
-//      enters every key into the target's list in LDS with the bounded insertion (all slots start
-//      as the largest key, so a list fills from slot 0 up and then keeps its L smallest keys);
-//      lists and counts (filled slots) go out in one contiguous piece.
+//      enters every key into the target's list in LDS with the bounded insertion; lists and
+//      counts (filled slots) go out in one contiguous piece.
 // Whatever the order of the offers, a list ends up with the L smallest keys offered to it.
 
 constexpr int kBktRows = 1024;        // source rows per offer block = targets per bucket
 constexpr int kBktThreads = 1024;
-constexpr int64_t kBktMaxN = 1 << 21;    // table of (n / kBktRows)^2 runs: 16 MB at most
+constexpr int64_t kBktMaxN = 1 << 21;    // table of (n / kBktRows)^2 runs: 16 MB at most; targets fit 21 bits
+static_assert(kBktRows == 1024, "an offer word keeps the source row in ten bits");
+
+__host__ __device__ inline size_t bucket_lists_lds(int L, int n_blocks);
 
 __host__ __device__ inline bool bucketed_lists(int64_t n, int K, int L)
 {
-    return K <= 16 && L <= 16 && n <= kBktMaxN;
+    return K <= 16 && L <= 16 && n <= kBktMaxN &&
+           bucket_lists_lds(L, (int)((n + kBktRows - 1) / kBktRows)) <= 160 * 1024 - 256;
 }
 
 // All lanes of the wave call this together; lanes with `take` set append `offer`.
-__device__ inline void offer_append(bool take, u64 offer, u64 *offers, int *hist, int *fill)
+__device__ inline void offer_append(bool take, u32 offer, u32 *offers, int *hist, int *fill)
 {
     const u64 mask = __ballot(take);
     if (mask == 0) return;
@@ -956,14 +968,14 @@ __device__ inline void offer_append(bool take, u64 offer, u64 *offers, int *hist
     base = __shfl(base, leader, EF_WAVE);
     if (take) {
         offers[base + lanes_below(mask)] = offer;
-        atomicAdd(&hist[(int)(offer >> 32) / kBktRows], 1);
+        atomicAdd(&hist[offer >> 20], 1);
     }
 }
 
 // End of an offer block: runs per bucket in `out` (this block's part of the offer array) and
 // the block's column of the table.  hist, cursor: [n_buckets] in LDS, n_buckets <= 2 * kBktThreads.
-__device__ inline void offers_flush(const u64 *offers, const int *hist, int *cursor, int n_buckets,
-                                    int total, u64 *__restrict__ out, u32 *__restrict__ table)
+__device__ inline void offers_flush(const u32 *offers, const int *hist, int *cursor, int n_buckets,
+                                    int total, u32 *__restrict__ out, u32 *__restrict__ table)
 {
     __shared__ int wave_tot[kBktThreads / EF_WAVE];
     const int t = threadIdx.x, b0 = 2 * t;
@@ -983,30 +995,34 @@ __device__ inline void offers_flush(const u64 *offers, const int *hist, int *cur
     }
     __syncthreads();
     for (int e = t; e < total; e += kBktThreads) {
-        const u64 o = offers[e];
-        out[atomicAdd(&cursor[(int)(o >> 32) / kBktRows], 1)] = o;
+        const u32 o = offers[e];
+        out[atomicAdd(&cursor[o >> 20], 1)] = o;
     }
 }
 
 // Alg. 4 step 1+2 for short rows: sample_row for kBktRows rows, the reverse-new offers to the
-// block's runs.  LDS: offers [kBktRows * L] u64, hist and cursor [n_buckets] int each.
+// block's runs.  LDS: offers [kBktRows * L] words, hist and cursor [n_buckets] int each.
 __global__ void __launch_bounds__(kBktThreads)
 sample_bucket_kernel(u64 *graph, int n, int K, int L, int *__restrict__ nw, int *__restrict__ od,
                      int *__restrict__ nw_c, int *__restrict__ od_c, u32 *worst, int n_buckets,
-                     u64 *__restrict__ offer_runs, u32 *__restrict__ table)
+                     u32 *__restrict__ offer_runs, u32 *__restrict__ table)
 {
-    extern __shared__ __align__(16) u64 offer_sm[];
-    u64 *offers = offer_sm;
+    extern __shared__ __align__(16) u32 offer_sm[];
+    u32 *offers = offer_sm;
     int *hist = (int *)(offers + (size_t)kBktRows * L), *cursor = hist + n_buckets;
     __shared__ int fill;
     for (int b = threadIdx.x; b < n_buckets; b += kBktThreads) hist[b] = 0;
     if (threadIdx.x == 0) fill = 0;
     __syncthreads();
+    // (loading the entries of several of a thread's rows ahead of time gains nothing measurable,
+    // and beyond 64 registers the second block of a CU is lost)
     constexpr int kRowsPerPass = kBktThreads / 16;
     for (int pass = 0; pass < kBktRows / kRowsPerPass; ++pass) {
         const int i = blockIdx.x * kBktRows + pass * kRowsPerPass + (int)(threadIdx.x >> 4);
-        sample_row<16, 1>(graph, i, i < n, K, L, nw, od, nw_c, od_c, worst, [&](bool take, int id) {
-            offer_append(take, ((u64)(u32)id << 32) | (u32)i, offers, hist, &fill);
+        u64 e[1];
+        sample_load<16, 1>(graph, i, i < n, K, e);
+        sample_row<16, 1>(graph, e, i, i < n, K, L, nw, od, nw_c, od_c, worst, [&](bool take, int id) {
+            offer_append(take, ((u32)id << 10) | (u32)(i & (kBktRows - 1)), offers, hist, &fill);
         });
     }
     __syncthreads();
@@ -1014,13 +1030,13 @@ sample_bucket_kernel(u64 *graph, int n, int K, int L, int *__restrict__ nw, int 
 }
 
 // Reverse-old offers of kBktRows rows (to points that join something, as in reverse_old_kernel).
-// LDS: offers [kBktRows * K] u64, hist and cursor [n_buckets] int each.
+// LDS: offers [kBktRows * K] words, hist and cursor [n_buckets] int each.
 __global__ void __launch_bounds__(kBktThreads)
 reverse_old_bucket_kernel(const int *__restrict__ od, int n, int K, const u64 *__restrict__ active,
-                          int n_buckets, u64 *__restrict__ offer_runs, u32 *__restrict__ table)
+                          int n_buckets, u32 *__restrict__ offer_runs, u32 *__restrict__ table)
 {
-    extern __shared__ __align__(16) u64 offer_sm[];
-    u64 *offers = offer_sm;
+    extern __shared__ __align__(16) u32 offer_sm[];
+    u32 *offers = offer_sm;
     int *hist = (int *)(offers + (size_t)kBktRows * K), *cursor = hist + n_buckets;
     __shared__ int fill;
     for (int b = threadIdx.x; b < n_buckets; b += kBktThreads) hist[b] = 0;
@@ -1031,50 +1047,72 @@ reverse_old_bucket_kernel(const int *__restrict__ od, int n, int K, const u64 *_
         const int f = f0 + (int)threadIdx.x;
         const int id = f < rows_here * K ? od[(size_t)first * K + f] : -1;
         const bool take = id >= 0 && ((active[id / EF_WAVE] >> (id % EF_WAVE)) & 1);
-        offer_append(take, ((u64)(u32)id << 32) | (u32)(first + f / K), offers, hist, &fill);
+        offer_append(take, ((u32)id << 10) | (u32)(f / K), offers, hist, &fill);
     }
     __syncthreads();
     offers_flush(offers, hist, cursor, n_buckets, fill, offer_runs + (size_t)blockIdx.x * kBktRows * K, table);
 }
 
 // The lists of one bucket.  run_cap: offers per part of an offer block (kBktRows * L or * K).
-// LDS: lists [kBktRows * L] u64, scan [n_blocks + 1] int; n_blocks <= 2 * kBktThreads.
+// Every key goes through the bounded insertion; all slots start as the largest key, so a list
+// fills from slot 0 up and then keeps its L smallest keys.
+// LDS: lists [kBktRows * L] u64, scan [n_blocks + 1] and start [n_blocks] int;
+// n_blocks <= 2 * kBktThreads.
+// What the time is made of (headline workload, 93 us per launch on average, 190 us for the
+// ten million offers of the first iteration): 18 us fixed, about 5 ns per thousand offers to
+// find and load them, the rest LDS traffic of the insertions (eleven or more accesses of 64
+// random rows each per offer, which collide in the banks).  Variants that were no faster or
+// slower: a thread walking consecutive offers instead of a search per offer; offers loaded eight
+// ahead; list reads issued in groups; the first L offers of a list placed by a counter and the
+// others entered behind a per-list bound, or smallest first in rounds between barriers; offers
+// to popular points thinned out by a hash threshold first.
+__host__ __device__ inline size_t bucket_lists_lds(int L, int n_blocks)
+{
+    return (size_t)kBktRows * L * 8 + ((size_t)2 * n_blocks + 2) * 4;
+}
+
 __global__ void __launch_bounds__(kBktThreads)
-bucket_lists_kernel(const u64 *__restrict__ offer_runs, const u32 *__restrict__ table, int n_blocks,
+bucket_lists_kernel(const u32 *__restrict__ offer_runs, const u32 *__restrict__ table, int n_blocks,
                     int run_cap, u64 stream_key, int n, int L, u64 *__restrict__ lists,
                     int *__restrict__ counts)
 {
-    extern __shared__ __align__(16) u64 offer_sm[];
-    u64 *ll = offer_sm;
-    int *scan = (int *)(ll + (size_t)kBktRows * L);
+    extern __shared__ __align__(16) u64 list_sm[];
+    u64 *ll = list_sm;
+    int *scan = (int *)(ll + (size_t)kBktRows * L), *start = scan + n_blocks + 1;
     __shared__ int wave_tot[kBktThreads / EF_WAVE];
     const int t = threadIdx.x, first = blockIdx.x * kBktRows, rows_here = min(kBktRows, n - first);
     for (int f = t; f < kBktRows * L; f += kBktThreads) ll[f] = ~0ULL;
     const u32 *runs = table + (size_t)blockIdx.x * n_blocks;
     {
         const int k0 = 2 * t;
-        const int c0 = k0 < n_blocks ? (int)(runs[k0] & 0xffffu) : 0;
-        const int c1 = k0 + 1 < n_blocks ? (int)(runs[k0 + 1] & 0xffffu) : 0;
+        const u32 r0 = k0 < n_blocks ? runs[k0] : 0u, r1 = k0 + 1 < n_blocks ? runs[k0 + 1] : 0u;
+        const int c0 = (int)(r0 & 0xffffu), c1 = (int)(r1 & 0xffffu);
         const int incl = ef_wave_scan_i32(c0 + c1);
         if (ef_lane() == EF_WAVE - 1) wave_tot[t / EF_WAVE] = incl;
         __syncthreads();
         int off = incl - (c0 + c1);
         for (int v = 0; v < t / EF_WAVE; ++v) off += wave_tot[v];
-        if (k0 < n_blocks) scan[k0] = off;
-        if (k0 + 1 < n_blocks) scan[k0 + 1] = off + c0;
+        if (k0 < n_blocks) {
+            scan[k0] = off;
+            start[k0] = (int)(r0 >> 16);
+        }
+        if (k0 + 1 < n_blocks) {
+            scan[k0 + 1] = off + c0;
+            start[k0 + 1] = (int)(r1 >> 16);
+        }
         if (t == kBktThreads - 1) scan[n_blocks] = off + c0 + c1;      // everything before it, and its own
     }
     __syncthreads();
     const int total = scan[n_blocks];
-    for (int j = t; j < total; j += kBktThreads) {
+    for (int j = t; j < total; j += kBktThreads) {      // neighbouring threads take neighbouring offers
         int lo = 0, hi = n_blocks;      // scan[lo] <= j < scan[hi]
         while (hi - lo > 1) {
             const int mid = (lo + hi) >> 1;
             if (scan[mid] <= j) lo = mid;
             else hi = mid;
         }
-        const u64 o = offer_runs[(size_t)lo * run_cap + (runs[lo] >> 16) + (j - scan[lo])];
-        const int target = (int)(o >> 32), source = (int)(u32)o;
+        const u32 o = offer_runs[(size_t)lo * run_cap + start[lo] + (j - scan[lo])];
+        const int target = (int)(o >> 10), source = lo * kBktRows + (int)(o & (kBktRows - 1));
         const int row = target - first;
         if ((unsigned)row >= (unsigned)rows_here) continue;      // cannot happen: runs are filed by bucket
         const u64 key = reverse_key(stream_key, target, source);
@@ -1906,8 +1944,8 @@ struct NndWs {
     int *nw, *od, *nw_c, *od_c, *work, *work_count, *rnew_c, *rold_c, *ovf_count, *ulist, *upd_block;
     int2 *ucount;
     void *overflow;
-    u64 *rnew, *rold, *list_max, *active, *fresh, *offer_runs;
-    u32 *run_table;
+    u64 *rnew, *rold, *list_max, *active, *fresh;
+    u32 *offer_runs, *run_table;
     long long *part;
     u32 *worst;
     float *norms;
@@ -1938,7 +1976,7 @@ NndWs carve_nnd(void *ws, int64_t n, int K, int L)
     const bool bkt = bucketed_lists(n, K, L);
     const size_t n_bkt = (size_t)(n + kBktRows - 1) / kBktRows;
     w.overflow = take(bkt ? 0 : ovf_region_for(n, K) * kOvfQueues * sizeof(Overflow));
-    w.offer_runs = (u64 *)take(bkt ? n_bkt * kBktRows * (size_t)(K > L ? K : L) * 8 : 0);
+    w.offer_runs = (u32 *)take(bkt ? n_bkt * kBktRows * (size_t)(K > L ? K : L) * 4 : 0);
     w.run_table = (u32 *)take(bkt ? n_bkt * n_bkt * 4 : 0);
     w.ovf_count = (int *)take((size_t)kOvfQueues * kOvfCounterPitch * 4);
     w.ulist = (int *)take((size_t)n * (K + 2 * L) * 4);
@@ -2136,18 +2174,18 @@ extern "C" int efanna_nndescent(const float *X, int64_t n, int32_t d, int32_t k,
     const float thr_scale = (float)(1.0 + 4.0 * (d / 16.0 + 8.0) * 5.9604644775390625e-08);
     hipStream_t st = (hipStream_t)stream;
     NndWs w = carve_nnd(ws, n, K, L);
-    // reverse lists by buckets (short rows and lists): LDS of an offer or list block with `per_row`
-    // keys per row, and one int per bucket or offer block twice over
+    // reverse lists by buckets (short rows and lists): LDS of an offer block (words) or a list
+    // block (keys) with `per_row` of them per row, and one int per bucket or offer block twice over
     const bool bkt = bucketed_lists(n, K, L);
     const int n_bkt = (int)((n + kBktRows - 1) / kBktRows);
-    auto bkt_lds = [&](int per_row) { return (size_t)kBktRows * per_row * 8 + ((size_t)2 * n_bkt + 4) * 4; };
+    auto bkt_lds = [&](int per_row, int bytes) { return (size_t)kBktRows * per_row * bytes + ((size_t)2 * n_bkt + 4) * 4; };
     if (bkt) {
         EF_HIP_CHECK(hipFuncSetAttribute((const void *)sample_bucket_kernel,
-                                         hipFuncAttributeMaxDynamicSharedMemorySize, (int)bkt_lds(L)));
+                                         hipFuncAttributeMaxDynamicSharedMemorySize, (int)bkt_lds(L, 4)));
         EF_HIP_CHECK(hipFuncSetAttribute((const void *)reverse_old_bucket_kernel,
-                                         hipFuncAttributeMaxDynamicSharedMemorySize, (int)bkt_lds(K)));
+                                         hipFuncAttributeMaxDynamicSharedMemorySize, (int)bkt_lds(K, 4)));
         EF_HIP_CHECK(hipFuncSetAttribute((const void *)bucket_lists_kernel,
-                                         hipFuncAttributeMaxDynamicSharedMemorySize, (int)bkt_lds(L)));
+                                         hipFuncAttributeMaxDynamicSharedMemorySize, (int)bucket_lists_lds(L, n_bkt)));
     }
     if (max_rows > rows1)
         EF_HIP_CHECK(hipFuncSetAttribute(K >= 2 * EF_WIDE_PIECES ? (const void *)join_kernel<true>
@@ -2192,9 +2230,9 @@ extern "C" int efanna_nndescent(const float *X, int64_t n, int32_t d, int32_t k,
     reverse_old_kernel<G><<<grid_for((size_t)n * G, kBlock), kBlock, 0, st>>>(                   \
         w.od, (int)n, K, L, ko, w.active, w.rold, w.rold_c, ovf, ovf_region, w.ovf_count)
             if (bkt) {
-                sample_bucket_kernel<<<n_bkt, kBktThreads, bkt_lds(L), st>>>(
+                sample_bucket_kernel<<<n_bkt, kBktThreads, bkt_lds(L, 4), st>>>(
                     graph, (int)n, K, L, w.nw, w.od, w.nw_c, w.od_c, w.worst, n_bkt, w.offer_runs, w.run_table);
-                bucket_lists_kernel<<<n_bkt, kBktThreads, bkt_lds(L), st>>>(
+                bucket_lists_kernel<<<n_bkt, kBktThreads, bucket_lists_lds(L, n_bkt), st>>>(
                     w.offer_runs, w.run_table, n_bkt, kBktRows * L, kn, (int)n, L, w.rnew, w.rnew_c);
             } else if (K <= 16) EF_SAMPLE(16, 1);
             else if (K <= 32) EF_SAMPLE(32, 1);
@@ -2202,9 +2240,9 @@ extern "C" int efanna_nndescent(const float *X, int64_t n, int32_t d, int32_t k,
             else EF_SAMPLE(64, 2);
             active_kernel<<<grid_for((size_t)n, kBlock), kBlock, 0, st>>>(w.nw_c, w.rnew_c, (int)n, w.active);
             if (bkt) {
-                reverse_old_bucket_kernel<<<n_bkt, kBktThreads, bkt_lds(K), st>>>(
+                reverse_old_bucket_kernel<<<n_bkt, kBktThreads, bkt_lds(K, 4), st>>>(
                     w.od, (int)n, K, w.active, n_bkt, w.offer_runs, w.run_table);
-                bucket_lists_kernel<<<n_bkt, kBktThreads, bkt_lds(L), st>>>(
+                bucket_lists_kernel<<<n_bkt, kBktThreads, bucket_lists_lds(L, n_bkt), st>>>(
                     w.offer_runs, w.run_table, n_bkt, kBktRows * K, ko, (int)n, L, w.rold, w.rold_c);
             } else if (K <= 16) EF_REVERSE_OLD(16);
             else if (K <= 32) EF_REVERSE_OLD(32);

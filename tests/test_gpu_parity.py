@@ -254,6 +254,10 @@ def test_nndescent_bit_exact_every_iteration(ef, name, n, T, S, K, L, I):
     (12, 4, 2, 3, 10, 10, 3),            # hardly more points than K (the library wants k < n)
     (33, 8, 1, 64, 5, 5, 2),             # one leaf holds everything
     (65, 4, 3, 1, 4, 2, 4),              # leaves of one point: the initial graph is empty
+    (1_025, 8, 2, 16, 10, 10, 3),        # reverse lists by target ranges of 1024: a second range of one point
+    (5_000, 8, 2, 16, 16, 16, 2),        # the longest rows and lists that scheme takes, a ragged last range
+    (2_100, 8, 2, 16, 16, 17, 2),        # one more: the counter scheme with 16 lanes per row
+    (4_096, 12, 2, 16, 3, 1, 4),         # lists of a single key
 ])
 def test_nndescent_more_shapes(ef, n, d, T, S, K, L, I):
     rng = np.random.default_rng(n + d + K)
@@ -267,6 +271,26 @@ def test_nndescent_more_shapes(ef, n, d, T, S, K, L, I):
         want = oracle.nndescent(X, *want[:3], 1, L, 11, iter0=it)
         ids, dists = graph_equal(ef, graph, want)
         assert int(host(stats)[0, 0]) == int(want[3][0, 0])
+    oracle.check_graph_invariants(X, ids, dists)
+
+
+def test_reverse_lists_of_popular_points(ef):
+    """A few points that are everybody's neighbours: their reverse lists are offered thousands of
+    keys, from every block of source rows, and keep the L smallest."""
+    rng = np.random.default_rng(5)
+    n, d, K, L = 6_000, 32, 10, 10
+    X = rng.standard_normal((n, d)).astype(np.float32)      # a Gaussian cloud in 32 dimensions: its points
+    X[::1500] = (0.01 * rng.standard_normal((4, d))).astype(np.float32)   # are closer to its centre than to each other
+    Xd = dev(X)
+    (perm, off, nl), (operm, ooff, onl) = trees_equal(ef, X, 3, 16, 3)
+    graph = ef.efanna_init_graph(Xd, perm, off, nl, 16, K)
+    want = oracle.init_graph(X, operm, ooff, onl, K)
+    for it in range(4):
+        ef.efanna_nndescent(Xd, graph, 1, L, 3, first_iter=it)
+        want = oracle.nndescent(X, *want[:3], 1, L, 3, iter0=it)
+        ids, dists = graph_equal(ef, graph, want)
+    indeg = np.bincount(ids.ravel(), minlength=n)
+    assert indeg[::1500].min() > 1000      # the case is what it says
     oracle.check_graph_invariants(X, ids, dists)
 
 
