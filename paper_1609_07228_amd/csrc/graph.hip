@@ -1069,7 +1069,10 @@ reverse_old_bucket_kernel(const int *__restrict__ od, int n, int K, const u64 *_
 // instead of a search per offer; offers loaded eight ahead; list reads issued in groups; the
 // first L offers of a list placed by a counter and the others entered behind a per-list bound,
 // or smallest first in rounds between barriers; a per-list bound on the hash in front of the
-// scan; offers to popular points thinned out by a hash threshold first.
+// scan; offers to popular points thinned out by a hash threshold first; the keys sorted by
+// target in LDS (count, prefix sum, scatter) and one thread per target selecting its L smallest
+// alone, without atomics (175 us: the popular points' threads run long, and the offers are
+// found twice).
 __host__ __device__ inline size_t bucket_lists_lds(int L, int n_blocks)
 {
     return (size_t)kBktRows * L * 8 + ((size_t)2 * n_blocks + 2) * 4;

@@ -274,13 +274,17 @@ def test_nndescent_more_shapes(ef, n, d, T, S, K, L, I):
     oracle.check_graph_invariants(X, ids, dists)
 
 
-def test_reverse_lists_of_popular_points(ef):
+@pytest.mark.parametrize("hubs", [
+    [0, 1500, 3000, 4500],      # spread over the ranges of 1024 targets
+    [3, 200, 700, 1023],        # all in one range: twenty thousand offers for its thousand lists
+])
+def test_reverse_lists_of_popular_points(ef, hubs):
     """A few points that are everybody's neighbours: their reverse lists are offered thousands of
     keys, from every block of source rows, and keep the L smallest."""
     rng = np.random.default_rng(5)
     n, d, K, L = 6_000, 32, 10, 10
     X = rng.standard_normal((n, d)).astype(np.float32)      # a Gaussian cloud in 32 dimensions: its points
-    X[::1500] = (0.01 * rng.standard_normal((4, d))).astype(np.float32)   # are closer to its centre than to each other
+    X[hubs] = (0.01 * rng.standard_normal((4, d))).astype(np.float32)     # are closer to its centre than to each other
     Xd = dev(X)
     (perm, off, nl), (operm, ooff, onl) = trees_equal(ef, X, 3, 16, 3)
     graph = ef.efanna_init_graph(Xd, perm, off, nl, 16, K)
@@ -290,7 +294,7 @@ def test_reverse_lists_of_popular_points(ef):
         want = oracle.nndescent(X, *want[:3], 1, L, 3, iter0=it)
         ids, dists = graph_equal(ef, graph, want)
     indeg = np.bincount(ids.ravel(), minlength=n)
-    assert indeg[::1500].min() > 1000      # the case is what it says
+    assert indeg[hubs].min() > 1000      # the case is what it says
     oracle.check_graph_invariants(X, ids, dists)
 
 
