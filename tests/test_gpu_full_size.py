@@ -168,3 +168,29 @@ def test_gist1m_like_full_size_bit_exact():
 @pytest.mark.timeout(900)
 def test_mixed4m_d96_full_size_properties():
     _full_size_properties("mixed4m_d96", 1000, 100)
+
+
+@pytest.mark.timeout(600)
+@pytest.mark.parametrize("n", [1 << 21, (1 << 21) + 1])
+def test_two_million_short_vectors_bit_exact(n):
+    """The largest point count whose reverse lists are built by target ranges (2048 ranges, the
+    most an offer block's table takes), and one point more, which goes the way of the per-list
+    counters: tiny vectors, so that the oracle follows in seconds."""
+    if not torch.cuda.is_available():
+        pytest.fail("GPU tests need a GPU: there is no CPU fallback")
+    from paper_1609_07228_amd import efanna
+    d, T, S, K, L, I = 4, 1, 8, 4, 4, 2
+    X = np.random.default_rng(n).standard_normal((n, d)).astype(np.float32)
+    Xd = torch.from_numpy(X).to("cuda:0")
+    perm, leaf_off, n_leaves = efanna.efanna_build_trees(Xd, T, S, 3, max_leaves=n // 2 + 16)
+    graph = efanna.efanna_init_graph(Xd, perm, leaf_off, n_leaves, S, K)
+    stats = efanna.efanna_nndescent(Xd, graph, I, L, 3).cpu().numpy()
+    ids, dists, flags = [t.cpu().numpy() for t in efanna.efanna_get_graph(graph, with_flags=True)]
+    print("gpu path done", flush=True)
+    operm, ooff, onl = oracle.build_trees(X, T, S, 3)
+    assert np.array_equal(perm.cpu().numpy(), operm)
+    want = oracle.nndescent(X, *oracle.init_graph(X, operm, ooff, onl, K), I, L, 3)
+    assert np.array_equal(ids, want[0])
+    assert np.array_equal(dists.view(np.uint32), want[1].view(np.uint32))
+    assert np.array_equal(flags, want[2])
+    assert np.array_equal(stats[:, 0].astype(np.int64), want[3][:, 0].astype(np.int64))
