@@ -932,33 +932,39 @@ reverse_overflow_kernel(const Overflow *__restrict__ overflow, size_t ovf_region
 }
 
 // ---------------------------------------------------------------------------------------
-// Reverse lists without device-wide atomics, for short rows and lists (K, L <= 16) of at most
-// 2^21 points.  A counter bump per offer is bound by the rate of atomics on random addresses;
+// Reverse lists without device-wide atomics, for short rows and lists (K, L <= 32) of at most
+// 2^21 points (2^20 if L > 16).  A counter bump per offer is bound by the rate of atomics on random addresses;
 // here the offers are sorted by target range instead, and the lists of a range are built in LDS:
 //   1. an offer block (1024 threads) handles kBktRows consecutive source rows, keeps their
 //      offers (one word: target << 10 | source row inside the block) in LDS, counts them per
-//      bucket (bucket = target / kBktRows), and writes them to its own part of the offer array,
-//      bucket after bucket; table[bucket][block] = start << 16 | count of that run;
+//      bucket (a range of 1024 targets, of 512 if L > 16: the lists of a range have to fit the
+//      LDS), and writes them to its own part of the offer array, bucket after bucket;
+//      table[bucket][block] = start << 16 | count of that run;
 //   2. a list block (one per bucket) walks the runs of its bucket, one thread per offer, and
 //      enters every key into the target's list in LDS with the bounded insertion; lists and
 //      counts (filled slots) go out in one contiguous piece.
 // Whatever the order of the offers, a list ends up with the L smallest keys offered to it.
 
-constexpr int kBktRows = 1024;        // source rows per offer block = targets per bucket
+constexpr int kBktRows = 1024;        // source rows per offer block
 constexpr int kBktThreads = 1024;
-constexpr int64_t kBktMaxN = 1 << 21;    // table of (n / kBktRows)^2 runs: 16 MB at most; targets fit 21 bits
+constexpr int kBktMaxRuns = 2 * kBktThreads;    // buckets and offer blocks a block-wide scan of two per thread takes
 static_assert(kBktRows == 1024, "an offer word keeps the source row in ten bits");
+
+// log2 of the targets per bucket
+__host__ __device__ inline int bucket_shift(int L) { return L <= 16 ? 10 : 9; }
 
 __host__ __device__ inline size_t bucket_lists_lds(int L, int n_blocks);
 
 __host__ __device__ inline bool bucketed_lists(int64_t n, int K, int L)
 {
-    return K <= 16 && L <= 16 && n <= kBktMaxN &&
-           bucket_lists_lds(L, (int)((n + kBktRows - 1) / kBktRows)) <= 160 * 1024 - 256;
+    if (K > 32 || L > 32 || n > (1 << 21)) return false;      // (targets fit 21 bits of an offer word)
+    const int64_t n_blocks = (n + kBktRows - 1) / kBktRows, n_buckets = ((n - 1) >> bucket_shift(L)) + 1;
+    return n_blocks <= kBktMaxRuns && n_buckets <= kBktMaxRuns &&
+           bucket_lists_lds(L, (int)n_blocks) <= 160 * 1024 - 256;
 }
 
 // All lanes of the wave call this together; lanes with `take` set append `offer`.
-__device__ inline void offer_append(bool take, u32 offer, u32 *offers, int *hist, int *fill)
+__device__ inline void offer_append(bool take, u32 offer, int shift, u32 *offers, int *hist, int *fill)
 {
     const u64 mask = __ballot(take);
     if (mask == 0) return;
@@ -968,13 +974,13 @@ __device__ inline void offer_append(bool take, u32 offer, u32 *offers, int *hist
     base = __shfl(base, leader, EF_WAVE);
     if (take) {
         offers[base + lanes_below(mask)] = offer;
-        atomicAdd(&hist[offer >> 20], 1);
+        atomicAdd(&hist[offer >> (10 + shift)], 1);
     }
 }
 
 // End of an offer block: runs per bucket in `out` (this block's part of the offer array) and
-// the block's column of the table.  hist, cursor: [n_buckets] in LDS, n_buckets <= 2 * kBktThreads.
-__device__ inline void offers_flush(const u32 *offers, const int *hist, int *cursor, int n_buckets,
+// the block's column of the table.  hist, cursor: [n_buckets] in LDS, n_buckets <= kBktMaxRuns.
+__device__ inline void offers_flush(const u32 *offers, const int *hist, int *cursor, int n_buckets, int shift,
                                     int total, u32 *__restrict__ out, u32 *__restrict__ table)
 {
     __shared__ int wave_tot[kBktThreads / EF_WAVE];
@@ -996,15 +1002,17 @@ __device__ inline void offers_flush(const u32 *offers, const int *hist, int *cur
     __syncthreads();
     for (int e = t; e < total; e += kBktThreads) {
         const u32 o = offers[e];
-        out[atomicAdd(&cursor[o >> 20], 1)] = o;
+        out[atomicAdd(&cursor[o >> (10 + shift)], 1)] = o;
     }
 }
 
 // Alg. 4 step 1+2 for short rows: sample_row for kBktRows rows, the reverse-new offers to the
 // block's runs.  LDS: offers [kBktRows * L] words, hist and cursor [n_buckets] int each.
+// E: entries per lane of a row's eight lanes (8 E >= K).
+template <int E>
 __global__ void __launch_bounds__(kBktThreads)
 sample_bucket_kernel(u64 *graph, int n, int K, int L, int *__restrict__ nw, int *__restrict__ od,
-                     int *__restrict__ nw_c, int *__restrict__ od_c, u32 *worst, int n_buckets,
+                     int *__restrict__ nw_c, int *__restrict__ od_c, u32 *worst, int n_buckets, int shift,
                      u32 *__restrict__ offer_runs, u32 *__restrict__ table)
 {
     extern __shared__ __align__(16) u32 offer_sm[];
@@ -1019,24 +1027,24 @@ sample_bucket_kernel(u64 *graph, int n, int K, int L, int *__restrict__ nw, int 
     // eight lanes with two entries each per row: a wave ranks eight rows with the broadcasts that
     // four rows of sixteen lanes would take (147 -> 93 us on the headline; four or two lanes
     // per row: the same again)
-    constexpr int G = 8, E = 2, kRowsPerPass = kBktThreads / G;
+    constexpr int G = 8, kRowsPerPass = kBktThreads / G;
     for (int pass = 0; pass < kBktRows / kRowsPerPass; ++pass) {
         const int i = blockIdx.x * kBktRows + pass * kRowsPerPass + (int)(threadIdx.x / G);
         u64 e[E];
         sample_load<G, E>(graph, i, i < n, K, e);
         sample_row<G, E>(graph, e, i, i < n, K, L, nw, od, nw_c, od_c, worst, [&](bool take, int id) {
-            offer_append(take, ((u32)id << 10) | (u32)(i & (kBktRows - 1)), offers, hist, &fill);
+            offer_append(take, ((u32)id << 10) | (u32)(i & (kBktRows - 1)), shift, offers, hist, &fill);
         });
     }
     __syncthreads();
-    offers_flush(offers, hist, cursor, n_buckets, fill, offer_runs + (size_t)blockIdx.x * kBktRows * L, table);
+    offers_flush(offers, hist, cursor, n_buckets, shift, fill, offer_runs + (size_t)blockIdx.x * kBktRows * L, table);
 }
 
 // Reverse-old offers of kBktRows rows (to points that join something, as in reverse_old_kernel).
 // LDS: offers [kBktRows * K] words, hist and cursor [n_buckets] int each.
 __global__ void __launch_bounds__(kBktThreads)
 reverse_old_bucket_kernel(const int *__restrict__ od, int n, int K, const u64 *__restrict__ active,
-                          int n_buckets, u32 *__restrict__ offer_runs, u32 *__restrict__ table)
+                          int n_buckets, int shift, u32 *__restrict__ offer_runs, u32 *__restrict__ table)
 {
     extern __shared__ __align__(16) u32 offer_sm[];
     u32 *offers = offer_sm;
@@ -1050,17 +1058,17 @@ reverse_old_bucket_kernel(const int *__restrict__ od, int n, int K, const u64 *_
         const int f = f0 + (int)threadIdx.x;
         const int id = f < rows_here * K ? od[(size_t)first * K + f] : -1;
         const bool take = id >= 0 && ((active[id / EF_WAVE] >> (id % EF_WAVE)) & 1);
-        offer_append(take, ((u32)id << 10) | (u32)(f / K), offers, hist, &fill);
+        offer_append(take, ((u32)id << 10) | (u32)(f / K), shift, offers, hist, &fill);
     }
     __syncthreads();
-    offers_flush(offers, hist, cursor, n_buckets, fill, offer_runs + (size_t)blockIdx.x * kBktRows * K, table);
+    offers_flush(offers, hist, cursor, n_buckets, shift, fill, offer_runs + (size_t)blockIdx.x * kBktRows * K, table);
 }
 
 // The lists of one bucket.  run_cap: offers per part of an offer block (kBktRows * L or * K).
 // Every key goes through the bounded insertion; all slots start as the largest key, so a list
 // fills from slot 0 up and then keeps its L smallest keys.
-// LDS: lists [kBktRows * L] u64, scan [n_blocks + 1] and start [n_blocks] int;
-// n_blocks <= 2 * kBktThreads.
+// LDS: lists [bucket's targets * L] u64, scan [n_blocks + 1] and start [n_blocks] int;
+// n_blocks <= kBktMaxRuns.
 // What the time is made of (headline workload, 93 us per launch on average, 190 us for the
 // ten million offers of the first iteration): 18 us fixed, about 5 ns per thousand offers to
 // find and load them, the rest the insertions; by the counters the SIMDs issue an instruction
@@ -1075,7 +1083,7 @@ reverse_old_bucket_kernel(const int *__restrict__ od, int n, int K, const u64 *_
 // found twice).
 __host__ __device__ inline size_t bucket_lists_lds(int L, int n_blocks)
 {
-    return (size_t)kBktRows * L * 8 + ((size_t)2 * n_blocks + 2) * 4;
+    return ((size_t)L << bucket_shift(L)) * 8 + ((size_t)2 * n_blocks + 2) * 4;
 }
 
 __global__ void __launch_bounds__(kBktThreads)
@@ -1085,10 +1093,11 @@ bucket_lists_kernel(const u32 *__restrict__ offer_runs, const u32 *__restrict__ 
 {
     extern __shared__ __align__(16) u64 list_sm[];
     u64 *ll = list_sm;
-    int *scan = (int *)(ll + (size_t)kBktRows * L), *start = scan + n_blocks + 1;
+    const int targets = 1 << bucket_shift(L);
+    int *scan = (int *)(ll + (size_t)targets * L), *start = scan + n_blocks + 1;
     __shared__ int wave_tot[kBktThreads / EF_WAVE];
-    const int t = threadIdx.x, first = blockIdx.x * kBktRows, rows_here = min(kBktRows, n - first);
-    for (int f = t; f < kBktRows * L; f += kBktThreads) ll[f] = ~0ULL;
+    const int t = threadIdx.x, first = blockIdx.x * targets, rows_here = min(targets, n - first);
+    for (int f = t; f < targets * L; f += kBktThreads) ll[f] = ~0ULL;
     const u32 *runs = table + (size_t)blockIdx.x * n_blocks;
     {
         const int k0 = 2 * t;
@@ -1981,10 +1990,10 @@ NndWs carve_nnd(void *ws, int64_t n, int K, int L)
     // reverse lists: either the overflow queues of the counter scheme or the offer runs and
     // their table of the bucket scheme
     const bool bkt = bucketed_lists(n, K, L);
-    const size_t n_bkt = (size_t)(n + kBktRows - 1) / kBktRows;
+    const size_t n_bkt = (size_t)(n + kBktRows - 1) / kBktRows, n_buckets = (size_t)((n - 1) >> bucket_shift(L)) + 1;
     w.overflow = take(bkt ? 0 : ovf_region_for(n, K) * kOvfQueues * sizeof(Overflow));
     w.offer_runs = (u32 *)take(bkt ? n_bkt * kBktRows * (size_t)(K > L ? K : L) * 4 : 0);
-    w.run_table = (u32 *)take(bkt ? n_bkt * n_bkt * 4 : 0);
+    w.run_table = (u32 *)take(bkt ? n_buckets * n_bkt * 4 : 0);
     w.ovf_count = (int *)take((size_t)kOvfQueues * kOvfCounterPitch * 4);
     w.ulist = (int *)take((size_t)n * (K + 2 * L) * 4);
     w.ucount = (int2 *)take((size_t)n * 8);
@@ -2184,13 +2193,14 @@ extern "C" int efanna_nndescent(const float *X, int64_t n, int32_t d, int32_t k,
     // reverse lists by buckets (short rows and lists): LDS of an offer block (words) or a list
     // block (keys) with `per_row` of them per row, and one int per bucket or offer block twice over
     const bool bkt = bucketed_lists(n, K, L);
-    const int n_bkt = (int)((n + kBktRows - 1) / kBktRows);
-    auto bkt_lds = [&](int per_row, int bytes) { return (size_t)kBktRows * per_row * bytes + ((size_t)2 * n_bkt + 4) * 4; };
+    const int n_bkt = (int)((n + kBktRows - 1) / kBktRows);      // offer blocks
+    const int bshift = bucket_shift(L), n_buckets = (int)(((n - 1) >> bshift) + 1);
+    auto bkt_lds = [&](int per_row) { return (size_t)kBktRows * per_row * 4 + ((size_t)2 * n_buckets + 4) * 4; };
     if (bkt) {
-        EF_HIP_CHECK(hipFuncSetAttribute((const void *)sample_bucket_kernel,
-                                         hipFuncAttributeMaxDynamicSharedMemorySize, (int)bkt_lds(L, 4)));
+        EF_HIP_CHECK(hipFuncSetAttribute(K <= 16 ? (const void *)sample_bucket_kernel<2> : (const void *)sample_bucket_kernel<4>,
+                                         hipFuncAttributeMaxDynamicSharedMemorySize, (int)bkt_lds(L)));
         EF_HIP_CHECK(hipFuncSetAttribute((const void *)reverse_old_bucket_kernel,
-                                         hipFuncAttributeMaxDynamicSharedMemorySize, (int)bkt_lds(K, 4)));
+                                         hipFuncAttributeMaxDynamicSharedMemorySize, (int)bkt_lds(K)));
         EF_HIP_CHECK(hipFuncSetAttribute((const void *)bucket_lists_kernel,
                                          hipFuncAttributeMaxDynamicSharedMemorySize, (int)bucket_lists_lds(L, n_bkt)));
     }
@@ -2237,9 +2247,13 @@ extern "C" int efanna_nndescent(const float *X, int64_t n, int32_t d, int32_t k,
     reverse_old_kernel<G><<<grid_for((size_t)n * G, kBlock), kBlock, 0, st>>>(                   \
         w.od, (int)n, K, L, ko, w.active, w.rold, w.rold_c, ovf, ovf_region, w.ovf_count)
             if (bkt) {
-                sample_bucket_kernel<<<n_bkt, kBktThreads, bkt_lds(L, 4), st>>>(
-                    graph, (int)n, K, L, w.nw, w.od, w.nw_c, w.od_c, w.worst, n_bkt, w.offer_runs, w.run_table);
-                bucket_lists_kernel<<<n_bkt, kBktThreads, bucket_lists_lds(L, n_bkt), st>>>(
+                if (K <= 16)
+                    sample_bucket_kernel<2><<<n_bkt, kBktThreads, bkt_lds(L), st>>>(
+                        graph, (int)n, K, L, w.nw, w.od, w.nw_c, w.od_c, w.worst, n_buckets, bshift, w.offer_runs, w.run_table);
+                else
+                    sample_bucket_kernel<4><<<n_bkt, kBktThreads, bkt_lds(L), st>>>(
+                        graph, (int)n, K, L, w.nw, w.od, w.nw_c, w.od_c, w.worst, n_buckets, bshift, w.offer_runs, w.run_table);
+                bucket_lists_kernel<<<n_buckets, kBktThreads, bucket_lists_lds(L, n_bkt), st>>>(
                     w.offer_runs, w.run_table, n_bkt, kBktRows * L, kn, (int)n, L, w.rnew, w.rnew_c);
             } else if (K <= 16) EF_SAMPLE(16, 1);
             else if (K <= 32) EF_SAMPLE(32, 1);
@@ -2247,9 +2261,9 @@ extern "C" int efanna_nndescent(const float *X, int64_t n, int32_t d, int32_t k,
             else EF_SAMPLE(64, 2);
             active_kernel<<<grid_for((size_t)n, kBlock), kBlock, 0, st>>>(w.nw_c, w.rnew_c, (int)n, w.active);
             if (bkt) {
-                reverse_old_bucket_kernel<<<n_bkt, kBktThreads, bkt_lds(K, 4), st>>>(
-                    w.od, (int)n, K, w.active, n_bkt, w.offer_runs, w.run_table);
-                bucket_lists_kernel<<<n_bkt, kBktThreads, bucket_lists_lds(L, n_bkt), st>>>(
+                reverse_old_bucket_kernel<<<n_bkt, kBktThreads, bkt_lds(K), st>>>(
+                    w.od, (int)n, K, w.active, n_buckets, bshift, w.offer_runs, w.run_table);
+                bucket_lists_kernel<<<n_buckets, kBktThreads, bucket_lists_lds(L, n_bkt), st>>>(
                     w.offer_runs, w.run_table, n_bkt, kBktRows * K, ko, (int)n, L, w.rold, w.rold_c);
             } else if (K <= 16) EF_REVERSE_OLD(16);
             else if (K <= 32) EF_REVERSE_OLD(32);
