@@ -255,8 +255,10 @@ def test_nndescent_bit_exact_every_iteration(ef, name, n, T, S, K, L, I):
     (33, 8, 1, 64, 5, 5, 2),             # one leaf holds everything
     (65, 4, 3, 1, 4, 2, 4),              # leaves of one point: the initial graph is empty
     (1_025, 8, 2, 16, 10, 10, 3),        # reverse lists by target ranges of 1024: a second range of one point
-    (5_000, 8, 2, 16, 16, 16, 2),        # the longest rows and lists that scheme takes, a ragged last range
-    (2_100, 8, 2, 16, 16, 17, 2),        # one more: the counter scheme with 16 lanes per row
+    (5_000, 8, 2, 16, 16, 16, 2),        # the longest lists with ranges of 1024, a ragged last range
+    (2_100, 8, 2, 16, 16, 17, 2),        # one more: ranges of 512 targets
+    (3_000, 8, 2, 16, 32, 32, 2),        # the longest rows and lists that scheme takes
+    (2_000, 8, 2, 16, 33, 16, 1),        # one more: lists by counters
     (4_096, 12, 2, 16, 3, 1, 4),         # lists of a single key
 ])
 def test_nndescent_more_shapes(ef, n, d, T, S, K, L, I):
