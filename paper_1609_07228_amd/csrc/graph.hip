@@ -1086,14 +1086,16 @@ __host__ __device__ inline size_t bucket_lists_lds(int L, int n_blocks)
     return ((size_t)L << bucket_shift(L)) * 8 + ((size_t)2 * n_blocks + 2) * 4;
 }
 
+template <int SHIFT, int LT>      // log2 of the bucket's targets; the list length if fixed at compile time, else 0
 __global__ void __launch_bounds__(kBktThreads)
 bucket_lists_kernel(const u32 *__restrict__ offer_runs, const u32 *__restrict__ table, int n_blocks,
-                    int run_cap, u64 stream_key, int n, int L, u64 *__restrict__ lists,
+                    int run_cap, u64 stream_key, int n, int L_, u64 *__restrict__ lists,
                     int *__restrict__ counts)
 {
+    const int L = LT ? LT : L_;
     extern __shared__ __align__(16) u64 list_sm[];
     u64 *ll = list_sm;
-    const int targets = 1 << bucket_shift(L);
+    constexpr int targets = 1 << SHIFT;
     int *scan = (int *)(ll + (size_t)targets * L), *start = scan + n_blocks + 1;
     __shared__ int wave_tot[kBktThreads / EF_WAVE];
     const int t = threadIdx.x, first = blockIdx.x * targets, rows_here = min(targets, n - first);
@@ -2201,7 +2203,11 @@ extern "C" int efanna_nndescent(const float *X, int64_t n, int32_t d, int32_t k,
                                          hipFuncAttributeMaxDynamicSharedMemorySize, (int)bkt_lds(L)));
         EF_HIP_CHECK(hipFuncSetAttribute((const void *)reverse_old_bucket_kernel,
                                          hipFuncAttributeMaxDynamicSharedMemorySize, (int)bkt_lds(K)));
-        EF_HIP_CHECK(hipFuncSetAttribute((const void *)bucket_lists_kernel,
+        // (list lengths of 10 and 20 are compiled in: the scan of a list unrolls, 8 % off the kernel)
+        EF_HIP_CHECK(hipFuncSetAttribute(L == 10   ? (const void *)bucket_lists_kernel<10, 10>
+                                         : L == 20 ? (const void *)bucket_lists_kernel<9, 20>
+                                         : bshift == 10 ? (const void *)bucket_lists_kernel<10, 0>
+                                                        : (const void *)bucket_lists_kernel<9, 0>,
                                          hipFuncAttributeMaxDynamicSharedMemorySize, (int)bucket_lists_lds(L, n_bkt)));
     }
     if (max_rows > rows1)
@@ -2243,6 +2249,21 @@ extern "C" int efanna_nndescent(const float *X, int64_t n, int32_t d, int32_t k,
     sample_kernel<G, E><<<grid_for((size_t)n * G, kBlock), kBlock, 0, st>>>(                     \
         graph, (int)n, K, L, kn, w.nw, w.od, w.nw_c, w.od_c, w.rnew, w.rnew_c, ovf,              \
         ovf_region, w.ovf_count, w.worst)
+#define EF_BUCKET_LISTS(RUN_CAP, KEY, LISTS, COUNTS)                                             \
+    do {                                                                                         \
+        if (L == 10)                                                                             \
+            bucket_lists_kernel<10, 10><<<n_buckets, kBktThreads, bucket_lists_lds(L, n_bkt), st>>>( \
+                w.offer_runs, w.run_table, n_bkt, RUN_CAP, KEY, (int)n, L, LISTS, COUNTS);       \
+        else if (L == 20)                                                                        \
+            bucket_lists_kernel<9, 20><<<n_buckets, kBktThreads, bucket_lists_lds(L, n_bkt), st>>>( \
+                w.offer_runs, w.run_table, n_bkt, RUN_CAP, KEY, (int)n, L, LISTS, COUNTS);       \
+        else if (bshift == 10)                                                                   \
+            bucket_lists_kernel<10, 0><<<n_buckets, kBktThreads, bucket_lists_lds(L, n_bkt), st>>>( \
+                w.offer_runs, w.run_table, n_bkt, RUN_CAP, KEY, (int)n, L, LISTS, COUNTS);       \
+        else                                                                                     \
+            bucket_lists_kernel<9, 0><<<n_buckets, kBktThreads, bucket_lists_lds(L, n_bkt), st>>>( \
+                w.offer_runs, w.run_table, n_bkt, RUN_CAP, KEY, (int)n, L, LISTS, COUNTS);       \
+    } while (0)
 #define EF_REVERSE_OLD(G)                                                                        \
     reverse_old_kernel<G><<<grid_for((size_t)n * G, kBlock), kBlock, 0, st>>>(                   \
         w.od, (int)n, K, L, ko, w.active, w.rold, w.rold_c, ovf, ovf_region, w.ovf_count)
@@ -2253,8 +2274,7 @@ extern "C" int efanna_nndescent(const float *X, int64_t n, int32_t d, int32_t k,
                 else
                     sample_bucket_kernel<4><<<n_bkt, kBktThreads, bkt_lds(L), st>>>(
                         graph, (int)n, K, L, w.nw, w.od, w.nw_c, w.od_c, w.worst, n_buckets, bshift, w.offer_runs, w.run_table);
-                bucket_lists_kernel<<<n_buckets, kBktThreads, bucket_lists_lds(L, n_bkt), st>>>(
-                    w.offer_runs, w.run_table, n_bkt, kBktRows * L, kn, (int)n, L, w.rnew, w.rnew_c);
+                EF_BUCKET_LISTS(kBktRows * L, kn, w.rnew, w.rnew_c);
             } else if (K <= 16) EF_SAMPLE(16, 1);
             else if (K <= 32) EF_SAMPLE(32, 1);
             else if (K <= 64) EF_SAMPLE(64, 1);
@@ -2263,13 +2283,13 @@ extern "C" int efanna_nndescent(const float *X, int64_t n, int32_t d, int32_t k,
             if (bkt) {
                 reverse_old_bucket_kernel<<<n_bkt, kBktThreads, bkt_lds(K), st>>>(
                     w.od, (int)n, K, w.active, n_buckets, bshift, w.offer_runs, w.run_table);
-                bucket_lists_kernel<<<n_buckets, kBktThreads, bucket_lists_lds(L, n_bkt), st>>>(
-                    w.offer_runs, w.run_table, n_bkt, kBktRows * K, ko, (int)n, L, w.rold, w.rold_c);
+                EF_BUCKET_LISTS(kBktRows * K, ko, w.rold, w.rold_c);
             } else if (K <= 16) EF_REVERSE_OLD(16);
             else if (K <= 32) EF_REVERSE_OLD(32);
             else EF_REVERSE_OLD(64);
 #undef EF_SAMPLE
 #undef EF_REVERSE_OLD
+#undef EF_BUCKET_LISTS
             if (bkt) {
             } else if (L >= 2 * EF_WIDE_PIECES)
                 reverse_overflow_kernel<true><<<dim3(kOvfBlocksPerQueue, kOvfQueues), kBlock, 0, st>>>(
