@@ -1485,14 +1485,15 @@ __device__ inline int propose_pair(Proposal *queue, int fill, bool mine, float d
     return fill + __popcll(mask_b);
 }
 
-template <int NB, bool ONE>
+template <int NB, bool ONE, int KT>      // KT: the row length if fixed at compile time (the row scans unroll), else 0
 __global__ void __launch_bounds__(EF_WAVE) __attribute__((amdgpu_waves_per_eu(NB > 1 ? 3 : 4)))
-join_reg_kernel(const float *__restrict__ X, const float *__restrict__ norms, int d, int K,
+join_reg_kernel(const float *__restrict__ X, const float *__restrict__ norms, int d, int K_,
                 const int *__restrict__ work, const int *__restrict__ work_count, int q_cap,
                 float margin_rel, float thr_scale, const int *__restrict__ ulist,
                 const int2 *__restrict__ ucount, int ucap, u64 *graph, u32 *worst,
                 int *__restrict__ upd_block)
 {
+    const int K = KT ? KT : K_;
     constexpr int R = 16 * NB;                    // rows
     constexpr int S_CAP = R * (R - 1) / 2 + 8;    // every pair may survive
     extern __shared__ __align__(16) float smem[];
@@ -2303,11 +2304,17 @@ extern "C" int efanna_nndescent(const float *X, int64_t n, int32_t d, int32_t k,
             (u32)(((1ULL << 32) + max_rows - 1) / max_rows), rows0, rows1, w.ulist, w.ucount, w.work, w.work_count, w.part);
         if (ev) EF_HIP_CHECK(hipEventRecord(ev[5 * it + 1], st));
         if (reg_ok) {
-#define EF_JOIN_REG(NB, ONE, LIST)                                                                 \
-    join_reg_kernel<NB, ONE><<<reg_grid, EF_WAVE, reg_lds(16 * NB), st>>>(                         \
+#define EF_JOIN_REG_K(NB, ONE, LIST, KT)                                                           \
+    join_reg_kernel<NB, ONE, KT><<<reg_grid, EF_WAVE, reg_lds(16 * NB), st>>>(                     \
         X, w.norms, d, K, w.work + (size_t)(LIST) * n, w.work_count + (LIST), reg_q_cap_for(16 * NB), \
         margin_rel, thr_scale, w.ulist, w.ucount, max_rows, graph, w.worst,                        \
         w.upd_block + (LIST) * reg_grid)
+    // (a row length of 10 is compiled in: 3 % off the joins of 17..32 vectors)
+#define EF_JOIN_REG(NB, ONE, LIST)                                                                 \
+    do {                                                                                           \
+        if (K == 10) EF_JOIN_REG_K(NB, ONE, LIST, 10);                                             \
+        else EF_JOIN_REG_K(NB, ONE, LIST, 0);                                                      \
+    } while (0)
             if (d <= 128) EF_JOIN_REG(1, true, 0);
             else EF_JOIN_REG(1, false, 0);
             if (ev) EF_HIP_CHECK(hipEventRecord(ev[5 * it + 2], st));
@@ -2316,6 +2323,7 @@ extern "C" int efanna_nndescent(const float *X, int64_t n, int32_t d, int32_t k,
                 else EF_JOIN_REG(2, false, 1);
             }
 #undef EF_JOIN_REG
+#undef EF_JOIN_REG_K
         } else if (ev) {
             EF_HIP_CHECK(hipEventRecord(ev[5 * it + 2], st));
         }
