@@ -1033,7 +1033,10 @@ sample_bucket_kernel(u64 *graph, int n, int K, int L, int *__restrict__ nw, int 
         u64 e[E];
         sample_load<G, E>(graph, i, i < n, K, e);
         sample_row<G, E>(graph, e, i, i < n, K, L, nw, od, nw_c, od_c, worst, [&](bool take, int id) {
-            offer_append(take, ((u32)id << 10) | (u32)(i & (kBktRows - 1)), shift, offers, hist, &fill);
+            // (an id outside the data, from a graph the library did not write, is not offered:
+            // it would index the bucket counters out of bounds)
+            offer_append(take && (unsigned)id < (unsigned)n, ((u32)id << 10) | (u32)(i & (kBktRows - 1)), shift, offers,
+                         hist, &fill);
         });
     }
     __syncthreads();
@@ -1057,7 +1060,7 @@ reverse_old_bucket_kernel(const int *__restrict__ od, int n, int K, const u64 *_
     for (int f0 = 0; f0 < rows_here * K; f0 += kBktThreads) {      // all threads take every round
         const int f = f0 + (int)threadIdx.x;
         const int id = f < rows_here * K ? od[(size_t)first * K + f] : -1;
-        const bool take = id >= 0 && ((active[id / EF_WAVE] >> (id % EF_WAVE)) & 1);
+        const bool take = id >= 0 && id < n && ((active[id / EF_WAVE] >> (id % EF_WAVE)) & 1);
         offer_append(take, ((u32)id << 10) | (u32)(f / K), shift, offers, hist, &fill);
     }
     __syncthreads();
