@@ -1092,7 +1092,7 @@ __host__ __device__ inline size_t bucket_lists_lds(int L, int n_blocks)
 template <int SHIFT, int LT>      // log2 of the bucket's targets; the list length if fixed at compile time, else 0
 __global__ void __launch_bounds__(kBktThreads)
 bucket_lists_kernel(const u32 *__restrict__ offer_runs, const u32 *__restrict__ table, int n_blocks,
-                    int run_cap, u64 stream_key, int n, int L_, u64 *__restrict__ lists,
+                    int run_cap, u64 stream_key, int n, int L_, u32 *__restrict__ lists,
                     int *__restrict__ counts)
 {
     const int L = LT ? LT : L_;
@@ -1154,7 +1154,8 @@ bucket_lists_kernel(const u32 *__restrict__ offer_runs, const u32 *__restrict__ 
         }
     }
     __syncthreads();
-    for (int f = t; f < rows_here * L; f += kBktThreads) lists[(size_t)first * L + f] = ll[f];
+    // only the sources are wanted from here on (the keys decided who is in the list)
+    for (int f = t; f < rows_here * L; f += kBktThreads) lists[(size_t)first * L + f] = (u32)ll[f];
     if (t < rows_here) {
         int c = 0;
         for (int a = 0; a < L; ++a) c += ll[t * L + a] != ~0ULL ? 1 : 0;
@@ -1170,6 +1171,7 @@ bucket_lists_kernel(const u32 *__restrict__ offer_runs, const u32 *__restrict__ 
 // ids inside one sampled list are distinct, and so are the sources inside one reverse
 // list.  ulist: [n][cap] (written through LDS so that the stores coalesce), ucount: [n]
 // (m_new, m); work: [3][n], work_count: [3].
+template <bool IDS32>      // reverse lists hold 32-bit sources (bucket scheme), not 64-bit keys
 __global__ void prepare_kernel(const int *__restrict__ nw, const int *__restrict__ od,
                                const int *__restrict__ nw_c, const int *__restrict__ od_c,
                                const u64 *__restrict__ rnew, const u64 *__restrict__ rold,
@@ -1192,7 +1194,7 @@ __global__ void prepare_kernel(const int *__restrict__ nw, const int *__restrict
         if (c_new + rn == 0) c_old = 0;      // empty U_new: no join, nothing to list
         for (int a = 0; a < c_new; ++a) mine[m++] = nw[(size_t)i * L + a];
         for (int a = 0; a < rn; ++a) {
-            const int id = (int)(u32)rnew[(size_t)i * L + a];
+            const int id = IDS32 ? (int)((const u32 *)rnew)[(size_t)i * L + a] : (int)(u32)rnew[(size_t)i * L + a];
             bool dup = false;
             for (int k = 0; k < c_new; ++k) dup |= mine[k] == id;
             if (!dup) mine[m++] = id;
@@ -1206,7 +1208,7 @@ __global__ void prepare_kernel(const int *__restrict__ nw, const int *__restrict
         }
         const int m_mid = m;
         for (int a = 0; a < ro; ++a) {
-            const int id = (int)(u32)rold[(size_t)i * L + a];
+            const int id = IDS32 ? (int)((const u32 *)rold)[(size_t)i * L + a] : (int)(u32)rold[(size_t)i * L + a];
             bool dup = false;
             for (int k = 0; k < m_mid; ++k) dup |= mine[k] == id;
             if (!dup) mine[m++] = id;
@@ -2257,16 +2259,16 @@ extern "C" int efanna_nndescent(const float *X, int64_t n, int32_t d, int32_t k,
     do {                                                                                         \
         if (L == 10)                                                                             \
             bucket_lists_kernel<10, 10><<<n_buckets, kBktThreads, bucket_lists_lds(L, n_bkt), st>>>( \
-                w.offer_runs, w.run_table, n_bkt, RUN_CAP, KEY, (int)n, L, LISTS, COUNTS);       \
+                w.offer_runs, w.run_table, n_bkt, RUN_CAP, KEY, (int)n, L, (u32 *)(LISTS), COUNTS); \
         else if (L == 20)                                                                        \
             bucket_lists_kernel<9, 20><<<n_buckets, kBktThreads, bucket_lists_lds(L, n_bkt), st>>>( \
-                w.offer_runs, w.run_table, n_bkt, RUN_CAP, KEY, (int)n, L, LISTS, COUNTS);       \
+                w.offer_runs, w.run_table, n_bkt, RUN_CAP, KEY, (int)n, L, (u32 *)(LISTS), COUNTS); \
         else if (bshift == 10)                                                                   \
             bucket_lists_kernel<10, 0><<<n_buckets, kBktThreads, bucket_lists_lds(L, n_bkt), st>>>( \
-                w.offer_runs, w.run_table, n_bkt, RUN_CAP, KEY, (int)n, L, LISTS, COUNTS);       \
+                w.offer_runs, w.run_table, n_bkt, RUN_CAP, KEY, (int)n, L, (u32 *)(LISTS), COUNTS); \
         else                                                                                     \
             bucket_lists_kernel<9, 0><<<n_buckets, kBktThreads, bucket_lists_lds(L, n_bkt), st>>>( \
-                w.offer_runs, w.run_table, n_bkt, RUN_CAP, KEY, (int)n, L, LISTS, COUNTS);       \
+                w.offer_runs, w.run_table, n_bkt, RUN_CAP, KEY, (int)n, L, (u32 *)(LISTS), COUNTS); \
     } while (0)
 #define EF_REVERSE_OLD(G)                                                                        \
     reverse_old_kernel<G><<<grid_for((size_t)n * G, kBlock), kBlock, 0, st>>>(                   \
@@ -2302,9 +2304,14 @@ extern "C" int efanna_nndescent(const float *X, int64_t n, int32_t d, int32_t k,
                 reverse_overflow_kernel<false><<<dim3(kOvfBlocksPerQueue, kOvfQueues), kBlock, 0, st>>>(
                     ovf, ovf_region, w.ovf_count, (size_t)n, w.rnew, w.rold, w.list_max, L);
         }
-        prepare_kernel<<<grid_for((size_t)n, prep_threads), prep_threads, prep_lds, st>>>(
-            w.nw, w.od, w.nw_c, w.od_c, w.rnew, w.rold, w.rnew_c, w.rold_c, (int)n, K, L, max_rows,
-            (u32)(((1ULL << 32) + max_rows - 1) / max_rows), rows0, rows1, w.ulist, w.ucount, w.work, w.work_count, w.part);
+#define EF_PREPARE(IDS32)                                                                          \
+    prepare_kernel<IDS32><<<grid_for((size_t)n, prep_threads), prep_threads, prep_lds, st>>>(       \
+        w.nw, w.od, w.nw_c, w.od_c, w.rnew, w.rold, w.rnew_c, w.rold_c, (int)n, K, L, max_rows,     \
+        (u32)(((1ULL << 32) + max_rows - 1) / max_rows), rows0, rows1, w.ulist, w.ucount, w.work,  \
+        w.work_count, w.part)
+        if (bkt) EF_PREPARE(true);
+        else EF_PREPARE(false);
+#undef EF_PREPARE
         if (ev) EF_HIP_CHECK(hipEventRecord(ev[5 * it + 1], st));
         if (reg_ok) {
 #define EF_JOIN_REG_K(NB, ONE, LIST, KT)                                                           \
