@@ -2244,8 +2244,9 @@ extern "C" int efanna_nndescent(const float *X, int64_t n, int32_t d, int32_t k,
     for (int it = 0; it < iters; ++it) {
         const int g = first_iter + it;
         if (ev) EF_HIP_CHECK(hipEventRecord(ev[5 * it], st));
-        fill_reverse_kernel<<<grid_for((size_t)n, kBlock), kBlock, 0, st>>>(
-            w.rnew_c, w.rold_c, w.list_max, (size_t)n, w.work_count, w.upd_block,
+        // (the bucket scheme writes every list count itself: only the small arrays are reset)
+        fill_reverse_kernel<<<grid_for(bkt ? (size_t)(2 * kRegGrid + kMaxLargeGrid) : (size_t)n, kBlock), kBlock, 0, st>>>(
+            w.rnew_c, w.rold_c, w.list_max, bkt ? (size_t)0 : (size_t)n, w.work_count, w.upd_block,
             2 * kRegGrid + kMaxLargeGrid, w.ovf_count);
         {
             const u64 kn = ef_stream_key(seed, 2 * g), ko = ef_stream_key(seed, 2 * g + 1);
