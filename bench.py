@@ -111,40 +111,40 @@ def main():
     k_ms_sum, k_bytes_sum, k_launches = 0.0, 0.0, 0
     all_ms_sum, all_bytes_sum = 0.0, 0.0
 
+    # Phase times come from events on the launch stream, read after the timed region: a step has
+    # no host synchronisation of its own (the tree build reads its level counters and the phase
+    # timing of efanna_nndescent waits for the stream; both are part of the library calls).
+    step_events = []
+
     def step(timed: bool):
-        nonlocal k_ms_sum, k_bytes_sum, k_launches, all_ms_sum, all_bytes_sum
-        t0 = time.perf_counter()
+        ev = [torch.cuda.Event(enable_timing=True) for _ in range(5)]
+        ev[0].record()
         trees = efanna.efanna_build_trees(Xd, T, S, synth.ALGO_SEED, max_leaves=max_leaves,
                                           workspace=ws_tree, with_nodes=conquer)
         perm, leaf_off, n_leaves = trees[:3]
-        t1 = time.perf_counter()          # build_trees returns synchronised
+        ev[1].record()
         if conquer:
             efanna.efanna_init_graph(Xd, perm, leaf_off, n_leaves, S, K, graph=graph, workspace=ws_init,
                                      nodes=trees[3], leaf_up=trees[4], tree_depth=trees[5],
                                      conquer_depth=args.conquer_depth)
         else:
             efanna.efanna_init_graph(Xd, perm, leaf_off, n_leaves, S, K, graph=graph, workspace=ws_init)
-        torch.cuda.synchronize()
-        t2 = time.perf_counter()
+        ev[2].record()
         efanna.efanna_nndescent(Xd, graph, I, L, synth.ALGO_SEED, stats=stats, workspace=ws_nnd,
                                 phase_ms=phase_ms)
-        t3 = time.perf_counter()          # synchronised by the phase timing
+        ev[3].record()
         ids, dists = efanna.efanna_get_graph(graph)
-        torch.cuda.synchronize()
-        t4 = time.perf_counter()
+        ev[4].record()
         if args.progress:
-            print(f"step: trees {t1 - t0:.3f} s, init {t2 - t1:.3f} s, nndescent {t3 - t2:.3f} s, "
-                  f"get {t4 - t3:.3f} s", file=sys.stderr, flush=True)
+            torch.cuda.synchronize()
+            print("step: trees %.3f ms, init %.3f ms, nndescent %.3f ms, get %.3f ms"
+                  % tuple(ev[k].elapsed_time(ev[k + 1]) for k in range(4)), file=sys.stderr, flush=True)
         if timed:
-            phases[:] += (t1 - t0, t2 - t1, t3 - t2, t4 - t3)
-            st = stats.cpu().numpy()
-            k_ms_sum += float(phase_ms[:, 1].sum())
-            k_bytes_sum += float((st[:, 3] * (d * 4 + 8)).sum())
-            k_launches += I
-            all_ms_sum += float(phase_ms[:, 1:].sum())
-            all_bytes_sum += float((st[:, 2] * (d * 4 + 8) + st[:, 1] * 8).sum())
+            step_events.append(ev)
+            step_phase_ms.append(phase_ms.copy())      # host memory, filled by the call above
         state.update(perm=perm, leaf_off=leaf_off, n_leaves=n_leaves, ids=ids, dists=dists)
 
+    step_phase_ms = []
     for _ in range(args.warmup):
         step(False)
     torch.cuda.synchronize()
@@ -153,6 +153,15 @@ def main():
         step(True)
     torch.cuda.synchronize()
     seconds = (time.perf_counter() - t_begin) / max(1, args.steps)
+    for ev in step_events:
+        phases[:] += [ev[k].elapsed_time(ev[k + 1]) * 1e-3 for k in range(4)]
+    st_steps = stats.cpu().numpy()      # the path is deterministic: the same in every step
+    for pm in step_phase_ms:
+        k_ms_sum += float(pm[:, 1].sum())
+        k_bytes_sum += float((st_steps[:, 3] * (d * 4 + 8)).sum())
+        k_launches += I
+        all_ms_sum += float(pm[:, 1:].sum())
+        all_bytes_sum += float((st_steps[:, 2] * (d * 4 + 8) + st_steps[:, 1] * 8).sum())
 
     if args.calibrate:
         a = torch.empty(64 * 1024 * 1024, dtype=torch.float32, device=dev)
