@@ -755,7 +755,16 @@ extern "C" int efanna_build_trees(const float *X, int64_t n, int32_t d, int32_t 
     const int fin = finish_limit(S);
     roots_kernel<<<grid_pos, kBlock, 0, st>>>(w.nodes_a, w.dims_a, w.node_a, w.leaf_flag, (int)n, T, S, fin,
                                               w.small, seed, d, w.counters);
-    Counters host_c;
+    // The level counters are read into pinned host memory (one small buffer per calling thread,
+    // kept for the life of the process): a copy to pageable memory is staged and takes some 20 us
+    // longer, during which the GPU has nothing to do.  Without pinned memory: a local variable.
+    Counters host_local;
+    thread_local Counters *host_pinned = nullptr;
+    if (!host_pinned && hipHostMalloc((void **)&host_pinned, sizeof(Counters), hipHostMallocDefault) != hipSuccess) {
+        host_pinned = nullptr;
+        (void)hipGetLastError();
+    }
+    Counters &host_c = host_pinned ? *host_pinned : host_local;
     EF_HIP_CHECK(hipMemcpyAsync(&host_c, w.counters, sizeof(Counters), hipMemcpyDeviceToHost, st));
     EF_HIP_CHECK(hipStreamSynchronize(st));
     if (host_c.bad_input) return EFANNA_EINPUT;
