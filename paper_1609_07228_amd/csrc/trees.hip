@@ -251,20 +251,29 @@ struct FlagPred {
     const unsigned char *flag;
     __device__ int operator()(size_t p) const { return flag[p]; }
 };
+// a predicate that scan_reduce_kernel has evaluated and kept, one bit per position
+struct BitsPred {
+    const u64 *bits;
+    __device__ int operator()(size_t p) const { return (int)((bits[p >> 6] >> (p & 63)) & 1); }
+};
 
 // A scan block covers kScanTile consecutive positions; thread t looks at positions t,
 // t + kBlock, ... of the tile, so that a wave reads consecutive words.  The predicates are
 // single bits: a wave counts them with a ballot.
+// bits (or null): the predicate of positions 64 w .. 64 w + 63 goes to bits[w], for the kernels
+// that need it again.
 template <class Pred>
-__global__ void scan_reduce_kernel(Pred pred, size_t total, int *block_sums)
+__global__ void scan_reduce_kernel(Pred pred, size_t total, int *block_sums, u64 *__restrict__ bits)
 {
     __shared__ int sh[kBlock / EF_WAVE];
     const size_t base = (size_t)blockIdx.x * kScanTile + threadIdx.x;
     int v = 0;
 #pragma unroll
     for (int k = 0; k < kScanItems; ++k) {
-        const size_t p = base + (size_t)k * kBlock;
-        v += __popcll(__ballot(p < total && pred(p)));
+        const size_t p = base + (size_t)k * kBlock;      // lane 0: a multiple of 64
+        const u64 bal = __ballot(p < total && pred(p));
+        v += __popcll(bal);
+        if (bits && ef_lane() == 0 && p < total) bits[p >> 6] = bal;
     }
     if (ef_lane() == 0) sh[threadIdx.x / EF_WAVE] = v;      // the whole wave holds the same count
     __syncthreads();
@@ -410,7 +419,7 @@ __global__ void children_kernel(Node *cur, int level, Node *next, int *next_dims
 
 __global__ void scatter_kernel(const int *__restrict__ perm_in, int *__restrict__ perm_out,
                                const int *__restrict__ node_in, int *__restrict__ node_out,
-                               const Node *__restrict__ nodes, const float *__restrict__ val,
+                               const Node *__restrict__ nodes, const u64 *__restrict__ left_bits,
                                const int *__restrict__ lcount, size_t total)
 {
     size_t p = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
@@ -425,8 +434,7 @@ __global__ void scatter_kernel(const int *__restrict__ perm_in, int *__restrict_
     const Node nd = nodes[s];
     size_t dst = p;
     if (nd.moved) {
-        long long cnt = nd.e - nd.b;
-        bool left = cnt * ef_quantise(val[p]) < nd.sum;
+        const bool left = (left_bits[p >> 6] >> (p & 63)) & 1;      // the split test, as the scan evaluated it
         int lc = lcount[p] - lcount[nd.b];
         dst = left ? (size_t)nd.b + lc : (size_t)nd.mid + ((int)(p - nd.b) - lc);
     }
@@ -666,6 +674,7 @@ struct TreeWs {
     int *perm_tmp, *node_a, *node_b, *lcount, *block_sums, *n_leaves_dev;
     float *val, *xt;
     unsigned char *leaf_flag;
+    u64 *left_bits;      // the split test of every position, one bit each
     Node *nodes_a, *nodes_b;
     int *dims_a, *dims_b;
     SmallNode *small;
@@ -693,6 +702,7 @@ TreeWs carve(void *ws, int64_t n, int32_t d, int32_t T, int32_t S, bool with_nod
     w.node_b = (int *)take(total * 4);
     w.lcount = (int *)take((total + 1) * 4);
     w.val = (float *)take(total * 4);
+    w.left_bits = (u64 *)take((total / 64 + 1) * 8);
     w.leaf_flag = (unsigned char *)take(total);
     w.block_sums = (int *)take((nb + 1) * 4);
     w.nodes_a = (Node *)take(max_nodes * sizeof(Node));
@@ -709,13 +719,18 @@ TreeWs carve(void *ws, int64_t n, int32_t d, int32_t T, int32_t S, bool with_nod
     return w;
 }
 
+// bits (or null): room for one bit per position; the predicate is then evaluated once and its
+// bits serve the second pass (and the caller afterwards).
 template <class Pred>
-void device_scan(Pred pred, size_t total, int *block_sums, int *out, hipStream_t st)
+void device_scan(Pred pred, size_t total, int *block_sums, int *out, u64 *bits, hipStream_t st)
 {
     int nb = (int)((total + kScanTile - 1) / kScanTile);
-    scan_reduce_kernel<<<nb, kBlock, 0, st>>>(pred, total, block_sums);
+    scan_reduce_kernel<<<nb, kBlock, 0, st>>>(pred, total, block_sums, bits);
     scan_blocksums_kernel<<<1, kBlock, 0, st>>>(block_sums, nb);
-    scan_apply_kernel<<<nb, kBlock, 0, st>>>(pred, total, block_sums, nb, out);
+    if (bits)
+        scan_apply_kernel<<<nb, kBlock, 0, st>>>(BitsPred{bits}, total, block_sums, nb, out);
+    else
+        scan_apply_kernel<<<nb, kBlock, 0, st>>>(pred, total, block_sums, nb, out);
 }
 
 }  // namespace
@@ -789,12 +804,12 @@ extern "C" int efanna_build_trees(const float *X, int64_t n, int32_t d, int32_t 
         sum_kernel<<<(grid_pos + tiles - 1) / tiles, kBlock, 0, st>>>(w.xt, (int)n, perm_cur, node_cur, nodes_cur,
                                                                       dims_cur, w.val, total, w.counters, level, tiles);
         LeftPred pred{node_cur, nodes_cur, w.val};
-        device_scan(pred, total, w.block_sums, w.lcount, st);
+        device_scan(pred, total, w.block_sums, w.lcount, w.left_bits, st);
         children_kernel<<<grid_nodes, kBlock, 0, st>>>(
             nodes_cur, level, nodes_nxt, dims_nxt, w.lcount, w.leaf_flag, S, fin, w.small, seed, (int)n, d,
             w.counters, w.rec, w.leaf_rec);
         scatter_kernel<<<grid_pos, kBlock, 0, st>>>(perm_cur, perm_nxt, node_cur, node_nxt, nodes_cur,
-                                                    w.val, w.lcount, total);
+                                                    w.left_bits, w.lcount, total);
         if (level + 1 >= sure) {
             EF_HIP_CHECK(hipMemcpyAsync(&host_c, w.counters, sizeof(Counters), hipMemcpyDeviceToHost, st));
             EF_HIP_CHECK(hipStreamSynchronize(st));
@@ -818,7 +833,7 @@ extern "C" int efanna_build_trees(const float *X, int64_t n, int32_t d, int32_t 
         EF_HIP_CHECK(hipMemcpyAsync(perm, perm_cur, total * 4, hipMemcpyDeviceToDevice, st));
 
     FlagPred fp{w.leaf_flag};
-    device_scan(fp, total, w.block_sums, w.lcount, st);
+    device_scan(fp, total, w.block_sums, w.lcount, (u64 *)nullptr, st);
     leaf_offsets_kernel<<<grid_pos, kBlock, 0, st>>>(w.leaf_flag, w.lcount, (int)n, T, max_leaves,
                                                      leaf_off, w.n_leaves_dev);
     if (nodes)
