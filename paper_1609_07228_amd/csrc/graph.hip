@@ -773,21 +773,42 @@ __device__ inline void sample_row(u64 *graph, const u64 (&e)[E], int i, bool row
                                   int *__restrict__ od_c, u32 *worst, Offer &&offer)
 {
     const int gl = threadIdx.x & (G - 1);
-    // ranks among new-marked and among old entries (all lanes of the group take part)
     int rn[E], ro[E];
+    const bool all_sampled = K <= L;
+    if (all_sampled) {
+        // Rows no longer than the sample: every marked entry is sampled and every other entry is
+        // old, whatever their ranks.  The two lists are sets (their order decides nothing), so
+        // the places in them are handed out by compaction: a ballot instead of K broadcasts.
+        const int lane = ef_lane();
+        const u64 group = (G == 64 ? ~0ULL : ((1ULL << (G & 63)) - 1)) << (lane & ~(G - 1));
+        const u64 below = group & ((1ULL << lane) - 1);
+        int base_n = 0, base_o = 0;
 #pragma unroll
-    for (int h = 0; h < E; ++h) rn[h] = ro[h] = 0;
+        for (int h = 0; h < E; ++h) {
+            const bool valid = gl + h * G < K;
+            const u64 bn = __ballot(valid && (e[h] & 1)) & group;
+            const u64 bo = __ballot(valid && !(e[h] & 1) && !ef_is_empty(e[h])) & group;
+            rn[h] = base_n + __popcll(bn & below);
+            ro[h] = base_o + __popcll(bo & below);
+            base_n += __popcll(bn);
+            base_o += __popcll(bo);
+        }
+    } else {
+        // ranks among new-marked and among old entries (all lanes of the group take part)
 #pragma unroll
-    for (int part = 0; part < E; ++part) {
-        const int k_end = min(K - part * G, G);
-        for (int k = 0; k < k_end; ++k) {
-            const u64 o = __shfl(e[part], k, G);
-            const bool o_new = o & 1, o_old = !o_new && !ef_is_empty(o);
+        for (int h = 0; h < E; ++h) rn[h] = ro[h] = 0;
 #pragma unroll
-            for (int h = 0; h < E; ++h) {
-                const bool less = o < e[h];
-                rn[h] += (less && o_new) ? 1 : 0;
-                ro[h] += (less && o_old) ? 1 : 0;
+        for (int part = 0; part < E; ++part) {
+            const int k_end = min(K - part * G, G);
+            for (int k = 0; k < k_end; ++k) {
+                const u64 o = __shfl(e[part], k, G);
+                const bool o_new = o & 1, o_old = !o_new && !ef_is_empty(o);
+#pragma unroll
+                for (int h = 0; h < E; ++h) {
+                    const bool less = o < e[h];
+                    rn[h] += (less && o_new) ? 1 : 0;
+                    ro[h] += (less && o_old) ? 1 : 0;
+                }
             }
         }
     }
@@ -803,7 +824,7 @@ __device__ inline void sample_row(u64 *graph, const u64 (&e)[E], int i, bool row
         take_new[h] = is_new[h] && rn[h] < L;
         total_new += is_new[h] ? 1 : 0;
         if (valid) wbits = max(wbits, ef_dist_bits(e[h]));
-        if (take_new[h] && rn[h] == L - 1) stop = e[h];
+        if (!all_sampled && take_new[h] && rn[h] == L - 1) stop = e[h];
     }
     for (int m = G / 2; m >= 1; m >>= 1) {
         total_new += __shfl_xor(total_new, m, G);
