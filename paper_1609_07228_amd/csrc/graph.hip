@@ -1093,11 +1093,11 @@ reverse_old_bucket_kernel(const int *__restrict__ od, int n, int K, const u64 *_
 // fills from slot 0 up and then keeps its L smallest keys.
 // LDS: lists [bucket's targets * L] u64, scan [n_blocks + 1] and start [n_blocks] int;
 // n_blocks <= kBktMaxRuns.
-// What the time is made of (headline workload, 93 us per launch on average, 190 us for the
+// What the time is made of (headline workload, 82 us per launch on average, 170 us for the
 // ten million offers of the first iteration): 18 us fixed, about 5 ns per thousand offers to
 // find and load them, the rest the insertions; by the counters the SIMDs issue an instruction
-// in 85 % of their clocks (about 630 instructions per 64 offers), the LDS is active a third of
-// the time.  Variants that were no faster or slower: a thread walking consecutive offers
+// in 70 to 85 % of their clocks (500 to 600 instructions per 64 offers), the LDS is active a third
+// of the time.  Variants that were no faster or slower: a thread walking consecutive offers
 // instead of a search per offer; offers loaded eight ahead; list reads issued in groups; the
 // first L offers of a list placed by a counter and the others entered behind a per-list bound,
 // or smallest first in rounds between barriers; a per-list bound on the hash in front of the
