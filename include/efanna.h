@@ -14,6 +14,10 @@
  *    a caller-provided workspace (`ws`, `ws_bytes`, 256-byte aligned); its required
  *    size is returned by the matching *_workspace_bytes function.  Workspace contents
  *    need not survive between calls.
+ *  - Host-side resources: efanna_build_trees keeps one small pinned host buffer per
+ *    calling thread (hipHostMalloc, 32 bytes, never freed) to read its level counters
+ *    into; efanna_nndescent creates and destroys 5 * iters HIP events when phase_ms is
+ *    given.  Nothing else is allocated on either side.
  *  - Pointers marked [host] are ordinary host addresses.
  *  - `stream` is a hipStream_t (NULL = the default stream).  Work is enqueued on it;
  *    entry points documented as synchronising wait for that stream before returning.
@@ -29,7 +33,8 @@
  *    list updates are set operations (a list ends up holding the K smallest
  *    (distance, id) keys ever proposed to it), so scheduling cannot change them.
  *  - Calls that use the same graph, workspace or stream concurrently race; calls on
- *    distinct buffers and streams are independent.  The library keeps no global state.
+ *    distinct buffers and streams are independent.  Apart from the resources named above
+ *    the library keeps no state between calls.
  */
 #ifndef EFANNA_H
 #define EFANNA_H
@@ -45,7 +50,7 @@ typedef enum {
     EFANNA_OK = 0,
     EFANNA_EINVAL = -1,     /* null pointer or parameter out of range                 */
     EFANNA_EWORKSPACE = -2, /* workspace missing, misaligned or too small             */
-    EFANNA_EINPUT = -3,     /* X holds a non-finite value or |x| >= 2^20              */
+    EFANNA_EINPUT = -3,     /* X holds a non-finite value, |x| >= 2^20 or n*|x| >= 2^43 */
     EFANNA_EHIP = -4,       /* a HIP runtime call failed                              */
     EFANNA_ECAPACITY = -5,  /* a tree has more leaves than `max_leaves`               */
     EFANNA_EUNSUPPORTED = -6 /* shape outside what the kernels handle (see each call) */
@@ -86,7 +91,9 @@ const char *efanna_status_string(int status);
  * quantised to multiples of 2^-20 and compared as cnt*q(x) < sum(q).  If one side
  * would be empty (or below depth 60) the node is cut into positional halves.
  *
- * X        [device] n*d float32, row-major, finite, |x| < 2^20.
+ * X        [device] n*d float32, row-major, finite, |x| < 2^20 and n * |x| < 2^43 (the latter
+ *          only binds beyond 2^23 points: it keeps cnt*q(x) and the sums inside 64 bits);
+ *          EFANNA_EINPUT otherwise.
  * perm     [device] out, n_trees*n int32: ids of tree t at perm[t*n ..], every leaf a
  *          contiguous run, leaves in left-to-right order, ids ascending inside a leaf.
  * leaf_off [device] out, n_trees*(max_leaves+1) int32: start of each leaf of tree t
@@ -115,7 +122,7 @@ int efanna_build_trees(const float *X, int64_t n, int32_t d, int32_t n_trees, in
  * Candidates of point i: in every tree, the other members of its leaf and - when nodes is
  * given - for every ancestor N of that leaf with depth >= conquer_depth, the members of the
  * leaf that i reaches when it is sent down the subtree of N's other child by the nodes' split
- * tests (Section 3.3.2: the sibling subtree classifies i).  Graph row i ends up holding the K
+ * tests (Section 3.3.1: the sibling subtree classifies i).  Graph row i ends up holding the K
  * closest distinct candidates (fewer if there are fewer; the rest of the row is empty).
  * Every entry carries the "new" mark (Alg. 4 starts from G_new = G_init).
  *

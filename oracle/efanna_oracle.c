@@ -177,6 +177,10 @@ int oracle_build_trees_nodes(const float *X, int64_t n, int32_t d, int32_t T, in
                              oracle_node *nodes, int32_t *leaf_up)
 {
     if (!X || n < 1 || d < 1 || T < 1 || S < 1 || (!nodes) != (!leaf_up)) return -1;
+    /* domain of the exact mean test: finite, |x| < 2^20 (so |q| <= 2^40), and n * |x| < 2^43, so
+     * that cnt * q(x) and the sum of q over a node stay below 2^63 */
+    for (int64_t i = 0; i < n * d; ++i)
+        if (!(fabsf(X[i]) < 1048576.0f) || (double)fabsf(X[i]) * (double)n >= 8796093022208.0) return -3;
     int32_t *tmp = (int32_t *)malloc((size_t)n * sizeof(int32_t));
     oracle_node *rec = nodes ? (oracle_node *)malloc((size_t)(n + 1) * sizeof(oracle_node)) : NULL;
     int32_t *leaf_rec = nodes ? (int32_t *)malloc((size_t)(n + 1) * sizeof(int32_t)) : NULL;
@@ -289,7 +293,7 @@ static int cmp_i32(const void *a, const void *b)
 
 /* Alg. 3, the walk up from the leaf: N is the ancestor of point i's leaf at
  * depth d, Sib the child of N that is not on i's path; i is sent down the
- * subtree of Sib by the split test of every node it meets (Section 3.3.2: the
+ * subtree of Sib by the split test of every node it meets (Section 3.3.1: the
  * subtree is used as a classifier for i) and the members of the leaf it reaches
  * join the candidates.  `up` is the link of the node below N on i's path.
  * A node without a split dimension (below depth 60) sends every point left. */

@@ -105,7 +105,8 @@ transpose_check_kernel(const float *__restrict__ X, int n, int d, float *__restr
         float v = 0.0f;
         if (row < n && col < d) {
             v = X[(size_t)row * d + col];
-            bad |= !(fabsf(v) < 1048576.0f);   // false for NaN and inf as well
+            // false for NaN and inf as well; n |x| < 2^43 keeps cnt * q(x) and the sums below 2^63
+            bad |= !(fabsf(v) < 1048576.0f) || (double)fabsf(v) * (double)n >= 8796093022208.0;
         }
         tile[ty + 8 * k][tx] = v;
     }

@@ -170,6 +170,54 @@ def test_mixed4m_d96_full_size_properties():
     _full_size_properties("mixed4m_d96", 1000, 100)
 
 
+@pytest.mark.timeout(900)
+def test_mixed_d96_prefix_every_element_against_oracle():
+    """The parameters of `mixed4m_d96` (K = 100, 16 trees, leaves of 64, L = 50) on its first
+    262 144 rows, three iterations: rows of a hundred entries take the per-list counters with their
+    overflow queues, the wide overflow kernel and the LDS-row join with its long-row list updates,
+    at a size where the queues fill and hubs are fought over.  Every element of the trees, of the
+    initial and of the refined graph and the pairs evaluated per iteration against the oracle,
+    and both accuracies against exact brute force (Alg. 3 at the leaves, Alg. 4)."""
+    if not torch.cuda.is_available():
+        pytest.fail("GPU tests need a GPU: there is no CPU fallback")
+    from paper_1609_07228_amd import efanna
+    name, n, iters = "mixed4m_d96", 4 * synth.CHUNK, 3
+    p = synth.params(name)
+    K, T, S, L = p["K"], p["T"], p["S"], p["L"]
+    X = synth.generate(name, n=n)
+    Xd = torch.from_numpy(X).to("cuda:0")
+    perm, off, nl = efanna.efanna_build_trees(Xd, T, S, synth.ALGO_SEED, max_leaves=n // (S // 4) + 16)
+    graph = efanna.efanna_init_graph(Xd, perm, off, nl, S, K)
+    init = [t.cpu().numpy() for t in efanna.efanna_get_graph(graph, with_flags=True)]
+    stats = efanna.efanna_nndescent(Xd, graph, iters, L, synth.ALGO_SEED).cpu().numpy()
+    ids, dists, flags = [t.cpu().numpy() for t in efanna.efanna_get_graph(graph, with_flags=True)]
+    _progress(f"{name}[:{n}]: gpu path done")
+    operm, ooff, onl = oracle.build_trees(X, T, S, synth.ALGO_SEED)
+    assert np.array_equal(nl, onl) and np.array_equal(perm.cpu().numpy(), operm)
+    goff = off.cpu().numpy()
+    for t in range(T):
+        assert np.array_equal(goff[t, :onl[t] + 1], ooff[t, :onl[t] + 1])
+    _progress(f"{name}[:{n}]: trees equal")
+    want = oracle.init_graph(X, operm, ooff, onl, K)
+    assert np.array_equal(init[0], want[0])
+    assert init[1].tobytes() == want[1].tobytes()
+    assert np.array_equal(init[2], want[2])
+    _progress(f"{name}[:{n}]: initial graph equal")
+    want = oracle.nndescent(X, *want[:3], iters, L, synth.ALGO_SEED)
+    _progress(f"{name}[:{n}]: oracle refined")
+    assert np.array_equal(ids, want[0])
+    assert dists.tobytes() == want[1].tobytes()
+    assert np.array_equal(flags, want[2])
+    assert np.array_equal(stats[:, 0].astype(np.uint64), want[3][:, 0])
+    rows = synth.sample_rows(n, 500)
+    oracle.check_graph_invariants(X, ids[rows], dists[rows], rows=rows)
+    tid, _ = oracle.exact_knn(X, rows, K)
+    r_gpu, r_cpu = oracle.recall(ids[rows], tid), oracle.recall(want[0][rows], tid)
+    _progress(f"{name}[:{n}]: accuracy {r_gpu:.4f} (oracle {r_cpu:.4f})")
+    assert abs(r_gpu - r_cpu) <= 0.005
+    assert r_gpu > oracle.recall(init[0][rows], tid)
+
+
 @pytest.mark.timeout(600)
 @pytest.mark.parametrize("n", [1 << 21, (1 << 21) + 1])
 def test_two_million_short_vectors_bit_exact(n):

@@ -91,6 +91,13 @@ def test_trees_reject_bad_input(ef):
         ef.efanna_build_trees(dev(X), 2, 4, 0)
     assert e.value.status == -3
     X[17, 2] = 0
+    # beyond 2^23 points n * |x| < 2^43 binds before |x| < 2^20 (64-bit sums of the exact mean test)
+    big = torch.zeros(((1 << 24) + 3, 1), dtype=torch.float32, device="cuda:0")
+    big[12345, 0] = 2.0 ** 19
+    with pytest.raises(ef.EfannaError) as e:
+        ef.efanna_build_trees(big, 1, 64, 0, max_leaves=(1 << 20))
+    assert e.value.status == -3
+    del big
     with pytest.raises(ef.EfannaError) as e:
         ef.efanna_build_trees(dev(X), 2, 4, 0, workspace=torch.empty(256, dtype=torch.uint8, device="cuda:0"))
     assert e.value.status == -2

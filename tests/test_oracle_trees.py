@@ -151,3 +151,26 @@ def test_quantisation_ties_and_large_values():
     perm, off, nl = oracle.build_trees(X, T=1, S=1, seed=0)
     perms, offs = rederive(X, 1, 1, 0)
     assert perm[0].tolist() == perms[0] and off[0, :nl[0] + 1].tolist() == offs[0]
+
+
+def test_input_outside_the_exact_domain_is_rejected():
+    """The mean test compares cnt * q(x) with a sum of q in 64-bit integers: inputs that could
+    overflow them (non-finite, |x| >= 2^20, n * |x| >= 2^43) are refused, not wrapped."""
+    X = np.zeros((50, 2), dtype=np.float32)
+    for bad in (np.nan, np.inf, -np.inf, 2.0 ** 20, -(2.0 ** 20)):
+        Y = X.copy()
+        Y[13, 1] = bad
+        with pytest.raises(ValueError):
+            oracle.build_trees(Y, 1, 4, 0)
+    Y = X.copy()
+    Y[13, 1] = np.nextafter(np.float32(2.0 ** 20), np.float32(0))      # the largest value inside
+    oracle.build_trees(Y, 1, 4, 0)
+    # beyond 2^23 points the bound on n * |x| binds first: 2^24 points take |x| < 2^19
+    n = 1 << 24
+    Z = np.zeros((n, 1), dtype=np.float32)
+    Z[5, 0] = 2.0 ** 19
+    with pytest.raises(ValueError):
+        oracle.build_trees(Z, 1, n, 0)
+    Z[5, 0] = np.nextafter(np.float32(2.0 ** 19), np.float32(0))
+    perm, off, nl = oracle.build_trees(Z, 1, n, 0)      # S >= n: a single leaf, nothing to sum
+    assert nl[0] == 1
