@@ -21,10 +21,29 @@ sys.path.insert(0, os.path.dirname(os.path.abspath(__file__)))
 
 HBM_PEAK_GBS = 8000.0
 
-# HBM bytes per launch of the dominant kernel, from two rocprofv3 --pmc runs (FETCH_SIZE, WRITE_SIZE)
-# scaled by what the same counters read for a plain 256 MiB copy (factors 2.0 and 1.0); summary and
-# commands in profiles/join_kernels_sift1m_like_hbm_traffic.txt.  Only measured for the headline workload.
-MEASURED_TRAFFIC_BYTES = {"sift1m_like": {"calibrated": 4.85e9, "raw_counters": 2.53e9}}
+TRAFFIC_SUMMARY = os.path.join(os.path.dirname(os.path.abspath(__file__)), "profiles",
+                               "join_kernels_sift1m_like_hbm_traffic.txt")
+
+
+def measured_traffic(workload: str):
+    """HBM bytes per launch of the dominant kernel as the tracked rocprofv3 summary states them
+    (`key: value` lines: workload, commit, traffic_bytes_per_launch, ...), or None when the
+    summary covers another workload.  The figures are counters of a profiled run, not of this run."""
+    try:
+        kv = {}
+        with open(TRAFFIC_SUMMARY) as f:
+            for line in f:
+                if ":" in line and not line.startswith(" "):
+                    k, v = line.split(":", 1)
+                    kv[k.strip()] = v.strip()
+        if kv.get("workload") != workload:
+            return None
+        return {"traffic": float(kv["traffic_bytes_per_launch"]),
+                "fetch_bytes": float(kv["fetch_bytes_per_launch"]),
+                "write_bytes": float(kv["write_bytes_per_launch"]),
+                "commit": kv.get("commit"), "source": "profiles/" + os.path.basename(TRAFFIC_SUMMARY)}
+    except (OSError, KeyError, ValueError):
+        return None
 
 
 def exact_knn_torch(Xd, rows, K):
@@ -43,6 +62,121 @@ def exact_knn_torch(Xd, rows, K):
     return torch.cat(out).cpu().numpy()
 
 
+def recall_of_ids(ids_dev, Xd, rows, K):
+    """recall@K (eqs. (2)-(3)) of the graph rows `rows` against float64 brute force."""
+    import torch
+    rows_d = torch.from_numpy(rows).to(Xd.device)
+    truth = exact_knn_torch(Xd, rows_d, K)
+    got = ids_dev[rows_d].cpu().numpy()
+    hits = sum(np.intersect1d(a[a >= 0], b).shape[0] for a, b in zip(got, truth))
+    return hits / float(truth.size)
+
+
+def measure(name, n_rows, steps, warmup, recall_rows, conquer_depth=None, progress=False):
+    """`warmup` untimed and `steps` timed builds of workload `name` (trees + initial graph +
+    NN-descent + finalise, inputs resident in HBM).  Returns the figures of the timed builds and
+    what later legs need (device data, the last build's outputs)."""
+    import torch
+    from paper_1609_07228_amd import efanna, synth
+
+    p = synth.params(name)
+    X = synth.generate(name, n=n_rows)
+    n, d = X.shape
+    if progress:
+        print(f"generated {name}: {n} x {d}", file=sys.stderr, flush=True)
+    K, T, S, I, L = p["K"], p["T"], p["S"], p["I"], p["L"]
+    dev = torch.device("cuda:0")
+    Xd = torch.from_numpy(X).to(dev)
+    L_ = efanna.lib()
+    conquer = conquer_depth is not None
+    ws_tree = torch.empty(L_.efanna_trees_workspace_bytes(n, d, T, S, 1 if conquer else 0),
+                          dtype=torch.uint8, device=dev)
+    ws_init = torch.empty(max(256, L_.efanna_init_workspace_bytes(n, 64 if conquer else 0)),
+                          dtype=torch.uint8, device=dev)
+    ws_nnd = torch.empty(L_.efanna_nndescent_workspace_bytes(n, K, L), dtype=torch.uint8, device=dev)
+    graph = torch.empty((n, K), dtype=torch.int64, device=dev)
+    stats = torch.zeros((I, 4), dtype=torch.int64, device=dev)
+    phase_ms = np.zeros((I, 4), dtype=np.float32)
+    max_leaves = n // max(1, S // 4) + 16      # generous: mean splits leave leaves ~0.7*S full
+    state = {}
+    # Phase times come from events on the launch stream, read after the timed region: a step has
+    # no host synchronisation of its own (the tree build reads its level counters and the phase
+    # timing of efanna_nndescent waits for the stream; both are part of the library calls).
+    step_events, step_phase_ms = [], []
+
+    def step(timed: bool):
+        ev = [torch.cuda.Event(enable_timing=True) for _ in range(5)]
+        ev[0].record()
+        trees = efanna.efanna_build_trees(Xd, T, S, synth.ALGO_SEED, max_leaves=max_leaves,
+                                          workspace=ws_tree, with_nodes=conquer)
+        perm, leaf_off, n_leaves = trees[:3]
+        ev[1].record()
+        if conquer:
+            efanna.efanna_init_graph(Xd, perm, leaf_off, n_leaves, S, K, graph=graph, workspace=ws_init,
+                                     nodes=trees[3], leaf_up=trees[4], tree_depth=trees[5],
+                                     conquer_depth=conquer_depth)
+        else:
+            efanna.efanna_init_graph(Xd, perm, leaf_off, n_leaves, S, K, graph=graph, workspace=ws_init)
+        ev[2].record()
+        efanna.efanna_nndescent(Xd, graph, I, L, synth.ALGO_SEED, stats=stats, workspace=ws_nnd,
+                                phase_ms=phase_ms)
+        ev[3].record()
+        ids, dists = efanna.efanna_get_graph(graph)
+        ev[4].record()
+        if progress:
+            torch.cuda.synchronize()
+            print("step: trees %.3f ms, init %.3f ms, nndescent %.3f ms, get %.3f ms"
+                  % tuple(ev[k].elapsed_time(ev[k + 1]) for k in range(4)), file=sys.stderr, flush=True)
+        if timed:
+            step_events.append(ev)
+            step_phase_ms.append(phase_ms.copy())      # host memory, filled by the call above
+        state.update(perm=perm, leaf_off=leaf_off, n_leaves=n_leaves, ids=ids, dists=dists)
+
+    for _ in range(warmup):
+        step(False)
+    torch.cuda.synchronize()
+    t_begin = time.perf_counter()
+    for _ in range(steps):
+        step(True)
+    torch.cuda.synchronize()
+    seconds = (time.perf_counter() - t_begin) / max(1, steps)
+    phases = np.zeros(4)
+    for ev in step_events:
+        phases[:] += [ev[k].elapsed_time(ev[k + 1]) * 1e-3 for k in range(4)]
+    st = stats.cpu().numpy()      # the path is deterministic: the same in every step
+    # dominant kernel: the join of points that gather at most 16 vectors (one launch per iteration)
+    k_ms_sum = k_bytes_sum = all_ms_sum = all_bytes_sum = 0.0
+    for pm in step_phase_ms:
+        k_ms_sum += float(pm[:, 1].sum())
+        k_bytes_sum += float((st[:, 3] * (d * 4 + 8)).sum())
+        all_ms_sum += float(pm[:, 1:].sum())
+        all_bytes_sum += float((st[:, 2] * (d * 4 + 8) + st[:, 1] * 8).sum())
+    k_launches = I * len(step_phase_ms)
+    # work done per step
+    off = state["leaf_off"].cpu().numpy().astype(np.int64)
+    init_evals = 0
+    for t in range(T):
+        sizes = np.diff(off[t, :state["n_leaves"][t] + 1])
+        init_evals += int((sizes * (sizes - 1) // 2).sum())
+    evals = init_evals + int(st[:, 0].sum())
+    recall = None
+    if recall_rows > 0:
+        recall = recall_of_ids(state["ids"], Xd, synth.sample_rows(n, recall_rows), K)
+    achieved = k_bytes_sum / 1e9 / (k_ms_sum / 1e3) if k_ms_sum > 0 else 0.0
+    achieved_all = all_bytes_sum / 1e9 / (all_ms_sum / 1e3) if all_ms_sum > 0 else 0.0
+    return {
+        "name": name, "X": X, "Xd": Xd, "state": state, "params": p, "max_leaves": max_leaves,
+        "ws_tree": ws_tree, "ws_init": ws_init, "ws_nnd": ws_nnd,
+        "n": n, "d": d, "seconds": seconds, "evals": evals, "recall": recall,
+        "phases_ms": {k: float(v) * 1e3 / max(1, steps)
+                      for k, v in zip(("trees", "init_graph", "nndescent", "get_graph"), phases)},
+        "phase_ms": phase_ms, "stats": st,
+        "join_le16": {"achieved": achieved, "avg_launch_ms": k_ms_sum / max(1, k_launches),
+                      "bytes_per_launch": k_bytes_sum / max(1, k_launches)},
+        "all_joins": {"achieved": achieved_all, "ms_per_step": all_ms_sum / max(1, steps)},
+    }
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -54,9 +188,16 @@ def main():
                     help="rows of the workload the CPU oracle is timed on (0 = skip)")
     ap.add_argument("--recall-rows", type=int, default=10_000, help="0 = skip recall")
     ap.add_argument("--progress", action="store_true", help="report each phase on stderr as it ends")
+    ap.add_argument("--others", default=None, metavar="LIST",
+                    help="comma-separated workloads measured after the headline steps (1 warm-up + 2 builds "
+                         "each, recall on, no CPU leg) and reported under `other_workloads`; default: the four "
+                         "other configurations when the workload is the headline at full size, none otherwise; "
+                         "'none' switches them off")
     ap.add_argument("--calibrate", action="store_true",
-                    help="after the timed steps, fill 256 MiB and add a constant to 256 MiB with plain torch kernels: a known "
-                         "amount of HBM traffic to scale rocprofv3's FETCH_SIZE / WRITE_SIZE counters by")
+                    help="after the timed steps, run kernels with a known amount of HBM traffic to scale rocprofv3's "
+                         "FETCH_SIZE / WRITE_SIZE counters by: a torch fill of 256 MiB, an elementwise add over "
+                         "256 MiB, and efanna_pair_distances over 4M random pairs of the data (random row gathers "
+                         "in 64-byte pieces, the join's access pattern: 2 rows fetched and 4 bytes written per pair)")
     ap.add_argument("--search", type=int, default=0, metavar="NQ",
                     help="after the build, answer NQ synthetic queries with the index (Alg. 1) and add a "
                          "`search` object to the line: queries per second, recall against brute force")
@@ -86,82 +227,15 @@ def main():
         sys.exit(3)
     efanna.lib()
     name = args.workload
-    p = synth.params(name)
-    X = synth.generate(name, n=args.n)
-    n, d = X.shape
-    if args.progress:
-        print(f"generated {name}: {n} x {d}", file=sys.stderr, flush=True)
-    K, T, S, I, L = p["K"], p["T"], p["S"], p["I"], p["L"]
-    dev = torch.device("cuda:0")
-    Xd = torch.from_numpy(X).to(dev)
-    L_ = efanna.lib()
     conquer = args.conquer_depth is not None
-    ws_tree = torch.empty(L_.efanna_trees_workspace_bytes(n, d, T, S, 1 if conquer else 0),
-                          dtype=torch.uint8, device=dev)
-    ws_init = torch.empty(max(256, L_.efanna_init_workspace_bytes(n, 64 if conquer else 0)),
-                          dtype=torch.uint8, device=dev)
-    ws_nnd = torch.empty(L_.efanna_nndescent_workspace_bytes(n, K, L), dtype=torch.uint8, device=dev)
-    graph = torch.empty((n, K), dtype=torch.int64, device=dev)
-    stats = torch.zeros((I, 4), dtype=torch.int64, device=dev)
-    phase_ms = np.zeros((I, 4), dtype=np.float32)
-    max_leaves = n // max(1, S // 4) + 16      # generous: mean splits leave leaves ~0.7*S full
-    state = {}
-    phases = np.zeros(4)
-    # dominant kernel: the join of points that gather at most 16 vectors (one launch per iteration)
-    k_ms_sum, k_bytes_sum, k_launches = 0.0, 0.0, 0
-    all_ms_sum, all_bytes_sum = 0.0, 0.0
-
-    # Phase times come from events on the launch stream, read after the timed region: a step has
-    # no host synchronisation of its own (the tree build reads its level counters and the phase
-    # timing of efanna_nndescent waits for the stream; both are part of the library calls).
-    step_events = []
-
-    def step(timed: bool):
-        ev = [torch.cuda.Event(enable_timing=True) for _ in range(5)]
-        ev[0].record()
-        trees = efanna.efanna_build_trees(Xd, T, S, synth.ALGO_SEED, max_leaves=max_leaves,
-                                          workspace=ws_tree, with_nodes=conquer)
-        perm, leaf_off, n_leaves = trees[:3]
-        ev[1].record()
-        if conquer:
-            efanna.efanna_init_graph(Xd, perm, leaf_off, n_leaves, S, K, graph=graph, workspace=ws_init,
-                                     nodes=trees[3], leaf_up=trees[4], tree_depth=trees[5],
-                                     conquer_depth=args.conquer_depth)
-        else:
-            efanna.efanna_init_graph(Xd, perm, leaf_off, n_leaves, S, K, graph=graph, workspace=ws_init)
-        ev[2].record()
-        efanna.efanna_nndescent(Xd, graph, I, L, synth.ALGO_SEED, stats=stats, workspace=ws_nnd,
-                                phase_ms=phase_ms)
-        ev[3].record()
-        ids, dists = efanna.efanna_get_graph(graph)
-        ev[4].record()
-        if args.progress:
-            torch.cuda.synchronize()
-            print("step: trees %.3f ms, init %.3f ms, nndescent %.3f ms, get %.3f ms"
-                  % tuple(ev[k].elapsed_time(ev[k + 1]) for k in range(4)), file=sys.stderr, flush=True)
-        if timed:
-            step_events.append(ev)
-            step_phase_ms.append(phase_ms.copy())      # host memory, filled by the call above
-        state.update(perm=perm, leaf_off=leaf_off, n_leaves=n_leaves, ids=ids, dists=dists)
-
-    step_phase_ms = []
-    for _ in range(args.warmup):
-        step(False)
-    torch.cuda.synchronize()
-    t_begin = time.perf_counter()
-    for _ in range(args.steps):
-        step(True)
-    torch.cuda.synchronize()
-    seconds = (time.perf_counter() - t_begin) / max(1, args.steps)
-    for ev in step_events:
-        phases[:] += [ev[k].elapsed_time(ev[k + 1]) * 1e-3 for k in range(4)]
-    st_steps = stats.cpu().numpy()      # the path is deterministic: the same in every step
-    for pm in step_phase_ms:
-        k_ms_sum += float(pm[:, 1].sum())
-        k_bytes_sum += float((st_steps[:, 3] * (d * 4 + 8)).sum())
-        k_launches += I
-        all_ms_sum += float(pm[:, 1:].sum())
-        all_bytes_sum += float((st_steps[:, 2] * (d * 4 + 8) + st_steps[:, 1] * 8).sum())
+    m = measure(name, args.n, args.steps, args.warmup, args.recall_rows, args.conquer_depth, args.progress)
+    X, Xd, state, p = m["X"], m["Xd"], m["state"], m["params"]
+    n, d = m["n"], m["d"]
+    K, T, S, I, L = p["K"], p["T"], p["S"], p["I"], p["L"]
+    dev = Xd.device
+    max_leaves, ws_tree, ws_init, ws_nnd = m["max_leaves"], m["ws_tree"], m["ws_init"], m["ws_nnd"]
+    seconds, evals, recall, phase_ms, st = m["seconds"], m["evals"], m["recall"], m["phase_ms"], m["stats"]
+    phases_ms, join_le16, all_joins = m["phases_ms"], m["join_le16"], m["all_joins"]
 
     if args.calibrate:
         a = torch.empty(64 * 1024 * 1024, dtype=torch.float32, device=dev)
@@ -171,29 +245,20 @@ def main():
         torch.add(a, 1.0, out=b)      # an elementwise kernel (a plain copy may go to a DMA engine instead)
         torch.cuda.synchronize()
         del a, b
-
-    # work done per step (identical in every step: the path is deterministic)
-    st = stats.cpu().numpy()
-    off = state["leaf_off"].cpu().numpy().astype(np.int64)
-    init_evals = 0
-    for t in range(T):
-        sizes = np.diff(off[t, :state["n_leaves"][t] + 1])
-        init_evals += int((sizes * (sizes - 1) // 2).sum())
-    evals = init_evals + int(st[:, 0].sum())
-
-    recall = None
-    if args.recall_rows > 0:
-        rows = synth.sample_rows(n, args.recall_rows)
-        truth = exact_knn_torch(Xd, torch.from_numpy(rows).to(dev), K)
-        got = state["ids"][torch.from_numpy(rows).to(dev)].cpu().numpy()
-        hits = sum(np.intersect1d(a[a >= 0], b).shape[0] for a, b in zip(got, truth))
-        recall = hits / float(truth.size)
+        gen = torch.Generator(device=dev)
+        gen.manual_seed(1)
+        pa = torch.randint(0, n, (4 * 1024 * 1024,), generator=gen, device=dev, dtype=torch.int32)
+        pb = torch.randint(0, n, (4 * 1024 * 1024,), generator=gen, device=dev, dtype=torch.int32)
+        torch.cuda.synchronize()
+        efanna.efanna_pair_distances(Xd, pa, pb)
+        torch.cuda.synchronize()
+        del pa, pb
 
     cpu = None
     if args.cpu_rows > 0:
         import oracle
-        m = min(n, args.cpu_rows)
-        Xs = X[:m]
+        mm = min(n, args.cpu_rows)
+        Xs = X[:mm]
         c0 = time.perf_counter()
         operm, ooff, onl = oracle.build_trees(Xs, T, S, synth.ALGO_SEED)
         g = oracle.init_graph(Xs, operm, ooff, onl, K)
@@ -206,8 +271,7 @@ def main():
         cpu = {"value": c_evals / c_sec, "unit": "distance evals/s", "cores": oracle.num_threads(),
                "kind": "oracle", "seconds": c_sec,
                "sample": f"whole path (trees, leaf init, {I} NN-descent iterations) on the first "
-                         f"{m} rows of {name}"}
-
+                         f"{mm} rows of {name}"}
     search = None
     if args.search > 0:
         # the index of the last step, with the trees built once more to get their nodes
@@ -286,8 +350,33 @@ def main():
             curves[label] = descend(g, (time.perf_counter() - a0) * 1e3)
         ablation = {"recall_rows": int(rows.shape[0]), **curves}
 
-    achieved = k_bytes_sum / 1e9 / (k_ms_sum / 1e3) if k_ms_sum > 0 else 0.0
-    achieved_all = all_bytes_sum / 1e9 / (all_ms_sum / 1e3) if all_ms_sum > 0 else 0.0
+    # the other configurations: a build each on the same GPU, after the headline's buffers are gone
+    others_arg = args.others
+    if others_arg is None:
+        others_arg = ("gmm10k_d32,sift100k_like,gist1m_like,mixed4m_d96"
+                      if name == "sift1m_like" and args.n is None and not conquer else "none")
+    others = None
+    if others_arg != "none":
+        del m, Xd, ws_tree, ws_init, ws_nnd, state
+        torch.cuda.empty_cache()
+        others = {}
+        for other in [o for o in others_arg.split(",") if o]:
+            o = measure(other, None, 2, 1, min(args.recall_rows, 10_000) if args.recall_rows > 0 else 0,
+                        None, args.progress)
+            op = o["params"]
+            others[other] = {
+                "config": {"n": o["n"], "d": o["d"], "K": op["K"], "trees": op["T"], "leaf_size": op["S"],
+                           "iterations": op["I"], "sample_L": op["L"]},
+                "steps": 2, "warmup": 1, "ms_per_build": o["seconds"] * 1e3,
+                "dist_evals_per_s": o["evals"] / o["seconds"], "dist_evals_per_build": o["evals"],
+                "recall_at_K": o["recall"], "phase_ms": o["phases_ms"],
+                "join_le16_frac": o["join_le16"]["achieved"] / HBM_PEAK_GBS,
+                "all_join_kernels_frac": o["all_joins"]["achieved"] / HBM_PEAK_GBS,
+                "all_join_kernels_ms": o["all_joins"]["ms_per_step"]}
+            del o
+            torch.cuda.empty_cache()
+
+    traffic = measured_traffic(name) if args.n is None and not conquer else None
     out = {
         "metric": "kNN-graph build seconds + distance evals/sec at recall@K, N=1M d=128 K=10",
         "value": evals / seconds,
@@ -302,8 +391,7 @@ def main():
         "build_seconds": seconds,
         "dist_evals_per_step": evals,
         "recall_at_K": recall, "recall_rows": args.recall_rows if recall is not None else 0,
-        "phase_ms": {k: float(v) * 1e3 / max(1, args.steps)
-                     for k, v in zip(("trees", "init_graph", "nndescent", "get_graph"), phases)},
+        "phase_ms": phases_ms,
         "nndescent_iter_ms": {"sample_and_lists": [float(x) for x in phase_ms[:, 0]],
                               "join_le16": [float(x) for x in phase_ms[:, 1]],
                               "join_17_32": [float(x) for x in phase_ms[:, 2]],
@@ -312,18 +400,21 @@ def main():
                                 "insertions": [int(x) for x in st[:, 1]],
                                 "vectors_gathered": [int(x) for x in st[:, 2]],
                                 "vectors_gathered_join_le16": [int(x) for x in st[:, 3]]},
-        "roofline": {"kernel": "join_reg_kernel<1> (joins of at most 16 vectors)", "bound": "hbm",
-                     "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBS,
-                     "traffic": (MEASURED_TRAFFIC_BYTES.get(name, {}).get("calibrated") if args.n is None else None),
-                     "traffic_raw_counters": (MEASURED_TRAFFIC_BYTES.get(name, {}).get("raw_counters")
-                                              if args.n is None else None),
-                     "avg_launch_ms": k_ms_sum / max(1, k_launches),
-                     "algorithmic_bytes_per_launch": k_bytes_sum / max(1, k_launches),
-                     "all_join_kernels": {"achieved": achieved_all, "frac": achieved_all / HBM_PEAK_GBS,
-                                          "ms_per_step": all_ms_sum / max(1, args.steps)}},
+        "roofline": {"kernel": "join_reg_kernel (joins of at most 16 vectors)", "bound": "hbm",
+                     "achieved": join_le16["achieved"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": join_le16["achieved"] / HBM_PEAK_GBS,
+                     "traffic": traffic["traffic"] if traffic else None,
+                     "traffic_detail": ({k: traffic[k] for k in ("fetch_bytes", "write_bytes", "commit", "source")}
+                                        if traffic else None),
+                     "avg_launch_ms": join_le16["avg_launch_ms"],
+                     "algorithmic_bytes_per_launch": join_le16["bytes_per_launch"],
+                     "all_join_kernels": {"achieved": all_joins["achieved"],
+                                          "frac": all_joins["achieved"] / HBM_PEAK_GBS,
+                                          "ms_per_step": all_joins["ms_per_step"]}},
         "cpu_baseline": cpu,
     }
+    if others is not None:
+        out["other_workloads"] = others
     if search is not None:
         out["search"] = search
     if ablation is not None:

@@ -203,8 +203,12 @@ def test_mixed_d96_prefix_every_element_against_oracle():
     assert init[1].tobytes() == want[1].tobytes()
     assert np.array_equal(init[2], want[2])
     _progress(f"{name}[:{n}]: initial graph equal")
-    want = oracle.nndescent(X, *want[:3], iters, L, synth.ALGO_SEED)
-    _progress(f"{name}[:{n}]: oracle refined")
+    evals = []
+    for it in range(iters):      # one iteration per call (equal to one call of three) so that progress shows
+        want = oracle.nndescent(X, *want[:3], 1, L, synth.ALGO_SEED, iter0=it)
+        evals.append(want[3][0, 0])
+        _progress(f"{name}[:{n}]: oracle iteration {it + 1} done")
+    want = (*want[:3], np.array(evals, dtype=np.uint64)[:, None])
     assert np.array_equal(ids, want[0])
     assert dists.tobytes() == want[1].tobytes()
     assert np.array_equal(flags, want[2])
