@@ -13,7 +13,8 @@
  *    library neither allocates nor frees device memory.  Temporary storage comes from
  *    a caller-provided workspace (`ws`, `ws_bytes`, 256-byte aligned); its required
  *    size is returned by the matching *_workspace_bytes function.  Workspace contents
- *    need not survive between calls.
+ *    need not survive between calls.  (efanna_nndescent_noalloc uses a fixed device
+ *    array of the library's own instead.)
  *  - Host-side resources: efanna_build_trees keeps one small pinned host buffer per
  *    calling thread (hipHostMalloc, 32 bytes, never freed) to read its level counters
  *    into; efanna_nndescent creates and destroys 5 * iters HIP events when phase_ms is
@@ -53,7 +54,9 @@ typedef enum {
     EFANNA_EINPUT = -3,     /* X holds a non-finite value, |x| >= 2^20 or n*|x| >= 2^43 */
     EFANNA_EHIP = -4,       /* a HIP runtime call failed                              */
     EFANNA_ECAPACITY = -5,  /* a tree has more leaves than `max_leaves`               */
-    EFANNA_EUNSUPPORTED = -6 /* shape outside what the kernels handle (see each call) */
+    EFANNA_EUNSUPPORTED = -6, /* shape outside what the kernels handle (see each call) */
+    EFANNA_ESCRATCH = -7     /* efanna_nndescent_noalloc: the input needs more scratch memory
+                                than EFANNA_NOALLOC_SCRATCH_BYTES                       */
 } efanna_status;
 
 /* Limits of this build (checked, EFANNA_EUNSUPPORTED / EFANNA_EINVAL beyond them). */
@@ -61,6 +64,8 @@ typedef enum {
 #define EFANNA_MAX_SAMPLE 64    /* NN-descent sample size L                            */
 #define EFANNA_MAX_LEAF 64      /* leaf population S                                   */
 #define EFANNA_MAX_TREES 64
+/* size of the fixed device array behind efanna_nndescent_noalloc (64 MiB per GPU in use) */
+#define EFANNA_NOALLOC_SCRATCH_BYTES (64u << 20)
 
 /* A graph entry: bits 63..32 float32 bit pattern of the squared distance, bits 31..1
  * neighbour id, bit 0 the "new" mark of Alg. 4.  An empty slot has distance +inf.
@@ -184,6 +189,22 @@ int efanna_nndescent(const float *X, int64_t n, int32_t d, int32_t k, efanna_ent
                      int32_t iters, int32_t sample_L, uint64_t seed, int32_t first_iter,
                      float delta, int32_t *iters_done,
                      uint64_t *stats, float *phase_ms, void *ws, size_t ws_bytes, void *stream);
+
+/* The same refinement for callers that cannot allocate device memory and have no workspace
+ * to hand in: code under HIP graph capture, tight serving loops, harnesses that forbid
+ * hipMalloc.  Everything efanna_nndescent keeps in its workspace lives in a fixed array of
+ * EFANNA_NOALLOC_SCRATCH_BYTES that is part of the library's code object (every GPU the
+ * library runs on holds its own copy until the process ends); the call allocates and frees
+ * nothing, on the device or through the HIP runtime, and creates no events.  Arguments as
+ * for efanna_nndescent, without early termination and phase timing; the result is the same,
+ * bit for bit.  Returns EFANNA_ESCRATCH when efanna_nndescent_workspace_bytes(n, k, sample_L)
+ * exceeds EFANNA_NOALLOC_SCRATCH_BYTES (64 MiB: about 140 000 points at k = sample_L = 10).
+ * All calls on one GPU share that GPU's array (it keeps the last call's contents; the call
+ * resets what it needs): calls that overlap on one GPU race, whatever their streams.
+ * Asynchronous on `stream`. */
+int efanna_nndescent_noalloc(const float *X, int64_t n, int32_t d, int32_t k, efanna_entry *graph,
+                             int32_t iters, int32_t sample_L, uint64_t seed, int32_t first_iter,
+                             uint64_t *stats, void *stream);
 
 /* ---- result ("Ensure: approximate kNN graph G") -------------------------------------
  * Sorts every row by (distance, id) and unpacks it.

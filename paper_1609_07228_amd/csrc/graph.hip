@@ -7,6 +7,7 @@
 // values feed 16 fused multiply-adds per lane and step), and a transposed butterfly
 // leaves the finished distance of pair l in lane l.  Each lane then offers its pair to
 // the two rows concerned through the lock-free bounded insertion.
+#include <atomic>
 #include <vector>
 
 #include "common.h"
@@ -2060,6 +2061,7 @@ extern "C" const char *efanna_status_string(int status)
     case EFANNA_EHIP: return "HIP runtime error";
     case EFANNA_ECAPACITY: return "more leaves than max_leaves";
     case EFANNA_EUNSUPPORTED: return "shape not supported by this build";
+    case EFANNA_ESCRATCH: return "input needs more scratch memory than the library's fixed array holds";
     default: return "unknown status";
     }
 }
@@ -2138,11 +2140,72 @@ extern "C" size_t efanna_nndescent_workspace_bytes(int64_t n, int32_t k, int32_t
     return carve_nnd(nullptr, n, k, sample_L).bytes;
 }
 
+namespace {
+
+// Scratch of the entry point that allocates nothing: device memory that the code object
+// brings along, one copy per GPU.  Host code never uses the array's name as an address (on
+// the host it is only a handle for hipGetSymbolAddress): the address on each device is
+// looked up once, with that device current, and kept.
+__device__ __align__(256) unsigned char noalloc_scratch[EFANNA_NOALLOC_SCRATCH_BYTES];
+
+constexpr int kMaxDevices = 64;
+std::atomic<void *> noalloc_scratch_ptr[kMaxDevices];
+
+// The scratch array's address on the current device (nullptr and a status on failure).
+int noalloc_scratch_address(void **out)
+{
+    *out = nullptr;
+    int dev = -1;
+    EF_HIP_CHECK(hipGetDevice(&dev));
+    if (dev < 0 || dev >= kMaxDevices) return EFANNA_EUNSUPPORTED;
+    void *p = noalloc_scratch_ptr[dev].load(std::memory_order_acquire);
+    if (!p) {
+        EF_HIP_CHECK(hipGetSymbolAddress(&p, HIP_SYMBOL(noalloc_scratch)));
+        if (!p) return EFANNA_EHIP;
+        noalloc_scratch_ptr[dev].store(p, std::memory_order_release);      // racing callers store the same address
+    }
+    *out = p;
+    return EFANNA_OK;
+}
+
+int nndescent_run(const float *X, int64_t n, int32_t d, int32_t k, efanna_entry *graph_, int32_t iters,
+                  int32_t sample_L, uint64_t seed, int32_t first_iter, float delta, int32_t *iters_done,
+                  uint64_t *stats_, float *phase_ms, void *ws, size_t ws_bytes, void *stream);
+
+}  // namespace
+
 extern "C" int efanna_nndescent(const float *X, int64_t n, int32_t d, int32_t k,
                                 efanna_entry *graph_, int32_t iters, int32_t sample_L,
                                 uint64_t seed, int32_t first_iter, float delta,
                                 int32_t *iters_done, uint64_t *stats_, float *phase_ms, void *ws,
                                 size_t ws_bytes, void *stream)
+{
+    return nndescent_run(X, n, d, k, graph_, iters, sample_L, seed, first_iter, delta, iters_done, stats_,
+                         phase_ms, ws, ws_bytes, stream);
+}
+
+extern "C" int efanna_nndescent_noalloc(const float *X, int64_t n, int32_t d, int32_t k,
+                                        efanna_entry *graph_, int32_t iters, int32_t sample_L,
+                                        uint64_t seed, int32_t first_iter, uint64_t *stats_,
+                                        void *stream)
+{
+    if (n < 1 || k < 1 || sample_L < 1) return EFANNA_EINVAL;
+    if (efanna_nndescent_workspace_bytes(n, k, sample_L) > (size_t)EFANNA_NOALLOC_SCRATCH_BYTES)
+        return EFANNA_ESCRATCH;
+    void *scratch = nullptr;
+    const int rc = noalloc_scratch_address(&scratch);
+    if (rc != EFANNA_OK) return rc;
+    // no early termination (it reads a counter back after every iteration) and no phase timing
+    // (it creates events): neither allocates device memory, but both make the call wait
+    return nndescent_run(X, n, d, k, graph_, iters, sample_L, seed, first_iter, 0.0f, nullptr, stats_,
+                         nullptr, scratch, (size_t)EFANNA_NOALLOC_SCRATCH_BYTES, stream);
+}
+
+namespace {
+
+int nndescent_run(const float *X, int64_t n, int32_t d, int32_t k, efanna_entry *graph_, int32_t iters,
+                  int32_t sample_L, uint64_t seed, int32_t first_iter, float delta, int32_t *iters_done,
+                  uint64_t *stats_, float *phase_ms, void *ws, size_t ws_bytes, void *stream)
 {
     if (iters_done) *iters_done = 0;
     if (!X || !graph_ || !(delta >= 0.0f)) return EFANNA_EINVAL;
@@ -2399,6 +2462,8 @@ extern "C" int efanna_nndescent(const float *X, int64_t n, int32_t d, int32_t k,
     }
     return EFANNA_OK;
 }
+
+}  // namespace
 
 extern "C" int efanna_get_graph(const efanna_entry *graph_, int64_t n, int32_t k, int32_t *ids,
                                 float *dists, uint8_t *flags, void *stream)

@@ -17,12 +17,12 @@ from . import build as _build
 _lib = None
 
 STATUS = {0: "EFANNA_OK", -1: "EFANNA_EINVAL", -2: "EFANNA_EWORKSPACE", -3: "EFANNA_EINPUT",
-          -4: "EFANNA_EHIP", -5: "EFANNA_ECAPACITY", -6: "EFANNA_EUNSUPPORTED"}
+          -4: "EFANNA_EHIP", -5: "EFANNA_ECAPACITY", -6: "EFANNA_EUNSUPPORTED", -7: "EFANNA_ESCRATCH"}
 
 # every symbol include/efanna.h declares
 SYMBOLS = ["efanna_status_string", "efanna_trees_workspace_bytes", "efanna_build_trees",
            "efanna_init_workspace_bytes", "efanna_init_graph", "efanna_nndescent_workspace_bytes",
-           "efanna_nndescent", "efanna_get_graph", "efanna_set_graph", "efanna_pair_distances",
+           "efanna_nndescent", "efanna_nndescent_noalloc", "efanna_get_graph", "efanna_set_graph", "efanna_pair_distances",
            "efanna_search_workspace_bytes", "efanna_search"]
 
 
@@ -57,6 +57,8 @@ def lib():
         L.efanna_nndescent_workspace_bytes.argtypes = [i64, i32, i32]
         L.efanna_nndescent.restype = C.c_int
         L.efanna_nndescent.argtypes = [vp, i64, i32, i32, vp, i32, i32, u64, i32, C.c_float, vp, vp, vp, vp, sz, vp]
+        L.efanna_nndescent_noalloc.restype = C.c_int
+        L.efanna_nndescent_noalloc.argtypes = [vp, i64, i32, i32, vp, i32, i32, u64, i32, vp, vp]
         L.efanna_get_graph.restype = C.c_int
         L.efanna_get_graph.argtypes = [vp, i64, i32, vp, vp, vp, vp]
         L.efanna_set_graph.restype = C.c_int
@@ -191,6 +193,22 @@ def efanna_nndescent(X: torch.Tensor, graph: torch.Tensor, iters: int, sample_L:
     if delta > 0.0:
         return stats[:done.value], int(done.value)
     return stats[:iters]
+
+
+def efanna_nndescent_noalloc(X: torch.Tensor, graph: torch.Tensor, iters: int, sample_L: int, seed: int,
+                             stats: torch.Tensor, first_iter: int = 0):
+    """efanna_nndescent on the library's fixed scratch array: the call itself allocates nothing,
+    so `stats` ([iters,4] int64 device tensor) comes from the caller.  Returns stats."""
+    X = _dev(X, torch.float32)
+    n, d = X.shape
+    graph = _dev(graph, torch.int64)
+    stats = _dev(stats, torch.int64)
+    if stats.numel() < 4 * max(iters, 1):
+        raise ValueError("stats holds fewer than 4 * iters values")
+    _check(lib().efanna_nndescent_noalloc(X.data_ptr(), n, d, graph.shape[1], graph.data_ptr(), iters,
+                                          sample_L, seed, first_iter, stats.data_ptr(), _stream()),
+           "efanna_nndescent_noalloc")
+    return stats
 
 
 def efanna_get_graph(graph: torch.Tensor, with_flags: bool = False):
