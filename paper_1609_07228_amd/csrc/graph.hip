@@ -20,6 +20,7 @@ constexpr int kLeafGrid = 256 * 256;   // blocks of the register-operand leaf ke
                                        // per headline graph against 1.74 ms with 256 * 32, where a block walks eleven)
 constexpr int kMaxLargeGrid = 256 * 32 * 2;     // most blocks the LDS-row join kernel is launched with
 constexpr int kRowPad = 4;   // floats appended to each LDS row
+constexpr int kMaxClasses = 8;      // most work lists (size classes of joins)
 
 inline size_t align_up(size_t x) { return (x + 255) & ~(size_t)255; }
 // LDS regions are laid out in units of floats; round to 16 bytes so that 8- and 16-byte
@@ -40,7 +41,7 @@ __global__ void fill_reverse_kernel(int *a_count, int *b_count, u64 *list_max, s
                                     int *work_count, int *upd_block, int n_upd_block, int *ovf_count)
 {
     size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (i < 8) work_count[i] = 0;     // three work lists
+    if (i < kMaxClasses) work_count[i] = 0;     // the work lists
     for (size_t j = i; j < (size_t)kOvfQueues * kOvfCounterPitch; j += (size_t)gridDim.x * blockDim.x) ovf_count[j] = 0;
     // insertion counts of join blocks: kernels that are not launched leave theirs at zero
     for (size_t j = i; j < (size_t)n_upd_block; j += (size_t)gridDim.x * blockDim.x) upd_block[j] = 0;
@@ -78,6 +79,12 @@ __device__ inline float tile_distance(const float *rows, int stride, int d, cons
             }
     }
     return ef_group_transpose_reduce16(acc, gl);
+}
+
+// Number of set bits of a ballot below the calling lane.
+__device__ inline int lanes_below(u64 ballot)
+{
+    return (int)__builtin_amdgcn_mbcnt_hi((u32)(ballot >> 32), __builtin_amdgcn_mbcnt_lo((u32)ballot, 0u));
 }
 
 // A proposal waiting in the block's LDS queue: entry `key` offered to row `target`.
@@ -705,12 +712,6 @@ struct Overflow {
     int which;    // 0: reverse-new, 1: reverse-old
 };
 
-// Number of set bits of a ballot below the calling lane.
-__device__ inline int lanes_below(u64 ballot)
-{
-    return (int)__builtin_amdgcn_mbcnt_hi((u32)(ballot >> 32), __builtin_amdgcn_mbcnt_lo((u32)ballot, 0u));
-}
-
 // Parked keys go to kOvfQueues dense queues, block b of the sampling kernels to queue
 // b % kOvfQueues: a wave bumps its queue's counter once for all the keys it parks (bumps of one
 // address serialise, so the counters are many and a cache line apart), and
@@ -1185,20 +1186,44 @@ bucket_lists_kernel(const u32 *__restrict__ offer_runs, const u32 *__restrict__ 
     }
 }
 
+// Work lists by the number of vectors a join gathers: list c takes the joins of at most
+// bound[c] vectors that no earlier list takes (bounds ascending; a bound of 0: no such list).
+// Lists 0 and 1 are the register-operand joins (16 and 32 vectors), the others the size classes
+// of the LDS-row join: a launch per class with a row buffer of that size, so that small joins
+// do not occupy the LDS of the largest one and several blocks fit a CU.
+struct JoinClasses {
+    int n;
+    int bound[kMaxClasses];
+};
+
+// the size classes for joins of up to max_rows vectors; reg_ok: lists 0 and 1 are in use
+inline JoinClasses join_classes(int max_rows, bool reg_ok)
+{
+    JoinClasses jc;
+    jc.n = 2;
+    jc.bound[0] = reg_ok ? 16 : 0;
+    jc.bound[1] = reg_ok ? 32 : 0;
+    for (int c : {48, 64, 96, 128, 160})
+        if (c < max_rows && c > jc.bound[1]) jc.bound[jc.n++] = c;
+    jc.bound[jc.n++] = max_rows;
+    for (int c = jc.n; c < kMaxClasses; ++c) jc.bound[c] = 0;
+    return jc;
+}
+
 // After sampling and the reverse lists: one thread per point merges its four id lists
 // into U_new ++ U_old (Alg. 4: G_new U G_rnew, G_old U G_rold), without duplicates and
 // with everything already in U_new left out of U_old, and files the point under one of
-// three work lists by the number of vectors its join gathers (<= rows0, <= rows1, more).
+// the work lists by the number of vectors its join gathers.
 // Points with an empty U_new are dropped.  A thread compares only what can collide:
 // ids inside one sampled list are distinct, and so are the sources inside one reverse
 // list.  ulist: [n][cap] (written through LDS so that the stores coalesce), ucount: [n]
-// (m_new, m); work: [3][n], work_count: [3].
+// (m_new, m); work: [jc.n][n], work_count: [kMaxClasses].
 template <bool IDS32>      // reverse lists hold 32-bit sources (bucket scheme), not 64-bit keys
 __global__ void prepare_kernel(const int *__restrict__ nw, const int *__restrict__ od,
                                const int *__restrict__ nw_c, const int *__restrict__ od_c,
                                const u64 *__restrict__ rnew, const u64 *__restrict__ rold,
                                const int *__restrict__ rnew_c, const int *__restrict__ rold_c,
-                               int n, int K, int L, int cap, u32 cap_magic, int rows0, int rows1,
+                               int n, int K, int L, int cap, u32 cap_magic, JoinClasses jc,
                                int *__restrict__ ulist, int2 *__restrict__ ucount,
                                int *__restrict__ work, int *__restrict__ work_count,
                                long long *__restrict__ part)
@@ -1237,7 +1262,8 @@ __global__ void prepare_kernel(const int *__restrict__ nw, const int *__restrict
         }
         ucount[i] = make_int2(m_new, m);
         if (m_new >= 1 && m >= 2) {
-            cls = m <= rows0 ? 0 : (m <= rows1 ? 1 : 2);
+            cls = 0;
+            while (cls < jc.n - 1 && m > jc.bound[cls]) ++cls;
             evals = m_new * (m_new - 1) / 2 + m_new * (m - m_new);
             rows = m;
         }
@@ -1252,12 +1278,11 @@ __global__ void prepare_kernel(const int *__restrict__ nw, const int *__restrict
     }
     // append to the work lists: ranks inside the block first, then one counter bump per
     // list and block (bumps of one address serialise at about 11 ns each)
-    __shared__ int wave_cnt[3][kBlock / EF_WAVE], block_base[3];
+    __shared__ int wave_cnt[kMaxClasses][kBlock / EF_WAVE], block_base[kMaxClasses];
     __shared__ int wave_sum[3][kBlock / EF_WAVE];
     const int lane = ef_lane(), wave = threadIdx.x / EF_WAVE, n_waves = blockDim.x / EF_WAVE;
     int rank = 0;
-#pragma unroll
-    for (int c = 0; c < 3; ++c) {
+    for (int c = 0; c < jc.n; ++c) {
         const u64 mask = __ballot(cls == c);
         if (cls == c) rank = __popcll(mask & ((1ULL << lane) - 1));
         if (lane == 0) wave_cnt[c][wave] = __popcll(mask);
@@ -1272,14 +1297,14 @@ __global__ void prepare_kernel(const int *__restrict__ nw, const int *__restrict
         wave_sum[2][wave] = s_r0;
     }
     __syncthreads();
-    if (threadIdx.x < 3) {
+    if ((int)threadIdx.x < jc.n) {
         int tot = 0;
-        long long sum = 0;
-        for (int v = 0; v < n_waves; ++v) {
-            tot += wave_cnt[threadIdx.x][v];
-            sum += wave_sum[threadIdx.x][v];
-        }
+        for (int v = 0; v < n_waves; ++v) tot += wave_cnt[threadIdx.x][v];
         block_base[threadIdx.x] = tot ? atomicAdd(&work_count[threadIdx.x], tot) : 0;
+    }
+    if (threadIdx.x < 3) {
+        long long sum = 0;
+        for (int v = 0; v < n_waves; ++v) sum += wave_sum[threadIdx.x][v];
         part[(size_t)blockIdx.x * 3 + threadIdx.x] = sum;
     }
     __syncthreads();
@@ -1316,12 +1341,24 @@ struct JoinLds {
     float *nrm;       // [cap_rows] squared norms (float32, any order: filter only)
     int *meta;        // [2] updates [3] queue count [4] survivor count
     u32 *surv;        // [s_cap] a | b << 16
+    u32 *known;       // [cap_rows][known_words(cap_rows)] bit c of row r: uid[c] is (or was) in the graph row of uid[r]
+    int *hkey, *hidx; // [known_slots(cap_rows)] each: open-addressing table id -> place in uid
     Proposal *queue;  // [q_cap]
 };
 
+// words per row of the `known` bit table, slots of the id table (a power of two, at most half full)
+__host__ __device__ inline int known_words(int cap_rows) { return (cap_rows + 31) >> 5; }
+__host__ __device__ inline int known_slots(int cap_rows)
+{
+    int s = 64;
+    while (s < 2 * cap_rows) s <<= 1;
+    return s;
+}
+
 __host__ __device__ inline size_t join_lds_floats(int cap_rows, int stride, int s_cap)
 {
-    return (size_t)align4(cap_rows * stride) + align4(3 * cap_rows) + 8 + align4(s_cap);
+    return (size_t)align4(cap_rows * stride) + align4(3 * cap_rows) + 8 + align4(s_cap) +
+           align4(cap_rows * known_words(cap_rows)) + 2 * known_slots(cap_rows);
 }
 
 __device__ inline JoinLds join_lds_carve(float *smem, int cap_rows, int stride, int s_cap)
@@ -1333,13 +1370,16 @@ __device__ inline JoinLds join_lds_carve(float *smem, int cap_rows, int stride, 
     l.nrm = (float *)(l.thr + cap_rows);
     l.meta = l.uid + align4(3 * cap_rows);
     l.surv = (u32 *)(l.meta + 8);
-    l.queue = (Proposal *)(l.surv + align4(s_cap));
+    l.known = l.surv + align4(s_cap);
+    l.hkey = (int *)(l.known + align4(cap_rows * known_words(cap_rows)));
+    l.hidx = l.hkey + known_slots(cap_rows);
+    l.queue = (Proposal *)(l.hidx + known_slots(cap_rows));
     return l;
 }
 
 template <bool WIDE>      // WIDE: graph rows of fifty entries or more are read fifty entries at a time
 __global__ void __launch_bounds__(512) join_kernel(const float *__restrict__ X, const float *__restrict__ norms, int d,
-                            int dpad, int stride, u32 q4_magic, int K,
+                            int dpad, int stride, u32 q4_magic, int K, u32 k_magic,
                             const int *__restrict__ work, const int *__restrict__ work_count,
                             int cap_rows, int s_cap, int q_cap, float margin_rel, float thr_scale,
                             const int *__restrict__ ulist, const int2 *__restrict__ ucount,
@@ -1351,6 +1391,7 @@ __global__ void __launch_bounds__(512) join_kernel(const float *__restrict__ X, 
     const int lane = tid & (EF_WAVE - 1), wave = tid / EF_WAVE, n_waves = nthr / EF_WAVE;
     const int grp = tid >> 4, gl = tid & 15, n_grp = nthr >> 4;
     const int count = *work_count;
+    const int kw = known_words(cap_rows), hslots = known_slots(cap_rows), hshift = 32 - (31 - __clz(hslots));
     int block_updates = 0;      // thread 0: insertions made by this block
     for (int w = blockIdx.x; w < count; w += gridDim.x) {
         const int i = work[w];
@@ -1359,14 +1400,51 @@ __global__ void __launch_bounds__(512) join_kernel(const float *__restrict__ X, 
         const int m_new = mc.x, m = mc.y;
         for (int r = tid; r < m; r += nthr) lds.uid[r] = ulist[(size_t)i * ucap + r];
         if (tid < 8) lds.meta[tid] = 0;
+        for (int f = tid; f < m * kw; f += nthr) lds.known[f] = 0u;
+        for (int f = tid; f < hslots; f += nthr) lds.hkey[f] = -1;
         __syncthreads();
         // ---- 1. gather -------------------------------------------------------------------
         for (int r = tid; r < m; r += nthr) {
             const int id = lds.uid[r];
             lds.thr[r] = ef_load_coherent(worst + id);
             lds.nrm[r] = norms[id];
+            // the members' places by id (ids of a list are distinct: every one finds a free slot)
+            int h = (int)(((u32)id * 0x9E3779B1u) >> hshift);
+            while (atomicCAS(&lds.hkey[h], -1, id) != -1) h = (h + 1) & (hslots - 1);
+            lds.hidx[h] = r;
         }
         gather_rows(X, d, stride, q4_magic, lds.uid, m, lds.rows, tid, nthr);
+        __syncthreads();      // the id table is complete
+        // Which members already know which: the graph rows of all members are read once (plain
+        // loads: a row as it was some time ago will do) and every entry that is itself a member
+        // sets a bit.  An entry that is or ever was in a row never needs to be offered to that row
+        // again (rows only improve: what has left a row cannot come back), so such pairs are
+        // neither evaluated exactly nor queued; with rows of a hundred entries they are nearly all
+        // of the pairs inside the thresholds, and each would otherwise cost a scan of the row.
+        for (int f0 = tid; f0 < m * K; f0 += 8 * nthr) {      // eight entries in flight per thread
+            u64 en[8];
+            int rr[8];
+#pragma unroll
+            for (int q = 0; q < 8; ++q) {
+                const int f = f0 + q * nthr;
+                rr[q] = (int)(((u64)(u32)min(f, m * K - 1) * k_magic) >> 32);
+                en[q] = f < m * K ? graph[(size_t)lds.uid[rr[q]] * K + (f - rr[q] * K)] : ~0ULL;
+            }
+#pragma unroll
+            for (int q = 0; q < 8; ++q) {
+                if (ef_is_empty(en[q])) continue;
+                const int id = ef_id(en[q]);
+                int h = (int)(((u32)id * 0x9E3779B1u) >> hshift);
+                for (int k = lds.hkey[h]; k != -1; k = lds.hkey[h]) {
+                    if (k == id) {
+                        const int c = lds.hidx[h];
+                        atomicOr(&lds.known[rr[q] * kw + (c >> 5)], 1u << (c & 31));
+                        break;
+                    }
+                    h = (h + 1) & (hslots - 1);
+                }
+            }
+        }
         if (dpad > d)
             for (int f = tid; f < m * (dpad - d); f += nthr) {
                 const int r = f / (dpad - d), c = f - r * (dpad - d);
@@ -1402,6 +1480,8 @@ __global__ void __launch_bounds__(512) join_kernel(const float *__restrict__ X, 
                 const int b = 16 * bj + r16;
                 const float nb = lds.nrm[min(b, m - 1)];
                 const float tb = __uint_as_float(lds.thr[min(b, m - 1)]);
+                // what row b already knows of rows 16 bi .. 16 bi + 15 (one half of a word)
+                const u32 known_b = lds.known[min(b, m - 1) * kw + (bi >> 1)] >> (16 * (bi & 1));
 #pragma unroll
                 for (int k = 0; k < 4; ++k) {
                     const int a = 16 * bi + 4 * g + k;
@@ -1409,9 +1489,11 @@ __global__ void __launch_bounds__(512) join_kernel(const float *__restrict__ X, 
                         const float na = lds.nrm[a];
                         const float ta = __uint_as_float(lds.thr[a]);
                         const float sum = na + nb;
-                        const float approx = sum - 2.0f * (acc0[k] + acc1[k]);
-                        if (approx - margin_rel * sum <= fmaxf(ta, tb) * thr_scale)
-                            lds.surv[atomicAdd(&lds.meta[4], 1)] = (u32)a | ((u32)b << 16);
+                        const float low = sum - 2.0f * (acc0[k] + acc1[k]) - margin_rel * sum;
+                        // the pair is wanted by a row that may still accept it and does not know it yet
+                        const bool for_a = low <= ta * thr_scale && !((lds.known[a * kw + (b >> 5)] >> (b & 31)) & 1u);
+                        const bool for_b = low <= tb * thr_scale && !((known_b >> (4 * g + k)) & 1u);
+                        if (for_a || for_b) lds.surv[atomicAdd(&lds.meta[4], 1)] = (u32)a | ((u32)b << 16);
                     }
                 }
             }
@@ -1436,12 +1518,12 @@ __global__ void __launch_bounds__(512) join_kernel(const float *__restrict__ X, 
                         const float dist = ef_group_reduce16(acc);
                         if (gl == 0 && p0 + grp < c1) {
                             const u32 db = __float_as_uint(dist);
-                            if (db <= lds.thr[a]) {
+                            if (db <= lds.thr[a] && !((lds.known[a * kw + (b >> 5)] >> (b & 31)) & 1u)) {
                                 const int slot = atomicAdd(&lds.meta[3], 1);
                                 lds.queue[slot].key = ef_pack(dist, lds.uid[b], 1);
                                 lds.queue[slot].target = lds.uid[a];
                             }
-                            if (db <= lds.thr[b]) {
+                            if (db <= lds.thr[b] && !((lds.known[b * kw + (a >> 5)] >> (a & 31)) & 1u)) {
                                 const int slot = atomicAdd(&lds.meta[3], 1);
                                 lds.queue[slot].key = ef_pack(dist, lds.uid[a], 1);
                                 lds.queue[slot].target = lds.uid[b];
@@ -1551,6 +1633,10 @@ join_reg_kernel(const float *__restrict__ X, const float *__restrict__ norms, in
     // The block is one wave: the fill of the queue and of the survivor lists are wave-uniform
     // registers, and a lane finds its slot from a ballot (no LDS counters, no round trips).
     int updates = 0, q_fill = 0;
+    auto drain = [&](const Proposal *from, int cnt) {
+        return drain_queue<false, NB == 1>(from, cnt, graph, worst, K, lane, EF_WAVE);
+    };
+    auto drain_mid = drain;
     for (; i >= 0; w += gridDim.x) {
         // ---- 0. the point's U_new ++ U_old (the loop ends with a barrier: LDS is free) -------
         const int m_new = c_pre.x, m = c_pre.y;
@@ -1702,7 +1788,7 @@ join_reg_kernel(const float *__restrict__ X, const float *__restrict__ norms, in
         if (rotated) {
             auto room = [&]() {      // a step adds at most two proposals per lane
                 if (q_fill + 2 * EF_WAVE > q_cap) {
-                    updates += drain_queue<false, NB == 1>(queue, q_fill, graph, worst, K, lane, EF_WAVE);
+                    updates += drain_mid(queue, q_fill);
                     q_fill = 0;
                     __syncthreads();
                 }
@@ -1815,7 +1901,7 @@ join_reg_kernel(const float *__restrict__ X, const float *__restrict__ norms, in
                     // NB = 1: the queue is sized so that a point's proposals always fit (at most 240
                     // on top of fewer than q_cap / 2): no drain while the operands are live
                     if (NB > 1 && q_fill + 32 > q_cap) {      // a round adds at most two proposals per pair
-                        updates += drain_queue<false, NB == 1>(queue, q_fill, graph, worst, K, lane, EF_WAVE);
+                        updates += drain_mid(queue, q_fill);
                         q_fill = 0;
                         __syncthreads();
                     }
@@ -1826,13 +1912,13 @@ join_reg_kernel(const float *__restrict__ X, const float *__restrict__ norms, in
             // whole passes of 64 only, from the end of the queue: what is left waits for the next
             // drain (a pass costs its two round trips however few lanes it fills)
             const int rest = q_fill & (EF_WAVE - 1);
-            updates += drain_queue<false, NB == 1>(queue + rest, q_fill - rest, graph, worst, K, lane, EF_WAVE);
+            updates += drain(queue + rest, q_fill - rest);
             q_fill = rest;
         }
         __syncthreads();
     }
     __syncthreads();
-    updates += drain_queue<false, NB == 1>(queue, q_fill, graph, worst, K, lane, EF_WAVE);
+    updates += drain(queue, q_fill);
     updates = ef_wave_sum_i32(updates);
     if (lane == 0) upd_block[blockIdx.x] = updates;
 }
@@ -2013,8 +2099,9 @@ NndWs carve_nnd(void *ws, int64_t n, int K, int L)
     w.nw_c = (int *)take((size_t)n * 4);
     w.od_c = (int *)take((size_t)n * 4);
     w.part = (long long *)take(((size_t)n / EF_WAVE + 1) * 3 * 8);      // prepare blocks hold >= 64 points
-    w.work = (int *)take((size_t)n * 3 * 4);
-    w.work_count = (int *)take(8 * 4);     // [0..2] list sizes
+    const int n_lists = join_classes(K + 2 * L, true).n;      // (without the register joins there are no more lists)
+    w.work = (int *)take((size_t)n * n_lists * 4);
+    w.work_count = (int *)take(kMaxClasses * 4);     // list sizes
     w.rnew_c = (int *)take((size_t)n * 4);
     w.rold_c = (int *)take((size_t)n * 4);
     // reverse lists: either the overflow queues of the counter scheme or the offer runs and
@@ -2027,7 +2114,7 @@ NndWs carve_nnd(void *ws, int64_t n, int K, int L)
     w.ovf_count = (int *)take((size_t)kOvfQueues * kOvfCounterPitch * 4);
     w.ulist = (int *)take((size_t)n * (K + 2 * L) * 4);
     w.ucount = (int2 *)take((size_t)n * 8);
-    w.upd_block = (int *)take((size_t)(2 * kRegGrid + kMaxLargeGrid) * 4);
+    w.upd_block = (int *)take((size_t)(2 * kRegGrid + (n_lists - 2) * kMaxLargeGrid) * 4);
     w.rnew = (u64 *)take((size_t)n * L * 8);
     w.rold = (u64 *)take((size_t)n * L * 8);
     w.list_max = (u64 *)take((size_t)n * 2 * 8);
@@ -2222,10 +2309,12 @@ int nndescent_run(const float *X, int64_t n, int32_t d, int32_t k, efanna_entry 
     // a join gathers at most K + 2L vectors: new and old sets together come from one row
     // of K entries, each reverse list adds at most L
     const int max_rows = K + 2 * L;
-    // three work lists: joins of at most 16 and at most 32 vectors run from register
-    // operands (needs 16-byte aligned rows), the rest through the LDS row buffer
+    // work lists: joins of at most 16 and at most 32 vectors run from register operands (needs
+    // 16-byte aligned rows), the rest through LDS row buffers, one launch per size class
     const bool reg_ok = (d & 3) == 0 && ((uintptr_t)X & 15) == 0;
-    const int rows0 = reg_ok ? 16 : 0, rows1 = reg_ok ? 32 : 0;
+    const int rows1 = reg_ok ? 32 : 0;
+    const JoinClasses jc = join_classes(max_rows, reg_ok);
+    const int n_upd_block = 2 * kRegGrid + (jc.n - 2) * kMaxLargeGrid;
     struct Shape {
         int cap_rows, threads, s_cap, q_cap, grid;
         size_t lds;
@@ -2243,7 +2332,8 @@ int nndescent_run(const float *X, int64_t n, int32_t d, int32_t k, efanna_entry 
             sh.s_cap = 256 * n_waves;
             if (pairs > sh.s_cap && pairs <= 1024) sh.s_cap = align4((int)pairs);
             if (cap_rows <= 16) sh.s_cap = 128;     // a single block of at most 120 pairs
-            for (sh.q_cap = 4 * sh.threads; sh.q_cap >= 128 && !fits; sh.q_cap /= 2) {
+            // (pairs that a row already knows are not queued: a few hundred proposals per join at most)
+            for (sh.q_cap = min(4 * sh.threads, 512); sh.q_cap >= 128 && !fits; sh.q_cap /= 2) {
                 sh.lds = join_lds_floats(cap_rows, stride, sh.s_cap) * 4 +
                          (size_t)sh.q_cap * sizeof(Proposal);
                 fits = sh.lds <= kLdsLimit;
@@ -2260,8 +2350,13 @@ int nndescent_run(const float *X, int64_t n, int32_t d, int32_t k, efanna_entry 
         sh.grid = (int)(256 * per_cu * 2);
         return sh;
     };
-    const Shape large = shape_for(max_rows);
-    if (max_rows > rows1 && large.lds > kLdsLimit) return EFANNA_EUNSUPPORTED;
+    Shape large[kMaxClasses];
+    size_t large_lds = 0;
+    for (int c = 2; c < jc.n; ++c) {
+        large[c] = shape_for(jc.bound[c]);
+        large_lds = large[c].lds > large_lds ? large[c].lds : large_lds;
+    }
+    if (max_rows > rows1 && large_lds > kLdsLimit) return EFANNA_EUNSUPPORTED;
     // joins of at most 16 vectors from registers (d <= 128): room for a whole point's proposals
     // (240) above the drain mark; the others drain between rounds as well (joins of 17..32
     // vectors: 256 entries measured 3 % faster than 128, 512 no better)
@@ -2303,7 +2398,7 @@ int nndescent_run(const float *X, int64_t n, int32_t d, int32_t k, efanna_entry 
     if (max_rows > rows1)
         EF_HIP_CHECK(hipFuncSetAttribute(K >= 2 * EF_WIDE_PIECES ? (const void *)join_kernel<true>
                                                                  : (const void *)join_kernel<false>,
-                                         hipFuncAttributeMaxDynamicSharedMemorySize, (int)large.lds));
+                                         hipFuncAttributeMaxDynamicSharedMemorySize, (int)large_lds));
     norms_kernel<<<grid_for((size_t)n * 16, kBlock), kBlock, 0, st>>>(X, (int)n, d, w.norms);
     if (stats) zero_u64_kernel<<<grid_for((size_t)iters * 4 + 1, kBlock), kBlock, 0, st>>>(stats, iters * 4);
     // optional phase timing: events around the sampling and the join of every iteration
@@ -2329,9 +2424,9 @@ int nndescent_run(const float *X, int64_t n, int32_t d, int32_t k, efanna_entry 
         const int g = first_iter + it;
         if (ev) EF_HIP_CHECK(hipEventRecord(ev[5 * it], st));
         // (the bucket scheme writes every list count itself: only the small arrays are reset)
-        fill_reverse_kernel<<<grid_for(bkt ? (size_t)(2 * kRegGrid + kMaxLargeGrid) : (size_t)n, kBlock), kBlock, 0, st>>>(
+        fill_reverse_kernel<<<grid_for(bkt ? (size_t)n_upd_block : (size_t)n, kBlock), kBlock, 0, st>>>(
             w.rnew_c, w.rold_c, w.list_max, bkt ? (size_t)0 : (size_t)n, w.work_count, w.upd_block,
-            2 * kRegGrid + kMaxLargeGrid, w.ovf_count);
+            n_upd_block, w.ovf_count);
         {
             const u64 kn = ef_stream_key(seed, 2 * g), ko = ef_stream_key(seed, 2 * g + 1);
             Overflow *ovf = (Overflow *)w.overflow;
@@ -2392,7 +2487,7 @@ int nndescent_run(const float *X, int64_t n, int32_t d, int32_t k, efanna_entry 
 #define EF_PREPARE(IDS32)                                                                          \
     prepare_kernel<IDS32><<<grid_for((size_t)n, prep_threads), prep_threads, prep_lds, st>>>(       \
         w.nw, w.od, w.nw_c, w.od_c, w.rnew, w.rold, w.rnew_c, w.rold_c, (int)n, K, L, max_rows,     \
-        (u32)(((1ULL << 32) + max_rows - 1) / max_rows), rows0, rows1, w.ulist, w.ucount, w.work,  \
+        (u32)(((1ULL << 32) + max_rows - 1) / max_rows), jc, w.ulist, w.ucount, w.work,            \
         w.work_count, w.part)
         if (bkt) EF_PREPARE(true);
         else EF_PREPARE(false);
@@ -2423,20 +2518,22 @@ int nndescent_run(const float *X, int64_t n, int32_t d, int32_t k, efanna_entry 
             EF_HIP_CHECK(hipEventRecord(ev[5 * it + 2], st));
         }
         if (ev) EF_HIP_CHECK(hipEventRecord(ev[5 * it + 3], st));
-#define EF_JOIN_LARGE(WIDE)                                                                        \
-    join_kernel<WIDE><<<large.grid, large.threads, large.lds, st>>>(                               \
-        X, w.norms, d, dpad, stride, q4_magic_for(d), K, w.work + 2 * (size_t)n, w.work_count + 2, \
-        large.cap_rows, large.s_cap, large.q_cap, margin_rel, thr_scale, w.ulist, w.ucount,        \
-        max_rows, graph, w.worst, w.upd_block + 2 * reg_grid)
-        if (max_rows > rows1) {
-            if (K >= 2 * EF_WIDE_PIECES) EF_JOIN_LARGE(true);
-            else EF_JOIN_LARGE(false);
+#define EF_JOIN_LARGE(WIDE, C)                                                                     \
+    join_kernel<WIDE><<<large[C].grid, large[C].threads, large[C].lds, st>>>(                      \
+        X, w.norms, d, dpad, stride, q4_magic_for(d), K, (u32)(((1ULL << 32) + K - 1) / K),       \
+        w.work + (size_t)(C) * n, w.work_count + (C),                                              \
+        large[C].cap_rows, large[C].s_cap, large[C].q_cap, margin_rel, thr_scale, w.ulist,         \
+        w.ucount, max_rows, graph, w.worst, w.upd_block + 2 * reg_grid + ((C) - 2) * kMaxLargeGrid)
+        // the larger classes first: their blocks run longest
+        for (int c = jc.n - 1; c >= 2 && max_rows > rows1; --c) {
+            if (K >= 2 * EF_WIDE_PIECES) EF_JOIN_LARGE(true, c);
+            else EF_JOIN_LARGE(false, c);
         }
 #undef EF_JOIN_LARGE
         if (ev) EF_HIP_CHECK(hipEventRecord(ev[5 * it + 4], st));
         if (stats)
             stats_kernel<<<16, kBlock, 0, st>>>(w.part, grid_for((size_t)n, prep_threads), w.upd_block,
-                                                2 * reg_grid + kMaxLargeGrid, stats + 4 * it);
+                                                n_upd_block, stats + 4 * it);
         done = it + 1;
         if (delta > 0.0f) {      // early termination: the host looks at the count after every iteration
             u64 fresh = 0;
