@@ -1923,6 +1923,227 @@ join_reg_kernel(const float *__restrict__ X, const float *__restrict__ norms, in
     if (lane == 0) upd_block[blockIdx.x] = updates;
 }
 
+// ---------------------------------------------------------------------------------------
+// The local join for points whose join gathers more than 32 vectors of at most 128 coordinates
+// (d % 4 == 0, X 16-byte aligned), without a row buffer: one wave per point, the vectors pass
+// through registers sixteen at a time.  For every tile of sixteen new rows (A) and every tile of
+// sixteen rows from it onwards (B) the wave loads both tiles as join_reg_kernel does - lane
+// (r, g) the 16-byte pieces 16 s + 4 g of row r - forms their Gram block with fp32 MFMA, filters,
+// and evaluates the surviving pairs exactly from the same registers.  B tiles are read once per
+// A tile: the rows of a join (some tens of KB) come from the caches after the first time.  What
+// a block keeps in LDS is small (ids, thresholds, the table of pairs already known, queues: a few
+// KB against the tens of KB of a row buffer), its waves never wait for one another, and a dozen
+// joins are in flight on a CU instead of one or two.
+struct TileLds {
+    int *uid;          // [cap] U_new ++ U_old
+    u32 *thr;          // [cap] threshold bits (exact test)
+    float *nf, *tf;    // [cap] |x|^2 (1 - margin), threshold * scale (filter)
+    u32 *known;        // [cap][known_words(cap)]
+    int *hkey, *hidx;  // [known_slots(cap)]
+    u32 *surv;         // [256] surviving pairs of the tile pair in hand
+    Proposal *queue;   // [q_cap]
+};
+__host__ __device__ inline size_t tile_lds_bytes(int cap, int q_cap)
+{
+    return (size_t)(align4(cap) * 4 + align4(cap * known_words(cap)) + 2 * known_slots(cap) + 256) * 4 +
+           (size_t)q_cap * sizeof(Proposal);
+}
+__device__ inline TileLds tile_lds_carve(float *smem, int cap)
+{
+    TileLds l;
+    const int c4 = align4(cap);
+    l.uid = (int *)smem;
+    l.thr = (u32 *)(l.uid + c4);
+    l.nf = (float *)(l.thr + c4);
+    l.tf = l.nf + c4;
+    l.known = (u32 *)(l.tf + c4);
+    l.hkey = (int *)(l.known + align4(cap * known_words(cap)));
+    l.hidx = l.hkey + known_slots(cap);
+    l.surv = (u32 *)(l.hidx + known_slots(cap));
+    l.queue = (Proposal *)(l.surv + 256);
+    return l;
+}
+
+template <bool LONG_ROWS>      // graph rows of even length, 16-byte aligned, more than 16 entries: sixteen lanes per proposal
+__global__ void __launch_bounds__(EF_WAVE) __attribute__((amdgpu_waves_per_eu(3)))
+join_tile_kernel(const float *__restrict__ X, const float *__restrict__ norms, int d, int K, u32 k_magic,
+                 const int *__restrict__ work, const int *__restrict__ work_count, int cap, int q_cap,
+                 float margin_rel, float thr_scale, const int *__restrict__ ulist,
+                 const int2 *__restrict__ ucount, int ucap, u64 *graph, u32 *worst,
+                 int *__restrict__ upd_block)
+{
+    extern __shared__ __align__(16) float smem[];
+    const TileLds lds = tile_lds_carve(smem, cap);
+    const int lane = threadIdx.x, r16 = lane & 15, g = lane >> 4;
+    const int kw = known_words(cap), hslots = known_slots(cap), hshift = 32 - (31 - __clz(hslots));
+    const int count = *work_count;
+    const int n_pieces = (d + 15) >> 4;      // 16-coordinate pieces of a vector (at most 8)
+    int updates = 0, q_fill = 0;
+    auto drain = [&]() {
+        updates += LONG_ROWS ? drain_queue_g16(lds.queue, q_fill, graph, worst, K, lane, EF_WAVE)
+                             : drain_queue<false, false>(lds.queue, q_fill, graph, worst, K, lane, EF_WAVE);
+        q_fill = 0;
+        __syncthreads();
+    };
+    auto is_known = [&](int row, int col) { return (lds.known[row * kw + (col >> 5)] >> (col & 31)) & 1u; };
+    for (int w = blockIdx.x; w < count; w += gridDim.x) {
+        const int i = work[w];
+        const int2 mc = ucount[i];
+        const int m_new = mc.x, m = min(mc.y, cap);
+        // ---- 0. ids, thresholds, norms; the members' places by id ---------------------------
+        for (int f = lane; f < m * kw; f += EF_WAVE) lds.known[f] = 0u;
+        for (int f = lane; f < hslots; f += EF_WAVE) lds.hkey[f] = -1;
+        __syncthreads();
+        for (int r = lane; r < m; r += EF_WAVE) {
+            const int id = ulist[(size_t)i * ucap + r];
+            const u32 t = ef_load_coherent(worst + id);
+            lds.uid[r] = id;
+            lds.thr[r] = t;
+            lds.tf[r] = __uint_as_float(t) * thr_scale;
+            lds.nf[r] = norms[id] * (1.0f - margin_rel);
+            int h = (int)(((u32)id * 0x9E3779B1u) >> hshift);
+            while (atomicCAS(&lds.hkey[h], -1, id) != -1) h = (h + 1) & (hslots - 1);
+            lds.hidx[h] = r;
+        }
+        __syncthreads();
+        // ---- 1. which members already know which (see join_kernel) --------------------------
+        for (int f0 = lane; f0 < m * K; f0 += 8 * EF_WAVE) {
+            u64 en[8];
+            int rr[8];
+#pragma unroll
+            for (int q = 0; q < 8; ++q) {
+                const int f = f0 + q * EF_WAVE;
+                rr[q] = (int)(((u64)(u32)min(f, m * K - 1) * k_magic) >> 32);
+                en[q] = f < m * K ? graph[(size_t)lds.uid[rr[q]] * K + (f - rr[q] * K)] : ~0ULL;
+            }
+#pragma unroll
+            for (int q = 0; q < 8; ++q) {
+                if (ef_is_empty(en[q])) continue;
+                const int id = ef_id(en[q]);
+                int h = (int)(((u32)id * 0x9E3779B1u) >> hshift);
+                for (int k = lds.hkey[h]; k != -1; k = lds.hkey[h]) {
+                    if (k == id) {
+                        const int c = lds.hidx[h];
+                        atomicOr(&lds.known[rr[q] * kw + (c >> 5)], 1u << (c & 31));
+                        break;
+                    }
+                    h = (h + 1) & (hslots - 1);
+                }
+            }
+        }
+        __syncthreads();
+        // ---- 2. tile pairs ---------------------------------------------------------------------
+        const int nbr = (m_new + 15) >> 4, nbc = (m + 15) >> 4;
+        for (int bi = 0; bi < nbr; ++bi) {
+            float4 va[8];
+            {
+                const float *pa = X + (size_t)lds.uid[min(16 * bi + r16, m - 1)] * d + 4 * g;
+#pragma unroll
+                for (int s = 0; s < 8; ++s) {
+                    const bool in = 16 * s + 4 * g + 3 < d;      // d % 4 == 0: a piece is in or out
+                    va[s] = in ? *reinterpret_cast<const float4 *>(pa + 16 * s) : make_float4(0.f, 0.f, 0.f, 0.f);
+                }
+            }
+            for (int bj = bi; bj < nbc; ++bj) {
+                float4 vb[8];
+                if (bj == bi) {
+#pragma unroll
+                    for (int s = 0; s < 8; ++s) vb[s] = va[s];
+                } else {
+                    const float *pb = X + (size_t)lds.uid[min(16 * bj + r16, m - 1)] * d + 4 * g;
+#pragma unroll
+                    for (int s = 0; s < 8; ++s) {
+                        const bool in = 16 * s + 4 * g + 3 < d;
+                        vb[s] = in ? *reinterpret_cast<const float4 *>(pb + 16 * s) : make_float4(0.f, 0.f, 0.f, 0.f);
+                    }
+                }
+                floatx4 acc0 = {0.f, 0.f, 0.f, 0.f}, acc1 = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                for (int s = 0; s < 8; ++s) {
+                    if (s >= n_pieces) break;
+                    acc0 = __builtin_amdgcn_mfma_f32_16x16x4f32(va[s].x, vb[s].x, acc0, 0, 0, 0);
+                    acc1 = __builtin_amdgcn_mfma_f32_16x16x4f32(va[s].y, vb[s].y, acc1, 0, 0, 0);
+                    acc0 = __builtin_amdgcn_mfma_f32_16x16x4f32(va[s].z, vb[s].z, acc0, 0, 0, 0);
+                    acc1 = __builtin_amdgcn_mfma_f32_16x16x4f32(va[s].w, vb[s].w, acc1, 0, 0, 0);
+                }
+                // ---- filter: the lane holds G[a = 16 bi + 4 g + k][b = 16 bj + r16] ---------------
+                const int b = 16 * bj + r16, bc = min(b, m - 1);
+                const float nfb = lds.nf[bc], tfb = lds.tf[bc];
+                const u32 known_b = lds.known[bc * kw + (bi >> 1)] >> (16 * (bi & 1));      // row b on rows 16 bi ..
+                int n_surv = 0;
+#pragma unroll
+                for (int k = 0; k < 4; ++k) {
+                    const int a = 16 * bi + 4 * g + k, ac = min(a, m - 1);
+                    const float low = __builtin_fmaf(-2.0f, acc0[k] + acc1[k], lds.nf[ac] + nfb);
+                    const bool valid = a < m_new && b < m && a < b;
+                    // wanted by a row that may still accept the pair and does not know it yet
+                    const bool keep = valid && ((low <= lds.tf[ac] && !is_known(ac, bc)) ||
+                                                (low <= tfb && !((known_b >> (4 * g + k)) & 1u)));
+                    const u64 kept = __ballot(keep);
+                    if (keep) lds.surv[n_surv + lanes_below(kept)] = (u32)(4 * g + k) | ((u32)r16 << 8);
+                    n_surv += __popcll(kept);
+                }
+                __syncthreads();
+                // ---- survivors from registers, sixteen pairs per round (see join_reg_kernel) ------
+                for (int p0 = 0; p0 < n_surv; p0 += 16) {
+                    const bool has = p0 + r16 < n_surv;
+                    const u32 ent = lds.surv[min(p0 + r16, n_surv - 1)];
+                    const int al = ent & 15, bl = (ent >> 8) & 15;
+                    const int src_a = al + 16 * g, src_b = bl + 16 * g;
+                    float p0s = 0.f, p1s = 0.f, p2s = 0.f, p3s = 0.f;
+#pragma unroll
+                    for (int s = 0; s < 8; ++s) {
+                        if (s >= n_pieces) break;
+                        const float d0 = __shfl(va[s].x, src_a, EF_WAVE) - __shfl(vb[s].x, src_b, EF_WAVE);
+                        const float d1 = __shfl(va[s].y, src_a, EF_WAVE) - __shfl(vb[s].y, src_b, EF_WAVE);
+                        const float d2 = __shfl(va[s].z, src_a, EF_WAVE) - __shfl(vb[s].z, src_b, EF_WAVE);
+                        const float d3 = __shfl(va[s].w, src_a, EF_WAVE) - __shfl(vb[s].w, src_b, EF_WAVE);
+                        p0s = __builtin_fmaf(d0, d0, p0s);
+                        p1s = __builtin_fmaf(d1, d1, p1s);
+                        p2s = __builtin_fmaf(d2, d2, p2s);
+                        p3s = __builtin_fmaf(d3, d3, p3s);
+                    }
+                    p0s += __shfl_xor(p0s, 32, EF_WAVE);
+                    p1s += __shfl_xor(p1s, 32, EF_WAVE);
+                    p2s += __shfl_xor(p2s, 32, EF_WAVE);
+                    p3s += __shfl_xor(p3s, 32, EF_WAVE);
+                    p0s += __shfl_xor(p0s, 16, EF_WAVE);
+                    p1s += __shfl_xor(p1s, 16, EF_WAVE);
+                    p2s += __shfl_xor(p2s, 16, EF_WAVE);
+                    p3s += __shfl_xor(p3s, 16, EF_WAVE);
+                    const float dist = (p0s + p2s) + (p1s + p3s);
+                    const int a = 16 * bi + al, bb = 16 * bj + bl;
+                    const u32 db = __float_as_uint(dist);
+                    const bool mine = has && g == 0;
+                    const bool to_a = mine && db <= lds.thr[a] && !is_known(a, bb);
+                    const bool to_b = mine && db <= lds.thr[bb] && !is_known(bb, a);
+                    const u64 mask_a = __ballot(to_a), mask_b = __ballot(to_b);
+                    if (to_a) {
+                        Proposal &pr = lds.queue[q_fill + lanes_below(mask_a)];
+                        pr.key = ef_pack(dist, lds.uid[bb], 1);
+                        pr.target = lds.uid[a];
+                    }
+                    q_fill += __popcll(mask_a);
+                    if (to_b) {
+                        Proposal &pr = lds.queue[q_fill + lanes_below(mask_b)];
+                        pr.key = ef_pack(dist, lds.uid[a], 1);
+                        pr.target = lds.uid[bb];
+                    }
+                    q_fill += __popcll(mask_b);
+                    __syncthreads();
+                    if (q_fill + 32 > q_cap) drain();      // a round adds at most two proposals per pair
+                }
+                __syncthreads();      // the survivor list is free again
+            }
+        }
+        if (q_fill >= q_cap / 2) drain();
+        __syncthreads();
+    }
+    drain();
+    updates = ef_wave_sum_i32(updates);
+    if (lane == 0) upd_block[blockIdx.x] = updates;
+}
+
 // squared norms in float32 (only the join's filter uses them; any summation order will do)
 __global__ void norms_kernel(const float *__restrict__ X, int n, int d, float *__restrict__ norms)
 {
@@ -2356,7 +2577,10 @@ int nndescent_run(const float *X, int64_t n, int32_t d, int32_t k, efanna_entry 
         large[c] = shape_for(jc.bound[c]);
         large_lds = large[c].lds > large_lds ? large[c].lds : large_lds;
     }
-    if (max_rows > rows1 && large_lds > kLdsLimit) return EFANNA_EUNSUPPORTED;
+    // joins of more than 32 vectors: register tiles for vectors of at most 128 coordinates, else rows in LDS
+    const bool tiles = reg_ok && d <= 128;
+    if (tiles && max_rows > rows1 && tile_lds_bytes(max_rows, 256) > kLdsLimit) return EFANNA_EUNSUPPORTED;
+    if (!tiles && max_rows > rows1 && large_lds > kLdsLimit) return EFANNA_EUNSUPPORTED;
     // joins of at most 16 vectors from registers (d <= 128): room for a whole point's proposals
     // (240) above the drain mark; the others drain between rounds as well (joins of 17..32
     // vectors: 256 entries measured 3 % faster than 128, 512 no better)
@@ -2395,7 +2619,13 @@ int nndescent_run(const float *X, int64_t n, int32_t d, int32_t k, efanna_entry 
                                                         : (const void *)bucket_lists_kernel<9, 0>,
                                          hipFuncAttributeMaxDynamicSharedMemorySize, (int)bucket_lists_lds(L, n_bkt)));
     }
-    if (max_rows > rows1)
+    if (max_rows > rows1 && tiles && tile_lds_bytes(max_rows, 256) > 64 * 1024) {
+        EF_HIP_CHECK(hipFuncSetAttribute((const void *)join_tile_kernel<true>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                         (int)tile_lds_bytes(max_rows, 256)));
+        EF_HIP_CHECK(hipFuncSetAttribute((const void *)join_tile_kernel<false>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                         (int)tile_lds_bytes(max_rows, 256)));
+    }
+    if (max_rows > rows1 && !tiles)
         EF_HIP_CHECK(hipFuncSetAttribute(K >= 2 * EF_WIDE_PIECES ? (const void *)join_kernel<true>
                                                                  : (const void *)join_kernel<false>,
                                          hipFuncAttributeMaxDynamicSharedMemorySize, (int)large_lds));
@@ -2526,7 +2756,23 @@ int nndescent_run(const float *X, int64_t n, int32_t d, int32_t k, efanna_entry 
         w.ucount, max_rows, graph, w.worst, w.upd_block + 2 * reg_grid + ((C) - 2) * kMaxLargeGrid)
         // the larger classes first: their blocks run longest
         for (int c = jc.n - 1; c >= 2 && max_rows > rows1; --c) {
-            if (K >= 2 * EF_WIDE_PIECES) EF_JOIN_LARGE(true, c);
+            if (tiles) {      // vectors of at most 128 coordinates pass through registers
+                const int tq = 256;
+                const size_t tl = tile_lds_bytes(jc.bound[c], tq);
+                long per_cu = (long)(kLdsLimit / tl);
+                per_cu = per_cu > 12 ? 12 : (per_cu < 1 ? 1 : per_cu);      // three waves per SIMD
+                const int tgrid = (int)(256 * per_cu * 4);
+                int *upd = w.upd_block + 2 * reg_grid + (c - 2) * kMaxLargeGrid;
+                const u32 km = (u32)(((1ULL << 32) + K - 1) / K);
+                if (K > 16 && (K & 1) == 0 && ((uintptr_t)graph & 15) == 0)
+                    join_tile_kernel<true><<<tgrid, EF_WAVE, tl, st>>>(
+                        X, w.norms, d, K, km, w.work + (size_t)c * n, w.work_count + c, jc.bound[c], tq, margin_rel,
+                        thr_scale, w.ulist, w.ucount, max_rows, graph, w.worst, upd);
+                else
+                    join_tile_kernel<false><<<tgrid, EF_WAVE, tl, st>>>(
+                        X, w.norms, d, K, km, w.work + (size_t)c * n, w.work_count + c, jc.bound[c], tq, margin_rel,
+                        thr_scale, w.ulist, w.ucount, max_rows, graph, w.worst, upd);
+            } else if (K >= 2 * EF_WIDE_PIECES) EF_JOIN_LARGE(true, c);
             else EF_JOIN_LARGE(false, c);
         }
 #undef EF_JOIN_LARGE
