@@ -1939,13 +1939,25 @@ struct TileLds {
     u32 *thr;          // [cap] threshold bits (exact test)
     float *nf, *tf;    // [cap] |x|^2 (1 - margin), threshold * scale (filter)
     u32 *known;        // [cap][known_words(cap)]
-    int *hkey, *hidx;  // [known_slots(cap)]
+    int *hkey;         // [tile_slots(cap)] ids in buckets of two slots, -1 = free
+    int *hidx;         // [tile_slots(cap)] the place in uid of the id in that slot
     u32 *surv;         // [256] surviving pairs of the tile pair in hand
     Proposal *queue;   // [q_cap]
 };
+// The table that maps an id to its place in the list: buckets of two slots, a quarter full at
+// most, so that nearly every look-up is one 8-byte read of the id's own bucket (ten thousand
+// look-ups per join: a probe loop whose length differs from lane to lane was most of a join).
+// An id goes to the first free slot of its bucket, else of the buckets after it; a look-up
+// therefore ends at the first bucket with a free slot.
+__host__ __device__ inline int tile_slots(int cap)
+{
+    int s = 128;
+    while (s < 4 * cap) s <<= 1;
+    return s;
+}
 __host__ __device__ inline size_t tile_lds_bytes(int cap, int q_cap)
 {
-    return (size_t)(align4(cap) * 4 + align4(cap * known_words(cap)) + 2 * known_slots(cap) + 256) * 4 +
+    return (size_t)(align4(cap) * 4 + align4(cap * known_words(cap)) + 2 * tile_slots(cap) + 256) * 4 +
            (size_t)q_cap * sizeof(Proposal);
 }
 __device__ inline TileLds tile_lds_carve(float *smem, int cap)
@@ -1958,8 +1970,8 @@ __device__ inline TileLds tile_lds_carve(float *smem, int cap)
     l.tf = l.nf + c4;
     l.known = (u32 *)(l.tf + c4);
     l.hkey = (int *)(l.known + align4(cap * known_words(cap)));
-    l.hidx = l.hkey + known_slots(cap);
-    l.surv = (u32 *)(l.hidx + known_slots(cap));
+    l.hidx = l.hkey + tile_slots(cap);
+    l.surv = (u32 *)(l.hidx + tile_slots(cap));
     l.queue = (Proposal *)(l.surv + 256);
     return l;
 }
@@ -1975,11 +1987,22 @@ join_tile_kernel(const float *__restrict__ X, const float *__restrict__ norms, i
     extern __shared__ __align__(16) float smem[];
     const TileLds lds = tile_lds_carve(smem, cap);
     const int lane = threadIdx.x, r16 = lane & 15, g = lane >> 4;
-    const int kw = known_words(cap), hslots = known_slots(cap), hshift = 32 - (31 - __clz(hslots));
+    const int kw = known_words(cap), hslots = tile_slots(cap), n_buckets = hslots >> 1;
+    const int hshift = 32 - (31 - __clz(n_buckets));      // id * odd constant >> hshift: the id's bucket
     const int count = *work_count;
     const int n_pieces = (d + 15) >> 4;      // 16-coordinate pieces of a vector (at most 8)
     int updates = 0, q_fill = 0;
+#ifdef EF_PROF
+    long long pc[5] = {0, 0, 0, 0, 0}, t0 = 0;
+    int n_joins = 0, n_surv_tot = 0, n_prop = 0;
+#define EF_T(k) do { long long t1 = __builtin_readcyclecounter(); pc[k] += t1 - t0; t0 = t1; } while (0)
+#else
+#define EF_T(k)
+#endif
     auto drain = [&]() {
+#ifdef EF_PROF
+        n_prop += q_fill;
+#endif
         updates += LONG_ROWS ? drain_queue_g16(lds.queue, q_fill, graph, worst, K, lane, EF_WAVE)
                              : drain_queue<false, false>(lds.queue, q_fill, graph, worst, K, lane, EF_WAVE);
         q_fill = 0;
@@ -1990,6 +2013,9 @@ join_tile_kernel(const float *__restrict__ X, const float *__restrict__ norms, i
         const int i = work[w];
         const int2 mc = ucount[i];
         const int m_new = mc.x, m = min(mc.y, cap);
+#ifdef EF_PROF
+        t0 = __builtin_readcyclecounter(); ++n_joins;
+#endif
         // ---- 0. ids, thresholds, norms; the members' places by id ---------------------------
         for (int f = lane; f < m * kw; f += EF_WAVE) lds.known[f] = 0u;
         for (int f = lane; f < hslots; f += EF_WAVE) lds.hkey[f] = -1;
@@ -2001,12 +2027,13 @@ join_tile_kernel(const float *__restrict__ X, const float *__restrict__ norms, i
             lds.thr[r] = t;
             lds.tf[r] = __uint_as_float(t) * thr_scale;
             lds.nf[r] = norms[id] * (1.0f - margin_rel);
-            int h = (int)(((u32)id * 0x9E3779B1u) >> hshift);
+            int h = 2 * (int)(((u32)id * 0x9E3779B1u) >> hshift);      // ids of a list are distinct: every one finds a slot
             while (atomicCAS(&lds.hkey[h], -1, id) != -1) h = (h + 1) & (hslots - 1);
             lds.hidx[h] = r;
         }
         __syncthreads();
-        // ---- 1. which members already know which (see join_kernel) --------------------------
+        EF_T(0);
+        // ---- 1. which members already know which (see join_kernel), eight entries in flight per lane
         for (int f0 = lane; f0 < m * K; f0 += 8 * EF_WAVE) {
             u64 en[8];
             int rr[8];
@@ -2016,22 +2043,32 @@ join_tile_kernel(const float *__restrict__ X, const float *__restrict__ norms, i
                 rr[q] = (int)(((u64)(u32)min(f, m * K - 1) * k_magic) >> 32);
                 en[q] = f < m * K ? graph[(size_t)lds.uid[rr[q]] * K + (f - rr[q] * K)] : ~0ULL;
             }
+            u64 bk[8];      // the ids' own buckets: these reads do not depend on one another
+#pragma unroll
+            for (int q = 0; q < 8; ++q)
+                bk[q] = *reinterpret_cast<const u64 *>(lds.hkey + 2 * (int)(((u32)ef_id(en[q]) * 0x9E3779B1u) >> hshift));
 #pragma unroll
             for (int q = 0; q < 8; ++q) {
                 if (ef_is_empty(en[q])) continue;
                 const int id = ef_id(en[q]);
-                int h = (int)(((u32)id * 0x9E3779B1u) >> hshift);
-                for (int k = lds.hkey[h]; k != -1; k = lds.hkey[h]) {
-                    if (k == id) {
-                        const int c = lds.hidx[h];
-                        atomicOr(&lds.known[rr[q] * kw + (c >> 5)], 1u << (c & 31));
-                        break;
-                    }
-                    h = (h + 1) & (hslots - 1);
+                int b = (int)(((u32)id * 0x9E3779B1u) >> hshift), slot = -1;
+                u64 two = bk[q];
+                for (;;) {
+                    const int k0 = (int)(u32)two, k1 = (int)(two >> 32);
+                    if (k0 == id) slot = 2 * b;
+                    else if (k1 == id) slot = 2 * b + 1;
+                    if (slot >= 0 || k0 == -1 || k1 == -1) break;
+                    b = (b + 1) & (n_buckets - 1);      // a full bucket without the id: it may have moved on
+                    two = *reinterpret_cast<const u64 *>(lds.hkey + 2 * b);
+                }
+                if (slot >= 0) {
+                    const int c = lds.hidx[slot];
+                    atomicOr(&lds.known[rr[q] * kw + (c >> 5)], 1u << (c & 31));
                 }
             }
         }
         __syncthreads();
+        EF_T(1);
         // ---- 2. tile pairs ---------------------------------------------------------------------
         const int nbr = (m_new + 15) >> 4, nbc = (m + 15) >> 4;
         for (int bi = 0; bi < nbr; ++bi) {
@@ -2136,10 +2173,17 @@ join_tile_kernel(const float *__restrict__ X, const float *__restrict__ norms, i
                 __syncthreads();      // the survivor list is free again
             }
         }
+        EF_T(2);
         if (q_fill >= q_cap / 2) drain();
         __syncthreads();
+        EF_T(3);
     }
     drain();
+#ifdef EF_PROF
+    if (blockIdx.x == 7 && lane == 0 && n_joins)
+        printf("tile cap %d joins %d  cycles/join: setup %lld scan %lld tiles %lld drain %lld  proposals/join %.1f\n", cap, n_joins,
+               pc[0] / n_joins, pc[1] / n_joins, pc[2] / n_joins, pc[3] / n_joins, (double)n_prop / n_joins);
+#endif
     updates = ef_wave_sum_i32(updates);
     if (lane == 0) upd_block[blockIdx.x] = updates;
 }
