@@ -1427,7 +1427,7 @@ __global__ void __launch_bounds__(512) join_kernel(const float *__restrict__ X, 
 #pragma unroll
             for (int q = 0; q < 8; ++q) {
                 const int f = f0 + q * nthr;
-                rr[q] = (int)(((u64)(u32)min(f, m * K - 1) * k_magic) >> 32);
+                rr[q] = K == 1 ? min(f, m * K - 1) : (int)(((u64)(u32)min(f, m * K - 1) * k_magic) >> 32);
                 en[q] = f < m * K ? graph[(size_t)lds.uid[rr[q]] * K + (f - rr[q] * K)] : ~0ULL;
             }
 #pragma unroll
@@ -1939,13 +1939,12 @@ struct TileLds {
     u32 *thr;          // [cap] threshold bits (exact test)
     float *nf, *tf;    // [cap] |x|^2 (1 - margin), threshold * scale (filter)
     u32 *known;        // [cap][known_words(cap)]
-    int *hkey;         // [tile_slots(cap)] ids in buckets of two slots, -1 = free
-    int *hidx;         // [tile_slots(cap)] the place in uid of the id in that slot
+    int2 *hslot;       // [tile_slots(cap)] (id, its place in uid) in buckets of two slots, id -1 = free
     u32 *surv;         // [256] surviving pairs of the tile pair in hand
     Proposal *queue;   // [q_cap]
 };
 // The table that maps an id to its place in the list: buckets of two slots, a quarter full at
-// most, so that nearly every look-up is one 8-byte read of the id's own bucket (ten thousand
+// most, so that nearly every look-up is one 16-byte read of the id's own bucket (ten thousand
 // look-ups per join: a probe loop whose length differs from lane to lane was most of a join).
 // An id goes to the first free slot of its bucket, else of the buckets after it; a look-up
 // therefore ends at the first bucket with a free slot.
@@ -1969,17 +1968,19 @@ __device__ inline TileLds tile_lds_carve(float *smem, int cap)
     l.nf = (float *)(l.thr + c4);
     l.tf = l.nf + c4;
     l.known = (u32 *)(l.tf + c4);
-    l.hkey = (int *)(l.known + align4(cap * known_words(cap)));
-    l.hidx = l.hkey + tile_slots(cap);
-    l.surv = (u32 *)(l.hidx + tile_slots(cap));
+    l.hslot = (int2 *)(l.known + align4(cap * known_words(cap)));
+    l.surv = (u32 *)(l.hslot + tile_slots(cap));
     l.queue = (Proposal *)(l.surv + 256);
     return l;
 }
 
 template <bool LONG_ROWS>      // graph rows of even length, 16-byte aligned, more than 16 entries: sixteen lanes per proposal
-__global__ void __launch_bounds__(EF_WAVE) __attribute__((amdgpu_waves_per_eu(3)))
+#ifndef EF_TILE_WAVES
+#define EF_TILE_WAVES 3
+#endif
+__global__ void __launch_bounds__(EF_WAVE) __attribute__((amdgpu_waves_per_eu(EF_TILE_WAVES)))
 join_tile_kernel(const float *__restrict__ X, const float *__restrict__ norms, int d, int K, u32 k_magic,
-                 const int *__restrict__ work, const int *__restrict__ work_count, int cap, int q_cap,
+                 u32 kq_magic, const int *__restrict__ gid, const int *__restrict__ work, const int *__restrict__ work_count, int cap, int q_cap,
                  float margin_rel, float thr_scale, const int *__restrict__ ulist,
                  const int2 *__restrict__ ucount, int ucap, u64 *graph, u32 *worst,
                  int *__restrict__ upd_block)
@@ -2008,7 +2009,11 @@ join_tile_kernel(const float *__restrict__ X, const float *__restrict__ norms, i
         q_fill = 0;
         __syncthreads();
     };
-    auto is_known = [&](int row, int col) { return (lds.known[row * kw + (col >> 5)] >> (col & 31)) & 1u; };
+    // The table of known pairs is kept by column: bit r of the words of member c says that row r
+    // holds (or held) c.  The lanes of a wave scan the same row or two at a time, and the ids of a
+    // row are distinct: their hits then fall into different words (by row, they would all be
+    // or-ed into the same few words, one after the other).
+    auto is_known = [&](int row, int col) { return (lds.known[col * kw + (row >> 5)] >> (row & 31)) & 1u; };
     for (int w = blockIdx.x; w < count; w += gridDim.x) {
         const int i = work[w];
         const int2 mc = ucount[i];
@@ -2018,7 +2023,7 @@ join_tile_kernel(const float *__restrict__ X, const float *__restrict__ norms, i
 #endif
         // ---- 0. ids, thresholds, norms; the members' places by id ---------------------------
         for (int f = lane; f < m * kw; f += EF_WAVE) lds.known[f] = 0u;
-        for (int f = lane; f < hslots; f += EF_WAVE) lds.hkey[f] = -1;
+        for (int f = lane; f < hslots; f += EF_WAVE) lds.hslot[f].x = -1;
         __syncthreads();
         for (int r = lane; r < m; r += EF_WAVE) {
             const int id = ulist[(size_t)i * ucap + r];
@@ -2028,42 +2033,69 @@ join_tile_kernel(const float *__restrict__ X, const float *__restrict__ norms, i
             lds.tf[r] = __uint_as_float(t) * thr_scale;
             lds.nf[r] = norms[id] * (1.0f - margin_rel);
             int h = 2 * (int)(((u32)id * 0x9E3779B1u) >> hshift);      // ids of a list are distinct: every one finds a slot
-            while (atomicCAS(&lds.hkey[h], -1, id) != -1) h = (h + 1) & (hslots - 1);
-            lds.hidx[h] = r;
+            while (atomicCAS(&lds.hslot[h].x, -1, id) != -1) h = (h + 1) & (hslots - 1);
+            lds.hslot[h].y = r;
         }
         __syncthreads();
         EF_T(0);
-        // ---- 1. which members already know which (see join_kernel), eight entries in flight per lane
-        for (int f0 = lane; f0 < m * K; f0 += 8 * EF_WAVE) {
-            u64 en[8];
-            int rr[8];
-#pragma unroll
-            for (int q = 0; q < 8; ++q) {
-                const int f = f0 + q * EF_WAVE;
-                rr[q] = (int)(((u64)(u32)min(f, m * K - 1) * k_magic) >> 32);
-                en[q] = f < m * K ? graph[(size_t)lds.uid[rr[q]] * K + (f - rr[q] * K)] : ~0ULL;
+        // ---- 1. which members already know which (see join_kernel): the members' rows of ids, sixteen
+        //         loads in flight per lane, four ids per load where rows allow it -----------------
+        // `two`: the id's own bucket, read beforehand (several look-ups are issued together: one
+        // after the other, each would wait out its own LDS round trips)
+        auto note = [&](int row, int id, int4 two) {
+            if (id < 0) return;
+            int c = two.x == id ? two.y : (two.z == id ? two.w : -1);
+            if (c < 0 && two.x != -1 && two.z != -1) {      // a full bucket without the id: it may have moved on (rare)
+                int b = (int)(((u32)id * 0x9E3779B1u) >> hshift);
+                do {
+                    b = (b + 1) & (n_buckets - 1);
+                    two = *reinterpret_cast<const int4 *>(lds.hslot + 2 * b);
+                    c = two.x == id ? two.y : (two.z == id ? two.w : -1);
+                } while (c < 0 && two.x != -1 && two.z != -1);
             }
-            u64 bk[8];      // the ids' own buckets: these reads do not depend on one another
+            if (c >= 0) atomicOr(&lds.known[c * kw + (row >> 5)], 1u << (row & 31));
+        };
+        auto bucket_of = [&](int id) {      // (an id of -1 reads some bucket and is dropped afterwards)
+            return *reinterpret_cast<const int4 *>(lds.hslot + 2 * (int)(((u32)id * 0x9E3779B1u) >> hshift));
+        };
+        if ((K & 3) == 0 && ((uintptr_t)gid & 15) == 0) {
+            const int kq = K >> 2, total = m * kq;
+            for (int f0 = lane; f0 < total; f0 += 16 * EF_WAVE) {
+                int4 four[16];
+                int rr[16];
 #pragma unroll
-            for (int q = 0; q < 8; ++q)
-                bk[q] = *reinterpret_cast<const u64 *>(lds.hkey + 2 * (int)(((u32)ef_id(en[q]) * 0x9E3779B1u) >> hshift));
-#pragma unroll
-            for (int q = 0; q < 8; ++q) {
-                if (ef_is_empty(en[q])) continue;
-                const int id = ef_id(en[q]);
-                int b = (int)(((u32)id * 0x9E3779B1u) >> hshift), slot = -1;
-                u64 two = bk[q];
-                for (;;) {
-                    const int k0 = (int)(u32)two, k1 = (int)(two >> 32);
-                    if (k0 == id) slot = 2 * b;
-                    else if (k1 == id) slot = 2 * b + 1;
-                    if (slot >= 0 || k0 == -1 || k1 == -1) break;
-                    b = (b + 1) & (n_buckets - 1);      // a full bucket without the id: it may have moved on
-                    two = *reinterpret_cast<const u64 *>(lds.hkey + 2 * b);
+                for (int q = 0; q < 16; ++q) {
+                    const int f = f0 + q * EF_WAVE;
+                    rr[q] = kq == 1 ? min(f, total - 1) : (int)(((u64)(u32)min(f, total - 1) * kq_magic) >> 32);
+                    four[q] = f < total ? *reinterpret_cast<const int4 *>(gid + (size_t)lds.uid[rr[q]] * K + 4 * (f - rr[q] * kq))
+                                        : make_int4(-1, -1, -1, -1);
                 }
-                if (slot >= 0) {
-                    const int c = lds.hidx[slot];
-                    atomicOr(&lds.known[rr[q] * kw + (c >> 5)], 1u << (c & 31));
+#pragma unroll
+                for (int q = 0; q < 16; ++q) {
+                    const int id4[4] = {four[q].x, four[q].y, four[q].z, four[q].w};
+                    int4 bk[4];
+#pragma unroll
+                    for (int t = 0; t < 4; ++t) bk[t] = bucket_of(id4[t]);
+#pragma unroll
+                    for (int t = 0; t < 4; ++t) note(rr[q], id4[t], bk[t]);
+                }
+            }
+        } else {
+            for (int f0 = lane; f0 < m * K; f0 += 8 * EF_WAVE) {
+                int one[8], rr[8];
+#pragma unroll
+                for (int q = 0; q < 8; ++q) {
+                    const int f = f0 + q * EF_WAVE;
+                    rr[q] = K == 1 ? min(f, m * K - 1) : (int)(((u64)(u32)min(f, m * K - 1) * k_magic) >> 32);
+                    one[q] = f < m * K ? gid[(size_t)lds.uid[rr[q]] * K + (f - rr[q] * K)] : -1;
+                }
+#pragma unroll
+                for (int q0 = 0; q0 < 8; q0 += 4) {
+                    int4 bk[4];
+#pragma unroll
+                    for (int t = 0; t < 4; ++t) bk[t] = bucket_of(one[q0 + t]);
+#pragma unroll
+                    for (int t = 0; t < 4; ++t) note(rr[q0 + t], one[q0 + t], bk[t]);
                 }
             }
         }
@@ -2106,7 +2138,7 @@ join_tile_kernel(const float *__restrict__ X, const float *__restrict__ norms, i
                 // ---- filter: the lane holds G[a = 16 bi + 4 g + k][b = 16 bj + r16] ---------------
                 const int b = 16 * bj + r16, bc = min(b, m - 1);
                 const float nfb = lds.nf[bc], tfb = lds.tf[bc];
-                const u32 known_b = lds.known[bc * kw + (bi >> 1)] >> (16 * (bi & 1));      // row b on rows 16 bi ..
+                const u32 knows_b = lds.known[bc * kw + (bi >> 1)] >> (16 * (bi & 1));      // which of rows 16 bi .. know b
                 int n_surv = 0;
 #pragma unroll
                 for (int k = 0; k < 4; ++k) {
@@ -2114,8 +2146,8 @@ join_tile_kernel(const float *__restrict__ X, const float *__restrict__ norms, i
                     const float low = __builtin_fmaf(-2.0f, acc0[k] + acc1[k], lds.nf[ac] + nfb);
                     const bool valid = a < m_new && b < m && a < b;
                     // wanted by a row that may still accept the pair and does not know it yet
-                    const bool keep = valid && ((low <= lds.tf[ac] && !is_known(ac, bc)) ||
-                                                (low <= tfb && !((known_b >> (4 * g + k)) & 1u)));
+                    const bool keep = valid && ((low <= lds.tf[ac] && !((knows_b >> (4 * g + k)) & 1u)) ||
+                                                (low <= tfb && !is_known(bc, ac)));
                     const u64 kept = __ballot(keep);
                     if (keep) lds.surv[n_surv + lanes_below(kept)] = (u32)(4 * g + k) | ((u32)r16 << 8);
                     n_surv += __popcll(kept);
@@ -2186,6 +2218,18 @@ join_tile_kernel(const float *__restrict__ X, const float *__restrict__ norms, i
 #endif
     updates = ef_wave_sum_i32(updates);
     if (lane == 0) upd_block[blockIdx.x] = updates;
+}
+
+// The ids of all graph entries (-1 for an empty slot), written once per iteration after the
+// sampling: the tile join looks for pairs that already know each other in these, at half the
+// bytes of the entries themselves.  Rows as they were when the iteration began: an id that is or
+// was in a row is all the table of known pairs asks for.
+__global__ void __launch_bounds__(kBlock) graph_ids_kernel(const u64 *__restrict__ graph, size_t total, int *__restrict__ gid)
+{
+    for (size_t i = (size_t)blockIdx.x * kBlock + threadIdx.x; i < total; i += (size_t)gridDim.x * kBlock) {
+        const u64 e = graph[i];
+        gid[i] = ef_is_empty(e) ? -1 : ef_id(e);
+    }
 }
 
 // squared norms in float32 (only the join's filter uses them; any summation order will do)
@@ -2343,6 +2387,7 @@ struct NndWs {
     void *overflow;
     u64 *rnew, *rold, *list_max, *active, *fresh;
     u32 *offer_runs, *run_table;
+    int *gid;      // ids of all graph entries (joins of more than 32 vectors)
     long long *part;
     u32 *worst;
     float *norms;
@@ -2387,6 +2432,7 @@ NndWs carve_nnd(void *ws, int64_t n, int K, int L)
     w.fresh = (u64 *)take(8);
     w.worst = (u32 *)take((size_t)n * 4);
     w.norms = (float *)take((size_t)n * 4);
+    w.gid = (int *)take(K + 2 * L > 32 ? (size_t)n * K * 4 : 0);
     w.bytes = off;
     return w;
 }
@@ -2792,6 +2838,8 @@ int nndescent_run(const float *X, int64_t n, int32_t d, int32_t k, efanna_entry 
             EF_HIP_CHECK(hipEventRecord(ev[5 * it + 2], st));
         }
         if (ev) EF_HIP_CHECK(hipEventRecord(ev[5 * it + 3], st));
+        if (tiles && max_rows > rows1)
+            graph_ids_kernel<<<min(grid_for((size_t)n * K, kBlock), 256 * 64), kBlock, 0, st>>>(graph, (size_t)n * K, w.gid);
 #define EF_JOIN_LARGE(WIDE, C)                                                                     \
     join_kernel<WIDE><<<large[C].grid, large[C].threads, large[C].lds, st>>>(                      \
         X, w.norms, d, dpad, stride, q4_magic_for(d), K, (u32)(((1ULL << 32) + K - 1) / K),       \
@@ -2804,18 +2852,19 @@ int nndescent_run(const float *X, int64_t n, int32_t d, int32_t k, efanna_entry 
                 const int tq = 256;
                 const size_t tl = tile_lds_bytes(jc.bound[c], tq);
                 long per_cu = (long)(kLdsLimit / tl);
-                per_cu = per_cu > 12 ? 12 : (per_cu < 1 ? 1 : per_cu);      // three waves per SIMD
+                per_cu = per_cu > 4 * EF_TILE_WAVES ? 4 * EF_TILE_WAVES : (per_cu < 1 ? 1 : per_cu);      // by registers
                 const int tgrid = (int)(256 * per_cu * 4);
                 int *upd = w.upd_block + 2 * reg_grid + (c - 2) * kMaxLargeGrid;
                 const u32 km = (u32)(((1ULL << 32) + K - 1) / K);
+                const u32 kqm = K >= 4 ? (u32)(((1ULL << 32) + (K >> 2) - 1) / (K >> 2)) : 0u;
                 if (K > 16 && (K & 1) == 0 && ((uintptr_t)graph & 15) == 0)
                     join_tile_kernel<true><<<tgrid, EF_WAVE, tl, st>>>(
-                        X, w.norms, d, K, km, w.work + (size_t)c * n, w.work_count + c, jc.bound[c], tq, margin_rel,
-                        thr_scale, w.ulist, w.ucount, max_rows, graph, w.worst, upd);
+                        X, w.norms, d, K, km, kqm, w.gid, w.work + (size_t)c * n, w.work_count + c, jc.bound[c], tq,
+                        margin_rel, thr_scale, w.ulist, w.ucount, max_rows, graph, w.worst, upd);
                 else
                     join_tile_kernel<false><<<tgrid, EF_WAVE, tl, st>>>(
-                        X, w.norms, d, K, km, w.work + (size_t)c * n, w.work_count + c, jc.bound[c], tq, margin_rel,
-                        thr_scale, w.ulist, w.ucount, max_rows, graph, w.worst, upd);
+                        X, w.norms, d, K, km, kqm, w.gid, w.work + (size_t)c * n, w.work_count + c, jc.bound[c], tq,
+                        margin_rel, thr_scale, w.ulist, w.ucount, max_rows, graph, w.worst, upd);
             } else if (K >= 2 * EF_WIDE_PIECES) EF_JOIN_LARGE(true, c);
             else EF_JOIN_LARGE(false, c);
         }
