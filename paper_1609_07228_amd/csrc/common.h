@@ -416,7 +416,9 @@ __device__ inline void ef_load_pieces_at(const void *p0, const void *p1, const v
 // group fetches 256 contiguous bytes per load: a quarter of the memory transactions that a lane
 // reading the whole row alone needs, and one round trip for rows of up to 128 entries.  The
 // row must be 16-byte aligned and of even length; the group's lanes must all be active.
-__device__ inline bool ef_bounded_insert_g16(u64 *list, int cap, u64 key, int ignore, u64 *new_max, int gl)
+// slot (or null): receives the slot the key went into.
+__device__ inline bool ef_bounded_insert_g16(u64 *list, int cap, u64 key, int ignore, u64 *new_max, int gl,
+                                             int *slot = nullptr)
 {
     const u64 kcmp = key >> ignore;
     const int np = cap >> 1;
@@ -468,6 +470,7 @@ __device__ inline bool ef_bounded_insert_g16(u64 *list, int cap, u64 key, int ig
         seen = __shfl(seen, 0, 16);
         if (seen == mx) {
             *new_max = key > mx2 ? key : mx2;
+            if (slot) *slot = ms;
             return true;
         }
     }

@@ -149,16 +149,20 @@ __device__ inline int drain_queue(const Proposal *queue, int count, u64 *graph, 
 
 // The same for long rows (even length, 16-byte aligned): a group of sixteen threads per
 // proposal (nthr a multiple of 16; all threads of the block call this together).
+// gid (or null): the mirror of the rows' ids (graph_ids_kernel), kept up to date with the insertions.
 __device__ inline int drain_queue_g16(const Proposal *queue, int count, u64 *graph, u32 *worst, int K,
-                                      int tid, int nthr)
+                                      int tid, int nthr, int *gid = nullptr)
 {
     int updates = 0;
     const int gl = tid & 15;
     for (int e = tid >> 4; e < count; e += nthr >> 4) {
         const Proposal p = queue[e];
         u64 new_max;
-        if (ef_bounded_insert_g16(graph + (size_t)p.target * K, K, p.key, 1, &new_max, gl) && gl == 0) {
+        int slot = 0;
+        if (ef_bounded_insert_g16(graph + (size_t)p.target * K, K, p.key, 1, &new_max, gl, &slot) && gl == 0) {
             atomicMin(worst + p.target, ef_dist_bits(new_max));
+            // (a plain store: whatever order stores to a slot land in, the slot names an id that was in the row)
+            if (gid) gid[(size_t)p.target * K + slot] = ef_id(p.key);
             ++updates;
         }
     }
@@ -1980,7 +1984,7 @@ template <bool LONG_ROWS>      // graph rows of even length, 16-byte aligned, mo
 #endif
 __global__ void __launch_bounds__(EF_WAVE) __attribute__((amdgpu_waves_per_eu(EF_TILE_WAVES)))
 join_tile_kernel(const float *__restrict__ X, const float *__restrict__ norms, int d, int K, u32 k_magic,
-                 u32 kq_magic, const int *__restrict__ gid, const int *__restrict__ work, const int *__restrict__ work_count, int cap, int q_cap,
+                 u32 kq_magic, int *gid, const int *__restrict__ work, const int *__restrict__ work_count, int cap, int q_cap,
                  float margin_rel, float thr_scale, const int *__restrict__ ulist,
                  const int2 *__restrict__ ucount, int ucap, u64 *graph, u32 *worst,
                  int *__restrict__ upd_block)
@@ -2004,7 +2008,7 @@ join_tile_kernel(const float *__restrict__ X, const float *__restrict__ norms, i
 #ifdef EF_PROF
         n_prop += q_fill;
 #endif
-        updates += LONG_ROWS ? drain_queue_g16(lds.queue, q_fill, graph, worst, K, lane, EF_WAVE)
+        updates += LONG_ROWS ? drain_queue_g16(lds.queue, q_fill, graph, worst, K, lane, EF_WAVE, gid)
                              : drain_queue<false, false>(lds.queue, q_fill, graph, worst, K, lane, EF_WAVE);
         q_fill = 0;
         __syncthreads();
@@ -2222,8 +2226,8 @@ join_tile_kernel(const float *__restrict__ X, const float *__restrict__ norms, i
 
 // The ids of all graph entries (-1 for an empty slot), written once per iteration after the
 // sampling: the tile join looks for pairs that already know each other in these, at half the
-// bytes of the entries themselves.  Rows as they were when the iteration began: an id that is or
-// was in a row is all the table of known pairs asks for.
+// bytes of the entries themselves, and notes the ids it inserts there as well.  An id that is or
+// was in a row is all the table of known pairs asks for: the mirror may lag behind the rows.
 __global__ void __launch_bounds__(kBlock) graph_ids_kernel(const u64 *__restrict__ graph, size_t total, int *__restrict__ gid)
 {
     for (size_t i = (size_t)blockIdx.x * kBlock + threadIdx.x; i < total; i += (size_t)gridDim.x * kBlock) {
