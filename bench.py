@@ -209,6 +209,11 @@ def main():
                          "the tree-built initial graph and from a seeded random graph (the starting point of "
                          "plain NN-descent) and add an `ablation_init` object: time and recall after every "
                          "iteration of both")
+    ap.add_argument("--ablation-marking", type=int, default=0, metavar="ITERS",
+                    help="after the build, run NN-descent one iteration at a time for ITERS iterations with fresh "
+                         "entries always marked new (the default) and with the literal marking of Alg. 4 (what a new "
+                         "and an old member insert is marked old) and add an `ablation_marking` object: time, "
+                         "recall and pairs evaluated after every iteration of both")
     ap.add_argument("--conquer-depth", type=int, default=None,
                     help="walk the conquer step of Alg. 3 up to this depth (default: stop at the leaves, "
                          "the configuration the metric is quoted on); distance evaluations above the "
@@ -350,6 +355,35 @@ def main():
             curves[label] = descend(g, (time.perf_counter() - a0) * 1e3)
         ablation = {"recall_rows": int(rows.shape[0]), **curves}
 
+    marking = None
+    if args.ablation_marking > 0:
+        rows_m = torch.from_numpy(synth.sample_rows(n, max(1000, args.recall_rows))).to(dev)
+        truth_m = exact_knn_torch(Xd, rows_m, K)
+
+        def recall_m(g):
+            got = efanna.efanna_get_graph(g)[0][rows_m].cpu().numpy()
+            return sum(np.intersect1d(a[a >= 0], b).shape[0] for a, b in zip(got, truth_m)) / float(truth_m.size)
+
+        marking = {"recall_rows": int(rows_m.shape[0])}
+        for label, cross_old in (("fresh_entries_new", False), ("literal_new_x_old_marked_old", True)):
+            curve = []
+            for rep_ in range(2):      # the first round warms up
+                trees = efanna.efanna_build_trees(Xd, T, S, synth.ALGO_SEED, max_leaves=max_leaves, workspace=ws_tree)
+                g = efanna.efanna_init_graph(Xd, trees[0], trees[1], trees[2], S, K, workspace=ws_init)
+                curve, ms, pairs = [], 0.0, 0
+                for it in range(args.ablation_marking):
+                    torch.cuda.synchronize()
+                    a0 = time.perf_counter()
+                    stt = efanna.efanna_nndescent(Xd, g, 1, L, synth.ALGO_SEED, first_iter=it, workspace=ws_nnd,
+                                                  cross_old=cross_old)
+                    torch.cuda.synchronize()
+                    ms += (time.perf_counter() - a0) * 1e3
+                    pairs += int(stt[0, 0].item())
+                    if rep_ == 1:
+                        curve.append({"iterations": it + 1, "nndescent_ms": ms, "pairs_evaluated": pairs,
+                                      "recall_at_K": recall_m(g)})
+            marking[label] = curve
+
     # the other configurations: a build each on the same GPU, after the headline's buffers are gone
     others_arg = args.others
     if others_arg is None:
@@ -419,6 +453,8 @@ def main():
         out["search"] = search
     if ablation is not None:
         out["ablation_init"] = ablation
+    if marking is not None:
+        out["ablation_marking"] = marking
     print(json.dumps(out))
 
 

@@ -167,6 +167,12 @@ int efanna_init_graph(const float *X, int64_t n, int32_t d, const int32_t *perm,
  *          that leaves fewer than delta*n*k entries carrying the new mark (fresh entries that
  *          were still in their row when the iteration ended); the call then synchronises the
  *          stream after every iteration.
+ * cross_old 0: every fresh entry is marked new.  1: the literal marking of Alg. 4's second inner
+ *          loop - an entry inserted by a pair of a new and an old member of a join is marked old
+ *          (it will not be sampled as new), one inserted by a pair of two new members is marked
+ *          new.  To make the outcome independent of scheduling the joins then run twice per
+ *          iteration: all pairs of two new members first, so that an entry offered by both kinds
+ *          of pair is new.  Fewer joins later, lower accuracy: an ablation, not the default.
  * iters_done [host] out or NULL: iterations carried out.
  * graph    [device] in/out.  The call may be repeated to continue refining: pass the
  *          number of iterations already done as first_iter so that the hash stream
@@ -178,7 +184,8 @@ int efanna_init_graph(const float *X, int64_t n, int32_t d, const int32_t *perm,
  * phase_ms [host] out or NULL: iters*4 float: milliseconds of {sampling + reverse lists
  *          + join lists, joins of at most 16 vectors, joins of 17..32 vectors, larger
  *          joins} per iteration, from HIP events on `stream`.  When given, the call
- *          synchronises the stream before returning.
+ *          synchronises the stream before returning.  (With cross_old the split by join size
+ *          covers the second pass only; the first pass is booked under the smallest joins.)
  * Asynchronous on `stream` otherwise.  Limits: k <= EFANNA_MAX_K, sample_L <= EFANNA_MAX_SAMPLE,
  * if k + 2*sample_L > 32 (or rows are not 16-byte aligned), k + 2*sample_L rows of d floats
  * must fit the 160 KB LDS.
@@ -187,7 +194,7 @@ size_t efanna_nndescent_workspace_bytes(int64_t n, int32_t k, int32_t sample_L);
 
 int efanna_nndescent(const float *X, int64_t n, int32_t d, int32_t k, efanna_entry *graph,
                      int32_t iters, int32_t sample_L, uint64_t seed, int32_t first_iter,
-                     float delta, int32_t *iters_done,
+                     float delta, int32_t cross_old, int32_t *iters_done,
                      uint64_t *stats, float *phase_ms, void *ws, size_t ws_bytes, void *stream);
 
 /* The same refinement for callers that cannot allocate device memory and have no workspace

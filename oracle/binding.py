@@ -64,6 +64,10 @@ def _load():
         lib.oracle_nndescent_until.argtypes = [C.c_void_p, C.c_int64, C.c_int32, C.c_int32, C.c_void_p,
                                                C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_uint64,
                                                C.c_int32, C.c_void_p, C.c_double, C.c_void_p]
+        lib.oracle_nndescent_opts.restype = C.c_int
+        lib.oracle_nndescent_opts.argtypes = [C.c_void_p, C.c_int64, C.c_int32, C.c_int32, C.c_void_p,
+                                              C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_uint64,
+                                              C.c_int32, C.c_void_p, C.c_double, C.c_void_p, C.c_int32]
         lib.oracle_search.restype = C.c_int
         lib.oracle_search.argtypes = [C.c_void_p, C.c_int64, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p,
                                       C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_int32, C.c_void_p,
@@ -215,11 +219,12 @@ def search(X, perm, leaf_off, n_leaves, nodes, S: int, graph_ids, queries, K: in
 
 
 def nndescent(X, ids, dists, flags, iters: int, L: int, seed: int, iter0: int = 0,
-              delta: float = 0.0):
+              delta: float = 0.0, cross_old: bool = False):
     """Alg. 4.  Returns new (ids, dists, flags) and stats [iters, 2] =
     (distance evaluations, accepted insertions) per iteration.  With delta > 0 (early
     termination) a fifth value follows: the number of iterations carried out, and stats
-    has that many rows."""
+    has that many rows.  cross_old: entries inserted by a pair of a new and an old member are
+    marked old (the literal marking of Alg. 4), pairs of two new members being inserted first."""
     X = _f32(X)
     n, d = X.shape
     K = ids.shape[1]
@@ -228,8 +233,8 @@ def nndescent(X, ids, dists, flags, iters: int, L: int, seed: int, iter0: int = 
     flags = np.array(flags, dtype=np.uint8, order="C")
     stats = np.zeros((max(iters, 1), 2), dtype=np.uint64)
     done = C.c_int32(0)
-    rc = _load().oracle_nndescent_until(_p(X), n, d, K, _p(ids), _p(dists), _p(flags), iters, L, seed,
-                                        iter0, _p(stats), float(delta), C.byref(done))
+    rc = _load().oracle_nndescent_opts(_p(X), n, d, K, _p(ids), _p(dists), _p(flags), iters, L, seed,
+                                       iter0, _p(stats), float(delta), C.byref(done), 1 if cross_old else 0)
     if rc != 0:
         raise ValueError(f"oracle_nndescent failed: {rc}")
     if delta > 0.0:

@@ -236,7 +236,7 @@ static int entry_less(float da, int32_t ia, float db, int32_t ib)
 
 /* pool := K smallest of pool U {(dist,id,new)}; an id already present is kept
  * as it is.  Returns 1 if the entry went in. */
-static int pool_insert(entry *pool, int32_t *cnt, int32_t K, float dist, int32_t id)
+static int pool_insert_marked(entry *pool, int32_t *cnt, int32_t K, float dist, int32_t id, uint8_t is_new)
 {
     for (int32_t s = 0; s < *cnt; ++s)
         if (pool[s].id == id) return 0;
@@ -248,8 +248,13 @@ static int pool_insert(entry *pool, int32_t *cnt, int32_t K, float dist, int32_t
     }
     pool[s].dist = dist;
     pool[s].id = id;
-    pool[s].is_new = 1;
+    pool[s].is_new = is_new;
     return 1;
+}
+
+static int pool_insert(entry *pool, int32_t *cnt, int32_t K, float dist, int32_t id)
+{
+    return pool_insert_marked(pool, cnt, K, dist, id, 1);
 }
 
 static void pools_load(entry *pool, int32_t *cnt, int64_t n, int32_t K, const int32_t *ids,
@@ -458,9 +463,28 @@ static int32_t sorted_union(const int32_t *a, int32_t na, const int32_t *b, int3
  * leaves fewer than delta*n*K entries carrying the new mark, i.e. fresh entries that were
  * still in their pool when the iteration ended.  iters_done (may be NULL) receives the
  * number of iterations carried out. */
+/* cross_old != 0: the literal marking of Alg. 4's second inner loop (an entry that a pair of a
+ * new and an old member inserts is marked old, one that a pair of two new members inserts is
+ * marked new).  Which of the two an entry gets when both kinds of pair offer it in the same
+ * iteration depends on the order of insertion in the listing; here the pairs of two new members
+ * of all joins are inserted first, then the others, so that the new mark wins. */
+int oracle_nndescent_opts(const float *X, int64_t n, int32_t d, int32_t K, int32_t *ids,
+                          float *dists, uint8_t *flags, int32_t iters, int32_t L, uint64_t seed,
+                          int32_t iter0, uint64_t *stats, double delta, int32_t *iters_done,
+                          int32_t cross_old);
+
 int oracle_nndescent_until(const float *X, int64_t n, int32_t d, int32_t K, int32_t *ids,
                            float *dists, uint8_t *flags, int32_t iters, int32_t L, uint64_t seed,
                            int32_t iter0, uint64_t *stats, double delta, int32_t *iters_done)
+{
+    return oracle_nndescent_opts(X, n, d, K, ids, dists, flags, iters, L, seed, iter0, stats, delta,
+                                 iters_done, 0);
+}
+
+int oracle_nndescent_opts(const float *X, int64_t n, int32_t d, int32_t K, int32_t *ids,
+                          float *dists, uint8_t *flags, int32_t iters, int32_t L, uint64_t seed,
+                          int32_t iter0, uint64_t *stats, double delta, int32_t *iters_done,
+                          int32_t cross_old)
 {
     if (!X || !ids || !dists || !flags || n < 2 || K < 1 || L < 1 || iters < 0) return -1;
     if (iters_done) *iters_done = 0;
@@ -504,6 +528,8 @@ int oracle_nndescent_until(const float *X, int64_t n, int32_t d, int32_t K, int3
         /* local join: every unordered pair inside U_new and every pair of
          * U_new x U_old is evaluated once and proposed to both end points. */
         uint64_t evals = 0, updates = 0;
+        /* one pass over all joins, or (cross_old) two: pairs inside U_new, then U_new x U_old */
+        for (int32_t pass = 0; pass < (cross_old ? 2 : 1); ++pass)
 #pragma omp parallel reduction(+ : evals, updates)
         {
             int32_t *un = (int32_t *)malloc((size_t)2 * L * sizeof(int32_t));
@@ -518,19 +544,22 @@ int oracle_nndescent_until(const float *X, int64_t n, int32_t d, int32_t K, int3
                         uo[n_old++] = uo[s];
                 for (int32_t a = 0; a < n_new; ++a) {
                     int32_t u = un[a];
-                    for (int32_t b = a + 1; b < n_new + n_old; ++b) {
+                    int32_t b_lo = cross_old && pass == 1 ? n_new : a + 1;
+                    int32_t b_hi = cross_old && pass == 0 ? n_new : n_new + n_old;
+                    uint8_t mark = !(cross_old && pass == 1);
+                    for (int32_t b = b_lo; b < b_hi; ++b) {
                         int32_t v = b < n_new ? un[b] : uo[b - n_new];
                         float dist = oracle_dist(X + (int64_t)u * d, X + (int64_t)v * d, d);
                         ++evals;
 #ifdef _OPENMP
                         omp_set_lock(&lock[u]);
 #endif
-                        updates += pool_insert(pool + (int64_t)u * K, &cnt[u], K, dist, v);
+                        updates += pool_insert_marked(pool + (int64_t)u * K, &cnt[u], K, dist, v, mark);
 #ifdef _OPENMP
                         omp_unset_lock(&lock[u]);
                         omp_set_lock(&lock[v]);
 #endif
-                        updates += pool_insert(pool + (int64_t)v * K, &cnt[v], K, dist, u);
+                        updates += pool_insert_marked(pool + (int64_t)v * K, &cnt[v], K, dist, u, mark);
 #ifdef _OPENMP
                         omp_unset_lock(&lock[v]);
 #endif

@@ -1387,10 +1387,11 @@ __global__ void __launch_bounds__(512) join_kernel(const float *__restrict__ X, 
                             const int *__restrict__ work, const int *__restrict__ work_count,
                             int cap_rows, int s_cap, int q_cap, float margin_rel, float thr_scale,
                             const int *__restrict__ ulist, const int2 *__restrict__ ucount,
-                            int ucap, u64 *graph, u32 *worst, int *__restrict__ upd_block)
+                            int ucap, u64 *graph, u32 *worst, int *__restrict__ upd_block, int mode)
 {
     extern __shared__ __align__(16) float smem[];
     const JoinLds lds = join_lds_carve(smem, cap_rows, stride, s_cap);
+    const int mark = mode != 2;      // (modes: see join_reg_kernel)
     const int tid = threadIdx.x, nthr = blockDim.x;
     const int lane = tid & (EF_WAVE - 1), wave = tid / EF_WAVE, n_waves = nthr / EF_WAVE;
     const int grp = tid >> 4, gl = tid & 15, n_grp = nthr >> 4;
@@ -1489,7 +1490,7 @@ __global__ void __launch_bounds__(512) join_kernel(const float *__restrict__ X, 
 #pragma unroll
                 for (int k = 0; k < 4; ++k) {
                     const int a = 16 * bi + 4 * g + k;
-                    if (a < b && a < m_new && b < m) {
+                    if (a < b && a < m_new && b < m && (mode == 0 || (mode == 1) == (b < m_new))) {
                         const float na = lds.nrm[a];
                         const float ta = __uint_as_float(lds.thr[a]);
                         const float sum = na + nb;
@@ -1524,12 +1525,12 @@ __global__ void __launch_bounds__(512) join_kernel(const float *__restrict__ X, 
                             const u32 db = __float_as_uint(dist);
                             if (db <= lds.thr[a] && !((lds.known[a * kw + (b >> 5)] >> (b & 31)) & 1u)) {
                                 const int slot = atomicAdd(&lds.meta[3], 1);
-                                lds.queue[slot].key = ef_pack(dist, lds.uid[b], 1);
+                                lds.queue[slot].key = ef_pack(dist, lds.uid[b], mark);
                                 lds.queue[slot].target = lds.uid[a];
                             }
                             if (db <= lds.thr[b] && !((lds.known[b * kw + (a >> 5)] >> (a & 31)) & 1u)) {
                                 const int slot = atomicAdd(&lds.meta[3], 1);
-                                lds.queue[slot].key = ef_pack(dist, lds.uid[a], 1);
+                                lds.queue[slot].key = ef_pack(dist, lds.uid[a], mark);
                                 lds.queue[slot].target = lds.uid[b];
                             }
                         }
@@ -1552,7 +1553,7 @@ __global__ void __launch_bounds__(512) join_kernel(const float *__restrict__ X, 
         if (tid == 0) block_updates += lds.meta[2];
         __syncthreads();
     }
-    if (tid == 0) upd_block[blockIdx.x] = block_updates;
+    if (tid == 0) upd_block[blockIdx.x] += block_updates;      // (zeroed once per iteration; passes add up)
 }
 
 // ---------------------------------------------------------------------------------------
@@ -1578,7 +1579,7 @@ constexpr int kFewPairs = 4;
 // offered to row a and to row b where it passes their thresholds.  All lanes of the wave call
 // this together; `fill` is the wave-uniform number of proposals queued, the new one is returned.
 __device__ inline int propose_pair(Proposal *queue, int fill, bool mine, float dist, int a, int b,
-                                   const u32 *thr, const int *uid)
+                                   const u32 *thr, const int *uid, int mark)
 {
     const u32 db = __float_as_uint(dist);
     const int ua = uid[a], ub = uid[b];
@@ -1586,13 +1587,13 @@ __device__ inline int propose_pair(Proposal *queue, int fill, bool mine, float d
     const u64 mask_a = __ballot(to_a), mask_b = __ballot(to_b);
     if (to_a) {
         Proposal &p = queue[fill + lanes_below(mask_a)];
-        p.key = ef_pack(dist, ub, 1);
+        p.key = ef_pack(dist, ub, mark);
         p.target = ua;
     }
     fill += __popcll(mask_a);
     if (to_b) {
         Proposal &p = queue[fill + lanes_below(mask_b)];
-        p.key = ef_pack(dist, ua, 1);
+        p.key = ef_pack(dist, ua, mark);
         p.target = ub;
     }
     return fill + __popcll(mask_b);
@@ -1604,8 +1605,13 @@ join_reg_kernel(const float *__restrict__ X, const float *__restrict__ norms, in
                 const int *__restrict__ work, const int *__restrict__ work_count, int q_cap,
                 float margin_rel, float thr_scale, const int *__restrict__ ulist,
                 const int2 *__restrict__ ucount, int ucap, u64 *graph, u32 *worst,
-                int *__restrict__ upd_block)
+                int *__restrict__ upd_block, int mode)
 {
+    // mode 0: every pair of the join, fresh entries marked new.  1: only pairs of two new members.
+    // 2: only pairs of a new and an old member, fresh entries marked old (the literal marking of
+    // Alg. 4's second inner loop runs the joins twice, mode 1 before mode 2).  Rows 0 .. m_new - 1
+    // of a list are its new members, so a pair (a, b), a < b, a new, is of two new members iff b is.
+    const int mark = mode != 2;
     const int K = KT ? KT : K_;
     constexpr int R = 16 * NB;                    // rows
     constexpr int S_CAP = R * (R - 1) / 2 + 8;    // every pair may survive
@@ -1644,6 +1650,7 @@ join_reg_kernel(const float *__restrict__ X, const float *__restrict__ norms, in
     for (; i >= 0; w += gridDim.x) {
         // ---- 0. the point's U_new ++ U_old (the loop ends with a barrier: LDS is free) -------
         const int m_new = c_pre.x, m = c_pre.y;
+        auto mode_ok = [&](int b) { return mode == 0 || (mode == 1) == (b < m_new); };      // b: the pair's larger row
         const int u_cur = u_pre;
         if (lane < R) {
             uid[lane] = u_cur;
@@ -1773,7 +1780,8 @@ join_reg_kernel(const float *__restrict__ X, const float *__restrict__ norms, in
             if (rotated) break;
             const int bi = q == 2 ? 1 : 0, bj = q == 0 ? 0 : 1;
             const int b = 16 * bj + r16, a0 = 16 * bi + 4 * g;
-            const int lim = b < m ? min(m_new, b) : 0;           // valid pairs: a < lim
+            // valid pairs: a < lim
+            const int lim = b >= m ? 0 : mode == 0 ? min(m_new, b) : mode == 1 ? (b < m_new ? b : 0) : (b >= m_new ? m_new : 0);
             const float nfb = nf[b], tfb = tf[b];                  // junk beyond m, masked by lim
             const float4 nfa = *reinterpret_cast<const float4 *>(nf + a0);
             const float4 tfa = *reinterpret_cast<const float4 *>(tf + a0);
@@ -1803,13 +1811,16 @@ join_reg_kernel(const float *__restrict__ X, const float *__restrict__ norms, in
                 // rotation 8 meets every pair from both ends: the lower row keeps it
                 const bool once = rot != 8 || r16 < b;
                 room();
-                q_fill = propose_pair(queue, q_fill, once && r16 < m && b < m && min(r16, b) < m_new, two[t], r16, b,
-                                      thr, uid);
+                q_fill = propose_pair(queue, q_fill,
+                                      once && r16 < m && b < m && min(r16, b) < m_new && mode_ok(max(r16, b)), two[t],
+                                      r16, b, thr, uid, mark);
                 __syncthreads();
                 if (NB > 1 && need11) {
                     room();
-                    q_fill = propose_pair(queue, q_fill, once && 16 + r16 < m && 16 + b < m && 16 + min(r16, b) < m_new,
-                                          two_b[t], 16 + r16, 16 + b, thr, uid);
+                    q_fill = propose_pair(queue, q_fill,
+                                          once && 16 + r16 < m && 16 + b < m && 16 + min(r16, b) < m_new &&
+                                              mode_ok(16 + max(r16, b)),
+                                          two_b[t], 16 + r16, 16 + b, thr, uid, mark);
                     __syncthreads();
                 }
             }
@@ -1854,7 +1865,8 @@ join_reg_kernel(const float *__restrict__ X, const float *__restrict__ norms, in
                     for (int t = 0; t < 2; ++t) {
                         const int rot = 8 * h + 2 * g + t, b = 16 + ((r16 + dirn * rot) & 15);
                         room();
-                        q_fill = propose_pair(queue, q_fill, b < m && r16 < m_new, cross[t], r16, b, thr, uid);
+                        q_fill = propose_pair(queue, q_fill, b < m && r16 < m_new && mode_ok(b), cross[t], r16, b, thr,
+                                              uid, mark);
                         __syncthreads();
                     }
                 }
@@ -1900,7 +1912,7 @@ join_reg_kernel(const float *__restrict__ X, const float *__restrict__ norms, in
                     p2s += __shfl_xor(p2s, 16, EF_WAVE);
                     p3s += __shfl_xor(p3s, 16, EF_WAVE);
                     const float dist = (p0s + p2s) + (p1s + p3s);
-                    q_fill = propose_pair(queue, q_fill, has && g == 0, dist, 16 * bi + al, 16 * bj + bl, thr, uid);
+                    q_fill = propose_pair(queue, q_fill, has && g == 0, dist, 16 * bi + al, 16 * bj + bl, thr, uid, mark);
                     __syncthreads();
                     // NB = 1: the queue is sized so that a point's proposals always fit (at most 240
                     // on top of fewer than q_cap / 2): no drain while the operands are live
@@ -1924,7 +1936,7 @@ join_reg_kernel(const float *__restrict__ X, const float *__restrict__ norms, in
     __syncthreads();
     updates += drain(queue, q_fill);
     updates = ef_wave_sum_i32(updates);
-    if (lane == 0) upd_block[blockIdx.x] = updates;
+    if (lane == 0) upd_block[blockIdx.x] += updates;      // (zeroed once per iteration; passes add up)
 }
 
 // ---------------------------------------------------------------------------------------
@@ -1987,10 +1999,11 @@ join_tile_kernel(const float *__restrict__ X, const float *__restrict__ norms, i
                  u32 kq_magic, int *gid, const int *__restrict__ work, const int *__restrict__ work_count, int cap, int q_cap,
                  float margin_rel, float thr_scale, const int *__restrict__ ulist,
                  const int2 *__restrict__ ucount, int ucap, u64 *graph, u32 *worst,
-                 int *__restrict__ upd_block)
+                 int *__restrict__ upd_block, int mode)
 {
     extern __shared__ __align__(16) float smem[];
     const TileLds lds = tile_lds_carve(smem, cap);
+    const int mark = mode != 2;      // (modes: see join_reg_kernel)
     const int lane = threadIdx.x, r16 = lane & 15, g = lane >> 4;
     const int kw = known_words(cap), hslots = tile_slots(cap), n_buckets = hslots >> 1;
     const int hshift = 32 - (31 - __clz(n_buckets));      // id * odd constant >> hshift: the id's bucket
@@ -2148,7 +2161,7 @@ join_tile_kernel(const float *__restrict__ X, const float *__restrict__ norms, i
                 for (int k = 0; k < 4; ++k) {
                     const int a = 16 * bi + 4 * g + k, ac = min(a, m - 1);
                     const float low = __builtin_fmaf(-2.0f, acc0[k] + acc1[k], lds.nf[ac] + nfb);
-                    const bool valid = a < m_new && b < m && a < b;
+                    const bool valid = a < m_new && b < m && a < b && (mode == 0 || (mode == 1) == (b < m_new));
                     // wanted by a row that may still accept the pair and does not know it yet
                     const bool keep = valid && ((low <= lds.tf[ac] && !((knows_b >> (4 * g + k)) & 1u)) ||
                                                 (low <= tfb && !is_known(bc, ac)));
@@ -2193,13 +2206,13 @@ join_tile_kernel(const float *__restrict__ X, const float *__restrict__ norms, i
                     const u64 mask_a = __ballot(to_a), mask_b = __ballot(to_b);
                     if (to_a) {
                         Proposal &pr = lds.queue[q_fill + lanes_below(mask_a)];
-                        pr.key = ef_pack(dist, lds.uid[bb], 1);
+                        pr.key = ef_pack(dist, lds.uid[bb], mark);
                         pr.target = lds.uid[a];
                     }
                     q_fill += __popcll(mask_a);
                     if (to_b) {
                         Proposal &pr = lds.queue[q_fill + lanes_below(mask_b)];
-                        pr.key = ef_pack(dist, lds.uid[a], 1);
+                        pr.key = ef_pack(dist, lds.uid[a], mark);
                         pr.target = lds.uid[bb];
                     }
                     q_fill += __popcll(mask_b);
@@ -2221,7 +2234,7 @@ join_tile_kernel(const float *__restrict__ X, const float *__restrict__ norms, i
                pc[0] / n_joins, pc[1] / n_joins, pc[2] / n_joins, pc[3] / n_joins, (double)n_prop / n_joins);
 #endif
     updates = ef_wave_sum_i32(updates);
-    if (lane == 0) upd_block[blockIdx.x] = updates;
+    if (lane == 0) upd_block[blockIdx.x] += updates;      // (zeroed once per iteration; passes add up)
 }
 
 // The ids of all graph entries (-1 for an empty slot), written once per iteration after the
@@ -2571,19 +2584,19 @@ int noalloc_scratch_address(void **out)
 }
 
 int nndescent_run(const float *X, int64_t n, int32_t d, int32_t k, efanna_entry *graph_, int32_t iters,
-                  int32_t sample_L, uint64_t seed, int32_t first_iter, float delta, int32_t *iters_done,
-                  uint64_t *stats_, float *phase_ms, void *ws, size_t ws_bytes, void *stream);
+                  int32_t sample_L, uint64_t seed, int32_t first_iter, float delta, int32_t cross_old,
+                  int32_t *iters_done, uint64_t *stats_, float *phase_ms, void *ws, size_t ws_bytes, void *stream);
 
 }  // namespace
 
 extern "C" int efanna_nndescent(const float *X, int64_t n, int32_t d, int32_t k,
                                 efanna_entry *graph_, int32_t iters, int32_t sample_L,
-                                uint64_t seed, int32_t first_iter, float delta,
+                                uint64_t seed, int32_t first_iter, float delta, int32_t cross_old,
                                 int32_t *iters_done, uint64_t *stats_, float *phase_ms, void *ws,
                                 size_t ws_bytes, void *stream)
 {
-    return nndescent_run(X, n, d, k, graph_, iters, sample_L, seed, first_iter, delta, iters_done, stats_,
-                         phase_ms, ws, ws_bytes, stream);
+    return nndescent_run(X, n, d, k, graph_, iters, sample_L, seed, first_iter, delta, cross_old, iters_done,
+                         stats_, phase_ms, ws, ws_bytes, stream);
 }
 
 extern "C" int efanna_nndescent_noalloc(const float *X, int64_t n, int32_t d, int32_t k,
@@ -2599,15 +2612,15 @@ extern "C" int efanna_nndescent_noalloc(const float *X, int64_t n, int32_t d, in
     if (rc != EFANNA_OK) return rc;
     // no early termination (it reads a counter back after every iteration) and no phase timing
     // (it creates events): neither allocates device memory, but both make the call wait
-    return nndescent_run(X, n, d, k, graph_, iters, sample_L, seed, first_iter, 0.0f, nullptr, stats_,
+    return nndescent_run(X, n, d, k, graph_, iters, sample_L, seed, first_iter, 0.0f, 0, nullptr, stats_,
                          nullptr, scratch, (size_t)EFANNA_NOALLOC_SCRATCH_BYTES, stream);
 }
 
 namespace {
 
 int nndescent_run(const float *X, int64_t n, int32_t d, int32_t k, efanna_entry *graph_, int32_t iters,
-                  int32_t sample_L, uint64_t seed, int32_t first_iter, float delta, int32_t *iters_done,
-                  uint64_t *stats_, float *phase_ms, void *ws, size_t ws_bytes, void *stream)
+                  int32_t sample_L, uint64_t seed, int32_t first_iter, float delta, int32_t cross_old,
+                  int32_t *iters_done, uint64_t *stats_, float *phase_ms, void *ws, size_t ws_bytes, void *stream)
 {
     if (iters_done) *iters_done = 0;
     if (!X || !graph_ || !(delta >= 0.0f)) return EFANNA_EINVAL;
@@ -2817,12 +2830,21 @@ int nndescent_run(const float *X, int64_t n, int32_t d, int32_t k, efanna_entry 
         else EF_PREPARE(false);
 #undef EF_PREPARE
         if (ev) EF_HIP_CHECK(hipEventRecord(ev[5 * it + 1], st));
+        if (tiles && max_rows > rows1)
+            graph_ids_kernel<<<min(grid_for((size_t)n * K, kBlock), 256 * 64), kBlock, 0, st>>>(graph, (size_t)n * K, w.gid);
+        // One pass over the joins; with cross_old two, all pairs of two new members of every join
+        // before any pair of a new and an old one (the phase events are recorded in the last pass:
+        // the split by join size then says little).
+        const int n_pass = cross_old ? 2 : 1;
+        for (int pass = 0; pass < n_pass; ++pass) {
+        const int mode = cross_old ? 1 + pass : 0;
+        const bool timed = ev && pass == n_pass - 1;
         if (reg_ok) {
 #define EF_JOIN_REG_K(NB, ONE, LIST, KT)                                                           \
     join_reg_kernel<NB, ONE, KT><<<reg_grid, EF_WAVE, reg_lds(16 * NB), st>>>(                     \
         X, w.norms, d, K, w.work + (size_t)(LIST) * n, w.work_count + (LIST), reg_q_cap_for(16 * NB), \
         margin_rel, thr_scale, w.ulist, w.ucount, max_rows, graph, w.worst,                        \
-        w.upd_block + (LIST) * reg_grid)
+        w.upd_block + (LIST) * reg_grid, mode)
     // (a row length of 10 is compiled in: 3 % off the joins of 17..32 vectors)
 #define EF_JOIN_REG(NB, ONE, LIST)                                                                 \
     do {                                                                                           \
@@ -2831,25 +2853,23 @@ int nndescent_run(const float *X, int64_t n, int32_t d, int32_t k, efanna_entry 
     } while (0)
             if (d <= 128) EF_JOIN_REG(1, true, 0);
             else EF_JOIN_REG(1, false, 0);
-            if (ev) EF_HIP_CHECK(hipEventRecord(ev[5 * it + 2], st));
+            if (timed) EF_HIP_CHECK(hipEventRecord(ev[5 * it + 2], st));
             if (max_rows > 16) {
                 if (d <= 128) EF_JOIN_REG(2, true, 1);
                 else EF_JOIN_REG(2, false, 1);
             }
 #undef EF_JOIN_REG
 #undef EF_JOIN_REG_K
-        } else if (ev) {
+        } else if (timed) {
             EF_HIP_CHECK(hipEventRecord(ev[5 * it + 2], st));
         }
-        if (ev) EF_HIP_CHECK(hipEventRecord(ev[5 * it + 3], st));
-        if (tiles && max_rows > rows1)
-            graph_ids_kernel<<<min(grid_for((size_t)n * K, kBlock), 256 * 64), kBlock, 0, st>>>(graph, (size_t)n * K, w.gid);
+        if (timed) EF_HIP_CHECK(hipEventRecord(ev[5 * it + 3], st));
 #define EF_JOIN_LARGE(WIDE, C)                                                                     \
     join_kernel<WIDE><<<large[C].grid, large[C].threads, large[C].lds, st>>>(                      \
         X, w.norms, d, dpad, stride, q4_magic_for(d), K, (u32)(((1ULL << 32) + K - 1) / K),       \
         w.work + (size_t)(C) * n, w.work_count + (C),                                              \
         large[C].cap_rows, large[C].s_cap, large[C].q_cap, margin_rel, thr_scale, w.ulist,         \
-        w.ucount, max_rows, graph, w.worst, w.upd_block + 2 * reg_grid + ((C) - 2) * kMaxLargeGrid)
+        w.ucount, max_rows, graph, w.worst, w.upd_block + 2 * reg_grid + ((C) - 2) * kMaxLargeGrid, mode)
         // the larger classes first: their blocks run longest
         for (int c = jc.n - 1; c >= 2 && max_rows > rows1; --c) {
             if (tiles) {      // vectors of at most 128 coordinates pass through registers
@@ -2864,15 +2884,16 @@ int nndescent_run(const float *X, int64_t n, int32_t d, int32_t k, efanna_entry 
                 if (K > 16 && (K & 1) == 0 && ((uintptr_t)graph & 15) == 0)
                     join_tile_kernel<true><<<tgrid, EF_WAVE, tl, st>>>(
                         X, w.norms, d, K, km, kqm, w.gid, w.work + (size_t)c * n, w.work_count + c, jc.bound[c], tq,
-                        margin_rel, thr_scale, w.ulist, w.ucount, max_rows, graph, w.worst, upd);
+                        margin_rel, thr_scale, w.ulist, w.ucount, max_rows, graph, w.worst, upd, mode);
                 else
                     join_tile_kernel<false><<<tgrid, EF_WAVE, tl, st>>>(
                         X, w.norms, d, K, km, kqm, w.gid, w.work + (size_t)c * n, w.work_count + c, jc.bound[c], tq,
-                        margin_rel, thr_scale, w.ulist, w.ucount, max_rows, graph, w.worst, upd);
+                        margin_rel, thr_scale, w.ulist, w.ucount, max_rows, graph, w.worst, upd, mode);
             } else if (K >= 2 * EF_WIDE_PIECES) EF_JOIN_LARGE(true, c);
             else EF_JOIN_LARGE(false, c);
         }
 #undef EF_JOIN_LARGE
+        }      // pass
         if (ev) EF_HIP_CHECK(hipEventRecord(ev[5 * it + 4], st));
         if (stats)
             stats_kernel<<<16, kBlock, 0, st>>>(w.part, grid_for((size_t)n, prep_threads), w.upd_block,

@@ -56,7 +56,7 @@ def lib():
         L.efanna_nndescent_workspace_bytes.restype = sz
         L.efanna_nndescent_workspace_bytes.argtypes = [i64, i32, i32]
         L.efanna_nndescent.restype = C.c_int
-        L.efanna_nndescent.argtypes = [vp, i64, i32, i32, vp, i32, i32, u64, i32, C.c_float, vp, vp, vp, vp, sz, vp]
+        L.efanna_nndescent.argtypes = [vp, i64, i32, i32, vp, i32, i32, u64, i32, C.c_float, i32, vp, vp, vp, vp, sz, vp]
         L.efanna_nndescent_noalloc.restype = C.c_int
         L.efanna_nndescent_noalloc.argtypes = [vp, i64, i32, i32, vp, i32, i32, u64, i32, vp, vp]
         L.efanna_get_graph.restype = C.c_int
@@ -168,13 +168,14 @@ def efanna_init_graph(X: torch.Tensor, perm: torch.Tensor, leaf_off: torch.Tenso
 def efanna_nndescent(X: torch.Tensor, graph: torch.Tensor, iters: int, sample_L: int, seed: int,
                      first_iter: int = 0, stats: torch.Tensor | None = None,
                      workspace: torch.Tensor | None = None, phase_ms: np.ndarray | None = None,
-                     delta: float = 0.0):
+                     delta: float = 0.0, cross_old: bool = False):
     """Alg. 4, in place on `graph`.  Returns stats [iters,4] (int64 device tensor:
     distance evaluations, accepted insertions, vectors gathered, vectors gathered by the
     joins of at most 16 vectors).  `phase_ms`, if given, is a float32 numpy array
     [iters,4] that receives (sampling, small / medium / large joins) times and makes the
     call synchronise.  With delta > 0 (early termination) the call synchronises after every
-    iteration and returns (stats of the iterations carried out, their number)."""
+    iteration and returns (stats of the iterations carried out, their number).  cross_old: the
+    literal marking of Alg. 4 (entries inserted by a new and an old member are marked old)."""
     X = _dev(X, torch.float32)
     n, d = X.shape
     graph = _dev(graph, torch.int64)
@@ -187,7 +188,7 @@ def efanna_nndescent(X: torch.Tensor, graph: torch.Tensor, iters: int, sample_L:
     ws = _workspace(need, X.device) if workspace is None else workspace
     done = C.c_int32(0)
     _check(lib().efanna_nndescent(X.data_ptr(), n, d, k, graph.data_ptr(), iters, sample_L, seed,
-                                  first_iter, float(delta), C.byref(done), stats.data_ptr(),
+                                  first_iter, float(delta), 1 if cross_old else 0, C.byref(done), stats.data_ptr(),
                                   None if phase_ms is None else phase_ms.ctypes.data_as(C.c_void_p),
                                   ws.data_ptr(), ws.numel(), _stream()), "efanna_nndescent")
     if delta > 0.0:

@@ -70,9 +70,9 @@ def test_argument_errors_are_caught_on_the_host(lib):
     # nodes without leaf_up (and the reverse) is an argument error
     assert lib.efanna_build_trees(one, 10, 4, 1, 2, 0, one, one, 10, one, one, None, None, one, 1 << 20, None) == -1
     assert lib.efanna_init_graph(one, 10, 4, one, one, 10, one, None, one, 5, 0, 1, 2, 3, one, one, 256, None) == -1
-    assert lib.efanna_nndescent(one, 10, 4, 10, one, 1, 4, 0, 0, 0.0, None, None, None, one, 1 << 20, None) == -1  # k >= n
-    assert lib.efanna_nndescent(one, 100, 4, 129, one, 1, 4, 0, 0, 0.0, None, None, None, one, 1 << 30, None) == -1
-    assert lib.efanna_nndescent(one, 100, 4, 10, one, 1, 4, 0, 0, -1.0, None, None, None, one, 1 << 30, None) == -1  # delta < 0
+    assert lib.efanna_nndescent(one, 10, 4, 10, one, 1, 4, 0, 0, 0.0, 0, None, None, None, one, 1 << 20, None) == -1  # k >= n
+    assert lib.efanna_nndescent(one, 100, 4, 129, one, 1, 4, 0, 0, 0.0, 0, None, None, None, one, 1 << 30, None) == -1
+    assert lib.efanna_nndescent(one, 100, 4, 10, one, 1, 4, 0, 0, -1.0, 0, None, None, None, one, 1 << 30, None) == -1  # delta < 0
     assert lib.efanna_get_graph(null, 10, 4, one, one, None, None) == -1
     assert lib.efanna_set_graph(one, 10, 0, one, one, None, None) == -1
     assert lib.efanna_pair_distances(one, 10, 4, null, one, 5, one, None) == -1

@@ -283,6 +283,38 @@ def test_nndescent_more_shapes(ef, n, d, T, S, K, L, I):
     oracle.check_graph_invariants(X, ids, dists)
 
 
+@pytest.mark.parametrize("n,d,T,S,K,L,I", [
+    (6_000, 32, 3, 8, 10, 10, 4),        # joins of at most 16 and of 17..32 vectors, rows of ten
+    (4_000, 128, 2, 16, 20, 20, 3),      # tile joins (more than 32 vectors of up to 128 coordinates)
+    (3_000, 200, 2, 12, 8, 8, 3),        # long vectors: joins by rotations
+    (3_000, 160, 2, 16, 24, 16, 3),      # long vectors and more than 32 of them: rows in LDS
+    (2_000, 24, 2, 8, 7, 9, 3),          # odd row length
+    (4_000, 16, 2, 16, 50, 25, 3),       # L < K: unsampled entries keep their new mark through the join
+])
+def test_nndescent_literal_marking_bit_exact(ef, n, d, T, S, K, L, I):
+    """The literal marking of Alg. 4's second inner loop (cross_old): entries that a new and an old
+    member insert are marked old, pairs of two new members going first.  Ids, distance bits, marks
+    and pairs evaluated equal the oracle's after every iteration, in every join kernel."""
+    rng = np.random.default_rng(n + d)
+    X = (rng.standard_normal((n, d)) + 3.0 * rng.integers(0, 5, (n, 1))).astype(np.float32)
+    Xd = dev(X)
+    (perm, off, nl), (operm, ooff, onl) = trees_equal(ef, X, T, S, 11)
+    graph = ef.efanna_init_graph(Xd, perm, off, nl, S, K)
+    want = oracle.init_graph(X, operm, ooff, onl, K)
+    marks = []
+    for it in range(I):
+        stats = ef.efanna_nndescent(Xd, graph, 1, L, 11, first_iter=it, cross_old=True)
+        want = oracle.nndescent(X, *want[:3], 1, L, 11, iter0=it, cross_old=True)
+        graph_equal(ef, graph, want)
+        assert int(host(stats)[0, 0]) == int(want[3][0, 0])
+        marks.append(int(want[2].sum()))
+    # and all iterations in one call (the passes alternate inside the library)
+    graph2 = ef.efanna_init_graph(Xd, perm, off, nl, S, K)
+    ef.efanna_nndescent(Xd, graph2, I, L, 11, cross_old=True)
+    graph_equal(ef, graph2, want)
+    assert any(want[2].ravel() == 0) and marks[-1] < marks[0]
+
+
 @pytest.mark.parametrize("hubs", [
     [0, 1500, 3000, 4500],      # spread over the ranges of 1024 targets
     [3, 200, 700, 1023],        # all in one range: twenty thousand offers for its thousand lists

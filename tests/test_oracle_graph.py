@@ -125,9 +125,10 @@ def test_more_trees_never_lower_init_accuracy():
 # ----------------------------------------------------------------------------------
 # Alg. 4
 
-def py_iteration(Xi, pools, K, L, seed, it):
+def py_iteration(Xi, pools, K, L, seed, it, cross_old=False):
     """One NN-descent iteration written with Python sets on integer data.
-    pools: list of dict id -> [dist, is_new]."""
+    pools: list of dict id -> [dist, is_new].  cross_old: what only pairs of a new and an old
+    member offer to a pool enters it marked old (the literal marking of Alg. 4)."""
     n = len(pools)
     new, old = [], []
     for i in range(n):
@@ -153,22 +154,27 @@ def py_iteration(Xi, pools, K, L, seed, it):
 
     rnew, rold = reverse(new, 2 * it), reverse(old, 2 * it + 1)
     proposals = [dict() for _ in range(n)]
+    by_new_pairs = [set() for _ in range(n)]      # offered by a pair of two new members
     evals = 0
     for i in range(n):
         un = sorted(set(new[i]) | set(rnew[i]))
         uo = sorted((set(old[i]) | set(rold[i])) - set(un))
         pairs = [(u, v) for a, u in enumerate(un) for v in un[a + 1:]]
+        n_new_pairs = len(pairs)
         pairs += [(u, v) for u in un for v in uo]
-        for u, v in pairs:
+        for k, (u, v) in enumerate(pairs):
             dist = int(((Xi[u] - Xi[v]) ** 2).sum())
             evals += 1
             proposals[u][v] = dist
             proposals[v][u] = dist
+            if k < n_new_pairs:
+                by_new_pairs[u].add(v)
+                by_new_pairs[v].add(u)
     for u in range(n):
         merged = dict(pools[u])
         for v, dist in proposals[u].items():
             if v not in merged:
-                merged[v] = [dist, 1]
+                merged[v] = [dist, 1 if (not cross_old or v in by_new_pairs[u]) else 0]
         keep = sorted(merged.items(), key=lambda kv: (kv[1][0], kv[0]))[:K]
         pools[u] = {j: e for j, e in keep}
     return evals
@@ -190,16 +196,17 @@ def arrays_from_pools(pools, K):
     return ids, dists, flags
 
 
-@pytest.mark.parametrize("K,L", [(6, 6), (8, 3)])
-def test_nndescent_iterations_against_set_based_python(K, L):
+@pytest.mark.parametrize("K,L,cross_old", [(6, 6, False), (8, 3, False), (6, 6, True), (8, 3, True)])
+def test_nndescent_iterations_against_set_based_python(K, L, cross_old):
     X = synth.generate("sift100k_like", n=600)[:, :24].copy()
     Xi = X.astype(np.int64)
     perm, off, nl = oracle.build_trees(X, 2, 6, seed=9)
     ids, dists, flags = oracle.init_graph(X, perm, off, nl, K)
     pools = pools_from_arrays(ids, dists, flags)
-    for it in range(3):
-        ev = py_iteration(Xi, pools, K, L, seed=77, it=it)
-        ids, dists, flags, stats = oracle.nndescent(X, ids, dists, flags, 1, L, seed=77, iter0=it)
+    for it in range(4 if cross_old else 3):
+        ev = py_iteration(Xi, pools, K, L, seed=77, it=it, cross_old=cross_old)
+        ids, dists, flags, stats = oracle.nndescent(X, ids, dists, flags, 1, L, seed=77, iter0=it,
+                                                    cross_old=cross_old)
         wi, wd, wf = arrays_from_pools(pools, K)
         assert int(stats[0, 0]) == ev
         assert np.array_equal(ids, wi) and np.array_equal(dists, wd) and np.array_equal(flags, wf)
@@ -310,3 +317,41 @@ def test_early_termination_stops_where_the_fresh_entries_run_out():
     # a threshold nothing can meet stops after one iteration, zero never stops early
     assert oracle.nndescent(X, *g0[:3], 5, L, 42, delta=2.0)[4] == 1
     assert oracle.nndescent(X, *g0[:3], 3, L, 42)[3].shape[0] == 3
+
+
+def test_literal_marking_hand_case_and_properties():
+    """Alg. 4's second inner loop marks what a new and an old member insert as old.  Five points on a
+    line, rows of 2, sample of 2: after one ordinary iteration from a hand-made graph, point 0 has
+    the new neighbour 1 and the old neighbour 4... written out below."""
+    # points at 0, 1, 2, 10, 11; K = 2.  Row 2 holds {3 (old), 1 (new)}: the join of point 2 pairs the
+    # new member 1 with the old member 3 only: 1 <- 3 (dist 81) and 3 <- 1.
+    X = np.array([[0.0], [1.0], [2.0], [10.0], [11.0]], dtype=np.float32)
+    ids = np.array([[-1, -1], [-1, -1], [1, 3], [-1, -1], [-1, -1]], dtype=np.int32)
+    dists = np.array([[np.inf, np.inf], [np.inf, np.inf], [1.0, 64.0], [np.inf, np.inf], [np.inf, np.inf]],
+                     dtype=np.float32)
+    flags = np.array([[0, 0], [0, 0], [1, 0], [0, 0], [0, 0]], dtype=np.uint8)
+    a = oracle.nndescent(X, ids, dists, flags, 1, 2, seed=0)
+    b = oracle.nndescent(X, ids, dists, flags, 1, 2, seed=0, cross_old=True)
+    # the same entries either way (1 <-> 3 at distance 81, found by the join of point 2) ...
+    assert np.array_equal(a[0], b[0]) and np.array_equal(a[1], b[1])
+    assert a[0][1].tolist() == [3, -1] and a[0][3].tolist() == [1, -1] and a[1][1, 0] == 81.0
+    # ... marked new by default and old in the literal reading
+    assert a[2][1, 0] == 1 and a[2][3, 0] == 1
+    assert b[2][1, 0] == 0 and b[2][3, 0] == 0
+    assert int(a[3][0, 0]) == 1 and int(b[3][0, 0]) == 1      # one pair evaluated
+
+    # on real-shaped data: same work in the first iteration (every entry is new: no old members), never
+    # more marks than the default afterwards, and the join dries up sooner
+    Xs = synth.generate("gmm10k_d32", n=1500)
+    perm, off, nl = oracle.build_trees(Xs, 3, 8, seed=2)
+    g0 = oracle.init_graph(Xs, perm, off, nl, 8)
+    d1 = oracle.nndescent(Xs, *g0, 1, 8, seed=5)
+    l1 = oracle.nndescent(Xs, *g0, 1, 8, seed=5, cross_old=True)
+    assert all(np.array_equal(x, y) for x, y in zip(d1[:3], l1[:3])) and d1[3][0, 0] == l1[3][0, 0]
+    d6 = oracle.nndescent(Xs, *g0, 6, 8, seed=5)
+    l6 = oracle.nndescent(Xs, *g0, 6, 8, seed=5, cross_old=True)
+    assert l6[3][:, 0].sum() < d6[3][:, 0].sum()
+    assert l6[2].sum() <= d6[2].sum()
+    tid, _ = oracle.exact_knn(Xs, np.arange(1500), 8)
+    assert oracle.recall(l6[0], tid) <= oracle.recall(d6[0], tid) + 0.01
+    oracle.check_graph_invariants(Xs, l6[0], l6[1])

@@ -104,6 +104,12 @@ MUTANTS = [
     ("conquer: every ancestor's sibling is searched from the point's leaf-level parent",
      "up = pj < 0 ? -1 : pj * 2 + (nd[pj].child[1] == j);", "up = pj < 0 ? -1 : pj * 2 + (nd[pj].child[0] == j);",
      CONQUER),
+    ("NN-descent, literal marking: what a new and an old member insert is marked new after all",
+     "uint8_t mark = !(cross_old && pass == 1);", "uint8_t mark = 1;", GRAPH),
+    ("NN-descent, literal marking: pairs of a new and an old member are inserted first",
+     "int32_t b_lo = cross_old && pass == 1 ? n_new : a + 1;\n                    int32_t b_hi = cross_old && pass == 0 ? n_new : n_new + n_old;\n                    uint8_t mark = !(cross_old && pass == 1);",
+     "int32_t b_lo = cross_old && pass == 0 ? n_new : a + 1;\n                    int32_t b_hi = cross_old && pass == 1 ? n_new : n_new + n_old;\n                    uint8_t mark = !(cross_old && pass == 0);",
+     GRAPH),
     ("NN-descent: reverse hash takes (source, target)",
      "c->hash = oracle_reverse_hash(seed, iter, v, (int32_t)u);", "c->hash = oracle_reverse_hash(seed, iter, (int32_t)u, v);",
      GRAPH),
