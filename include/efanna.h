@@ -140,8 +140,9 @@ int efanna_build_trees(const float *X, int64_t n, int32_t d, int32_t n_trees, in
  *                  <= 0 or no nodes: 256 bytes).
  * graph    [device] out, n*k entries.
  * Asynchronous on `stream`.  Limits: k <= EFANNA_MAX_K, k < n, n < 2^31 - 256, a leaf
- * of leaf_size rows of d floats must fit the 160 KB LDS; with nodes: leaf_size <= 16, d a
- * multiple of 4, X 16-byte aligned and levels <= 64 (EFANNA_EUNSUPPORTED otherwise).
+ * of leaf_size rows of d floats must fit the 160 KB LDS; with nodes: levels <= 64
+ * (EFANNA_EUNSUPPORTED otherwise).  Leaves of at most 16 points with d a multiple of 4 and a
+ * 16-byte aligned X take the fast kernels, every other shape general ones.
  */
 size_t efanna_init_workspace_bytes(int64_t n, int32_t levels);
 

@@ -697,6 +697,135 @@ conquer_kernel(const float *__restrict__ X, int d, const int *__restrict__ perm_
 }
 
 // ---------------------------------------------------------------------------------------
+// The same step for any leaf size up to 64 and any dimension (the kernels above want leaves of at
+// most 16 points and d % 4 == 0).  classify_any_kernel: one wave per leaf, lane r sends member r
+// down the sibling subtree of every ancestor in range.  conquer_any_kernel: one wave per member
+// (the waves of a block take the members of one home leaf, which owns its members' rows during
+// the launch); per level the wave evaluates its member against the members of the leaf reached,
+// one pair per group of sixteen lanes in the library's fixed order, and merges by rank in LDS.
+__global__ void __launch_bounds__(kBlock)
+classify_any_kernel(const float *__restrict__ X, int d, const int *__restrict__ perm_t,
+                    const int *__restrict__ leaf_off_t, int n_leaves,
+                    const efanna_node *__restrict__ nodes_t, const int *__restrict__ leaf_up_t, int dep,
+                    int levels, int *__restrict__ etab)
+{
+    const int lane = ef_lane(), wave = threadIdx.x / EF_WAVE;
+    const int last = n_leaves - 1;
+    const int n_waves = gridDim.x * (kBlock / EF_WAVE);
+    for (int leaf = blockIdx.x * (kBlock / EF_WAVE) + wave; leaf < n_leaves; leaf += n_waves) {
+        const int b0 = leaf_off_t[leaf];
+        const int s = min(leaf_off_t[leaf + 1] - b0, EF_WAVE);
+        if (lane >= s) continue;
+        const int my_id = perm_t[b0 + lane];
+        int up = min(leaf_up_t[leaf], 2 * last + 1);
+        for (int k = 0; k < levels; ++k) {
+            int e = -1;
+            if (up >= 0) {
+                const int j = up >> 1;
+                const efanna_node anc = nodes_t[j];
+                if (anc.depth >= dep) {
+                    int c = anc.child[1 - (up & 1)];
+                    for (int steps = 0; c >= 0 && steps < 4096; ++steps) {      // (bounded: foreign tables cannot hold it)
+                        const efanna_node nd = nodes_t[min(c, last)];
+                        const bool left = nd.dim < 0 ||
+                                          (long long)nd.cnt * ef_quantise(X[(size_t)my_id * d + max(0, min(nd.dim, d - 1))]) < nd.sum;
+                        c = nd.child[left ? 0 : 1];
+                    }
+                    e = c >= 0 ? 0 : min(~c, last);
+                    const int pj = min(anc.parent, last);
+                    up = pj < 0 ? -1 : pj * 2 + (j > pj ? 1 : 0);
+                } else {
+                    up = -1;
+                }
+            }
+            etab[(size_t)(b0 + lane) * levels + k] = e;
+        }
+    }
+}
+
+__global__ void __launch_bounds__(kBlock)
+conquer_any_kernel(const float *__restrict__ X, int d, const int *__restrict__ perm_t,
+                   const int *__restrict__ leaf_off_t, int n_leaves, const int *__restrict__ etab,
+                   int levels, int K, u64 *graph)
+{
+    extern __shared__ __align__(16) float smem[];
+    const int lane = ef_lane(), wave = threadIdx.x / EF_WAVE, n_waves = kBlock / EF_WAVE;
+    const int grp = lane >> 4, gl = lane & 15;
+    u64 *row_a = (u64 *)smem + (size_t)wave * (2 * K + EF_WAVE);      // [K] the row being merged, ascending
+    u64 *row_b = row_a + K;                                           // [K] the other copy
+    u64 *cand = row_b + K;                                            // [64] candidates of the level in hand
+    auto wave_sync = [&]() {      // one wave: its LDS operations complete in program order
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+    };
+    for (int leaf = blockIdx.x; leaf < n_leaves; leaf += gridDim.x) {
+        const int b0 = leaf_off_t[leaf];
+        const int s = min(leaf_off_t[leaf + 1] - b0, EF_WAVE);
+        for (int r = wave; r < s; r += n_waves) {
+            if (levels < 1 || etab[(size_t)(b0 + r) * levels] < 0) continue;      // nothing above this leaf to visit
+            const int my_id = perm_t[b0 + r];
+            const float *xa = X + (size_t)my_id * d;
+            u64 *cur = row_a, *nxt = row_b;
+            wave_sync();
+            for (int c = lane; c < K; c += EF_WAVE) cur[c] = graph[(size_t)my_id * K + c];
+            for (int k = 0; k < levels; ++k) {
+                const int e = etab[(size_t)(b0 + r) * levels + k];
+                if (e < 0) break;      // the ancestors in range are the first ones
+                const int bb = leaf_off_t[min(e, n_leaves - 1)];
+                const int sb = min(leaf_off_t[min(e, n_leaves - 1) + 1] - bb, EF_WAVE);
+                // ---- distances to the members of the leaf reached, four pairs at a time -----------
+                for (int j0 = 0; j0 < sb; j0 += 4) {
+                    const int j = min(j0 + grp, sb - 1);      // (whole groups stay busy)
+                    const int id_b = perm_t[bb + j];
+                    const float *xb = X + (size_t)id_b * d;
+                    float acc = 0.0f;
+                    for (int t = gl; t < d; t += 16) {
+                        const float diff = xa[t] - xb[t];
+                        acc = __builtin_fmaf(diff, diff, acc);
+                    }
+                    acc = ef_group_reduce16(acc);
+                    if (gl == 0 && j0 + grp < sb) cand[j0 + grp] = id_b != my_id ? ef_pack(acc, id_b, 1) : ~0ULL;
+                }
+                wave_sync();
+                // ---- merge by rank: K old entries and sb candidates, the K smallest stay ------------
+                u64 key = ~0ULL;
+                int below = 0;      // old entries below the candidate
+                if (lane < sb) {
+                    key = cand[lane];
+                    int lo = 0, hi = K;
+                    while (lo < hi) {
+                        const int mid = (lo + hi) >> 1;
+                        if (cur[mid] < key) lo = mid + 1;
+                        else hi = mid;
+                    }
+                    if (lo < K && cur[lo] == key) key = ~0ULL;      // already in the row
+                    below = lo;
+                }
+                wave_sync();
+                cand[lane] = key;      // (dropped candidates become the largest key: they count for nobody)
+                wave_sync();
+                if (key != ~0ULL) {
+                    int rank = below;
+                    for (int o = 0; o < sb; ++o) rank += cand[o] < key ? 1 : 0;
+                    if (rank < K) nxt[rank] = key;
+                }
+                for (int c = lane; c < K; c += EF_WAVE) {
+                    const u64 en = cur[c];
+                    int rank = c;
+                    for (int o = 0; o < sb; ++o) rank += cand[o] < en ? 1 : 0;
+                    if (rank < K) nxt[rank] = en;
+                }
+                wave_sync();
+                u64 *tmp = cur;
+                cur = nxt;
+                nxt = tmp;
+            }
+            for (int c = lane; c < K; c += EF_WAVE) graph[(size_t)my_id * K + c] = cur[c];
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------------------
 // Alg. 4 step 1+2: sample the new / old sets of every row, clear the sampled marks,
 // refresh the row's threshold and enter the row's id into the reverse lists of the
 // sampled neighbours.
@@ -2518,7 +2647,7 @@ extern "C" int efanna_init_graph(const float *X, int64_t n, int32_t d, const int
                        (size_t)leaf_size * 4;
     const int block_threads = EF_WAVE * ((leaf_size + 15) / 16);
     const bool reg_ok = leaf_size <= 16 && d % 4 == 0 && ((uintptr_t)X & 15) == 0;
-    if (nodes && !reg_ok) return EFANNA_EUNSUPPORTED;      // the step above the leaves has one kernel only
+    if (leaf_size > EF_WAVE) return EFANNA_EUNSUPPORTED;
     if (reg_ok) {
         const size_t reg_lds = (size_t)16 * k * 8 + (size_t)16 * kCandPitch * 8 + 16 * 4;
         const size_t conquer_lds = (size_t)2 * 16 * k * 8 + (size_t)16 * kCandPitch * 8 + 16 * 16 * 4;
@@ -2541,10 +2670,20 @@ extern "C" int efanna_init_graph(const float *X, int64_t n, int32_t d, const int
     if (lds > kLdsLimit) return EFANNA_EUNSUPPORTED;
     EF_HIP_CHECK(hipFuncSetAttribute((const void *)init_tree_kernel,
                                      hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-    for (int t = 0; t < n_trees; ++t)
+    const size_t any_lds = (size_t)(kBlock / EF_WAVE) * (2 * k + EF_WAVE) * 8;
+    for (int t = 0; t < n_trees; ++t) {
+        const int32_t *perm_t = perm + (size_t)t * n, *off_t = leaf_off + (size_t)t * (max_leaves + 1);
         init_tree_kernel<<<n_leaves[t], block_threads, lds, st>>>(
-            X, d, stride, q4_magic_for(d), leaf_size, perm + (size_t)t * n, leaf_off + (size_t)t * (max_leaves + 1), k,
-            graph, t == 0);
+            X, d, stride, q4_magic_for(d), leaf_size, perm_t, off_t, k, graph, t == 0);
+        if (levels > 0) {      // above the leaves: the general kernels (any leaf size up to 64, any d)
+            int *etab = (int *)ws;
+            classify_any_kernel<<<min(grid_for((size_t)n_leaves[t], kBlock / EF_WAVE), 256 * 8), kBlock, 0, st>>>(
+                X, d, perm_t, off_t, n_leaves[t], nodes + (size_t)t * (max_leaves + 1),
+                leaf_up + (size_t)t * (max_leaves + 1), conquer_depth, levels, etab);
+            conquer_any_kernel<<<min(n_leaves[t], 256 * 64), kBlock, any_lds, st>>>(
+                X, d, perm_t, off_t, n_leaves[t], etab, levels, k, graph);
+        }
+    }
     EF_HIP_CHECK(hipGetLastError());
     return EFANNA_OK;
 }

@@ -200,6 +200,9 @@ def test_tree_nodes_edge_cases(ef):
     ("gmm10k_d32", 6_000, 3, 8, 10, (0, 5, 9, 99)),
     ("sift100k_like", 8_000, 4, 16, 20, (7,)),       # integer data: ties, points found again in other trees
     ("gmm10k_d32", 1_003, 2, 3, 16, (0,)),           # up to the root, rows that stay under-full
+    ("mixed4m_d96", 9_001, 2, 64, 100, (0, 4, 99)),  # leaves of more than 16 points: the general kernels
+    ("mixed4m_d96", 5_000, 3, 40, 24, (3,)),
+    ("gist1m_like", 3_000, 2, 33, 12, (2,)),         # d = 960, rows wider than a leaf
 ])
 def test_conquer_above_the_leaves_bit_exact(ef, name, n, T, S, K, deps):
     X = synth.generate(name, n=n)
@@ -224,11 +227,13 @@ def test_conquer_shapes_and_limits(ef):
     graph = ef.efanna_init_graph(dev(X), g[0], g[1], g[2], 13, 10, nodes=g[3], leaf_up=g[4], tree_depth=g[5],
                                  conquer_depth=4)
     graph_equal(ef, graph, oracle.conquer_graph(X, *o, 4, 10))
-    X = rng.standard_normal((2_000, 8)).astype(np.float32)
-    g, _ = tree_nodes_equal(ef, X, 1, 64, 3)
-    with pytest.raises(ef.EfannaError) as e:                     # only leaves of at most 16 points
-        ef.efanna_init_graph(dev(X), g[0], g[1], g[2], 64, 10, nodes=g[3], leaf_up=g[4], tree_depth=g[5], conquer_depth=0)
-    assert e.value.status == -6
+    for n, d, S, K, dep in ((2_000, 8, 64, 10, 0), (3_001, 30, 40, 48, 5), (1_500, 7, 12, 9, 3), (900, 3, 5, 70, 1)):
+        X = rng.standard_normal((n, d)).astype(np.float32)       # d not a multiple of 4, K above the leaf size
+        g, o = tree_nodes_equal(ef, X, 2, S, 3)
+        graph = ef.efanna_init_graph(dev(X), g[0], g[1], g[2], S, K, nodes=g[3], leaf_up=g[4], tree_depth=g[5],
+                                     conquer_depth=dep)
+        ids, dists = graph_equal(ef, graph, oracle.conquer_graph(X, *o, dep, K))
+        oracle.check_graph_invariants(X, ids, dists)
 
 
 @pytest.mark.parametrize("name,n,T,S,K,L,I", [
