@@ -47,6 +47,10 @@ def _load():
         lib.oracle_build_trees_nodes.argtypes = [C.c_void_p, C.c_int64, C.c_int32, C.c_int32, C.c_int32,
                                                  C.c_uint64, C.c_void_p, C.c_void_p, C.c_void_p,
                                                  C.c_void_p, C.c_void_p]
+        lib.oracle_build_trees_rule.restype = C.c_int
+        lib.oracle_build_trees_rule.argtypes = [C.c_void_p, C.c_int64, C.c_int32, C.c_int32, C.c_int32,
+                                                C.c_uint64, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p,
+                                                C.c_void_p, C.c_void_p]
         lib.oracle_conquer_graph.restype = C.c_int
         lib.oracle_conquer_graph.argtypes = [C.c_void_p, C.c_int64, C.c_int32, C.c_void_p, C.c_void_p,
                                              C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32,
@@ -112,14 +116,19 @@ def dist(a, b) -> np.float32:
     return np.float32(_load().oracle_dist(_p(a), _p(b), a.shape[0]))
 
 
-def build_trees(X, T: int, S: int, seed: int):
-    """Alg. 2.  Returns (perm [T,n] int32, leaf_off [T,n+1] int32, n_leaves [T] int32)."""
+def build_trees(X, T: int, S: int, seed: int, split_rule: int = 0):
+    """Alg. 2 (split_rule 1: the split dimension is chosen among the five of largest variance).
+    Returns (perm [T,n] int32, leaf_off [T,n+1] int32, n_leaves [T] int32)."""
     X = _f32(X)
     n, d = X.shape
     perm = np.empty((T, n), dtype=np.int32)
     leaf_off = np.full((T, n + 1), -1, dtype=np.int32)
     n_leaves = np.zeros(T, dtype=np.int32)
-    rc = _load().oracle_build_trees(_p(X), n, d, T, S, seed, _p(perm), _p(leaf_off), _p(n_leaves))
+    if split_rule:
+        rc = _load().oracle_build_trees_rule(_p(X), n, d, T, S, seed, split_rule, _p(perm), _p(leaf_off),
+                                             _p(n_leaves), None, None)
+    else:
+        rc = _load().oracle_build_trees(_p(X), n, d, T, S, seed, _p(perm), _p(leaf_off), _p(n_leaves))
     if rc != 0:
         raise ValueError(f"oracle_build_trees failed: {rc}")
     return perm, leaf_off, n_leaves
@@ -131,7 +140,7 @@ NODE_DTYPE = np.dtype([("sum", np.int64), ("dim", np.int32), ("cnt", np.int32), 
 assert NODE_DTYPE.itemsize == 32
 
 
-def build_trees_nodes(X, T: int, S: int, seed: int):
+def build_trees_nodes(X, T: int, S: int, seed: int, split_rule: int = 0):
     """Alg. 2 with the internal nodes kept for the conquer step of Alg. 3.  Returns (perm,
     leaf_off, n_leaves, nodes [T,n+1] NODE_DTYPE, leaf_up [T,n+1] int32)."""
     X = _f32(X)
@@ -141,8 +150,8 @@ def build_trees_nodes(X, T: int, S: int, seed: int):
     n_leaves = np.zeros(T, dtype=np.int32)
     nodes = np.zeros((T, n + 1), dtype=NODE_DTYPE)
     leaf_up = np.full((T, n + 1), -1, dtype=np.int32)
-    rc = _load().oracle_build_trees_nodes(_p(X), n, d, T, S, seed, _p(perm), _p(leaf_off),
-                                          _p(n_leaves), _p(nodes), _p(leaf_up))
+    rc = _load().oracle_build_trees_rule(_p(X), n, d, T, S, seed, split_rule, _p(perm), _p(leaf_off),
+                                         _p(n_leaves), _p(nodes), _p(leaf_up))
     if rc != 0:
         raise ValueError(f"oracle_build_trees_nodes failed: {rc}")
     return perm, leaf_off, n_leaves, nodes, leaf_up

@@ -112,6 +112,7 @@ typedef struct {
     const float *X;
     int64_t n;
     int32_t d, S, tree;
+    int32_t split_rule; /* 0: the dimension is drawn uniformly (Alg. 2 as printed), 1: by variance */
     uint64_t seed;
     int32_t *perm;     /* this tree's id array, partitioned in place */
     int32_t *tmp;      /* scratch of n ids */
@@ -120,6 +121,40 @@ typedef struct {
     oracle_node *rec;  /* NULL, or n+1 records indexed by the position where the right part starts */
     int32_t *leaf_rec; /* NULL, or for the leaf starting at position b: parent position * 2 + side */
 } tree_ctx;
+
+/* Split dimension by variance, the rule of the randomized KD-tree that Sec. 3.2 takes over
+ * (its trees differ from that one in the leaf size only): estimate every dimension's variance
+ * on a sample of the node's points, keep the five dimensions with the largest one and let the
+ * node's draw choose among them.  Made exact here: the sample is the first 100 positions of
+ * the node (all of them if it has fewer), the coordinates are the quantised ones, the
+ * variances are compared as the integers m * sum(q^2) - sum(q)^2, equal ones by the smaller
+ * dimension. */
+static int32_t variance_dim(const tree_ctx *c, int64_t b, int64_t e, uint64_t draw)
+{
+    int64_t m = e - b < 100 ? e - b : 100;
+    int32_t top[5], n_top = 0;
+    __int128 topv[5];
+    for (int32_t j = 0; j < c->d; ++j) {
+        __int128 s = 0, s2 = 0;
+        for (int64_t p = b; p < b + m; ++p) {
+            int64_t q = quantise(c->X[(int64_t)c->perm[p] * c->d + j]);
+            s += q;
+            s2 += (__int128)q * q;
+        }
+        __int128 v = (__int128)m * s2 - s * s;
+        int32_t pos = n_top; /* place among the largest so far: after every one that is >= v */
+        while (pos > 0 && topv[pos - 1] < v) --pos;
+        if (pos >= 5) continue;
+        if (n_top < 5) ++n_top;
+        for (int32_t r = n_top - 1; r > pos; --r) {
+            top[r] = top[r - 1];
+            topv[r] = topv[r - 1];
+        }
+        top[pos] = j;
+        topv[pos] = v;
+    }
+    return top[draw % (uint64_t)n_top];
+}
 
 /* Returns the position where the node's right part starts (internal node) or
  * ~(start position) for a leaf; the caller links it. */
@@ -134,7 +169,8 @@ static int64_t build_node(tree_ctx *c, uint64_t heap_id, int32_t depth, int64_t 
     int32_t dim = -1;
     int64_t sum = 0;
     if (depth < 60) {
-        dim = (int32_t)(oracle_node_rand(c->seed, c->tree, heap_id) % (uint64_t)c->d);
+        uint64_t draw = oracle_node_rand(c->seed, c->tree, heap_id);
+        dim = c->split_rule == 1 ? variance_dim(c, b, e, draw) : (int32_t)(draw % (uint64_t)c->d);
         for (int64_t p = b; p < e; ++p) sum += quantise(c->X[(int64_t)c->perm[p] * c->d + dim]);
         int64_t nl = 0, nr = 0;
         for (int64_t p = b; p < e; ++p) { /* stable: both parts keep their order */
@@ -172,11 +208,12 @@ static int64_t build_node(tree_ctx *c, uint64_t heap_id, int32_t depth, int64_t 
  * nodes (may be NULL): [T][n+1] internal nodes, numbered as described at
  * oracle_node; leaf_up (NULL iff nodes is): [T][n+1], for leaf l the number of its
  * parent node * 2 + (1 if l is the right child), -1 if the tree is one leaf. */
-int oracle_build_trees_nodes(const float *X, int64_t n, int32_t d, int32_t T, int32_t S,
-                             uint64_t seed, int32_t *perm, int32_t *leaf_off, int32_t *n_leaves,
-                             oracle_node *nodes, int32_t *leaf_up)
+int oracle_build_trees_rule(const float *X, int64_t n, int32_t d, int32_t T, int32_t S,
+                            uint64_t seed, int32_t split_rule, int32_t *perm, int32_t *leaf_off,
+                            int32_t *n_leaves, oracle_node *nodes, int32_t *leaf_up)
 {
     if (!X || n < 1 || d < 1 || T < 1 || S < 1 || (!nodes) != (!leaf_up)) return -1;
+    if (split_rule != 0 && split_rule != 1) return -1;
     /* domain of the exact mean test: finite, |x| < 2^20 (so |q| <= 2^40), and n * |x| < 2^43, so
      * that cnt * q(x) and the sum of q over a node stay below 2^63 */
     for (int64_t i = 0; i < n * d; ++i)
@@ -187,7 +224,7 @@ int oracle_build_trees_nodes(const float *X, int64_t n, int32_t d, int32_t T, in
     int32_t *lidx = nodes ? (int32_t *)malloc((size_t)(n + 1) * sizeof(int32_t)) : NULL;
     if (!tmp || (nodes && (!rec || !leaf_rec || !lidx))) return -4;
     for (int32_t t = 0; t < T; ++t) {
-        tree_ctx c = {X, n, d, S, t, seed, perm + (int64_t)t * n, tmp,
+        tree_ctx c = {X, n, d, S, t, split_rule, seed, perm + (int64_t)t * n, tmp,
                       leaf_off + (int64_t)t * (n + 1), 0, rec, leaf_rec};
         for (int64_t i = 0; i < n; ++i) c.perm[i] = (int32_t)i;
         if (nodes)
@@ -216,6 +253,13 @@ int oracle_build_trees_nodes(const float *X, int64_t n, int32_t d, int32_t T, in
     free(leaf_rec);
     free(lidx);
     return 0;
+}
+
+int oracle_build_trees_nodes(const float *X, int64_t n, int32_t d, int32_t T, int32_t S,
+                             uint64_t seed, int32_t *perm, int32_t *leaf_off, int32_t *n_leaves,
+                             oracle_node *nodes, int32_t *leaf_up)
+{
+    return oracle_build_trees_rule(X, n, d, T, S, seed, 0, perm, leaf_off, n_leaves, nodes, leaf_up);
 }
 
 int oracle_build_trees(const float *X, int64_t n, int32_t d, int32_t T, int32_t S, uint64_t seed,

@@ -39,7 +39,8 @@ MUTANTS = [
     ("trees: a node of exactly S points is split",
      "if (cnt <= c->S) {", "if (cnt < c->S) {", TREES),
     ("trees: split dimension drawn from the parent's number",
-     "oracle_node_rand(c->seed, c->tree, heap_id) %", "oracle_node_rand(c->seed, c->tree, heap_id >> 1) %", TREES),
+     "uint64_t draw = oracle_node_rand(c->seed, c->tree, heap_id);",
+     "uint64_t draw = oracle_node_rand(c->seed, c->tree, heap_id >> 1);", TREES),
     ("trees: degenerate split puts the odd point on the left",
      "mid = b + cnt / 2; /* degenerate", "mid = b + (cnt + 1) / 2; /* degenerate", TREES),
     ("trees: coordinates rounded to 2^-19 instead of 2^-20",
@@ -47,6 +48,18 @@ MUTANTS = [
     ("trees: right part written back in reverse order (partition not stable)",
      "memcpy(c->perm + b + nl, c->tmp, (size_t)nr * sizeof(int32_t));",
      "for (int64_t r = 0; r < nr; ++r) c->perm[b + nl + r] = c->tmp[nr - 1 - r];", TREES),
+    ("trees, variance rule: the square of the sum is not taken off",
+     "__int128 v = (__int128)m * s2 - s * s;", "__int128 v = (__int128)m * s2;", TREES),
+    ("trees, variance rule: the whole node is the sample",
+     "int64_t m = e - b < 100 ? e - b : 100;", "int64_t m = e - b;", TREES),
+    ("trees, variance rule: the smallest variances are kept",
+     "while (pos > 0 && topv[pos - 1] < v) --pos;", "while (pos > 0 && topv[pos - 1] > v) --pos;", TREES),
+    ("trees, variance rule: of equal variances the later dimension comes first",
+     "while (pos > 0 && topv[pos - 1] < v) --pos;", "while (pos > 0 && topv[pos - 1] <= v) --pos;", TREES),
+    ("trees, variance rule: squares added in 64 bits",
+     "s2 += (__int128)q * q;", "s2 += (__int128)(int64_t)((uint64_t)q * (uint64_t)q);", TREES),
+    ("trees, variance rule: four candidates instead of five",
+     "return top[draw % (uint64_t)n_top];", "return top[draw % (uint64_t)(n_top > 4 ? 4 : n_top)];", TREES),
     ("lists: equal distances ordered by the larger id",
      "(da == db && ia < ib)", "(da == db && ia > ib)", GRAPH),
     ("lists: an id already present is entered again",

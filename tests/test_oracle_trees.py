@@ -60,7 +60,21 @@ def q(x):
     return round(float(x) * 1048576.0)
 
 
-def rederive(X, T, S, seed):
+def variance_dim(X, ids, draw):
+    """The split dimension by variance in Python integers: over the node's first 100 ids, the five
+    dimensions with the largest m * sum(q^2) - sum(q)^2 (equal ones: smaller dimension first); the
+    node's draw picks among them."""
+    sample = ids[:100]
+    m = len(sample)
+    var = []
+    for j in range(X.shape[1]):
+        qs = [q(X[i, j]) for i in sample]
+        var.append(m * sum(v * v for v in qs) - sum(qs) ** 2)
+    order = sorted(range(X.shape[1]), key=lambda j: (-var[j], j))[:5]
+    return order[draw % len(order)]
+
+
+def rederive(X, T, S, seed, split_rule=0):
     """Top-down rebuild with Python integers: every segment of every tree must be
     sorted(left ids) ++ sorted(right ids) of the mean split on the node's dimension."""
     n, d = X.shape
@@ -73,7 +87,8 @@ def rederive(X, T, S, seed):
                 off.append(len(out))
                 out.extend(ids)
                 return
-            dim = oracle.node_rand(seed, t, h) % d
+            draw = oracle.node_rand(seed, t, h)
+            dim = variance_dim(X, ids, draw) if split_rule == 1 else draw % d
             qs = [q(X[i, dim]) for i in ids]
             tot = sum(qs)
             left = [i for i, v in zip(ids, qs) if len(ids) * v < tot]
@@ -99,6 +114,76 @@ def test_rederivation_in_python_integers(name, n, T, S):
     for t in range(T):
         assert perm[t].tolist() == perms[t]
         assert off[t, :nl[t] + 1].tolist() == offs[t]
+
+
+@pytest.mark.parametrize("name,n,T,S", [("gmm10k_d32", 1500, 3, 8), ("sift100k_like", 1200, 2, 16),
+                                         ("mixed4m_d96", 900, 2, 64)])
+def test_variance_rule_rederivation_in_python_integers(name, n, T, S):
+    X = synth.generate(name, n=n)
+    perm, off, nl = oracle.build_trees(X, T=T, S=S, seed=synth.ALGO_SEED, split_rule=1)
+    perms, offs = rederive(X, T, S, synth.ALGO_SEED, split_rule=1)
+    for t in range(T):
+        assert perm[t].tolist() == perms[t]
+        assert off[t, :nl[t] + 1].tolist() == offs[t]
+    plain, _, _ = oracle.build_trees(X, T=T, S=S, seed=synth.ALGO_SEED)
+    assert not np.array_equal(plain, perm)
+
+
+def root_dim(nodes_t, nl_t):
+    roots = [int(nd["dim"]) for nd in nodes_t[1:nl_t] if nd["parent"] == -1]
+    assert len(roots) == 1
+    return roots[0]
+
+
+def test_variance_rule_hand_cases():
+    rng = np.random.default_rng(8)
+    # five dimensions spread widely, the others hardly: every split is on one of the five,
+    # and the draws use all of them
+    wide = [3, 7, 11, 20, 30]
+    X = (0.05 * rng.standard_normal((4000, 32))).astype(np.float32)
+    X[:, wide] = (10.0 * rng.standard_normal((4000, 5))).astype(np.float32)
+    _, _, nl, nodes, _ = oracle.build_trees_nodes(X, T=3, S=8, seed=5, split_rule=1)
+    seen = set()
+    for t in range(3):
+        dims = nodes[t, 1:nl[t]]["dim"]
+        assert set(dims.tolist()) <= set(wide)
+        seen |= set(dims.tolist())
+    assert seen == set(wide)
+    # a constant dimension among six: never one of the five
+    X = rng.standard_normal((600, 6)).astype(np.float32)
+    X[:, 2] = 1.5
+    _, _, nl, nodes, _ = oracle.build_trees_nodes(X, T=4, S=4, seed=1, split_rule=1)
+    for t in range(4):
+        assert 2 not in nodes[t, 1:nl[t]]["dim"].tolist()
+    # two dimensions: the order is by variance, the root's draw picks the place in it
+    X = np.stack([np.arange(40, dtype=np.float32), 100.0 * ((np.arange(40) * 7) % 40).astype(np.float32)], axis=1)
+    for seed in range(6):
+        _, _, nl, nodes, _ = oracle.build_trees_nodes(X, T=1, S=20, seed=seed, split_rule=1)
+        assert root_dim(nodes[0], nl[0]) == [1, 0][oracle.node_rand(seed, 0, 1) % 2]
+    # the variance is taken about the mean: a far-off but narrow dimension loses to a wide one at zero
+    X = np.stack([1000.0 + 0.01 * np.arange(30), np.arange(30) - 15.0], axis=1).astype(np.float32)
+    for seed in range(4):
+        _, _, nl, nodes, _ = oracle.build_trees_nodes(X, T=1, S=15, seed=seed, split_rule=1)
+        assert root_dim(nodes[0], nl[0]) == [1, 0][oracle.node_rand(seed, 0, 1) % 2]
+    # only the first 100 points of a node are looked at
+    X = np.zeros((300, 2), dtype=np.float32)
+    X[:100, 0] = np.arange(100)
+    X[100:, 1] = 1000.0 * np.arange(200)
+    for seed in range(4):
+        _, _, nl, nodes, _ = oracle.build_trees_nodes(X, T=1, S=150, seed=seed, split_rule=1)
+        assert root_dim(nodes[0], nl[0]) == [0, 1][oracle.node_rand(seed, 0, 1) % 2]
+    # equal variances: the smaller dimension comes first
+    col = rng.standard_normal(50).astype(np.float32)
+    X = np.stack([col, col, col], axis=1)
+    for seed in range(6):
+        _, _, nl, nodes, _ = oracle.build_trees_nodes(X, T=1, S=25, seed=seed, split_rule=1)
+        assert root_dim(nodes[0], nl[0]) == oracle.node_rand(seed, 0, 1) % 3
+    # large coordinates: the squares need more than 64 bits
+    X = (rng.integers(-2**19, 2**19, size=(500, 8)).astype(np.float32) + 0.5)
+    X[:, 5] *= 1e-3
+    perm, off, nl = oracle.build_trees(X, T=2, S=10, seed=2, split_rule=1)
+    perms, offs = rederive(X, 2, 10, 2, split_rule=1)
+    assert perm[0].tolist() == perms[0] and perm[1].tolist() == perms[1]
 
 
 def test_structural_invariants_and_randomisation():
