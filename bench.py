@@ -209,6 +209,10 @@ def main():
                          "the tree-built initial graph and from a seeded random graph (the starting point of "
                          "plain NN-descent) and add an `ablation_init` object: time and recall after every "
                          "iteration of both")
+    ap.add_argument("--ablation-split", type=int, default=0, metavar="ITERS",
+                    help="also build the trees with the split dimension taken among the five of largest "
+                         "variance (Sec. 3.2) and add an `ablation_split` object: tree time, accuracy of the "
+                         "initial graph and after every one of ITERS iterations, for both rules")
     ap.add_argument("--ablation-marking", type=int, default=0, metavar="ITERS",
                     help="after the build, run NN-descent one iteration at a time for ITERS iterations with fresh "
                          "entries always marked new (the default) and with the literal marking of Alg. 4 (what a new "
@@ -384,6 +388,31 @@ def main():
                                       "recall_at_K": recall_m(g)})
             marking[label] = curve
 
+    split = None
+    if args.ablation_split > 0:
+        rows_s = torch.from_numpy(synth.sample_rows(n, max(1000, args.recall_rows))).to(dev)
+        truth_s = exact_knn_torch(Xd, rows_s, K)
+
+        def recall_s(g):
+            got = efanna.efanna_get_graph(g)[0][rows_s].cpu().numpy()
+            return sum(np.intersect1d(a[a >= 0], b).shape[0] for a, b in zip(got, truth_s)) / float(truth_s.size)
+
+        split = {"recall_rows": int(rows_s.shape[0])}
+        for label, rule in (("uniform", efanna.SPLIT_UNIFORM), ("variance", efanna.SPLIT_VARIANCE)):
+            for rep_ in range(2):      # the first round warms up
+                torch.cuda.synchronize()
+                a0 = time.perf_counter()
+                trees = efanna.efanna_build_trees_rule(Xd, T, S, synth.ALGO_SEED, rule, max_leaves=max_leaves,
+                                                       workspace=ws_tree)
+                torch.cuda.synchronize()
+                trees_ms = (time.perf_counter() - a0) * 1e3
+                g = efanna.efanna_init_graph(Xd, trees[0], trees[1], trees[2], S, K, workspace=ws_init)
+                curve = [{"iterations": 0, "recall_at_K": recall_s(g)}]
+                for it in range(args.ablation_split):
+                    efanna.efanna_nndescent(Xd, g, 1, L, synth.ALGO_SEED, first_iter=it, workspace=ws_nnd)
+                    curve.append({"iterations": it + 1, "recall_at_K": recall_s(g)})
+            split[label] = {"trees_ms": trees_ms, "curve": curve}
+
     # the other configurations: a build each on the same GPU, after the headline's buffers are gone
     others_arg = args.others
     if others_arg is None:
@@ -453,6 +482,8 @@ def main():
         out["search"] = search
     if ablation is not None:
         out["ablation_init"] = ablation
+    if split is not None:
+        out["ablation_split"] = split
     if marking is not None:
         out["ablation_marking"] = marking
     print(json.dumps(out))

@@ -123,6 +123,24 @@ int efanna_build_trees(const float *X, int64_t n, int32_t d, int32_t n_trees, in
                        int32_t *n_leaves, efanna_node *nodes, int32_t *leaf_up,
                        int32_t *tree_depth, void *ws, size_t ws_bytes, void *stream);
 
+/* The same with a choice of how a node takes its split dimension (Section 3.2: the trees
+ * are the randomized KD-trees of the literature except for the leaf size).
+ * split_rule EFANNA_SPLIT_UNIFORM: drawn uniformly over the d dimensions, Alg. 2 as printed
+ *          (what efanna_build_trees does).
+ * split_rule EFANNA_SPLIT_VARIANCE: that tree's own rule - among the five dimensions of largest
+ *          variance the node's draw picks one.  The variance is estimated on the node's first
+ *          100 positions (all of them in a smaller node), exactly: as the integer
+ *          m*sum(q^2) - sum(q)^2 of the quantised coordinates, equal values ordered by the
+ *          smaller dimension; with d < 5 all dimensions are candidates, in that order.
+ * Any other value: EFANNA_EINVAL.  Everything else as efanna_build_trees. */
+#define EFANNA_SPLIT_UNIFORM 0
+#define EFANNA_SPLIT_VARIANCE 1
+int efanna_build_trees_rule(const float *X, int64_t n, int32_t d, int32_t n_trees, int32_t leaf_size,
+                            uint64_t seed, int32_t split_rule, int32_t *perm, int32_t *leaf_off,
+                            int32_t max_leaves, int32_t *n_leaves, efanna_node *nodes,
+                            int32_t *leaf_up, int32_t *tree_depth, void *ws, size_t ws_bytes,
+                            void *stream);
+
 /* ---- Alg. 3, conquer step ---------------------------------------------------------------
  * Candidates of point i: in every tree, the other members of its leaf and - when nodes is
  * given - for every ancestor N of that leaf with depth >= conquer_depth, the members of the

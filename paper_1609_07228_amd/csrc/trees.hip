@@ -119,8 +119,100 @@ transpose_check_kernel(const float *__restrict__ X, int n, int d, float *__restr
     if (__any(bad) && ef_lane() == 0) atomicOr(&c->bad_input, 1);
 }
 
+// ---------------------------------------------------------------------------------------
+// Split dimension by variance (split_rule 1), the rule of the randomized KD-tree that Sec. 3.2
+// takes over: over the node's first kVarSample positions, the kVarDims dimensions with the
+// largest integer variance m * sum(q^2) - sum(q)^2 of the quantised coordinates (equal ones:
+// the smaller dimension first); the node's draw picks one of them.  One whole wave per node:
+// lane l takes dimensions l, l + 64, ... and keeps its own best five in registers, then five
+// rounds of a wave-wide maximum pop the overall order.  `ids` may point into LDS or global
+// memory; every lane of the wave must call with the same arguments.
+constexpr int kVarSample = 100, kVarDims = 5;
+constexpr int kDimPending = -2;      // Node::dim of a node whose dimension is still to be chosen
+
+struct VarKey {
+    __int128 v;
+    int j;
+};
+__device__ inline bool var_before(const VarKey &a, const VarKey &b)
+{
+    return a.v > b.v || (a.v == b.v && a.j < b.j);
+}
+
+__device__ inline int variance_dim_wave(const float *__restrict__ X, int d, const int *ids, int cnt, u64 draw)
+{
+    const int lane = ef_lane();
+    const int m = cnt < kVarSample ? cnt : kVarSample;
+    VarKey top[kVarDims];
+#pragma unroll
+    for (int r = 0; r < kVarDims; ++r) {
+        top[r].v = -1;      // below every variance
+        top[r].j = 0x7FFFFFFF;
+    }
+    for (int j = lane; j < d; j += EF_WAVE) {
+        long long s1 = 0;
+        __int128 s2 = 0;
+        for (int p = 0; p < m; ++p) {
+            const long long q = ef_quantise(X[(size_t)ids[p] * d + j]);
+            s1 += q;
+            s2 += (__int128)q * q;
+        }
+        VarKey c;
+        c.v = (__int128)m * s2 - (__int128)s1 * s1;
+        c.j = j;
+#pragma unroll
+        for (int r = 0; r < kVarDims; ++r)
+            if (var_before(c, top[r])) {
+                const VarKey t = top[r];
+                top[r] = c;
+                c = t;
+            }
+    }
+    const int n_top = d < kVarDims ? d : kVarDims;
+    const int want = (int)(draw % (u64)n_top);
+    int chosen = 0;
+    for (int r = 0; r < n_top; ++r) {      // (uniform)
+        VarKey best = top[0];
+        for (int o = EF_WAVE / 2; o >= 1; o >>= 1) {
+            VarKey other;
+            const u64 lo = __shfl_xor((u64)best.v, o, EF_WAVE);
+            const u64 hi = __shfl_xor((u64)(best.v >> 64), o, EF_WAVE);
+            other.v = (__int128)(((unsigned __int128)hi << 64) | lo);
+            other.j = __shfl_xor(best.j, o, EF_WAVE);
+            if (var_before(other, best)) best = other;
+        }
+        if (r == want) chosen = best.j;
+        if (top[0].j == best.j) {      // the winner's lane moves on to its next one
+#pragma unroll
+            for (int q = 0; q + 1 < kVarDims; ++q) top[q] = top[q + 1];
+            top[kVarDims - 1].v = -1;
+            top[kVarDims - 1].j = 0x7FFFFFFF;
+        }
+    }
+    return chosen;
+}
+
+// One wave per live node of the level: fixes the dimension of the nodes that wait for one.
+__global__ void __launch_bounds__(kBlock)
+choose_dims_kernel(const float *__restrict__ X, int d, int n, const int *__restrict__ perm, Node *nodes,
+                   int *dims, const Counters *c, int level, u64 seed)
+{
+    const int n_cur = c->n_nodes[level & 1];
+    const int n_waves = gridDim.x * (kBlock / EF_WAVE);
+    for (int s = blockIdx.x * (kBlock / EF_WAVE) + threadIdx.x / EF_WAVE; s < n_cur; s += n_waves) {
+        const int b = nodes[s].b, e = nodes[s].e;
+        if (nodes[s].dim != kDimPending) continue;      // (uniform)
+        const u64 draw = ef_mix64(ef_stream_key(seed, b / n) + nodes[s].heap);
+        const int dim = variance_dim_wave(X, d, perm + b, e - b, draw);
+        if (ef_lane() == 0) {
+            nodes[s].dim = dim;
+            dims[s] = dim;
+        }
+    }
+}
+
 __global__ void roots_kernel(Node *nodes, int *dims, int *node_of, unsigned char *leaf_flag, int n,
-                             int T, int S, int fin, SmallNode *small, u64 seed, int d, Counters *c)
+                             int T, int S, int fin, SmallNode *small, u64 seed, int d, Counters *c, int rule)
 {
     size_t p = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
     size_t total = (size_t)n * T;
@@ -145,7 +237,7 @@ __global__ void roots_kernel(Node *nodes, int *dims, int *node_of, unsigned char
         nd.e = nd.b + n;
         nd.heap = 1;
         nd.sum = 0;
-        nd.dim = (int)(ef_mix64(ef_stream_key(seed, (int)p) + 1) % (u64)d);
+        nd.dim = rule == 1 ? kDimPending : (int)(ef_mix64(ef_stream_key(seed, (int)p) + 1) % (u64)d);
         nd.depth = 0;
         nd.mid = nd.b;
         nd.moved = 0;
@@ -343,7 +435,7 @@ __global__ void scan_apply_kernel(Pred pred, size_t total, const int *block_sums
 __global__ void children_kernel(Node *cur, int level, Node *next, int *next_dims,
                                 const int *__restrict__ lcount,
                                 unsigned char *leaf_flag, int S, int fin, SmallNode *small, u64 seed,
-                                int n, int d, Counters *c, NodeRec *rec, int *leaf_rec)
+                                int n, int d, Counters *c, NodeRec *rec, int *leaf_rec, int rule)
 {
     int s = blockIdx.x * blockDim.x + threadIdx.x;
     int kind[2] = {0, 0};      // 0 leaf, 1 finished later inside one workgroup, 2 next level
@@ -393,7 +485,7 @@ __global__ void children_kernel(Node *cur, int level, Node *next, int *next_dims
             ch.e = ce;
             ch.depth = nd.depth + 1;
             ch.heap = ch_heap;
-            ch.dim = ch.depth < 60 ? (int)(ef_mix64(key + ch.heap) % (u64)d) : -1;
+            ch.dim = ch.depth < 60 ? (rule == 1 ? kDimPending : (int)(ef_mix64(key + ch.heap) % (u64)d)) : -1;
             ch.sum = 0;
             ch.mid = cb;
             ch.moved = 0;
@@ -460,7 +552,7 @@ struct LNode {
 __global__ void __launch_bounds__(kFinThreads)
 finish_kernel(const float *__restrict__ XT, int d, int *perm, const SmallNode *__restrict__ small,
               unsigned char *leaf_flag, int S, u64 seed, int n, NodeRec *rec, int *leaf_rec,
-              int *max_depth)
+              int *max_depth, const float *__restrict__ X, int rule)
 {
     // One 16-byte aligned LDS block carved by hand (no separate static LDS variables, whose
     // size would shift the 8-byte node records off their alignment).
@@ -488,7 +580,7 @@ finish_kernel(const float *__restrict__ XT, int d, int *perm, const SmallNode *_
         r.heap = seg.heap;
         r.sum = 0;
         r.depth = seg.depth;
-        r.dim = seg.depth < 60 ? (int)(ef_mix64(key + seg.heap) % (u64)d) : -1;
+        r.dim = seg.depth < 60 ? (rule == 1 ? kDimPending : (int)(ef_mix64(key + seg.heap) % (u64)d)) : -1;
         r.child[0] = r.child[1] = -1;
         r.parent = seg.parent;
         r.pad = 0;
@@ -503,6 +595,15 @@ finish_kernel(const float *__restrict__ XT, int d, int *perm, const SmallNode *_
         int *idc = ids_base + cur * kFinMax, *idn = ids_base + (cur ^ 1) * kFinMax;
         int *nc = nidx_base + cur * kFinMax, *nn = nidx_base + (cur ^ 1) * kFinMax;
         LNode *tc = tabs_base + cur * kFinNodes, *tn = tabs_base + (cur ^ 1) * kFinNodes;
+        // 0. split dimensions by variance, one wave per node
+        if (rule == 1) {
+            for (int k = tid / EF_WAVE; k < n_cur; k += kFinThreads / EF_WAVE) {
+                if (tc[k].dim != kDimPending) continue;      // (uniform)
+                const int dim = variance_dim_wave(X, d, idc + tc[k].b, tc[k].e - tc[k].b, ef_mix64(key + tc[k].heap));
+                if (ef_lane() == 0) tc[k].dim = dim;
+            }
+            __syncthreads();
+        }
         // 1. sums
         for (int p = tid; p < cnt; p += kFinThreads) {
             const int k = nc[p];
@@ -565,7 +666,7 @@ finish_kernel(const float *__restrict__ XT, int d, int *perm, const SmallNode *_
                     ch.moved = 0;
                     ch.depth = nd.depth + 1;
                     ch.heap = nd.depth < 60 ? 2 * nd.heap + side : nd.heap;
-                    ch.dim = ch.depth < 60 ? (int)(ef_mix64(key + ch.heap) % (u64)d) : -1;
+                    ch.dim = ch.depth < 60 ? (rule == 1 ? kDimPending : (int)(ef_mix64(key + ch.heap) % (u64)d)) : -1;
                     ch.sum = 0;
                     ch.child[0] = ch.child[1] = -1;
                     ch.parent = seg.b + nd.mid;
@@ -743,13 +844,14 @@ extern "C" size_t efanna_trees_workspace_bytes(int64_t n, int32_t d, int32_t n_t
     return carve(nullptr, n, d, n_trees, leaf_size, with_nodes != 0).bytes;
 }
 
-extern "C" int efanna_build_trees(const float *X, int64_t n, int32_t d, int32_t n_trees,
-                                  int32_t leaf_size, uint64_t seed, int32_t *perm,
-                                  int32_t *leaf_off, int32_t max_leaves, int32_t *n_leaves,
-                                  efanna_node *nodes, int32_t *leaf_up, int32_t *tree_depth,
-                                  void *ws, size_t ws_bytes, void *stream)
+extern "C" int efanna_build_trees_rule(const float *X, int64_t n, int32_t d, int32_t n_trees,
+                                       int32_t leaf_size, uint64_t seed, int32_t split_rule, int32_t *perm,
+                                       int32_t *leaf_off, int32_t max_leaves, int32_t *n_leaves,
+                                       efanna_node *nodes, int32_t *leaf_up, int32_t *tree_depth,
+                                       void *ws, size_t ws_bytes, void *stream)
 {
     if (!X || !perm || !leaf_off || !n_leaves || (!nodes) != (!leaf_up)) return EFANNA_EINVAL;
+    if (split_rule != EFANNA_SPLIT_UNIFORM && split_rule != EFANNA_SPLIT_VARIANCE) return EFANNA_EINVAL;
     if (n < 1 || d < 1 || n_trees < 1 || n_trees > EFANNA_MAX_TREES || leaf_size < 1 ||
         leaf_size > EFANNA_MAX_LEAF || max_leaves < 1)
         return EFANNA_EINVAL;
@@ -770,7 +872,7 @@ extern "C" int efanna_build_trees(const float *X, int64_t n, int32_t d, int32_t 
     iota_kernel<<<grid_pos, kBlock, 0, st>>>(perm, (int)n, total);
     const int fin = finish_limit(S);
     roots_kernel<<<grid_pos, kBlock, 0, st>>>(w.nodes_a, w.dims_a, w.node_a, w.leaf_flag, (int)n, T, S, fin,
-                                              w.small, seed, d, w.counters);
+                                              w.small, seed, d, w.counters, split_rule);
     // The level counters are read into pinned host memory (one small buffer per calling thread,
     // kept for the life of the process): a copy to pageable memory is staged and takes some 20 us
     // longer, during which the GPU has nothing to do.  Without pinned memory: a local variable.
@@ -802,13 +904,16 @@ extern "C" int efanna_build_trees(const float *X, int64_t n, int32_t d, int32_t 
     for (int level = 0; n_cur > 0; ++level) {
         // sixteen tiles per block while nodes are a million positions and more (levels 0..3 of the headline)
         const int tiles = (total >> level) / (size_t)T >= (size_t)kBlock * 256 ? 16 : 1;
+        if (split_rule == EFANNA_SPLIT_VARIANCE)
+            choose_dims_kernel<<<min(grid_nodes * (kBlock / EF_WAVE), 2048), kBlock, 0, st>>>(
+                X, d, (int)n, perm_cur, nodes_cur, dims_cur, w.counters, level, seed);
         sum_kernel<<<(grid_pos + tiles - 1) / tiles, kBlock, 0, st>>>(w.xt, (int)n, perm_cur, node_cur, nodes_cur,
                                                                       dims_cur, w.val, total, w.counters, level, tiles);
         LeftPred pred{node_cur, nodes_cur, w.val};
         device_scan(pred, total, w.block_sums, w.lcount, w.left_bits, st);
         children_kernel<<<grid_nodes, kBlock, 0, st>>>(
             nodes_cur, level, nodes_nxt, dims_nxt, w.lcount, w.leaf_flag, S, fin, w.small, seed, (int)n, d,
-            w.counters, w.rec, w.leaf_rec);
+            w.counters, w.rec, w.leaf_rec, split_rule);
         scatter_kernel<<<grid_pos, kBlock, 0, st>>>(perm_cur, perm_nxt, node_cur, node_nxt, nodes_cur,
                                                     w.left_bits, w.lcount, total);
         if (level + 1 >= sure) {
@@ -828,7 +933,7 @@ extern "C" int efanna_build_trees(const float *X, int64_t n, int32_t d, int32_t 
                                          hipFuncAttributeMaxDynamicSharedMemorySize, (int)fin_lds));
         finish_kernel<<<host_c.small_nodes, kFinThreads, fin_lds, st>>>(w.xt, d, perm_cur, w.small, w.leaf_flag,
                                                                   S, seed, (int)n, w.rec, w.leaf_rec,
-                                                                  &w.counters->max_depth);
+                                                                  &w.counters->max_depth, X, split_rule);
     }
     if (perm_cur != perm)
         EF_HIP_CHECK(hipMemcpyAsync(perm, perm_cur, total * 4, hipMemcpyDeviceToDevice, st));
@@ -852,4 +957,14 @@ extern "C" int efanna_build_trees(const float *X, int64_t n, int32_t d, int32_t 
     for (int t = 0; t < T; ++t)
         if (n_leaves[t] > max_leaves) return EFANNA_ECAPACITY;
     return EFANNA_OK;
+}
+
+extern "C" int efanna_build_trees(const float *X, int64_t n, int32_t d, int32_t n_trees,
+                                  int32_t leaf_size, uint64_t seed, int32_t *perm,
+                                  int32_t *leaf_off, int32_t max_leaves, int32_t *n_leaves,
+                                  efanna_node *nodes, int32_t *leaf_up, int32_t *tree_depth,
+                                  void *ws, size_t ws_bytes, void *stream)
+{
+    return efanna_build_trees_rule(X, n, d, n_trees, leaf_size, seed, EFANNA_SPLIT_UNIFORM, perm, leaf_off,
+                                   max_leaves, n_leaves, nodes, leaf_up, tree_depth, ws, ws_bytes, stream);
 }

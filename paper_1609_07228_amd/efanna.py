@@ -20,7 +20,7 @@ STATUS = {0: "EFANNA_OK", -1: "EFANNA_EINVAL", -2: "EFANNA_EWORKSPACE", -3: "EFA
           -4: "EFANNA_EHIP", -5: "EFANNA_ECAPACITY", -6: "EFANNA_EUNSUPPORTED", -7: "EFANNA_ESCRATCH"}
 
 # every symbol include/efanna.h declares
-SYMBOLS = ["efanna_status_string", "efanna_trees_workspace_bytes", "efanna_build_trees",
+SYMBOLS = ["efanna_status_string", "efanna_trees_workspace_bytes", "efanna_build_trees", "efanna_build_trees_rule",
            "efanna_init_workspace_bytes", "efanna_init_graph", "efanna_nndescent_workspace_bytes",
            "efanna_nndescent", "efanna_nndescent_noalloc", "efanna_get_graph", "efanna_set_graph", "efanna_pair_distances",
            "efanna_search_workspace_bytes", "efanna_search"]
@@ -49,6 +49,8 @@ def lib():
         L.efanna_trees_workspace_bytes.argtypes = [i64, i32, i32, i32, i32]
         L.efanna_build_trees.restype = C.c_int
         L.efanna_build_trees.argtypes = [vp, i64, i32, i32, i32, u64, vp, vp, i32, vp, vp, vp, vp, vp, sz, vp]
+        L.efanna_build_trees_rule.restype = C.c_int
+        L.efanna_build_trees_rule.argtypes = [vp, i64, i32, i32, i32, u64, i32, vp, vp, i32, vp, vp, vp, vp, vp, sz, vp]
         L.efanna_init_workspace_bytes.restype = sz
         L.efanna_init_workspace_bytes.argtypes = [i64, i32]
         L.efanna_init_graph.restype = C.c_int
@@ -99,9 +101,21 @@ def _workspace(nbytes: int, device) -> torch.Tensor:
 NODE_BYTES = 32      # sizeof(efanna_node): int64 sum; int32 dim, cnt, parent, depth, child[2]
 
 
+SPLIT_UNIFORM, SPLIT_VARIANCE = 0, 1
+
+
+def efanna_build_trees_rule(X: torch.Tensor, n_trees: int, leaf_size: int, seed: int, split_rule: int,
+                            max_leaves: int | None = None, workspace: torch.Tensor | None = None,
+                            with_nodes: bool = False):
+    """Alg. 2 with the split dimension taken by `split_rule` (SPLIT_UNIFORM: drawn over all d,
+    SPLIT_VARIANCE: drawn among the five dimensions of largest variance).  Returns what
+    efanna_build_trees returns."""
+    return efanna_build_trees(X, n_trees, leaf_size, seed, max_leaves, workspace, with_nodes, _rule=int(split_rule))
+
+
 def efanna_build_trees(X: torch.Tensor, n_trees: int, leaf_size: int, seed: int,
                        max_leaves: int | None = None, workspace: torch.Tensor | None = None,
-                       with_nodes: bool = False):
+                       with_nodes: bool = False, _rule: int | None = None):
     """Alg. 2.  Returns (perm [T,n] int32 device, leaf_off [T,max_leaves+1] int32 device,
     n_leaves [T] int32 numpy) and, with_nodes, also (nodes [T,max_leaves+1,32] uint8 device
     holding efanna_node records, leaf_up [T,max_leaves+1] int32 device, tree_depth int: depth of
@@ -119,12 +133,14 @@ def efanna_build_trees(X: torch.Tensor, n_trees: int, leaf_size: int, seed: int,
     depth = C.c_int32(-1)
     need = lib().efanna_trees_workspace_bytes(n, d, n_trees, leaf_size, 1 if with_nodes else 0)
     ws = _workspace(need, X.device) if workspace is None else workspace
-    _check(lib().efanna_build_trees(X.data_ptr(), n, d, n_trees, leaf_size, seed, perm.data_ptr(),
-                                    leaf_off.data_ptr(), max_leaves,
-                                    n_leaves.ctypes.data_as(C.c_void_p),
-                                    nodes.data_ptr() if with_nodes else None,
-                                    leaf_up.data_ptr() if with_nodes else None, C.byref(depth),
-                                    ws.data_ptr(), ws.numel(), _stream()), "efanna_build_trees")
+    tail = (perm.data_ptr(), leaf_off.data_ptr(), max_leaves, n_leaves.ctypes.data_as(C.c_void_p),
+            nodes.data_ptr() if with_nodes else None, leaf_up.data_ptr() if with_nodes else None,
+            C.byref(depth), ws.data_ptr(), ws.numel(), _stream())
+    if _rule is None:
+        _check(lib().efanna_build_trees(X.data_ptr(), n, d, n_trees, leaf_size, seed, *tail), "efanna_build_trees")
+    else:
+        _check(lib().efanna_build_trees_rule(X.data_ptr(), n, d, n_trees, leaf_size, seed, _rule, *tail),
+               "efanna_build_trees_rule")
     if with_nodes:
         return perm, leaf_off, n_leaves, nodes, leaf_up, int(depth.value)
     return perm, leaf_off, n_leaves

@@ -163,9 +163,12 @@ def test_init_graph_small_leaf_shapes(ef, d, S, K, T):
     oracle.check_graph_invariants(X, ids, dists)
 
 
-def tree_nodes_equal(ef, X, T, S, seed):
-    perm, off, nl, nodes, up, depth = ef.efanna_build_trees(dev(X), T, S, seed, with_nodes=True)
-    operm, ooff, onl, onodes, oup = oracle.build_trees_nodes(X, T, S, seed)
+def tree_nodes_equal(ef, X, T, S, seed, split_rule=None):
+    if split_rule is None:
+        perm, off, nl, nodes, up, depth = ef.efanna_build_trees(dev(X), T, S, seed, with_nodes=True)
+    else:
+        perm, off, nl, nodes, up, depth = ef.efanna_build_trees_rule(dev(X), T, S, seed, split_rule, with_nodes=True)
+    operm, ooff, onl, onodes, oup = oracle.build_trees_nodes(X, T, S, seed, split_rule or 0)
     assert depth == max([int(onodes[t, 1:onl[t]]["depth"].max()) for t in range(T) if onl[t] > 1], default=-1)
     assert np.array_equal(nl, onl) and np.array_equal(host(perm), operm)
     gn = host(nodes).view(oracle.NODE_DTYPE)[..., 0]
@@ -186,6 +189,36 @@ def tree_nodes_equal(ef, X, T, S, seed):
 ])
 def test_tree_nodes_bit_exact(ef, name, n, T, S):
     tree_nodes_equal(ef, synth.generate(name, n=n), T, S, synth.ALGO_SEED)
+
+
+@pytest.mark.parametrize("name,n,T,S", [
+    ("gmm10k_d32", 10_000, 4, 8),
+    ("sift100k_like", 40_000, 3, 16),      # device-wide levels and the in-LDS finish
+    ("mixed4m_d96", 20_000, 2, 64),
+    ("gist1m_like", 3_000, 2, 16),         # fifteen dimensions per lane
+    ("gmm10k_d32", 1_003, 2, 1),
+])
+def test_trees_variance_rule_bit_exact(ef, name, n, T, S):
+    X = synth.generate(name, n=n)
+    g, _ = tree_nodes_equal(ef, X, T, S, synth.ALGO_SEED, split_rule=1)
+    plain = ef.efanna_build_trees(dev(X), T, S, synth.ALGO_SEED)
+    same = ef.efanna_build_trees_rule(dev(X), T, S, synth.ALGO_SEED, 0)
+    assert torch.equal(plain[0], same[0]) and not torch.equal(plain[0], g[0])
+
+
+def test_trees_variance_rule_shapes(ef):
+    rng = np.random.default_rng(31)
+    for n, d in ((700, 3), (2_500, 5), (5_000, 70), (300, 1)):      # fewer than five dimensions; a ragged last lane round
+        X = rng.standard_normal((n, d)).astype(np.float32)
+        tree_nodes_equal(ef, X, 2, 6, 9, split_rule=1)
+    X = (rng.integers(-2**19, 2**19, size=(6_000, 8)).astype(np.float32) + 0.5)      # squares beyond 64 bits
+    X[:, 5] *= 1e-3
+    tree_nodes_equal(ef, X, 2, 10, 2, split_rule=1)
+    X = np.repeat(rng.standard_normal((40, 6)).astype(np.float32), 100, axis=0)      # equal points: zero variances, ties
+    tree_nodes_equal(ef, X, 2, 16, 4, split_rule=1)
+    with pytest.raises(ef.EfannaError) as e:
+        ef.efanna_build_trees_rule(dev(X), 2, 16, 4, 2)
+    assert e.value.status == -1
 
 
 def test_tree_nodes_edge_cases(ef):
