@@ -1730,7 +1730,7 @@ __device__ inline int propose_pair(Proposal *queue, int fill, bool mine, float d
 
 template <int NB, bool ONE, int KT>      // KT: the row length if fixed at compile time (the row scans unroll), else 0
 __global__ void __launch_bounds__(EF_WAVE) __attribute__((amdgpu_waves_per_eu(NB > 1 ? 3 : 4)))
-join_reg_kernel(const float *__restrict__ X, const float *__restrict__ norms, int d, int K_,
+join_reg_kernel(const float *__restrict__ X, int d, int K_,
                 const int *__restrict__ work, const int *__restrict__ work_count, int q_cap,
                 float margin_rel, float thr_scale, const int *__restrict__ ulist,
                 const int2 *__restrict__ ucount, int ucap, u64 *graph, u32 *worst,
@@ -1754,9 +1754,9 @@ join_reg_kernel(const float *__restrict__ X, const float *__restrict__ norms, in
     const int lane = threadIdx.x, r16 = lane & 15, g = lane >> 4, gl = r16, grp = g;
     const int dirn = (EF_ROW_ROR(r16, 1) - r16) & 15;      // a rotation by t brings row r + t * dirn to row r
     const int count = *work_count;
-    // The id list and the sizes of a point are fetched one point ahead, and the thresholds and
-    // norms of its vectors as soon as those ids are there, so that they travel while the
-    // point before is being worked on: the row loads are the only latency a point waits for.
+    // The id list and the sizes of a point are fetched one point ahead, and the thresholds of
+    // its vectors as soon as those ids are there, so that they travel while the point before
+    // is being worked on: the row loads are the only latency a point waits for.
     // (Thresholds only ever fall: one that is a point old lets a few more pairs through the
     // filter, nothing else.)
     int w = blockIdx.x;
@@ -1765,7 +1765,6 @@ join_reg_kernel(const float *__restrict__ X, const float *__restrict__ norms, in
     int2 c_pre = i >= 0 ? ucount[i] : make_int2(0, 0);
     int i_next = w + (int)gridDim.x < count ? work[w + gridDim.x] : -1;
     u32 t_pre = u_pre >= 0 ? worst[u_pre] : 0u;
-    float n_pre = u_pre >= 0 ? norms[u_pre] : 0.0f;
     // Proposals wait in the queue across points and are applied when about half of it is
     // full (and at the end): late iterations accept well under one proposal per point, and
     // a drain costs two memory round trips whatever its size.
@@ -1785,7 +1784,6 @@ join_reg_kernel(const float *__restrict__ X, const float *__restrict__ norms, in
             uid[lane] = u_cur;
             thr[lane] = t_pre;
             tf[lane] = __uint_as_float(t_pre) * thr_scale;
-            nf[lane] = n_pre * (1.0f - margin_rel);
         }
         i = i_next;
         u_pre = i >= 0 && lane < R ? ulist[(size_t)i * ucap + min(lane, ucap - 1)] : -1;
@@ -1813,6 +1811,7 @@ join_reg_kernel(const float *__restrict__ X, const float *__restrict__ norms, in
         // rotations 0..15 of rows 16..31.
         constexpr bool rotated = !ONE;
         float two[2] = {0.f, 0.f}, two_b[2] = {0.f, 0.f};
+        float nb_sq = 0.0f;      // rows 16 ..: this lane's share of |row|^2
         if (rotated) {
             float P[8][4], PB[NB > 1 ? 8 : 1][4];
 #pragma unroll
@@ -1883,6 +1882,10 @@ join_reg_kernel(const float *__restrict__ X, const float *__restrict__ norms, in
                 if (NB > 1) {
                     constexpr int Q1 = NB > 1 ? 1 : 0, Q2 = NB > 1 ? 2 : 0;
                     const float4 wb = vb[NB > 1 ? s : 0];
+                    nb_sq = __builtin_fmaf(wb.x, wb.x, nb_sq);
+                    nb_sq = __builtin_fmaf(wb.y, wb.y, nb_sq);
+                    nb_sq = __builtin_fmaf(wb.z, wb.z, nb_sq);
+                    nb_sq = __builtin_fmaf(wb.w, wb.w, nb_sq);
                     acc[Q1][0] = __builtin_amdgcn_mfma_f32_16x16x4f32(va[s].x, wb.x, acc[Q1][0], 0, 0, 0);
                     acc[Q1][1] = __builtin_amdgcn_mfma_f32_16x16x4f32(va[s].y, wb.y, acc[Q1][1], 0, 0, 0);
                     acc[Q1][0] = __builtin_amdgcn_mfma_f32_16x16x4f32(va[s].z, wb.z, acc[Q1][0], 0, 0, 0);
@@ -1896,9 +1899,26 @@ join_reg_kernel(const float *__restrict__ X, const float *__restrict__ norms, in
                 }
             }
         }
+        if (!rotated) {
+            // The filter's |row|^2 need not be gathered: for rows 0..15 it is the diagonal of Gram
+            // block (0,0) (lane (r16, g) holds G[4 g + k][r16]), for rows 16.. the four lanes of a
+            // row add the squares of their coordinates.  Both are within the filter's margin of
+            // the exact value, like the Gram entries themselves.
+            if ((r16 >> 2) == g) {
+                const int kd = r16 & 3;
+                const float dg = kd == 0 ? acc[0][0][0] + acc[0][1][0]
+                               : kd == 1 ? acc[0][0][1] + acc[0][1][1]
+                               : kd == 2 ? acc[0][0][2] + acc[0][1][2] : acc[0][0][3] + acc[0][1][3];
+                nf[r16] = dg * (1.0f - margin_rel);
+            }
+            if (NB > 1) {
+                nb_sq += __shfl_xor(nb_sq, 16, EF_WAVE);
+                nb_sq += __shfl_xor(nb_sq, 32, EF_WAVE);
+                if (g == 0) nf[16 + r16] = nb_sq * (1.0f - margin_rel);
+            }
+        }
         __syncthreads();      // uid, thr, nf, tf visible
         t_pre = u_pre >= 0 ? worst[u_pre] : 0u;      // the next point's; its ids have arrived by now
-        n_pre = u_pre >= 0 ? norms[u_pre] : 0.0f;
         // ---- filter: lane holds G[a = 16 bi + 4 g + k][b = 16 bj + r16] of block q -----------
         // pair (a, b) survives if (|a|^2 + |b|^2)(1 - margin) - 2 a.b <= max threshold * scale
         int n_surv[NQ];
@@ -2981,7 +3001,7 @@ int nndescent_run(const float *X, int64_t n, int32_t d, int32_t k, efanna_entry 
         if (reg_ok) {
 #define EF_JOIN_REG_K(NB, ONE, LIST, KT)                                                           \
     join_reg_kernel<NB, ONE, KT><<<reg_grid, EF_WAVE, reg_lds(16 * NB), st>>>(                     \
-        X, w.norms, d, K, w.work + (size_t)(LIST) * n, w.work_count + (LIST), reg_q_cap_for(16 * NB), \
+        X, d, K, w.work + (size_t)(LIST) * n, w.work_count + (LIST), reg_q_cap_for(16 * NB), \
         margin_rel, thr_scale, w.ulist, w.ucount, max_rows, graph, w.worst,                        \
         w.upd_block + (LIST) * reg_grid, mode)
     // (a row length of 10 is compiled in: 3 % off the joins of 17..32 vectors)
