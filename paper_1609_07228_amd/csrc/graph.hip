@@ -2139,11 +2139,9 @@ __device__ inline TileLds tile_lds_carve(float *smem, int cap)
     return l;
 }
 
+constexpr int kTileWaves = 3;      // waves per SIMD the tile join is compiled for (four would spill)
 template <bool LONG_ROWS>      // graph rows of even length, 16-byte aligned, more than 16 entries: sixteen lanes per proposal
-#ifndef EF_TILE_WAVES
-#define EF_TILE_WAVES 3
-#endif
-__global__ void __launch_bounds__(EF_WAVE) __attribute__((amdgpu_waves_per_eu(EF_TILE_WAVES)))
+__global__ void __launch_bounds__(EF_WAVE) __attribute__((amdgpu_waves_per_eu(kTileWaves)))
 join_tile_kernel(const float *__restrict__ X, const float *__restrict__ norms, int d, int K, u32 k_magic,
                  u32 kq_magic, int *gid, const int *__restrict__ work, const int *__restrict__ work_count, int cap, int q_cap,
                  float margin_rel, float thr_scale, const int *__restrict__ ulist,
@@ -2159,17 +2157,7 @@ join_tile_kernel(const float *__restrict__ X, const float *__restrict__ norms, i
     const int count = *work_count;
     const int n_pieces = (d + 15) >> 4;      // 16-coordinate pieces of a vector (at most 8)
     int updates = 0, q_fill = 0;
-#ifdef EF_PROF
-    long long pc[5] = {0, 0, 0, 0, 0}, t0 = 0;
-    int n_joins = 0, n_surv_tot = 0, n_prop = 0;
-#define EF_T(k) do { long long t1 = __builtin_readcyclecounter(); pc[k] += t1 - t0; t0 = t1; } while (0)
-#else
-#define EF_T(k)
-#endif
     auto drain = [&]() {
-#ifdef EF_PROF
-        n_prop += q_fill;
-#endif
         updates += LONG_ROWS ? drain_queue_g16(lds.queue, q_fill, graph, worst, K, lane, EF_WAVE, gid)
                              : drain_queue<false, false>(lds.queue, q_fill, graph, worst, K, lane, EF_WAVE);
         q_fill = 0;
@@ -2184,9 +2172,6 @@ join_tile_kernel(const float *__restrict__ X, const float *__restrict__ norms, i
         const int i = work[w];
         const int2 mc = ucount[i];
         const int m_new = mc.x, m = min(mc.y, cap);
-#ifdef EF_PROF
-        t0 = __builtin_readcyclecounter(); ++n_joins;
-#endif
         // ---- 0. ids, thresholds, norms; the members' places by id ---------------------------
         for (int f = lane; f < m * kw; f += EF_WAVE) lds.known[f] = 0u;
         for (int f = lane; f < hslots; f += EF_WAVE) lds.hslot[f].x = -1;
@@ -2203,7 +2188,6 @@ join_tile_kernel(const float *__restrict__ X, const float *__restrict__ norms, i
             lds.hslot[h].y = r;
         }
         __syncthreads();
-        EF_T(0);
         // ---- 1. which members already know which (see join_kernel): the members' rows of ids, sixteen
         //         loads in flight per lane, four ids per load where rows allow it -----------------
         // `two`: the id's own bucket, read beforehand (several look-ups are issued together: one
@@ -2266,7 +2250,6 @@ join_tile_kernel(const float *__restrict__ X, const float *__restrict__ norms, i
             }
         }
         __syncthreads();
-        EF_T(1);
         // ---- 2. tile pairs ---------------------------------------------------------------------
         const int nbr = (m_new + 15) >> 4, nbc = (m + 15) >> 4;
         for (int bi = 0; bi < nbr; ++bi) {
@@ -2371,17 +2354,10 @@ join_tile_kernel(const float *__restrict__ X, const float *__restrict__ norms, i
                 __syncthreads();      // the survivor list is free again
             }
         }
-        EF_T(2);
         if (q_fill >= q_cap / 2) drain();
         __syncthreads();
-        EF_T(3);
     }
     drain();
-#ifdef EF_PROF
-    if (blockIdx.x == 7 && lane == 0 && n_joins)
-        printf("tile cap %d joins %d  cycles/join: setup %lld scan %lld tiles %lld drain %lld  proposals/join %.1f\n", cap, n_joins,
-               pc[0] / n_joins, pc[1] / n_joins, pc[2] / n_joins, pc[3] / n_joins, (double)n_prop / n_joins);
-#endif
     updates = ef_wave_sum_i32(updates);
     if (lane == 0) upd_block[blockIdx.x] += updates;      // (zeroed once per iteration; passes add up)
 }
@@ -3035,7 +3011,7 @@ int nndescent_run(const float *X, int64_t n, int32_t d, int32_t k, efanna_entry 
                 const int tq = 256;
                 const size_t tl = tile_lds_bytes(jc.bound[c], tq);
                 long per_cu = (long)(kLdsLimit / tl);
-                per_cu = per_cu > 4 * EF_TILE_WAVES ? 4 * EF_TILE_WAVES : (per_cu < 1 ? 1 : per_cu);      // by registers
+                per_cu = per_cu > 4 * kTileWaves ? 4 * kTileWaves : (per_cu < 1 ? 1 : per_cu);      // by registers
                 const int tgrid = (int)(256 * per_cu * 4);
                 int *upd = w.upd_block + 2 * reg_grid + (c - 2) * kMaxLargeGrid;
                 const u32 km = (u32)(((1ULL << 32) + K - 1) / K);
