@@ -1466,6 +1466,18 @@ __global__ void prepare_kernel(const int *__restrict__ nw, const int *__restrict
 // cap_rows: how many vectors the LDS row buffer of this launch holds.
 
 typedef float floatx4 __attribute__((ext_vector_type(4)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+
+// Eight coordinates of a vector as bfloat16 (round to nearest even), an operand of the
+// 16x16x32 matrix instruction.  Both operands of a Gram block are packed the same way, so the
+// order of the coordinates inside the operand does not matter.
+__device__ inline bf16x8 ef_pack_bf16(const float4 &lo, const float4 &hi)
+{
+    bf16x8 v;
+    v[0] = (__bf16)lo.x; v[1] = (__bf16)lo.y; v[2] = (__bf16)lo.z; v[3] = (__bf16)lo.w;
+    v[4] = (__bf16)hi.x; v[5] = (__bf16)hi.y; v[6] = (__bf16)hi.z; v[7] = (__bf16)hi.w;
+    return v;
+}
 
 struct JoinLds {
     float *rows;      // [cap_rows][stride], columns d..dpad-1 zero
@@ -1811,7 +1823,6 @@ join_reg_kernel(const float *__restrict__ X, int d, int K_,
         // rotations 0..15 of rows 16..31.
         constexpr bool rotated = !ONE;
         float two[2] = {0.f, 0.f}, two_b[2] = {0.f, 0.f};
-        float nb_sq = 0.0f;      // rows 16 ..: this lane's share of |row|^2
         if (rotated) {
             float P[8][4], PB[NB > 1 ? 8 : 1][4];
 #pragma unroll
@@ -1873,48 +1884,34 @@ join_reg_kernel(const float *__restrict__ X, int d, int K_,
                 }
             }
 #pragma unroll
-            for (int s = 0; s < 8; ++s) {
-                if (c0 + 16 * s >= d) break;
-                acc[0][0] = __builtin_amdgcn_mfma_f32_16x16x4f32(va[s].x, va[s].x, acc[0][0], 0, 0, 0);
-                acc[0][1] = __builtin_amdgcn_mfma_f32_16x16x4f32(va[s].y, va[s].y, acc[0][1], 0, 0, 0);
-                acc[0][0] = __builtin_amdgcn_mfma_f32_16x16x4f32(va[s].z, va[s].z, acc[0][0], 0, 0, 0);
-                acc[0][1] = __builtin_amdgcn_mfma_f32_16x16x4f32(va[s].w, va[s].w, acc[0][1], 0, 0, 0);
+            for (int s = 0; s < 8; s += 2) {
+                if (c0 + 16 * s >= d) break;      // (pieces beyond d were loaded as zeros)
+                const bf16x8 oa = ef_pack_bf16(va[s], va[s + 1]);
+                acc[0][(s >> 1) & 1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(oa, oa, acc[0][(s >> 1) & 1], 0, 0, 0);
                 if (NB > 1) {
                     constexpr int Q1 = NB > 1 ? 1 : 0, Q2 = NB > 1 ? 2 : 0;
-                    const float4 wb = vb[NB > 1 ? s : 0];
-                    nb_sq = __builtin_fmaf(wb.x, wb.x, nb_sq);
-                    nb_sq = __builtin_fmaf(wb.y, wb.y, nb_sq);
-                    nb_sq = __builtin_fmaf(wb.z, wb.z, nb_sq);
-                    nb_sq = __builtin_fmaf(wb.w, wb.w, nb_sq);
-                    acc[Q1][0] = __builtin_amdgcn_mfma_f32_16x16x4f32(va[s].x, wb.x, acc[Q1][0], 0, 0, 0);
-                    acc[Q1][1] = __builtin_amdgcn_mfma_f32_16x16x4f32(va[s].y, wb.y, acc[Q1][1], 0, 0, 0);
-                    acc[Q1][0] = __builtin_amdgcn_mfma_f32_16x16x4f32(va[s].z, wb.z, acc[Q1][0], 0, 0, 0);
-                    acc[Q1][1] = __builtin_amdgcn_mfma_f32_16x16x4f32(va[s].w, wb.w, acc[Q1][1], 0, 0, 0);
-                    if (need11) {
-                        acc[Q2][0] = __builtin_amdgcn_mfma_f32_16x16x4f32(wb.x, wb.x, acc[Q2][0], 0, 0, 0);
-                        acc[Q2][1] = __builtin_amdgcn_mfma_f32_16x16x4f32(wb.y, wb.y, acc[Q2][1], 0, 0, 0);
-                        acc[Q2][0] = __builtin_amdgcn_mfma_f32_16x16x4f32(wb.z, wb.z, acc[Q2][0], 0, 0, 0);
-                        acc[Q2][1] = __builtin_amdgcn_mfma_f32_16x16x4f32(wb.w, wb.w, acc[Q2][1], 0, 0, 0);
-                    }
+                    const bf16x8 ob = ef_pack_bf16(vb[NB > 1 ? s : 0], vb[NB > 1 ? s + 1 : 0]);
+                    acc[Q1][(s >> 1) & 1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(oa, ob, acc[Q1][(s >> 1) & 1], 0, 0, 0);
+                    acc[Q2][(s >> 1) & 1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ob, ob, acc[Q2][(s >> 1) & 1], 0, 0, 0);
                 }
             }
         }
         if (!rotated) {
-            // The filter's |row|^2 need not be gathered: for rows 0..15 it is the diagonal of Gram
-            // block (0,0) (lane (r16, g) holds G[4 g + k][r16]), for rows 16.. the four lanes of a
-            // row add the squares of their coordinates.  Both are within the filter's margin of
-            // the exact value, like the Gram entries themselves.
+            // The filter's squared norms are those of the rounded vectors: the diagonals of Gram
+            // blocks (0,0) and (1,1) (lane (r16, g) holds G[4 g + k][r16]).
             if ((r16 >> 2) == g) {
                 const int kd = r16 & 3;
                 const float dg = kd == 0 ? acc[0][0][0] + acc[0][1][0]
                                : kd == 1 ? acc[0][0][1] + acc[0][1][1]
                                : kd == 2 ? acc[0][0][2] + acc[0][1][2] : acc[0][0][3] + acc[0][1][3];
                 nf[r16] = dg * (1.0f - margin_rel);
-            }
-            if (NB > 1) {
-                nb_sq += __shfl_xor(nb_sq, 16, EF_WAVE);
-                nb_sq += __shfl_xor(nb_sq, 32, EF_WAVE);
-                if (g == 0) nf[16 + r16] = nb_sq * (1.0f - margin_rel);
+                if (NB > 1) {
+                    constexpr int Q2 = NB > 1 ? 2 : 0;
+                    const float dh = kd == 0 ? acc[Q2][0][0] + acc[Q2][1][0]
+                                   : kd == 1 ? acc[Q2][0][1] + acc[Q2][1][1]
+                                   : kd == 2 ? acc[Q2][0][2] + acc[Q2][1][2] : acc[Q2][0][3] + acc[Q2][1][3];
+                    nf[16 + r16] = dh * (1.0f - margin_rel);
+                }
             }
         }
         __syncthreads();      // uid, thr, nf, tf visible
@@ -2841,6 +2838,19 @@ int nndescent_run(const float *X, int64_t n, int32_t d, int32_t k, efanna_entry 
     // doubled; the fixed-order distance is within (d/16 + 8) u of the true one, doubled twice
     const float margin_rel = (float)((4.0 * dpad + 16.0) * 5.9604644775390625e-08);
     const float thr_scale = (float)(1.0 + 4.0 * (d / 16.0 + 8.0) * 5.9604644775390625e-08);
+    // The register joins filter with Gram blocks of the vectors rounded to bfloat16 (u = 2^-8 per
+    // coordinate): the blocks' diagonals are the rounded vectors' squared norms, so the filter's
+    // left side is the squared distance D'^2 of the rounded vectors, up to the accumulation error.
+    // |D' - D| <= u (|a| + |b|) =: r, hence D^2 <= T implies
+    //   D'^2 <= T + 2 sqrt(T) r + r^2 <= T (1 + eta) + r^2 (1 + 1/eta),   r^2 <= 2 u^2 (|a'|^2 + |b'|^2) / (1 - u)^2.
+    // With eta = 1/16 the threshold grows by a sixteenth and the norms lose 34 u^2 / (1 - u)^2 of
+    // themselves, plus four times (dpad + 4) 2^-23 for the three accumulations in single precision
+    // (a bound that holds whether the matrix unit rounds or truncates its partial sums).
+    const double bf_u = 1.0 / 256.0, bf_eta = 1.0 / 16.0;
+    const float margin_bf = (float)(2.0 * bf_u * bf_u * (1.0 + 1.0 / bf_eta) / ((1.0 - bf_u) * (1.0 - bf_u)) +
+                                    4.0 * (dpad + 4.0) * 1.1920928955078125e-07 + 16.0 * 5.9604644775390625e-08);
+    const float thr_scale_bf = (float)((1.0 + 4.0 * (d / 16.0 + 8.0) * 5.9604644775390625e-08) * (1.0 + bf_eta) *
+                                       (1.0 + 4.0 * 5.9604644775390625e-08));
     hipStream_t st = (hipStream_t)stream;
     NndWs w = carve_nnd(ws, n, K, L);
     // reverse lists by buckets (short rows and lists): LDS of an offer block (words) or a list
@@ -2978,8 +2988,8 @@ int nndescent_run(const float *X, int64_t n, int32_t d, int32_t k, efanna_entry 
 #define EF_JOIN_REG_K(NB, ONE, LIST, KT)                                                           \
     join_reg_kernel<NB, ONE, KT><<<reg_grid, EF_WAVE, reg_lds(16 * NB), st>>>(                     \
         X, d, K, w.work + (size_t)(LIST) * n, w.work_count + (LIST), reg_q_cap_for(16 * NB), \
-        margin_rel, thr_scale, w.ulist, w.ucount, max_rows, graph, w.worst,                        \
-        w.upd_block + (LIST) * reg_grid, mode)
+        (ONE) ? margin_bf : margin_rel, (ONE) ? thr_scale_bf : thr_scale, w.ulist, w.ucount,       \
+        max_rows, graph, w.worst, w.upd_block + (LIST) * reg_grid, mode)
     // (a row length of 10 is compiled in: 3 % off the joins of 17..32 vectors)
 #define EF_JOIN_REG(NB, ONE, LIST)                                                                 \
     do {                                                                                           \
