@@ -8,6 +8,7 @@
 // leaves the finished distance of pair l in lane l.  Each lane then offers its pair to
 // the two rows concerned through the lock-free bounded insertion.
 #include <atomic>
+#include <type_traits>
 #include <vector>
 
 #include "common.h"
@@ -510,6 +511,27 @@ __device__ inline void reduce_rotations(const float (&P)[8][4], int g, float (&o
         }
 #pragma unroll
     for (int t = 0; t < 2; ++t) out[t] = (R[t][0] + R[t][2]) + (R[t][1] + R[t][3]);
+}
+
+// The same for four rotations (T0 + 1 .. T0 + 4 in P[0..3]): lane (r, g) ends up with the distance
+// from row r to the row T0 + 1 + g places on.
+__device__ inline float reduce_rotations4(const float (&P)[4][4], int g)
+{
+    const bool hi = g & 2, odd = g & 1;
+    float Q[2][4], R[4];
+#pragma unroll
+    for (int t = 0; t < 2; ++t)
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            const float keep = hi ? P[t + 2][k] : P[t][k], send = hi ? P[t][k] : P[t + 2][k];
+            Q[t][k] = keep + __shfl_xor(send, 32, EF_WAVE);
+        }
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+        const float keep = odd ? Q[1][k] : Q[0][k], send = odd ? Q[0][k] : Q[1][k];
+        R[k] = keep + __shfl_xor(send, 16, EF_WAVE);
+    }
+    return (R[0] + R[2]) + (R[1] + R[3]);
 }
 
 // Which leaf of each sibling subtree every point reaches: etab[p * levels + k] for the point at
@@ -1466,17 +1488,31 @@ __global__ void prepare_kernel(const int *__restrict__ nw, const int *__restrict
 // cap_rows: how many vectors the LDS row buffer of this launch holds.
 
 typedef float floatx4 __attribute__((ext_vector_type(4)));
-typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
+typedef __fp16 fp16x2 __attribute__((ext_vector_type(2)));
 
-// Eight coordinates of a vector as bfloat16 (round to nearest even), an operand of the
-// 16x16x32 matrix instruction.  Both operands of a Gram block are packed the same way, so the
-// order of the coordinates inside the operand does not matter.
-__device__ inline bf16x8 ef_pack_bf16(const float4 &lo, const float4 &hi)
+// Eight coordinates of a vector, times a power of two, as half-precision numbers rounded towards
+// zero: an operand of the 16x16x32 matrix instruction.  Both operands of a Gram block are packed
+// the same way, so the order of the coordinates inside the operand does not matter.
+template <bool SCALED>
+__device__ inline f16x8 ef_pack_f16(const float4 &lo, const float4 &hi, float s)
 {
-    bf16x8 v;
-    v[0] = (__bf16)lo.x; v[1] = (__bf16)lo.y; v[2] = (__bf16)lo.z; v[3] = (__bf16)lo.w;
-    v[4] = (__bf16)hi.x; v[5] = (__bf16)hi.y; v[6] = (__bf16)hi.z; v[7] = (__bf16)hi.w;
-    return v;
+    union {
+        fp16x2 h[4];
+        f16x8 v;
+    } u;
+    if (SCALED) {
+        u.h[0] = __builtin_amdgcn_cvt_pkrtz(lo.x * s, lo.y * s);
+        u.h[1] = __builtin_amdgcn_cvt_pkrtz(lo.z * s, lo.w * s);
+        u.h[2] = __builtin_amdgcn_cvt_pkrtz(hi.x * s, hi.y * s);
+        u.h[3] = __builtin_amdgcn_cvt_pkrtz(hi.z * s, hi.w * s);
+    } else {
+        u.h[0] = __builtin_amdgcn_cvt_pkrtz(lo.x, lo.y);
+        u.h[1] = __builtin_amdgcn_cvt_pkrtz(lo.z, lo.w);
+        u.h[2] = __builtin_amdgcn_cvt_pkrtz(hi.x, hi.y);
+        u.h[3] = __builtin_amdgcn_cvt_pkrtz(hi.z, hi.w);
+    }
+    return u.v;
 }
 
 struct JoinLds {
@@ -1715,6 +1751,8 @@ __global__ void __launch_bounds__(512) join_kernel(const float *__restrict__ X, 
 __device__ constexpr int kSurvBase[3] = {0, 120, 376};
 // d > 128: up to this many surviving pairs of a Gram block (per 16 rows) are read pair by pair
 constexpr int kFewPairs = 4;
+// d <= 128: more survivors than this inside one set of sixteen rows and all its pairs are evaluated by row rotations
+constexpr int kDenseSurvivors = 24;
 
 // One surviving pair (rows a, b of the point's list) per lane with `mine` set: its distance is
 // offered to row a and to row b where it passes their thresholds.  All lanes of the wave call
@@ -1744,9 +1782,9 @@ template <int NB, bool ONE, int KT>      // KT: the row length if fixed at compi
 __global__ void __launch_bounds__(EF_WAVE) __attribute__((amdgpu_waves_per_eu(NB > 1 ? 3 : 4)))
 join_reg_kernel(const float *__restrict__ X, int d, int K_,
                 const int *__restrict__ work, const int *__restrict__ work_count, int q_cap,
-                float margin_rel, float thr_scale, const int *__restrict__ ulist,
+                float margin_rel, float thr_scale, float u_rel, float rho0, const int *__restrict__ ulist,
                 const int2 *__restrict__ ucount, int ucap, u64 *graph, u32 *worst,
-                int *__restrict__ upd_block, int mode)
+                int *__restrict__ upd_block, int mode, int dense_min, const u32 *__restrict__ xmax)
 {
     // mode 0: every pair of the join, fresh entries marked new.  1: only pairs of two new members.
     // 2: only pairs of a new and an old member, fresh entries marked old (the literal marking of
@@ -1760,12 +1798,19 @@ join_reg_kernel(const float *__restrict__ X, int d, int K_,
     int *uid = (int *)smem;                       // [R]
     u32 *thr = (u32 *)(uid + R);                  // [R] threshold bits (exact test)
     float *nf = (float *)(thr + R);               // [R] |x|^2 (1 - margin)   } the filter's
-    float *tf = nf + R;                           // [R] threshold * scale    } operands
-    u32 *surv = (u32 *)(tf + R);                  // [S_CAP] surviving pairs
+    float *tf = nf + R;                           // [R] threshold * scale    } operands (in the
+    float *sq = tf + R;                           // [R] its square root      } scaled units of
+    float *rr = sq + R;                           // [R] rounding radius      } the operands)
+    u32 *surv = (u32 *)(rr + R);                  // [S_CAP] surviving pairs
     Proposal *queue = (Proposal *)(surv + align4(S_CAP));   // [q_cap]
     const int lane = threadIdx.x, r16 = lane & 15, g = lane >> 4, gl = r16, grp = g;
     const int dirn = (EF_ROW_ROR(r16, 1) - r16) & 15;      // a rotation by t brings row r + t * dirn to row r
     const int count = *work_count;
+    // The filter works on the vectors times a power of two that brings the largest coordinate of
+    // the data below 2^15 (1 for all data below that already): half precision then never overflows.
+    const int x_exp = (int)(*xmax >> 23) - 127;
+    const float scale = x_exp >= 15 ? __uint_as_float((u32)(127 + 14 - x_exp) << 23) : 1.0f;
+    const float t_scale = thr_scale * scale * scale;
     // The id list and the sizes of a point are fetched one point ahead, and the thresholds of
     // its vectors as soon as those ids are there, so that they travel while the point before
     // is being worked on: the row loads are the only latency a point waits for.
@@ -1795,7 +1840,9 @@ join_reg_kernel(const float *__restrict__ X, int d, int K_,
         if (lane < R) {
             uid[lane] = u_cur;
             thr[lane] = t_pre;
-            tf[lane] = __uint_as_float(t_pre) * thr_scale;
+            const float t = __uint_as_float(t_pre) * t_scale;
+            tf[lane] = t;
+            sq[lane] = __builtin_sqrtf(t) * 1.000001f;
         }
         i = i_next;
         u_pre = i >= 0 && lane < R ? ulist[(size_t)i * ucap + min(lane, ucap - 1)] : -1;
@@ -1883,41 +1930,52 @@ join_reg_kernel(const float *__restrict__ X, int d, int K_,
                         vb[NB > 1 ? s : 0] = in ? *reinterpret_cast<const float4 *>(pb + c0 + 16 * s) : make_float4(0.f, 0.f, 0.f, 0.f);
                 }
             }
+            auto gram = [&](auto scaled) {
 #pragma unroll
-            for (int s = 0; s < 8; s += 2) {
-                if (c0 + 16 * s >= d) break;      // (pieces beyond d were loaded as zeros)
-                const bf16x8 oa = ef_pack_bf16(va[s], va[s + 1]);
-                acc[0][(s >> 1) & 1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(oa, oa, acc[0][(s >> 1) & 1], 0, 0, 0);
-                if (NB > 1) {
-                    constexpr int Q1 = NB > 1 ? 1 : 0, Q2 = NB > 1 ? 2 : 0;
-                    const bf16x8 ob = ef_pack_bf16(vb[NB > 1 ? s : 0], vb[NB > 1 ? s + 1 : 0]);
-                    acc[Q1][(s >> 1) & 1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(oa, ob, acc[Q1][(s >> 1) & 1], 0, 0, 0);
-                    acc[Q2][(s >> 1) & 1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ob, ob, acc[Q2][(s >> 1) & 1], 0, 0, 0);
+                for (int s = 0; s < 8; s += 2) {
+                    if (c0 + 16 * s >= d) break;      // (pieces beyond d were loaded as zeros)
+                    const f16x8 oa = ef_pack_f16<decltype(scaled)::value>(va[s], va[s + 1], scale);
+                    acc[0][(s >> 1) & 1] = __builtin_amdgcn_mfma_f32_16x16x32_f16(oa, oa, acc[0][(s >> 1) & 1], 0, 0, 0);
+                    if (NB > 1) {
+                        constexpr int Q1 = NB > 1 ? 1 : 0, Q2 = NB > 1 ? 2 : 0;
+                        const f16x8 ob = ef_pack_f16<decltype(scaled)::value>(vb[NB > 1 ? s : 0], vb[NB > 1 ? s + 1 : 0], scale);
+                        acc[Q1][(s >> 1) & 1] = __builtin_amdgcn_mfma_f32_16x16x32_f16(oa, ob, acc[Q1][(s >> 1) & 1], 0, 0, 0);
+                        acc[Q2][(s >> 1) & 1] = __builtin_amdgcn_mfma_f32_16x16x32_f16(ob, ob, acc[Q2][(s >> 1) & 1], 0, 0, 0);
+                    }
                 }
-            }
+            };
+            if (scale != 1.0f) gram(std::true_type{});
+            else gram(std::false_type{});
         }
         if (!rotated) {
             // The filter's squared norms are those of the rounded vectors: the diagonals of Gram
-            // blocks (0,0) and (1,1) (lane (r16, g) holds G[4 g + k][r16]).
+            // blocks (0,0) and (1,1) (lane (r16, g) holds G[4 g + k][r16]).  rr: how far rounding may
+            // have moved the vector, u |x'| + r0.
             if ((r16 >> 2) == g) {
                 const int kd = r16 & 3;
                 const float dg = kd == 0 ? acc[0][0][0] + acc[0][1][0]
                                : kd == 1 ? acc[0][0][1] + acc[0][1][1]
                                : kd == 2 ? acc[0][0][2] + acc[0][1][2] : acc[0][0][3] + acc[0][1][3];
                 nf[r16] = dg * (1.0f - margin_rel);
+                rr[r16] = __builtin_fmaf(u_rel, __builtin_sqrtf(dg), rho0);
                 if (NB > 1) {
                     constexpr int Q2 = NB > 1 ? 2 : 0;
                     const float dh = kd == 0 ? acc[Q2][0][0] + acc[Q2][1][0]
                                    : kd == 1 ? acc[Q2][0][1] + acc[Q2][1][1]
                                    : kd == 2 ? acc[Q2][0][2] + acc[Q2][1][2] : acc[Q2][0][3] + acc[Q2][1][3];
                     nf[16 + r16] = dh * (1.0f - margin_rel);
+                    rr[16 + r16] = __builtin_fmaf(u_rel, __builtin_sqrtf(dh), rho0);
                 }
             }
         }
-        __syncthreads();      // uid, thr, nf, tf visible
+        __syncthreads();      // uid, thr, nf, tf, sq, rr visible
         t_pre = u_pre >= 0 ? worst[u_pre] : 0u;      // the next point's; its ids have arrived by now
         // ---- filter: lane holds G[a = 16 bi + 4 g + k][b = 16 bj + r16] of block q -----------
-        // pair (a, b) survives if (|a|^2 + |b|^2)(1 - margin) - 2 a.b <= max threshold * scale
+        // With D' the distance of the rounded vectors, r = rr[a] + rr[b] and T the larger threshold:
+        // |D' - D| <= r, so D^2 <= T implies D'^2 <= T + r (2 sqrt(T) + r).  Pair (a, b) survives
+        // unless (|a'|^2 + |b'|^2)(1 - margin) - 2 a'.b' is above that (the margin covers the three
+        // accumulations; a comparison with a NaN - an infinite threshold times a zero radius -
+        // keeps the pair).
         int n_surv[NQ];
 #pragma unroll
         for (int q = 0; q < NQ; ++q) n_surv[q] = 0;
@@ -1928,15 +1986,20 @@ join_reg_kernel(const float *__restrict__ X, int d, int K_,
             const int b = 16 * bj + r16, a0 = 16 * bi + 4 * g;
             // valid pairs: a < lim
             const int lim = b >= m ? 0 : mode == 0 ? min(m_new, b) : mode == 1 ? (b < m_new ? b : 0) : (b >= m_new ? m_new : 0);
-            const float nfb = nf[b], tfb = tf[b];                  // junk beyond m, masked by lim
+            const float nfb = nf[b], tfb = tf[b], sqb = sq[b], rrb = rr[b];      // junk beyond m, masked by lim
             const float4 nfa = *reinterpret_cast<const float4 *>(nf + a0);
             const float4 tfa = *reinterpret_cast<const float4 *>(tf + a0);
+            const float4 sqa = *reinterpret_cast<const float4 *>(sq + a0);
+            const float4 rra = *reinterpret_cast<const float4 *>(rr + a0);
             const float nfa_k[4] = {nfa.x, nfa.y, nfa.z, nfa.w}, tfa_k[4] = {tfa.x, tfa.y, tfa.z, tfa.w};
+            const float sqa_k[4] = {sqa.x, sqa.y, sqa.z, sqa.w}, rra_k[4] = {rra.x, rra.y, rra.z, rra.w};
 #pragma unroll
             for (int k = 0; k < 4; ++k) {
                 const float lhs = __builtin_fmaf(-2.0f, acc[q][0][k] + acc[q][1][k], nfa_k[k] + nfb);
+                const float rad = rra_k[k] + rrb;
+                const float rhs = __builtin_fmaf(rad, __builtin_fmaf(2.0f, fmaxf(sqa_k[k], sqb), rad), fmaxf(tfa_k[k], tfb));
                 // one list per Gram block, entries are rows local to the block
-                const bool keep = a0 + k < lim && lhs <= fmaxf(tfa_k[k], tfb);
+                const bool keep = a0 + k < lim && !(lhs > rhs);
                 const u64 kept = __ballot(keep);
                 if (keep) surv[kSurvBase[q] + n_surv[q] + lanes_below(kept)] = (u32)((a0 + k) & 15) | ((u32)(b & 15) << 8);
                 n_surv[q] += __popcll(kept);
@@ -2027,6 +2090,45 @@ join_reg_kernel(const float *__restrict__ X, int d, int K_,
             for (int q = 0; q < (NB > 1 ? 3 : 1); ++q) {
                 const int bi = q == 2 ? 1 : 0, bj = q == 0 ? 0 : 1;
                 const int n_q = n_surv[q];
+                // Many survivors inside one set of sixteen rows (early iterations: most pairs
+                // pass): all 120 pairs by row rotations, as for long vectors, cost what two rounds
+                // of sixteen survivors cost.  The filter never drops a pair that would pass a
+                // threshold, so which way a pair takes makes no difference to what is proposed.
+                if (NB == 1 && n_q > dense_min) {
+                    const float4 (&rows)[8] = reinterpret_cast<const float4 (&)[8]>(*(q == 0 ? va : vb));
+                    const int n_pieces = (d + 15) >> 4, base = 16 * bi;
+#pragma unroll
+                    for (int half = 0; half < 2; ++half) {      // rotations 1..4, then 5..8
+                        float P[4][4];
+#pragma unroll
+                        for (int t = 0; t < 4; ++t) P[t][0] = P[t][1] = P[t][2] = P[t][3] = 0.0f;
+                        if (half == 0) {
+                            init_round<1>(rows, n_pieces, P[0]);
+                            init_round<2>(rows, n_pieces, P[1]);
+                            init_round<3>(rows, n_pieces, P[2]);
+                            init_round<4>(rows, n_pieces, P[3]);
+                        } else {
+                            init_round<5>(rows, n_pieces, P[0]);
+                            init_round<6>(rows, n_pieces, P[1]);
+                            init_round<7>(rows, n_pieces, P[2]);
+                            init_round<8>(rows, n_pieces, P[3]);
+                        }
+                        const float dist = reduce_rotations4(P, g);
+                        const int rot = 4 * half + 1 + g, b = (r16 + dirn * rot) & 15;
+                        const bool once = rot != 8 || r16 < b;      // rotation 8 meets every pair from both ends
+                        if (NB > 1 && q_fill + 2 * EF_WAVE > q_cap) {
+                            updates += drain_mid(queue, q_fill);
+                            q_fill = 0;
+                            __syncthreads();
+                        }
+                        q_fill = propose_pair(queue, q_fill,
+                                              once && base + r16 < m && base + b < m && base + min(r16, b) < m_new &&
+                                                  mode_ok(base + max(r16, b)),
+                                              dist, base + r16, base + b, thr, uid, mark);
+                        __syncthreads();
+                    }
+                    continue;
+                }
                 for (int p0 = 0; p0 < n_q; p0 += 16) {
                     const bool has = p0 + r16 < n_q;
                     const u32 ent = surv[kSurvBase[q] + min(p0 + r16, n_q - 1)];
@@ -2371,17 +2473,35 @@ __global__ void __launch_bounds__(kBlock) graph_ids_kernel(const u64 *__restrict
     }
 }
 
-// squared norms in float32 (only the join's filter uses them; any summation order will do)
-__global__ void norms_kernel(const float *__restrict__ X, int n, int d, float *__restrict__ norms)
+// squared norms in float32 (only the join's filter uses them; any summation order will do) and
+// the largest |coordinate| of the data (its bits, which order like the values; *xmax starts at 0).
+// A group of sixteen lanes per point, points strided over the grid: one atomic per block.
+__global__ void __launch_bounds__(kBlock)
+norms_kernel(const float *__restrict__ X, int n, int d, float *__restrict__ norms, u32 *xmax)
 {
-    const size_t g = ((size_t)blockIdx.x * blockDim.x + threadIdx.x) >> 4;
+    __shared__ u32 wave_max[kBlock / EF_WAVE];
     const int gl = threadIdx.x & 15;
-    const size_t gc = g < (size_t)n ? g : (size_t)n - 1;
-    const float *a = X + gc * d;
-    float acc = 0.0f;
-    for (int j = gl; j < d; j += 16) acc = __builtin_fmaf(a[j], a[j], acc);
-    acc = ef_group_reduce16(acc);
-    if (g < (size_t)n && gl == 0) norms[g] = acc;
+    const size_t n_groups = (size_t)gridDim.x * (kBlock / 16);
+    float mx = 0.0f;
+    for (size_t g = ((size_t)blockIdx.x * kBlock + threadIdx.x) >> 4; g < (size_t)n; g += n_groups) {
+        const float *a = X + g * d;
+        float acc = 0.0f;
+        for (int j = gl; j < d; j += 16) {
+            const float v = a[j];
+            acc = __builtin_fmaf(v, v, acc);
+            mx = fmaxf(mx, fabsf(v));
+        }
+        acc = ef_group_reduce16(acc);
+        if (gl == 0) norms[g] = acc;
+    }
+    for (int o = EF_WAVE / 2; o >= 1; o >>= 1) mx = fmaxf(mx, __shfl_xor(mx, o, EF_WAVE));
+    if (ef_lane() == 0) wave_max[threadIdx.x / EF_WAVE] = __float_as_uint(mx);
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        u32 m = 0;
+        for (int w = 0; w < kBlock / EF_WAVE; ++w) m = max(m, wave_max[w]);
+        if (m) atomicMax(xmax, m);
+    }
 }
 
 // per-iteration counters from the per-block partial sums: part[b] = (pairs evaluated, vectors
@@ -2530,6 +2650,7 @@ struct NndWs {
     long long *part;
     u32 *worst;
     float *norms;
+    u32 *xmax;      // bits of the largest |coordinate| of the data
     size_t bytes;
 };
 
@@ -2571,6 +2692,7 @@ NndWs carve_nnd(void *ws, int64_t n, int K, int L)
     w.fresh = (u64 *)take(8);
     w.worst = (u32 *)take((size_t)n * 4);
     w.norms = (float *)take((size_t)n * 4);
+    w.xmax = (u32 *)take(8);
     w.gid = (int *)take(K + 2 * L > 32 ? (size_t)n * K * 4 : 0);
     w.bytes = off;
     return w;
@@ -2826,7 +2948,7 @@ int nndescent_run(const float *X, int64_t n, int32_t d, int32_t k, efanna_entry 
     auto reg_q_cap_for = [&](int R) { return R == 16 ? (d <= 128 ? 512 : 256) : (d <= 128 ? 256 : 384); };
     auto reg_lds = [&](int R) {
         const int reg_q_cap = reg_q_cap_for(R);
-        return (size_t)(4 * R + align4(R * (R - 1) / 2 + 8)) * 4 +
+        return (size_t)(6 * R + align4(R * (R - 1) / 2 + 8)) * 4 +
                (size_t)reg_q_cap * sizeof(Proposal);
     };
     const int reg_grid = kRegGrid;
@@ -2838,19 +2960,19 @@ int nndescent_run(const float *X, int64_t n, int32_t d, int32_t k, efanna_entry 
     // doubled; the fixed-order distance is within (d/16 + 8) u of the true one, doubled twice
     const float margin_rel = (float)((4.0 * dpad + 16.0) * 5.9604644775390625e-08);
     const float thr_scale = (float)(1.0 + 4.0 * (d / 16.0 + 8.0) * 5.9604644775390625e-08);
-    // The register joins filter with Gram blocks of the vectors rounded to bfloat16 (u = 2^-8 per
-    // coordinate): the blocks' diagonals are the rounded vectors' squared norms, so the filter's
-    // left side is the squared distance D'^2 of the rounded vectors, up to the accumulation error.
-    // |D' - D| <= u (|a| + |b|) =: r, hence D^2 <= T implies
-    //   D'^2 <= T + 2 sqrt(T) r + r^2 <= T (1 + eta) + r^2 (1 + 1/eta),   r^2 <= 2 u^2 (|a'|^2 + |b'|^2) / (1 - u)^2.
-    // With eta = 1/16 the threshold grows by a sixteenth and the norms lose 34 u^2 / (1 - u)^2 of
-    // themselves, plus four times (dpad + 4) 2^-23 for the three accumulations in single precision
-    // (a bound that holds whether the matrix unit rounds or truncates its partial sums).
-    const double bf_u = 1.0 / 256.0, bf_eta = 1.0 / 16.0;
-    const float margin_bf = (float)(2.0 * bf_u * bf_u * (1.0 + 1.0 / bf_eta) / ((1.0 - bf_u) * (1.0 - bf_u)) +
-                                    4.0 * (dpad + 4.0) * 1.1920928955078125e-07 + 16.0 * 5.9604644775390625e-08);
-    const float thr_scale_bf = (float)((1.0 + 4.0 * (d / 16.0 + 8.0) * 5.9604644775390625e-08) * (1.0 + bf_eta) *
-                                       (1.0 + 4.0 * 5.9604644775390625e-08));
+    // The register joins filter with Gram blocks of the vectors in half precision, rounded towards
+    // zero after a scaling by a power of two that keeps them below 2^15: a coordinate moves by at
+    // most 2^-10 of itself or, below 2^-14, by 2^-24.  The blocks' diagonals are the rounded
+    // vectors' squared norms, so the filter's left side is the squared distance D'^2 of the rounded
+    // vectors up to the accumulation error, and |D' - D| <= r(a) + r(b) with
+    // r(x) = u |x'| + r0, u = 2^-10 / (1 - 2^-10) (+ slack for the square root and the norm's own
+    // error), r0 = 1.01 sqrt(d) 2^-24.  The margin on the norms pays for the three accumulations in
+    // single precision: four times (dpad + 4) 2^-23, a bound that holds whether the matrix unit
+    // rounds or truncates its partial sums.
+    const float margin_f16 = (float)(4.0 * (dpad + 4.0) * 1.1920928955078125e-07 + 16.0 * 5.9604644775390625e-08);
+    const float thr_scale_f16 = (float)((1.0 + 4.0 * (d / 16.0 + 8.0) * 5.9604644775390625e-08) * (1.0 + 1e-6));
+    const float u_f16 = (float)(1.01 / 1023.0);
+    const float rho0_f16 = (float)(1.01 * sqrt((double)d) * 5.9604644775390625e-08);
     hipStream_t st = (hipStream_t)stream;
     NndWs w = carve_nnd(ws, n, K, L);
     // reverse lists by buckets (short rows and lists): LDS of an offer block (words) or a list
@@ -2881,7 +3003,8 @@ int nndescent_run(const float *X, int64_t n, int32_t d, int32_t k, efanna_entry 
         EF_HIP_CHECK(hipFuncSetAttribute(K >= 2 * EF_WIDE_PIECES ? (const void *)join_kernel<true>
                                                                  : (const void *)join_kernel<false>,
                                          hipFuncAttributeMaxDynamicSharedMemorySize, (int)large_lds));
-    norms_kernel<<<grid_for((size_t)n * 16, kBlock), kBlock, 0, st>>>(X, (int)n, d, w.norms);
+    zero_u64_kernel<<<1, EF_WAVE, 0, st>>>((u64 *)w.xmax, 1);
+    norms_kernel<<<min(grid_for((size_t)n * 16, kBlock), 256 * 8), kBlock, 0, st>>>(X, (int)n, d, w.norms, w.xmax);
     if (stats) zero_u64_kernel<<<grid_for((size_t)iters * 4 + 1, kBlock), kBlock, 0, st>>>(stats, iters * 4);
     // optional phase timing: events around the sampling and the join of every iteration
     struct PhaseEvents {      // destroyed on every way out of the call
@@ -2988,8 +3111,9 @@ int nndescent_run(const float *X, int64_t n, int32_t d, int32_t k, efanna_entry 
 #define EF_JOIN_REG_K(NB, ONE, LIST, KT)                                                           \
     join_reg_kernel<NB, ONE, KT><<<reg_grid, EF_WAVE, reg_lds(16 * NB), st>>>(                     \
         X, d, K, w.work + (size_t)(LIST) * n, w.work_count + (LIST), reg_q_cap_for(16 * NB), \
-        (ONE) ? margin_bf : margin_rel, (ONE) ? thr_scale_bf : thr_scale, w.ulist, w.ucount,       \
-        max_rows, graph, w.worst, w.upd_block + (LIST) * reg_grid, mode)
+        (ONE) ? margin_f16 : margin_rel, (ONE) ? thr_scale_f16 : thr_scale, u_f16, rho0_f16,       \
+        w.ulist, w.ucount, max_rows, graph, w.worst, w.upd_block + (LIST) * reg_grid, mode,        \
+        kDenseSurvivors, w.xmax)
     // (a row length of 10 is compiled in: 3 % off the joins of 17..32 vectors)
 #define EF_JOIN_REG(NB, ONE, LIST)                                                                 \
     do {                                                                                           \
