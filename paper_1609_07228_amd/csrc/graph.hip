@@ -2094,7 +2094,8 @@ join_reg_kernel(const float *__restrict__ X, int d, int K_,
                 // pass): all 120 pairs by row rotations, as for long vectors, cost what two rounds
                 // of sixteen survivors cost.  The filter never drops a pair that would pass a
                 // threshold, so which way a pair takes makes no difference to what is proposed.
-                if (NB == 1 && n_q > dense_min) {
+                // (only with the row length compiled in: the other variants would spill registers)
+                if (NB == 1 && KT != 0 && n_q > dense_min) {
                     const float4 (&rows)[8] = reinterpret_cast<const float4 (&)[8]>(*(q == 0 ? va : vb));
                     const int n_pieces = (d + 15) >> 4, base = 16 * bi;
 #pragma unroll
