@@ -76,11 +76,11 @@ MUTANTS = [
     ("NN-descent: reverse-old lists drawn from the reverse-new stream",
      "2 * (iter0 + it) + 1, rod, rod_c", "2 * (iter0 + it), rod, rod_c", GRAPH),
     ("NN-descent: new x old pairs dropped from the join",
-     "for (int32_t b = a + 1; b < n_new + n_old; ++b) {", "for (int32_t b = a + 1; b < n_new; ++b) {", GRAPH),
+     "int32_t b_hi = cross_old && pass == 0 ? n_new : n_new + n_old;", "int32_t b_hi = n_new;", GRAPH),
     ("NN-descent: pair offered to one end point only",
-     "                        updates += pool_insert(pool + (int64_t)v * K, &cnt[v], K, dist, u);\n", "", GRAPH),
+     "                        updates += pool_insert_marked(pool + (int64_t)v * K, &cnt[v], K, dist, u, mark);\n", "", GRAPH),
     ("NN-descent: inserted entries are not marked new",
-     "    pool[s].is_new = 1;\n", "    pool[s].is_new = 0;\n", GRAPH),
+     "    pool[s].is_new = is_new;\n", "    pool[s].is_new = 0;\n", GRAPH),
     ("NN-descent: members of U_new stay in U_old",
      "if (!bsearch(&uo[s], un, (size_t)n_new, sizeof(int32_t), cmp_i32))", "if (1)", GRAPH),
     ("conquer: a node without a split test sends points right",
