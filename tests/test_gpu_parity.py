@@ -290,6 +290,43 @@ def test_nndescent_bit_exact_every_iteration(ef, name, n, T, S, K, L, I):
     oracle.check_graph_invariants(X, ids, dists)
 
 
+def filter_data(kind, n, d):
+    """Data that strains the joins' half-precision Gram filter (a filter that drops a pair it must
+    keep shows as a row that differs from the oracle's)."""
+    rng = np.random.default_rng(97)
+    X = rng.standard_normal((n, d)).astype(np.float32)
+    if kind == "large":            # coordinates up to 2^19: scaled down before rounding
+        X = X * np.float32(90_000.0)
+    elif kind == "just_below":     # largest coordinate just under 2^15: not scaled
+        X = X * np.float32(32_000.0 / np.abs(X).max())
+    elif kind == "tiny":           # below the smallest normal half-precision number
+        X = X * np.float32(3e-6)
+    elif kind == "offset":         # norms a thousand times the distances
+        X = X + np.float32(900.0)
+    elif kind == "outlier":        # one huge coordinate sets the scale, the rest turn subnormal
+        X[17, 3] = np.float32(500_000.0)
+    elif kind == "integers":       # heavy ties, many zero distances
+        X = rng.integers(0, 3, size=(n, d)).astype(np.float32)
+    elif kind == "mixed_scales":   # every dimension its own magnitude, 2^-12 .. 2^12
+        X = X * np.exp2(rng.integers(-12, 13, size=d)).astype(np.float32)
+    return X
+
+
+@pytest.mark.parametrize("kind", ["large", "just_below", "tiny", "offset", "outlier", "integers", "mixed_scales"])
+@pytest.mark.parametrize("d,K,L", [(128, 10, 10), (36, 10, 16)])      # joins of at most 16 and of 17..32 vectors
+def test_nndescent_filter_ranges_bit_exact(ef, kind, d, K, L):
+    n, T, S, I = 6_000, 3, 16, 4
+    X = filter_data(kind, n, d)
+    Xd = dev(X)
+    (perm, off, nl), (operm, ooff, onl) = trees_equal(ef, X, T, S, synth.ALGO_SEED)
+    graph = ef.efanna_init_graph(Xd, perm, off, nl, S, K)
+    want = oracle.init_graph(X, operm, ooff, onl, K)
+    for it in range(I):
+        ef.efanna_nndescent(Xd, graph, 1, L, synth.ALGO_SEED, first_iter=it)
+        want = oracle.nndescent(X, *want[:3], 1, L, synth.ALGO_SEED, iter0=it)
+        graph_equal(ef, graph, want)
+
+
 @pytest.mark.parametrize("n,d,T,S,K,L,I", [
     (3_000, 200, 2, 12, 8, 8, 3),        # long vectors with a ragged last piece (128 + 72): joins by rotations
     (2_500, 132, 2, 16, 10, 10, 2),      # just over one piece
