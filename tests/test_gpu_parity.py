@@ -303,6 +303,8 @@ def filter_data(kind, n, d):
         X = X * np.float32(3e-6)
     elif kind == "offset":         # norms a thousand times the distances
         X = X + np.float32(900.0)
+    elif kind == "far_offset":     # neighbouring points round to the same few half-precision values
+        X = X + np.float32(30_000.0)
     elif kind == "outlier":        # one huge coordinate sets the scale, the rest turn subnormal
         X[17, 3] = np.float32(500_000.0)
     elif kind == "integers":       # heavy ties, many zero distances
@@ -312,7 +314,8 @@ def filter_data(kind, n, d):
     return X
 
 
-@pytest.mark.parametrize("kind", ["large", "just_below", "tiny", "offset", "outlier", "integers", "mixed_scales"])
+@pytest.mark.parametrize("kind", ["large", "just_below", "tiny", "offset", "far_offset", "outlier", "integers",
+                                  "mixed_scales"])
 @pytest.mark.parametrize("d,K,L", [(128, 10, 10), (36, 10, 16)])      # joins of at most 16 and of 17..32 vectors
 def test_nndescent_filter_ranges_bit_exact(ef, kind, d, K, L):
     n, T, S, I = 6_000, 3, 16, 4
