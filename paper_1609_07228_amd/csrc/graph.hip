@@ -171,7 +171,7 @@ __device__ inline int drain_queue_g16(const Proposal *queue, int count, u64 *gra
 }
 
 // ---------------------------------------------------------------------------------------
-// Alg. 3 at the leaves, one tree per launch, one block per leaf (64 threads per 16 leaf
+// Alg. 3 at the leaves, one tree per launch, one block per leaf (256 threads per 16 leaf
 // slots).  Within one tree every point lies in exactly one leaf, so a block owns the graph
 // rows of its members for the duration of the launch and needs no atomics.  Launches of
 // successive trees are ordered by the stream.
@@ -184,7 +184,7 @@ __device__ inline int drain_queue_g16(const Proposal *queue, int count, u64 *gra
 // it; ranks below K are stored straight to the row.  Every slot of a row is written exactly
 // once (K old entries plus the fresh candidates are at least K keys, all distinct).
 
-__global__ void __launch_bounds__(kBlock)
+__global__ void __launch_bounds__(1024)
 init_tree_kernel(const float *__restrict__ X, int d, int stride, u32 q4_magic, int S,
                  const int *__restrict__ perm_t, const int *__restrict__ leaf_off_t, int K,
                  u64 *graph, int first_tree)
@@ -195,6 +195,7 @@ init_tree_kernel(const float *__restrict__ X, int d, int stride, u32 q4_magic, i
     u64 *pools = (u64 *)(dmat + align4(S * S));           // [S][K] old rows, ascending
     u64 *cand = pools + (size_t)S * K;                    // [S][S + 1] candidate keys of each row
     int *uid = (int *)(cand + (size_t)S * (S + 1));       // [S]
+    int *ncand = uid + S;                                 // [S] candidates of each row that may enter it
     int *below = (int *)dmat;
     const int tid = threadIdx.x, nthr = blockDim.x;
     const int b = leaf_off_t[blockIdx.x];
@@ -249,23 +250,43 @@ init_tree_kernel(const float *__restrict__ X, int d, int stride, u32 q4_magic, i
                 if (lo < K && row[lo] == key) key = ~0ULL;      // already there from an earlier tree
             }
         }
+        // A key above all K old entries stays out of the row, and so does every candidate above
+        // it: it counts for nobody.  (Rows are full after a tree or two; from then on this is what
+        // happens to most candidates.)
+        if (lo >= K) key = ~0ULL;
         cand[a * pitch + o] = key;
         below[a * S + o] = lo;
     }
     __syncthreads();
+    // the candidates still in the race move to the front of their row (a wave per row: its
+    // lanes read the row before any of them writes), their number to ncand
+    for (int a = tid / EF_WAVE; a < s; a += nthr / EF_WAVE) {
+        const int o = ef_lane();
+        const u64 key = o < s ? cand[a * pitch + o] : ~0ULL;
+        const int lo = o < s ? below[a * S + o] : 0;
+        const u64 alive = __ballot(key != ~0ULL);
+        if (key != ~0ULL) {
+            const int pos = __popcll(alive & ((1ULL << o) - 1));
+            cand[a * pitch + pos] = key;
+            below[a * S + pos] = lo;
+        }
+        if (o == 0) ncand[a] = __popcll(alive);
+    }
+    __syncthreads();
     for (int e = tid; e < s * s; e += nthr) {      // the candidates' places
-        const int a = e / s, o = e - a * s;
+        const int a = e / s, o = e - a * s, nc = ncand[a];
+        if (o >= nc) continue;
         const u64 key = cand[a * pitch + o];
-        if (key == ~0ULL) continue;
         int rank = below[a * S + o];
-        for (int k = 0; k < s; ++k) rank += cand[a * pitch + k] < key ? 1 : 0;
+        for (int k = 0; k < nc; ++k) rank += cand[a * pitch + k] < key ? 1 : 0;
         if (rank < K) graph[(size_t)uid[a] * K + rank] = key;
     }
-    for (int e = tid; e < s * K; e += nthr) {      // the old entries' places
-        const int a = e / K, j = e - a * K;
+    for (int e = tid; e < s * K; e += nthr) {      // the old entries' places (a row without candidates stays as it is)
+        const int a = e / K, j = e - a * K, nc = ncand[a];
+        if (nc == 0 && !first_tree) continue;
         const u64 en = pools[e];
         int rank = j;
-        for (int k = 0; k < s; ++k) rank += cand[a * pitch + k] < en ? 1 : 0;
+        for (int k = 0; k < nc; ++k) rank += cand[a * pitch + k] < en ? 1 : 0;
         if (rank < K) graph[(size_t)uid[a] * K + rank] = en;
     }
 }
@@ -2760,8 +2781,10 @@ extern "C" int efanna_init_graph(const float *X, int64_t n, int32_t d, const int
     const int stride = d + kRowPad;
     const size_t lds = (size_t)(align4(leaf_size * stride) + align4(leaf_size * leaf_size)) * 4 +
                        (size_t)leaf_size * k * 8 + (size_t)leaf_size * (leaf_size + 1) * 8 +
-                       (size_t)leaf_size * 4;
-    const int block_threads = EF_WAVE * ((leaf_size + 15) / 16);
+                       (size_t)leaf_size * 8;
+    // (a block per leaf and, with leaves of 64 and rows of 100, one block per CU: sixteen waves
+    // of it keep the CU busy through the loads of the rows)
+    const int block_threads = 4 * EF_WAVE * ((leaf_size + 15) / 16);
     const bool reg_ok = leaf_size <= 16 && d % 4 == 0 && ((uintptr_t)X & 15) == 0;
     if (leaf_size > EF_WAVE) return EFANNA_EUNSUPPORTED;
     if (reg_ok) {
