@@ -1755,6 +1755,139 @@ __global__ void __launch_bounds__(512) join_kernel(const float *__restrict__ X, 
 }
 
 // ---------------------------------------------------------------------------------------
+// The same for long lists (some hundred ids per point): a thread per point would compare every
+// id with every other and leaves room for a wave or three per CU next to its lists.  Here a
+// wave takes a point: the four lists are read 64 ids at a time, an id is new to the join if
+// its insertion into a hash table in LDS (open addressing, cleared per point) finds it absent,
+// and a ballot gives the fresh ids their places.  A block of four waves takes 256 consecutive
+// points per round and appends them to the work lists together (one counter bump per list and
+// round).  Same lists as prepare_kernel up to the order of the ids inside U_new and U_old,
+// which nothing depends on.  part: one triple per block.
+template <bool IDS32>
+__global__ void __launch_bounds__(kBlock)
+prepare_wave_kernel(const int *__restrict__ nw, const int *__restrict__ od,
+                    const int *__restrict__ nw_c, const int *__restrict__ od_c,
+                    const u64 *__restrict__ rnew, const u64 *__restrict__ rold,
+                    const int *__restrict__ rnew_c, const int *__restrict__ rold_c,
+                    int n, int K, int L, int cap, int hash_slots, JoinClasses jc,
+                    int *__restrict__ ulist, int2 *__restrict__ ucount,
+                    int *__restrict__ work, int *__restrict__ work_count,
+                    long long *__restrict__ part)
+{
+    extern __shared__ int prep_sh[];
+    constexpr int n_waves = kBlock / EF_WAVE;
+    const int lane = ef_lane(), wave = threadIdx.x / EF_WAVE;
+    int *hash = prep_sh + wave * (hash_slots + cap + EF_WAVE);      // [hash_slots]
+    int *out = hash + hash_slots;                                  // [cap]
+    int *cls_of = out + cap;                                       // [64] class of each point of the round
+    __shared__ int wave_cnt[kMaxClasses][n_waves], block_base[kMaxClasses];
+    __shared__ long long wave_sum[3][n_waves];
+    const int hshift = 32 - (31 - __clz(hash_slots));
+    auto wave_sync = [&]() {      // one wave: its LDS operations complete in program order
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+    };
+    long long evals = 0, rows = 0, rows0 = 0;      // lane 0: this wave's share of the iteration's work counters
+    for (int i0 = blockIdx.x * kBlock; i0 < n; i0 += gridDim.x * kBlock) {      // (uniform over the block)
+        const int w0 = i0 + wave * EF_WAVE;
+        for (int p = 0; p < EF_WAVE; ++p) {
+            const int i = w0 + p;
+            if (i >= n) break;
+            const int c_new = nw_c[i], rn = min(rnew_c[i], L);
+            int m = 0, m_new = 0, cls = -1;
+            if (c_new + rn > 0) {
+                const int c_old = od_c[i], ro = min(rold_c[i], L);
+                for (int f = lane; f < hash_slots; f += EF_WAVE) hash[f] = -1;
+                wave_sync();
+                auto add = [&](int id, bool have) {      // all lanes call; have: this lane offers id
+                    bool fresh = false;
+                    if (have) {
+                        int h = (int)(((u32)id * 0x9E3779B1u) >> hshift);
+                        for (;;) {
+                            const int prev = atomicCAS(&hash[h], -1, id);
+                            if (prev == -1) {
+                                fresh = true;
+                                break;
+                            }
+                            if (prev == id) break;
+                            h = (h + 1) & (hash_slots - 1);
+                        }
+                    }
+                    const u64 mask = __ballot(fresh);
+                    if (fresh) out[m + __popcll(mask & ((1ULL << lane) - 1))] = id;
+                    m += __popcll(mask);
+                };
+                for (int a0 = 0; a0 < c_new; a0 += EF_WAVE) {
+                    const int a = a0 + lane;
+                    add(a < c_new ? nw[(size_t)i * L + a] : -1, a < c_new);
+                }
+                for (int a0 = 0; a0 < rn; a0 += EF_WAVE) {
+                    const int a = a0 + lane;
+                    const int id = a < rn ? (IDS32 ? (int)((const u32 *)rnew)[(size_t)i * L + a] : (int)(u32)rnew[(size_t)i * L + a]) : -1;
+                    add(id, a < rn);
+                }
+                m_new = m;
+                for (int a0 = 0; a0 < c_old; a0 += EF_WAVE) {
+                    const int a = a0 + lane;
+                    add(a < c_old ? od[(size_t)i * K + a] : -1, a < c_old);
+                }
+                for (int a0 = 0; a0 < ro; a0 += EF_WAVE) {
+                    const int a = a0 + lane;
+                    const int id = a < ro ? (IDS32 ? (int)((const u32 *)rold)[(size_t)i * L + a] : (int)(u32)rold[(size_t)i * L + a]) : -1;
+                    add(id, a < ro);
+                }
+                wave_sync();
+                if (m_new >= 1 && m >= 2) {
+                    cls = 0;
+                    while (cls < jc.n - 1 && m > jc.bound[cls]) ++cls;
+                    evals += (long long)m_new * (m_new - 1) / 2 + (long long)m_new * (m - m_new);
+                    rows += m;
+                    if (cls == 0) rows0 += m;
+                }
+            }
+            for (int f = lane; f < cap; f += EF_WAVE) ulist[(size_t)i * cap + f] = f < m ? out[f] : -1;
+            if (lane == 0) {
+                ucount[i] = make_int2(m_new, m);
+                cls_of[p] = cls;
+            }
+            wave_sync();      // out is free for the next point
+        }
+        // append the round's points to the work lists
+        const int mine = w0 + lane < n ? cls_of[lane] : -1;
+        int rank = 0;
+        for (int c = 0; c < jc.n; ++c) {
+            const u64 mask = __ballot(mine == c);
+            if (mine == c) rank = __popcll(mask & ((1ULL << lane) - 1));
+            if (lane == 0) wave_cnt[c][wave] = __popcll(mask);
+        }
+        __syncthreads();
+        if ((int)threadIdx.x < jc.n) {
+            int tot = 0;
+            for (int v = 0; v < n_waves; ++v) tot += wave_cnt[threadIdx.x][v];
+            block_base[threadIdx.x] = tot ? atomicAdd(&work_count[threadIdx.x], tot) : 0;
+        }
+        __syncthreads();
+        if (mine >= 0) {
+            int off = block_base[mine] + rank;
+            for (int v = 0; v < wave; ++v) off += wave_cnt[mine][v];
+            work[(size_t)mine * n + off] = w0 + lane;
+        }
+        __syncthreads();      // wave_cnt and block_base are free for the next round
+    }
+    if (lane == 0) {
+        wave_sum[0][wave] = evals;
+        wave_sum[1][wave] = rows;
+        wave_sum[2][wave] = rows0;
+    }
+    __syncthreads();
+    if (threadIdx.x < 3) {
+        long long sum = 0;
+        for (int v = 0; v < n_waves; ++v) sum += wave_sum[threadIdx.x][v];
+        part[(size_t)blockIdx.x * 3 + threadIdx.x] = sum;
+    }
+}
+
+// ---------------------------------------------------------------------------------------
 // The same local join for points whose join gathers at most 16 * NB vectors (NB = 1, 2),
 // which is nearly all of them.  One wave per point and no row buffer in LDS: lane
 // (r, g) = (lane % 16, lane / 16) loads 16-byte pieces of vector r (and 16 + r) straight
@@ -2980,6 +3113,13 @@ int nndescent_run(const float *X, int64_t n, int32_t d, int32_t k, efanna_entry 
     int prep_threads = (int)(65536 / ((size_t)(max_rows | 1) * 4)) / EF_WAVE * EF_WAVE;
     prep_threads = prep_threads > kBlock ? kBlock : (prep_threads < EF_WAVE ? EF_WAVE : prep_threads);
     const size_t prep_lds = (size_t)prep_threads * (max_rows | 1) * 4;
+    // long lists: a wave per point with a hash table of at least twice the longest list
+    const bool prep_wave = max_rows > 96;
+    int prep_hash = 128;
+    while (prep_hash < 2 * max_rows) prep_hash <<= 1;
+    const size_t prep_wave_lds = (size_t)(kBlock / EF_WAVE) * (prep_hash + max_rows + EF_WAVE) * 4;
+    const int prep_wave_grid = min(grid_for((size_t)n, kBlock), 256 * 8);
+    const int n_part = prep_wave ? prep_wave_grid : grid_for((size_t)n, prep_threads);
     // filter margins: Gram-form rounding error <= (2*dpad + 4) u (|a|^2 + |b|^2), u = 2^-24,
     // doubled; the fixed-order distance is within (d/16 + 8) u of the true one, doubled twice
     const float margin_rel = (float)((4.0 * dpad + 16.0) * 5.9604644775390625e-08);
@@ -3118,8 +3258,18 @@ int nndescent_run(const float *X, int64_t n, int32_t d, int32_t k, efanna_entry 
         w.nw, w.od, w.nw_c, w.od_c, w.rnew, w.rold, w.rnew_c, w.rold_c, (int)n, K, L, max_rows,     \
         (u32)(((1ULL << 32) + max_rows - 1) / max_rows), jc, w.ulist, w.ucount, w.work,            \
         w.work_count, w.part)
-        if (bkt) EF_PREPARE(true);
-        else EF_PREPARE(false);
+#define EF_PREPARE_WAVE(IDS32)                                                                      \
+    prepare_wave_kernel<IDS32><<<prep_wave_grid, kBlock, prep_wave_lds, st>>>(                      \
+        w.nw, w.od, w.nw_c, w.od_c, w.rnew, w.rold, w.rnew_c, w.rold_c, (int)n, K, L, max_rows,     \
+        prep_hash, jc, w.ulist, w.ucount, w.work, w.work_count, w.part)
+        if (prep_wave) {
+            if (bkt) EF_PREPARE_WAVE(true);
+            else EF_PREPARE_WAVE(false);
+        } else {
+            if (bkt) EF_PREPARE(true);
+            else EF_PREPARE(false);
+        }
+#undef EF_PREPARE_WAVE
 #undef EF_PREPARE
         if (ev) EF_HIP_CHECK(hipEventRecord(ev[5 * it + 1], st));
         if (tiles && max_rows > rows1)
@@ -3189,7 +3339,7 @@ int nndescent_run(const float *X, int64_t n, int32_t d, int32_t k, efanna_entry 
         }      // pass
         if (ev) EF_HIP_CHECK(hipEventRecord(ev[5 * it + 4], st));
         if (stats)
-            stats_kernel<<<16, kBlock, 0, st>>>(w.part, grid_for((size_t)n, prep_threads), w.upd_block,
+            stats_kernel<<<16, kBlock, 0, st>>>(w.part, n_part, w.upd_block,
                                                 n_upd_block, stats + 4 * it);
         done = it + 1;
         if (delta > 0.0f) {      // early termination: the host looks at the count after every iteration
