@@ -563,7 +563,7 @@ finish_kernel(const float *__restrict__ XT, int d, int *perm, const SmallNode *_
     int *wave_tot = fsm + 6 * kFinMax + 4;                         // [kFinThreads / EF_WAVE]
     int &n_next_sh = fsm[6 * kFinMax + 2];
     int &depth_sh = fsm[6 * kFinMax + 3];                          // deepest node of this subtree
-    LNode *const tabs_base = (LNode *)(fsm + 6 * kFinMax + 16);     // [2][kFinNodes], 8-byte aligned
+    LNode *const tabs_base = (LNode *)(fsm + 6 * kFinMax + 32);     // [2][kFinNodes], 8-byte aligned
     const SmallNode seg = small[blockIdx.x];
     const int cnt = seg.e - seg.b, tid = threadIdx.x;
     const u64 key = ef_stream_key(seed, seg.b / n);
@@ -928,7 +928,7 @@ extern "C" int efanna_build_trees_rule(const float *X, int64_t n, int32_t d, int
     }
     // host_c.small_nodes is current: it was read after the last level (or after the roots)
     if (host_c.small_nodes > 0) {
-        const size_t fin_lds = (size_t)(6 * kFinMax + 16) * 4 + 2 * (size_t)kFinNodes * sizeof(LNode);
+        const size_t fin_lds = (size_t)(6 * kFinMax + 32) * 4 + 2 * (size_t)kFinNodes * sizeof(LNode);
         EF_HIP_CHECK(hipFuncSetAttribute((const void *)finish_kernel,
                                          hipFuncAttributeMaxDynamicSharedMemorySize, (int)fin_lds));
         finish_kernel<<<host_c.small_nodes, kFinThreads, fin_lds, st>>>(w.xt, d, perm_cur, w.small, w.leaf_flag,
