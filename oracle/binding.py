@@ -117,7 +117,8 @@ def dist(a, b) -> np.float32:
 
 
 def build_trees(X, T: int, S: int, seed: int, split_rule: int = 0):
-    """Alg. 2 (split_rule 1: the split dimension is chosen among the five of largest variance).
+    """Alg. 2 (split_rule 1: the split dimension is chosen among the five of largest variance; 2: a
+    node splits on a random projection, a signed sum of eight coordinates).
     Returns (perm [T,n] int32, leaf_off [T,n+1] int32, n_leaves [T] int32)."""
     X = _f32(X)
     n, d = X.shape

@@ -112,7 +112,7 @@ typedef struct {
     const float *X;
     int64_t n;
     int32_t d, S, tree;
-    int32_t split_rule; /* 0: the dimension is drawn uniformly (Alg. 2 as printed), 1: by variance */
+    int32_t split_rule; /* 0: the dimension is drawn uniformly (Alg. 2 as printed), 1: by variance, 2: a random projection */
     uint64_t seed;
     int32_t *perm;     /* this tree's id array, partitioned in place */
     int32_t *tmp;      /* scratch of n ids */
@@ -121,6 +121,27 @@ typedef struct {
     oracle_node *rec;  /* NULL, or n+1 records indexed by the position where the right part starts */
     int32_t *leaf_rec; /* NULL, or for the leaf starting at position b: parent position * 2 + side */
 } tree_ctx;
+
+/* What a node's split test looks at.  dim >= 0: the quantised coordinate dim.  dim <= -3: a random
+ * projection (the trees the paper's last section proposes to try for high dimensions): the sum
+ * of eight quantised coordinates with signs, both drawn from the 30-bit number r = -3 - dim that
+ * the node's draw supplies - term k takes z = mix64((r << 8) + k + golden), coordinate z mod d,
+ * minus if the top bit of z is set.  Exact in 64-bit integers for n * 8 * |x| < 2^43. */
+#define RP_TERMS 8
+static int64_t node_value(const float *x, int32_t d, int32_t dim)
+{
+    if (dim >= 0) return quantise(x[dim]);
+    uint64_t r = (uint64_t)(uint32_t)(-3 - dim);
+    int64_t v = 0;
+    for (int k = 0; k < RP_TERMS; ++k) {
+        uint64_t z = mix64((r << 8) + (uint64_t)k + 0x9E3779B97F4A7C15ULL);
+        int64_t q = quantise(x[z % (uint64_t)d]);
+        v += (z >> 63) ? -q : q;
+    }
+    return v;
+}
+/* the dimension code of a projection node from the node's draw */
+static int32_t projection_code(uint64_t draw) { return -3 - (int32_t)((draw >> 34) & 0x3FFFFFFFULL); }
 
 /* Split dimension by variance, the rule of the randomized KD-tree that Sec. 3.2 takes over
  * (its trees differ from that one in the leaf size only): estimate every dimension's variance
@@ -170,12 +191,14 @@ static int64_t build_node(tree_ctx *c, uint64_t heap_id, int32_t depth, int64_t 
     int64_t sum = 0;
     if (depth < 60) {
         uint64_t draw = oracle_node_rand(c->seed, c->tree, heap_id);
-        dim = c->split_rule == 1 ? variance_dim(c, b, e, draw) : (int32_t)(draw % (uint64_t)c->d);
-        for (int64_t p = b; p < e; ++p) sum += quantise(c->X[(int64_t)c->perm[p] * c->d + dim]);
+        dim = c->split_rule == 1   ? variance_dim(c, b, e, draw)
+              : c->split_rule == 2 ? projection_code(draw)
+                                   : (int32_t)(draw % (uint64_t)c->d);
+        for (int64_t p = b; p < e; ++p) sum += node_value(c->X + (int64_t)c->perm[p] * c->d, c->d, dim);
         int64_t nl = 0, nr = 0;
         for (int64_t p = b; p < e; ++p) { /* stable: both parts keep their order */
             int32_t id = c->perm[p];
-            if (cnt * quantise(c->X[(int64_t)id * c->d + dim]) < sum) c->perm[b + nl++] = id;
+            if (cnt * node_value(c->X + (int64_t)id * c->d, c->d, dim) < sum) c->perm[b + nl++] = id;
             else c->tmp[nr++] = id;
         }
         memcpy(c->perm + b + nl, c->tmp, (size_t)nr * sizeof(int32_t));
@@ -213,11 +236,13 @@ int oracle_build_trees_rule(const float *X, int64_t n, int32_t d, int32_t T, int
                             int32_t *n_leaves, oracle_node *nodes, int32_t *leaf_up)
 {
     if (!X || n < 1 || d < 1 || T < 1 || S < 1 || (!nodes) != (!leaf_up)) return -1;
-    if (split_rule != 0 && split_rule != 1) return -1;
+    if (split_rule < 0 || split_rule > 2) return -1;
     /* domain of the exact mean test: finite, |x| < 2^20 (so |q| <= 2^40), and n * |x| < 2^43, so
      * that cnt * q(x) and the sum of q over a node stay below 2^63 */
     for (int64_t i = 0; i < n * d; ++i)
-        if (!(fabsf(X[i]) < 1048576.0f) || (double)fabsf(X[i]) * (double)n >= 8796093022208.0) return -3;
+        if (!(fabsf(X[i]) < 1048576.0f) ||
+            (double)fabsf(X[i]) * (double)n * (split_rule == 2 ? RP_TERMS : 1) >= 8796093022208.0)
+            return -3;
     int32_t *tmp = (int32_t *)malloc((size_t)n * sizeof(int32_t));
     oracle_node *rec = nodes ? (oracle_node *)malloc((size_t)(n + 1) * sizeof(oracle_node)) : NULL;
     int32_t *leaf_rec = nodes ? (int32_t *)malloc((size_t)(n + 1) * sizeof(int32_t)) : NULL;
@@ -346,12 +371,12 @@ static int cmp_i32(const void *a, const void *b)
  * subtree is used as a classifier for i) and the members of the leaf it reaches
  * join the candidates.  `up` is the link of the node below N on i's path.
  * A node without a split dimension (below depth 60) sends every point left. */
-static int32_t sibling_leaf(const float *xi, const oracle_node *nodes, int32_t up)
+static int32_t sibling_leaf(const float *xi, int32_t d, const oracle_node *nodes, int32_t up)
 {
     int32_t c = nodes[up >> 1].child[1 - (up & 1)];
     while (c >= 0) {
         const oracle_node *nd = &nodes[c];
-        int left = nd->dim < 0 || (int64_t)nd->cnt * quantise(xi[nd->dim]) < nd->sum;
+        int left = nd->dim == -1 || (int64_t)nd->cnt * node_value(xi, d, nd->dim) < nd->sum;
         c = nd->child[left ? 0 : 1];
     }
     return ~c;
@@ -408,7 +433,7 @@ int oracle_conquer_graph(const float *X, int64_t n, int32_t d, const int32_t *pe
                         if (j != i) cand[nc++] = j;
                     }
                     if (up < 0 || nd[up >> 1].depth < dep) break;
-                    l = sibling_leaf(X + i * d, nd, up);
+                    l = sibling_leaf(X + i * d, d, nd, up);
                     int32_t j = up >> 1, pj = nd[j].parent;
                     up = pj < 0 ? -1 : pj * 2 + (nd[pj].child[1] == j);
                 }
@@ -660,7 +685,7 @@ typedef struct { double prio; int32_t link; } branch;
  * (priority, link) put aside so far is followed.  A node without a dimension sends
  * the query left and puts the right child aside at the same priority.  Returns the
  * number of leaves written to `leaves` (at most want). */
-static int32_t tree_search(const float *q, const oracle_node *nodes, int32_t n_leaves, int32_t want,
+static int32_t tree_search(const float *q, int32_t d, const oracle_node *nodes, int32_t n_leaves, int32_t want,
                            int32_t *leaves, branch *heap, int32_t heap_cap)
 {
     if (n_leaves == 1) {
@@ -679,11 +704,11 @@ static int32_t tree_search(const float *q, const oracle_node *nodes, int32_t n_l
             const oracle_node *nd = &nodes[link];
             int left = 1;
             double other = prio;
-            if (nd->dim >= 0) {
-                int64_t diff = (int64_t)nd->cnt * quantise(q[nd->dim]) - nd->sum;
+            if (nd->dim != -1) {
+                int64_t diff = (int64_t)nd->cnt * node_value(q, d, nd->dim) - nd->sum;
                 left = diff < 0;
                 double gap = (double)diff / ((double)nd->cnt * 1048576.0);
-                other = fma(gap, gap, prio);
+                other = fma(gap, gap, prio); /* (along a projection: in units of its length, the same for every node) */
             }
             if (n_heap == heap_cap) return -1; /* cannot happen with the caller's capacity */
             heap[n_heap].prio = other;
@@ -738,7 +763,7 @@ int oracle_search(const float *X, int64_t n, int32_t d, const int32_t *perm,
             int32_t cnt = 0, n_touched = 0, cap = E;
             for (int32_t t = 0; t < T; ++t) {
                 const int32_t *off = leaf_off + (int64_t)t * (n + 1);
-                int32_t found = tree_search(q, nodes + (int64_t)t * (n + 1), n_leaves[t], want, leaves,
+                int32_t found = tree_search(q, d, nodes + (int64_t)t * (n + 1), n_leaves[t], want, leaves,
                                             heap, heap_cap);
                 if (found < 0) {
 #pragma omp atomic write

@@ -18,6 +18,7 @@ TREES = ["tests/test_oracle_trees.py"]
 GRAPH = ["tests/test_oracle_graph.py"]
 CONQUER = ["tests/test_oracle_conquer.py"]
 SEARCH = ["tests/test_oracle_search.py"]
+PROJ = ["tests/test_oracle_projection.py"]
 
 # (name, text in the oracle, what the mistake turns it into, pin files that must notice)
 MUTANTS = [
@@ -60,6 +61,18 @@ MUTANTS = [
      "s2 += (__int128)q * q;", "s2 += (__int128)(int64_t)((uint64_t)q * (uint64_t)q);", TREES),
     ("trees, variance rule: four candidates instead of five",
      "return top[draw % (uint64_t)n_top];", "return top[draw % (uint64_t)(n_top > 4 ? 4 : n_top)];", TREES),
+    ("trees, projections: the signs are ignored",
+     "v += (z >> 63) ? -q : q;", "v += q;", PROJ),
+    ("trees, projections: seven terms instead of eight",
+     "for (int k = 0; k < RP_TERMS; ++k) {\n        uint64_t z = mix64((r << 8)",
+     "for (int k = 0; k < RP_TERMS - 1; ++k) {\n        uint64_t z = mix64((r << 8)", PROJ),
+    ("trees, projections: the code keeps the wrong bits of the draw",
+     "((draw >> 34) & 0x3FFFFFFFULL)", "(draw & 0x3FFFFFFFULL)", PROJ),
+    ("trees, projections: routing in a sibling subtree looks at one coordinate only",
+     "int left = nd->dim == -1 || (int64_t)nd->cnt * node_value(xi, d, nd->dim) < nd->sum;",
+     "int left = nd->dim < 0 || (int64_t)nd->cnt * quantise(xi[nd->dim]) < nd->sum;", PROJ),
+    ("search, projections: a projection node sends every query left",
+     "            if (nd->dim != -1) {\n                int64_t diff", "            if (nd->dim >= 0) {\n                int64_t diff", PROJ),
     ("lists: equal distances ordered by the larger id",
      "(da == db && ia < ib)", "(da == db && ia > ib)", GRAPH),
     ("lists: an id already present is entered again",
@@ -84,8 +97,8 @@ MUTANTS = [
     ("NN-descent: members of U_new stay in U_old",
      "if (!bsearch(&uo[s], un, (size_t)n_new, sizeof(int32_t), cmp_i32))", "if (1)", GRAPH),
     ("conquer: a node without a split test sends points right",
-     "int left = nd->dim < 0 || (int64_t)nd->cnt * quantise(xi[nd->dim]) < nd->sum;",
-     "int left = nd->dim >= 0 && (int64_t)nd->cnt * quantise(xi[nd->dim]) < nd->sum;", CONQUER),
+     "int left = nd->dim == -1 || (int64_t)nd->cnt * node_value(xi, d, nd->dim) < nd->sum;",
+     "int left = nd->dim != -1 && (int64_t)nd->cnt * node_value(xi, d, nd->dim) < nd->sum;", CONQUER),
     ("conquer: the point's own side is searched instead of the sibling's",
      "int32_t c = nodes[up >> 1].child[1 - (up & 1)];", "int32_t c = nodes[up >> 1].child[up & 1];", CONQUER),
     ("search: the branch put aside forgets the priority of the path so far",
