@@ -211,8 +211,9 @@ def main():
                          "iteration of both")
     ap.add_argument("--ablation-split", type=int, default=0, metavar="ITERS",
                     help="also build the trees with the split dimension taken among the five of largest "
-                         "variance (Sec. 3.2) and add an `ablation_split` object: tree time, accuracy of the "
-                         "initial graph and after every one of ITERS iterations, for both rules")
+                         "variance (Sec. 3.2) and with random-projection splits, and add an `ablation_split` "
+                         "object: tree time, accuracy of the initial graph and after every one of ITERS "
+                         "iterations, for the three rules")
     ap.add_argument("--ablation-marking", type=int, default=0, metavar="ITERS",
                     help="after the build, run NN-descent one iteration at a time for ITERS iterations with fresh "
                          "entries always marked new (the default) and with the literal marking of Alg. 4 (what a new "
@@ -398,7 +399,8 @@ def main():
             return sum(np.intersect1d(a[a >= 0], b).shape[0] for a, b in zip(got, truth_s)) / float(truth_s.size)
 
         split = {"recall_rows": int(rows_s.shape[0])}
-        for label, rule in (("uniform", efanna.SPLIT_UNIFORM), ("variance", efanna.SPLIT_VARIANCE)):
+        for label, rule in (("uniform", efanna.SPLIT_UNIFORM), ("variance", efanna.SPLIT_VARIANCE),
+                            ("projection", efanna.SPLIT_PROJECTION)):
             for rep_ in range(2):      # the first round warms up
                 torch.cuda.synchronize()
                 a0 = time.perf_counter()

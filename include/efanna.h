@@ -74,8 +74,9 @@ typedef uint64_t efanna_entry;
 
 /* An internal tree node as the conquer step of Alg. 3 uses it.  A point x goes to the left
  * child iff cnt * q(x[dim]) < sum, q(x) = x * 2^20 rounded to the nearest integer (ties to
- * even), which is the test the node's own points were divided by; dim < 0 (nodes below depth
- * 60, which are cut by position) sends every point left.  The internal nodes of a tree are
+ * even), which is the test the node's own points were divided by; dim -1 (nodes below depth
+ * 60, which are cut by position) sends every point left; dim <= -3 names a random projection
+ * that takes the place of q(x[dim]) (EFANNA_SPLIT_PROJECTION below).  The internal nodes of a tree are
  * numbered 1 .. n_leaves-1: node j is the one whose right part starts with leaf j.
  * child[s] >= 0 names an internal node, child[s] < 0 is ~(leaf index); parent is -1 at the
  * root; depth counts from 0 at the root. */
@@ -132,9 +133,18 @@ int efanna_build_trees(const float *X, int64_t n, int32_t d, int32_t n_trees, in
  *          100 positions (all of them in a smaller node), exactly: as the integer
  *          m*sum(q^2) - sum(q)^2 of the quantised coordinates, equal values ordered by the
  *          smaller dimension; with d < 5 all dimensions are candidates, in that order.
+ * split_rule EFANNA_SPLIT_PROJECTION: a node splits on a random projection instead of a coordinate
+ *          (the trees the paper's closing section proposes to try for high dimensions): the sum
+ *          of eight quantised coordinates with signs, both drawn from a 30-bit number r taken
+ *          from the node's draw (bits 34..63) - term k uses z = mix(256 r + k + golden),
+ *          coordinate z mod d, minus if the top bit of z is set.  The mean test is the same,
+ *          cnt*p(x) < sum(p), exact for n * 8 * |x| < 2^43 (EFANNA_EINPUT otherwise).  Such a
+ *          node's efanna_node.dim is -3 - r; efanna_init_graph and efanna_search route through
+ *          these nodes like through any other.
  * Any other value: EFANNA_EINVAL.  Everything else as efanna_build_trees. */
 #define EFANNA_SPLIT_UNIFORM 0
 #define EFANNA_SPLIT_VARIANCE 1
+#define EFANNA_SPLIT_PROJECTION 2
 int efanna_build_trees_rule(const float *X, int64_t n, int32_t d, int32_t n_trees, int32_t leaf_size,
                             uint64_t seed, int32_t split_rule, int32_t *perm, int32_t *leaf_off,
                             int32_t max_leaves, int32_t *n_leaves, efanna_node *nodes,

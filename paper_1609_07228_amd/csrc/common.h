@@ -43,6 +43,29 @@ __host__ __device__ inline u64 ef_stream_key(u64 seed, int k)
 // coordinate of the exact mean test of Alg. 2: multiples of 2^-20 as integers
 __device__ inline long long ef_quantise(float x) { return (long long)rint((double)x * 1048576.0); }
 
+// What a tree node's split test looks at.  dim >= 0: the quantised coordinate dim (clamped into
+// the vector: foreign tables cannot lead out of it).  dim <= -3: a random projection, the sum of
+// eight quantised coordinates with signs, both drawn from the 30-bit number r = -3 - dim that the
+// node's draw supplies - term k takes z = mix((r << 8) + k + golden), coordinate z mod d, minus if
+// the top bit of z is set.  dim -1 (and -2): no test.  coord(j) returns coordinate j of the vector.
+constexpr int kProjectionTerms = 8;
+__host__ __device__ inline bool ef_has_test(int dim) { return dim >= 0 || dim <= -3; }
+__host__ __device__ inline int ef_projection_code(u64 draw) { return -3 - (int)((draw >> 34) & 0x3FFFFFFFULL); }
+template <class Coord>
+__device__ inline long long ef_node_value(Coord coord, int d, int dim)
+{
+    if (dim >= 0) return ef_quantise(coord(dim < d ? dim : d - 1));
+    const u64 r = (u64)(u32)(-3 - dim);
+    long long v = 0;
+#pragma unroll
+    for (int k = 0; k < kProjectionTerms; ++k) {
+        const u64 z = ef_mix64((r << 8) + (u64)k + 0x9E3779B97F4A7C15ULL);
+        const long long q = ef_quantise(coord((int)(z % (u64)d)));
+        v += (z >> 63) ? -q : q;
+    }
+    return v;
+}
+
 // ---- packed graph entries -------------------------------------------------------------
 __device__ inline u64 ef_pack(float dist, int id, int is_new)
 {

@@ -600,8 +600,9 @@ classify_kernel(const float *__restrict__ X, int d, const int *__restrict__ perm
                     int c = sib_sh[wave][k];
                     for (int steps = 0; c >= 0 && steps < 4096; ++steps) {
                         const efanna_node nd = nodes_t[min(c, last)];
-                        const bool left = nd.dim < 0 ||
-                                          (long long)nd.cnt * ef_quantise(X[(size_t)my_id * d + max(0, min(nd.dim, d - 1))]) < nd.sum;
+                        const float *xi = X + (size_t)my_id * d;
+                        const bool left = !ef_has_test(nd.dim) ||
+                                          (long long)nd.cnt * ef_node_value([&](int j) { return xi[j]; }, d, nd.dim) < nd.sum;
                         c = nd.child[left ? 0 : 1];
                     }
                     e = c >= 0 ? 0 : min(~c, last);
@@ -770,8 +771,9 @@ classify_any_kernel(const float *__restrict__ X, int d, const int *__restrict__ 
                     int c = anc.child[1 - (up & 1)];
                     for (int steps = 0; c >= 0 && steps < 4096; ++steps) {      // (bounded: foreign tables cannot hold it)
                         const efanna_node nd = nodes_t[min(c, last)];
-                        const bool left = nd.dim < 0 ||
-                                          (long long)nd.cnt * ef_quantise(X[(size_t)my_id * d + max(0, min(nd.dim, d - 1))]) < nd.sum;
+                        const float *xi = X + (size_t)my_id * d;
+                        const bool left = !ef_has_test(nd.dim) ||
+                                          (long long)nd.cnt * ef_node_value([&](int j) { return xi[j]; }, d, nd.dim) < nd.sum;
                         c = nd.child[left ? 0 : 1];
                     }
                     e = c >= 0 ? 0 : min(~c, last);

@@ -225,8 +225,8 @@ search_kernel(const float *__restrict__ X, int d, int n, const int *__restrict__
                     const efanna_node nd = nd_t[min(link, last)];
                     bool left = true;
                     double other = prio;
-                    if (nd.dim >= 0) {
-                        const long long diff = (long long)nd.cnt * ef_quantise(q[min(nd.dim, d - 1)]) - nd.sum;
+                    if (ef_has_test(nd.dim)) {
+                        const long long diff = (long long)nd.cnt * ef_node_value([&](int j) { return q[j]; }, d, nd.dim) - nd.sum;
                         left = diff < 0;
                         const double gap = (double)diff / ((double)nd.cnt * 1048576.0);
                         other = __fma_rn(gap, gap, prio);

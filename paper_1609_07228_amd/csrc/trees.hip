@@ -93,7 +93,7 @@ inline int finish_limit(int S)
 // nearly consecutive) would touch one 4-byte word out of every row, a stride that keeps
 // hitting the same memory channels; in the transposed copy those reads are contiguous.
 __global__ void __launch_bounds__(kBlock)
-transpose_check_kernel(const float *__restrict__ X, int n, int d, float *__restrict__ XT, Counters *c)
+transpose_check_kernel(const float *__restrict__ X, int n, int d, float *__restrict__ XT, Counters *c, double terms)
 {
     __shared__ float tile[32][33];
     const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;      // 32 x 8
@@ -106,7 +106,8 @@ transpose_check_kernel(const float *__restrict__ X, int n, int d, float *__restr
         if (row < n && col < d) {
             v = X[(size_t)row * d + col];
             // false for NaN and inf as well; n |x| < 2^43 keeps cnt * q(x) and the sums below 2^63
-            bad |= !(fabsf(v) < 1048576.0f) || (double)fabsf(v) * (double)n >= 8796093022208.0;
+            // (terms: how many coordinates a node's test adds up, 1 or kProjectionTerms)
+            bad |= !(fabsf(v) < 1048576.0f) || (double)fabsf(v) * (double)n * terms >= 8796093022208.0;
         }
         tile[ty + 8 * k][tx] = v;
     }
@@ -192,6 +193,12 @@ __device__ inline int variance_dim_wave(const float *__restrict__ X, int d, cons
     return chosen;
 }
 
+// a fresh node's dimension code from its draw: the coordinate, "to be chosen by variance", or a projection
+__device__ inline int node_dim(int rule, u64 draw, int d)
+{
+    return rule == 1 ? kDimPending : rule == 2 ? ef_projection_code(draw) : (int)(draw % (u64)d);
+}
+
 // One wave per live node of the level: fixes the dimension of the nodes that wait for one.
 __global__ void __launch_bounds__(kBlock)
 choose_dims_kernel(const float *__restrict__ X, int d, int n, const int *__restrict__ perm, Node *nodes,
@@ -237,7 +244,8 @@ __global__ void roots_kernel(Node *nodes, int *dims, int *node_of, unsigned char
         nd.e = nd.b + n;
         nd.heap = 1;
         nd.sum = 0;
-        nd.dim = rule == 1 ? kDimPending : (int)(ef_mix64(ef_stream_key(seed, (int)p) + 1) % (u64)d);
+        const u64 draw = ef_mix64(ef_stream_key(seed, (int)p) + 1);
+        nd.dim = rule == 1 ? kDimPending : rule == 2 ? ef_projection_code(draw) : (int)(draw % (u64)d);
         nd.depth = 0;
         nd.mid = nd.b;
         nd.moved = 0;
@@ -259,7 +267,8 @@ __global__ void roots_kernel(Node *nodes, int *dims, int *node_of, unsigned char
 __global__ void __launch_bounds__(kBlock)
 sum_kernel(const float *__restrict__ XT, int n, const int *__restrict__ perm,
            const int *__restrict__ node_of, Node *nodes, const int *__restrict__ dims,
-           float *__restrict__ val, size_t total, Counters *c, int level, int tiles)
+           float *__restrict__ val, size_t total, Counters *c, int level, int tiles,
+           const float *__restrict__ X, int d)      // X: the rows (a projection adds up coordinates of one row)
 {
     if (blockIdx.x == 0 && threadIdx.x == 0) c->n_nodes[(level + 1) & 1] = 0;      // filled by children_kernel
     __shared__ long long wave_tot[kBlock / EF_WAVE];
@@ -281,6 +290,9 @@ sum_kernel(const float *__restrict__ XT, int n, const int *__restrict__ perm,
                     float x = XT[(size_t)dim * n + perm[p]];
                     val[p] = x;
                     q = ef_quantise(x);
+                } else if (dim <= -3) {
+                    const float *row = X + (size_t)perm[p] * d;
+                    q = ef_node_value([&](int j) { return row[j]; }, d, dim);
                 } else {
                     s = -1;
                 }
@@ -330,14 +342,19 @@ struct LeftPred {
     const int *node_of;
     const Node *nodes;
     const float *val;
+    const float *X;      // rows and ids, for the nodes that split on a projection
+    const int *perm;
+    int d;
     __device__ int operator()(size_t p) const
     {
         int s = node_of[p];
         if (s < 0) return 0;
         const Node &nd = nodes[s];
-        if (nd.dim < 0) return 0;
+        if (!ef_has_test(nd.dim)) return 0;
         long long cnt = nd.e - nd.b;
-        return cnt * ef_quantise(val[p]) < nd.sum ? 1 : 0;
+        if (nd.dim >= 0) return cnt * ef_quantise(val[p]) < nd.sum ? 1 : 0;
+        const float *row = X + (size_t)perm[p] * d;
+        return cnt * ef_node_value([&](int j) { return row[j]; }, d, nd.dim) < nd.sum ? 1 : 0;
     }
 };
 struct FlagPred {
@@ -444,7 +461,7 @@ __global__ void children_kernel(Node *cur, int level, Node *next, int *next_dims
     if (s < n_cur) {
         nd = cur[s];
         int cnt = nd.e - nd.b;
-        int nl = nd.dim >= 0 ? lcount[nd.e] - lcount[nd.b] : 0;
+        int nl = ef_has_test(nd.dim) ? lcount[nd.e] - lcount[nd.b] : 0;
         if (nl == 0 || nl == cnt) {
             nd.moved = 0;
             nd.mid = nd.b + cnt / 2;
@@ -485,7 +502,7 @@ __global__ void children_kernel(Node *cur, int level, Node *next, int *next_dims
             ch.e = ce;
             ch.depth = nd.depth + 1;
             ch.heap = ch_heap;
-            ch.dim = ch.depth < 60 ? (rule == 1 ? kDimPending : (int)(ef_mix64(key + ch.heap) % (u64)d)) : -1;
+            ch.dim = ch.depth < 60 ? node_dim(rule, ef_mix64(key + ch.heap), d) : -1;
             ch.sum = 0;
             ch.mid = cb;
             ch.moved = 0;
@@ -564,6 +581,9 @@ finish_kernel(const float *__restrict__ XT, int d, int *perm, const SmallNode *_
     int &n_next_sh = fsm[6 * kFinMax + 2];
     int &depth_sh = fsm[6 * kFinMax + 3];                          // deepest node of this subtree
     LNode *const tabs_base = (LNode *)(fsm + 6 * kFinMax + 32);     // [2][kFinNodes], 8-byte aligned
+    long long *const pval = (long long *)(tabs_base + 2 * kFinNodes);      // [kFinMax] projections (only with that rule)
+    // the quantised value position p is tested on, in a node with the dimension code dim
+    auto tested = [&](int p, int dim) { return dim >= 0 ? ef_quantise(val[p]) : pval[p]; };
     const SmallNode seg = small[blockIdx.x];
     const int cnt = seg.e - seg.b, tid = threadIdx.x;
     const u64 key = ef_stream_key(seed, seg.b / n);
@@ -580,7 +600,7 @@ finish_kernel(const float *__restrict__ XT, int d, int *perm, const SmallNode *_
         r.heap = seg.heap;
         r.sum = 0;
         r.depth = seg.depth;
-        r.dim = seg.depth < 60 ? (rule == 1 ? kDimPending : (int)(ef_mix64(key + seg.heap) % (u64)d)) : -1;
+        r.dim = seg.depth < 60 ? node_dim(rule, ef_mix64(key + seg.heap), d) : -1;
         r.child[0] = r.child[1] = -1;
         r.parent = seg.parent;
         r.pad = 0;
@@ -611,6 +631,11 @@ finish_kernel(const float *__restrict__ XT, int d, int *perm, const SmallNode *_
                 const float x = XT[(size_t)tc[k].dim * n + idc[p]];
                 val[p] = x;
                 atomicAdd((u64 *)&tc[k].sum, (u64)ef_quantise(x));
+            } else if (k >= 0 && tc[k].dim <= -3) {
+                const float *row = X + (size_t)idc[p] * d;
+                const long long v = ef_node_value([&](int j) { return row[j]; }, d, tc[k].dim);
+                pval[p] = v;
+                atomicAdd((u64 *)&tc[k].sum, (u64)v);
             }
         }
         __syncthreads();
@@ -621,8 +646,8 @@ finish_kernel(const float *__restrict__ XT, int d, int *perm, const SmallNode *_
             for (int p = p0; p < p1; ++p) {
                 const int k = nc[p];
                 int f = 0;
-                if (k >= 0 && tc[k].dim >= 0)
-                    f = (long long)(tc[k].e - tc[k].b) * ef_quantise(val[p]) < tc[k].sum ? 1 : 0;
+                if (k >= 0 && ef_has_test(tc[k].dim))
+                    f = (long long)(tc[k].e - tc[k].b) * tested(p, tc[k].dim) < tc[k].sum ? 1 : 0;
                 lcnt[p] = f;
                 mine += f;
             }
@@ -643,7 +668,7 @@ finish_kernel(const float *__restrict__ XT, int d, int *perm, const SmallNode *_
         for (int k = tid; k < n_cur; k += kFinThreads) {
             LNode nd = tc[k];
             const int c = nd.e - nd.b;
-            const int nl = nd.dim >= 0 ? lcnt[nd.e] - lcnt[nd.b] : 0;
+            const int nl = ef_has_test(nd.dim) ? lcnt[nd.e] - lcnt[nd.b] : 0;
             if (nl == 0 || nl == c) {
                 nd.moved = 0;
                 nd.mid = nd.b + c / 2;
@@ -666,7 +691,7 @@ finish_kernel(const float *__restrict__ XT, int d, int *perm, const SmallNode *_
                     ch.moved = 0;
                     ch.depth = nd.depth + 1;
                     ch.heap = nd.depth < 60 ? 2 * nd.heap + side : nd.heap;
-                    ch.dim = ch.depth < 60 ? (rule == 1 ? kDimPending : (int)(ef_mix64(key + ch.heap) % (u64)d)) : -1;
+                    ch.dim = ch.depth < 60 ? node_dim(rule, ef_mix64(key + ch.heap), d) : -1;
                     ch.sum = 0;
                     ch.child[0] = ch.child[1] = -1;
                     ch.parent = seg.b + nd.mid;
@@ -694,7 +719,7 @@ finish_kernel(const float *__restrict__ XT, int d, int *perm, const SmallNode *_
             const LNode &nd = tc[k];
             int dst = p;
             if (nd.moved) {
-                const bool left = (long long)(nd.e - nd.b) * ef_quantise(val[p]) < nd.sum;
+                const bool left = (long long)(nd.e - nd.b) * tested(p, nd.dim) < nd.sum;
                 const int lc = lcnt[p] - lcnt[nd.b];
                 dst = left ? nd.b + lc : nd.mid + (p - nd.b - lc);
             }
@@ -851,7 +876,9 @@ extern "C" int efanna_build_trees_rule(const float *X, int64_t n, int32_t d, int
                                        void *ws, size_t ws_bytes, void *stream)
 {
     if (!X || !perm || !leaf_off || !n_leaves || (!nodes) != (!leaf_up)) return EFANNA_EINVAL;
-    if (split_rule != EFANNA_SPLIT_UNIFORM && split_rule != EFANNA_SPLIT_VARIANCE) return EFANNA_EINVAL;
+    if (split_rule != EFANNA_SPLIT_UNIFORM && split_rule != EFANNA_SPLIT_VARIANCE &&
+        split_rule != EFANNA_SPLIT_PROJECTION)
+        return EFANNA_EINVAL;
     if (n < 1 || d < 1 || n_trees < 1 || n_trees > EFANNA_MAX_TREES || leaf_size < 1 ||
         leaf_size > EFANNA_MAX_LEAF || max_leaves < 1)
         return EFANNA_EINVAL;
@@ -868,7 +895,7 @@ extern "C" int efanna_build_trees_rule(const float *X, int64_t n, int32_t d, int
     EF_HIP_CHECK(hipMemsetAsync(w.counters, 0, sizeof(Counters), st));
     if (nodes) EF_HIP_CHECK(hipMemsetAsync(w.leaf_rec, 0xFF, total * 4, st));      // a lone root leaf has no parent
     transpose_check_kernel<<<dim3((unsigned)((n + 31) / 32), (unsigned)((d + 31) / 32)), kBlock, 0, st>>>(
-        X, (int)n, d, w.xt, w.counters);
+        X, (int)n, d, w.xt, w.counters, split_rule == EFANNA_SPLIT_PROJECTION ? (double)kProjectionTerms : 1.0);
     iota_kernel<<<grid_pos, kBlock, 0, st>>>(perm, (int)n, total);
     const int fin = finish_limit(S);
     roots_kernel<<<grid_pos, kBlock, 0, st>>>(w.nodes_a, w.dims_a, w.node_a, w.leaf_flag, (int)n, T, S, fin,
@@ -908,8 +935,8 @@ extern "C" int efanna_build_trees_rule(const float *X, int64_t n, int32_t d, int
             choose_dims_kernel<<<min(grid_nodes * (kBlock / EF_WAVE), 2048), kBlock, 0, st>>>(
                 X, d, (int)n, perm_cur, nodes_cur, dims_cur, w.counters, level, seed);
         sum_kernel<<<(grid_pos + tiles - 1) / tiles, kBlock, 0, st>>>(w.xt, (int)n, perm_cur, node_cur, nodes_cur,
-                                                                      dims_cur, w.val, total, w.counters, level, tiles);
-        LeftPred pred{node_cur, nodes_cur, w.val};
+                                                                      dims_cur, w.val, total, w.counters, level, tiles, X, d);
+        LeftPred pred{node_cur, nodes_cur, w.val, X, perm_cur, d};
         device_scan(pred, total, w.block_sums, w.lcount, w.left_bits, st);
         children_kernel<<<grid_nodes, kBlock, 0, st>>>(
             nodes_cur, level, nodes_nxt, dims_nxt, w.lcount, w.leaf_flag, S, fin, w.small, seed, (int)n, d,
@@ -928,7 +955,8 @@ extern "C" int efanna_build_trees_rule(const float *X, int64_t n, int32_t d, int
     }
     // host_c.small_nodes is current: it was read after the last level (or after the roots)
     if (host_c.small_nodes > 0) {
-        const size_t fin_lds = (size_t)(6 * kFinMax + 32) * 4 + 2 * (size_t)kFinNodes * sizeof(LNode);
+        const size_t fin_lds = (size_t)(6 * kFinMax + 32) * 4 + 2 * (size_t)kFinNodes * sizeof(LNode) +
+                               (split_rule == EFANNA_SPLIT_PROJECTION ? (size_t)kFinMax * 8 : 0);
         EF_HIP_CHECK(hipFuncSetAttribute((const void *)finish_kernel,
                                          hipFuncAttributeMaxDynamicSharedMemorySize, (int)fin_lds));
         finish_kernel<<<host_c.small_nodes, kFinThreads, fin_lds, st>>>(w.xt, d, perm_cur, w.small, w.leaf_flag,

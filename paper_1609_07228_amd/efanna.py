@@ -101,14 +101,15 @@ def _workspace(nbytes: int, device) -> torch.Tensor:
 NODE_BYTES = 32      # sizeof(efanna_node): int64 sum; int32 dim, cnt, parent, depth, child[2]
 
 
-SPLIT_UNIFORM, SPLIT_VARIANCE = 0, 1
+SPLIT_UNIFORM, SPLIT_VARIANCE, SPLIT_PROJECTION = 0, 1, 2
 
 
 def efanna_build_trees_rule(X: torch.Tensor, n_trees: int, leaf_size: int, seed: int, split_rule: int,
                             max_leaves: int | None = None, workspace: torch.Tensor | None = None,
                             with_nodes: bool = False):
     """Alg. 2 with the split dimension taken by `split_rule` (SPLIT_UNIFORM: drawn over all d,
-    SPLIT_VARIANCE: drawn among the five dimensions of largest variance).  Returns what
+    SPLIT_VARIANCE: drawn among the five dimensions of largest variance, SPLIT_PROJECTION: a signed
+    sum of eight coordinates instead of one).  Returns what
     efanna_build_trees returns."""
     return efanna_build_trees(X, n_trees, leaf_size, seed, max_leaves, workspace, with_nodes, _rule=int(split_rule))
 

@@ -206,6 +206,53 @@ def test_trees_variance_rule_bit_exact(ef, name, n, T, S):
     assert torch.equal(plain[0], same[0]) and not torch.equal(plain[0], g[0])
 
 
+@pytest.mark.parametrize("name,n,T,S", [
+    ("gmm10k_d32", 10_000, 4, 8),
+    ("sift100k_like", 40_000, 3, 16),      # device-wide levels and the in-LDS finish
+    ("mixed4m_d96", 20_000, 2, 64),
+    ("gist1m_like", 3_000, 2, 16),
+    ("gmm10k_d32", 1_003, 2, 1),
+])
+def test_trees_projection_rule_bit_exact(ef, name, n, T, S):
+    X = synth.generate(name, n=n)
+    g, _ = tree_nodes_equal(ef, X, T, S, synth.ALGO_SEED, split_rule=2)
+    plain = ef.efanna_build_trees(dev(X), T, S, synth.ALGO_SEED)
+    assert not torch.equal(plain[0], g[0])
+
+
+def test_projection_rule_conquer_search_and_limits(ef):
+    rng = np.random.default_rng(41)
+    for n, d in ((700, 1), (2_500, 3), (5_000, 70)):      # one dimension: signs may cancel (positional halves)
+        X = rng.standard_normal((n, d)).astype(np.float32)
+        tree_nodes_equal(ef, X, 2, 6, 9, split_rule=2)
+    # the conquer step and the search route through projection nodes
+    X = synth.generate("sift100k_like", n=8_000)
+    g, o = tree_nodes_equal(ef, X, 3, 16, 5, split_rule=2)
+    for S, K, dep in ((16, 12, 7),):
+        graph = ef.efanna_init_graph(dev(X), g[0], g[1], g[2], S, K, nodes=g[3], leaf_up=g[4], tree_depth=g[5],
+                                     conquer_depth=dep)
+        graph_equal(ef, graph, oracle.conquer_graph(X, *o, dep, K))
+    Xm = synth.generate("mixed4m_d96", n=5_000)           # the general conquer kernels
+    gm, om = tree_nodes_equal(ef, Xm, 2, 40, 5, split_rule=2)
+    graph = ef.efanna_init_graph(dev(Xm), gm[0], gm[1], gm[2], 40, 24, nodes=gm[3], leaf_up=gm[4], tree_depth=gm[5],
+                                 conquer_depth=4)
+    graph_equal(ef, graph, oracle.conquer_graph(Xm, *om, 4, 24))
+    K = 10
+    graph = ef.efanna_init_graph(dev(X), g[0], g[1], g[2], 16, K)
+    ids = ef.efanna_get_graph(graph)[0]
+    Q = np.round(X[rng.choice(8_000, 300)] + 3 * rng.standard_normal((300, X.shape[1]))).astype(np.float32)
+    got = ef.efanna_search(dev(X), g[0], g[1], g[2], g[3], g[5], 16, ids, dev(Q), K, 100, 50, 3)
+    want = oracle.search(X, o[0], o[1], o[2], o[3], 16, host(ids), Q, K, 100, 50, 3)
+    assert np.array_equal(host(got[0]), want[0]) and np.array_equal(host(got[1]), want[1])
+    assert np.array_equal(host(got[2]), want[2])
+    # the domain is eight times narrower: 2^19 * 2^21 * 8 = 2^43
+    big = torch.full((1 << 21, 1), 2.0 ** 19, dtype=torch.float32, device="cuda")
+    with pytest.raises(ef.EfannaError) as e:
+        ef.efanna_build_trees_rule(big, 1, 64, 0, 2)
+    assert e.value.status == -3
+    ef.efanna_build_trees_rule(big, 1, 64, 0, 0)
+
+
 def test_trees_variance_rule_shapes(ef):
     rng = np.random.default_rng(31)
     for n, d in ((700, 3), (2_500, 5), (5_000, 70), (300, 1)):      # fewer than five dimensions; a ragged last lane round
@@ -217,7 +264,7 @@ def test_trees_variance_rule_shapes(ef):
     X = np.repeat(rng.standard_normal((40, 6)).astype(np.float32), 100, axis=0)      # equal points: zero variances, ties
     tree_nodes_equal(ef, X, 2, 16, 4, split_rule=1)
     with pytest.raises(ef.EfannaError) as e:
-        ef.efanna_build_trees_rule(dev(X), 2, 16, 4, 2)
+        ef.efanna_build_trees_rule(dev(X), 2, 16, 4, 3)
     assert e.value.status == -1
 
 
