@@ -216,8 +216,9 @@ int efanna_init_graph(const float *X, int64_t n, int32_t d, const int32_t *perm,
  *          synchronises the stream before returning.  (With cross_old the split by join size
  *          covers the second pass only; the first pass is booked under the smallest joins.)
  * Asynchronous on `stream` otherwise.  Limits: k <= EFANNA_MAX_K, sample_L <= EFANNA_MAX_SAMPLE,
- * if k + 2*sample_L > 32 (or rows are not 16-byte aligned), k + 2*sample_L rows of d floats
- * must fit the 160 KB LDS.
+ * where joins can gather more than 32 vectors (k + 2*sample_L > 32) of more than 128
+ * coordinates, or d is not a multiple of 4, or X is not 16-byte aligned, k + 2*sample_L rows of
+ * d floats must fit the 160 KB LDS (EFANNA_EUNSUPPORTED otherwise).
  */
 size_t efanna_nndescent_workspace_bytes(int64_t n, int32_t k, int32_t sample_L);
 
