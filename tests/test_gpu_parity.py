@@ -392,6 +392,9 @@ def test_nndescent_filter_ranges_bit_exact(ef, kind, d, K, L):
     (3_000, 8, 2, 16, 32, 32, 2),        # the longest rows and lists that scheme takes
     (2_000, 8, 2, 16, 33, 16, 1),        # one more: lists by counters
     (4_096, 12, 2, 16, 3, 1, 4),         # lists of a single key
+    (2_000, 16, 2, 16, 64, 32, 2),       # join lists of 128 ids: a wave per point, hash table of 256 slots
+    (1_500, 8, 2, 16, 128, 64, 1),       # the longest rows and samples the library takes (lists of 256 ids)
+    (1_200, 20, 2, 16, 40, 29, 2),       # lists of 98 ids: just over the switch to a wave per point
 ])
 def test_nndescent_more_shapes(ef, n, d, T, S, K, L, I):
     rng = np.random.default_rng(n + d + K)
